@@ -1,0 +1,205 @@
+"""CPU oracle (test infrastructure only): numpy front end of ``freescale_oracle.c``.
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py``
+may import this package.  It never imports the HIP binding.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "freescale_oracle.c")
+_LIB = os.path.join(_HERE, "libfs_oracle.so")
+
+F32, BF16 = 0, 1
+OK, EINVAL, ENOMEM, ERANGE = 0, -1, -2, -5
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with the host C compiler (no FMA contraction, plain -O2)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-std=c11", "-O2", "-ffp-contract=off", "-fPIC", "-shared",
+               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.fso_f32_to_bf16.restype = ctypes.c_uint16
+        _lib.fso_f32_to_bf16.argtypes = [ctypes.c_float]
+        _lib.fso_bf16_to_f32.restype = ctypes.c_float
+        _lib.fso_bf16_to_f32.argtypes = [ctypes.c_uint16]
+    return _lib
+
+
+class OracleError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        super().__init__(f"{where} failed with status {code}")
+        self.code = code
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _check(code: int, where: str) -> None:
+    if code != OK:
+        raise OracleError(code, where)
+
+
+def _c(a, dtype) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def dtype_code(table: np.ndarray) -> int:
+    """fp32 tables are float32 arrays; bf16 tables are uint16 arrays of bf16 bit patterns."""
+    if table.dtype == np.float32:
+        return F32
+    if table.dtype == np.uint16:
+        return BF16
+    raise TypeError(f"table dtype {table.dtype} (want float32, or uint16 holding bf16 bits)")
+
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Element-wise through the oracle's own scalar conversion (slow; for tests)."""
+    x = _c(x, np.float32)
+    out = np.empty(x.shape, dtype=np.uint16)
+    f = lib().fso_f32_to_bf16
+    flat_in, flat_out = x.reshape(-1), out.reshape(-1)
+    for i in range(flat_in.size):
+        flat_out[i] = f(float(flat_in[i]))
+    return out
+
+
+def bf16_bits_to_f32(h: np.ndarray) -> np.ndarray:
+    """Exact widening (a bit shift; no arithmetic of the method)."""
+    h = _c(h, np.uint16)
+    return (h.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+# ---- the five operations ---------------------------------------------------------------
+def gather_jagged(table: np.ndarray, values: np.ndarray, offsets: Optional[np.ndarray]) -> np.ndarray:
+    assert table.ndim == 2 and table.flags.c_contiguous
+    values = _c(values, np.int64)
+    n = values.shape[0]
+    if offsets is None:
+        offsets = np.array([0, n], dtype=np.int64)
+    offsets = _c(offsets, np.int64)
+    out = np.empty((n, table.shape[1]), dtype=table.dtype)
+    rc = lib().fso_gather_jagged(_p(table), ctypes.c_int64(table.shape[0]), ctypes.c_int32(table.shape[1]),
+                                 ctypes.c_int(dtype_code(table)), _p(values), _p(offsets),
+                                 ctypes.c_int64(offsets.shape[0] - 1), ctypes.c_int64(n), _p(out))
+    _check(rc, "fso_gather_jagged")
+    return out
+
+
+def unique_ids(ids: np.ndarray, num_rows: int = 0) -> Dict[str, np.ndarray]:
+    ids = _c(ids, np.int64)
+    n = ids.shape[0]
+    unique = np.empty(max(n, 1), dtype=np.int64)
+    seg = np.empty(n + 1, dtype=np.int32)
+    perm = np.empty(max(n, 1), dtype=np.int32)
+    inv = np.empty(max(n, 1), dtype=np.int32)
+    nu = ctypes.c_int64(0)
+    rc = lib().fso_unique_ids(_p(ids), ctypes.c_int64(n), ctypes.c_int64(num_rows), _p(unique), _p(seg),
+                              _p(perm), _p(inv), ctypes.byref(nu))
+    _check(rc, "fso_unique_ids")
+    u = nu.value
+    return {"unique": unique[:u].copy(), "seg_offsets": seg[:u + 1].copy(), "perm": perm[:n].copy(),
+            "inverse": inv[:n].copy(), "n_unique": u}
+
+
+def collision_split(u_t: np.ndarray, u_t1: np.ndarray) -> Dict[str, np.ndarray]:
+    u_t, u_t1 = _c(u_t, np.int64), _c(u_t1, np.int64)
+    nt, nt1 = u_t.shape[0], u_t1.shape[0]
+    co, cos = np.empty(max(nt, 1), np.int64), np.empty(max(nt, 1), np.int32)
+    ex, exs = np.empty(max(nt, 1), np.int64), np.empty(max(nt, 1), np.int32)
+    exn, exns = np.empty(max(nt1, 1), np.int64), np.empty(max(nt1, 1), np.int32)
+    counts = np.zeros(3, dtype=np.int64)
+    rc = lib().fso_collision_split(_p(u_t), ctypes.c_int64(nt), _p(u_t1), ctypes.c_int64(nt1),
+                                   _p(co), _p(cos), _p(ex), _p(exs), _p(exn), _p(exns), _p(counts))
+    _check(rc, "fso_collision_split")
+    a, b, c = (int(x) for x in counts)
+    return {"co": co[:a].copy(), "co_slot": cos[:a].copy(), "ex": ex[:b].copy(), "ex_slot": exs[:b].copy(),
+            "ex_next": exn[:c].copy(), "ex_next_slot": exns[:c].copy()}
+
+
+def segment_reduce_grads(grads: np.ndarray, perm: np.ndarray, seg_offsets: np.ndarray) -> np.ndarray:
+    grads = _c(grads, np.float32)
+    perm, seg_offsets = _c(perm, np.int32), _c(seg_offsets, np.int32)
+    n, dim = grads.shape
+    nu = seg_offsets.shape[0] - 1
+    out = np.empty((nu, dim), dtype=np.float32)
+    rc = lib().fso_segment_reduce_grads(_p(grads), ctypes.c_int64(n), ctypes.c_int32(dim), _p(perm),
+                                        _p(seg_offsets), ctypes.c_int64(nu), _p(out))
+    _check(rc, "fso_segment_reduce_grads")
+    return out
+
+
+def rowwise_adagrad_update(table: np.ndarray, state: np.ndarray, rows: np.ndarray, slots: np.ndarray,
+                           reduced: np.ndarray, lr: float, eps: float) -> None:
+    """In place on ``table`` and ``state``."""
+    assert table.flags.c_contiguous and state.flags.c_contiguous and state.dtype == np.float32
+    rows, slots = _c(rows, np.int64), _c(slots, np.int32)
+    reduced = _c(reduced, np.float32)
+    rc = lib().fso_rowwise_adagrad_update(_p(table), ctypes.c_int(dtype_code(table)), _p(state),
+                                          ctypes.c_int64(table.shape[0]), ctypes.c_int32(table.shape[1]),
+                                          _p(rows), _p(slots), ctypes.c_int64(rows.shape[0]), _p(reduced),
+                                          ctypes.c_float(lr), ctypes.c_float(eps))
+    _check(rc, "fso_rowwise_adagrad_update")
+
+
+# ---- one step of the prioritized schedule -------------------------------------------------
+SCHEDULES = ("co_then_ex", "ex_then_co", "all_at_once", "gather_between")
+
+
+def step(table: np.ndarray, state: np.ndarray, layout_t: Dict[str, np.ndarray], grads_t: np.ndarray,
+         values_next: Optional[np.ndarray], offsets_next: Optional[np.ndarray], lr: float, eps: float,
+         schedule: str = "co_then_ex") -> Dict[str, object]:
+    """Iteration t on one shard (Algorithm 2 with the collectives removed).
+
+    layout_t is unique_ids(values_t).  With a lookahead batch (values_next): dedup it, split U_t
+    against U_{t+1}, reduce G_t, update the collision rows, update the exclusive rows, gather the
+    rows of the lookahead batch.  Without one (last iteration) every row of U_t is exclusive.
+    ``schedule`` permutes the order of the passes; all orders must give identical results
+    (Section 3.2: strict write-read ordering is only needed on collision rows).
+    """
+    num_rows = table.shape[0]
+    g = segment_reduce_grads(grads_t, layout_t["perm"], layout_t["seg_offsets"])
+    u_t = layout_t["unique"]
+    if values_next is None:
+        layout_next = None
+        sp = collision_split(u_t, np.empty(0, dtype=np.int64))
+    else:
+        layout_next = unique_ids(values_next, num_rows)
+        sp = collision_split(u_t, layout_next["unique"])
+    emb = None
+
+    def upd(rows, slots):
+        rowwise_adagrad_update(table, state, rows, slots, g, lr, eps)
+
+    def gat():
+        return None if values_next is None else gather_jagged(table, values_next, offsets_next)
+
+    if schedule == "co_then_ex":
+        upd(sp["co"], sp["co_slot"]); upd(sp["ex"], sp["ex_slot"]); emb = gat()
+    elif schedule == "ex_then_co":
+        upd(sp["ex"], sp["ex_slot"]); upd(sp["co"], sp["co_slot"]); emb = gat()
+    elif schedule == "all_at_once":
+        upd(u_t, np.arange(u_t.shape[0], dtype=np.int32)); emb = gat()
+    elif schedule == "gather_between":
+        upd(sp["co"], sp["co_slot"]); emb = gat(); upd(sp["ex"], sp["ex_slot"])
+    else:
+        raise ValueError(schedule)
+    return {"reduced": g, "split": sp, "layout_next": layout_next, "emb_next": emb}

@@ -1,0 +1,232 @@
+/*
+ * Plain CPU oracle for one embedding-table shard's prioritized-update path.
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It exists to check the HIP library; nothing in the
+ * product path may call it.  It is written for obviousness, not speed: one thread,
+ * no blocking, no fusion, fp64 accumulation, one rounding per output element.  It
+ * shares no source, header, table or helper with the HIP library.
+ *
+ * What each function follows (FreeScale paper, Section 3.2 "Prioritized Embedding
+ * Updates" and its Algorithm 2 "Prioritized Embedding Autograd Function"):
+ *   fso_gather_jagged          Lookup(I): rows of the shard-major table selected by a
+ *                              jagged ID tensor (Section 2.1 describes the lookup, Section
+ *                              4.2 the jagged layout).
+ *   fso_unique_ids             the distinct rows of one iteration's IDs; collisions are
+ *                              defined on rows (Section 2.3).
+ *   fso_collision_split        compute_collision(I^i, I^{i+1}) -> I_co^i, I_ex^i, I_ex^{i+1}
+ *                              (Algorithm 2; the collision definition below it).
+ *   fso_segment_reduce_grads   first half of update_embedding(I, G): one summed gradient
+ *                              per distinct row.
+ *   fso_rowwise_adagrad_update second half of update_embedding(I, G): the sparse optimizer
+ *                              step.  The paper does not name the optimizer; this build
+ *                              fixes row-wise Adagrad (one accumulator per row that adds
+ *                              the MEAN over columns of the squared summed gradient, eps
+ *                              outside the square root, no decay, no clipping).
+ *
+ * Pins (tests/test_oracle_pins.py): brute-force set logic on tiny inputs, dense one-hot
+ * reduction, hand-computed Adagrad steps, element-wise Adagrad of a library on the
+ * special case where both coincide, a closed form over T steps, and the invariants of
+ * the partition (union, disjointness, schedule independence).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { FSO_OK = 0, FSO_EINVAL = -1, FSO_ENOMEM = -2, FSO_ERANGE = -5 };
+enum { FSO_F32 = 0, FSO_BF16 = 1 };
+
+/* Set to 0 to accumulate the SUM (not the mean) of squared gradients per row. */
+#ifndef FSO_ADAGRAD_MEAN
+#define FSO_ADAGRAD_MEAN 1
+#endif
+
+/* ---- bf16 <-> f32 ------------------------------------------------------------------- */
+static float bf16_to_f32(uint16_t h)
+{
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+/* round to nearest, ties to even; NaN stays NaN */
+static uint16_t f32_to_bf16_rne(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u)
+        return (uint16_t)((u >> 16) | 0x0040u);
+    uint32_t lsb = (u >> 16) & 1u;
+    u += 0x7fffu + lsb;
+    return (uint16_t)(u >> 16);
+}
+
+static size_t elem_size(int dt) { return dt == FSO_BF16 ? 2 : 4; }
+
+/* ---- O1: gather ---------------------------------------------------------------------- */
+/* out[j, :] = table[values[j], :] for every j in [0, n_values).  offsets describes how the
+ * n_values occurrences are grouped into `batch` sequences; the output keeps that grouping,
+ * so offsets is only validated. */
+int fso_gather_jagged(const void *table, int64_t num_rows, int32_t dim, int dt,
+                      const int64_t *values, const int64_t *offsets, int64_t batch,
+                      int64_t n_values, void *out)
+{
+    if (num_rows < 0 || dim <= 0 || batch < 0 || n_values < 0) return FSO_EINVAL;
+    if (dt != FSO_F32 && dt != FSO_BF16) return FSO_EINVAL;
+    if (offsets) {
+        if (offsets[0] != 0 || offsets[batch] != n_values) return FSO_ERANGE;
+        for (int64_t b = 0; b < batch; ++b)
+            if (offsets[b + 1] < offsets[b]) return FSO_ERANGE;
+    }
+    size_t row_bytes = (size_t)dim * elem_size(dt);
+    for (int64_t j = 0; j < n_values; ++j) {
+        int64_t r = values[j];
+        if (r < 0 || r >= num_rows) return FSO_ERANGE;
+        memcpy((char *)out + (size_t)j * row_bytes, (const char *)table + (size_t)r * row_bytes, row_bytes);
+    }
+    return FSO_OK;
+}
+
+/* ---- O2: unique ---------------------------------------------------------------------- */
+typedef struct { int64_t key; int32_t idx; } keyidx;
+
+static int cmp_keyidx(const void *a, const void *b)
+{
+    const keyidx *x = (const keyidx *)a, *y = (const keyidx *)b;
+    if (x->key < y->key) return -1;
+    if (x->key > y->key) return 1;
+    return (x->idx > y->idx) - (x->idx < y->idx);   /* ties by ascending position */
+}
+
+/* unique      : ascending distinct IDs, *n_unique of them
+ * seg_offsets : seg_offsets[k]..seg_offsets[k+1] is the range of sorted positions of unique[k]
+ * perm        : perm[p] = original position of the occurrence at sorted position p
+ *               (sorted by ID, equal IDs in ascending original position)
+ * inverse     : ids[j] == unique[inverse[j]]
+ * num_rows > 0 bounds the legal IDs to [0, num_rows); 0 means any non-negative int64. */
+int fso_unique_ids(const int64_t *ids, int64_t n, int64_t num_rows, int64_t *unique,
+                   int32_t *seg_offsets, int32_t *perm, int32_t *inverse, int64_t *n_unique)
+{
+    if (n < 0 || n > INT32_MAX || num_rows < 0) return FSO_EINVAL;
+    *n_unique = 0;
+    seg_offsets[0] = 0;
+    if (n == 0) return FSO_OK;
+    for (int64_t j = 0; j < n; ++j)
+        if (ids[j] < 0 || (num_rows > 0 && ids[j] >= num_rows)) return FSO_ERANGE;
+    keyidx *a = (keyidx *)malloc((size_t)n * sizeof(keyidx));
+    if (!a) return FSO_ENOMEM;
+    for (int64_t j = 0; j < n; ++j) { a[j].key = ids[j]; a[j].idx = (int32_t)j; }
+    qsort(a, (size_t)n, sizeof(keyidx), cmp_keyidx);
+    int64_t u = 0;
+    for (int64_t p = 0; p < n; ++p) {
+        if (p == 0 || a[p].key != a[p - 1].key) {
+            unique[u] = a[p].key;
+            seg_offsets[u] = (int32_t)p;
+            ++u;
+        }
+        perm[p] = a[p].idx;
+        inverse[a[p].idx] = (int32_t)(u - 1);
+    }
+    seg_offsets[u] = (int32_t)n;
+    *n_unique = u;
+    free(a);
+    return FSO_OK;
+}
+
+/* ---- O3: collision split --------------------------------------------------------------- */
+/* u_t, u_t1: ascending distinct IDs of iterations t and t+1.
+ * co      = u_t  intersect u_t1   (rows updated at t AND read at t+1: update first)
+ * ex      = u_t  minus     u_t1   (rows whose update may be deferred)
+ * ex_next = u_t1 minus     u_t    (rows of t+1 that are safe to read before t's updates)
+ * co_slot/ex_slot index u_t, ex_next_slot indexes u_t1.  counts = {|co|, |ex|, |ex_next|}. */
+int fso_collision_split(const int64_t *u_t, int64_t n_t, const int64_t *u_t1, int64_t n_t1,
+                        int64_t *co, int32_t *co_slot, int64_t *ex, int32_t *ex_slot,
+                        int64_t *ex_next, int32_t *ex_next_slot, int64_t *counts)
+{
+    if (n_t < 0 || n_t1 < 0) return FSO_EINVAL;
+    for (int64_t i = 1; i < n_t; ++i) if (u_t[i] <= u_t[i - 1]) return FSO_EINVAL;
+    for (int64_t i = 1; i < n_t1; ++i) if (u_t1[i] <= u_t1[i - 1]) return FSO_EINVAL;
+    int64_t i = 0, j = 0, nco = 0, nex = 0, nexn = 0;
+    while (i < n_t || j < n_t1) {
+        if (j >= n_t1 || (i < n_t && u_t[i] < u_t1[j])) {
+            ex[nex] = u_t[i]; ex_slot[nex] = (int32_t)i; ++nex; ++i;
+        } else if (i >= n_t || u_t1[j] < u_t[i]) {
+            ex_next[nexn] = u_t1[j]; ex_next_slot[nexn] = (int32_t)j; ++nexn; ++j;
+        } else {
+            co[nco] = u_t[i]; co_slot[nco] = (int32_t)i; ++nco; ++i; ++j;
+        }
+    }
+    counts[0] = nco; counts[1] = nex; counts[2] = nexn;
+    return FSO_OK;
+}
+
+/* ---- O4: gradient segment reduce ------------------------------------------------------- */
+/* reduced[k, :] = sum of grads[j, :] over the occurrences j of distinct row k, accumulated
+ * in fp64 in ascending j (perm is stable), rounded once to fp32. */
+int fso_segment_reduce_grads(const float *grads, int64_t n, int32_t dim, const int32_t *perm,
+                             const int32_t *seg_offsets, int64_t n_unique, float *reduced)
+{
+    if (n < 0 || dim <= 0 || n_unique < 0) return FSO_EINVAL;
+    double *acc = (double *)malloc((size_t)dim * sizeof(double));
+    if (!acc) return FSO_ENOMEM;
+    for (int64_t k = 0; k < n_unique; ++k) {
+        for (int32_t d = 0; d < dim; ++d) acc[d] = 0.0;
+        for (int32_t p = seg_offsets[k]; p < seg_offsets[k + 1]; ++p) {
+            const float *g = grads + (size_t)perm[p] * (size_t)dim;
+            for (int32_t d = 0; d < dim; ++d) acc[d] += (double)g[d];
+        }
+        for (int32_t d = 0; d < dim; ++d) reduced[(size_t)k * (size_t)dim + d] = (float)acc[d];
+    }
+    free(acc);
+    return FSO_OK;
+}
+
+/* ---- O5: row-wise Adagrad ---------------------------------------------------------------- */
+/* For every listed pair (r = rows[i], k = slots[i]):
+ *     m    = mean over columns of reduced[k, d]^2            (fp64 sum, rounded once to fp32)
+ *     S[r] = S[r] + m                                         (fp32)
+ *     c    = lr / (sqrt(S[r]) + eps)                          (fp32)
+ *     W[r, d] = W[r, d] - c * reduced[k, d]                   (fp32; bf16 tables: widen, update, RNE)
+ * Rows not listed are untouched. */
+int fso_rowwise_adagrad_update(void *table, int dt, float *state, int64_t num_rows, int32_t dim,
+                               const int64_t *rows, const int32_t *slots, int64_t n_rows,
+                               const float *reduced, float lr, float eps)
+{
+    if (num_rows < 0 || dim <= 0 || n_rows < 0) return FSO_EINVAL;
+    if (dt != FSO_F32 && dt != FSO_BF16) return FSO_EINVAL;
+    for (int64_t i = 0; i < n_rows; ++i) {
+        int64_t r = rows[i];
+        if (r < 0 || r >= num_rows) return FSO_ERANGE;
+        const float *g = reduced + (size_t)slots[i] * (size_t)dim;
+        double ss = 0.0;
+        for (int32_t d = 0; d < dim; ++d) ss += (double)g[d] * (double)g[d];
+#if FSO_ADAGRAD_MEAN
+        float m = (float)(ss / (double)dim);
+#else
+        float m = (float)ss;
+#endif
+        float s_new = state[r] + m;
+        state[r] = s_new;
+        float c = lr / (sqrtf(s_new) + eps);
+        if (dt == FSO_F32) {
+            float *w = (float *)table + (size_t)r * (size_t)dim;
+            for (int32_t d = 0; d < dim; ++d) {
+                float step = c * g[d];
+                w[d] = w[d] - step;
+            }
+        } else {
+            uint16_t *w = (uint16_t *)table + (size_t)r * (size_t)dim;
+            for (int32_t d = 0; d < dim; ++d) {
+                float step = c * g[d];
+                float v = bf16_to_f32(w[d]) - step;
+                w[d] = f32_to_bf16_rne(v);
+            }
+        }
+    }
+    return FSO_OK;
+}
+
+/* exposed for the bf16 conversion pins */
+uint16_t fso_f32_to_bf16(float f) { return f32_to_bf16_rne(f); }
+float fso_bf16_to_f32(uint16_t h) { return bf16_to_f32(h); }
