@@ -1,0 +1,188 @@
+/*
+ * freescale.h - C ABI of the MI355X (gfx950) library for one embedding-table shard's
+ * prioritized embedding updates (FreeScale paper, Section 3.2 and its Algorithm 2,
+ * "Prioritized Embedding Autograd Function", with the collectives removed: one GPU, one
+ * shard, shard-major IDs).
+ *
+ * Conventions that hold for every call unless a comment says otherwise
+ *   - Every pointer except fs_ctx* and the *_host out-parameters is CALLER-OWNED DEVICE
+ *     memory on the context's GPU.  The library neither frees nor keeps it past the stream
+ *     work it enqueues.
+ *   - Calls are ASYNCHRONOUS: they enqueue kernels on `stream` (a hipStream_t passed as
+ *     void*; NULL = the default stream) and return.  Data-dependent sizes (number of
+ *     distinct rows, sizes of the collision / exclusive sets) are written to device scalars
+ *     and read from device scalars by the calls that consume them; no call synchronises.
+ *   - The return value is a status code.  No call aborts, throws or prints.  Errors that the
+ *     host can see (NULL pointer, negative size, unsupported dim/dtype, size beyond the
+ *     context capacity) are returned at once and nothing is enqueued.  Errors only the
+ *     device can see (row ID outside [0, num_rows), malformed offsets) never fault: the
+ *     offending access is suppressed (gathered row zero-filled, update skipped) and a flag is
+ *     raised that fs_check_async() reports as FS_ERANGE.
+ *   - n == 0 is a valid no-op everywhere.
+ *   - Row layout: tables are row-major [num_rows, dim], 16-byte aligned, fp32 or bf16; the
+ *     Adagrad state is one fp32 per row; gradients are fp32 [n, dim].  dim must be a
+ *     multiple of 4 (fp32) or 8 (bf16) and at most FS_MAX_DIM.
+ *   - One context serves one GPU and one caller thread at a time.  Calls that use the
+ *     context workspace (fs_unique_ids, fs_collision_split, fs_segment_reduce_grads,
+ *     fs_prioritized_step) must not overlap each other on different streams.
+ */
+#ifndef FREESCALE_H
+#define FREESCALE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FS_MAX_DIM 256
+
+typedef struct fs_ctx fs_ctx;            /* opaque: workspace, side streams, events, last error */
+typedef void *fs_stream;                 /* a hipStream_t */
+
+typedef enum { FS_F32 = 0, FS_BF16 = 1 } fs_dtype;
+
+enum {
+    FS_OK = 0,
+    FS_EINVAL = -1,      /* bad argument visible to the host */
+    FS_ENOMEM = -2,      /* size beyond the context capacity, or allocation failure */
+    FS_EHIP = -3,        /* a HIP runtime call failed; fs_last_error() has its text */
+    FS_ENOTIMPL = -4,
+    FS_ERANGE = -5       /* device-detected: row ID out of range / malformed offsets */
+};
+
+/* ---- context ------------------------------------------------------------------------- */
+
+/* Allocates the workspace for inputs of at most max_ids IDs per iteration and rows of at
+ * most max_dim columns on GPU `device` (sort double buffers, histograms, scan partials,
+ * fp64 partial rows of the segment reduce), two side streams at default priority and the
+ * events that order the passes.  This is the only call that allocates device memory. */
+int fs_ctx_create(fs_ctx **out, int device, int64_t max_ids, int32_t max_dim);
+int fs_ctx_destroy(fs_ctx *ctx);
+
+/* Text of the last host-visible error on this context ("" if none).  Never NULL. */
+const char *fs_last_error(const fs_ctx *ctx);
+
+/* Waits for `stream`, then reports and clears the device-side error flags:
+ * FS_OK, or FS_ERANGE if any kernel since the last check suppressed an access. */
+int fs_check_async(fs_ctx *ctx, fs_stream stream);
+
+/* Bytes of device workspace held by the context. */
+size_t fs_ctx_workspace_bytes(const fs_ctx *ctx);
+
+/* ---- the five operations ---------------------------------------------------------------- */
+
+/* Lookup(I) of Algorithm 2 (embedding lookup of Section 2.1 on the jagged ID layout of
+ * Section 4.2):  out[j, :] = table[values[j], :]  for j in [0, n_values), bit-exact.
+ * values  [n_values] int64 row IDs of `batch` sequences laid end to end;
+ * offsets [batch+1]  int64, offsets[b]..offsets[b+1] is sequence b (may be empty); may be NULL,
+ *         otherwise it is validated on the device (offsets[0]==0, non-decreasing,
+ *         offsets[batch]==n_values) - the output keeps the same jagged grouping.
+ * out     [n_values, dim] of the table's dtype.  An out-of-range ID yields a zero row. */
+int fs_gather_jagged(fs_ctx *ctx, const void *table, int64_t num_rows, int32_t dim, fs_dtype dt,
+                     const int64_t *values, const int64_t *offsets, int64_t batch, int64_t n_values,
+                     void *out, fs_stream stream);
+
+/* Distinct rows of one iteration's IDs (collisions are defined on rows, Section 2.3).
+ * ids          [n] int64, each in [0, num_rows) when num_rows > 0; num_rows == 0 sorts on all
+ *              63 value bits of non-negative IDs.
+ * unique       [>= n]   ascending distinct IDs; entries past *n_unique_dev are unspecified
+ * seg_offsets  [>= n+1] sorted positions seg_offsets[k]..seg_offsets[k+1] hold unique[k]
+ * perm         [n]      original position of the occurrence at each sorted position (stable:
+ *                       equal IDs keep ascending original position)
+ * inverse      [n]      ids[j] == unique[inverse[j]]          (may be NULL)
+ * n_unique_dev [1]      int64 device scalar
+ * n <= context max_ids. */
+int fs_unique_ids(fs_ctx *ctx, const int64_t *ids, int64_t n, int64_t num_rows,
+                  int64_t *unique, int32_t *seg_offsets, int32_t *perm, int32_t *inverse,
+                  int64_t *n_unique_dev, fs_stream stream);
+
+/* compute_collision(I^i, I^{i+1}) -> I_co^i, I_ex^i, I_ex^{i+1} of Algorithm 2, on distinct
+ * ascending row lists:
+ *   co      = u_t  intersect u_t1   rows updated at t and read at t+1 (update these first)
+ *   ex      = u_t  minus u_t1       rows whose update may be deferred
+ *   ex_next = u_t1 minus u_t        rows of t+1 that may be fetched before t's updates land
+ * u_t [*n_t_dev], u_t1 [*n_t1_dev] ascending; cap_t / cap_t1 bound the two counts (host
+ * values used to size the launch; the outputs need that many entries).
+ * co_slot / ex_slot index u_t (and so the reduced-gradient rows), ex_next_slot indexes u_t1.
+ * n_t1_dev may be NULL with cap_t1 == 0: no lookahead batch, everything is exclusive.
+ * counts_dev [3] int64 = |co|, |ex|, |ex_next|.  All outputs ascending. */
+int fs_collision_split(fs_ctx *ctx, const int64_t *u_t, const int64_t *n_t_dev,
+                       const int64_t *u_t1, const int64_t *n_t1_dev, int64_t cap_t, int64_t cap_t1,
+                       int64_t *co, int32_t *co_slot, int64_t *ex, int32_t *ex_slot,
+                       int64_t *ex_next, int32_t *ex_next_slot, int64_t *counts_dev, fs_stream stream);
+
+/* First half of update_embedding(I, G) of Algorithm 2: one summed gradient per distinct row,
+ *   reduced[k, :] = sum over sorted positions p in [seg_offsets[k], seg_offsets[k+1]) of
+ *                   grads[perm[p], :]
+ * accumulated in fp64 in a fixed order (results do not vary run to run) and rounded once to
+ * fp32.  grads [n, dim] fp32; reduced needs *n_unique_dev rows (at most n). */
+int fs_segment_reduce_grads(fs_ctx *ctx, const float *grads, int64_t n, int32_t dim,
+                            const int32_t *perm, const int32_t *seg_offsets, const int64_t *n_unique_dev,
+                            float *reduced, fs_stream stream);
+
+/* Second half of update_embedding(I, G): fused row-wise Adagrad on the listed rows, in place.
+ * For i < *n_rows_dev, r = rows[i], k = slots[i]:
+ *     S[r] += mean over columns of reduced[k, :]^2
+ *     W[r, :] -= lr * reduced[k, :] / (sqrt(S[r]) + eps)        (bf16: widen, update, round
+ *                                                                to nearest even)
+ * Called once with the collision rows (priority pass) and once with the exclusive rows
+ * (deferred pass); rows must be distinct within and across concurrent calls.  cap bounds
+ * *n_rows_dev (host value used to size the launch).  Out-of-range rows are skipped and
+ * flagged. */
+int fs_rowwise_adagrad_update(fs_ctx *ctx, void *table, fs_dtype dt, float *state, int64_t num_rows,
+                              int32_t dim, const int64_t *rows, const int32_t *slots,
+                              const int64_t *n_rows_dev, int64_t cap, const float *reduced,
+                              float lr, float eps, fs_stream stream);
+
+/* ---- one whole iteration ------------------------------------------------------------------ */
+
+/* Arguments of fs_prioritized_step (plain pointers; `t` is the iteration whose gradients
+ * arrive, `t1` the lookahead batch whose rows are fetched). */
+typedef struct fs_step_args {
+    void *table; float *state; int64_t num_rows; int32_t dim; int32_t dtype; /* fs_dtype */
+    float lr, eps;
+    /* iteration t: layout produced by the previous step (or by fs_unique_ids), gradients */
+    const int64_t *u_t; const int32_t *seg_offsets_t; const int32_t *perm_t; const int64_t *n_unique_t_dev;
+    const float *grads_t; int64_t n_t;
+    /* lookahead batch t+1 (values_t1 == NULL: last iteration, every row is exclusive) */
+    const int64_t *values_t1; const int64_t *offsets_t1; int64_t batch_t1; int64_t n_t1;
+    /* outputs: layout of t+1 */
+    int64_t *u_t1; int32_t *seg_offsets_t1; int32_t *perm_t1; int32_t *inverse_t1; int64_t *n_unique_t1_dev;
+    /* outputs: the split of U_t */
+    int64_t *co; int32_t *co_slot; int64_t *ex; int32_t *ex_slot; int64_t *ex_next; int32_t *ex_next_slot;
+    int64_t *counts_dev;        /* [3] */
+    /* outputs: reduced gradients [n_t, dim] capacity, and gathered rows of t+1 [n_t1, dim] */
+    float *reduced; void *emb_t1;
+} fs_step_args;
+
+/* Iteration t on one shard, scheduled as Section 3.2 prescribes (strict write-read ordering
+ * on collision rows only):
+ *   side stream A : fs_unique_ids(values_t1) -> fs_collision_split(U_t, U_t1)
+ *   `stream`      : fs_segment_reduce_grads(G_t); wait A; update(co)  [priority pass];
+ *                   fs_gather_jagged(values_t1)
+ *   side stream B : after the reduce and the split: update(ex)        [deferred pass],
+ *                   overlapping the gather, which is race-free because ex and U_t1 are disjoint
+ * and `stream` finally waits for B, so the step is complete when `stream` is.  Results are
+ * identical to running the five calls one after another. */
+int fs_prioritized_step(fs_ctx *ctx, const fs_step_args *args, fs_stream stream);
+
+/* ---- input generation and calibration helpers (not part of the method) ------------------- */
+
+/* Fills a table with the counter-based integer-hash rule of the synthetic workloads:
+ * e = row*dim + col; h = mix32(lo32(e) ^ mix32(hi32(e) + 0x9E3779B9));
+ * fp32: ((h & 0xFFFF) - 32768) * 2^-22;  bf16: ((h & 0xFF) - 128) * 2^-14. */
+int fs_init_table_hash(fs_ctx *ctx, void *table, int64_t num_rows, int32_t dim, fs_dtype dt, fs_stream stream);
+
+/* Plain 16-byte-per-lane copy of n_bytes (multiple of 16) from src to dst: the calibration
+ * kernel for bandwidth counters and the achievable-copy ceiling. */
+int fs_stream_copy(fs_ctx *ctx, const void *src, void *dst, int64_t n_bytes, fs_stream stream);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int fs_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FREESCALE_H */

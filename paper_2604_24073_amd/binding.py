@@ -1,0 +1,291 @@
+"""ctypes binding of libfreescale_hip.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (include/freescale.h) and does
+nothing but turn torch device tensors into pointers, allocate outputs through torch and pass
+the current stream.  No step of the method is computed here, and there is no CPU fallback: if
+the HIP library is missing, importing succeeds but the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import re
+from typing import Dict, Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfreescale_hip.so")
+
+FS_F32, FS_BF16 = 0, 1
+FS_OK, FS_EINVAL, FS_ENOMEM, FS_EHIP, FS_ENOTIMPL, FS_ERANGE = 0, -1, -2, -3, -4, -5
+FS_MAX_DIM = 256
+
+c_i64, c_i32, c_vp, c_f = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_float
+
+
+class fs_step_args(ctypes.Structure):
+    _fields_ = [
+        ("table", c_vp), ("state", c_vp), ("num_rows", c_i64), ("dim", c_i32), ("dtype", c_i32),
+        ("lr", c_f), ("eps", c_f),
+        ("u_t", c_vp), ("seg_offsets_t", c_vp), ("perm_t", c_vp), ("n_unique_t_dev", c_vp),
+        ("grads_t", c_vp), ("n_t", c_i64),
+        ("values_t1", c_vp), ("offsets_t1", c_vp), ("batch_t1", c_i64), ("n_t1", c_i64),
+        ("u_t1", c_vp), ("seg_offsets_t1", c_vp), ("perm_t1", c_vp), ("inverse_t1", c_vp), ("n_unique_t1_dev", c_vp),
+        ("co", c_vp), ("co_slot", c_vp), ("ex", c_vp), ("ex_slot", c_vp), ("ex_next", c_vp), ("ex_next_slot", c_vp),
+        ("counts_dev", c_vp),
+        ("reduced", c_vp), ("emb_t1", c_vp),
+    ]
+
+
+class FreeScaleError(RuntimeError):
+    def __init__(self, code: int, where: str, detail: str = ""):
+        super().__init__(f"{where} failed with status {code}" + (f": {detail}" if detail else ""))
+        self.code = code
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads the in-tree HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} is missing: build it with `python -m paper_2604_24073_amd.build` "
+                                "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    S = c_vp  # stream
+    sig = {
+        "fs_version": (ctypes.c_int, []),
+        "fs_ctx_create": (ctypes.c_int, [ctypes.POINTER(c_vp), ctypes.c_int, c_i64, c_i32]),
+        "fs_ctx_destroy": (ctypes.c_int, [c_vp]),
+        "fs_last_error": (ctypes.c_char_p, [c_vp]),
+        "fs_check_async": (ctypes.c_int, [c_vp, S]),
+        "fs_ctx_workspace_bytes": (ctypes.c_size_t, [c_vp]),
+        "fs_gather_jagged": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i32, ctypes.c_int, c_vp, c_vp, c_i64, c_i64, c_vp, S]),
+        "fs_unique_ids": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i64, c_vp, c_vp, c_vp, c_vp, c_vp, S]),
+        "fs_collision_split": (ctypes.c_int, [c_vp, c_vp, c_vp, c_vp, c_vp, c_i64, c_i64, c_vp, c_vp, c_vp, c_vp,
+                                              c_vp, c_vp, c_vp, S]),
+        "fs_segment_reduce_grads": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i32, c_vp, c_vp, c_vp, c_vp, S]),
+        "fs_rowwise_adagrad_update": (ctypes.c_int, [c_vp, c_vp, ctypes.c_int, c_vp, c_i64, c_i32, c_vp, c_vp, c_vp,
+                                                     c_i64, c_vp, c_f, c_f, S]),
+        "fs_prioritized_step": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args), S]),
+        "fs_init_table_hash": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i32, ctypes.c_int, S]),
+        "fs_stream_copy": (ctypes.c_int, [c_vp, c_vp, c_vp, c_i64, S]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = lib
+    return lib
+
+
+def declared_symbols(header_path: Optional[str] = None):
+    """Names of the functions declared in include/freescale.h."""
+    if header_path is None:
+        header_path = os.path.join(os.path.dirname(_HERE), "include", "freescale.h")
+    text = open(header_path).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fs_[a-z0-9_]+)\s*\(", text)))
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, torch.cuda.Stream):
+        h = stream.cuda_stream
+    else:
+        h = int(stream)
+    return h if h else None
+
+
+def table_dtype_code(table: torch.Tensor) -> int:
+    if table.dtype == torch.float32:
+        return FS_F32
+    if table.dtype == torch.bfloat16:
+        return FS_BF16
+    raise TypeError(f"table dtype {table.dtype}: fp32 or bf16 only")
+
+
+class Context:
+    """Owner of an fs_ctx (device workspace, side streams, events)."""
+
+    def __init__(self, max_ids: int, max_dim: int = FS_MAX_DIM, device: Optional[int] = None):
+        self.lib = load_library()
+        if device is None:
+            device = torch.cuda.current_device()
+        self.device = device
+        h = c_vp()
+        rc = self.lib.fs_ctx_create(ctypes.byref(h), device, max_ids, max_dim)
+        if rc != FS_OK:
+            raise FreeScaleError(rc, "fs_ctx_create")
+        self.handle = h
+        self.max_ids, self.max_dim = max_ids, max_dim
+
+    def close(self) -> None:
+        if getattr(self, "handle", None):
+            self.lib.fs_ctx_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def last_error(self) -> str:
+        return self.lib.fs_last_error(self.handle).decode()
+
+    def check(self, rc: int, where: str) -> None:
+        if rc != FS_OK:
+            raise FreeScaleError(rc, where, self.last_error())
+
+    def workspace_bytes(self) -> int:
+        return int(self.lib.fs_ctx_workspace_bytes(self.handle))
+
+
+def fs_check_async(ctx: Context, stream=None) -> int:
+    return ctx.lib.fs_check_async(ctx.handle, _stream(stream))
+
+
+def fs_gather_jagged(ctx: Context, table: torch.Tensor, values: torch.Tensor, offsets: Optional[torch.Tensor],
+                     out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    n = values.numel()
+    if out is None:
+        out = torch.empty((n, table.shape[1]), dtype=table.dtype, device=table.device)
+    batch = 0 if offsets is None else offsets.numel() - 1
+    rc = ctx.lib.fs_gather_jagged(ctx.handle, _ptr(table), table.shape[0], table.shape[1], table_dtype_code(table),
+                                  _ptr(values), _ptr(offsets), batch, n, _ptr(out), _stream(stream))
+    ctx.check(rc, "fs_gather_jagged")
+    return out
+
+
+def fs_unique_ids(ctx: Context, ids: torch.Tensor, num_rows: int, out: Optional[Dict[str, torch.Tensor]] = None,
+                  stream=None) -> Dict[str, torch.Tensor]:
+    n = ids.numel()
+    dev = ids.device
+    if out is None:
+        out = {
+            "unique": torch.empty(max(n, 1), dtype=torch.int64, device=dev),
+            "seg_offsets": torch.empty(n + 1, dtype=torch.int32, device=dev),
+            "perm": torch.empty(max(n, 1), dtype=torch.int32, device=dev),
+            "inverse": torch.empty(max(n, 1), dtype=torch.int32, device=dev),
+            "n_unique": torch.zeros(1, dtype=torch.int64, device=dev),
+        }
+    rc = ctx.lib.fs_unique_ids(ctx.handle, _ptr(ids), n, num_rows, _ptr(out["unique"]), _ptr(out["seg_offsets"]),
+                               _ptr(out["perm"]), _ptr(out.get("inverse")), _ptr(out["n_unique"]), _stream(stream))
+    ctx.check(rc, "fs_unique_ids")
+    out["n"] = n
+    return out
+
+
+def fs_collision_split(ctx: Context, u_t: Optional[torch.Tensor], n_t_dev: Optional[torch.Tensor],
+                       u_t1: Optional[torch.Tensor], n_t1_dev: Optional[torch.Tensor], cap_t: int, cap_t1: int,
+                       out: Optional[Dict[str, torch.Tensor]] = None, stream=None) -> Dict[str, torch.Tensor]:
+    dev = (u_t if u_t is not None else u_t1).device if (u_t is not None or u_t1 is not None) else torch.device("cuda")
+    if out is None:
+        i64 = lambda k: torch.empty(max(k, 1), dtype=torch.int64, device=dev)
+        i32 = lambda k: torch.empty(max(k, 1), dtype=torch.int32, device=dev)
+        out = {"co": i64(cap_t), "co_slot": i32(cap_t), "ex": i64(cap_t), "ex_slot": i32(cap_t),
+               "ex_next": i64(cap_t1), "ex_next_slot": i32(cap_t1),
+               "counts": torch.zeros(3, dtype=torch.int64, device=dev)}
+    rc = ctx.lib.fs_collision_split(ctx.handle, _ptr(u_t), _ptr(n_t_dev), _ptr(u_t1), _ptr(n_t1_dev), cap_t, cap_t1,
+                                    _ptr(out["co"]), _ptr(out["co_slot"]), _ptr(out["ex"]), _ptr(out["ex_slot"]),
+                                    _ptr(out["ex_next"]), _ptr(out["ex_next_slot"]), _ptr(out["counts"]),
+                                    _stream(stream))
+    ctx.check(rc, "fs_collision_split")
+    return out
+
+
+def fs_segment_reduce_grads(ctx: Context, grads: torch.Tensor, perm: torch.Tensor, seg_offsets: torch.Tensor,
+                            n_unique_dev: torch.Tensor, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    n, dim = grads.shape
+    if out is None:
+        out = torch.empty((max(n, 1), dim), dtype=torch.float32, device=grads.device)
+    rc = ctx.lib.fs_segment_reduce_grads(ctx.handle, _ptr(grads), n, dim, _ptr(perm), _ptr(seg_offsets),
+                                         _ptr(n_unique_dev), _ptr(out), _stream(stream))
+    ctx.check(rc, "fs_segment_reduce_grads")
+    return out
+
+
+def fs_rowwise_adagrad_update(ctx: Context, table: torch.Tensor, state: torch.Tensor, rows: torch.Tensor,
+                              slots: torch.Tensor, n_rows_dev: torch.Tensor, cap: int, reduced: torch.Tensor,
+                              lr: float, eps: float, stream=None) -> None:
+    rc = ctx.lib.fs_rowwise_adagrad_update(ctx.handle, _ptr(table), table_dtype_code(table), _ptr(state),
+                                           table.shape[0], table.shape[1], _ptr(rows), _ptr(slots), _ptr(n_rows_dev),
+                                           cap, _ptr(reduced), lr, eps, _stream(stream))
+    ctx.check(rc, "fs_rowwise_adagrad_update")
+
+
+def fs_prioritized_step(ctx: Context, args: fs_step_args, stream=None) -> None:
+    rc = ctx.lib.fs_prioritized_step(ctx.handle, ctypes.byref(args), _stream(stream))
+    ctx.check(rc, "fs_prioritized_step")
+
+
+def fs_init_table_hash(ctx: Context, table: torch.Tensor, stream=None) -> None:
+    rc = ctx.lib.fs_init_table_hash(ctx.handle, _ptr(table), table.shape[0], table.shape[1], table_dtype_code(table),
+                                    _stream(stream))
+    ctx.check(rc, "fs_init_table_hash")
+
+
+def fs_stream_copy(ctx: Context, src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
+    nbytes = src.numel() * src.element_size()
+    rc = ctx.lib.fs_stream_copy(ctx.handle, _ptr(src), _ptr(dst), nbytes, _stream(stream))
+    ctx.check(rc, "fs_stream_copy")
+
+
+# ---- buffer bundles for the whole-iteration call (allocation only) -----------------------------
+def alloc_layout(n: int, device) -> Dict[str, torch.Tensor]:
+    return {
+        "unique": torch.empty(max(n, 1), dtype=torch.int64, device=device),
+        "seg_offsets": torch.empty(n + 1, dtype=torch.int32, device=device),
+        "perm": torch.empty(max(n, 1), dtype=torch.int32, device=device),
+        "inverse": torch.empty(max(n, 1), dtype=torch.int32, device=device),
+        "n_unique": torch.zeros(1, dtype=torch.int64, device=device),
+        "n": n,
+    }
+
+
+def alloc_split(cap_t: int, cap_t1: int, device) -> Dict[str, torch.Tensor]:
+    i64 = lambda k: torch.empty(max(k, 1), dtype=torch.int64, device=device)
+    i32 = lambda k: torch.empty(max(k, 1), dtype=torch.int32, device=device)
+    return {"co": i64(cap_t), "co_slot": i32(cap_t), "ex": i64(cap_t), "ex_slot": i32(cap_t),
+            "ex_next": i64(cap_t1), "ex_next_slot": i32(cap_t1),
+            "counts": torch.zeros(3, dtype=torch.int64, device=device)}
+
+
+def make_step_args(table: torch.Tensor, state: torch.Tensor, lr: float, eps: float,
+                   layout_t: Dict[str, torch.Tensor], grads_t: Optional[torch.Tensor],
+                   values_t1: Optional[torch.Tensor], offsets_t1: Optional[torch.Tensor],
+                   layout_t1: Optional[Dict[str, torch.Tensor]], split: Dict[str, torch.Tensor],
+                   reduced: Optional[torch.Tensor], emb_t1: Optional[torch.Tensor]) -> fs_step_args:
+    """Fills the argument record of fs_prioritized_step from tensors (pointers only)."""
+    a = fs_step_args()
+    a.table, a.state = _ptr(table), _ptr(state)
+    a.num_rows, a.dim, a.dtype = table.shape[0], table.shape[1], table_dtype_code(table)
+    a.lr, a.eps = lr, eps
+    a.u_t, a.seg_offsets_t, a.perm_t = _ptr(layout_t["unique"]), _ptr(layout_t["seg_offsets"]), _ptr(layout_t["perm"])
+    a.n_unique_t_dev = _ptr(layout_t["n_unique"])
+    a.grads_t = _ptr(grads_t)
+    a.n_t = layout_t["n"]
+    if values_t1 is not None:
+        a.values_t1, a.offsets_t1 = _ptr(values_t1), _ptr(offsets_t1)
+        a.batch_t1 = 0 if offsets_t1 is None else offsets_t1.numel() - 1
+        a.n_t1 = values_t1.numel()
+        a.u_t1, a.seg_offsets_t1 = _ptr(layout_t1["unique"]), _ptr(layout_t1["seg_offsets"])
+        a.perm_t1, a.inverse_t1 = _ptr(layout_t1["perm"]), _ptr(layout_t1.get("inverse"))
+        a.n_unique_t1_dev = _ptr(layout_t1["n_unique"])
+        a.emb_t1 = _ptr(emb_t1)
+    else:
+        a.n_t1, a.batch_t1 = 0, 0
+    a.co, a.co_slot, a.ex, a.ex_slot = _ptr(split["co"]), _ptr(split["co_slot"]), _ptr(split["ex"]), _ptr(split["ex_slot"])
+    a.ex_next, a.ex_next_slot = _ptr(split["ex_next"]), _ptr(split["ex_next_slot"])
+    a.counts_dev = _ptr(split["counts"])
+    a.reduced = _ptr(reduced)
+    return a

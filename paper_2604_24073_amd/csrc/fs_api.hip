@@ -1,0 +1,290 @@
+// C-ABI entry points: argument validation, context/workspace management and the two-stream
+// schedule of one prioritized iteration (Section 3.2 / Algorithm 2 of the paper, collectives
+// removed).  No kernel lives here.
+#include <new>
+
+#include "fs_common.h"
+
+using namespace fs;
+
+namespace {
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct Carver {
+    char *base;
+    size_t off;
+    template <typename T>
+    T *take(size_t count) {
+        off = align_up(off, 256);
+        T *p = base ? reinterpret_cast<T *>(base + off) : nullptr;
+        off += count * sizeof(T);
+        return p;
+    }
+};
+
+void carve(fs_ctx *c, char *base, size_t *total) {
+    Carver cv{base, 0};
+    const size_t n = (size_t)c->max_ids;
+    const size_t sort_tiles = (size_t)ceil_div(c->max_ids, kSortTile) + 1;
+    const size_t scan_tiles = (size_t)ceil_div(c->max_ids, kScanTile) + 2;
+    const size_t chunks = (size_t)ceil_div(c->max_ids, kReduceChunk) + 1;
+    c->d_flags = cv.take<int>(4);
+    c->d_zero = cv.take<int64_t>(1);
+    c->keys[0] = cv.take<uint64_t>(n);
+    c->keys[1] = cv.take<uint64_t>(n);
+    c->idx[0] = cv.take<int32_t>(n);
+    c->idx[1] = cv.take<int32_t>(n);
+    c->tile_hist = cv.take<uint32_t>(sort_tiles * kRadix);
+    c->digit_base = cv.take<uint32_t>(kRadix);
+    c->tile_heads = cv.take<int32_t>(scan_tiles);
+    c->split_flag_t = cv.take<uint8_t>(n + 16);
+    c->split_flag_t1 = cv.take<uint8_t>(n + 16);
+    c->split_cnt = cv.take<int32_t>(2 * scan_tiles);
+    c->part_head = cv.take<double>(chunks * (size_t)c->max_dim);
+    c->part_last = cv.take<double>(chunks * (size_t)c->max_dim);
+    c->chunk_desc = cv.take<int32_t>(chunks * 4);
+    *total = align_up(cv.off, 256);
+}
+
+hipStream_t as_stream(fs_stream s) { return reinterpret_cast<hipStream_t>(s); }
+
+#define FS_REQUIRE(ctx, cond, msg)                          \
+    do {                                                    \
+        if (!(cond)) return set_err(ctx, FS_EINVAL, msg);   \
+    } while (0)
+
+}  // namespace
+
+extern "C" {
+
+int fs_version(void) { return 100; }
+
+int fs_ctx_create(fs_ctx **out, int device, int64_t max_ids, int32_t max_dim) {
+    if (!out) return FS_EINVAL;
+    *out = nullptr;
+    if (device < 0 || max_ids < 1 || max_ids > (1ll << 30) || max_dim < 4 || max_dim > FS_MAX_DIM) return FS_EINVAL;
+    fs_ctx *c = new (std::nothrow) fs_ctx();
+    if (!c) return FS_ENOMEM;
+    memset(c, 0, sizeof(*c));
+    c->device = device;
+    c->max_ids = max_ids;
+    c->max_dim = max_dim;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || device >= ndev) {
+        delete c;
+        return FS_EHIP;
+    }
+    if (hipSetDevice(device) != hipSuccess) {
+        delete c;
+        return FS_EHIP;
+    }
+    carve(c, nullptr, &c->slab_bytes);
+    if (hipMalloc(&c->slab, c->slab_bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        delete c;
+        return FS_ENOMEM;
+    }
+    size_t total;
+    carve(c, static_cast<char *>(c->slab), &total);
+    bool ok = hipMemset(c->slab, 0, 4096) == hipSuccess;
+    ok = ok && hipStreamCreateWithFlags(&c->stream_a, hipStreamNonBlocking) == hipSuccess;
+    ok = ok && hipStreamCreateWithFlags(&c->stream_b, hipStreamNonBlocking) == hipSuccess;
+    hipEvent_t *evs[] = {&c->ev_fork, &c->ev_split, &c->ev_reduce, &c->ev_co, &c->ev_ex};
+    for (hipEvent_t *e : evs) ok = ok && hipEventCreateWithFlags(e, hipEventDisableTiming) == hipSuccess;
+    if (!ok) {
+        fs_ctx_destroy(c);
+        return FS_EHIP;
+    }
+    *out = c;
+    return FS_OK;
+}
+
+int fs_ctx_destroy(fs_ctx *c) {
+    if (!c) return FS_OK;
+    (void)hipSetDevice(c->device);
+    if (c->stream_a) { (void)hipStreamSynchronize(c->stream_a); (void)hipStreamDestroy(c->stream_a); }
+    if (c->stream_b) { (void)hipStreamSynchronize(c->stream_b); (void)hipStreamDestroy(c->stream_b); }
+    hipEvent_t evs[] = {c->ev_fork, c->ev_split, c->ev_reduce, c->ev_co, c->ev_ex};
+    for (hipEvent_t e : evs)
+        if (e) (void)hipEventDestroy(e);
+    if (c->slab) (void)hipFree(c->slab);
+    delete c;
+    return FS_OK;
+}
+
+const char *fs_last_error(const fs_ctx *ctx) { return ctx ? ctx->err : "null context"; }
+
+size_t fs_ctx_workspace_bytes(const fs_ctx *ctx) { return ctx ? ctx->slab_bytes : 0; }
+
+int fs_check_async(fs_ctx *ctx, fs_stream stream) {
+    if (!ctx) return FS_EINVAL;
+    FS_HIP(ctx, hipStreamSynchronize(as_stream(stream)));
+    FS_HIP(ctx, hipStreamSynchronize(ctx->stream_a));
+    FS_HIP(ctx, hipStreamSynchronize(ctx->stream_b));
+    int flags[4] = {0, 0, 0, 0};
+    FS_HIP(ctx, hipMemcpy(flags, ctx->d_flags, sizeof(flags), hipMemcpyDeviceToHost));
+    if (flags[0] == 0) return FS_OK;
+    FS_HIP(ctx, hipMemset(ctx->d_flags, 0, sizeof(flags)));
+    snprintf(ctx->err, sizeof(ctx->err), "device flags 0x%x:%s%s%s", flags[0],
+             (flags[0] & kFlagRowRange) ? " row id out of range" : "",
+             (flags[0] & kFlagOffsets) ? " malformed offsets" : "", (flags[0] & kFlagInternal) ? " internal" : "");
+    return FS_ERANGE;
+}
+
+int fs_gather_jagged(fs_ctx *ctx, const void *table, int64_t num_rows, int32_t dim, fs_dtype dt,
+                     const int64_t *values, const int64_t *offsets, int64_t batch, int64_t n_values, void *out,
+                     fs_stream stream) {
+    if (!ctx) return FS_EINVAL;
+    FS_REQUIRE(ctx, dt == FS_F32 || dt == FS_BF16, "gather: unknown dtype");
+    FS_REQUIRE(ctx, dim_ok(dim, dt), "gather: dim must be a multiple of 4 (fp32) / 8 (bf16), at most FS_MAX_DIM");
+    FS_REQUIRE(ctx, num_rows >= 0 && batch >= 0 && n_values >= 0, "gather: negative size");
+    FS_REQUIRE(ctx, n_values <= (1ll << 31) - 1, "gather: more than 2^31-1 values");
+    if (n_values == 0) return FS_OK;
+    FS_REQUIRE(ctx, table && values && out, "gather: null pointer");
+    const int row_bytes = dim * (dt == FS_F32 ? 4 : 2);
+    return launch_gather(ctx, table, num_rows, row_bytes, values, offsets, batch, n_values, out, as_stream(stream));
+}
+
+int fs_unique_ids(fs_ctx *ctx, const int64_t *ids, int64_t n, int64_t num_rows, int64_t *unique,
+                  int32_t *seg_offsets, int32_t *perm, int32_t *inverse, int64_t *n_unique_dev, fs_stream stream) {
+    if (!ctx) return FS_EINVAL;
+    FS_REQUIRE(ctx, n >= 0 && num_rows >= 0, "unique: negative size");
+    if (n > ctx->max_ids) return set_err(ctx, FS_ENOMEM, "unique: n beyond the context capacity");
+    FS_REQUIRE(ctx, seg_offsets && n_unique_dev, "unique: null pointer");
+    if (n > 0) FS_REQUIRE(ctx, ids && unique && perm, "unique: null pointer");
+    return launch_unique(ctx, ids, n, num_rows, unique, seg_offsets, perm, inverse, n_unique_dev, as_stream(stream));
+}
+
+int fs_collision_split(fs_ctx *ctx, const int64_t *u_t, const int64_t *n_t_dev, const int64_t *u_t1,
+                       const int64_t *n_t1_dev, int64_t cap_t, int64_t cap_t1, int64_t *co, int32_t *co_slot,
+                       int64_t *ex, int32_t *ex_slot, int64_t *ex_next, int32_t *ex_next_slot, int64_t *counts_dev,
+                       fs_stream stream) {
+    if (!ctx) return FS_EINVAL;
+    FS_REQUIRE(ctx, cap_t >= 0 && cap_t1 >= 0, "split: negative capacity");
+    if (cap_t > ctx->max_ids || cap_t1 > ctx->max_ids)
+        return set_err(ctx, FS_ENOMEM, "split: capacity beyond the context capacity");
+    FS_REQUIRE(ctx, counts_dev, "split: null counts");
+    if (cap_t > 0) FS_REQUIRE(ctx, u_t && n_t_dev && co && co_slot && ex && ex_slot, "split: null pointer (t side)");
+    if (cap_t1 > 0) FS_REQUIRE(ctx, u_t1 && n_t1_dev && ex_next && ex_next_slot, "split: null pointer (t+1 side)");
+    return launch_split(ctx, u_t, cap_t > 0 ? n_t_dev : nullptr, u_t1, cap_t1 > 0 ? n_t1_dev : nullptr, cap_t, cap_t1,
+                        co, co_slot, ex, ex_slot, ex_next, ex_next_slot, counts_dev, as_stream(stream));
+}
+
+int fs_segment_reduce_grads(fs_ctx *ctx, const float *grads, int64_t n, int32_t dim, const int32_t *perm,
+                            const int32_t *seg_offsets, const int64_t *n_unique_dev, float *reduced,
+                            fs_stream stream) {
+    if (!ctx) return FS_EINVAL;
+    FS_REQUIRE(ctx, n >= 0, "reduce: negative size");
+    FS_REQUIRE(ctx, dim_ok(dim, FS_F32), "reduce: dim must be a multiple of 4, at most FS_MAX_DIM");
+    if (n > ctx->max_ids || dim > ctx->max_dim) return set_err(ctx, FS_ENOMEM, "reduce: beyond the context capacity");
+    if (n == 0) return FS_OK;
+    FS_REQUIRE(ctx, grads && perm && seg_offsets && n_unique_dev && reduced, "reduce: null pointer");
+    return launch_reduce(ctx, grads, n, dim, perm, seg_offsets, n_unique_dev, reduced, as_stream(stream));
+}
+
+int fs_rowwise_adagrad_update(fs_ctx *ctx, void *table, fs_dtype dt, float *state, int64_t num_rows, int32_t dim,
+                              const int64_t *rows, const int32_t *slots, const int64_t *n_rows_dev, int64_t cap,
+                              const float *reduced, float lr, float eps, fs_stream stream) {
+    if (!ctx) return FS_EINVAL;
+    FS_REQUIRE(ctx, dt == FS_F32 || dt == FS_BF16, "adagrad: unknown dtype");
+    FS_REQUIRE(ctx, dim_ok(dim, dt), "adagrad: dim must be a multiple of 4 (fp32) / 8 (bf16), at most FS_MAX_DIM");
+    FS_REQUIRE(ctx, num_rows >= 0 && cap >= 0, "adagrad: negative size");
+    if (cap == 0) return FS_OK;
+    FS_REQUIRE(ctx, table && state && rows && slots && n_rows_dev && reduced, "adagrad: null pointer");
+    return launch_adagrad(ctx, table, dt, state, num_rows, dim, rows, slots, n_rows_dev, cap, reduced, lr, eps,
+                          as_stream(stream));
+}
+
+int fs_init_table_hash(fs_ctx *ctx, void *table, int64_t num_rows, int32_t dim, fs_dtype dt, fs_stream stream) {
+    if (!ctx) return FS_EINVAL;
+    FS_REQUIRE(ctx, dt == FS_F32 || dt == FS_BF16, "init: unknown dtype");
+    FS_REQUIRE(ctx, dim_ok(dim, dt) && num_rows >= 0, "init: bad shape");
+    if (num_rows == 0) return FS_OK;
+    FS_REQUIRE(ctx, table, "init: null pointer");
+    return launch_init_hash(ctx, table, num_rows, dim, dt, as_stream(stream));
+}
+
+int fs_stream_copy(fs_ctx *ctx, const void *src, void *dst, int64_t n_bytes, fs_stream stream) {
+    if (!ctx) return FS_EINVAL;
+    FS_REQUIRE(ctx, n_bytes >= 0 && n_bytes % 16 == 0, "copy: size must be a non-negative multiple of 16");
+    if (n_bytes == 0) return FS_OK;
+    FS_REQUIRE(ctx, src && dst, "copy: null pointer");
+    return launch_copy(ctx, src, dst, n_bytes, as_stream(stream));
+}
+
+int fs_prioritized_step(fs_ctx *ctx, const fs_step_args *a, fs_stream stream) {
+    if (!ctx) return FS_EINVAL;
+    FS_REQUIRE(ctx, a, "step: null args");
+    const int dt = a->dtype;
+    FS_REQUIRE(ctx, dt == FS_F32 || dt == FS_BF16, "step: unknown dtype");
+    FS_REQUIRE(ctx, dim_ok(a->dim, dt), "step: unsupported dim");
+    FS_REQUIRE(ctx, a->num_rows >= 0 && a->n_t >= 0 && a->n_t1 >= 0 && a->batch_t1 >= 0, "step: negative size");
+    if (a->n_t > ctx->max_ids || a->n_t1 > ctx->max_ids || a->dim > ctx->max_dim)
+        return set_err(ctx, FS_ENOMEM, "step: beyond the context capacity");
+    FS_REQUIRE(ctx, a->table && a->state && a->counts_dev, "step: null table/state/counts");
+    const bool have_t = a->n_t > 0;
+    const bool have_t1 = a->values_t1 != nullptr && a->n_t1 > 0;
+    if (have_t)
+        FS_REQUIRE(ctx, a->u_t && a->seg_offsets_t && a->perm_t && a->n_unique_t_dev && a->grads_t && a->reduced &&
+                            a->co && a->co_slot && a->ex && a->ex_slot,
+                   "step: null pointer (iteration t)");
+    if (have_t1)
+        FS_REQUIRE(ctx, a->u_t1 && a->seg_offsets_t1 && a->perm_t1 && a->n_unique_t1_dev && a->ex_next &&
+                            a->ex_next_slot && a->emb_t1,
+                   "step: null pointer (lookahead)");
+
+    hipStream_t sp = as_stream(stream), sa = ctx->stream_a, sb = ctx->stream_b;
+    const fs_dtype fdt = (fs_dtype)dt;
+    int rc;
+    // fork: the side streams start after whatever the caller already queued on `stream`
+    FS_HIP(ctx, hipEventRecord(ctx->ev_fork, sp));
+    FS_HIP(ctx, hipStreamWaitEvent(sa, ctx->ev_fork, 0));
+    FS_HIP(ctx, hipStreamWaitEvent(sb, ctx->ev_fork, 0));
+
+    // side stream A: dedup of the lookahead IDs, then the collision split
+    if (have_t1) {
+        rc = launch_unique(ctx, a->values_t1, a->n_t1, a->num_rows, a->u_t1, a->seg_offsets_t1, a->perm_t1,
+                           a->inverse_t1, a->n_unique_t1_dev, sa);
+        if (rc != FS_OK) return rc;
+    }
+    rc = launch_split(ctx, a->u_t, have_t ? a->n_unique_t_dev : nullptr, a->u_t1,
+                      have_t1 ? a->n_unique_t1_dev : nullptr, have_t ? a->n_t : 0, have_t1 ? a->n_t1 : 0, a->co,
+                      a->co_slot, a->ex, a->ex_slot, a->ex_next, a->ex_next_slot, a->counts_dev, sa);
+    if (rc != FS_OK) return rc;
+    FS_HIP(ctx, hipEventRecord(ctx->ev_split, sa));
+
+    // main stream: reduce the gradients of t while A works on the indices of t+1
+    if (have_t) {
+        rc = launch_reduce(ctx, a->grads_t, a->n_t, a->dim, a->perm_t, a->seg_offsets_t, a->n_unique_t_dev, a->reduced,
+                           sp);
+        if (rc != FS_OK) return rc;
+    }
+    FS_HIP(ctx, hipEventRecord(ctx->ev_reduce, sp));
+    FS_HIP(ctx, hipStreamWaitEvent(sp, ctx->ev_split, 0));
+
+    // deferred pass on B: needs the split and the reduced gradients, nothing else
+    FS_HIP(ctx, hipStreamWaitEvent(sb, ctx->ev_split, 0));
+    FS_HIP(ctx, hipStreamWaitEvent(sb, ctx->ev_reduce, 0));
+    if (have_t) {
+        // priority pass: collision rows, strictly before the lookahead rows are read
+        rc = launch_adagrad(ctx, a->table, fdt, a->state, a->num_rows, a->dim, a->co, a->co_slot, a->counts_dev + 0,
+                            a->n_t, a->reduced, a->lr, a->eps, sp);
+        if (rc != FS_OK) return rc;
+        rc = launch_adagrad(ctx, a->table, fdt, a->state, a->num_rows, a->dim, a->ex, a->ex_slot, a->counts_dev + 1,
+                            a->n_t, a->reduced, a->lr, a->eps, sb);
+        if (rc != FS_OK) return rc;
+    }
+    FS_HIP(ctx, hipEventRecord(ctx->ev_ex, sb));
+    if (have_t1) {
+        // exclusive rows and lookahead rows are disjoint, so this may overlap the deferred pass
+        const int row_bytes = a->dim * (dt == FS_F32 ? 4 : 2);
+        rc = launch_gather(ctx, a->table, a->num_rows, row_bytes, a->values_t1, a->offsets_t1, a->batch_t1, a->n_t1,
+                           a->emb_t1, sp);
+        if (rc != FS_OK) return rc;
+    }
+    FS_HIP(ctx, hipStreamWaitEvent(sp, ctx->ev_ex, 0));
+    return FS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,130 @@
+// Internal declarations shared by the HIP translation units of libfreescale_hip.so.
+// gfx950 only: 64-wide wavefronts, 16 bytes per lane per memory instruction.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "freescale.h"
+
+namespace fs {
+
+constexpr int kWave = 64;
+
+// radix sort geometry
+constexpr int kRadixBits = 8;
+constexpr int kRadix = 1 << kRadixBits;
+constexpr int kSortThreads = 256;
+constexpr int kSortKpt = 8;                               // keys per thread
+constexpr int kSortTile = kSortThreads * kSortKpt;        // keys per tile
+constexpr int kSortWaves = kSortThreads / kWave;
+
+// unique / split compaction geometry
+constexpr int kScanThreads = 256;
+constexpr int kScanIpt = 4;
+constexpr int kScanTile = kScanThreads * kScanIpt;
+
+// segment reduce: sorted positions owned by one wavefront
+constexpr int kReduceChunk = 128;
+constexpr int kReduceWavesPerBlock = 4;
+
+// device-side error flag bits (ctx->d_flags[0])
+constexpr int kFlagRowRange = 1;
+constexpr int kFlagOffsets = 2;
+constexpr int kFlagInternal = 4;
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+}  // namespace fs
+
+struct fs_ctx {
+    int device;
+    int64_t max_ids;
+    int32_t max_dim;
+    char err[512];
+
+    // one slab of device workspace, carved into the pointers below
+    void *slab;
+    size_t slab_bytes;
+
+    int *d_flags;             // [4] device error flags
+    // sort
+    uint64_t *keys[2];        // [max_ids] each (also used as uint32 keys)
+    int32_t *idx[2];          // [max_ids] each
+    uint32_t *tile_hist;      // [tiles * 256] per-tile digit counts, then their exclusive prefix
+    uint32_t *digit_base;     // [256]
+    int32_t *tile_heads;      // [scan tiles] heads per compaction tile
+    // split
+    uint8_t *split_flag_t;    // [max_ids]
+    uint8_t *split_flag_t1;   // [max_ids]
+    int32_t *split_cnt;       // [3 * scan tiles]
+    // segment reduce
+    double *part_head;        // [chunks, max_dim] fp64 partial of the first run of each chunk
+    double *part_last;        // [chunks, max_dim] fp64 partial of the last run of each chunk
+    int32_t *chunk_desc;      // [chunks * 4]
+    int64_t *d_zero;          // device scalar that stays 0 (stands in for a missing lookahead)
+
+    hipStream_t stream_a;     // index work of the lookahead batch
+    hipStream_t stream_b;     // deferred update pass
+    hipEvent_t ev_fork, ev_split, ev_reduce, ev_co, ev_ex;
+};
+
+namespace fs {
+
+inline int set_err(fs_ctx *ctx, int code, const char *msg) {
+    if (ctx) snprintf(ctx->err, sizeof(ctx->err), "%s", msg);
+    return code;
+}
+
+inline int hip_err(fs_ctx *ctx, hipError_t e, const char *what) {
+    if (ctx) snprintf(ctx->err, sizeof(ctx->err), "%s: %s", what, hipGetErrorString(e));
+    return FS_EHIP;
+}
+
+#define FS_HIP(ctx, call)                                        \
+    do {                                                         \
+        hipError_t e__ = (call);                                 \
+        if (e__ != hipSuccess) return fs::hip_err(ctx, e__, #call); \
+    } while (0)
+
+#define FS_LAUNCH_CHECK(ctx, name)                               \
+    do {                                                         \
+        hipError_t e__ = hipGetLastError();                      \
+        if (e__ != hipSuccess) return fs::hip_err(ctx, e__, name); \
+    } while (0)
+
+inline bool dim_ok(int32_t dim, int dt) {
+    if (dim <= 0 || dim > FS_MAX_DIM) return false;
+    return dt == FS_F32 ? (dim % 4 == 0) : (dim % 8 == 0);
+}
+
+// lanes that cover one row of `granules` 16-byte pieces: next power of two, at most 64
+inline int lanes_per_row(int granules) {
+    int l = 1;
+    while (l < granules) l <<= 1;
+    return l;
+}
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// launchers implemented in the kernel translation units (host side, argument-checked callers)
+int launch_gather(fs_ctx *, const void *table, int64_t num_rows, int row_bytes, const int64_t *values,
+                  const int64_t *offsets, int64_t batch, int64_t n, void *out, hipStream_t s);
+int launch_unique(fs_ctx *, const int64_t *ids, int64_t n, int64_t num_rows, int64_t *unique,
+                  int32_t *seg_offsets, int32_t *perm, int32_t *inverse, int64_t *n_unique_dev, hipStream_t s);
+int launch_split(fs_ctx *, const int64_t *u_t, const int64_t *n_t_dev, const int64_t *u_t1,
+                 const int64_t *n_t1_dev, int64_t cap_t, int64_t cap_t1, int64_t *co, int32_t *co_slot,
+                 int64_t *ex, int32_t *ex_slot, int64_t *ex_next, int32_t *ex_next_slot, int64_t *counts_dev,
+                 hipStream_t s);
+int launch_reduce(fs_ctx *, const float *grads, int64_t n, int32_t dim, const int32_t *perm,
+                  const int32_t *seg_offsets, const int64_t *n_unique_dev, float *reduced, hipStream_t s);
+int launch_adagrad(fs_ctx *, void *table, int dt, float *state, int64_t num_rows, int32_t dim,
+                   const int64_t *rows, const int32_t *slots, const int64_t *n_rows_dev, int64_t cap,
+                   const float *reduced, float lr, float eps, hipStream_t s);
+int launch_init_hash(fs_ctx *, void *table, int64_t num_rows, int32_t dim, int dt, hipStream_t s);
+int launch_copy(fs_ctx *, const void *src, void *dst, int64_t n_bytes, hipStream_t s);
+
+}  // namespace fs

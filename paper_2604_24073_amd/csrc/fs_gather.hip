@@ -1,0 +1,169 @@
+// Jagged row gather (Lookup(I) of Algorithm 2) plus the two helper kernels that only move or
+// generate bytes: the hash table initialiser and the plain stream copy.
+//
+// Gather layout: a row is `granules` 16-byte pieces.  LPR = next power of two >= granules lanes
+// cover one row, so one wavefront instruction moves 64/LPR rows (2 rows of 128 fp32, 4 rows of
+// 64 fp32 or 128 bf16, 1 row of 256 fp32).  Work is flat over the N occurrences, never one
+// workgroup per user, so a 16K-item sequence costs the same per item as a short one.
+#include "fs_common.h"
+
+namespace fs {
+
+template <int LPR, int UNR>
+__global__ __launch_bounds__(256) void gather_kernel(const u32x4 *__restrict__ table, int64_t num_rows,
+                                                     int granules, const int64_t *__restrict__ values,
+                                                     const int64_t *__restrict__ offsets, int64_t batch, int64_t n,
+                                                     u32x4 *__restrict__ out, int *__restrict__ flags) {
+    constexpr int GPW = kWave / LPR;                  // rows per wavefront instruction
+    constexpr int ROWS_PER_WAVE = GPW * UNR;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int grp = lane / LPR;
+    const int lig = lane % LPR;
+    const int64_t wave = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    const int64_t row0 = wave * ROWS_PER_WAVE;
+
+    // offsets validation rides along (grid-stride over the batch; almost free)
+    if (offsets != nullptr) {
+        const int64_t gtid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+        const int64_t gsz = (int64_t)gridDim.x * blockDim.x;
+        bool bad = false;
+        for (int64_t b = gtid; b < batch; b += gsz) bad |= offsets[b + 1] < offsets[b];
+        if (gtid == 0) bad |= (offsets[0] != 0) || (offsets[batch] != n);
+        if (bad) atomicOr(flags, kFlagOffsets);
+    }
+    if (row0 >= n) return;
+
+    int64_t id[UNR];
+    bool live[UNR];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+        const int64_t j = row0 + u * GPW + grp;
+        live[u] = (j < n) && (lig < granules);
+        id[u] = live[u] ? values[j] : 0;
+    }
+    u32x4 v[UNR];
+    bool oob = false;
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+        const bool in = (id[u] >= 0) && (id[u] < num_rows);
+        oob |= live[u] && !in;
+        v[u] = u32x4{0u, 0u, 0u, 0u};
+        if (live[u] && in) v[u] = table[id[u] * granules + lig];
+    }
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+        const int64_t j = row0 + u * GPW + grp;
+        if (live[u]) __builtin_nontemporal_store(v[u], &out[j * granules + lig]);
+    }
+    if (oob) atomicOr(flags, kFlagRowRange);
+}
+
+template <int LPR>
+static void gather_launch(const void *table, int64_t num_rows, int granules, const int64_t *values,
+                          const int64_t *offsets, int64_t batch, int64_t n, void *out, int *flags, hipStream_t s) {
+    constexpr int UNR = 4;
+    constexpr int ROWS_PER_BLOCK = (kWave / LPR) * UNR * 4;
+    const int64_t blocks = ceil_div(n, ROWS_PER_BLOCK);
+    hipLaunchKernelGGL((gather_kernel<LPR, UNR>), dim3((unsigned)blocks), dim3(256), 0, s, (const u32x4 *)table,
+                       num_rows, granules, values, offsets, batch, n, (u32x4 *)out, flags);
+}
+
+int launch_gather(fs_ctx *ctx, const void *table, int64_t num_rows, int row_bytes, const int64_t *values,
+                  const int64_t *offsets, int64_t batch, int64_t n, void *out, hipStream_t s) {
+    if (n == 0) return FS_OK;
+    const int granules = row_bytes / 16;
+    switch (lanes_per_row(granules)) {
+        case 1: gather_launch<1>(table, num_rows, granules, values, offsets, batch, n, out, ctx->d_flags, s); break;
+        case 2: gather_launch<2>(table, num_rows, granules, values, offsets, batch, n, out, ctx->d_flags, s); break;
+        case 4: gather_launch<4>(table, num_rows, granules, values, offsets, batch, n, out, ctx->d_flags, s); break;
+        case 8: gather_launch<8>(table, num_rows, granules, values, offsets, batch, n, out, ctx->d_flags, s); break;
+        case 16: gather_launch<16>(table, num_rows, granules, values, offsets, batch, n, out, ctx->d_flags, s); break;
+        case 32: gather_launch<32>(table, num_rows, granules, values, offsets, batch, n, out, ctx->d_flags, s); break;
+        case 64: gather_launch<64>(table, num_rows, granules, values, offsets, batch, n, out, ctx->d_flags, s); break;
+        default: return set_err(ctx, FS_EINVAL, "gather: row wider than 1024 bytes");
+    }
+    FS_LAUNCH_CHECK(ctx, "gather_kernel");
+    return FS_OK;
+}
+
+// ---- hash initialiser (input generator; mirrors the rule of the synthetic workloads) --------
+__device__ __forceinline__ uint32_t mix32(uint32_t x) {
+    x ^= x >> 16;
+    x *= 0x7FEB352Du;
+    x ^= x >> 15;
+    x *= 0x846CA68Bu;
+    x ^= x >> 16;
+    return x;
+}
+
+__device__ __forceinline__ uint32_t elem_hash(uint64_t e) {
+    return mix32((uint32_t)e ^ mix32((uint32_t)(e >> 32) + 0x9E3779B9u));
+}
+
+__global__ __launch_bounds__(256) void init_hash_f32_kernel(f32x4 *__restrict__ table, int64_t n_vec) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += stride) {
+        const uint64_t e = (uint64_t)i * 4;
+        f32x4 v;
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            v[c] = (float)((int)(elem_hash(e + c) & 0xFFFFu) - 32768) * 0x1p-22f;
+        __builtin_nontemporal_store(v, &table[i]);
+    }
+}
+
+__global__ __launch_bounds__(256) void init_hash_bf16_kernel(u32x4 *__restrict__ table, int64_t n_vec) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += stride) {
+        const uint64_t e = (uint64_t)i * 8;
+        u32x4 v;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            // values are exact in bf16 (8 significant bits): the high half of the fp32 pattern
+            const float lo = (float)((int)(elem_hash(e + 2 * c) & 0xFFu) - 128) * 0x1p-14f;
+            const float hi = (float)((int)(elem_hash(e + 2 * c + 1) & 0xFFu) - 128) * 0x1p-14f;
+            v[c] = (__float_as_uint(lo) >> 16) | (__float_as_uint(hi) & 0xFFFF0000u);
+        }
+        __builtin_nontemporal_store(v, &table[i]);
+    }
+}
+
+int launch_init_hash(fs_ctx *ctx, void *table, int64_t num_rows, int32_t dim, int dt, hipStream_t s) {
+    const int64_t elems = num_rows * (int64_t)dim;
+    if (elems == 0) return FS_OK;
+    const int64_t n_vec = elems / (dt == FS_F32 ? 4 : 8);
+    const int64_t blocks = ceil_div(n_vec, 256) < 16384 ? ceil_div(n_vec, 256) : 16384;
+    if (dt == FS_F32)
+        hipLaunchKernelGGL(init_hash_f32_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (f32x4 *)table, n_vec);
+    else
+        hipLaunchKernelGGL(init_hash_bf16_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (u32x4 *)table, n_vec);
+    FS_LAUNCH_CHECK(ctx, "init_hash_kernel");
+    return FS_OK;
+}
+
+// ---- plain copy (bandwidth calibration) -------------------------------------------------------
+__global__ __launch_bounds__(256) void copy_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, int64_t n_vec) {
+    const int64_t base = ((int64_t)blockIdx.x * blockDim.x) * 4 + threadIdx.x;
+    u32x4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int64_t i = base + (int64_t)u * blockDim.x;
+        if (i < n_vec) v[u] = __builtin_nontemporal_load(&src[i]);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int64_t i = base + (int64_t)u * blockDim.x;
+        if (i < n_vec) __builtin_nontemporal_store(v[u], &dst[i]);
+    }
+}
+
+int launch_copy(fs_ctx *ctx, const void *src, void *dst, int64_t n_bytes, hipStream_t s) {
+    const int64_t n_vec = n_bytes / 16;
+    if (n_vec == 0) return FS_OK;
+    const int64_t blocks = ceil_div(n_vec, 1024);
+    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const u32x4 *)src, (u32x4 *)dst, n_vec);
+    FS_LAUNCH_CHECK(ctx, "copy_kernel");
+    return FS_OK;
+}
+
+}  // namespace fs

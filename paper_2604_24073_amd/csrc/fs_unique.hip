@@ -1,0 +1,316 @@
+// Dedup of one iteration's row IDs: stable LSD radix sort of (ID, position) pairs followed by a
+// head-flag compaction that yields the ascending distinct rows, the segment offsets, the stable
+// permutation and the inverse map.  (Collisions are defined on rows, Section 2.3 of the paper;
+// compute_collision of Algorithm 2 consumes the distinct lists.)
+//
+// Only ceil(log2(num_rows)) key bits are sorted, 8 per pass; keys travel as 32-bit words when
+// they fit.  Each pass is three launches: per-tile digit histogram (LDS counters), one-workgroup
+// exclusive scan of the [tile][digit] table, and a scatter that ranks keys with wavefront
+// ballots so equal digits keep their order.
+#include "fs_common.h"
+
+namespace fs {
+
+// ---- small block-scan helper (256 threads) ---------------------------------------------------
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+    const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int t = __shfl_up(v, d, kWave);
+        if (lane >= d) v += t;
+    }
+    return v;
+}
+
+// exclusive scan of one int per thread over a 256-thread block; total returned to all threads.
+// `sh` must hold kScanThreads/kWave + 1 ints.  Contains two barriers.
+__device__ __forceinline__ int block_exclusive_scan(int v, int *sh, int &total) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = threadIdx.x / kWave;
+    const int inc = wave_inclusive_scan(v);
+    if (lane == kWave - 1) sh[w] = inc;
+    __syncthreads();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < kScanThreads / kWave; ++i) {
+        const int x = sh[i];
+        if (i < w) base += x;
+        tot += x;
+    }
+    __syncthreads();
+    total = tot;
+    return base + inc - v;
+}
+
+// ---- radix pass 1/3: per-tile digit histogram ---------------------------------------------------
+template <typename K, bool FIRST>
+__global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(const int64_t *__restrict__ ids,
+                                                                  const K *__restrict__ keys_in, int n, int shift,
+                                                                  int64_t num_rows, uint32_t *__restrict__ tile_hist,
+                                                                  int *__restrict__ flags) {
+    __shared__ uint32_t hist[kRadix];
+    hist[threadIdx.x] = 0;
+    __syncthreads();
+    const int base = blockIdx.x * kSortTile;
+    bool bad = false;
+#pragma unroll
+    for (int r = 0; r < kSortKpt; ++r) {
+        const int e = base + r * kSortThreads + threadIdx.x;
+        if (e < n) {
+            K key;
+            if (FIRST) {
+                const int64_t id = ids[e];
+                bad |= (id < 0) || (num_rows > 0 && id >= num_rows);
+                key = (K)id;
+            } else {
+                key = keys_in[e];
+            }
+            atomicAdd(&hist[(uint32_t)(key >> shift) & (kRadix - 1)], 1u);
+        }
+    }
+    __syncthreads();
+    tile_hist[blockIdx.x * kRadix + threadIdx.x] = hist[threadIdx.x];
+    if (bad) atomicOr(flags, kFlagRowRange);
+}
+
+// ---- radix pass 2/3: exclusive scan of the [tile][digit] table (digit-major order) ------------
+// One workgroup of 1024 threads: thread (q, d) owns a quarter of the tiles of digit d.
+__global__ __launch_bounds__(1024) void radix_scan_kernel(uint32_t *__restrict__ tile_hist, int tiles) {
+    __shared__ uint32_t part[4][kRadix];
+    __shared__ uint32_t dscan[kRadix];
+    const int d = threadIdx.x & (kRadix - 1);
+    const int q = threadIdx.x >> kRadixBits;
+    const int per = (tiles + 3) / 4;
+    const int t0 = q * per;
+    const int t1 = (t0 + per < tiles) ? t0 + per : tiles;
+    uint32_t sum = 0;
+    for (int t = t0; t < t1; ++t) sum += tile_hist[t * kRadix + d];
+    part[q][d] = sum;
+    __syncthreads();
+    if (q == 0) dscan[d] = part[0][d] + part[1][d] + part[2][d] + part[3][d];
+    __syncthreads();
+    // exclusive scan over the 256 digit totals (Hillis-Steele in LDS, first 256 threads)
+    uint32_t incl = 0;
+    for (int off = 1; off < kRadix; off <<= 1) {
+        uint32_t add = 0;
+        if (q == 0) {
+            incl = dscan[d];
+            if (d >= off) add = dscan[d - off];
+        }
+        __syncthreads();
+        if (q == 0) dscan[d] = incl + add;
+        __syncthreads();
+    }
+    uint32_t run = dscan[d] - (part[0][d] + part[1][d] + part[2][d] + part[3][d]);   // exclusive digit base
+    for (int i = 0; i < q; ++i) run += part[i][d];
+    for (int t = t0; t < t1; ++t) {
+        const uint32_t v = tile_hist[t * kRadix + d];
+        tile_hist[t * kRadix + d] = run;
+        run += v;
+    }
+}
+
+// ---- radix pass 3/3: stable scatter ---------------------------------------------------------------
+// Tile order is (wave, round, lane): wave w owns 64*KPT consecutive keys, read 64 at a time.
+template <typename K, bool FIRST>
+__global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(const int64_t *__restrict__ ids,
+                                                                     const K *__restrict__ keys_in,
+                                                                     const int32_t *__restrict__ idx_in,
+                                                                     K *__restrict__ keys_out,
+                                                                     int32_t *__restrict__ idx_out, int n, int shift,
+                                                                     const uint32_t *__restrict__ tile_offsets) {
+    __shared__ uint32_t cnt[kSortWaves][kRadix];
+    __shared__ uint32_t gbase[kRadix];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = threadIdx.x / kWave;
+#pragma unroll
+    for (int i = 0; i < kSortWaves; ++i) cnt[i][threadIdx.x] = 0;
+    gbase[threadIdx.x] = tile_offsets[blockIdx.x * kRadix + threadIdx.x];
+    __syncthreads();
+
+    const int base = blockIdx.x * kSortTile + w * (kWave * kSortKpt);
+    const uint64_t lt = (1ull << lane) - 1ull;
+    K key[kSortKpt];
+    uint32_t rank[kSortKpt];
+#pragma unroll
+    for (int r = 0; r < kSortKpt; ++r) {
+        const int e = base + r * kWave + lane;
+        const bool valid = e < n;
+        key[r] = 0;
+        if (valid) key[r] = FIRST ? (K)ids[e] : keys_in[e];
+    }
+#pragma unroll
+    for (int r = 0; r < kSortKpt; ++r) {
+        const int e = base + r * kWave + lane;
+        const bool valid = e < n;
+        const uint32_t digit = (uint32_t)(key[r] >> shift) & (kRadix - 1);
+        uint64_t peers = __ballot(valid);
+#pragma unroll
+        for (int b = 0; b < kRadixBits; ++b) {
+            const bool bit = (digit >> b) & 1u;
+            const uint64_t bal = __ballot(bit);
+            peers &= bit ? bal : ~bal;
+        }
+        const uint32_t before = __popcll(peers & lt);
+        const uint32_t old = valid ? cnt[w][digit] : 0u;              // all peers read ...
+        if (valid && before == 0) cnt[w][digit] = old + (uint32_t)__popcll(peers);   // ... then the first one writes
+        rank[r] = old + before;
+    }
+    __syncthreads();
+    {   // exclusive prefix over the waves of this tile, per digit
+        uint32_t run = 0;
+#pragma unroll
+        for (int i = 0; i < kSortWaves; ++i) {
+            const uint32_t v = cnt[i][threadIdx.x];
+            cnt[i][threadIdx.x] = run;
+            run += v;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < kSortKpt; ++r) {
+        const int e = base + r * kWave + lane;
+        if (e < n) {
+            const uint32_t digit = (uint32_t)(key[r] >> shift) & (kRadix - 1);
+            const uint32_t pos = gbase[digit] + cnt[w][digit] + rank[r];
+            keys_out[pos] = key[r];
+            idx_out[pos] = FIRST ? e : idx_in[e];
+        }
+    }
+}
+
+// ---- unique 1/2: heads per compaction tile ---------------------------------------------------------
+template <typename K>
+__device__ __forceinline__ int load_heads(const K *__restrict__ keys, int n, int p0, K (&k)[kScanIpt], bool (&head)[kScanIpt]) {
+    K prev = 0;
+    if (p0 > 0 && p0 < n) prev = keys[p0 - 1];
+    int c = 0;
+#pragma unroll
+    for (int i = 0; i < kScanIpt; ++i) {
+        const int p = p0 + i;
+        k[i] = (p < n) ? keys[p] : 0;
+        head[i] = (p < n) && (p == 0 || k[i] != prev);
+        prev = k[i];
+        c += head[i] ? 1 : 0;
+    }
+    return c;
+}
+
+template <typename K>
+__global__ __launch_bounds__(kScanThreads) void unique_count_kernel(const K *__restrict__ keys, int n,
+                                                                    int32_t *__restrict__ tile_heads) {
+    __shared__ int sh[kScanThreads / kWave + 1];
+    K k[kScanIpt];
+    bool head[kScanIpt];
+    const int c = load_heads<K>(keys, n, blockIdx.x * kScanTile + threadIdx.x * kScanIpt, k, head);
+    int total;
+    (void)block_exclusive_scan(c, sh, total);
+    if (threadIdx.x == 0) tile_heads[blockIdx.x] = total;
+}
+
+// ---- unique 2/2: compaction -------------------------------------------------------------------------
+template <typename K>
+__global__ __launch_bounds__(kScanThreads) void unique_compact_kernel(const K *__restrict__ keys,
+                                                                      const int32_t *__restrict__ perm, int n,
+                                                                      const int32_t *__restrict__ tile_heads,
+                                                                      int64_t *__restrict__ unique,
+                                                                      int32_t *__restrict__ seg_offsets,
+                                                                      int32_t *__restrict__ inverse,
+                                                                      int64_t *__restrict__ n_unique_dev) {
+    __shared__ int sh[kScanThreads / kWave + 1];
+    // heads in all earlier tiles: a cooperative sum (tiles is a few hundred)
+    int before = 0;
+    for (int t = threadIdx.x; t < (int)blockIdx.x; t += kScanThreads) before += tile_heads[t];
+    int tile_base;
+    (void)block_exclusive_scan(before, sh, tile_base);
+
+    K k[kScanIpt];
+    bool head[kScanIpt];
+    const int p0 = blockIdx.x * kScanTile + threadIdx.x * kScanIpt;
+    const int c = load_heads<K>(keys, n, p0, k, head);
+    int tile_total;
+    int rank = tile_base + block_exclusive_scan(c, sh, tile_total);    // heads strictly before p0
+#pragma unroll
+    for (int i = 0; i < kScanIpt; ++i) {
+        const int p = p0 + i;
+        if (p < n) {
+            if (head[i]) {
+                unique[rank] = (int64_t)k[i];
+                seg_offsets[rank] = p;
+                ++rank;
+            }
+            if (inverse != nullptr) inverse[perm[p]] = rank - 1;
+        }
+    }
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+        const int total = tile_base + tile_total;
+        seg_offsets[total] = n;
+        *n_unique_dev = total;
+    }
+}
+
+__global__ void unique_empty_kernel(int32_t *seg_offsets, int64_t *n_unique_dev) {
+    seg_offsets[0] = 0;
+    *n_unique_dev = 0;
+}
+
+// ---- host side ------------------------------------------------------------------------------------------
+template <typename K>
+static int unique_impl(fs_ctx *ctx, const int64_t *ids, int n, int key_bits, int64_t num_rows, int64_t *unique,
+                       int32_t *seg_offsets, int32_t *perm, int32_t *inverse, int64_t *n_unique_dev, hipStream_t s) {
+    const int tiles = (int)ceil_div(n, kSortTile);
+    const int passes = (key_bits + kRadixBits - 1) / kRadixBits;
+    K *kbuf[2] = {(K *)ctx->keys[0], (K *)ctx->keys[1]};
+    int cur = 0;   // buffer holding the input of the next pass (unused for the first pass)
+    for (int p = 0; p < passes; ++p) {
+        const int shift = p * kRadixBits;
+        const bool last = (p == passes - 1);
+        K *kout = kbuf[cur ^ 1];
+        int32_t *iout = last ? perm : ctx->idx[cur ^ 1];
+        if (p == 0) {
+            hipLaunchKernelGGL((radix_hist_kernel<K, true>), dim3(tiles), dim3(kSortThreads), 0, s, ids,
+                               (const K *)nullptr, n, shift, num_rows, ctx->tile_hist, ctx->d_flags);
+            hipLaunchKernelGGL(radix_scan_kernel, dim3(1), dim3(1024), 0, s, ctx->tile_hist, tiles);
+            hipLaunchKernelGGL((radix_scatter_kernel<K, true>), dim3(tiles), dim3(kSortThreads), 0, s, ids,
+                               (const K *)nullptr, (const int32_t *)nullptr, kout, iout, n, shift, ctx->tile_hist);
+        } else {
+            hipLaunchKernelGGL((radix_hist_kernel<K, false>), dim3(tiles), dim3(kSortThreads), 0, s,
+                               (const int64_t *)nullptr, (const K *)kbuf[cur], n, shift, num_rows, ctx->tile_hist,
+                               ctx->d_flags);
+            hipLaunchKernelGGL(radix_scan_kernel, dim3(1), dim3(1024), 0, s, ctx->tile_hist, tiles);
+            hipLaunchKernelGGL((radix_scatter_kernel<K, false>), dim3(tiles), dim3(kSortThreads), 0, s,
+                               (const int64_t *)nullptr, (const K *)kbuf[cur], (const int32_t *)ctx->idx[cur], kout,
+                               iout, n, shift, ctx->tile_hist);
+        }
+        cur ^= 1;
+    }
+    const int stiles = (int)ceil_div(n, kScanTile);
+    hipLaunchKernelGGL((unique_count_kernel<K>), dim3(stiles), dim3(kScanThreads), 0, s, (const K *)kbuf[cur], n,
+                       ctx->tile_heads);
+    hipLaunchKernelGGL((unique_compact_kernel<K>), dim3(stiles), dim3(kScanThreads), 0, s, (const K *)kbuf[cur],
+                       (const int32_t *)perm, n, (const int32_t *)ctx->tile_heads, unique, seg_offsets, inverse,
+                       n_unique_dev);
+    FS_LAUNCH_CHECK(ctx, "unique kernels");
+    return FS_OK;
+}
+
+int launch_unique(fs_ctx *ctx, const int64_t *ids, int64_t n, int64_t num_rows, int64_t *unique,
+                  int32_t *seg_offsets, int32_t *perm, int32_t *inverse, int64_t *n_unique_dev, hipStream_t s) {
+    if (n == 0) {
+        hipLaunchKernelGGL(unique_empty_kernel, dim3(1), dim3(1), 0, s, seg_offsets, n_unique_dev);
+        FS_LAUNCH_CHECK(ctx, "unique_empty_kernel");
+        return FS_OK;
+    }
+    int key_bits = 63;
+    if (num_rows > 0) {
+        key_bits = 1;
+        while (key_bits < 63 && (1ll << key_bits) < num_rows) ++key_bits;
+    }
+    if (key_bits <= 32)
+        return unique_impl<uint32_t>(ctx, ids, (int)n, key_bits, num_rows, unique, seg_offsets, perm, inverse,
+                                     n_unique_dev, s);
+    return unique_impl<uint64_t>(ctx, ids, (int)n, key_bits, num_rows, unique, seg_offsets, perm, inverse,
+                                 n_unique_dev, s);
+}
+
+}  // namespace fs

@@ -1,0 +1,54 @@
+"""Shared plumbing of the GPU parity tests (host<->device copies, comparisons)."""
+import numpy as np
+import torch
+
+RTOL, ATOL = 1e-5, 1e-6          # fp32 reduced gradients and updated rows (spec tolerance)
+
+
+def dev(a: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def table_to_dev(w: np.ndarray) -> torch.Tensor:
+    """float32 array -> fp32 tensor; uint16 array of bf16 bit patterns -> bf16 tensor."""
+    if w.dtype == np.float32:
+        return dev(w)
+    assert w.dtype == np.uint16
+    return dev(w.view(np.int16)).view(torch.bfloat16)
+
+
+def table_to_host(t: torch.Tensor) -> np.ndarray:
+    if t.dtype == torch.float32:
+        return t.cpu().numpy()
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def exact_f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """For values that are exactly representable in bf16 (the hash initialiser's)."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    assert not np.any(u & np.uint32(0xFFFF)), "value not exact in bf16"
+    return (u >> np.uint32(16)).astype(np.uint16)
+
+
+def assert_close_f32(got: np.ndarray, want: np.ndarray, what: str) -> None:
+    got64, want64 = got.astype(np.float64), want.astype(np.float64)
+    err = np.abs(got64 - want64)
+    tol = ATOL + RTOL * np.abs(want64)
+    bad = err > tol
+    assert not bad.any(), f"{what}: {int(bad.sum())} of {bad.size} elements off, max err {err.max():.3e}"
+
+
+def assert_bf16_within_1ulp(got_bits: np.ndarray, want_bits: np.ndarray, what: str) -> None:
+    g, w = got_bits.astype(np.int32), want_bits.astype(np.int32)
+    same_sign = (g >> 15) == (w >> 15)
+    dist = np.abs((g & 0x7FFF) - (w & 0x7FFF))
+    # +0 / -0 neighbours: both magnitudes zero
+    ok = (same_sign & (dist <= 1)) | (((g & 0x7FFF) == 0) & ((w & 0x7FFF) <= 1)) | (((w & 0x7FFF) == 0) & ((g & 0x7FFF) <= 1))
+    assert ok.all(), f"{what}: {int((~ok).sum())} of {ok.size} bf16 elements beyond 1 ulp"
+
+
+def assert_rows_close(got: np.ndarray, want: np.ndarray, what: str) -> None:
+    if want.dtype == np.uint16:
+        assert_bf16_within_1ulp(got, want, what)
+    else:
+        assert_close_f32(got, want, what)
