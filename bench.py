@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Throughput of the whole prioritized-update step on one MI355X.
+
+A "step" is one pass of the full hot path over one batch: dedup of the lookahead IDs, collision
+split, gradient segment-reduce, priority (collision-row) Adagrad pass, deferred (exclusive-row)
+Adagrad pass on its own stream, and the jagged gather of the lookahead batch.  The workload is
+BASELINE configs[1] (one 4M x 128 fp32 table shard, batch 1024, power-law UIH lengths, Zipf(1.05)
+IDs); its two consecutive iterations are stepped back and forth (t=0 with lookahead 1, then t=1
+with lookahead 0, ...) so that every step consumes the layout the previous step produced, as in
+steady-state training.  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line: rows/s, ms/step, the roofline of the dominant kernel (HIP events around it
+inside the timed steps) and the CPU oracle timed on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+
+
+def algorithmic_bytes(n_t, u_t, n_t1, u_t1, dim, w):
+    """Compulsory bytes of one step (each distinct row counted once per pass; the sort's
+    internal passes and the reduced-gradient round trip are NOT counted)."""
+    unique = 8 * n_t1 + 8 * u_t1 + 4 * n_t1
+    split = 16 * (u_t + u_t1)
+    gather = 8 * n_t1 + u_t1 * dim * w + n_t1 * dim * w
+    reduce_update = n_t * dim * 4 + 4 * n_t + 2 * u_t * dim * w + 8 * u_t + 8 * u_t
+    return {"unique": unique, "split": split, "gather": gather, "reduce_update": reduce_update,
+            "total": unique + split + gather + reduce_update}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=1, help="index into the workload configurations (default 1)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (one embedding-table shard, no collectives); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2604_24073_amd as fs
+    from fs_workloads import CONFIGS, make_iterations, hash_init_rows, compact_rows
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    cfg = CONFIGS[args.config]
+    if len(cfg.tables) != 1:
+        print("bench.py: single-table configurations only", file=sys.stderr)
+        return 2
+    tab = cfg.tables[0]
+    its = [x[0] for x in make_iterations(cfg, iterations=2)]
+    dim, w = tab.dim, (4 if tab.dtype == "f32" else 2)
+    tdtype = torch.float32 if tab.dtype == "f32" else torch.bfloat16
+
+    n = [int(it.values.shape[0]) for it in its]
+    ctx = fs.Context(max_ids=max(n), max_dim=dim)
+    table = torch.empty((tab.num_rows, dim), dtype=tdtype, device=dev)
+    fs.fs_init_table_hash(ctx, table)
+    state = torch.zeros(tab.num_rows, dtype=torch.float32, device=dev)
+    d_vals = [torch.from_numpy(it.values).to(dev) for it in its]
+    d_offs = [torch.from_numpy(it.offsets).to(dev) for it in its]
+    d_grads = [torch.from_numpy(it.grads).to(dev) for it in its]
+
+    layouts = [fs.alloc_layout(n[0], dev), fs.alloc_layout(n[1], dev)]
+    fs.fs_unique_ids(ctx, d_vals[0], tab.num_rows, out=layouts[0])
+    splits = [fs.alloc_split(n[0], n[1], dev), fs.alloc_split(n[1], n[0], dev)]
+    reduced = torch.empty((max(n), dim), dtype=torch.float32, device=dev)
+    embs = [torch.empty((n[1], dim), dtype=tdtype, device=dev), torch.empty((n[0], dim), dtype=tdtype, device=dev)]
+    step_args = [
+        fs.make_step_args(table, state, cfg.lr, cfg.eps, layouts[0], d_grads[0], d_vals[1], d_offs[1], layouts[1],
+                          splits[0], reduced, embs[0]),
+        fs.make_step_args(table, state, cfg.lr, cfg.eps, layouts[1], d_grads[1], d_vals[0], d_offs[0], layouts[0],
+                          splits[1], reduced, embs[1]),
+    ]
+
+    # ---- one untimed step from the fresh table, checked against the oracle on the touched rows
+    cpu_baseline = None
+    fs.fs_prioritized_step(ctx, step_args[0])
+    assert fs.fs_check_async(ctx) == fs.FS_OK, ctx.last_error()
+    u = [int(layouts[0]["n_unique"].item()), int(layouts[1]["n_unique"].item())]
+    counts0 = splits[0]["counts"].cpu().numpy().tolist()
+    if not args.no_cpu_baseline:
+        import oracle as O
+        touched, (v0c, v1c) = compact_rows([its[0].values, its[1].values])
+        w0 = hash_init_rows(touched, dim, tab.dtype)
+        if tab.dtype == "bf16":
+            w0 = (w0.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+        reps, times, want = 0, [], None
+        t_budget = time.perf_counter()
+        while reps < 3 or (time.perf_counter() - t_budget < 10.0 and reps < 30):
+            t_ref, s_ref = w0.copy(), np.zeros(len(touched), np.float32)
+            lay0 = O.unique_ids(v0c, len(touched))          # produced by the previous step: not timed
+            t0 = time.perf_counter()
+            want = O.step(t_ref, s_ref, lay0, its[0].grads, v1c, its[1].offsets, cfg.lr, cfg.eps)
+            times.append(time.perf_counter() - t0)
+            reps += 1
+        sp = want["split"]
+        ok = counts0 == [len(sp["co"]), len(sp["ex"]), len(sp["ex_next"])] and u[0] == len(lay0["unique"]) \
+            and u[1] == len(want["layout_next"]["unique"])
+        got_rows = table[torch.from_numpy(touched).to(dev)].float().cpu().numpy()
+        ref_rows = t_ref if tab.dtype == "f32" else O.bf16_bits_to_f32(t_ref)
+        ok = ok and np.allclose(got_rows, ref_rows, rtol=1e-5 if tab.dtype == "f32" else 8e-3, atol=1e-6)
+        ok = ok and np.allclose(reduced[:u[0]].cpu().numpy(), want["reduced"], rtol=1e-5, atol=1e-6)
+        if not ok:
+            print("bench.py: GPU step does not match the oracle", file=sys.stderr)
+            return 4
+        cpu_s = statistics.median(times)
+        cpu_baseline = {"value": u[0] / cpu_s, "unit": "rows/s", "cores": 1, "kind": "oracle",
+                        "ms_per_step": cpu_s * 1e3,
+                        "sample": f"the full step t=0 of this workload (N={n[0]}, U={u[0]}), median of {reps} runs of "
+                                  "the single-threaded C oracle on a table holding only the touched rows",
+                        "host_cpus": os.cpu_count()}
+
+    # the ping-pong continues with t=1 -> 0, then t=0 -> 1, ...
+    def run(k0, k):
+        for s in range(k0, k0 + k):
+            fs.fs_prioritized_step(ctx, step_args[s % 2])
+
+    run(1, args.warmup)
+    torch.cuda.synchronize()
+    fs.fs_ctx_set_kernel_timing(ctx, args.steps)
+    k0 = 1 + args.warmup
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(k0, args.steps)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    assert fs.fs_check_async(ctx) == fs.FS_OK, ctx.last_error()
+
+    kinds = {"reduce": fs.FS_TIME_REDUCE, "gather": fs.FS_TIME_GATHER, "update_co": fs.FS_TIME_UPDATE_CO,
+             "update_ex": fs.FS_TIME_UPDATE_EX}
+    kernel_ms = {}
+    for name, kind in kinds.items():
+        vals = fs.fs_ctx_get_kernel_timing(ctx, kind, args.steps)
+        kernel_ms[name] = (sum(vals) / len(vals)) if vals else None
+    fs.fs_ctx_set_kernel_timing(ctx, 0)
+
+    # rows updated over the timed steps: step s updates U_{s%2}
+    rows = sum(u[s % 2] for s in range(k0, k0 + args.steps))
+    ms_per_step = elapsed / args.steps * 1e3
+    by = [algorithmic_bytes(n[0], u[0], n[1], u[1], dim, w), algorithmic_bytes(n[1], u[1], n[0], u[0], dim, w)]
+    step_bytes = sum(by[s % 2]["total"] for s in range(k0, k0 + args.steps)) / args.steps
+    step_gbps = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # dominant kernel = the instrumented kernel with the longest average launch
+    gather_bytes = sum(by[s % 2]["gather"] for s in range(k0, k0 + args.steps)) / args.steps
+    reduce_bytes = sum(n[s % 2] * dim * 4 + 4 * n[s % 2] + 4 * u[s % 2] for s in range(k0, k0 + args.steps)) / args.steps
+    cand = []
+    if kernel_ms.get("gather"):
+        cand.append(("gather_kernel", kernel_ms["gather"], gather_bytes))
+    if kernel_ms.get("reduce"):
+        cand.append(("reduce_chunk_kernel", kernel_ms["reduce"], reduce_bytes))
+    roofline = None
+    if cand:
+        name, ms, nbytes = max(cand, key=lambda c: c[1])
+        achieved = nbytes / (ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": name, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                    "frac": achieved / HBM_PEAK_GBPS, "traffic": None, "avg_launch_us": ms * 1e3,
+                    "algorithmic_bytes_per_launch": nbytes}
+
+    out = {
+        "metric": "unique embedding rows updated/sec + achieved HBM GB/s (% of peak), 1 GPU",
+        "value": rows / elapsed, "unit": "rows/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": tab.dtype, "data": "synthetic",
+        "config": {"workload": f"configs[{cfg.index}] {cfg.name}: 1 table shard {tab.num_rows} rows x dim {dim} "
+                               f"{tab.dtype} + fp32 row-wise Adagrad state, batch {cfg.batch}, "
+                               f"{cfg.length_rule} UIH lengths [{cfg.length_lo},{cfg.length_hi}], Zipf({tab.zipf_alpha}) IDs, "
+                               "2 consecutive iterations stepped back and forth",
+                   "ids_per_iteration": n, "unique_rows": u, "collision_rows_first_step": counts0[0]},
+        "step_algorithmic_bytes": step_bytes, "step_algorithmic_GBps": step_gbps,
+        "step_frac_of_hbm_peak": step_gbps / HBM_PEAK_GBPS,
+        "kernel_avg_us": {k: (v * 1e3 if v is not None else None) for k, v in kernel_ms.items()},
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+    }
+    print(json.dumps(out))
+    ctx.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -168,6 +168,21 @@ typedef struct fs_step_args {
  * identical to running the five calls one after another. */
 int fs_prioritized_step(fs_ctx *ctx, const fs_step_args *args, fs_stream stream);
 
+/* ---- per-kernel timing of fs_prioritized_step (measurement aid) ---------------------------- */
+
+enum { FS_TIME_REDUCE = 0, FS_TIME_GATHER = 1, FS_TIME_UPDATE_CO = 2, FS_TIME_UPDATE_EX = 3, FS_TIME_KINDS = 4 };
+
+/* slots > 0: every later fs_prioritized_step brackets its segment-reduce main kernel, its gather
+ * and its two update passes with HIP events on the stream each is launched on (ring of `slots`
+ * steps).  slots == 0 turns it off (the default) and frees the events. */
+int fs_ctx_set_kernel_timing(fs_ctx *ctx, int slots);
+
+/* Waits for all streams, then writes the duration in milliseconds of kernel `which` for each of
+ * the steps recorded since timing was enabled (oldest first, at most max_out and at most the
+ * ring size) to the HOST array ms_out_host and their number to *n_out_host.  Enabling timing
+ * again clears the ring. */
+int fs_ctx_get_kernel_timing(fs_ctx *ctx, int which, float *ms_out_host, int max_out, int *n_out_host);
+
 /* ---- input generation and calibration helpers (not part of the method) ------------------- */
 
 /* Fills a table with the counter-based integer-hash rule of the synthetic workloads:

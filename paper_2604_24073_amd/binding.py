@@ -72,6 +72,9 @@ def load_library() -> ctypes.CDLL:
         "fs_rowwise_adagrad_update": (ctypes.c_int, [c_vp, c_vp, ctypes.c_int, c_vp, c_i64, c_i32, c_vp, c_vp, c_vp,
                                                      c_i64, c_vp, c_f, c_f, S]),
         "fs_prioritized_step": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args), S]),
+        "fs_ctx_set_kernel_timing": (ctypes.c_int, [c_vp, ctypes.c_int]),
+        "fs_ctx_get_kernel_timing": (ctypes.c_int, [c_vp, ctypes.c_int, ctypes.POINTER(c_f), ctypes.c_int,
+                                                    ctypes.POINTER(ctypes.c_int)]),
         "fs_init_table_hash": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i32, ctypes.c_int, S]),
         "fs_stream_copy": (ctypes.c_int, [c_vp, c_vp, c_vp, c_i64, S]),
     }
@@ -152,6 +155,21 @@ class Context:
 
 def fs_check_async(ctx: Context, stream=None) -> int:
     return ctx.lib.fs_check_async(ctx.handle, _stream(stream))
+
+
+FS_TIME_REDUCE, FS_TIME_GATHER, FS_TIME_UPDATE_CO, FS_TIME_UPDATE_EX = 0, 1, 2, 3
+
+
+def fs_ctx_set_kernel_timing(ctx: Context, slots: int) -> None:
+    ctx.check(ctx.lib.fs_ctx_set_kernel_timing(ctx.handle, slots), "fs_ctx_set_kernel_timing")
+
+
+def fs_ctx_get_kernel_timing(ctx: Context, which: int, max_out: int = 65536):
+    buf = (c_f * max_out)()
+    n = ctypes.c_int(0)
+    ctx.check(ctx.lib.fs_ctx_get_kernel_timing(ctx.handle, which, buf, max_out, ctypes.byref(n)),
+              "fs_ctx_get_kernel_timing")
+    return [buf[i] for i in range(n.value)]
 
 
 def fs_gather_jagged(ctx: Context, table: torch.Tensor, values: torch.Tensor, offsets: Optional[torch.Tensor],

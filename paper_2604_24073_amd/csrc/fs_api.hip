@@ -108,6 +108,7 @@ int fs_ctx_destroy(fs_ctx *c) {
     hipEvent_t evs[] = {c->ev_fork, c->ev_split, c->ev_reduce, c->ev_co, c->ev_ex};
     for (hipEvent_t e : evs)
         if (e) (void)hipEventDestroy(e);
+    (void)fs_ctx_set_kernel_timing(c, 0);
     if (c->slab) (void)hipFree(c->slab);
     delete c;
     return FS_OK;
@@ -130,6 +131,48 @@ int fs_check_async(fs_ctx *ctx, fs_stream stream) {
              (flags[0] & kFlagRowRange) ? " row id out of range" : "",
              (flags[0] & kFlagOffsets) ? " malformed offsets" : "", (flags[0] & kFlagInternal) ? " internal" : "");
     return FS_ERANGE;
+}
+
+int fs_ctx_set_kernel_timing(fs_ctx *ctx, int slots) {
+    if (!ctx || slots < 0 || slots > 65536) return FS_EINVAL;
+    if (ctx->timing_events) {
+        const size_t cnt = (size_t)FS_TIME_KINDS * ctx->timing_slots * 2;
+        for (size_t i = 0; i < cnt; ++i)
+            if (ctx->timing_events[i]) (void)hipEventDestroy(ctx->timing_events[i]);
+        delete[] ctx->timing_events;
+        ctx->timing_events = nullptr;
+    }
+    ctx->timing_slots = 0;
+    ctx->timing_steps = 0;
+    if (slots == 0) return FS_OK;
+    const size_t cnt = (size_t)FS_TIME_KINDS * slots * 2;
+    ctx->timing_events = new (std::nothrow) hipEvent_t[cnt]();
+    if (!ctx->timing_events) return FS_ENOMEM;
+    ctx->timing_slots = slots;
+    for (size_t i = 0; i < cnt; ++i) FS_HIP(ctx, hipEventCreate(&ctx->timing_events[i]));
+    return FS_OK;
+}
+
+int fs_ctx_get_kernel_timing(fs_ctx *ctx, int which, float *ms_out_host, int max_out, int *n_out_host) {
+    if (!ctx || which < 0 || which >= FS_TIME_KINDS || !ms_out_host || !n_out_host || max_out < 0) return FS_EINVAL;
+    *n_out_host = 0;
+    if (ctx->timing_slots <= 0) return FS_OK;
+    FS_HIP(ctx, hipDeviceSynchronize());
+    const int64_t have = ctx->timing_steps < ctx->timing_slots ? ctx->timing_steps : ctx->timing_slots;
+    const int64_t first = ctx->timing_steps - have;
+    int n = 0;
+    for (int64_t i = 0; i < have && n < max_out; ++i) {
+        const int slot = (int)((first + i) % ctx->timing_slots);
+        hipEvent_t *pair = ctx->timing_events + ((size_t)which * ctx->timing_slots + slot) * 2;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, pair[0], pair[1]) != hipSuccess) {
+            (void)hipGetLastError();
+            continue;                     // this kernel was not launched in that step
+        }
+        ms_out_host[n++] = ms;
+    }
+    *n_out_host = n;
+    return FS_OK;
 }
 
 int fs_gather_jagged(fs_ctx *ctx, const void *table, int64_t num_rows, int32_t dim, fs_dtype dt,
@@ -257,7 +300,7 @@ int fs_prioritized_step(fs_ctx *ctx, const fs_step_args *a, fs_stream stream) {
     // main stream: reduce the gradients of t while A works on the indices of t+1
     if (have_t) {
         rc = launch_reduce(ctx, a->grads_t, a->n_t, a->dim, a->perm_t, a->seg_offsets_t, a->n_unique_t_dev, a->reduced,
-                           sp);
+                           sp, timing_pair(ctx, FS_TIME_REDUCE));
         if (rc != FS_OK) return rc;
     }
     FS_HIP(ctx, hipEventRecord(ctx->ev_reduce, sp));
@@ -268,22 +311,31 @@ int fs_prioritized_step(fs_ctx *ctx, const fs_step_args *a, fs_stream stream) {
     FS_HIP(ctx, hipStreamWaitEvent(sb, ctx->ev_reduce, 0));
     if (have_t) {
         // priority pass: collision rows, strictly before the lookahead rows are read
+        hipEvent_t *tco = timing_pair(ctx, FS_TIME_UPDATE_CO), *tex = timing_pair(ctx, FS_TIME_UPDATE_EX);
+        if (tco) (void)hipEventRecord(tco[0], sp);
         rc = launch_adagrad(ctx, a->table, fdt, a->state, a->num_rows, a->dim, a->co, a->co_slot, a->counts_dev + 0,
                             a->n_t, a->reduced, a->lr, a->eps, sp);
         if (rc != FS_OK) return rc;
+        if (tco) (void)hipEventRecord(tco[1], sp);
+        if (tex) (void)hipEventRecord(tex[0], sb);
         rc = launch_adagrad(ctx, a->table, fdt, a->state, a->num_rows, a->dim, a->ex, a->ex_slot, a->counts_dev + 1,
                             a->n_t, a->reduced, a->lr, a->eps, sb);
         if (rc != FS_OK) return rc;
+        if (tex) (void)hipEventRecord(tex[1], sb);
     }
     FS_HIP(ctx, hipEventRecord(ctx->ev_ex, sb));
     if (have_t1) {
         // exclusive rows and lookahead rows are disjoint, so this may overlap the deferred pass
         const int row_bytes = a->dim * (dt == FS_F32 ? 4 : 2);
+        hipEvent_t *tg = timing_pair(ctx, FS_TIME_GATHER);
+        if (tg) (void)hipEventRecord(tg[0], sp);
         rc = launch_gather(ctx, a->table, a->num_rows, row_bytes, a->values_t1, a->offsets_t1, a->batch_t1, a->n_t1,
                            a->emb_t1, sp);
         if (rc != FS_OK) return rc;
+        if (tg) (void)hipEventRecord(tg[1], sp);
     }
     FS_HIP(ctx, hipStreamWaitEvent(sp, ctx->ev_ex, 0));
+    if (ctx->timing_slots > 0) ++ctx->timing_steps;
     return FS_OK;
 }
 

@@ -70,6 +70,11 @@ struct fs_ctx {
     hipStream_t stream_a;     // index work of the lookahead batch
     hipStream_t stream_b;     // deferred update pass
     hipEvent_t ev_fork, ev_split, ev_reduce, ev_co, ev_ex;
+
+    // optional per-kernel timing of the step: events[(kind * slots + slot) * 2 + {0,1}]
+    int timing_slots;
+    int64_t timing_steps;
+    hipEvent_t *timing_events;
 };
 
 namespace fs {
@@ -113,14 +118,22 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // launchers implemented in the kernel translation units (host side, argument-checked callers)
 int launch_gather(fs_ctx *, const void *table, int64_t num_rows, int row_bytes, const int64_t *values,
                   const int64_t *offsets, int64_t batch, int64_t n, void *out, hipStream_t s);
+// event pair of timing kind `kind` for the step being enqueued, or nullptr when timing is off
+inline hipEvent_t *timing_pair(fs_ctx *ctx, int kind) {
+    if (ctx->timing_slots <= 0) return nullptr;
+    const int slot = (int)(ctx->timing_steps % ctx->timing_slots);
+    return ctx->timing_events + ((size_t)kind * ctx->timing_slots + slot) * 2;
+}
 int launch_unique(fs_ctx *, const int64_t *ids, int64_t n, int64_t num_rows, int64_t *unique,
                   int32_t *seg_offsets, int32_t *perm, int32_t *inverse, int64_t *n_unique_dev, hipStream_t s);
 int launch_split(fs_ctx *, const int64_t *u_t, const int64_t *n_t_dev, const int64_t *u_t1,
                  const int64_t *n_t1_dev, int64_t cap_t, int64_t cap_t1, int64_t *co, int32_t *co_slot,
                  int64_t *ex, int32_t *ex_slot, int64_t *ex_next, int32_t *ex_next_slot, int64_t *counts_dev,
                  hipStream_t s);
+// `timing`: optional event pair recorded around the main (chunk) kernel only
 int launch_reduce(fs_ctx *, const float *grads, int64_t n, int32_t dim, const int32_t *perm,
-                  const int32_t *seg_offsets, const int64_t *n_unique_dev, float *reduced, hipStream_t s);
+                  const int32_t *seg_offsets, const int64_t *n_unique_dev, float *reduced, hipStream_t s,
+                  hipEvent_t *timing = nullptr);
 int launch_adagrad(fs_ctx *, void *table, int dt, float *state, int64_t num_rows, int32_t dim,
                    const int64_t *rows, const int32_t *slots, const int64_t *n_rows_dev, int64_t cap,
                    const float *reduced, float lr, float eps, hipStream_t s);

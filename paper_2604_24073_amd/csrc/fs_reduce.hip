@@ -220,14 +220,17 @@ __global__ __launch_bounds__(256) void reduce_fix_kernel(int n_chunks, int gvec,
 
 template <int LPR>
 static void reduce_launch(fs_ctx *ctx, const float *grads, int n, int gvec, const int32_t *perm,
-                          const int32_t *seg_offsets, const int64_t *n_unique_dev, float *reduced, hipStream_t s) {
+                          const int32_t *seg_offsets, const int64_t *n_unique_dev, float *reduced, hipStream_t s,
+                          hipEvent_t *timing) {
     constexpr int GPW = kWave / LPR;
     constexpr int UNR = (kReduceChunk / GPW) < 8 ? (kReduceChunk / GPW) : 8;
     const int n_chunks = (int)ceil_div(n, kReduceChunk);
     const int blocks = (int)ceil_div(n_chunks, kReduceWavesPerBlock);
+    if (timing) (void)hipEventRecord(timing[0], s);
     hipLaunchKernelGGL((reduce_chunk_kernel<LPR, UNR>), dim3(blocks), dim3(kReduceWavesPerBlock * kWave), 0, s,
                        (const f32x4 *)grads, n, gvec, perm, seg_offsets, n_unique_dev, (f32x4 *)reduced,
                        ctx->part_head, ctx->part_last, ctx->chunk_desc);
+    if (timing) (void)hipEventRecord(timing[1], s);
     const int chunks_per_block = 4 * GPW;
     hipLaunchKernelGGL((reduce_fix_kernel<LPR>), dim3((unsigned)ceil_div(n_chunks, chunks_per_block)), dim3(256), 0, s,
                        n_chunks, gvec, seg_offsets, (const double *)ctx->part_head, (const double *)ctx->part_last,
@@ -235,17 +238,18 @@ static void reduce_launch(fs_ctx *ctx, const float *grads, int n, int gvec, cons
 }
 
 int launch_reduce(fs_ctx *ctx, const float *grads, int64_t n, int32_t dim, const int32_t *perm,
-                  const int32_t *seg_offsets, const int64_t *n_unique_dev, float *reduced, hipStream_t s) {
+                  const int32_t *seg_offsets, const int64_t *n_unique_dev, float *reduced, hipStream_t s,
+                  hipEvent_t *timing) {
     if (n == 0) return FS_OK;
     const int gvec = dim / 4;
     switch (lanes_per_row(gvec)) {
-        case 1: reduce_launch<1>(ctx, grads, (int)n, gvec, perm, seg_offsets, n_unique_dev, reduced, s); break;
-        case 2: reduce_launch<2>(ctx, grads, (int)n, gvec, perm, seg_offsets, n_unique_dev, reduced, s); break;
-        case 4: reduce_launch<4>(ctx, grads, (int)n, gvec, perm, seg_offsets, n_unique_dev, reduced, s); break;
-        case 8: reduce_launch<8>(ctx, grads, (int)n, gvec, perm, seg_offsets, n_unique_dev, reduced, s); break;
-        case 16: reduce_launch<16>(ctx, grads, (int)n, gvec, perm, seg_offsets, n_unique_dev, reduced, s); break;
-        case 32: reduce_launch<32>(ctx, grads, (int)n, gvec, perm, seg_offsets, n_unique_dev, reduced, s); break;
-        case 64: reduce_launch<64>(ctx, grads, (int)n, gvec, perm, seg_offsets, n_unique_dev, reduced, s); break;
+        case 1: reduce_launch<1>(ctx, grads, (int)n, gvec, perm, seg_offsets, n_unique_dev, reduced, s, timing); break;
+        case 2: reduce_launch<2>(ctx, grads, (int)n, gvec, perm, seg_offsets, n_unique_dev, reduced, s, timing); break;
+        case 4: reduce_launch<4>(ctx, grads, (int)n, gvec, perm, seg_offsets, n_unique_dev, reduced, s, timing); break;
+        case 8: reduce_launch<8>(ctx, grads, (int)n, gvec, perm, seg_offsets, n_unique_dev, reduced, s, timing); break;
+        case 16: reduce_launch<16>(ctx, grads, (int)n, gvec, perm, seg_offsets, n_unique_dev, reduced, s, timing); break;
+        case 32: reduce_launch<32>(ctx, grads, (int)n, gvec, perm, seg_offsets, n_unique_dev, reduced, s, timing); break;
+        case 64: reduce_launch<64>(ctx, grads, (int)n, gvec, perm, seg_offsets, n_unique_dev, reduced, s, timing); break;
         default: return set_err(ctx, FS_EINVAL, "reduce: dim beyond 256");
     }
     FS_LAUNCH_CHECK(ctx, "reduce kernels");
