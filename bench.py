@@ -46,6 +46,12 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=1, help="index into the workload configurations (default 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--time-every", type=int, default=8,
+                    help="bracket the kernels of one timed step in this many with HIP event pairs")
+    ap.add_argument("--mode", choices=["graph", "pipelined", "sequential"], default="graph",
+                    help="graph: the pipelined step replayed as a HIP graph (default); pipelined: index half of "
+                         "step s+1 beside the gradient half of step s, eager launches; sequential: every step "
+                         "self-contained, eager launches")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one embedding-table shard, no collectives); "
@@ -80,21 +86,40 @@ def main() -> int:
     d_offs = [torch.from_numpy(it.offsets).to(dev) for it in its]
     d_grads = [torch.from_numpy(it.grads).to(dev) for it in its]
 
-    layouts = [fs.alloc_layout(n[0], dev), fs.alloc_layout(n[1], dev)]
+    # Buffers: layouts rotate over three buffers and splits over two, because the index half of
+    # step s+1 (writes layout s+2, split s+1) runs beside the gradient half of step s (reads
+    # layout s, split s).  The two batches alternate, so the argument records repeat with period 6.
+    nmax = max(n)
+    layouts = [fs.alloc_layout(nmax, dev) for _ in range(3)]
+    splits = [fs.alloc_split(nmax, nmax, dev) for _ in range(2)]
+    reduced = torch.empty((nmax, dim), dtype=torch.float32, device=dev)
+    embs = [torch.empty((n[0], dim), dtype=tdtype, device=dev), torch.empty((n[1], dim), dtype=tdtype, device=dev)]
+
+    def args_for(s):
+        lay = dict(layouts[s % 3]); lay["n"] = n[s % 2]
+        nb = (s + 1) % 2
+        return fs.make_step_args(table, state, cfg.lr, cfg.eps, lay, d_grads[s % 2], d_vals[nb], d_offs[nb],
+                                 layouts[(s + 1) % 3], splits[s % 2], reduced, embs[nb])
+
+    step_args = [args_for(s) for s in range(6)]
     fs.fs_unique_ids(ctx, d_vals[0], tab.num_rows, out=layouts[0])
-    splits = [fs.alloc_split(n[0], n[1], dev), fs.alloc_split(n[1], n[0], dev)]
-    reduced = torch.empty((max(n), dim), dtype=torch.float32, device=dev)
-    embs = [torch.empty((n[1], dim), dtype=tdtype, device=dev), torch.empty((n[0], dim), dtype=tdtype, device=dev)]
-    step_args = [
-        fs.make_step_args(table, state, cfg.lr, cfg.eps, layouts[0], d_grads[0], d_vals[1], d_offs[1], layouts[1],
-                          splits[0], reduced, embs[0]),
-        fs.make_step_args(table, state, cfg.lr, cfg.eps, layouts[1], d_grads[1], d_vals[0], d_offs[0], layouts[0],
-                          splits[1], reduced, embs[1]),
-    ]
+    pipelined = args.mode in ("pipelined", "graph")
+    graphs = None
+
+    def run(k0, k):
+        for s in range(k0, k0 + k):
+            if graphs is not None:
+                fs.fs_graph_launch(ctx, graphs[s % 6])
+            elif pipelined:
+                fs.fs_prioritized_step_pipelined(ctx, step_args[s % 6], step_args[(s + 1) % 6])
+            else:
+                fs.fs_prioritized_step(ctx, step_args[s % 6])
 
     # ---- one untimed step from the fresh table, checked against the oracle on the touched rows
     cpu_baseline = None
-    fs.fs_prioritized_step(ctx, step_args[0])
+    if pipelined:
+        fs.fs_step_forward(ctx, step_args[0])          # primes the pipeline: layout 1, split 0
+    run(0, 1)
     assert fs.fs_check_async(ctx) == fs.FS_OK, ctx.last_error()
     u = [int(layouts[0]["n_unique"].item()), int(layouts[1]["n_unique"].item())]
     counts0 = splits[0]["counts"].cpu().numpy().tolist()
@@ -131,20 +156,30 @@ def main() -> int:
                         "host_cpus": os.cpu_count()}
 
     # the ping-pong continues with t=1 -> 0, then t=0 -> 1, ...
-    def run(k0, k):
-        for s in range(k0, k0 + k):
-            fs.fs_prioritized_step(ctx, step_args[s % 2])
-
+    if args.mode == "graph":
+        graphs = [fs.fs_graph_capture_pipelined(ctx, step_args[s], step_args[(s + 1) % 6]) for s in range(6)]
     run(1, args.warmup)
     torch.cuda.synchronize()
-    fs.fs_ctx_set_kernel_timing(ctx, args.steps)
     k0 = 1 + args.warmup
+    if graphs is None:
+        fs.fs_ctx_set_kernel_timing(ctx, args.steps, args.time_every)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     run(k0, args.steps)
+    t_enq = time.perf_counter() - t0
+    fs.fs_step_join(ctx)                      # the index half of the last step is part of the timed work
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     assert fs.fs_check_async(ctx) == fs.FS_OK, ctx.last_error()
+    if graphs is not None:
+        # Per-kernel durations cannot be bracketed inside a replayed graph: the same kernels are
+        # timed with event pairs over as many eager pipelined steps right after the timed region.
+        k1 = k0 + args.steps
+        saved, graphs = graphs, None
+        fs.fs_ctx_set_kernel_timing(ctx, args.steps)
+        run(k1, args.steps)
+        torch.cuda.synchronize()
+        graphs = saved
 
     kinds = {"reduce": fs.FS_TIME_REDUCE, "gather": fs.FS_TIME_GATHER, "update_co": fs.FS_TIME_UPDATE_CO,
              "update_ex": fs.FS_TIME_UPDATE_EX}
@@ -153,6 +188,9 @@ def main() -> int:
         vals = fs.fs_ctx_get_kernel_timing(ctx, kind, args.steps)
         kernel_ms[name] = (sum(vals) / len(vals)) if vals else None
     fs.fs_ctx_set_kernel_timing(ctx, 0)
+    if graphs is not None:
+        for g in graphs:
+            fs.fs_graph_destroy(ctx, g)
 
     # rows updated over the timed steps: step s updates U_{s%2}
     rows = sum(u[s % 2] for s in range(k0, k0 + args.steps))
@@ -187,6 +225,7 @@ def main() -> int:
                                f"{cfg.length_rule} UIH lengths [{cfg.length_lo},{cfg.length_hi}], Zipf({tab.zipf_alpha}) IDs, "
                                "2 consecutive iterations stepped back and forth",
                    "ids_per_iteration": n, "unique_rows": u, "collision_rows_first_step": counts0[0]},
+        "schedule": args.mode, "host_enqueue_us_per_step": t_enq / args.steps * 1e6,
         "step_algorithmic_bytes": step_bytes, "step_algorithmic_GBps": step_gbps,
         "step_frac_of_hbm_peak": step_gbps / HBM_PEAK_GBPS,
         "kernel_avg_us": {k: (v * 1e3 if v is not None else None) for k, v in kernel_ms.items()},

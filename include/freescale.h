@@ -117,10 +117,13 @@ int fs_collision_split(fs_ctx *ctx, const int64_t *u_t, const int64_t *n_t_dev,
  *   reduced[k, :] = sum over sorted positions p in [seg_offsets[k], seg_offsets[k+1]) of
  *                   grads[perm[p], :]
  * accumulated in fp64 in a fixed order (results do not vary run to run) and rounded once to
- * fp32.  grads [n, dim] fp32; reduced needs *n_unique_dev rows (at most n). */
+ * fp32.  grads [n, dim] fp32; reduced needs *n_unique_dev rows (at most n).
+ * inverse [n] is OPTIONAL (NULL allowed): the inverse map that fs_unique_ids wrote next to perm
+ * and seg_offsets.  With it every wavefront reads the segment of its positions directly instead
+ * of searching seg_offsets; the results are bit-identical either way. */
 int fs_segment_reduce_grads(fs_ctx *ctx, const float *grads, int64_t n, int32_t dim,
-                            const int32_t *perm, const int32_t *seg_offsets, const int64_t *n_unique_dev,
-                            float *reduced, fs_stream stream);
+                            const int32_t *perm, const int32_t *seg_offsets, const int32_t *inverse,
+                            const int64_t *n_unique_dev, float *reduced, fs_stream stream);
 
 /* Second half of update_embedding(I, G): fused row-wise Adagrad on the listed rows, in place.
  * For i < *n_rows_dev, r = rows[i], k = slots[i]:
@@ -144,7 +147,8 @@ typedef struct fs_step_args {
     void *table; float *state; int64_t num_rows; int32_t dim; int32_t dtype; /* fs_dtype */
     float lr, eps;
     /* iteration t: layout produced by the previous step (or by fs_unique_ids), gradients */
-    const int64_t *u_t; const int32_t *seg_offsets_t; const int32_t *perm_t; const int64_t *n_unique_t_dev;
+    const int64_t *u_t; const int32_t *seg_offsets_t; const int32_t *perm_t; const int32_t *inverse_t /* may be NULL */;
+    const int64_t *n_unique_t_dev;
     const float *grads_t; int64_t n_t;
     /* lookahead batch t+1 (values_t1 == NULL: last iteration, every row is exclusive) */
     const int64_t *values_t1; const int64_t *offsets_t1; int64_t batch_t1; int64_t n_t1;
@@ -168,14 +172,60 @@ typedef struct fs_step_args {
  * identical to running the five calls one after another. */
 int fs_prioritized_step(fs_ctx *ctx, const fs_step_args *args, fs_stream stream);
 
+/* The index half of an iteration alone - what Forward of Algorithm 2 does with the prefetched
+ * indices of the next batch, long before the gradients arrive: on side stream A (forked from
+ * `stream`, joined back into it) dedup values_t1 into the layout of t+1 and split U_t against
+ * U_t1.  Uses only the index fields of `args` (no gradients, no table access). */
+int fs_step_forward(fs_ctx *ctx, const fs_step_args *args, fs_stream stream);
+
+/* Steady-state form of the iteration, software-pipelined by one batch exactly as Algorithm 2
+ * interleaves its Forward and Backward: the gradient half of iteration `cur` (reduce, priority
+ * pass, deferred pass on B, gather of cur's lookahead rows) runs on `stream`, while side stream
+ * A does the index half of iteration `next` (dedup of next's lookahead IDs, split of next's
+ * U_t), which needs nothing that `cur` writes.  The split of `cur` must already exist: it was
+ * produced by the previous call of this function (as its `next`) or by fs_step_forward.
+ * `next` may be NULL (last iteration).  Stream B is joined into `stream` before the call's work
+ * on `stream` ends.  The index half of `next` is NOT: it keeps running on A and is waited for
+ * exactly where its results are first needed - by the next pipelined call after its reduce, by
+ * fs_step_join, by fs_check_async, or by any other call that reuses the index workspace.  Use
+ * consecutive pipelined calls on ONE stream.  The caller keeps the buffers of `cur` and `next`
+ * distinct (three layout buffers in rotation, two split buffers). */
+int fs_prioritized_step_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs_step_args *next,
+                                  fs_stream stream);
+
+/* Makes `stream` wait for the index half that the last pipelined call left running (no-op if
+ * there is none): after it, work enqueued on `stream` sees that layout and split. */
+int fs_step_join(fs_ctx *ctx, fs_stream stream);
+
+/* fs_prioritized_step_pipelined hands the enqueueing of the index half to a second host thread
+ * owned by the context (on by default; started on first use, joined by fs_ctx_destroy), because
+ * the host cost of the launches would otherwise exceed the GPU time of an iteration.  on == 0
+ * makes the calling thread enqueue everything.  The results do not depend on this setting. */
+int fs_ctx_set_threaded_enqueue(fs_ctx *ctx, int on);
+
+/* ---- the pipelined iteration as a HIP graph ---------------------------------------------------- */
+
+/* One iteration enqueues about sixteen small and large kernels on three streams; replaying it as a
+ * graph removes the host launch cost.  fs_graph_capture_pipelined records exactly the work of
+ * fs_prioritized_step_pipelined(cur, next) (same kernels, same dependencies, pointers baked in:
+ * the buffers must stay alive and in place) on an internal stream; nothing runs during capture.
+ * fs_graph_launch replays it on `stream`.  A graph holds no memset node.  Replays of graphs that
+ * share a context must be ordered on one stream. */
+typedef struct fs_graph fs_graph;
+int fs_graph_capture_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs_step_args *next, fs_graph **out);
+int fs_graph_launch(fs_ctx *ctx, fs_graph *graph, fs_stream stream);
+int fs_graph_destroy(fs_graph *graph);
+
 /* ---- per-kernel timing of fs_prioritized_step (measurement aid) ---------------------------- */
 
 enum { FS_TIME_REDUCE = 0, FS_TIME_GATHER = 1, FS_TIME_UPDATE_CO = 2, FS_TIME_UPDATE_EX = 3, FS_TIME_KINDS = 4 };
 
-/* slots > 0: every later fs_prioritized_step brackets its segment-reduce main kernel, its gather
- * and its two update passes with HIP events on the stream each is launched on (ring of `slots`
- * steps).  slots == 0 turns it off (the default) and frees the events. */
-int fs_ctx_set_kernel_timing(fs_ctx *ctx, int slots);
+/* slots > 0: one in `every` later steps (fs_prioritized_step, fs_prioritized_step_pipelined)
+ * brackets its segment-reduce main kernel, its gather and its two update passes with HIP events
+ * on the stream each is launched on (ring of `slots` sampled steps).  An event record costs the
+ * host more than a kernel launch: sample sparsely when the steps themselves are being timed.
+ * slots == 0 turns it off (the default) and frees the events. */
+int fs_ctx_set_kernel_timing(fs_ctx *ctx, int slots, int every);
 
 /* Waits for all streams, then writes the duration in milliseconds of kernel `which` for each of
  * the steps recorded since timing was enabled (oldest first, at most max_out and at most the

@@ -28,7 +28,7 @@ class fs_step_args(ctypes.Structure):
     _fields_ = [
         ("table", c_vp), ("state", c_vp), ("num_rows", c_i64), ("dim", c_i32), ("dtype", c_i32),
         ("lr", c_f), ("eps", c_f),
-        ("u_t", c_vp), ("seg_offsets_t", c_vp), ("perm_t", c_vp), ("n_unique_t_dev", c_vp),
+        ("u_t", c_vp), ("seg_offsets_t", c_vp), ("perm_t", c_vp), ("inverse_t", c_vp), ("n_unique_t_dev", c_vp),
         ("grads_t", c_vp), ("n_t", c_i64),
         ("values_t1", c_vp), ("offsets_t1", c_vp), ("batch_t1", c_i64), ("n_t1", c_i64),
         ("u_t1", c_vp), ("seg_offsets_t1", c_vp), ("perm_t1", c_vp), ("inverse_t1", c_vp), ("n_unique_t1_dev", c_vp),
@@ -68,11 +68,20 @@ def load_library() -> ctypes.CDLL:
         "fs_unique_ids": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i64, c_vp, c_vp, c_vp, c_vp, c_vp, S]),
         "fs_collision_split": (ctypes.c_int, [c_vp, c_vp, c_vp, c_vp, c_vp, c_i64, c_i64, c_vp, c_vp, c_vp, c_vp,
                                               c_vp, c_vp, c_vp, S]),
-        "fs_segment_reduce_grads": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i32, c_vp, c_vp, c_vp, c_vp, S]),
+        "fs_segment_reduce_grads": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i32, c_vp, c_vp, c_vp, c_vp, c_vp, S]),
         "fs_rowwise_adagrad_update": (ctypes.c_int, [c_vp, c_vp, ctypes.c_int, c_vp, c_i64, c_i32, c_vp, c_vp, c_vp,
                                                      c_i64, c_vp, c_f, c_f, S]),
         "fs_prioritized_step": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args), S]),
-        "fs_ctx_set_kernel_timing": (ctypes.c_int, [c_vp, ctypes.c_int]),
+        "fs_step_forward": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args), S]),
+        "fs_prioritized_step_pipelined": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args),
+                                                         ctypes.POINTER(fs_step_args), S]),
+        "fs_graph_capture_pipelined": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args), ctypes.POINTER(fs_step_args),
+                                                      ctypes.POINTER(c_vp)]),
+        "fs_ctx_set_threaded_enqueue": (ctypes.c_int, [c_vp, ctypes.c_int]),
+        "fs_step_join": (ctypes.c_int, [c_vp, S]),
+        "fs_graph_launch": (ctypes.c_int, [c_vp, c_vp, S]),
+        "fs_graph_destroy": (ctypes.c_int, [c_vp]),
+        "fs_ctx_set_kernel_timing": (ctypes.c_int, [c_vp, ctypes.c_int, ctypes.c_int]),
         "fs_ctx_get_kernel_timing": (ctypes.c_int, [c_vp, ctypes.c_int, ctypes.POINTER(c_f), ctypes.c_int,
                                                     ctypes.POINTER(ctypes.c_int)]),
         "fs_init_table_hash": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i32, ctypes.c_int, S]),
@@ -160,8 +169,8 @@ def fs_check_async(ctx: Context, stream=None) -> int:
 FS_TIME_REDUCE, FS_TIME_GATHER, FS_TIME_UPDATE_CO, FS_TIME_UPDATE_EX = 0, 1, 2, 3
 
 
-def fs_ctx_set_kernel_timing(ctx: Context, slots: int) -> None:
-    ctx.check(ctx.lib.fs_ctx_set_kernel_timing(ctx.handle, slots), "fs_ctx_set_kernel_timing")
+def fs_ctx_set_kernel_timing(ctx: Context, slots: int, every: int = 1) -> None:
+    ctx.check(ctx.lib.fs_ctx_set_kernel_timing(ctx.handle, slots, every), "fs_ctx_set_kernel_timing")
 
 
 def fs_ctx_get_kernel_timing(ctx: Context, which: int, max_out: int = 65536):
@@ -222,12 +231,13 @@ def fs_collision_split(ctx: Context, u_t: Optional[torch.Tensor], n_t_dev: Optio
 
 
 def fs_segment_reduce_grads(ctx: Context, grads: torch.Tensor, perm: torch.Tensor, seg_offsets: torch.Tensor,
-                            n_unique_dev: torch.Tensor, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+                            n_unique_dev: torch.Tensor, out: Optional[torch.Tensor] = None, stream=None,
+                            inverse: Optional[torch.Tensor] = None) -> torch.Tensor:
     n, dim = grads.shape
     if out is None:
         out = torch.empty((max(n, 1), dim), dtype=torch.float32, device=grads.device)
     rc = ctx.lib.fs_segment_reduce_grads(ctx.handle, _ptr(grads), n, dim, _ptr(perm), _ptr(seg_offsets),
-                                         _ptr(n_unique_dev), _ptr(out), _stream(stream))
+                                         _ptr(inverse), _ptr(n_unique_dev), _ptr(out), _stream(stream))
     ctx.check(rc, "fs_segment_reduce_grads")
     return out
 
@@ -244,6 +254,37 @@ def fs_rowwise_adagrad_update(ctx: Context, table: torch.Tensor, state: torch.Te
 def fs_prioritized_step(ctx: Context, args: fs_step_args, stream=None) -> None:
     rc = ctx.lib.fs_prioritized_step(ctx.handle, ctypes.byref(args), _stream(stream))
     ctx.check(rc, "fs_prioritized_step")
+
+
+def fs_step_forward(ctx: Context, args: fs_step_args, stream=None) -> None:
+    rc = ctx.lib.fs_step_forward(ctx.handle, ctypes.byref(args), _stream(stream))
+    ctx.check(rc, "fs_step_forward")
+
+
+def fs_prioritized_step_pipelined(ctx: Context, cur: fs_step_args, nxt: Optional[fs_step_args], stream=None) -> None:
+    rc = ctx.lib.fs_prioritized_step_pipelined(ctx.handle, ctypes.byref(cur),
+                                               ctypes.byref(nxt) if nxt is not None else None, _stream(stream))
+    ctx.check(rc, "fs_prioritized_step_pipelined")
+
+
+def fs_step_join(ctx: Context, stream=None) -> None:
+    ctx.check(ctx.lib.fs_step_join(ctx.handle, _stream(stream)), "fs_step_join")
+
+
+def fs_graph_capture_pipelined(ctx: Context, cur: fs_step_args, nxt: Optional[fs_step_args]) -> c_vp:
+    g = c_vp()
+    rc = ctx.lib.fs_graph_capture_pipelined(ctx.handle, ctypes.byref(cur),
+                                            ctypes.byref(nxt) if nxt is not None else None, ctypes.byref(g))
+    ctx.check(rc, "fs_graph_capture_pipelined")
+    return g
+
+
+def fs_graph_launch(ctx: Context, graph: c_vp, stream=None) -> None:
+    ctx.check(ctx.lib.fs_graph_launch(ctx.handle, graph, _stream(stream)), "fs_graph_launch")
+
+
+def fs_graph_destroy(ctx: Context, graph: c_vp) -> None:
+    ctx.lib.fs_graph_destroy(graph)
 
 
 def fs_init_table_hash(ctx: Context, table: torch.Tensor, stream=None) -> None:
@@ -289,6 +330,7 @@ def make_step_args(table: torch.Tensor, state: torch.Tensor, lr: float, eps: flo
     a.num_rows, a.dim, a.dtype = table.shape[0], table.shape[1], table_dtype_code(table)
     a.lr, a.eps = lr, eps
     a.u_t, a.seg_offsets_t, a.perm_t = _ptr(layout_t["unique"]), _ptr(layout_t["seg_offsets"]), _ptr(layout_t["perm"])
+    a.inverse_t = _ptr(layout_t.get("inverse"))
     a.n_unique_t_dev = _ptr(layout_t["n_unique"])
     a.grads_t = _ptr(grads_t)
     a.n_t = layout_t["n"]

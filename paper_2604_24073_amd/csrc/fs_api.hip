@@ -1,7 +1,10 @@
 // C-ABI entry points: argument validation, context/workspace management and the two-stream
 // schedule of one prioritized iteration (Section 3.2 / Algorithm 2 of the paper, collectives
 // removed).  No kernel lives here.
+#include <condition_variable>
+#include <mutex>
 #include <new>
+#include <thread>
 
 #include "fs_common.h"
 
@@ -28,7 +31,7 @@ void carve(fs_ctx *c, char *base, size_t *total) {
     const size_t n = (size_t)c->max_ids;
     const size_t sort_tiles = (size_t)ceil_div(c->max_ids, kSortTile) + 1;
     const size_t scan_tiles = (size_t)ceil_div(c->max_ids, kScanTile) + 2;
-    const size_t chunks = (size_t)ceil_div(c->max_ids, kReduceChunk) + 1;
+    const size_t chunks = (size_t)ceil_div(c->max_ids, kReduceChunk) + 2;
     c->d_flags = cv.take<int>(4);
     c->d_zero = cv.take<int64_t>(1);
     c->keys[0] = cv.take<uint64_t>(n);
@@ -48,6 +51,9 @@ void carve(fs_ctx *c, char *base, size_t *total) {
 }
 
 hipStream_t as_stream(fs_stream s) { return reinterpret_cast<hipStream_t>(s); }
+
+void worker_stop(fs_ctx *ctx);
+int join_index_work(fs_ctx *ctx, hipStream_t s);
 
 #define FS_REQUIRE(ctx, cond, msg)                          \
     do {                                                    \
@@ -70,6 +76,7 @@ int fs_ctx_create(fs_ctx **out, int device, int64_t max_ids, int32_t max_dim) {
     c->device = device;
     c->max_ids = max_ids;
     c->max_dim = max_dim;
+    c->use_worker = true;
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || device >= ndev) {
         delete c;
@@ -90,7 +97,8 @@ int fs_ctx_create(fs_ctx **out, int device, int64_t max_ids, int32_t max_dim) {
     bool ok = hipMemset(c->slab, 0, 4096) == hipSuccess;
     ok = ok && hipStreamCreateWithFlags(&c->stream_a, hipStreamNonBlocking) == hipSuccess;
     ok = ok && hipStreamCreateWithFlags(&c->stream_b, hipStreamNonBlocking) == hipSuccess;
-    hipEvent_t *evs[] = {&c->ev_fork, &c->ev_split, &c->ev_reduce, &c->ev_co, &c->ev_ex};
+    ok = ok && hipStreamCreateWithFlags(&c->stream_cap, hipStreamNonBlocking) == hipSuccess;
+    hipEvent_t *evs[] = {&c->ev_fork, &c->ev_split, &c->ev_reduce, &c->ev_co, &c->ev_ex, &c->ev_idx[0], &c->ev_idx[1]};
     for (hipEvent_t *e : evs) ok = ok && hipEventCreateWithFlags(e, hipEventDisableTiming) == hipSuccess;
     if (!ok) {
         fs_ctx_destroy(c);
@@ -103,12 +111,14 @@ int fs_ctx_create(fs_ctx **out, int device, int64_t max_ids, int32_t max_dim) {
 int fs_ctx_destroy(fs_ctx *c) {
     if (!c) return FS_OK;
     (void)hipSetDevice(c->device);
+    worker_stop(c);
     if (c->stream_a) { (void)hipStreamSynchronize(c->stream_a); (void)hipStreamDestroy(c->stream_a); }
     if (c->stream_b) { (void)hipStreamSynchronize(c->stream_b); (void)hipStreamDestroy(c->stream_b); }
-    hipEvent_t evs[] = {c->ev_fork, c->ev_split, c->ev_reduce, c->ev_co, c->ev_ex};
+    if (c->stream_cap) (void)hipStreamDestroy(c->stream_cap);
+    hipEvent_t evs[] = {c->ev_fork, c->ev_split, c->ev_reduce, c->ev_co, c->ev_ex, c->ev_idx[0], c->ev_idx[1]};
     for (hipEvent_t e : evs)
         if (e) (void)hipEventDestroy(e);
-    (void)fs_ctx_set_kernel_timing(c, 0);
+    (void)fs_ctx_set_kernel_timing(c, 0, 1);
     if (c->slab) (void)hipFree(c->slab);
     delete c;
     return FS_OK;
@@ -120,6 +130,8 @@ size_t fs_ctx_workspace_bytes(const fs_ctx *ctx) { return ctx ? ctx->slab_bytes 
 
 int fs_check_async(fs_ctx *ctx, fs_stream stream) {
     if (!ctx) return FS_EINVAL;
+    const int jrc = join_index_work(ctx, as_stream(stream));
+    if (jrc != FS_OK) return jrc;
     FS_HIP(ctx, hipStreamSynchronize(as_stream(stream)));
     FS_HIP(ctx, hipStreamSynchronize(ctx->stream_a));
     FS_HIP(ctx, hipStreamSynchronize(ctx->stream_b));
@@ -133,8 +145,8 @@ int fs_check_async(fs_ctx *ctx, fs_stream stream) {
     return FS_ERANGE;
 }
 
-int fs_ctx_set_kernel_timing(fs_ctx *ctx, int slots) {
-    if (!ctx || slots < 0 || slots > 65536) return FS_EINVAL;
+int fs_ctx_set_kernel_timing(fs_ctx *ctx, int slots, int every) {
+    if (!ctx || slots < 0 || slots > 65536 || every < 1) return FS_EINVAL;
     if (ctx->timing_events) {
         const size_t cnt = (size_t)FS_TIME_KINDS * ctx->timing_slots * 2;
         for (size_t i = 0; i < cnt; ++i)
@@ -144,6 +156,9 @@ int fs_ctx_set_kernel_timing(fs_ctx *ctx, int slots) {
     }
     ctx->timing_slots = 0;
     ctx->timing_steps = 0;
+    ctx->step_counter = 0;
+    ctx->timing_every = every;
+    ctx->timing_now = false;
     if (slots == 0) return FS_OK;
     const size_t cnt = (size_t)FS_TIME_KINDS * slots * 2;
     ctx->timing_events = new (std::nothrow) hipEvent_t[cnt]();
@@ -196,6 +211,8 @@ int fs_unique_ids(fs_ctx *ctx, const int64_t *ids, int64_t n, int64_t num_rows, 
     if (n > ctx->max_ids) return set_err(ctx, FS_ENOMEM, "unique: n beyond the context capacity");
     FS_REQUIRE(ctx, seg_offsets && n_unique_dev, "unique: null pointer");
     if (n > 0) FS_REQUIRE(ctx, ids && unique && perm, "unique: null pointer");
+    const int jrc = join_index_work(ctx, as_stream(stream));      // the workspace may still be in use on A
+    if (jrc != FS_OK) return jrc;
     return launch_unique(ctx, ids, n, num_rows, unique, seg_offsets, perm, inverse, n_unique_dev, as_stream(stream));
 }
 
@@ -210,20 +227,25 @@ int fs_collision_split(fs_ctx *ctx, const int64_t *u_t, const int64_t *n_t_dev, 
     FS_REQUIRE(ctx, counts_dev, "split: null counts");
     if (cap_t > 0) FS_REQUIRE(ctx, u_t && n_t_dev && co && co_slot && ex && ex_slot, "split: null pointer (t side)");
     if (cap_t1 > 0) FS_REQUIRE(ctx, u_t1 && n_t1_dev && ex_next && ex_next_slot, "split: null pointer (t+1 side)");
+    const int jrc = join_index_work(ctx, as_stream(stream));      // the workspace may still be in use on A
+    if (jrc != FS_OK) return jrc;
     return launch_split(ctx, u_t, cap_t > 0 ? n_t_dev : nullptr, u_t1, cap_t1 > 0 ? n_t1_dev : nullptr, cap_t, cap_t1,
                         co, co_slot, ex, ex_slot, ex_next, ex_next_slot, counts_dev, as_stream(stream));
 }
 
 int fs_segment_reduce_grads(fs_ctx *ctx, const float *grads, int64_t n, int32_t dim, const int32_t *perm,
-                            const int32_t *seg_offsets, const int64_t *n_unique_dev, float *reduced,
-                            fs_stream stream) {
+                            const int32_t *seg_offsets, const int32_t *inverse, const int64_t *n_unique_dev,
+                            float *reduced, fs_stream stream) {
     if (!ctx) return FS_EINVAL;
     FS_REQUIRE(ctx, n >= 0, "reduce: negative size");
     FS_REQUIRE(ctx, dim_ok(dim, FS_F32), "reduce: dim must be a multiple of 4, at most FS_MAX_DIM");
     if (n > ctx->max_ids || dim > ctx->max_dim) return set_err(ctx, FS_ENOMEM, "reduce: beyond the context capacity");
     if (n == 0) return FS_OK;
     FS_REQUIRE(ctx, grads && perm && seg_offsets && n_unique_dev && reduced, "reduce: null pointer");
-    return launch_reduce(ctx, grads, n, dim, perm, seg_offsets, n_unique_dev, reduced, as_stream(stream));
+    ctx->reduce_inverse = inverse;
+    const int rc = launch_reduce(ctx, grads, n, dim, perm, seg_offsets, n_unique_dev, reduced, as_stream(stream));
+    ctx->reduce_inverse = nullptr;
+    return rc;
 }
 
 int fs_rowwise_adagrad_update(fs_ctx *ctx, void *table, fs_dtype dt, float *state, int64_t num_rows, int32_t dim,
@@ -256,8 +278,13 @@ int fs_stream_copy(fs_ctx *ctx, const void *src, void *dst, int64_t n_bytes, fs_
     return launch_copy(ctx, src, dst, n_bytes, as_stream(stream));
 }
 
-int fs_prioritized_step(fs_ctx *ctx, const fs_step_args *a, fs_stream stream) {
-    if (!ctx) return FS_EINVAL;
+}  // extern "C"
+
+namespace {
+
+// host-visible checks shared by the step entry points; `need_t`: iteration t is used (reduce,
+// updates), `need_t1`: the lookahead batch is used (dedup, gather)
+int check_step_args(fs_ctx *ctx, const fs_step_args *a, bool *have_t, bool *have_t1) {
     FS_REQUIRE(ctx, a, "step: null args");
     const int dt = a->dtype;
     FS_REQUIRE(ctx, dt == FS_F32 || dt == FS_BF16, "step: unknown dtype");
@@ -266,49 +293,53 @@ int fs_prioritized_step(fs_ctx *ctx, const fs_step_args *a, fs_stream stream) {
     if (a->n_t > ctx->max_ids || a->n_t1 > ctx->max_ids || a->dim > ctx->max_dim)
         return set_err(ctx, FS_ENOMEM, "step: beyond the context capacity");
     FS_REQUIRE(ctx, a->table && a->state && a->counts_dev, "step: null table/state/counts");
-    const bool have_t = a->n_t > 0;
-    const bool have_t1 = a->values_t1 != nullptr && a->n_t1 > 0;
-    if (have_t)
+    *have_t = a->n_t > 0;
+    *have_t1 = a->values_t1 != nullptr && a->n_t1 > 0;
+    if (*have_t)
         FS_REQUIRE(ctx, a->u_t && a->seg_offsets_t && a->perm_t && a->n_unique_t_dev && a->grads_t && a->reduced &&
                             a->co && a->co_slot && a->ex && a->ex_slot,
                    "step: null pointer (iteration t)");
-    if (have_t1)
+    if (*have_t1)
         FS_REQUIRE(ctx, a->u_t1 && a->seg_offsets_t1 && a->perm_t1 && a->n_unique_t1_dev && a->ex_next &&
                             a->ex_next_slot && a->emb_t1,
                    "step: null pointer (lookahead)");
+    return FS_OK;
+}
 
-    hipStream_t sp = as_stream(stream), sa = ctx->stream_a, sb = ctx->stream_b;
-    const fs_dtype fdt = (fs_dtype)dt;
+// Forward of Algorithm 2 (index work): dedup of the lookahead IDs, then the collision split
+int enqueue_index_work(fs_ctx *ctx, const fs_step_args *a, bool have_t, bool have_t1, hipStream_t s) {
     int rc;
-    // fork: the side streams start after whatever the caller already queued on `stream`
-    FS_HIP(ctx, hipEventRecord(ctx->ev_fork, sp));
-    FS_HIP(ctx, hipStreamWaitEvent(sa, ctx->ev_fork, 0));
-    FS_HIP(ctx, hipStreamWaitEvent(sb, ctx->ev_fork, 0));
-
-    // side stream A: dedup of the lookahead IDs, then the collision split
     if (have_t1) {
         rc = launch_unique(ctx, a->values_t1, a->n_t1, a->num_rows, a->u_t1, a->seg_offsets_t1, a->perm_t1,
-                           a->inverse_t1, a->n_unique_t1_dev, sa);
+                           a->inverse_t1, a->n_unique_t1_dev, s);
         if (rc != FS_OK) return rc;
     }
-    rc = launch_split(ctx, a->u_t, have_t ? a->n_unique_t_dev : nullptr, a->u_t1,
-                      have_t1 ? a->n_unique_t1_dev : nullptr, have_t ? a->n_t : 0, have_t1 ? a->n_t1 : 0, a->co,
-                      a->co_slot, a->ex, a->ex_slot, a->ex_next, a->ex_next_slot, a->counts_dev, sa);
-    if (rc != FS_OK) return rc;
-    FS_HIP(ctx, hipEventRecord(ctx->ev_split, sa));
+    return launch_split(ctx, a->u_t, have_t ? a->n_unique_t_dev : nullptr, a->u_t1,
+                        have_t1 ? a->n_unique_t1_dev : nullptr, have_t ? a->n_t : 0, have_t1 ? a->n_t1 : 0, a->co,
+                        a->co_slot, a->ex, a->ex_slot, a->ex_next, a->ex_next_slot, a->counts_dev, s);
+}
 
-    // main stream: reduce the gradients of t while A works on the indices of t+1
-    if (have_t) {
-        rc = launch_reduce(ctx, a->grads_t, a->n_t, a->dim, a->perm_t, a->seg_offsets_t, a->n_unique_t_dev, a->reduced,
-                           sp, timing_pair(ctx, FS_TIME_REDUCE));
-        if (rc != FS_OK) return rc;
-    }
-    FS_HIP(ctx, hipEventRecord(ctx->ev_reduce, sp));
-    FS_HIP(ctx, hipStreamWaitEvent(sp, ctx->ev_split, 0));
+// one step in `timing_every` gets its kernels bracketed by event pairs (an event record costs the
+// host more than a kernel launch, so bracketing every step would slow the very thing it measures)
+void begin_step_timing(fs_ctx *ctx) {
+    ctx->timing_now = ctx->timing_slots > 0 && !ctx->capturing && (ctx->step_counter % ctx->timing_every) == 0;
+    if (ctx->timing_slots > 0 && !ctx->capturing) ++ctx->step_counter;
+}
 
-    // deferred pass on B: needs the split and the reduced gradients, nothing else
-    FS_HIP(ctx, hipStreamWaitEvent(sb, ctx->ev_split, 0));
-    FS_HIP(ctx, hipStreamWaitEvent(sb, ctx->ev_reduce, 0));
+int enqueue_reduce(fs_ctx *ctx, const fs_step_args *a, hipStream_t sp) {
+    ctx->reduce_inverse = a->inverse_t;
+    const int rc = launch_reduce(ctx, a->grads_t, a->n_t, a->dim, a->perm_t, a->seg_offsets_t, a->n_unique_t_dev,
+                                 a->reduced, sp, timing_pair(ctx, FS_TIME_REDUCE));
+    ctx->reduce_inverse = nullptr;
+    return rc;
+}
+
+// Backward of Algorithm 2 after the reduce: priority pass on `sp`, deferred pass on B (which
+// already waits for the reduce and the split), gather of the lookahead rows on `sp`, join of B.
+int enqueue_updates_and_gather(fs_ctx *ctx, const fs_step_args *a, bool have_t, bool have_t1, hipStream_t sp) {
+    hipStream_t sb = ctx->stream_b;
+    const fs_dtype fdt = (fs_dtype)a->dtype;
+    int rc;
     if (have_t) {
         // priority pass: collision rows, strictly before the lookahead rows are read
         hipEvent_t *tco = timing_pair(ctx, FS_TIME_UPDATE_CO), *tex = timing_pair(ctx, FS_TIME_UPDATE_EX);
@@ -326,7 +357,7 @@ int fs_prioritized_step(fs_ctx *ctx, const fs_step_args *a, fs_stream stream) {
     FS_HIP(ctx, hipEventRecord(ctx->ev_ex, sb));
     if (have_t1) {
         // exclusive rows and lookahead rows are disjoint, so this may overlap the deferred pass
-        const int row_bytes = a->dim * (dt == FS_F32 ? 4 : 2);
+        const int row_bytes = a->dim * (a->dtype == FS_F32 ? 4 : 2);
         hipEvent_t *tg = timing_pair(ctx, FS_TIME_GATHER);
         if (tg) (void)hipEventRecord(tg[0], sp);
         rc = launch_gather(ctx, a->table, a->num_rows, row_bytes, a->values_t1, a->offsets_t1, a->batch_t1, a->n_t1,
@@ -335,7 +366,259 @@ int fs_prioritized_step(fs_ctx *ctx, const fs_step_args *a, fs_stream stream) {
         if (tg) (void)hipEventRecord(tg[1], sp);
     }
     FS_HIP(ctx, hipStreamWaitEvent(sp, ctx->ev_ex, 0));
-    if (ctx->timing_slots > 0) ++ctx->timing_steps;
+    if (ctx->timing_now) ++ctx->timing_steps;
+    return FS_OK;
+}
+
+}  // namespace
+
+struct fs_graph {
+    hipGraph_t graph;
+    hipGraphExec_t exec;
+};
+
+// A second host thread that enqueues the index half of an iteration on side stream A while the
+// calling thread enqueues the gradient half: an iteration is about sixteen launches and a dozen
+// event operations, and at a few microseconds each the host, not the GPU, would set the pace.
+struct fs_worker {
+    std::thread thread;
+    std::mutex mu;
+    std::condition_variable cv;
+    bool has_job = false, done = true, quit = false;
+    fs_step_args args;
+    bool have_t = false, have_t1 = false;
+    int parity = 0;               // which of the two index events the job records when it is enqueued
+    int rc = FS_OK;
+};
+
+namespace {
+
+void worker_main(fs_ctx *ctx) {
+    fs_worker *w = ctx->worker;
+    (void)hipSetDevice(ctx->device);
+    std::unique_lock<std::mutex> lk(w->mu);
+    for (;;) {
+        w->cv.wait(lk, [w] { return w->has_job || w->quit; });
+        if (w->quit) return;
+        w->has_job = false;
+        lk.unlock();
+        int rc = FS_OK;
+        if (hipStreamWaitEvent(ctx->stream_a, ctx->ev_fork, 0) != hipSuccess) rc = FS_EHIP;
+        if (rc == FS_OK) rc = enqueue_index_work(ctx, &w->args, w->have_t, w->have_t1, ctx->stream_a);
+        if (hipEventRecord(ctx->ev_idx[w->parity], ctx->stream_a) != hipSuccess && rc == FS_OK) rc = FS_EHIP;
+        lk.lock();
+        w->rc = rc;
+        w->done = true;
+        w->cv.notify_all();
+    }
+}
+
+// hands the index half to the worker (started on first use); false if no worker is available
+bool worker_post(fs_ctx *ctx, const fs_step_args *a, bool have_t, bool have_t1, int parity) {
+    if (!ctx->worker) {
+        ctx->worker = new (std::nothrow) fs_worker();
+        if (!ctx->worker) return false;
+        ctx->worker->thread = std::thread(worker_main, ctx);
+    }
+    fs_worker *w = ctx->worker;
+    std::lock_guard<std::mutex> lk(w->mu);
+    w->args = *a;
+    w->have_t = have_t;
+    w->have_t1 = have_t1;
+    w->parity = parity;
+    w->has_job = true;
+    w->done = false;
+    w->cv.notify_all();
+    return true;
+}
+
+int worker_wait(fs_ctx *ctx) {
+    fs_worker *w = ctx->worker;
+    if (!w) return FS_OK;
+    std::unique_lock<std::mutex> lk(w->mu);
+    w->cv.wait(lk, [w] { return w->done; });
+    return w->rc;
+}
+
+void worker_stop(fs_ctx *ctx) {
+    fs_worker *w = ctx->worker;
+    if (!w) return;
+    {
+        std::lock_guard<std::mutex> lk(w->mu);
+        w->quit = true;
+        w->cv.notify_all();
+    }
+    if (w->thread.joinable()) w->thread.join();
+    delete w;
+    ctx->worker = nullptr;
+}
+
+// Makes `s` wait for the index half that an earlier pipelined call left running on stream A.
+int join_index_work(fs_ctx *ctx, hipStream_t s) {
+    if (!ctx->idx_pending) return FS_OK;
+    const int wrc = worker_wait(ctx);                        // its enqueueing (and event record) is complete
+    ctx->idx_pending = false;
+    FS_HIP(ctx, hipStreamWaitEvent(s, ctx->ev_idx[ctx->idx_parity], 0));
+    return wrc;
+}
+
+}  // namespace
+
+extern "C" {
+
+int fs_step_forward(fs_ctx *ctx, const fs_step_args *a, fs_stream stream) {
+    if (!ctx) return FS_EINVAL;
+    bool have_t, have_t1;
+    int rc = check_step_args(ctx, a, &have_t, &have_t1);
+    if (rc != FS_OK) return rc;
+    hipStream_t sp = as_stream(stream), sa = ctx->stream_a;
+    rc = join_index_work(ctx, sp);
+    if (rc != FS_OK) return rc;
+    FS_HIP(ctx, hipEventRecord(ctx->ev_fork, sp));
+    FS_HIP(ctx, hipStreamWaitEvent(sa, ctx->ev_fork, 0));
+    rc = enqueue_index_work(ctx, a, have_t, have_t1, sa);
+    if (rc != FS_OK) return rc;
+    FS_HIP(ctx, hipEventRecord(ctx->ev_split, sa));
+    FS_HIP(ctx, hipStreamWaitEvent(sp, ctx->ev_split, 0));
+    return FS_OK;
+}
+
+int fs_prioritized_step(fs_ctx *ctx, const fs_step_args *a, fs_stream stream) {
+    if (!ctx) return FS_EINVAL;
+    bool have_t, have_t1;
+    int rc = check_step_args(ctx, a, &have_t, &have_t1);
+    if (rc != FS_OK) return rc;
+    hipStream_t sp = as_stream(stream), sa = ctx->stream_a, sb = ctx->stream_b;
+    rc = join_index_work(ctx, sp);
+    if (rc != FS_OK) return rc;
+    begin_step_timing(ctx);
+    // fork: the side streams start after whatever the caller already queued on `stream`
+    FS_HIP(ctx, hipEventRecord(ctx->ev_fork, sp));
+    FS_HIP(ctx, hipStreamWaitEvent(sa, ctx->ev_fork, 0));
+    FS_HIP(ctx, hipStreamWaitEvent(sb, ctx->ev_fork, 0));
+    // main stream first (the host enqueues the bandwidth-heavy kernel before the many small ones):
+    // reduce the gradients of t while A works on the indices of t+1
+    if (have_t) {
+        rc = enqueue_reduce(ctx, a, sp);
+        if (rc != FS_OK) return rc;
+    }
+    FS_HIP(ctx, hipEventRecord(ctx->ev_reduce, sp));
+    rc = enqueue_index_work(ctx, a, have_t, have_t1, sa);
+    if (rc != FS_OK) return rc;
+    FS_HIP(ctx, hipEventRecord(ctx->ev_split, sa));
+    FS_HIP(ctx, hipStreamWaitEvent(sp, ctx->ev_split, 0));
+    // deferred pass on B: needs the split and the reduced gradients, nothing else
+    FS_HIP(ctx, hipStreamWaitEvent(sb, ctx->ev_split, 0));
+    FS_HIP(ctx, hipStreamWaitEvent(sb, ctx->ev_reduce, 0));
+    return enqueue_updates_and_gather(ctx, a, have_t, have_t1, sp);
+}
+
+int fs_prioritized_step_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs_step_args *next, fs_stream stream) {
+    if (!ctx) return FS_EINVAL;
+    bool have_t, have_t1, nxt_t = false, nxt_t1 = false;
+    int rc = check_step_args(ctx, cur, &have_t, &have_t1);
+    if (rc != FS_OK) return rc;
+    if (next) {
+        rc = check_step_args(ctx, next, &nxt_t, &nxt_t1);
+        if (rc != FS_OK) return rc;
+    }
+    hipStream_t sp = as_stream(stream), sa = ctx->stream_a, sb = ctx->stream_b;
+    begin_step_timing(ctx);
+    // the previous call may have left its index half (the split of `cur`) running on A; its
+    // enqueueing is long finished, the GPU work is waited for only where it is needed (below)
+    const bool prev_pending = ctx->idx_pending;
+    const int prev_parity = ctx->idx_parity;
+    if (prev_pending) {
+        rc = worker_wait(ctx);
+        if (rc != FS_OK) return rc;
+    }
+    FS_HIP(ctx, hipEventRecord(ctx->ev_fork, sp));
+    // index half of the NEXT iteration: beside everything this iteration does, enqueued by a
+    // second host thread (not while a graph is being captured: capture is per thread)
+    const int parity = prev_parity ^ 1;
+    const bool threaded = next && !ctx->capturing && ctx->use_worker && worker_post(ctx, next, nxt_t, nxt_t1, parity);
+    if (next && !threaded) FS_HIP(ctx, hipStreamWaitEvent(sa, ctx->ev_fork, 0));
+    rc = FS_OK;
+    if (have_t) rc = enqueue_reduce(ctx, cur, sp);
+    // the reduce needed only the layout; the split of `cur` is needed from here on
+    if (rc == FS_OK && prev_pending && hipStreamWaitEvent(sp, ctx->ev_idx[prev_parity], 0) != hipSuccess) rc = FS_EHIP;
+    ctx->idx_pending = false;
+    if (rc == FS_OK && hipEventRecord(ctx->ev_reduce, sp) != hipSuccess) rc = FS_EHIP;
+    if (rc == FS_OK && hipStreamWaitEvent(sb, ctx->ev_reduce, 0) != hipSuccess) rc = FS_EHIP;   // reduce + split
+    if (next && !threaded) {
+        if (rc == FS_OK) rc = enqueue_index_work(ctx, next, nxt_t, nxt_t1, sa);
+        if (rc == FS_OK && hipEventRecord(ctx->ev_idx[parity], sa) != hipSuccess) rc = FS_EHIP;
+    }
+    if (rc == FS_OK) rc = enqueue_updates_and_gather(ctx, cur, have_t, have_t1, sp);
+    if (next) {
+        ctx->idx_parity = parity;
+        ctx->idx_pending = true;
+        // a captured graph must end with every stream joined; otherwise A keeps running and the
+        // next call (or fs_step_join / fs_check_async) waits for it where its results are needed
+        if (ctx->capturing && rc == FS_OK) rc = join_index_work(ctx, sp);
+    }
+    return rc;
+}
+
+int fs_step_join(fs_ctx *ctx, fs_stream stream) {
+    if (!ctx) return FS_EINVAL;
+    return join_index_work(ctx, as_stream(stream));
+}
+
+int fs_ctx_set_threaded_enqueue(fs_ctx *ctx, int on) {
+    if (!ctx) return FS_EINVAL;
+    ctx->use_worker = on != 0;
+    return FS_OK;
+}
+
+int fs_graph_capture_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs_step_args *next, fs_graph **out) {
+    if (!ctx || !out) return FS_EINVAL;
+    *out = nullptr;
+    fs_graph *g = new (std::nothrow) fs_graph();
+    if (!g) return FS_ENOMEM;
+    g->graph = nullptr;
+    g->exec = nullptr;
+    if (ctx->idx_pending) {                                  // nothing from outside may leak into the capture
+        (void)worker_wait(ctx);
+        ctx->idx_pending = false;
+        (void)hipStreamSynchronize(ctx->stream_a);
+    }
+    hipError_t e = hipStreamBeginCapture(ctx->stream_cap, hipStreamCaptureModeThreadLocal);
+    if (e != hipSuccess) {
+        delete g;
+        return hip_err(ctx, e, "hipStreamBeginCapture");
+    }
+    ctx->capturing = true;
+    const int rc = fs_prioritized_step_pipelined(ctx, cur, next, ctx->stream_cap);
+    ctx->capturing = false;
+    e = hipStreamEndCapture(ctx->stream_cap, &g->graph);       // always end the capture, also after an error
+    if (rc != FS_OK || e != hipSuccess || g->graph == nullptr) {
+        if (g->graph) (void)hipGraphDestroy(g->graph);
+        delete g;
+        (void)hipGetLastError();
+        return rc != FS_OK ? rc : hip_err(ctx, e, "hipStreamEndCapture");
+    }
+    e = hipGraphInstantiate(&g->exec, g->graph, nullptr, nullptr, 0);
+    if (e != hipSuccess) {
+        (void)hipGraphDestroy(g->graph);
+        delete g;
+        return hip_err(ctx, e, "hipGraphInstantiate");
+    }
+    *out = g;
+    return FS_OK;
+}
+
+int fs_graph_launch(fs_ctx *ctx, fs_graph *graph, fs_stream stream) {
+    if (!ctx || !graph || !graph->exec) return FS_EINVAL;
+    FS_HIP(ctx, hipGraphLaunch(graph->exec, as_stream(stream)));
+    return FS_OK;
+}
+
+int fs_graph_destroy(fs_graph *graph) {
+    if (!graph) return FS_OK;
+    if (graph->exec) (void)hipGraphExecDestroy(graph->exec);
+    if (graph->graph) (void)hipGraphDestroy(graph->graph);
+    delete graph;
     return FS_OK;
 }
 

@@ -14,10 +14,10 @@ namespace fs {
 constexpr int kWave = 64;
 
 // radix sort geometry
-constexpr int kRadixBits = 8;
-constexpr int kRadix = 1 << kRadixBits;
-constexpr int kSortThreads = 256;
-constexpr int kSortKpt = 8;                               // keys per thread
+constexpr int kRadixBits = 9;                             // most bits one pass may sort
+constexpr int kRadix = 1 << kRadixBits;                   // most bins of one pass
+constexpr int kSortThreads = 1024;
+constexpr int kSortKpt = 4;                               // keys per thread
 constexpr int kSortTile = kSortThreads * kSortKpt;        // keys per tile
 constexpr int kSortWaves = kSortThreads / kWave;
 
@@ -26,8 +26,9 @@ constexpr int kScanThreads = 256;
 constexpr int kScanIpt = 4;
 constexpr int kScanTile = kScanThreads * kScanIpt;
 
-// segment reduce: sorted positions owned by one wavefront
-constexpr int kReduceChunk = 128;
+// segment reduce: sorted positions owned by one wavefront (one 64-bit tail mask, one permutation
+// entry per lane).  Short chunks = many wavefronts with short dependent-load chains.
+constexpr int kReduceChunk = 64;
 constexpr int kReduceWavesPerBlock = 4;
 
 // device-side error flag bits (ctx->d_flags[0])
@@ -65,14 +66,25 @@ struct fs_ctx {
     double *part_head;        // [chunks, max_dim] fp64 partial of the first run of each chunk
     double *part_last;        // [chunks, max_dim] fp64 partial of the last run of each chunk
     int32_t *chunk_desc;      // [chunks * 4]
+    const int32_t *reduce_inverse;   // host-side: the caller's optional inverse map for the launch being enqueued
     int64_t *d_zero;          // device scalar that stays 0 (stands in for a missing lookahead)
 
     hipStream_t stream_a;     // index work of the lookahead batch
     hipStream_t stream_b;     // deferred update pass
     hipEvent_t ev_fork, ev_split, ev_reduce, ev_co, ev_ex;
+    hipEvent_t ev_idx[2];     // completion of the index half left running by a pipelined call (alternating)
+    int idx_parity;           // which of the two the pending index half records
+    bool idx_pending;         // host-side: an index half is in flight on stream A and not yet joined
 
     // optional per-kernel timing of the step: events[(kind * slots + slot) * 2 + {0,1}]
+    struct fs_worker *worker; // second host thread that enqueues the index half (started on first use)
+    bool use_worker;
+    hipStream_t stream_cap;   // capture stream of fs_graph_capture_pipelined
+    bool capturing;           // host-side: a step is being recorded into a graph (no timing events)
     int timing_slots;
+    int timing_every;         // bracket the kernels of one step in `timing_every`
+    bool timing_now;          // host-side: the step being enqueued is a sampled one
+    int64_t step_counter;
     int64_t timing_steps;
     hipEvent_t *timing_events;
 };
@@ -120,7 +132,7 @@ int launch_gather(fs_ctx *, const void *table, int64_t num_rows, int row_bytes, 
                   const int64_t *offsets, int64_t batch, int64_t n, void *out, hipStream_t s);
 // event pair of timing kind `kind` for the step being enqueued, or nullptr when timing is off
 inline hipEvent_t *timing_pair(fs_ctx *ctx, int kind) {
-    if (ctx->timing_slots <= 0) return nullptr;
+    if (!ctx->timing_now) return nullptr;
     const int slot = (int)(ctx->timing_steps % ctx->timing_slots);
     return ctx->timing_events + ((size_t)kind * ctx->timing_slots + slot) * 2;
 }

@@ -3,35 +3,63 @@
 //
 // Row popularity is Zipf: half of all occurrences sit in segments longer than a wavefront could
 // own, the hottest row alone has tens of thousands.  So the work is cut by POSITION, not by
-// segment: every wavefront owns kReduceChunk consecutive sorted positions and streams their
-// gradient rows (16 bytes per lane, 64/LPR rows per instruction, UNR instructions in flight),
-// accumulating in fp64.  A 128-bit tail mask (which positions end a segment) drives wave-uniform
-// flushes.  Runs that are cut by a chunk border go to fp64 partial rows, and a second launch
-// adds the partials of each cut segment in chunk order.  The summation order is fixed by the
-// layout alone, so results are reproducible.
+// segment: every wavefront owns 64 consecutive sorted positions and streams their gradient rows
+// (16 bytes per lane, 64/LPR rows per instruction, up to 16 instructions = 16 KB in flight),
+// accumulating in fp64.  On gfx9-family hardware loads and stores share one counter, so a
+// wavefront that interleaves result stores with its loads cannot keep a second batch in flight;
+// bandwidth comes from MANY short-lived wavefronts instead (short chunks, short dependent-load
+// chains, first batch requested before the index work).  A 64-bit mask of the positions that
+// end a segment drives wave-uniform flushes.  Runs cut by a chunk border go to fp64 partial
+// rows, and a second launch adds the partials of each cut segment in a fixed order.  The
+// summation order depends on the layout alone: results are reproducible.
 #include "fs_common.h"
 
 namespace fs {
 
+#ifndef FS_REDUCE_UNR
+#define FS_REDUCE_UNR 8
+#endif
+constexpr int kFixThreads = 512;
 constexpr int kDescInts = 4;   // per chunk: first segment, number of flushes, head run complete, has tail run
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
+// x + (x of the lane 32 away) in every lane: one cross-half swap per 32-bit word, no LDS traffic
+__device__ __forceinline__ double add_xor32(double x) {
+    const unsigned lo = (unsigned)__double2loint(x), hi = (unsigned)__double2hiint(x);
+    const u32x2 a = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+    const u32x2 b = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+    return __hiloint2double((int)b[0], (int)a[0]) + __hiloint2double((int)b[1], (int)a[1]);
+}
+
+// x + (x of the lane 16 away) in every lane
+__device__ __forceinline__ double add_xor16(double x) {
+    const unsigned lo = (unsigned)__double2loint(x), hi = (unsigned)__double2hiint(x);
+    const u32x2 a = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+    const u32x2 b = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+    return __hiloint2double((int)b[0], (int)a[0]) + __hiloint2double((int)b[1], (int)a[1]);
+}
+
+// sum over the 64/LPR groups of a wavefront, result in every lane; fixed order
 template <int LPR>
 __device__ __forceinline__ double across_groups(double x) {
+    if (LPR == 32) return add_xor32(x);
+    if (LPR == 16) return add_xor32(add_xor16(x));
 #pragma unroll
     for (int m = LPR; m < kWave; m <<= 1) x += __shfl_xor(x, m, kWave);
     return x;
 }
 
-template <int LPR, int UNR>
+template <int LPR, int UNR, bool HAS_INV>
 __global__ __launch_bounds__(kReduceWavesPerBlock *kWave) void reduce_chunk_kernel(
     const f32x4 *__restrict__ grads, int n, int gvec, const int32_t *__restrict__ perm,
-    const int32_t *__restrict__ seg_offsets, const int64_t *__restrict__ n_unique_dev, f32x4 *__restrict__ reduced,
+    const int32_t *__restrict__ seg_offsets, const int32_t *__restrict__ inverse,
+    const int64_t *__restrict__ n_unique_dev, f32x4 *__restrict__ reduced,
     double *__restrict__ part_head, double *__restrict__ part_last, int32_t *__restrict__ chunk_desc) {
-    constexpr int GPW = kWave / LPR;
-    constexpr int ITERS = kReduceChunk / GPW;
-    static_assert(kReduceChunk == 128, "tail mask is two 64-bit words");
-    static_assert(ITERS % UNR == 0, "unroll must divide the chunk");
-    __shared__ uint32_t tail_bits[kReduceWavesPerBlock][4];
+    constexpr int GPW = kWave / LPR;          // rows per wavefront instruction
+    constexpr int BP = GPW * UNR;             // positions per batch
+    constexpr int NB = kReduceChunk / BP;     // batches per chunk
+    static_assert(kReduceChunk == kWave && kReduceChunk % BP == 0, "one tail word, whole batches");
+    __shared__ uint32_t tail_bits[kReduceWavesPerBlock][2];
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wib = threadIdx.x / kWave;
@@ -41,11 +69,47 @@ __global__ __launch_bounds__(kReduceWavesPerBlock *kWave) void reduce_chunk_kern
     const int a = chunk * kReduceChunk;
     const bool active = a < n;                               // wave-uniform
     const int b = active ? ((a + kReduceChunk < n) ? a + kReduceChunk : n) : a;
-    const int U = (int)*n_unique_dev;
+    const int span = b - a;
+    const bool col_ok = lig < gvec;
 
-    if (lane < 4) tail_bits[wib][lane] = 0;
-    // first segment of the chunk: the largest s with seg_offsets[s] <= a (64-ary search)
+    // the gradient rows of the first batch are requested before anything else: the index work
+    // below (search of the first segment, tail mask) then runs under their latency
+    const int pr = (lane < span) ? perm[a + lane] : 0;
+    int edge = 0;                                            // lane 0: position a-1, lane 1: position b
+    if (HAS_INV && active && lane == 0 && a > 0) edge = perm[a - 1];
+    if (HAS_INV && active && lane == 1 && b < n) edge = perm[b];
+    auto load_batch = [&](f32x4(&v)[UNR], int k) {
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int q = k * BP + u * GPW + grp;             // position inside the chunk
+            const int p = __shfl(pr, q, kWave);
+            v[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (col_ok && q < span) v[u] = __builtin_nontemporal_load(&grads[(int64_t)p * gvec + lig]);
+        }
+    };
+    f32x4 v[UNR];
+    load_batch(v, 0);
+
     int s0 = 0;
+    bool head_complete = false;
+    uint64_t tails = 0;
+    if (HAS_INV) {
+        // Segment of every position straight from the inverse map (one gathered 4-byte load per
+        // position, issued together with the first batch of rows): a position ends a segment iff
+        // its successor belongs to another one.  No search, no LDS, one dependent round.
+        if (!active) return;
+        const int inv = (lane < span) ? inverse[pr] : -1;
+        const int inv_edge = (lane < 2) ? inverse[edge] : -1;
+        const int inv_prev = __shfl(inv_edge, 0, kWave), inv_after = __shfl(inv_edge, 1, kWave);
+        int nxt = __shfl_down(inv, 1, kWave);
+        if (lane == span - 1) nxt = (b < n) ? inv_after : -1;
+        tails = __ballot(lane < span && nxt != inv);
+        s0 = __shfl(inv, 0, kWave);
+        head_complete = (a == 0) || (inv_prev != s0);
+    } else {
+    const int U = (int)*n_unique_dev;
+    if (lane < 2) tail_bits[wib][lane] = 0;
+    // first segment of the chunk: the largest s with seg_offsets[s] <= a (64-ary search)
     if (active) {
         int lo = 0, hi = U;                                  // seg_offsets[lo] <= a < seg_offsets[hi]
         while (hi - lo > 1) {
@@ -61,45 +125,29 @@ __global__ __launch_bounds__(kReduceWavesPerBlock *kWave) void reduce_chunk_kern
         s0 = lo;
     }
     __syncthreads();
-    bool head_complete = false;
     if (active) {
-        // segment ends inside (a, b]: at most kReduceChunk of them, strictly increasing
-#pragma unroll
-        for (int i = 0; i < kReduceChunk / kWave; ++i) {
-            const int s = s0 + 1 + i * kWave + lane;
-            if (s <= U) {
-                const int e = seg_offsets[s];
-                if (e <= b) {
-                    const int bit = e - 1 - a;
-                    atomicOr(&tail_bits[wib][bit >> 5], 1u << (bit & 31));
-                }
+        // segment ends inside (a, b]: at most 64 of them, strictly increasing
+        const int s = s0 + 1 + lane;
+        if (s <= U) {
+            const int e = seg_offsets[s];
+            if (e <= b) {
+                const int bit = e - 1 - a;
+                atomicOr(&tail_bits[wib][bit >> 5], 1u << (bit & 31));
             }
         }
         head_complete = seg_offsets[s0] == a;
     }
     __syncthreads();
     if (!active) return;
-    uint64_t tails[2];
-    {
-        uint32_t w[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) w[i] = (uint32_t)__builtin_amdgcn_readfirstlane((int)tail_bits[wib][i]);
-        tails[0] = (uint64_t)w[0] | ((uint64_t)w[1] << 32);
-        tails[1] = (uint64_t)w[2] | ((uint64_t)w[3] << 32);
+    const uint32_t w0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)tail_bits[wib][0]);
+    const uint32_t w1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)tail_bits[wib][1]);
+    tails = (uint64_t)w0 | ((uint64_t)w1 << 32);
     }
-
-    // this chunk's slice of the permutation, one or two entries per lane
-    int pr[kReduceChunk / kWave];
-#pragma unroll
-    for (int i = 0; i < kReduceChunk / kWave; ++i) {
-        const int p = a + i * kWave + lane;
-        pr[i] = (p < b) ? perm[p] : 0;
-    }
+    s0 = __builtin_amdgcn_readfirstlane(s0);
 
     double acc[4] = {0.0, 0.0, 0.0, 0.0};
     int seg = s0;
     int nflush = 0;
-    const bool col_ok = lig < gvec;
     const int dim = gvec * 4;
 
     auto flush = [&]() {
@@ -120,41 +168,44 @@ __global__ __launch_bounds__(kReduceWavesPerBlock *kWave) void reduce_chunk_kern
         ++seg;
         ++nflush;
     };
-
-    for (int it0 = 0; it0 < ITERS; it0 += UNR) {
-        if (a + it0 * GPW >= b) break;                        // wave-uniform: ragged last chunk
-        f32x4 v[UNR];
+    auto add_batch = [&](const f32x4(&vv)[UNR], int k) {
+        const uint64_t shifted = tails >> ((k * BP) & 63);
+        const uint64_t batch_tails = (BP == kWave) ? shifted : (shifted & ((1ull << (BP & 63)) - 1ull));
+        if (batch_tails == 0) {                               // no segment ends in this batch
 #pragma unroll
-        for (int u = 0; u < UNR; ++u) {
-            const int q0 = (it0 + u) * GPW;                   // wave-uniform first position of this instruction
-            const int src = (q0 < kWave) ? pr[0] : pr[1];
-            const int p = __shfl(src, (q0 & (kWave - 1)) + grp, kWave);
-            v[u] = f32x4{0.f, 0.f, 0.f, 0.f};
-            if (col_ok && (a + q0 + grp) < b) v[u] = __builtin_nontemporal_load(&grads[(int64_t)p * gvec + lig]);
+            for (int u = 0; u < UNR; ++u)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc[c] += (double)vv[u][c];
+            return;
         }
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
-            const int q0 = (it0 + u) * GPW;
-            const uint64_t tw = (q0 < kWave) ? tails[0] : tails[1];
-            const uint64_t tb = (tw >> (q0 & 63)) & (GPW == kWave ? ~0ull : ((1ull << (GPW & 63)) - 1ull));
+            const uint64_t tb = (batch_tails >> (u * GPW)) & (GPW == kWave ? ~0ull : ((1ull << (GPW & 63)) - 1ull));
             if (tb == 0) {
 #pragma unroll
-                for (int c = 0; c < 4; ++c) acc[c] += (double)v[u][c];
+                for (int c = 0; c < 4; ++c) acc[c] += (double)vv[u][c];
             } else {
 #pragma unroll
                 for (int g = 0; g < GPW; ++g) {
                     if (grp == g) {
 #pragma unroll
-                        for (int c = 0; c < 4; ++c) acc[c] += (double)v[u][c];
+                        for (int c = 0; c < 4; ++c) acc[c] += (double)vv[u][c];
                     }
                     if ((tb >> g) & 1ull) flush();
                 }
             }
         }
+    };
+
+    add_batch(v, 0);
+    for (int k = 1; k < NB; ++k) {
+        if (k * BP >= span) break;                            // wave-uniform: ragged last chunk
+        load_batch(v, k);
+        add_batch(v, k);
     }
+
     // positions after the last segment end of the chunk (the chunk's last position is not a tail)
-    const int last_bit = b - 1 - a;
-    const bool has_rest = ((((last_bit < kWave) ? tails[0] : tails[1]) >> (last_bit & 63)) & 1ull) == 0;
+    const bool has_rest = ((tails >> (span - 1)) & 1ull) == 0;
     if (has_rest) {
         double t[4];
 #pragma unroll
@@ -174,48 +225,63 @@ __global__ __launch_bounds__(kReduceWavesPerBlock *kWave) void reduce_chunk_kern
     }
 }
 
-// One group of LPR lanes per chunk: if a cut segment STARTS in this chunk, add its partial rows in
-// chunk order and write the reduced row.
+// One workgroup per chunk: if a cut segment STARTS in this chunk, its partial rows (one per later
+// chunk it covers) are added by the groups of the workgroup in a strided, fixed order, combined
+// through LDS in group order, and the reduced row is written.  Hot rows cover hundreds of chunks.
 template <int LPR>
-__global__ __launch_bounds__(256) void reduce_fix_kernel(int n_chunks, int gvec, const int32_t *__restrict__ seg_offsets,
+__global__ __launch_bounds__(kFixThreads) void reduce_fix_kernel(int n_chunks, int gvec,
+                                                         const int32_t *__restrict__ seg_offsets,
                                                          const double *__restrict__ part_head,
                                                          const double *__restrict__ part_last,
                                                          const int32_t *__restrict__ chunk_desc,
                                                          f32x4 *__restrict__ reduced) {
-    constexpr int GPW = kWave / LPR;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int grp = lane / LPR;
-    const int lig = lane % LPR;
-    const int chunk = (blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave) * GPW + grp;
-    if (chunk >= n_chunks || lig >= gvec) return;
+    constexpr int GROUPS = kFixThreads / LPR;
+    __shared__ double red[kFixThreads * 4];
+    const int grp = threadIdx.x / LPR;
+    const int lig = threadIdx.x % LPR;
+    const int chunk = blockIdx.x;
     const int dim = gvec * 4;
     const int32_t *d = chunk_desc + (int64_t)chunk * kDescInts;
     const int s0 = d[0], nflush = d[1], head_complete = d[2], has_rest = d[3];
-    if (!has_rest) return;
+    if (!has_rest) return;                                   // whole workgroup
     if (nflush == 0 && !head_complete) return;               // interior of a segment that started earlier
     const int seg = s0 + nflush;
-    const double *x = (nflush == 0 ? part_head : part_last) + (int64_t)chunk * dim + lig * 4;
-    double t[4] = {x[0], x[1], x[2], x[3]};
     const int c_last = (seg_offsets[seg + 1] - 1) / kReduceChunk;
-    // partial rows are fetched eight at a time (independent loads) and added in chunk order
-    for (int c = chunk + 1; c <= c_last; c += 8) {
+    const bool col_ok = lig < gvec;
+    double t[4] = {0.0, 0.0, 0.0, 0.0};
+    if (grp == 0 && col_ok) {
+        const double *x = (nflush == 0 ? part_head : part_last) + (int64_t)chunk * dim + lig * 4;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) t[i] = x[i];
+    }
+    // partial rows are fetched eight at a time (independent loads) and added in a fixed order
+    for (int c = chunk + 1 + grp; c <= c_last; c += 8 * GROUPS) {
         double h[8][4];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const int cj = (c + j <= c_last) ? c + j : c_last;
-            const double *src = part_head + (int64_t)cj * dim + lig * 4;
+            const int cj = c + j * GROUPS;
+            const bool ok = col_ok && cj <= c_last;
+            const double *src = part_head + (int64_t)(ok ? cj : chunk) * dim + lig * 4;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) h[j][i] = src[i];
+            for (int i = 0; i < 4; ++i) h[j][i] = ok ? src[i] : 0.0;
         }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            if (c + j <= c_last) {
+        for (int j = 0; j < 8; ++j)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) t[i] += h[j][i];
-            }
+            for (int i = 0; i < 4; ++i) t[i] += h[j][i];
+    }
+    if (GROUPS > 1) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) red[(grp * LPR + lig) * 4 + i] = t[i];
+        __syncthreads();
+        if (grp == 0) {
+            for (int g = 1; g < GROUPS; ++g)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) t[i] += red[(g * LPR + lig) * 4 + i];
         }
     }
-    reduced[(int64_t)seg * gvec + lig] = f32x4{(float)t[0], (float)t[1], (float)t[2], (float)t[3]};
+    if (grp == 0 && col_ok)
+        reduced[(int64_t)seg * gvec + lig] = f32x4{(float)t[0], (float)t[1], (float)t[2], (float)t[3]};
 }
 
 template <int LPR>
@@ -223,17 +289,23 @@ static void reduce_launch(fs_ctx *ctx, const float *grads, int n, int gvec, cons
                           const int32_t *seg_offsets, const int64_t *n_unique_dev, float *reduced, hipStream_t s,
                           hipEvent_t *timing) {
     constexpr int GPW = kWave / LPR;
-    constexpr int UNR = (kReduceChunk / GPW) < 8 ? (kReduceChunk / GPW) : 8;
+    // row-group loads one wavefront issues per round (build-time tuning knob)
+    constexpr int UNR = (kReduceChunk / GPW) < FS_REDUCE_UNR ? (kReduceChunk / GPW) : FS_REDUCE_UNR;
     const int n_chunks = (int)ceil_div(n, kReduceChunk);
     const int blocks = (int)ceil_div(n_chunks, kReduceWavesPerBlock);
+    const int32_t *inverse = ctx->reduce_inverse;            // optional accelerator, set by the caller
     if (timing) (void)hipEventRecord(timing[0], s);
-    hipLaunchKernelGGL((reduce_chunk_kernel<LPR, UNR>), dim3(blocks), dim3(kReduceWavesPerBlock * kWave), 0, s,
-                       (const f32x4 *)grads, n, gvec, perm, seg_offsets, n_unique_dev, (f32x4 *)reduced,
-                       ctx->part_head, ctx->part_last, ctx->chunk_desc);
+    if (inverse)
+        hipLaunchKernelGGL((reduce_chunk_kernel<LPR, UNR, true>), dim3(blocks), dim3(kReduceWavesPerBlock * kWave), 0,
+                           s, (const f32x4 *)grads, n, gvec, perm, seg_offsets, inverse, n_unique_dev,
+                           (f32x4 *)reduced, ctx->part_head, ctx->part_last, ctx->chunk_desc);
+    else
+        hipLaunchKernelGGL((reduce_chunk_kernel<LPR, UNR, false>), dim3(blocks), dim3(kReduceWavesPerBlock * kWave),
+                           0, s, (const f32x4 *)grads, n, gvec, perm, seg_offsets, inverse, n_unique_dev,
+                           (f32x4 *)reduced, ctx->part_head, ctx->part_last, ctx->chunk_desc);
     if (timing) (void)hipEventRecord(timing[1], s);
-    const int chunks_per_block = 4 * GPW;
-    hipLaunchKernelGGL((reduce_fix_kernel<LPR>), dim3((unsigned)ceil_div(n_chunks, chunks_per_block)), dim3(256), 0, s,
-                       n_chunks, gvec, seg_offsets, (const double *)ctx->part_head, (const double *)ctx->part_last,
+    hipLaunchKernelGGL((reduce_fix_kernel<LPR>), dim3((unsigned)n_chunks), dim3(kFixThreads), 0, s, n_chunks, gvec,
+                       seg_offsets, (const double *)ctx->part_head, (const double *)ctx->part_last,
                        (const int32_t *)ctx->chunk_desc, (f32x4 *)reduced);
 }
 

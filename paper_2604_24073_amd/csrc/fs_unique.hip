@@ -3,15 +3,17 @@
 // permutation and the inverse map.  (Collisions are defined on rows, Section 2.3 of the paper;
 // compute_collision of Algorithm 2 consumes the distinct lists.)
 //
-// Only ceil(log2(num_rows)) key bits are sorted, 8 per pass; keys travel as 32-bit words when
-// they fit.  Each pass is three launches: per-tile digit histogram (LDS counters), one-workgroup
-// exclusive scan of the [tile][digit] table, and a scatter that ranks keys with wavefront
-// ballots so equal digits keep their order.
+// Only ceil(log2(num_rows)) key bits are sorted, in the fewest passes of at most 9 bits; keys
+// travel as 32-bit words when they fit.  The inputs are small (a few hundred thousand keys), so
+// the passes are latency bound: tiles are large (4096 keys, 1024 threads) to keep the
+// [tile][digit] table small enough that every scatter workgroup scans it by itself - a pass is
+// two launches (histogram, scan+rank+scatter) and no workgroup ever waits for another.  Ranking
+// uses wavefront ballots, so equal digits keep their order.
 #include "fs_common.h"
 
 namespace fs {
 
-// ---- small block-scan helper (256 threads) ---------------------------------------------------
+// ---- small block-scan helper (kScanThreads threads) -----------------------------------------
 __device__ __forceinline__ int wave_inclusive_scan(int v) {
     const int lane = threadIdx.x & (kWave - 1);
 #pragma unroll
@@ -22,8 +24,8 @@ __device__ __forceinline__ int wave_inclusive_scan(int v) {
     return v;
 }
 
-// exclusive scan of one int per thread over a 256-thread block; total returned to all threads.
-// `sh` must hold kScanThreads/kWave + 1 ints.  Contains two barriers.
+// exclusive scan of one int per thread over a kScanThreads block; total returned to all threads.
+// `sh` must hold kScanThreads/kWave ints.  Contains two barriers.
 __device__ __forceinline__ int block_exclusive_scan(int v, int *sh, int &total) {
     const int lane = threadIdx.x & (kWave - 1);
     const int w = threadIdx.x / kWave;
@@ -42,14 +44,16 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int *sh, int &total) 
     return base + inc - v;
 }
 
-// ---- radix pass 1/3: per-tile digit histogram ---------------------------------------------------
+// ---- radix pass 1/2: per-tile digit histogram ---------------------------------------------------
 template <typename K, bool FIRST>
 __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(const int64_t *__restrict__ ids,
                                                                   const K *__restrict__ keys_in, int n, int shift,
-                                                                  int64_t num_rows, uint32_t *__restrict__ tile_hist,
+                                                                  int bits, int64_t num_rows,
+                                                                  uint32_t *__restrict__ tile_hist,
                                                                   int *__restrict__ flags) {
     __shared__ uint32_t hist[kRadix];
-    hist[threadIdx.x] = 0;
+    const int bins = 1 << bits;
+    if ((int)threadIdx.x < bins) hist[threadIdx.x] = 0;
     __syncthreads();
     const int base = blockIdx.x * kSortTile;
     bool bad = false;
@@ -65,52 +69,15 @@ __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(const int64_t 
             } else {
                 key = keys_in[e];
             }
-            atomicAdd(&hist[(uint32_t)(key >> shift) & (kRadix - 1)], 1u);
+            atomicAdd(&hist[(uint32_t)(key >> shift) & (bins - 1)], 1u);
         }
     }
     __syncthreads();
-    tile_hist[blockIdx.x * kRadix + threadIdx.x] = hist[threadIdx.x];
+    if ((int)threadIdx.x < bins) tile_hist[blockIdx.x * bins + threadIdx.x] = hist[threadIdx.x];
     if (bad) atomicOr(flags, kFlagRowRange);
 }
 
-// ---- radix pass 2/3: exclusive scan of the [tile][digit] table (digit-major order) ------------
-// One workgroup of 1024 threads: thread (q, d) owns a quarter of the tiles of digit d.
-__global__ __launch_bounds__(1024) void radix_scan_kernel(uint32_t *__restrict__ tile_hist, int tiles) {
-    __shared__ uint32_t part[4][kRadix];
-    __shared__ uint32_t dscan[kRadix];
-    const int d = threadIdx.x & (kRadix - 1);
-    const int q = threadIdx.x >> kRadixBits;
-    const int per = (tiles + 3) / 4;
-    const int t0 = q * per;
-    const int t1 = (t0 + per < tiles) ? t0 + per : tiles;
-    uint32_t sum = 0;
-    for (int t = t0; t < t1; ++t) sum += tile_hist[t * kRadix + d];
-    part[q][d] = sum;
-    __syncthreads();
-    if (q == 0) dscan[d] = part[0][d] + part[1][d] + part[2][d] + part[3][d];
-    __syncthreads();
-    // exclusive scan over the 256 digit totals (Hillis-Steele in LDS, first 256 threads)
-    uint32_t incl = 0;
-    for (int off = 1; off < kRadix; off <<= 1) {
-        uint32_t add = 0;
-        if (q == 0) {
-            incl = dscan[d];
-            if (d >= off) add = dscan[d - off];
-        }
-        __syncthreads();
-        if (q == 0) dscan[d] = incl + add;
-        __syncthreads();
-    }
-    uint32_t run = dscan[d] - (part[0][d] + part[1][d] + part[2][d] + part[3][d]);   // exclusive digit base
-    for (int i = 0; i < q; ++i) run += part[i][d];
-    for (int t = t0; t < t1; ++t) {
-        const uint32_t v = tile_hist[t * kRadix + d];
-        tile_hist[t * kRadix + d] = run;
-        run += v;
-    }
-}
-
-// ---- radix pass 3/3: stable scatter ---------------------------------------------------------------
+// ---- radix pass 2/2: scan of the [tile][digit] table, stable ranking, scatter ---------------------
 // Tile order is (wave, round, lane): wave w owns 64*KPT consecutive keys, read 64 at a time.
 template <typename K, bool FIRST>
 __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(const int64_t *__restrict__ ids,
@@ -118,35 +85,92 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(const int64
                                                                      const int32_t *__restrict__ idx_in,
                                                                      K *__restrict__ keys_out,
                                                                      int32_t *__restrict__ idx_out, int n, int shift,
-                                                                     const uint32_t *__restrict__ tile_offsets) {
-    __shared__ uint32_t cnt[kSortWaves][kRadix];
+                                                                     int bits, int tiles,
+                                                                     const uint32_t *__restrict__ tile_hist) {
+    __shared__ uint32_t cnt[kSortWaves][kRadix];       // per-wave digit counters, then wave bases
+    __shared__ uint32_t sh_below[kSortThreads];
+    __shared__ uint32_t sh_total[kSortThreads];
     __shared__ uint32_t gbase[kRadix];
+    const int bins = 1 << bits;
     const int lane = threadIdx.x & (kWave - 1);
     const int w = threadIdx.x / kWave;
+    const int tile = blockIdx.x;
+
+    // keys first: their latency overlaps the table scan
+    const int base = tile * kSortTile + w * (kWave * kSortKpt);
+    K key[kSortKpt];
 #pragma unroll
-    for (int i = 0; i < kSortWaves; ++i) cnt[i][threadIdx.x] = 0;
-    gbase[threadIdx.x] = tile_offsets[blockIdx.x * kRadix + threadIdx.x];
+    for (int r = 0; r < kSortKpt; ++r) {
+        const int e = base + r * kWave + lane;
+        key[r] = 0;
+        if (e < n) key[r] = FIRST ? (K)ids[e] : keys_in[e];
+    }
+    for (int i = threadIdx.x; i < kSortWaves * kRadix; i += kSortThreads) (&cnt[0][0])[i] = 0;
+
+    // (1) every workgroup scans the table by itself: thread (q, d) adds the tiles t = q, q+groups, ...
+    {
+        const int groups = kSortThreads / bins;            // >= 2
+        const int d = threadIdx.x & (bins - 1);
+        const int q = threadIdx.x / bins;
+        uint32_t below = 0, total = 0;
+        for (int t = q; t < tiles; t += groups * 8) {       // eight independent loads in flight
+            uint32_t v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int tt = t + j * groups;
+                v[j] = (tt < tiles) ? tile_hist[tt * bins + d] : 0u;
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                total += v[j];
+                below += (t + j * groups < tile) ? v[j] : 0u;
+            }
+        }
+        sh_below[threadIdx.x] = below;
+        sh_total[threadIdx.x] = total;
+        __syncthreads();
+        if (q == 0) {
+            for (int g = 1; g < groups; ++g) {
+                below += sh_below[g * bins + d];
+                total += sh_total[g * bins + d];
+            }
+            sh_below[d] = below;
+            sh_total[d] = total;
+        }
+        __syncthreads();
+        // exclusive scan of the digit totals by the first wave: each lane owns bins/64 consecutive digits
+        if (w == 0) {
+            const int per = (bins + kWave - 1) / kWave;    // <= 8
+            uint32_t loc[kRadix / kWave];
+            uint32_t s = 0;
+#pragma unroll
+            for (int i = 0; i < kRadix / kWave; ++i) {
+                const int dd = lane * per + i;
+                loc[i] = (i < per && dd < bins) ? sh_total[dd] : 0u;
+                s += loc[i];
+            }
+            const uint32_t incl = (uint32_t)wave_inclusive_scan((int)s);
+            uint32_t run = incl - s;
+#pragma unroll
+            for (int i = 0; i < kRadix / kWave; ++i) {
+                const int dd = lane * per + i;
+                if (i < per && dd < bins) gbase[dd] = run + sh_below[dd];
+                run += loc[i];
+            }
+        }
+    }
     __syncthreads();
 
-    const int base = blockIdx.x * kSortTile + w * (kWave * kSortKpt);
+    // (2) stable rank of every key among the keys of its wave with the same digit
     const uint64_t lt = (1ull << lane) - 1ull;
-    K key[kSortKpt];
     uint32_t rank[kSortKpt];
 #pragma unroll
     for (int r = 0; r < kSortKpt; ++r) {
         const int e = base + r * kWave + lane;
         const bool valid = e < n;
-        key[r] = 0;
-        if (valid) key[r] = FIRST ? (K)ids[e] : keys_in[e];
-    }
-#pragma unroll
-    for (int r = 0; r < kSortKpt; ++r) {
-        const int e = base + r * kWave + lane;
-        const bool valid = e < n;
-        const uint32_t digit = (uint32_t)(key[r] >> shift) & (kRadix - 1);
+        const uint32_t digit = (uint32_t)(key[r] >> shift) & (bins - 1);
         uint64_t peers = __ballot(valid);
-#pragma unroll
-        for (int b = 0; b < kRadixBits; ++b) {
+        for (int b = 0; b < bits; ++b) {
             const bool bit = (digit >> b) & 1u;
             const uint64_t bal = __ballot(bit);
             peers &= bit ? bal : ~bal;
@@ -157,8 +181,9 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(const int64
         rank[r] = old + before;
     }
     __syncthreads();
-    {   // exclusive prefix over the waves of this tile, per digit
-        uint32_t run = 0;
+    // (3) exclusive prefix over the waves of this tile, per digit
+    if ((int)threadIdx.x < bins) {
+        uint32_t run = gbase[threadIdx.x];
 #pragma unroll
         for (int i = 0; i < kSortWaves; ++i) {
             const uint32_t v = cnt[i][threadIdx.x];
@@ -171,8 +196,8 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(const int64
     for (int r = 0; r < kSortKpt; ++r) {
         const int e = base + r * kWave + lane;
         if (e < n) {
-            const uint32_t digit = (uint32_t)(key[r] >> shift) & (kRadix - 1);
-            const uint32_t pos = gbase[digit] + cnt[w][digit] + rank[r];
+            const uint32_t digit = (uint32_t)(key[r] >> shift) & (bins - 1);
+            const uint32_t pos = cnt[w][digit] + rank[r];
             keys_out[pos] = key[r];
             idx_out[pos] = FIRST ? e : idx_in[e];
         }
@@ -199,7 +224,7 @@ __device__ __forceinline__ int load_heads(const K *__restrict__ keys, int n, int
 template <typename K>
 __global__ __launch_bounds__(kScanThreads) void unique_count_kernel(const K *__restrict__ keys, int n,
                                                                     int32_t *__restrict__ tile_heads) {
-    __shared__ int sh[kScanThreads / kWave + 1];
+    __shared__ int sh[kScanThreads / kWave];
     K k[kScanIpt];
     bool head[kScanIpt];
     const int c = load_heads<K>(keys, n, blockIdx.x * kScanTile + threadIdx.x * kScanIpt, k, head);
@@ -217,7 +242,11 @@ __global__ __launch_bounds__(kScanThreads) void unique_compact_kernel(const K *_
                                                                       int32_t *__restrict__ seg_offsets,
                                                                       int32_t *__restrict__ inverse,
                                                                       int64_t *__restrict__ n_unique_dev) {
-    __shared__ int sh[kScanThreads / kWave + 1];
+    __shared__ int sh[kScanThreads / kWave];
+    const int p0 = blockIdx.x * kScanTile + threadIdx.x * kScanIpt;
+    int pm[kScanIpt];
+#pragma unroll
+    for (int i = 0; i < kScanIpt; ++i) pm[i] = (inverse != nullptr && p0 + i < n) ? perm[p0 + i] : 0;
     // heads in all earlier tiles: a cooperative sum (tiles is a few hundred)
     int before = 0;
     for (int t = threadIdx.x; t < (int)blockIdx.x; t += kScanThreads) before += tile_heads[t];
@@ -226,7 +255,6 @@ __global__ __launch_bounds__(kScanThreads) void unique_compact_kernel(const K *_
 
     K k[kScanIpt];
     bool head[kScanIpt];
-    const int p0 = blockIdx.x * kScanTile + threadIdx.x * kScanIpt;
     const int c = load_heads<K>(keys, n, p0, k, head);
     int tile_total;
     int rank = tile_base + block_exclusive_scan(c, sh, tile_total);    // heads strictly before p0
@@ -239,7 +267,7 @@ __global__ __launch_bounds__(kScanThreads) void unique_compact_kernel(const K *_
                 seg_offsets[rank] = p;
                 ++rank;
             }
-            if (inverse != nullptr) inverse[perm[p]] = rank - 1;
+            if (inverse != nullptr) inverse[pm[i]] = rank - 1;
         }
     }
     if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
@@ -260,27 +288,27 @@ static int unique_impl(fs_ctx *ctx, const int64_t *ids, int n, int key_bits, int
                        int32_t *seg_offsets, int32_t *perm, int32_t *inverse, int64_t *n_unique_dev, hipStream_t s) {
     const int tiles = (int)ceil_div(n, kSortTile);
     const int passes = (key_bits + kRadixBits - 1) / kRadixBits;
+    const int bits = (key_bits + passes - 1) / passes;            // <= kRadixBits, evenly spread
     K *kbuf[2] = {(K *)ctx->keys[0], (K *)ctx->keys[1]};
     int cur = 0;   // buffer holding the input of the next pass (unused for the first pass)
     for (int p = 0; p < passes; ++p) {
-        const int shift = p * kRadixBits;
+        const int shift = p * bits;
         const bool last = (p == passes - 1);
         K *kout = kbuf[cur ^ 1];
         int32_t *iout = last ? perm : ctx->idx[cur ^ 1];
         if (p == 0) {
             hipLaunchKernelGGL((radix_hist_kernel<K, true>), dim3(tiles), dim3(kSortThreads), 0, s, ids,
-                               (const K *)nullptr, n, shift, num_rows, ctx->tile_hist, ctx->d_flags);
-            hipLaunchKernelGGL(radix_scan_kernel, dim3(1), dim3(1024), 0, s, ctx->tile_hist, tiles);
+                               (const K *)nullptr, n, shift, bits, num_rows, ctx->tile_hist, ctx->d_flags);
             hipLaunchKernelGGL((radix_scatter_kernel<K, true>), dim3(tiles), dim3(kSortThreads), 0, s, ids,
-                               (const K *)nullptr, (const int32_t *)nullptr, kout, iout, n, shift, ctx->tile_hist);
+                               (const K *)nullptr, (const int32_t *)nullptr, kout, iout, n, shift, bits, tiles,
+                               (const uint32_t *)ctx->tile_hist);
         } else {
             hipLaunchKernelGGL((radix_hist_kernel<K, false>), dim3(tiles), dim3(kSortThreads), 0, s,
-                               (const int64_t *)nullptr, (const K *)kbuf[cur], n, shift, num_rows, ctx->tile_hist,
-                               ctx->d_flags);
-            hipLaunchKernelGGL(radix_scan_kernel, dim3(1), dim3(1024), 0, s, ctx->tile_hist, tiles);
+                               (const int64_t *)nullptr, (const K *)kbuf[cur], n, shift, bits, num_rows,
+                               ctx->tile_hist, ctx->d_flags);
             hipLaunchKernelGGL((radix_scatter_kernel<K, false>), dim3(tiles), dim3(kSortThreads), 0, s,
                                (const int64_t *)nullptr, (const K *)kbuf[cur], (const int32_t *)ctx->idx[cur], kout,
-                               iout, n, shift, ctx->tile_hist);
+                               iout, n, shift, bits, tiles, (const uint32_t *)ctx->tile_hist);
         }
         cur ^= 1;
     }

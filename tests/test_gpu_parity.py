@@ -172,10 +172,15 @@ def test_split_degenerate(ctx):
 def check_reduce(ctx, ids, grads, num_rows):
     lay = O.unique_ids(ids, num_rows)
     want = O.segment_reduce_grads(grads, lay["perm"], lay["seg_offsets"])
-    got = fs.fs_segment_reduce_grads(ctx, dev(grads), dev(lay["perm"]), dev(lay["seg_offsets"]),
-                                     dev(np.array([lay["n_unique"]], dtype=np.int64)))
+    d_grads, d_perm, d_seg = dev(grads), dev(lay["perm"]), dev(lay["seg_offsets"])
+    d_nu = dev(np.array([lay["n_unique"]], dtype=np.int64))
+    got = fs.fs_segment_reduce_grads(ctx, d_grads, d_perm, d_seg, d_nu)
     torch.cuda.synchronize()
     assert_close_f32(got[:lay["n_unique"]].cpu().numpy(), want, "reduced gradients")
+    # the optional inverse map only changes how a wavefront finds its segments, not a single bit
+    got_inv = fs.fs_segment_reduce_grads(ctx, d_grads, d_perm, d_seg, d_nu, inverse=dev(lay["inverse"]))
+    torch.cuda.synchronize()
+    assert torch.equal(got[:lay["n_unique"]], got_inv[:lay["n_unique"]])
     return got[:lay["n_unique"]]
 
 

@@ -1,0 +1,147 @@
+"""The software-pipelined form of the step (index half of the next iteration beside the gradient
+half of the current one) must give exactly the bits of the five calls issued one after another."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_24073_amd as fs
+from helpers import dev, table_to_dev, table_to_host
+from test_gpu_parity import compare_runs, rand_table, run_steps_gpu, run_steps_oracle, zipf_ids
+
+pytestmark = pytest.mark.gpu
+
+
+class It:
+    pass
+
+
+def make_its(rng, rows, dim, n_iter, users=40, max_len=300):
+    its = []
+    for _ in range(n_iter):
+        it = It()
+        lens = rng.integers(0, max_len, size=users)
+        it.offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+        it.values = zipf_ids(rng, int(it.offsets[-1]), rows, a=1.1)
+        it.grads = rng.standard_normal((len(it.values), dim)).astype(np.float32)
+        its.append(it)
+    return its
+
+
+def run_pipelined(ctx, table, state, its, lr, eps):
+    d_table, d_state = table_to_dev(table), dev(state)
+    num_rows, dim = table.shape
+    T = len(its)
+    d_vals = [dev(it.values) for it in its]
+    d_offs = [dev(it.offsets) for it in its]
+    d_grads = [dev(it.grads) for it in its]
+    n = [v.numel() for v in d_vals]
+    nmax = max(n)
+    layouts = [fs.alloc_layout(nmax, "cuda") for _ in range(3)]         # rotation of three
+    splits = [fs.alloc_split(nmax, nmax, "cuda") for _ in range(2)]     # rotation of two
+    reduced = [torch.empty((nmax, dim), dtype=torch.float32, device="cuda") for _ in range(2)]
+    embs = [torch.empty((nmax, dim), dtype=d_table.dtype, device="cuda") for _ in range(2)]
+
+    def args_for(t):
+        lay_t = dict(layouts[t % 3]); lay_t["n"] = n[t]
+        last = t == T - 1
+        return fs.make_step_args(d_table, d_state, lr, eps, lay_t, d_grads[t], None if last else d_vals[t + 1],
+                                 None if last else d_offs[t + 1], None if last else layouts[(t + 1) % 3],
+                                 splits[t % 2], reduced[t % 2], None if last else embs[t % 2])
+
+    fs.fs_unique_ids(ctx, d_vals[0], num_rows, out=layouts[0])
+    all_args = [args_for(t) for t in range(T)]
+    fs.fs_step_forward(ctx, all_args[0])                          # primes the pipeline: layout 1, split 0
+    outs = []
+    for t in range(T):
+        nxt = all_args[t + 1] if t + 1 < T else None
+        fs.fs_prioritized_step_pipelined(ctx, all_args[t], nxt)
+        assert fs.fs_check_async(ctx) == fs.FS_OK
+        u = int(layouts[t % 3]["n_unique"].item())
+        rec = {"reduced": reduced[t % 2][:u].cpu().numpy(), "counts": splits[t % 2]["counts"].cpu().numpy()}
+        if t + 1 < T:
+            rec["emb_next"] = table_to_host(embs[t % 2][:n[t + 1]])
+        outs.append(rec)
+    return d_table, d_state, outs
+
+
+@pytest.mark.parametrize("dtype,dim", [("f32", 128), ("bf16", 128), ("f32", 64)])
+def test_pipelined_steps_match_sequential_calls_bitwise(dtype, dim):
+    ctx = fs.Context(max_ids=20000, max_dim=256)
+    rng = np.random.default_rng(2024)
+    rows = 30000
+    table = rand_table(rng, rows, dim, dtype)
+    state = np.zeros(rows, np.float32)
+    its = make_its(rng, rows, dim, 7)
+    tp, sp_, op = run_pipelined(ctx, table, state, its, 0.01, 1e-8)
+    ts, ss, os_ = run_steps_gpu(ctx, table, state, its, 0.01, 1e-8, use_step_call=False)
+    view = torch.int16 if dtype == "bf16" else torch.int32
+    assert torch.equal(tp.view(view), ts.view(view))
+    assert torch.equal(sp_, ss)
+    for a, b in zip(op, os_[1:]):
+        assert a["reduced"].tobytes() == b["reduced"].tobytes()
+        assert a["counts"].tolist() == b["counts"].tolist()
+        if "emb_next" in a:
+            assert a["emb_next"].tobytes() == b["emb_next"].tobytes()
+    t_ref, s_ref, want = run_steps_oracle(table, state, its, 0.01, 1e-8)
+    compare_runs(os_, want, table_to_host(ts), ss.cpu().numpy(), t_ref, s_ref)
+    ctx.close()
+
+
+def _ping_pong(ctx, table, state, its, steps, use_graph):
+    """Two batches stepped back and forth (three layout buffers, two split buffers: period 6)."""
+    d_table, d_state = table_to_dev(table), dev(state)
+    num_rows, dim = table.shape
+    d_vals = [dev(it.values) for it in its]
+    d_offs = [dev(it.offsets) for it in its]
+    d_grads = [dev(it.grads) for it in its]
+    n = [v.numel() for v in d_vals]
+    nmax = max(n)
+    layouts = [fs.alloc_layout(nmax, "cuda") for _ in range(3)]
+    splits = [fs.alloc_split(nmax, nmax, "cuda") for _ in range(2)]
+    reduced = torch.empty((nmax, dim), dtype=torch.float32, device="cuda")
+    embs = [torch.empty((n[0], dim), dtype=d_table.dtype, device="cuda"),
+            torch.empty((n[1], dim), dtype=d_table.dtype, device="cuda")]
+
+    def args_for(s):
+        lay = dict(layouts[s % 3]); lay["n"] = n[s % 2]
+        nb = (s + 1) % 2
+        return fs.make_step_args(d_table, d_state, 0.01, 1e-8, lay, d_grads[s % 2], d_vals[nb], d_offs[nb],
+                                 layouts[(s + 1) % 3], splits[s % 2], reduced, embs[nb])
+
+    args = [args_for(s) for s in range(6)]
+    fs.fs_unique_ids(ctx, d_vals[0], num_rows, out=layouts[0])
+    fs.fs_step_forward(ctx, args[0])
+    graphs = [fs.fs_graph_capture_pipelined(ctx, args[s], args[(s + 1) % 6]) for s in range(6)] if use_graph else None
+    snaps = []
+    for s in range(steps):
+        if use_graph:
+            fs.fs_graph_launch(ctx, graphs[s % 6])
+        else:
+            fs.fs_prioritized_step_pipelined(ctx, args[s % 6], args[(s + 1) % 6])
+        # eager work and a synchronisation between replays
+        assert fs.fs_check_async(ctx) == fs.FS_OK
+        snaps.append((d_table.clone(), d_state.clone(), reduced.clone(), embs[(s + 1) % 2].clone(),
+                      splits[s % 2]["counts"].clone()))
+    if use_graph:
+        for g in graphs:
+            fs.fs_graph_destroy(ctx, g)
+    return snaps
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_graph_replays_match_eager_steps_bitwise(dtype):
+    ctx = fs.Context(max_ids=20000, max_dim=128)
+    rng = np.random.default_rng(31)
+    rows, dim = 25000, 128
+    table = rand_table(rng, rows, dim, dtype)
+    state = np.zeros(rows, np.float32)
+    its = make_its(rng, rows, dim, 2)
+    eager = _ping_pong(ctx, table, state, its, 13, use_graph=False)
+    graph = _ping_pong(ctx, table, state, its, 13, use_graph=True)
+    view = torch.int16 if dtype == "bf16" else torch.int32
+    for s, (e, g) in enumerate(zip(eager, graph)):
+        assert torch.equal(e[0].view(view), g[0].view(view)), f"table after replay {s}"
+        assert torch.equal(e[1], g[1]), f"state after replay {s}"
+        assert torch.equal(e[3].view(view), g[3].view(view)), f"gathered rows after replay {s}"
+        assert torch.equal(e[4], g[4]), f"split counts after replay {s}"
+    ctx.close()
