@@ -86,20 +86,20 @@ def main() -> int:
     d_offs = [torch.from_numpy(it.offsets).to(dev) for it in its]
     d_grads = [torch.from_numpy(it.grads).to(dev) for it in its]
 
-    # Buffers: layouts rotate over three buffers and splits over two, because the index half of
+    # Buffers: layouts and splits rotate over three buffers, reduced gradients over two: the index half of
     # step s+1 (writes layout s+2, split s+1) runs beside the gradient half of step s (reads
     # layout s, split s).  The two batches alternate, so the argument records repeat with period 6.
     nmax = max(n)
     layouts = [fs.alloc_layout(nmax, dev) for _ in range(3)]
-    splits = [fs.alloc_split(nmax, nmax, dev) for _ in range(2)]
-    reduced = torch.empty((nmax, dim), dtype=torch.float32, device=dev)
+    splits = [fs.alloc_split(nmax, nmax, dev) for _ in range(3)]
+    reduced = [torch.empty((nmax, dim), dtype=torch.float32, device=dev) for _ in range(2)]
     embs = [torch.empty((n[0], dim), dtype=tdtype, device=dev), torch.empty((n[1], dim), dtype=tdtype, device=dev)]
 
     def args_for(s):
         lay = dict(layouts[s % 3]); lay["n"] = n[s % 2]
         nb = (s + 1) % 2
         return fs.make_step_args(table, state, cfg.lr, cfg.eps, lay, d_grads[s % 2], d_vals[nb], d_offs[nb],
-                                 layouts[(s + 1) % 3], splits[s % 2], reduced, embs[nb])
+                                 layouts[(s + 1) % 3], splits[s % 3], reduced[s % 2], embs[nb])
 
     step_args = [args_for(s) for s in range(6)]
     fs.fs_unique_ids(ctx, d_vals[0], tab.num_rows, out=layouts[0])
@@ -144,7 +144,7 @@ def main() -> int:
         got_rows = table[torch.from_numpy(touched).to(dev)].float().cpu().numpy()
         ref_rows = t_ref if tab.dtype == "f32" else O.bf16_bits_to_f32(t_ref)
         ok = ok and np.allclose(got_rows, ref_rows, rtol=1e-5 if tab.dtype == "f32" else 8e-3, atol=1e-6)
-        ok = ok and np.allclose(reduced[:u[0]].cpu().numpy(), want["reduced"], rtol=1e-5, atol=1e-6)
+        ok = ok and np.allclose(reduced[0][:u[0]].cpu().numpy(), want["reduced"], rtol=1e-5, atol=1e-6)
         if not ok:
             print("bench.py: GPU step does not match the oracle", file=sys.stderr)
             return 4
@@ -164,6 +164,7 @@ def main() -> int:
     if graphs is None:
         fs.fs_ctx_set_kernel_timing(ctx, args.steps, args.time_every)
     torch.cuda.synchronize()
+    fs.fs_ctx_host_times(ctx, reset=True)
     t0 = time.perf_counter()
     run(k0, args.steps)
     t_enq = time.perf_counter() - t0
@@ -171,6 +172,11 @@ def main() -> int:
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     assert fs.fs_check_async(ctx) == fs.FS_OK, ctx.last_error()
+    ht = fs.fs_ctx_host_times(ctx)
+    host_phases = None
+    if ht[6] > 0:
+        names = ("wait_worker", "post", "reduce", "events", "updates_gather", "worker_enqueue")
+        host_phases = {k: ht[i] / ht[6] for i, k in enumerate(names)}
     if graphs is not None:
         # Per-kernel durations cannot be bracketed inside a replayed graph: the same kernels are
         # timed with event pairs over as many eager pipelined steps right after the timed region.
@@ -226,6 +232,7 @@ def main() -> int:
                                "2 consecutive iterations stepped back and forth",
                    "ids_per_iteration": n, "unique_rows": u, "collision_rows_first_step": counts0[0]},
         "schedule": args.mode, "host_enqueue_us_per_step": t_enq / args.steps * 1e6,
+        "host_phase_us_per_step": host_phases,
         "step_algorithmic_bytes": step_bytes, "step_algorithmic_GBps": step_gbps,
         "step_frac_of_hbm_peak": step_gbps / HBM_PEAK_GBPS,
         "kernel_avg_us": {k: (v * 1e3 if v is not None else None) for k, v in kernel_ms.items()},

@@ -233,6 +233,12 @@ int fs_ctx_set_kernel_timing(fs_ctx *ctx, int slots, int every);
  * again clears the ring. */
 int fs_ctx_get_kernel_timing(fs_ctx *ctx, int which, float *ms_out_host, int max_out, int *n_out_host);
 
+/* Host-side microseconds that fs_prioritized_step_pipelined has spent so far in: [0] waiting for
+ * the second host thread, [1] handing it the index half, [2] enqueueing the reduce, [3] event
+ * waits and records, [4] enqueueing updates and gather, [5] the second thread's own enqueueing,
+ * [6] number of calls.  Written to the HOST array out7_host; reset != 0 clears the counters. */
+int fs_ctx_host_times(fs_ctx *ctx, double *out7_host, int reset);
+
 /* ---- input generation and calibration helpers (not part of the method) ------------------- */
 
 /* Fills a table with the counter-based integer-hash rule of the synthetic workloads:

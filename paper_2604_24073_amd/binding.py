@@ -79,6 +79,7 @@ def load_library() -> ctypes.CDLL:
                                                       ctypes.POINTER(c_vp)]),
         "fs_ctx_set_threaded_enqueue": (ctypes.c_int, [c_vp, ctypes.c_int]),
         "fs_step_join": (ctypes.c_int, [c_vp, S]),
+        "fs_ctx_host_times": (ctypes.c_int, [c_vp, ctypes.POINTER(ctypes.c_double), ctypes.c_int]),
         "fs_graph_launch": (ctypes.c_int, [c_vp, c_vp, S]),
         "fs_graph_destroy": (ctypes.c_int, [c_vp]),
         "fs_ctx_set_kernel_timing": (ctypes.c_int, [c_vp, ctypes.c_int, ctypes.c_int]),
@@ -265,6 +266,12 @@ def fs_prioritized_step_pipelined(ctx: Context, cur: fs_step_args, nxt: Optional
     rc = ctx.lib.fs_prioritized_step_pipelined(ctx.handle, ctypes.byref(cur),
                                                ctypes.byref(nxt) if nxt is not None else None, _stream(stream))
     ctx.check(rc, "fs_prioritized_step_pipelined")
+
+
+def fs_ctx_host_times(ctx: Context, reset: bool = False):
+    buf = (ctypes.c_double * 7)()
+    ctx.check(ctx.lib.fs_ctx_host_times(ctx.handle, buf, 1 if reset else 0), "fs_ctx_host_times")
+    return [buf[i] for i in range(7)]
 
 
 def fs_step_join(ctx: Context, stream=None) -> None:

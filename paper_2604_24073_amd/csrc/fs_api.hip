@@ -1,6 +1,8 @@
 // C-ABI entry points: argument validation, context/workspace management and the two-stream
 // schedule of one prioritized iteration (Section 3.2 / Algorithm 2 of the paper, collectives
 // removed).  No kernel lives here.
+#include <atomic>
+#include <chrono>
 #include <condition_variable>
 #include <mutex>
 #include <new>
@@ -52,8 +54,12 @@ void carve(fs_ctx *c, char *base, size_t *total) {
 
 hipStream_t as_stream(fs_stream s) { return reinterpret_cast<hipStream_t>(s); }
 
+double now_us() {
+    return std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
 void worker_stop(fs_ctx *ctx);
-int join_index_work(fs_ctx *ctx, hipStream_t s);
+int join_pending_work(fs_ctx *ctx, hipStream_t s);
 
 #define FS_REQUIRE(ctx, cond, msg)                          \
     do {                                                    \
@@ -98,7 +104,8 @@ int fs_ctx_create(fs_ctx **out, int device, int64_t max_ids, int32_t max_dim) {
     ok = ok && hipStreamCreateWithFlags(&c->stream_a, hipStreamNonBlocking) == hipSuccess;
     ok = ok && hipStreamCreateWithFlags(&c->stream_b, hipStreamNonBlocking) == hipSuccess;
     ok = ok && hipStreamCreateWithFlags(&c->stream_cap, hipStreamNonBlocking) == hipSuccess;
-    hipEvent_t *evs[] = {&c->ev_fork, &c->ev_split, &c->ev_reduce, &c->ev_co, &c->ev_ex, &c->ev_idx[0], &c->ev_idx[1]};
+    hipEvent_t *evs[] = {&c->ev_fork, &c->ev_split, &c->ev_reduce, &c->ev_co, &c->ev_ex, &c->ev_idx[0], &c->ev_idx[1],
+                         &c->ev_red[0], &c->ev_red[1], &c->ev_side[0], &c->ev_side[1]};
     for (hipEvent_t *e : evs) ok = ok && hipEventCreateWithFlags(e, hipEventDisableTiming) == hipSuccess;
     if (!ok) {
         fs_ctx_destroy(c);
@@ -115,7 +122,8 @@ int fs_ctx_destroy(fs_ctx *c) {
     if (c->stream_a) { (void)hipStreamSynchronize(c->stream_a); (void)hipStreamDestroy(c->stream_a); }
     if (c->stream_b) { (void)hipStreamSynchronize(c->stream_b); (void)hipStreamDestroy(c->stream_b); }
     if (c->stream_cap) (void)hipStreamDestroy(c->stream_cap);
-    hipEvent_t evs[] = {c->ev_fork, c->ev_split, c->ev_reduce, c->ev_co, c->ev_ex, c->ev_idx[0], c->ev_idx[1]};
+    hipEvent_t evs[] = {c->ev_fork, c->ev_split, c->ev_reduce, c->ev_co, c->ev_ex, c->ev_idx[0], c->ev_idx[1],
+                        c->ev_red[0], c->ev_red[1], c->ev_side[0], c->ev_side[1]};
     for (hipEvent_t e : evs)
         if (e) (void)hipEventDestroy(e);
     (void)fs_ctx_set_kernel_timing(c, 0, 1);
@@ -130,7 +138,7 @@ size_t fs_ctx_workspace_bytes(const fs_ctx *ctx) { return ctx ? ctx->slab_bytes 
 
 int fs_check_async(fs_ctx *ctx, fs_stream stream) {
     if (!ctx) return FS_EINVAL;
-    const int jrc = join_index_work(ctx, as_stream(stream));
+    const int jrc = join_pending_work(ctx, as_stream(stream));
     if (jrc != FS_OK) return jrc;
     FS_HIP(ctx, hipStreamSynchronize(as_stream(stream)));
     FS_HIP(ctx, hipStreamSynchronize(ctx->stream_a));
@@ -211,7 +219,7 @@ int fs_unique_ids(fs_ctx *ctx, const int64_t *ids, int64_t n, int64_t num_rows, 
     if (n > ctx->max_ids) return set_err(ctx, FS_ENOMEM, "unique: n beyond the context capacity");
     FS_REQUIRE(ctx, seg_offsets && n_unique_dev, "unique: null pointer");
     if (n > 0) FS_REQUIRE(ctx, ids && unique && perm, "unique: null pointer");
-    const int jrc = join_index_work(ctx, as_stream(stream));      // the workspace may still be in use on A
+    const int jrc = join_pending_work(ctx, as_stream(stream));      // the workspace may still be in use on A
     if (jrc != FS_OK) return jrc;
     return launch_unique(ctx, ids, n, num_rows, unique, seg_offsets, perm, inverse, n_unique_dev, as_stream(stream));
 }
@@ -227,7 +235,7 @@ int fs_collision_split(fs_ctx *ctx, const int64_t *u_t, const int64_t *n_t_dev, 
     FS_REQUIRE(ctx, counts_dev, "split: null counts");
     if (cap_t > 0) FS_REQUIRE(ctx, u_t && n_t_dev && co && co_slot && ex && ex_slot, "split: null pointer (t side)");
     if (cap_t1 > 0) FS_REQUIRE(ctx, u_t1 && n_t1_dev && ex_next && ex_next_slot, "split: null pointer (t+1 side)");
-    const int jrc = join_index_work(ctx, as_stream(stream));      // the workspace may still be in use on A
+    const int jrc = join_pending_work(ctx, as_stream(stream));      // the workspace may still be in use on A
     if (jrc != FS_OK) return jrc;
     return launch_split(ctx, u_t, cap_t > 0 ? n_t_dev : nullptr, u_t1, cap_t1 > 0 ? n_t1_dev : nullptr, cap_t, cap_t1,
                         co, co_slot, ex, ex_slot, ex_next, ex_next_slot, counts_dev, as_stream(stream));
@@ -336,7 +344,10 @@ int enqueue_reduce(fs_ctx *ctx, const fs_step_args *a, hipStream_t sp) {
 
 // Backward of Algorithm 2 after the reduce: priority pass on `sp`, deferred pass on B (which
 // already waits for the reduce and the split), gather of the lookahead rows on `sp`, join of B.
-int enqueue_updates_and_gather(fs_ctx *ctx, const fs_step_args *a, bool have_t, bool have_t1, hipStream_t sp) {
+// ex_done == nullptr: B is joined into `sp` at the end; otherwise the deferred pass records it
+// and the caller decides who waits for it.
+int enqueue_updates_and_gather(fs_ctx *ctx, const fs_step_args *a, bool have_t, bool have_t1, hipStream_t sp,
+                               hipEvent_t ex_done = nullptr) {
     hipStream_t sb = ctx->stream_b;
     const fs_dtype fdt = (fs_dtype)a->dtype;
     int rc;
@@ -354,7 +365,7 @@ int enqueue_updates_and_gather(fs_ctx *ctx, const fs_step_args *a, bool have_t, 
         if (rc != FS_OK) return rc;
         if (tex) (void)hipEventRecord(tex[1], sb);
     }
-    FS_HIP(ctx, hipEventRecord(ctx->ev_ex, sb));
+    FS_HIP(ctx, hipEventRecord(ex_done ? ex_done : ctx->ev_ex, sb));
     if (have_t1) {
         // exclusive rows and lookahead rows are disjoint, so this may overlap the deferred pass
         const int row_bytes = a->dim * (a->dtype == FS_F32 ? 4 : 2);
@@ -365,8 +376,31 @@ int enqueue_updates_and_gather(fs_ctx *ctx, const fs_step_args *a, bool have_t, 
         if (rc != FS_OK) return rc;
         if (tg) (void)hipEventRecord(tg[1], sp);
     }
-    FS_HIP(ctx, hipStreamWaitEvent(sp, ctx->ev_ex, 0));
+    if (!ex_done) FS_HIP(ctx, hipStreamWaitEvent(sp, ctx->ev_ex, 0));
     if (ctx->timing_now) ++ctx->timing_steps;
+    return FS_OK;
+}
+
+// pipelined form: priority pass and gather on `sp` (the deferred pass goes to the side stream)
+int enqueue_priority_and_gather(fs_ctx *ctx, const fs_step_args *a, bool have_t, bool have_t1, hipStream_t sp) {
+    int rc;
+    if (have_t) {
+        hipEvent_t *tco = timing_pair(ctx, FS_TIME_UPDATE_CO);
+        if (tco) (void)hipEventRecord(tco[0], sp);
+        rc = launch_adagrad(ctx, a->table, (fs_dtype)a->dtype, a->state, a->num_rows, a->dim, a->co, a->co_slot,
+                            a->counts_dev + 0, a->n_t, a->reduced, a->lr, a->eps, sp);
+        if (rc != FS_OK) return rc;
+        if (tco) (void)hipEventRecord(tco[1], sp);
+    }
+    if (have_t1) {
+        const int row_bytes = a->dim * (a->dtype == FS_F32 ? 4 : 2);
+        hipEvent_t *tg = timing_pair(ctx, FS_TIME_GATHER);
+        if (tg) (void)hipEventRecord(tg[0], sp);
+        rc = launch_gather(ctx, a->table, a->num_rows, row_bytes, a->values_t1, a->offsets_t1, a->batch_t1, a->n_t1,
+                           a->emb_t1, sp);
+        if (rc != FS_OK) return rc;
+        if (tg) (void)hipEventRecord(tg[1], sp);
+    }
     return FS_OK;
 }
 
@@ -385,13 +419,41 @@ struct fs_worker {
     std::mutex mu;
     std::condition_variable cv;
     bool has_job = false, done = true, quit = false;
-    fs_step_args args;
-    bool have_t = false, have_t1 = false;
-    int parity = 0;               // which of the two index events the job records when it is enqueued
+    // the job: index half of `next` (if has_next), then the deferred pass of `cur` (if has_cur)
+    fs_step_args next, cur;
+    bool has_next = false, nxt_t = false, nxt_t1 = false, has_cur = false;
+    int parity = 0;               // event set of the call that posted the job
+    hipEvent_t first_after = nullptr;   // A waits for this before the job's first kernel (may be null)
+    std::atomic<bool> red_recorded{false};   // set by the posting thread once ev_red[parity] is recorded
+    hipEvent_t *ex_timing = nullptr;
     int rc = FS_OK;
 };
 
 namespace {
+
+// Side stream A, in this order: index half of the next iteration (needs nothing of the current
+// one), then - once the reduce of the current iteration is done - its deferred pass, then the
+// event that the next call waits for before its priority pass.
+int enqueue_side_stream(fs_ctx *ctx, const fs_step_args *next, bool nxt_t, bool nxt_t1, const fs_step_args *cur,
+                        int parity, hipEvent_t first_after, std::atomic<bool> *red_recorded, hipEvent_t *ex_timing) {
+    hipStream_t sa = ctx->stream_a;
+    int rc = FS_OK;
+    if (first_after) FS_HIP(ctx, hipStreamWaitEvent(sa, first_after, 0));
+    if (next) rc = enqueue_index_work(ctx, next, nxt_t, nxt_t1, sa);
+    if (rc != FS_OK) return rc;
+    if (cur) {
+        if (red_recorded)
+            while (!red_recorded->load(std::memory_order_acquire)) std::this_thread::yield();
+        FS_HIP(ctx, hipStreamWaitEvent(sa, ctx->ev_red[parity], 0));
+        if (ex_timing) (void)hipEventRecord(ex_timing[0], sa);
+        rc = launch_adagrad(ctx, cur->table, (fs_dtype)cur->dtype, cur->state, cur->num_rows, cur->dim, cur->ex,
+                            cur->ex_slot, cur->counts_dev + 1, cur->n_t, cur->reduced, cur->lr, cur->eps, sa);
+        if (rc != FS_OK) return rc;
+        if (ex_timing) (void)hipEventRecord(ex_timing[1], sa);
+    }
+    FS_HIP(ctx, hipEventRecord(ctx->ev_side[parity], sa));
+    return FS_OK;
+}
 
 void worker_main(fs_ctx *ctx) {
     fs_worker *w = ctx->worker;
@@ -402,10 +464,11 @@ void worker_main(fs_ctx *ctx) {
         if (w->quit) return;
         w->has_job = false;
         lk.unlock();
-        int rc = FS_OK;
-        if (hipStreamWaitEvent(ctx->stream_a, ctx->ev_fork, 0) != hipSuccess) rc = FS_EHIP;
-        if (rc == FS_OK) rc = enqueue_index_work(ctx, &w->args, w->have_t, w->have_t1, ctx->stream_a);
-        if (hipEventRecord(ctx->ev_idx[w->parity], ctx->stream_a) != hipSuccess && rc == FS_OK) rc = FS_EHIP;
+        const double j0 = now_us();
+        const int rc = enqueue_side_stream(ctx, w->has_next ? &w->next : nullptr, w->nxt_t, w->nxt_t1,
+                                           w->has_cur ? &w->cur : nullptr, w->parity, w->first_after,
+                                           &w->red_recorded, w->ex_timing);
+        ctx->host_us[5] += now_us() - j0;                    // the worker's enqueueing
         lk.lock();
         w->rc = rc;
         w->done = true;
@@ -413,8 +476,9 @@ void worker_main(fs_ctx *ctx) {
     }
 }
 
-// hands the index half to the worker (started on first use); false if no worker is available
-bool worker_post(fs_ctx *ctx, const fs_step_args *a, bool have_t, bool have_t1, int parity) {
+// hands the side-stream work of one call to the worker (started on first use); false if no worker
+bool worker_post(fs_ctx *ctx, const fs_step_args *next, bool nxt_t, bool nxt_t1, const fs_step_args *cur, int parity,
+                 hipEvent_t first_after, hipEvent_t *ex_timing) {
     if (!ctx->worker) {
         ctx->worker = new (std::nothrow) fs_worker();
         if (!ctx->worker) return false;
@@ -422,10 +486,16 @@ bool worker_post(fs_ctx *ctx, const fs_step_args *a, bool have_t, bool have_t1, 
     }
     fs_worker *w = ctx->worker;
     std::lock_guard<std::mutex> lk(w->mu);
-    w->args = *a;
-    w->have_t = have_t;
-    w->have_t1 = have_t1;
+    w->has_next = next != nullptr;
+    if (next) w->next = *next;
+    w->nxt_t = nxt_t;
+    w->nxt_t1 = nxt_t1;
+    w->has_cur = cur != nullptr;
+    if (cur) w->cur = *cur;
     w->parity = parity;
+    w->first_after = first_after;
+    w->ex_timing = ex_timing;
+    w->red_recorded.store(false, std::memory_order_relaxed);
     w->has_job = true;
     w->done = false;
     w->cv.notify_all();
@@ -453,12 +523,16 @@ void worker_stop(fs_ctx *ctx) {
     ctx->worker = nullptr;
 }
 
-// Makes `s` wait for the index half that an earlier pipelined call left running on stream A.
-int join_index_work(fs_ctx *ctx, hipStream_t s) {
-    if (!ctx->idx_pending) return FS_OK;
-    const int wrc = worker_wait(ctx);                        // its enqueueing (and event record) is complete
-    ctx->idx_pending = false;
-    FS_HIP(ctx, hipStreamWaitEvent(s, ctx->ev_idx[ctx->idx_parity], 0));
+// Makes `s` wait for what an earlier pipelined call left running on side stream A: the index half
+// of its `next` and the deferred pass of its `cur`.
+int join_pending_work(fs_ctx *ctx, hipStream_t s) {
+    int wrc = FS_OK;
+    if (ctx->side_pending) {
+        wrc = worker_wait(ctx);                              // its enqueueing (and event record) is complete
+        ctx->side_pending = false;
+        FS_HIP(ctx, hipStreamWaitEvent(s, ctx->ev_side[ctx->pipe_parity], 0));
+    }
+    ctx->red_valid = false;                                  // the next pipelined call forks from its stream
     return wrc;
 }
 
@@ -472,7 +546,7 @@ int fs_step_forward(fs_ctx *ctx, const fs_step_args *a, fs_stream stream) {
     int rc = check_step_args(ctx, a, &have_t, &have_t1);
     if (rc != FS_OK) return rc;
     hipStream_t sp = as_stream(stream), sa = ctx->stream_a;
-    rc = join_index_work(ctx, sp);
+    rc = join_pending_work(ctx, sp);
     if (rc != FS_OK) return rc;
     FS_HIP(ctx, hipEventRecord(ctx->ev_fork, sp));
     FS_HIP(ctx, hipStreamWaitEvent(sa, ctx->ev_fork, 0));
@@ -489,7 +563,7 @@ int fs_prioritized_step(fs_ctx *ctx, const fs_step_args *a, fs_stream stream) {
     int rc = check_step_args(ctx, a, &have_t, &have_t1);
     if (rc != FS_OK) return rc;
     hipStream_t sp = as_stream(stream), sa = ctx->stream_a, sb = ctx->stream_b;
-    rc = join_index_work(ctx, sp);
+    rc = join_pending_work(ctx, sp);
     if (rc != FS_OK) return rc;
     begin_step_timing(ctx);
     // fork: the side streams start after whatever the caller already queued on `stream`
@@ -522,47 +596,83 @@ int fs_prioritized_step_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs
         rc = check_step_args(ctx, next, &nxt_t, &nxt_t1);
         if (rc != FS_OK) return rc;
     }
-    hipStream_t sp = as_stream(stream), sa = ctx->stream_a, sb = ctx->stream_b;
+    hipStream_t sp = as_stream(stream);
     begin_step_timing(ctx);
-    // the previous call may have left its index half (the split of `cur`) running on A; its
-    // enqueueing is long finished, the GPU work is waited for only where it is needed (below)
-    const bool prev_pending = ctx->idx_pending;
-    const int prev_parity = ctx->idx_parity;
-    if (prev_pending) {
-        rc = worker_wait(ctx);
+    // Side stream A still runs what the previous call left there: the index half that produced the
+    // split of `cur`, then the previous deferred pass.  It is not waited for at the call boundary -
+    // the big kernels of consecutive iterations follow each other without a barrier packet - but
+    // once, right before the priority pass.  Cross-stream waits are the expensive host operation
+    // here (each makes the runtime flush the producer queue), so there are two per call: A waits
+    // for the reduce, `stream` waits for A.
+    const bool prev_side = ctx->side_pending;
+    const int pp = ctx->pipe_parity, p = pp ^ 1;            // event set of the previous / this call
+    const double h0 = now_us();
+    if (prev_side) {
+        rc = worker_wait(ctx);                               // host side only: its enqueueing is complete
         if (rc != FS_OK) return rc;
     }
-    FS_HIP(ctx, hipEventRecord(ctx->ev_fork, sp));
-    // index half of the NEXT iteration: beside everything this iteration does, enqueued by a
-    // second host thread (not while a graph is being captured: capture is per thread)
-    const int parity = prev_parity ^ 1;
-    const bool threaded = next && !ctx->capturing && ctx->use_worker && worker_post(ctx, next, nxt_t, nxt_t1, parity);
-    if (next && !threaded) FS_HIP(ctx, hipStreamWaitEvent(sa, ctx->ev_fork, 0));
+    const double h1 = now_us();
+    // The reduce overwrites cur->reduced: if the caller did not alternate that buffer, the
+    // previous deferred pass (which reads it) has to finish first.
+    bool joined_early = false;
+    if (prev_side && cur->reduced == ctx->prev_reduced) {
+        FS_HIP(ctx, hipStreamWaitEvent(sp, ctx->ev_side[pp], 0));
+        joined_early = true;
+    }
+    // Without a previous pipelined call the side stream forks from `stream`; otherwise its order
+    // after the previous deferred pass (which waited for the previous reduce) is all it needs.
+    hipEvent_t first_after = nullptr;
+    if (!ctx->red_valid) {
+        FS_HIP(ctx, hipEventRecord(ctx->ev_fork, sp));
+        first_after = ctx->ev_fork;
+    }
+    hipEvent_t *tex = have_t ? timing_pair(ctx, FS_TIME_UPDATE_EX) : nullptr;
+    const bool threaded = !ctx->capturing && ctx->use_worker &&
+                          worker_post(ctx, next, nxt_t, nxt_t1, have_t ? cur : nullptr, p, first_after, tex);
+    const double h2 = now_us();
     rc = FS_OK;
     if (have_t) rc = enqueue_reduce(ctx, cur, sp);
-    // the reduce needed only the layout; the split of `cur` is needed from here on
-    if (rc == FS_OK && prev_pending && hipStreamWaitEvent(sp, ctx->ev_idx[prev_parity], 0) != hipSuccess) rc = FS_EHIP;
-    ctx->idx_pending = false;
-    if (rc == FS_OK && hipEventRecord(ctx->ev_reduce, sp) != hipSuccess) rc = FS_EHIP;
-    if (rc == FS_OK && hipStreamWaitEvent(sb, ctx->ev_reduce, 0) != hipSuccess) rc = FS_EHIP;   // reduce + split
-    if (next && !threaded) {
-        if (rc == FS_OK) rc = enqueue_index_work(ctx, next, nxt_t, nxt_t1, sa);
-        if (rc == FS_OK && hipEventRecord(ctx->ev_idx[parity], sa) != hipSuccess) rc = FS_EHIP;
-    }
-    if (rc == FS_OK) rc = enqueue_updates_and_gather(ctx, cur, have_t, have_t1, sp);
-    if (next) {
-        ctx->idx_parity = parity;
-        ctx->idx_pending = true;
-        // a captured graph must end with every stream joined; otherwise A keeps running and the
-        // next call (or fs_step_join / fs_check_async) waits for it where its results are needed
-        if (ctx->capturing && rc == FS_OK) rc = join_index_work(ctx, sp);
-    }
+    if (rc == FS_OK && hipEventRecord(ctx->ev_red[p], sp) != hipSuccess) rc = FS_EHIP;
+    if (threaded) ctx->worker->red_recorded.store(true, std::memory_order_release);
+    ctx->red_valid = (rc == FS_OK) && !ctx->capturing;
+    const double h3 = now_us();
+    // from here on the split of `cur` is needed, and the rows the previous deferred pass wrote
+    // must be in place before the gather reads the table
+    if (rc == FS_OK && prev_side && !joined_early && hipStreamWaitEvent(sp, ctx->ev_side[pp], 0) != hipSuccess)
+        rc = FS_EHIP;
+    ctx->side_pending = false;
+    const double h4 = now_us();
+    if (rc == FS_OK) rc = enqueue_priority_and_gather(ctx, cur, have_t, have_t1, sp);
+    const double h5 = now_us();
+    if (!threaded && rc == FS_OK)
+        rc = enqueue_side_stream(ctx, next, nxt_t, nxt_t1, have_t ? cur : nullptr, p, first_after, nullptr, tex);
+    if (ctx->timing_now) ++ctx->timing_steps;
+    ctx->host_us[0] += h1 - h0;      // waiting for the worker
+    ctx->host_us[1] += h2 - h1;      // posting the side-stream work
+    ctx->host_us[2] += h3 - h2;      // enqueueing the reduce, recording its event
+    ctx->host_us[3] += h4 - h3;      // waiting for the side stream
+    ctx->host_us[4] += h5 - h4;      // priority pass and gather
+    ctx->host_us[6] += 1.0;
+    ctx->pipe_parity = p;
+    ctx->prev_reduced = cur->reduced;
+    ctx->side_pending = (rc == FS_OK);
+    // a captured graph must end with every stream joined
+    if (ctx->capturing && rc == FS_OK) rc = join_pending_work(ctx, sp);
     return rc;
 }
 
 int fs_step_join(fs_ctx *ctx, fs_stream stream) {
     if (!ctx) return FS_EINVAL;
-    return join_index_work(ctx, as_stream(stream));
+    return join_pending_work(ctx, as_stream(stream));
+}
+
+int fs_ctx_host_times(fs_ctx *ctx, double *out7_host, int reset) {
+    if (!ctx || !out7_host) return FS_EINVAL;
+    (void)worker_wait(ctx);
+    for (int i = 0; i < 7; ++i) out7_host[i] = ctx->host_us[i];
+    if (reset)
+        for (int i = 0; i < 7; ++i) ctx->host_us[i] = 0.0;
+    return FS_OK;
 }
 
 int fs_ctx_set_threaded_enqueue(fs_ctx *ctx, int on) {
@@ -578,11 +688,12 @@ int fs_graph_capture_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs_st
     if (!g) return FS_ENOMEM;
     g->graph = nullptr;
     g->exec = nullptr;
-    if (ctx->idx_pending) {                                  // nothing from outside may leak into the capture
+    if (ctx->side_pending) {                                 // nothing from outside may leak into the capture
         (void)worker_wait(ctx);
-        ctx->idx_pending = false;
+        ctx->side_pending = false;
         (void)hipStreamSynchronize(ctx->stream_a);
     }
+    ctx->red_valid = false;
     hipError_t e = hipStreamBeginCapture(ctx->stream_cap, hipStreamCaptureModeThreadLocal);
     if (e != hipSuccess) {
         delete g;

@@ -72,9 +72,14 @@ struct fs_ctx {
     hipStream_t stream_a;     // index work of the lookahead batch
     hipStream_t stream_b;     // deferred update pass
     hipEvent_t ev_fork, ev_split, ev_reduce, ev_co, ev_ex;
-    hipEvent_t ev_idx[2];     // completion of the index half left running by a pipelined call (alternating)
-    int idx_parity;           // which of the two the pending index half records
-    bool idx_pending;         // host-side: an index half is in flight on stream A and not yet joined
+    hipEvent_t ev_idx[2];     // (unused by the current schedule)
+    hipEvent_t ev_red[2];     // reduce of a pipelined call done on the caller's stream (alternating)
+    hipEvent_t ev_side[2];    // side-stream work of a pipelined call (index half of next, deferred pass of cur) done
+    int pipe_parity;          // event set used by the last pipelined call
+    bool side_pending;        // host-side: side-stream work is in flight and not yet joined
+    bool red_valid;           // host-side: ev_red[pipe_parity] was recorded by the last pipelined call
+    const float *prev_reduced;   // host-side: reduced-gradient buffer of the last pipelined call
+    double host_us[7];        // host-side time spent in the phases of the pipelined call (measurement aid)
 
     // optional per-kernel timing of the step: events[(kind * slots + slot) * 2 + {0,1}]
     struct fs_worker *worker; // second host thread that enqueues the index half (started on first use)

@@ -7,6 +7,13 @@
 // workgroup per user, so a 16K-item sequence costs the same per item as a short one.
 #include "fs_common.h"
 
+#ifndef FS_GATHER_UNR
+#define FS_GATHER_UNR 4
+#endif
+#ifndef FS_GATHER_MAX_BLOCKS
+#define FS_GATHER_MAX_BLOCKS 1024
+#endif
+
 namespace fs {
 
 template <int LPR, int UNR>
@@ -20,7 +27,7 @@ __global__ __launch_bounds__(256) void gather_kernel(const u32x4 *__restrict__ t
     const int grp = lane / LPR;
     const int lig = lane % LPR;
     const int64_t wave = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
-    const int64_t row0 = wave * ROWS_PER_WAVE;
+    const int64_t waves = (int64_t)gridDim.x * (blockDim.x / kWave);
 
     // offsets validation rides along (grid-stride over the batch; almost free)
     if (offsets != nullptr) {
@@ -31,29 +38,29 @@ __global__ __launch_bounds__(256) void gather_kernel(const u32x4 *__restrict__ t
         if (gtid == 0) bad |= (offsets[0] != 0) || (offsets[batch] != n);
         if (bad) atomicOr(flags, kFlagOffsets);
     }
-    if (row0 >= n) return;
-
-    int64_t id[UNR];
-    bool live[UNR];
-#pragma unroll
-    for (int u = 0; u < UNR; ++u) {
-        const int64_t j = row0 + u * GPW + grp;
-        live[u] = (j < n) && (lig < granules);
-        id[u] = live[u] ? values[j] : 0;
-    }
-    u32x4 v[UNR];
     bool oob = false;
+    for (int64_t row0 = wave * ROWS_PER_WAVE; row0 < n; row0 += waves * ROWS_PER_WAVE) {
+        int64_t id[UNR];
+        bool live[UNR];
 #pragma unroll
-    for (int u = 0; u < UNR; ++u) {
-        const bool in = (id[u] >= 0) && (id[u] < num_rows);
-        oob |= live[u] && !in;
-        v[u] = u32x4{0u, 0u, 0u, 0u};
-        if (live[u] && in) v[u] = table[id[u] * granules + lig];
-    }
+        for (int u = 0; u < UNR; ++u) {
+            const int64_t j = row0 + u * GPW + grp;
+            live[u] = (j < n) && (lig < granules);
+            id[u] = live[u] ? values[j] : 0;
+        }
+        u32x4 v[UNR];
 #pragma unroll
-    for (int u = 0; u < UNR; ++u) {
-        const int64_t j = row0 + u * GPW + grp;
-        if (live[u]) __builtin_nontemporal_store(v[u], &out[j * granules + lig]);
+        for (int u = 0; u < UNR; ++u) {
+            const bool in = (id[u] >= 0) && (id[u] < num_rows);
+            oob |= live[u] && !in;
+            v[u] = u32x4{0u, 0u, 0u, 0u};
+            if (live[u] && in) v[u] = table[id[u] * granules + lig];
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int64_t j = row0 + u * GPW + grp;
+            if (live[u]) __builtin_nontemporal_store(v[u], &out[j * granules + lig]);
+        }
     }
     if (oob) atomicOr(flags, kFlagRowRange);
 }
@@ -61,9 +68,12 @@ __global__ __launch_bounds__(256) void gather_kernel(const u32x4 *__restrict__ t
 template <int LPR>
 static void gather_launch(const void *table, int64_t num_rows, int granules, const int64_t *values,
                           const int64_t *offsets, int64_t batch, int64_t n, void *out, int *flags, hipStream_t s) {
-    constexpr int UNR = 4;
+    // In-flight volume is a tuning knob: enough wavefronts x rows to saturate HBM, not so many that
+    // the queueing delay they create slows the small latency-bound kernels running beside them.
+    constexpr int UNR = FS_GATHER_UNR;
     constexpr int ROWS_PER_BLOCK = (kWave / LPR) * UNR * 4;
-    const int64_t blocks = ceil_div(n, ROWS_PER_BLOCK);
+    int64_t blocks = ceil_div(n, ROWS_PER_BLOCK);
+    if (blocks > FS_GATHER_MAX_BLOCKS) blocks = FS_GATHER_MAX_BLOCKS;
     hipLaunchKernelGGL((gather_kernel<LPR, UNR>), dim3((unsigned)blocks), dim3(256), 0, s, (const u32x4 *)table,
                        num_rows, granules, values, offsets, batch, n, (u32x4 *)out, flags);
 }

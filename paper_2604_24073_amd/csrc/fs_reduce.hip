@@ -17,10 +17,11 @@
 namespace fs {
 
 #ifndef FS_REDUCE_UNR
-#define FS_REDUCE_UNR 8
+#define FS_REDUCE_UNR 4
 #endif
-constexpr int kFixThreads = 512;
-constexpr int kDescInts = 4;   // per chunk: first segment, number of flushes, head run complete, has tail run
+constexpr int kFixThreads = 1024;
+constexpr int kDescInts = 4;   // per chunk: first segment, number of flushes, last chunk of the cut segment that
+                               // starts here (-1: none), flags
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 // x + (x of the lane 32 away) in every lane: one cross-half swap per 32-bit word, no LDS traffic
@@ -217,51 +218,35 @@ __global__ __launch_bounds__(kReduceWavesPerBlock *kWave) void reduce_chunk_kern
         }
     }
     if (lane == 0) {
-        int32_t *d = chunk_desc + (int64_t)chunk * kDescInts;
-        d[0] = s0;
-        d[1] = nflush;
-        d[2] = head_complete ? 1 : 0;
-        d[3] = has_rest ? 1 : 0;
+        // the second launch wants everything about this chunk's cut in ONE load: where the cut
+        // segment (if one starts here) ends is looked up now, at the end of a wavefront's life
+        const bool starts_cut = has_rest && (nflush != 0 || head_complete);
+        const int c_last = starts_cut ? (seg_offsets[s0 + nflush + 1] - 1) / kReduceChunk : -1;
+        typedef int i32x4 __attribute__((ext_vector_type(4)));
+        *reinterpret_cast<i32x4 *>(chunk_desc + (int64_t)chunk * kDescInts) =
+            i32x4{s0, nflush, c_last, (head_complete ? 1 : 0) | (has_rest ? 2 : 0)};
     }
 }
 
-// One workgroup per chunk: if a cut segment STARTS in this chunk, its partial rows (one per later
-// chunk it covers) are added by the groups of the workgroup in a strided, fixed order, combined
-// through LDS in group order, and the reduced row is written.  Hot rows cover hundreds of chunks.
+// Second launch: every cut segment gets its partial rows added in a fixed order.  One wavefront
+// looks at one chunk; if a cut segment STARTS there, its partials are the chunk's own tail (or
+// whole-chunk) partial plus the head partial of every later chunk it covers.  Short spans are
+// finished by the wavefront itself (its 64/LPR groups fetch eight partial rows each per round);
+// the few long ones (hot rows cover hundreds of chunks) are listed in LDS and then added by all
+// groups of the workgroup together.  The order of the additions depends only on the layout.
+constexpr int kFixWaves = kFixThreads / kWave;
+constexpr int kFixLongSpan = 32;              // partial rows beyond which the whole workgroup helps
+
 template <int LPR>
-__global__ __launch_bounds__(kFixThreads) void reduce_fix_kernel(int n_chunks, int gvec,
-                                                         const int32_t *__restrict__ seg_offsets,
-                                                         const double *__restrict__ part_head,
-                                                         const double *__restrict__ part_last,
-                                                         const int32_t *__restrict__ chunk_desc,
-                                                         f32x4 *__restrict__ reduced) {
-    constexpr int GROUPS = kFixThreads / LPR;
-    __shared__ double red[kFixThreads * 4];
-    const int grp = threadIdx.x / LPR;
-    const int lig = threadIdx.x % LPR;
-    const int chunk = blockIdx.x;
-    const int dim = gvec * 4;
-    const int32_t *d = chunk_desc + (int64_t)chunk * kDescInts;
-    const int s0 = d[0], nflush = d[1], head_complete = d[2], has_rest = d[3];
-    if (!has_rest) return;                                   // whole workgroup
-    if (nflush == 0 && !head_complete) return;               // interior of a segment that started earlier
-    const int seg = s0 + nflush;
-    const int c_last = (seg_offsets[seg + 1] - 1) / kReduceChunk;
-    const bool col_ok = lig < gvec;
-    double t[4] = {0.0, 0.0, 0.0, 0.0};
-    if (grp == 0 && col_ok) {
-        const double *x = (nflush == 0 ? part_head : part_last) + (int64_t)chunk * dim + lig * 4;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) t[i] = x[i];
-    }
-    // partial rows are fetched eight at a time (independent loads) and added in a fixed order
-    for (int c = chunk + 1 + grp; c <= c_last; c += 8 * GROUPS) {
+__device__ __forceinline__ void add_partials(double (&t)[4], const double *__restrict__ part_head, int dim, int lig,
+                                             bool col_ok, int c_begin, int c_last, int stride, int fallback) {
+    for (int c = c_begin; c <= c_last; c += 8 * stride) {
         double h[8][4];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const int cj = c + j * GROUPS;
+            const int cj = c + j * stride;
             const bool ok = col_ok && cj <= c_last;
-            const double *src = part_head + (int64_t)(ok ? cj : chunk) * dim + lig * 4;
+            const double *src = part_head + (int64_t)(ok ? cj : fallback) * dim + lig * 4;
 #pragma unroll
             for (int i = 0; i < 4; ++i) h[j][i] = ok ? src[i] : 0.0;
         }
@@ -270,18 +255,84 @@ __global__ __launch_bounds__(kFixThreads) void reduce_fix_kernel(int n_chunks, i
 #pragma unroll
             for (int i = 0; i < 4; ++i) t[i] += h[j][i];
     }
-    if (GROUPS > 1) {
+}
+
+template <int LPR>
+__global__ __launch_bounds__(kFixThreads) void reduce_fix_kernel(int n_chunks, int gvec,
+                                                         const int32_t *__restrict__ seg_offsets,
+                                                         const double *__restrict__ part_head,
+                                                         const double *__restrict__ part_last,
+                                                         const int32_t *__restrict__ chunk_desc,
+                                                         f32x4 *__restrict__ reduced) {
+    constexpr int GPW = kWave / LPR;
+    constexpr int GROUPS = kFixThreads / LPR;
+    __shared__ double red[kFixThreads * 4];
+    __shared__ int long_list[kFixWaves][3];       // chunk, segment, last chunk
+    __shared__ int n_long;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = threadIdx.x / kWave;
+    const int grp = lane / LPR;
+    const int lig = lane % LPR;
+    const bool col_ok = lig < gvec;
+    const int dim = gvec * 4;
+    if (threadIdx.x == 0) n_long = 0;
+    __syncthreads();
+
+    const int chunk = blockIdx.x * kFixWaves + w;
+    if (chunk < n_chunks) {
+        typedef int i32x4 __attribute__((ext_vector_type(4)));
+        const i32x4 d = *reinterpret_cast<const i32x4 *>(chunk_desc + (int64_t)chunk * kDescInts);
+        const int s0 = d[0], nflush = d[1], c_last = d[2];
+        // c_last >= 0: a cut segment starts here (the chunk ends inside a run that began in it)
+        if (c_last >= 0) {
+            const int seg = s0 + nflush;
+            if (c_last - chunk > kFixLongSpan) {
+                if (lane == 0) {
+                    const int slot = atomicAdd(&n_long, 1);
+                    long_list[slot][0] = chunk;
+                    long_list[slot][1] = seg;
+                    long_list[slot][2] = c_last;
+                }
+            } else {
+                double t[4] = {0.0, 0.0, 0.0, 0.0};
+                if (grp == 0 && col_ok) {
+                    const double *x = (nflush == 0 ? part_head : part_last) + (int64_t)chunk * dim + lig * 4;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) red[(grp * LPR + lig) * 4 + i] = t[i];
+                    for (int i = 0; i < 4; ++i) t[i] = x[i];
+                }
+                add_partials<LPR>(t, part_head, dim, lig, col_ok, chunk + 1 + grp, c_last, GPW, chunk);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) t[i] = across_groups<LPR>(t[i]);
+                if (grp == 0 && col_ok)
+                    reduced[(int64_t)seg * gvec + lig] = f32x4{(float)t[0], (float)t[1], (float)t[2], (float)t[3]};
+            }
+        }
+    }
+    __syncthreads();
+    // long spans: all groups of the workgroup, one span after the other (slot order is irrelevant
+    // for the values: every span is summed in the same fixed group/stride order)
+    const int bg = threadIdx.x / LPR;             // group index inside the workgroup
+    for (int k = 0; k < n_long; ++k) {
+        const int ch = long_list[k][0], seg = long_list[k][1], c_last = long_list[k][2];
+        double t[4] = {0.0, 0.0, 0.0, 0.0};
+        if (bg == 0 && col_ok) {
+            const int32_t *d = chunk_desc + (int64_t)ch * kDescInts;
+            const double *x = (d[1] == 0 ? part_head : part_last) + (int64_t)ch * dim + lig * 4;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) t[i] = x[i];
+        }
+        add_partials<LPR>(t, part_head, dim, lig, col_ok, ch + 1 + bg, c_last, GROUPS, ch);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) red[(bg * LPR + lig) * 4 + i] = t[i];
         __syncthreads();
-        if (grp == 0) {
+        if (bg == 0 && col_ok) {
             for (int g = 1; g < GROUPS; ++g)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) t[i] += red[(g * LPR + lig) * 4 + i];
+            reduced[(int64_t)seg * gvec + lig] = f32x4{(float)t[0], (float)t[1], (float)t[2], (float)t[3]};
         }
+        __syncthreads();
     }
-    if (grp == 0 && col_ok)
-        reduced[(int64_t)seg * gvec + lig] = f32x4{(float)t[0], (float)t[1], (float)t[2], (float)t[3]};
 }
 
 template <int LPR>
@@ -304,7 +355,7 @@ static void reduce_launch(fs_ctx *ctx, const float *grads, int n, int gvec, cons
                            0, s, (const f32x4 *)grads, n, gvec, perm, seg_offsets, inverse, n_unique_dev,
                            (f32x4 *)reduced, ctx->part_head, ctx->part_last, ctx->chunk_desc);
     if (timing) (void)hipEventRecord(timing[1], s);
-    hipLaunchKernelGGL((reduce_fix_kernel<LPR>), dim3((unsigned)n_chunks), dim3(kFixThreads), 0, s, n_chunks, gvec,
+    hipLaunchKernelGGL((reduce_fix_kernel<LPR>), dim3((unsigned)ceil_div(n_chunks, kFixWaves)), dim3(kFixThreads), 0, s, n_chunks, gvec,
                        seg_offsets, (const double *)ctx->part_head, (const double *)ctx->part_last,
                        (const int32_t *)ctx->chunk_desc, (f32x4 *)reduced);
 }

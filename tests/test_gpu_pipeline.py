@@ -37,7 +37,7 @@ def run_pipelined(ctx, table, state, its, lr, eps):
     n = [v.numel() for v in d_vals]
     nmax = max(n)
     layouts = [fs.alloc_layout(nmax, "cuda") for _ in range(3)]         # rotation of three
-    splits = [fs.alloc_split(nmax, nmax, "cuda") for _ in range(2)]     # rotation of two
+    splits = [fs.alloc_split(nmax, nmax, "cuda") for _ in range(3)]     # rotation of three
     reduced = [torch.empty((nmax, dim), dtype=torch.float32, device="cuda") for _ in range(2)]
     embs = [torch.empty((nmax, dim), dtype=d_table.dtype, device="cuda") for _ in range(2)]
 
@@ -46,7 +46,7 @@ def run_pipelined(ctx, table, state, its, lr, eps):
         last = t == T - 1
         return fs.make_step_args(d_table, d_state, lr, eps, lay_t, d_grads[t], None if last else d_vals[t + 1],
                                  None if last else d_offs[t + 1], None if last else layouts[(t + 1) % 3],
-                                 splits[t % 2], reduced[t % 2], None if last else embs[t % 2])
+                                 splits[t % 3], reduced[t % 2], None if last else embs[t % 2])
 
     fs.fs_unique_ids(ctx, d_vals[0], num_rows, out=layouts[0])
     all_args = [args_for(t) for t in range(T)]
@@ -57,7 +57,7 @@ def run_pipelined(ctx, table, state, its, lr, eps):
         fs.fs_prioritized_step_pipelined(ctx, all_args[t], nxt)
         assert fs.fs_check_async(ctx) == fs.FS_OK
         u = int(layouts[t % 3]["n_unique"].item())
-        rec = {"reduced": reduced[t % 2][:u].cpu().numpy(), "counts": splits[t % 2]["counts"].cpu().numpy()}
+        rec = {"reduced": reduced[t % 2][:u].cpu().numpy(), "counts": splits[t % 3]["counts"].cpu().numpy()}
         if t + 1 < T:
             rec["emb_next"] = table_to_host(embs[t % 2][:n[t + 1]])
         outs.append(rec)
@@ -97,8 +97,8 @@ def _ping_pong(ctx, table, state, its, steps, use_graph):
     n = [v.numel() for v in d_vals]
     nmax = max(n)
     layouts = [fs.alloc_layout(nmax, "cuda") for _ in range(3)]
-    splits = [fs.alloc_split(nmax, nmax, "cuda") for _ in range(2)]
-    reduced = torch.empty((nmax, dim), dtype=torch.float32, device="cuda")
+    splits = [fs.alloc_split(nmax, nmax, "cuda") for _ in range(3)]
+    reduced = [torch.empty((nmax, dim), dtype=torch.float32, device="cuda") for _ in range(2)]
     embs = [torch.empty((n[0], dim), dtype=d_table.dtype, device="cuda"),
             torch.empty((n[1], dim), dtype=d_table.dtype, device="cuda")]
 
@@ -106,7 +106,7 @@ def _ping_pong(ctx, table, state, its, steps, use_graph):
         lay = dict(layouts[s % 3]); lay["n"] = n[s % 2]
         nb = (s + 1) % 2
         return fs.make_step_args(d_table, d_state, 0.01, 1e-8, lay, d_grads[s % 2], d_vals[nb], d_offs[nb],
-                                 layouts[(s + 1) % 3], splits[s % 2], reduced, embs[nb])
+                                 layouts[(s + 1) % 3], splits[s % 3], reduced[s % 2], embs[nb])
 
     args = [args_for(s) for s in range(6)]
     fs.fs_unique_ids(ctx, d_vals[0], num_rows, out=layouts[0])
@@ -120,8 +120,8 @@ def _ping_pong(ctx, table, state, its, steps, use_graph):
             fs.fs_prioritized_step_pipelined(ctx, args[s % 6], args[(s + 1) % 6])
         # eager work and a synchronisation between replays
         assert fs.fs_check_async(ctx) == fs.FS_OK
-        snaps.append((d_table.clone(), d_state.clone(), reduced.clone(), embs[(s + 1) % 2].clone(),
-                      splits[s % 2]["counts"].clone()))
+        snaps.append((d_table.clone(), d_state.clone(), reduced[s % 2].clone(), embs[(s + 1) % 2].clone(),
+                      splits[s % 3]["counts"].clone()))
     if use_graph:
         for g in graphs:
             fs.fs_graph_destroy(ctx, g)
