@@ -48,10 +48,10 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--time-every", type=int, default=8,
                     help="bracket the kernels of one timed step in this many with HIP event pairs")
-    ap.add_argument("--mode", choices=["graph", "pipelined", "sequential"], default="graph",
-                    help="graph: the pipelined step replayed as a HIP graph (default); pipelined: index half of "
-                         "step s+1 beside the gradient half of step s, eager launches; sequential: every step "
-                         "self-contained, eager launches")
+    ap.add_argument("--mode", choices=["pipelined", "graph", "sequential"], default="pipelined",
+                    help="pipelined (default): index half of step s+1 beside the gradient half of step s, "
+                         "eager launches; graph: the same step replayed as a HIP graph (measured slower: the "
+                         "replay serialises its cross-stream edges); sequential: every step self-contained")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one embedding-table shard, no collectives); "
