@@ -139,6 +139,40 @@ int fs_rowwise_adagrad_update(fs_ctx *ctx, void *table, fs_dtype dt, float *stat
                               const int64_t *n_rows_dev, int64_t cap, const float *reduced,
                               float lr, float eps, fs_stream stream);
 
+/* ---- the fused update path of the whole iteration ------------------------------------------ */
+
+/* Class order of the occurrences of batch t (input of fs_reduce_update_class): the occurrences
+ * of collision rows first (class 0), then those of exclusive rows (class 1); inside a class by
+ * ascending row, inside a row in batch order.  Does fs_collision_split (same arguments, same
+ * outputs) and then lays the batch out:
+ *   cperm [n_t]          occurrence (row of G_t) at each class position
+ *   cslot [n_t]          slot in u_t of the row at each class position
+ *   cstart[cap_t]        class position of the first occurrence of u_t[k]
+ *   class_pos_dev [2]    int32: number of class-0 positions, number of positions (n_t)
+ * seg_offsets_t, perm_t, inverse_t: the layout of batch t as written by fs_unique_ids (all three
+ * required); cap_t is also the capacity of cstart.  This is the prioritization of Section 3.2
+ * carried down to the gradient rows: the priority pass reads only what collision rows need. */
+int fs_collision_split_classes(fs_ctx *ctx, const int64_t *u_t, const int64_t *n_t_dev,
+                               const int64_t *u_t1, const int64_t *n_t1_dev, int64_t cap_t, int64_t cap_t1,
+                               const int32_t *seg_offsets_t, const int32_t *perm_t, const int32_t *inverse_t,
+                               int64_t n_t, int64_t *co, int32_t *co_slot, int64_t *ex, int32_t *ex_slot,
+                               int64_t *ex_next, int32_t *ex_next_slot, int64_t *counts_dev, int32_t *cperm,
+                               int32_t *cslot, int32_t *cstart, int32_t *class_pos_dev, fs_stream stream);
+
+/* update_embedding(I, G) of Algorithm 2 for one class of rows in one launch: the segment reduce
+ * of fs_segment_reduce_grads and the Adagrad update of fs_rowwise_adagrad_update fused, same
+ * arithmetic (fp64 sums in a fixed order, one rounding to fp32, then the update), restricted to
+ * the rows of class `cls` (0: collision rows = priority pass, 1: exclusive rows = deferred
+ * pass).  The summed gradients do not go through memory unless `reduced` (OPTIONAL, [n_unique,
+ * dim] fp32) is given, in which case the rows of this class are also written there.
+ * Launches of the two classes may run side by side on different streams; launches of the same
+ * class on one context must be ordered. */
+int fs_reduce_update_class(fs_ctx *ctx, int cls, void *table, fs_dtype dt, float *state, int64_t num_rows,
+                           int32_t dim, float lr, float eps, const float *grads, int64_t n,
+                           const int64_t *u_t, const int32_t *seg_offsets, const int32_t *cperm,
+                           const int32_t *cslot, const int32_t *cstart, const int32_t *class_pos_dev,
+                           float *reduced, fs_stream stream);
+
 /* ---- one whole iteration ------------------------------------------------------------------ */
 
 /* Arguments of fs_prioritized_step (plain pointers; `t` is the iteration whose gradients
@@ -147,70 +181,95 @@ typedef struct fs_step_args {
     void *table; float *state; int64_t num_rows; int32_t dim; int32_t dtype; /* fs_dtype */
     float lr, eps;
     /* iteration t: layout produced by the previous step (or by fs_unique_ids), gradients */
-    const int64_t *u_t; const int32_t *seg_offsets_t; const int32_t *perm_t; const int32_t *inverse_t /* may be NULL */;
+    const int64_t *u_t; const int32_t *seg_offsets_t; const int32_t *perm_t; const int32_t *inverse_t;
     const int64_t *n_unique_t_dev;
     const float *grads_t; int64_t n_t;
     /* lookahead batch t+1 (values_t1 == NULL: last iteration, every row is exclusive) */
     const int64_t *values_t1; const int64_t *offsets_t1; int64_t batch_t1; int64_t n_t1;
-    /* outputs: layout of t+1 */
+    /* outputs: layout of t+1 (already there if fs_unique_ids_ahead was called on these buffers) */
     int64_t *u_t1; int32_t *seg_offsets_t1; int32_t *perm_t1; int32_t *inverse_t1; int64_t *n_unique_t1_dev;
     /* outputs: the split of U_t */
     int64_t *co; int32_t *co_slot; int64_t *ex; int32_t *ex_slot; int64_t *ex_next; int32_t *ex_next_slot;
     int64_t *counts_dev;        /* [3] */
-    /* outputs: reduced gradients [n_t, dim] capacity, and gathered rows of t+1 [n_t1, dim] */
+    /* outputs: class order of batch t: [n_t], [n_t], [n_t], [2] (see fs_collision_split_classes) */
+    int32_t *cperm; int32_t *cslot; int32_t *cstart; int32_t *class_pos_dev;
+    /* outputs: reduced gradients [n_t, dim] capacity (OPTIONAL, may be NULL: the step does not need
+     * them in memory), and gathered rows of t+1 [n_t1, dim] */
     float *reduced; void *emb_t1;
 } fs_step_args;
 
 /* Iteration t on one shard, scheduled as Section 3.2 prescribes (strict write-read ordering
  * on collision rows only):
- *   side stream A : fs_unique_ids(values_t1) -> fs_collision_split(U_t, U_t1)
- *   `stream`      : fs_segment_reduce_grads(G_t); wait A; update(co)  [priority pass];
+ *   side stream A : fs_unique_ids(values_t1) -> fs_collision_split_classes(U_t, U_t1)
+ *   `stream`      : wait A; fs_reduce_update_class(0)  [priority pass: collision rows];
  *                   fs_gather_jagged(values_t1)
- *   side stream B : after the reduce and the split: update(ex)        [deferred pass],
+ *   side stream B : after A: fs_reduce_update_class(1) [deferred pass: exclusive rows],
  *                   overlapping the gather, which is race-free because ex and U_t1 are disjoint
  * and `stream` finally waits for B, so the step is complete when `stream` is.  Results are
- * identical to running the five calls one after another. */
+ * identical to running the five operations one after another. */
 int fs_prioritized_step(fs_ctx *ctx, const fs_step_args *args, fs_stream stream);
 
 /* The index half of an iteration alone - what Forward of Algorithm 2 does with the prefetched
  * indices of the next batch, long before the gradients arrive: on side stream A (forked from
- * `stream`, joined back into it) dedup values_t1 into the layout of t+1 and split U_t against
- * U_t1.  Uses only the index fields of `args` (no gradients, no table access). */
+ * `stream`, joined back into it) dedup values_t1 into the layout of t+1 (unless
+ * fs_unique_ids_ahead already did), split U_t against U_t1 and lay batch t out in class order.
+ * Uses only the index fields of `args` (no gradients, no table access). */
 int fs_step_forward(fs_ctx *ctx, const fs_step_args *args, fs_stream stream);
 
+/* Dedup of a prefetched batch ahead of time: fs_unique_ids on one of the context's two index
+ * streams (used in turn), ordered after the work queued on `stream` so far and after nothing
+ * else.  Indices arrive batches ahead of the gradients (Forward of Algorithm 2 consumes
+ * prefetched indices), and the dedup is a chain of small latency-bound launches: started early
+ * it hides behind the bandwidth-bound passes of earlier iterations.  The results are consumed by
+ * a step call whose u_t1 is this `unique` buffer (it waits for them instead of doing the dedup
+ * itself); anyone else must call fs_step_join or fs_check_async first.  The outputs must not be
+ * in use by work that is not ordered before `stream`'s current position; in a loop of pipelined
+ * calls that means five layout buffers in rotation when the dedup runs two batches ahead of the
+ * call that consumes it as u_t1.  At most four such dedups may be outstanding. */
+int fs_unique_ids_ahead(fs_ctx *ctx, const int64_t *ids, int64_t n, int64_t num_rows,
+                        int64_t *unique, int32_t *seg_offsets, int32_t *perm, int32_t *inverse,
+                        int64_t *n_unique_dev, fs_stream stream);
+
 /* Steady-state form of the iteration, software-pipelined by one batch exactly as Algorithm 2
- * interleaves its Forward and Backward: the gradient half of iteration `cur` (reduce, priority
- * pass, deferred pass on B, gather of cur's lookahead rows) runs on `stream`, while side stream
- * A does the index half of iteration `next` (dedup of next's lookahead IDs, split of next's
- * U_t), which needs nothing that `cur` writes.  The split of `cur` must already exist: it was
- * produced by the previous call of this function (as its `next`) or by fs_step_forward.
- * `next` may be NULL (last iteration).  Stream B is joined into `stream` before the call's work
- * on `stream` ends.  The index half of `next` is NOT: it keeps running on A and is waited for
- * exactly where its results are first needed - by the next pipelined call after its reduce, by
- * fs_step_join, by fs_check_async, or by any other call that reuses the index workspace.  Use
- * consecutive pipelined calls on ONE stream.  The caller keeps the buffers of `cur` and `next`
- * distinct (three layout buffers in rotation, two split buffers). */
+ * interleaves its Forward and Backward.  For iteration `cur`:
+ *   `stream`      : wait for the side work of the previous call; priority pass of cur
+ *                   (fs_reduce_update_class(0)); gather of cur's lookahead rows
+ *   side stream A : (after the work queued on `stream` before the call, i.e. cur's gradients)
+ *                   deferred pass of cur (fs_reduce_update_class(1)); then the index half of
+ *                   `next`: dedup of next's lookahead IDs (or a wait for fs_unique_ids_ahead),
+ *                   split of next's U_t, class order of next's batch
+ * The split and class order of `cur` must already exist: they were produced by the previous call
+ * of this function (as its `next`) or by fs_step_forward.  `next` may be NULL (last iteration).
+ * Nothing on A is waited for when the call returns: the next pipelined call waits for it before
+ * its priority pass (its gather may read rows the deferred pass writes), and so do fs_step_join,
+ * fs_check_async and every call that reuses the index workspace.  Use consecutive pipelined
+ * calls on ONE stream.  The buffers of consecutive calls must be distinct: three split/class
+ * buffers in rotation, and three layout buffers (five with fs_unique_ids_ahead two batches
+ * ahead). */
 int fs_prioritized_step_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs_step_args *next,
                                   fs_stream stream);
 
-/* Makes `stream` wait for the index half that the last pipelined call left running (no-op if
- * there is none): after it, work enqueued on `stream` sees that layout and split. */
+/* Makes `stream` wait for everything earlier calls left running on the context's own streams
+ * (side work of the last pipelined call, outstanding ahead-of-time dedups); no-op if there is
+ * none. */
 int fs_step_join(fs_ctx *ctx, fs_stream stream);
 
-/* fs_prioritized_step_pipelined hands the enqueueing of the index half to a second host thread
- * owned by the context (on by default; started on first use, joined by fs_ctx_destroy), because
- * the host cost of the launches would otherwise exceed the GPU time of an iteration.  on == 0
- * makes the calling thread enqueue everything.  The results do not depend on this setting. */
+/* The pipelined call and fs_unique_ids_ahead hand the enqueueing of their side-stream work to
+ * host threads owned by the context (on by default; started on first use, joined by
+ * fs_ctx_destroy), because the host cost of the launches and cross-stream waits would otherwise
+ * exceed the GPU time of an iteration.  on == 0 makes the calling thread enqueue everything.
+ * The results do not depend on this setting. */
 int fs_ctx_set_threaded_enqueue(fs_ctx *ctx, int on);
 
 /* ---- the pipelined iteration as a HIP graph ---------------------------------------------------- */
 
-/* One iteration enqueues about sixteen small and large kernels on three streams; replaying it as a
- * graph removes the host launch cost.  fs_graph_capture_pipelined records exactly the work of
- * fs_prioritized_step_pipelined(cur, next) (same kernels, same dependencies, pointers baked in:
- * the buffers must stay alive and in place) on an internal stream; nothing runs during capture.
- * fs_graph_launch replays it on `stream`.  A graph holds no memset node.  Replays of graphs that
- * share a context must be ordered on one stream. */
+/* fs_graph_capture_pipelined records exactly the work of fs_prioritized_step_pipelined(cur,
+ * next) (same kernels, same dependencies, pointers baked in: the buffers must stay alive and in
+ * place; the dedup of next's lookahead IDs is part of the graph) on an internal stream; nothing
+ * runs during capture.  fs_graph_launch replays it on `stream`.  A graph holds no memset node.
+ * Replays of graphs that share a context must be ordered on one stream.  On this hardware the
+ * replay of a multi-stream graph costs the host more than the eager calls do; the eager
+ * pipelined call is the faster way to drive the step. */
 typedef struct fs_graph fs_graph;
 int fs_graph_capture_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs_step_args *next, fs_graph **out);
 int fs_graph_launch(fs_ctx *ctx, fs_graph *graph, fs_stream stream);
@@ -221,8 +280,9 @@ int fs_graph_destroy(fs_graph *graph);
 enum { FS_TIME_REDUCE = 0, FS_TIME_GATHER = 1, FS_TIME_UPDATE_CO = 2, FS_TIME_UPDATE_EX = 3, FS_TIME_KINDS = 4 };
 
 /* slots > 0: one in `every` later steps (fs_prioritized_step, fs_prioritized_step_pipelined)
- * brackets its segment-reduce main kernel, its gather and its two update passes with HIP events
- * on the stream each is launched on (ring of `slots` sampled steps).  An event record costs the
+ * brackets its gather and its two fused reduce+update passes (FS_TIME_UPDATE_CO, FS_TIME_UPDATE_EX;
+ * FS_TIME_REDUCE is not produced by the fused path) with HIP events on the stream each is
+ * launched on (ring of `slots` sampled steps).  An event record costs the
  * host more than a kernel launch: sample sparsely when the steps themselves are being timed.
  * slots == 0 turns it off (the default) and frees the events. */
 int fs_ctx_set_kernel_timing(fs_ctx *ctx, int slots, int every);
@@ -234,9 +294,10 @@ int fs_ctx_set_kernel_timing(fs_ctx *ctx, int slots, int every);
 int fs_ctx_get_kernel_timing(fs_ctx *ctx, int which, float *ms_out_host, int max_out, int *n_out_host);
 
 /* Host-side microseconds that fs_prioritized_step_pipelined has spent so far in: [0] waiting for
- * the second host thread, [1] handing it the index half, [2] enqueueing the reduce, [3] event
- * waits and records, [4] enqueueing updates and gather, [5] the second thread's own enqueueing,
- * [6] number of calls.  Written to the HOST array out7_host; reset != 0 clears the counters. */
+ * the side-stream thread, [1] recording the fork event and handing over the side work, [2] the
+ * wait for the previous side work, [3] enqueueing priority pass and gather, [4] the index-stream
+ * thread's enqueueing (fs_unique_ids_ahead), [5] the side-stream thread's enqueueing, [6] number
+ * of calls.  Written to the HOST array out7_host; reset != 0 clears the counters. */
 int fs_ctx_host_times(fs_ctx *ctx, double *out7_host, int reset);
 
 /* ---- input generation and calibration helpers (not part of the method) ------------------- */

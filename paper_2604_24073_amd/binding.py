@@ -34,6 +34,7 @@ class fs_step_args(ctypes.Structure):
         ("u_t1", c_vp), ("seg_offsets_t1", c_vp), ("perm_t1", c_vp), ("inverse_t1", c_vp), ("n_unique_t1_dev", c_vp),
         ("co", c_vp), ("co_slot", c_vp), ("ex", c_vp), ("ex_slot", c_vp), ("ex_next", c_vp), ("ex_next_slot", c_vp),
         ("counts_dev", c_vp),
+        ("cperm", c_vp), ("cslot", c_vp), ("cstart", c_vp), ("class_pos_dev", c_vp),
         ("reduced", c_vp), ("emb_t1", c_vp),
     ]
 
@@ -71,6 +72,12 @@ def load_library() -> ctypes.CDLL:
         "fs_segment_reduce_grads": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i32, c_vp, c_vp, c_vp, c_vp, c_vp, S]),
         "fs_rowwise_adagrad_update": (ctypes.c_int, [c_vp, c_vp, ctypes.c_int, c_vp, c_i64, c_i32, c_vp, c_vp, c_vp,
                                                      c_i64, c_vp, c_f, c_f, S]),
+        "fs_collision_split_classes": (ctypes.c_int, [c_vp, c_vp, c_vp, c_vp, c_vp, c_i64, c_i64, c_vp, c_vp, c_vp,
+                                                      c_i64, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp,
+                                                      c_vp, c_vp, S]),
+        "fs_reduce_update_class": (ctypes.c_int, [c_vp, ctypes.c_int, c_vp, ctypes.c_int, c_vp, c_i64, c_i32, c_f, c_f,
+                                                  c_vp, c_i64, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, S]),
+        "fs_unique_ids_ahead": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i64, c_vp, c_vp, c_vp, c_vp, c_vp, S]),
         "fs_prioritized_step": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args), S]),
         "fs_step_forward": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args), S]),
         "fs_prioritized_step_pipelined": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args),
@@ -231,6 +238,46 @@ def fs_collision_split(ctx: Context, u_t: Optional[torch.Tensor], n_t_dev: Optio
     return out
 
 
+def fs_collision_split_classes(ctx: Context, layout_t: Dict[str, torch.Tensor], u_t1: Optional[torch.Tensor],
+                               n_t1_dev: Optional[torch.Tensor], cap_t1: int,
+                               out: Optional[Dict[str, torch.Tensor]] = None, stream=None) -> Dict[str, torch.Tensor]:
+    """layout_t: what fs_unique_ids returned for batch t (with its "n")."""
+    n_t = layout_t["n"]
+    dev = layout_t["unique"].device
+    if out is None:
+        out = alloc_split(n_t, cap_t1, dev)
+    rc = ctx.lib.fs_collision_split_classes(
+        ctx.handle, _ptr(layout_t["unique"]), _ptr(layout_t["n_unique"]), _ptr(u_t1), _ptr(n_t1_dev), n_t, cap_t1,
+        _ptr(layout_t["seg_offsets"]), _ptr(layout_t["perm"]), _ptr(layout_t["inverse"]), n_t,
+        _ptr(out["co"]), _ptr(out["co_slot"]), _ptr(out["ex"]), _ptr(out["ex_slot"]), _ptr(out["ex_next"]),
+        _ptr(out["ex_next_slot"]), _ptr(out["counts"]), _ptr(out["cperm"]), _ptr(out["cslot"]), _ptr(out["cstart"]),
+        _ptr(out["class_pos"]), _stream(stream))
+    ctx.check(rc, "fs_collision_split_classes")
+    return out
+
+
+def fs_reduce_update_class(ctx: Context, cls: int, table: torch.Tensor, state: torch.Tensor, lr: float, eps: float,
+                           grads: torch.Tensor, layout_t: Dict[str, torch.Tensor], split: Dict[str, torch.Tensor],
+                           reduced: Optional[torch.Tensor] = None, stream=None) -> None:
+    n, dim = grads.shape
+    rc = ctx.lib.fs_reduce_update_class(
+        ctx.handle, cls, _ptr(table), table_dtype_code(table), _ptr(state), table.shape[0], dim, lr, eps,
+        _ptr(grads), n, _ptr(layout_t["unique"]), _ptr(layout_t["seg_offsets"]), _ptr(split["cperm"]),
+        _ptr(split["cslot"]), _ptr(split["cstart"]), _ptr(split["class_pos"]), _ptr(reduced), _stream(stream))
+    ctx.check(rc, "fs_reduce_update_class")
+
+
+def fs_unique_ids_ahead(ctx: Context, ids: torch.Tensor, num_rows: int, out: Dict[str, torch.Tensor],
+                        stream=None) -> Dict[str, torch.Tensor]:
+    n = ids.numel()
+    rc = ctx.lib.fs_unique_ids_ahead(ctx.handle, _ptr(ids), n, num_rows, _ptr(out["unique"]),
+                                     _ptr(out["seg_offsets"]), _ptr(out["perm"]), _ptr(out["inverse"]),
+                                     _ptr(out["n_unique"]), _stream(stream))
+    ctx.check(rc, "fs_unique_ids_ahead")
+    out["n"] = n
+    return out
+
+
 def fs_segment_reduce_grads(ctx: Context, grads: torch.Tensor, perm: torch.Tensor, seg_offsets: torch.Tensor,
                             n_unique_dev: torch.Tensor, out: Optional[torch.Tensor] = None, stream=None,
                             inverse: Optional[torch.Tensor] = None) -> torch.Tensor:
@@ -323,7 +370,9 @@ def alloc_split(cap_t: int, cap_t1: int, device) -> Dict[str, torch.Tensor]:
     i32 = lambda k: torch.empty(max(k, 1), dtype=torch.int32, device=device)
     return {"co": i64(cap_t), "co_slot": i32(cap_t), "ex": i64(cap_t), "ex_slot": i32(cap_t),
             "ex_next": i64(cap_t1), "ex_next_slot": i32(cap_t1),
-            "counts": torch.zeros(3, dtype=torch.int64, device=device)}
+            "counts": torch.zeros(3, dtype=torch.int64, device=device),
+            "cperm": i32(cap_t), "cslot": i32(cap_t), "cstart": i32(cap_t),
+            "class_pos": torch.zeros(2, dtype=torch.int32, device=device)}
 
 
 def make_step_args(table: torch.Tensor, state: torch.Tensor, lr: float, eps: float,
@@ -354,5 +403,7 @@ def make_step_args(table: torch.Tensor, state: torch.Tensor, lr: float, eps: flo
     a.co, a.co_slot, a.ex, a.ex_slot = _ptr(split["co"]), _ptr(split["co_slot"]), _ptr(split["ex"]), _ptr(split["ex_slot"])
     a.ex_next, a.ex_next_slot = _ptr(split["ex_next"]), _ptr(split["ex_next_slot"])
     a.counts_dev = _ptr(split["counts"])
+    a.cperm, a.cslot, a.cstart = _ptr(split["cperm"]), _ptr(split["cslot"]), _ptr(split["cstart"])
+    a.class_pos_dev = _ptr(split["class_pos"])
     a.reduced = _ptr(reduced)
     return a

@@ -9,26 +9,9 @@
 // plain definition.  HBM traffic per row: read+write of the row, read of the gradient row,
 // 8 bytes of state, 12 bytes of (row, slot).
 #include "fs_common.h"
+#include "fs_device.h"
 
 namespace fs {
-
-__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
-
-// round to nearest even; NaN stays NaN
-__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x0040u;
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return u >> 16;
-}
-
-template <int LPR>
-__device__ __forceinline__ double group_sum(double x) {
-#pragma unroll
-    for (int m = LPR / 2; m >= 1; m >>= 1) x += __shfl_xor(x, m, kWave);
-    return x;
-}
 
 template <bool BF16, int LPR, int UNR>
 __global__ __launch_bounds__(256) void adagrad_kernel(u32x4 *__restrict__ table, float *__restrict__ state,

@@ -4,6 +4,8 @@
 #include <atomic>
 #include <chrono>
 #include <condition_variable>
+#include <deque>
+#include <functional>
 #include <mutex>
 #include <new>
 #include <thread>
@@ -11,6 +13,76 @@
 #include "fs_common.h"
 
 using namespace fs;
+
+static double now_us() {
+    return std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
+struct fs_graph {
+    hipGraph_t graph;
+    hipGraphExec_t exec;
+};
+
+// A host thread that enqueues work on the context's own streams while the calling thread enqueues
+// on the caller's: an iteration is a dozen launches plus cross-stream waits, and at several
+// microseconds each the host, not the GPU, would set the pace.
+struct fs_worker {
+    std::thread thread;
+    std::mutex mu;
+    std::condition_variable cv;
+    std::deque<std::function<int()>> jobs;
+    bool busy = false, quit = false;
+    int rc = FS_OK;               // first failure since the last wait()
+    double busy_us = 0.0;
+
+    void main_loop(int device) {
+        (void)hipSetDevice(device);
+        std::unique_lock<std::mutex> lk(mu);
+        for (;;) {
+            cv.wait(lk, [this] { return !jobs.empty() || quit; });
+            if (jobs.empty() && quit) return;
+            std::function<int()> job = std::move(jobs.front());
+            jobs.pop_front();
+            busy = true;
+            lk.unlock();
+            const double t0 = now_us();
+            const int r = job();
+            const double t1 = now_us();
+            lk.lock();
+            busy_us += t1 - t0;
+            if (r != FS_OK && rc == FS_OK) rc = r;
+            busy = false;
+            cv.notify_all();
+        }
+    }
+    void post(std::function<int()> job) {
+        std::lock_guard<std::mutex> lk(mu);
+        jobs.push_back(std::move(job));
+        cv.notify_all();
+    }
+    int wait() {                  // everything posted so far has been enqueued on its stream
+        std::unique_lock<std::mutex> lk(mu);
+        cv.wait(lk, [this] { return jobs.empty() && !busy; });
+        const int r = rc;
+        rc = FS_OK;
+        return r;
+    }
+};
+
+// An ahead-of-time dedup whose results a later step consumes
+enum { kAheadFree = 0, kAheadPosted = 1, kAheadRecorded = 2 };
+struct fs_ahead {
+    const int64_t *unique = nullptr;   // key: the output buffer (calling thread only); null once claimed by a step
+    hipEvent_t fork = nullptr, done = nullptr;
+    std::atomic<int> state{kAheadFree};
+};
+constexpr int kAheadSlots = 4;
+
+struct fs_host {
+    fs_worker *worker[2] = {nullptr, nullptr};   // 0: side stream A, 1: index streams
+    fs_ahead ahead[kAheadSlots];
+    int x_turn = 0;
+};
 
 namespace {
 
@@ -36,30 +108,36 @@ void carve(fs_ctx *c, char *base, size_t *total) {
     const size_t chunks = (size_t)ceil_div(c->max_ids, kReduceChunk) + 2;
     c->d_flags = cv.take<int>(4);
     c->d_zero = cv.take<int64_t>(1);
-    c->keys[0] = cv.take<uint64_t>(n);
-    c->keys[1] = cv.take<uint64_t>(n);
-    c->idx[0] = cv.take<int32_t>(n);
-    c->idx[1] = cv.take<int32_t>(n);
-    c->tile_hist = cv.take<uint32_t>(sort_tiles * kRadix);
-    c->digit_base = cv.take<uint32_t>(kRadix);
-    c->tile_heads = cv.take<int32_t>(scan_tiles);
+    for (int k = 0; k < kSortSets; ++k) {
+        fs_sort_scratch &ws = c->sort[k];
+        ws.keys[0] = cv.take<uint64_t>(n);
+        ws.keys[1] = cv.take<uint64_t>(n);
+        ws.idx[0] = cv.take<int32_t>(n);
+        ws.idx[1] = cv.take<int32_t>(n);
+        ws.tile_hist = cv.take<uint32_t>(sort_tiles * kRadix);
+        ws.tile_heads = cv.take<int32_t>(scan_tiles);
+    }
     c->split_flag_t = cv.take<uint8_t>(n + 16);
     c->split_flag_t1 = cv.take<uint8_t>(n + 16);
     c->split_cnt = cv.take<int32_t>(2 * scan_tiles);
     c->part_head = cv.take<double>(chunks * (size_t)c->max_dim);
     c->part_last = cv.take<double>(chunks * (size_t)c->max_dim);
     c->chunk_desc = cv.take<int32_t>(chunks * 4);
+    for (int k = 0; k < 2; ++k) {
+        c->fpart_head[k] = cv.take<double>(chunks * (size_t)c->max_dim);
+        c->fpart_last[k] = cv.take<double>(chunks * (size_t)c->max_dim);
+        c->fcounters[k] = cv.take<int>(chunks);
+    }
+    c->cstart_local = cv.take<int32_t>(n + 16);
+    c->tile_len = cv.take<int32_t>(2 * scan_tiles);
     *total = align_up(cv.off, 256);
 }
 
 hipStream_t as_stream(fs_stream s) { return reinterpret_cast<hipStream_t>(s); }
 
-double now_us() {
-    return std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now().time_since_epoch()).count();
-}
-
 void worker_stop(fs_ctx *ctx);
 int join_pending_work(fs_ctx *ctx, hipStream_t s);
+void drop_ahead(fs_ctx *ctx, const int64_t *unique);
 
 #define FS_REQUIRE(ctx, cond, msg)                          \
     do {                                                    \
@@ -101,12 +179,20 @@ int fs_ctx_create(fs_ctx **out, int device, int64_t max_ids, int32_t max_dim) {
     size_t total;
     carve(c, static_cast<char *>(c->slab), &total);
     bool ok = hipMemset(c->slab, 0, 4096) == hipSuccess;
-    ok = ok && hipStreamCreateWithFlags(&c->stream_a, hipStreamNonBlocking) == hipSuccess;
-    ok = ok && hipStreamCreateWithFlags(&c->stream_b, hipStreamNonBlocking) == hipSuccess;
-    ok = ok && hipStreamCreateWithFlags(&c->stream_cap, hipStreamNonBlocking) == hipSuccess;
-    hipEvent_t *evs[] = {&c->ev_fork, &c->ev_split, &c->ev_reduce, &c->ev_co, &c->ev_ex, &c->ev_idx[0], &c->ev_idx[1],
-                         &c->ev_red[0], &c->ev_red[1], &c->ev_side[0], &c->ev_side[1]};
+    for (int k = 0; k < 2; ++k)
+        ok = ok && hipMemset(c->fcounters[k], 0, ((size_t)ceil_div(c->max_ids, kReduceChunk) + 2) * sizeof(int)) == hipSuccess;
+    c->host = new (std::nothrow) fs_host();
+    ok = ok && c->host != nullptr;
+    hipStream_t *streams[] = {&c->stream_a, &c->stream_b, &c->stream_cap, &c->stream_x[0], &c->stream_x[1]};
+    for (hipStream_t *st : streams) ok = ok && hipStreamCreateWithFlags(st, hipStreamNonBlocking) == hipSuccess;
+    hipEvent_t *evs[] = {&c->ev_fork, &c->ev_split, &c->ev_ex, &c->ev_pfork[0], &c->ev_pfork[1], &c->ev_side[0],
+                         &c->ev_side[1]};
     for (hipEvent_t *e : evs) ok = ok && hipEventCreateWithFlags(e, hipEventDisableTiming) == hipSuccess;
+    if (c->host)
+        for (fs_ahead &a : c->host->ahead) {
+            ok = ok && hipEventCreateWithFlags(&a.fork, hipEventDisableTiming) == hipSuccess;
+            ok = ok && hipEventCreateWithFlags(&a.done, hipEventDisableTiming) == hipSuccess;
+        }
     if (!ok) {
         fs_ctx_destroy(c);
         return FS_EHIP;
@@ -119,13 +205,20 @@ int fs_ctx_destroy(fs_ctx *c) {
     if (!c) return FS_OK;
     (void)hipSetDevice(c->device);
     worker_stop(c);
-    if (c->stream_a) { (void)hipStreamSynchronize(c->stream_a); (void)hipStreamDestroy(c->stream_a); }
-    if (c->stream_b) { (void)hipStreamSynchronize(c->stream_b); (void)hipStreamDestroy(c->stream_b); }
-    if (c->stream_cap) (void)hipStreamDestroy(c->stream_cap);
-    hipEvent_t evs[] = {c->ev_fork, c->ev_split, c->ev_reduce, c->ev_co, c->ev_ex, c->ev_idx[0], c->ev_idx[1],
-                        c->ev_red[0], c->ev_red[1], c->ev_side[0], c->ev_side[1]};
+    hipStream_t streams[] = {c->stream_a, c->stream_b, c->stream_x[0], c->stream_x[1], c->stream_cap};
+    for (hipStream_t st : streams)
+        if (st) { (void)hipStreamSynchronize(st); (void)hipStreamDestroy(st); }
+    hipEvent_t evs[] = {c->ev_fork, c->ev_split, c->ev_ex, c->ev_pfork[0], c->ev_pfork[1], c->ev_side[0], c->ev_side[1]};
     for (hipEvent_t e : evs)
         if (e) (void)hipEventDestroy(e);
+    if (c->host) {
+        for (fs_ahead &a : c->host->ahead) {
+            if (a.fork) (void)hipEventDestroy(a.fork);
+            if (a.done) (void)hipEventDestroy(a.done);
+        }
+        delete c->host;
+        c->host = nullptr;
+    }
     (void)fs_ctx_set_kernel_timing(c, 0, 1);
     if (c->slab) (void)hipFree(c->slab);
     delete c;
@@ -143,6 +236,8 @@ int fs_check_async(fs_ctx *ctx, fs_stream stream) {
     FS_HIP(ctx, hipStreamSynchronize(as_stream(stream)));
     FS_HIP(ctx, hipStreamSynchronize(ctx->stream_a));
     FS_HIP(ctx, hipStreamSynchronize(ctx->stream_b));
+    FS_HIP(ctx, hipStreamSynchronize(ctx->stream_x[0]));
+    FS_HIP(ctx, hipStreamSynchronize(ctx->stream_x[1]));
     int flags[4] = {0, 0, 0, 0};
     FS_HIP(ctx, hipMemcpy(flags, ctx->d_flags, sizeof(flags), hipMemcpyDeviceToHost));
     if (flags[0] == 0) return FS_OK;
@@ -221,6 +316,7 @@ int fs_unique_ids(fs_ctx *ctx, const int64_t *ids, int64_t n, int64_t num_rows, 
     if (n > 0) FS_REQUIRE(ctx, ids && unique && perm, "unique: null pointer");
     const int jrc = join_pending_work(ctx, as_stream(stream));      // the workspace may still be in use on A
     if (jrc != FS_OK) return jrc;
+    drop_ahead(ctx, unique);
     return launch_unique(ctx, ids, n, num_rows, unique, seg_offsets, perm, inverse, n_unique_dev, as_stream(stream));
 }
 
@@ -290,8 +386,8 @@ int fs_stream_copy(fs_ctx *ctx, const void *src, void *dst, int64_t n_bytes, fs_
 
 namespace {
 
-// host-visible checks shared by the step entry points; `need_t`: iteration t is used (reduce,
-// updates), `need_t1`: the lookahead batch is used (dedup, gather)
+// host-visible checks shared by the step entry points; `have_t`: iteration t is used (updates),
+// `have_t1`: the lookahead batch is used (dedup, gather)
 int check_step_args(fs_ctx *ctx, const fs_step_args *a, bool *have_t, bool *have_t1) {
     FS_REQUIRE(ctx, a, "step: null args");
     const int dt = a->dtype;
@@ -300,31 +396,18 @@ int check_step_args(fs_ctx *ctx, const fs_step_args *a, bool *have_t, bool *have
     FS_REQUIRE(ctx, a->num_rows >= 0 && a->n_t >= 0 && a->n_t1 >= 0 && a->batch_t1 >= 0, "step: negative size");
     if (a->n_t > ctx->max_ids || a->n_t1 > ctx->max_ids || a->dim > ctx->max_dim)
         return set_err(ctx, FS_ENOMEM, "step: beyond the context capacity");
-    FS_REQUIRE(ctx, a->table && a->state && a->counts_dev, "step: null table/state/counts");
+    FS_REQUIRE(ctx, a->table && a->state && a->counts_dev && a->class_pos_dev, "step: null table/state/counts");
     *have_t = a->n_t > 0;
     *have_t1 = a->values_t1 != nullptr && a->n_t1 > 0;
     if (*have_t)
-        FS_REQUIRE(ctx, a->u_t && a->seg_offsets_t && a->perm_t && a->n_unique_t_dev && a->grads_t && a->reduced &&
-                            a->co && a->co_slot && a->ex && a->ex_slot,
+        FS_REQUIRE(ctx, a->u_t && a->seg_offsets_t && a->perm_t && a->inverse_t && a->n_unique_t_dev && a->grads_t &&
+                            a->co && a->co_slot && a->ex && a->ex_slot && a->cperm && a->cslot && a->cstart,
                    "step: null pointer (iteration t)");
     if (*have_t1)
-        FS_REQUIRE(ctx, a->u_t1 && a->seg_offsets_t1 && a->perm_t1 && a->n_unique_t1_dev && a->ex_next &&
-                            a->ex_next_slot && a->emb_t1,
+        FS_REQUIRE(ctx, a->u_t1 && a->seg_offsets_t1 && a->perm_t1 && a->inverse_t1 && a->n_unique_t1_dev &&
+                            a->ex_next && a->ex_next_slot && a->emb_t1,
                    "step: null pointer (lookahead)");
     return FS_OK;
-}
-
-// Forward of Algorithm 2 (index work): dedup of the lookahead IDs, then the collision split
-int enqueue_index_work(fs_ctx *ctx, const fs_step_args *a, bool have_t, bool have_t1, hipStream_t s) {
-    int rc;
-    if (have_t1) {
-        rc = launch_unique(ctx, a->values_t1, a->n_t1, a->num_rows, a->u_t1, a->seg_offsets_t1, a->perm_t1,
-                           a->inverse_t1, a->n_unique_t1_dev, s);
-        if (rc != FS_OK) return rc;
-    }
-    return launch_split(ctx, a->u_t, have_t ? a->n_unique_t_dev : nullptr, a->u_t1,
-                        have_t1 ? a->n_unique_t1_dev : nullptr, have_t ? a->n_t : 0, have_t1 ? a->n_t1 : 0, a->co,
-                        a->co_slot, a->ex, a->ex_slot, a->ex_next, a->ex_next_slot, a->counts_dev, s);
 }
 
 // one step in `timing_every` gets its kernels bracketed by event pairs (an event record costs the
@@ -334,211 +417,232 @@ void begin_step_timing(fs_ctx *ctx) {
     if (ctx->timing_slots > 0 && !ctx->capturing) ++ctx->step_counter;
 }
 
-int enqueue_reduce(fs_ctx *ctx, const fs_step_args *a, hipStream_t sp) {
-    ctx->reduce_inverse = a->inverse_t;
-    const int rc = launch_reduce(ctx, a->grads_t, a->n_t, a->dim, a->perm_t, a->seg_offsets_t, a->n_unique_t_dev,
-                                 a->reduced, sp, timing_pair(ctx, FS_TIME_REDUCE));
-    ctx->reduce_inverse = nullptr;
-    return rc;
-}
-
-// Backward of Algorithm 2 after the reduce: priority pass on `sp`, deferred pass on B (which
-// already waits for the reduce and the split), gather of the lookahead rows on `sp`, join of B.
-// ex_done == nullptr: B is joined into `sp` at the end; otherwise the deferred pass records it
-// and the caller decides who waits for it.
-int enqueue_updates_and_gather(fs_ctx *ctx, const fs_step_args *a, bool have_t, bool have_t1, hipStream_t sp,
-                               hipEvent_t ex_done = nullptr) {
-    hipStream_t sb = ctx->stream_b;
-    const fs_dtype fdt = (fs_dtype)a->dtype;
-    int rc;
-    if (have_t) {
-        // priority pass: collision rows, strictly before the lookahead rows are read
-        hipEvent_t *tco = timing_pair(ctx, FS_TIME_UPDATE_CO), *tex = timing_pair(ctx, FS_TIME_UPDATE_EX);
-        if (tco) (void)hipEventRecord(tco[0], sp);
-        rc = launch_adagrad(ctx, a->table, fdt, a->state, a->num_rows, a->dim, a->co, a->co_slot, a->counts_dev + 0,
-                            a->n_t, a->reduced, a->lr, a->eps, sp);
-        if (rc != FS_OK) return rc;
-        if (tco) (void)hipEventRecord(tco[1], sp);
-        if (tex) (void)hipEventRecord(tex[0], sb);
-        rc = launch_adagrad(ctx, a->table, fdt, a->state, a->num_rows, a->dim, a->ex, a->ex_slot, a->counts_dev + 1,
-                            a->n_t, a->reduced, a->lr, a->eps, sb);
-        if (rc != FS_OK) return rc;
-        if (tex) (void)hipEventRecord(tex[1], sb);
-    }
-    FS_HIP(ctx, hipEventRecord(ex_done ? ex_done : ctx->ev_ex, sb));
-    if (have_t1) {
-        // exclusive rows and lookahead rows are disjoint, so this may overlap the deferred pass
-        const int row_bytes = a->dim * (a->dtype == FS_F32 ? 4 : 2);
-        hipEvent_t *tg = timing_pair(ctx, FS_TIME_GATHER);
-        if (tg) (void)hipEventRecord(tg[0], sp);
-        rc = launch_gather(ctx, a->table, a->num_rows, row_bytes, a->values_t1, a->offsets_t1, a->batch_t1, a->n_t1,
-                           a->emb_t1, sp);
-        if (rc != FS_OK) return rc;
-        if (tg) (void)hipEventRecord(tg[1], sp);
-    }
-    if (!ex_done) FS_HIP(ctx, hipStreamWaitEvent(sp, ctx->ev_ex, 0));
-    if (ctx->timing_now) ++ctx->timing_steps;
-    return FS_OK;
-}
-
-// pipelined form: priority pass and gather on `sp` (the deferred pass goes to the side stream)
-int enqueue_priority_and_gather(fs_ctx *ctx, const fs_step_args *a, bool have_t, bool have_t1, hipStream_t sp) {
-    int rc;
-    if (have_t) {
-        hipEvent_t *tco = timing_pair(ctx, FS_TIME_UPDATE_CO);
-        if (tco) (void)hipEventRecord(tco[0], sp);
-        rc = launch_adagrad(ctx, a->table, (fs_dtype)a->dtype, a->state, a->num_rows, a->dim, a->co, a->co_slot,
-                            a->counts_dev + 0, a->n_t, a->reduced, a->lr, a->eps, sp);
-        if (rc != FS_OK) return rc;
-        if (tco) (void)hipEventRecord(tco[1], sp);
-    }
-    if (have_t1) {
-        const int row_bytes = a->dim * (a->dtype == FS_F32 ? 4 : 2);
-        hipEvent_t *tg = timing_pair(ctx, FS_TIME_GATHER);
-        if (tg) (void)hipEventRecord(tg[0], sp);
-        rc = launch_gather(ctx, a->table, a->num_rows, row_bytes, a->values_t1, a->offsets_t1, a->batch_t1, a->n_t1,
-                           a->emb_t1, sp);
-        if (rc != FS_OK) return rc;
-        if (tg) (void)hipEventRecord(tg[1], sp);
-    }
-    return FS_OK;
-}
-
 }  // namespace
-
-struct fs_graph {
-    hipGraph_t graph;
-    hipGraphExec_t exec;
-};
-
-// A second host thread that enqueues the index half of an iteration on side stream A while the
-// calling thread enqueues the gradient half: an iteration is about sixteen launches and a dozen
-// event operations, and at a few microseconds each the host, not the GPU, would set the pace.
-struct fs_worker {
-    std::thread thread;
-    std::mutex mu;
-    std::condition_variable cv;
-    bool has_job = false, done = true, quit = false;
-    // the job: index half of `next` (if has_next), then the deferred pass of `cur` (if has_cur)
-    fs_step_args next, cur;
-    bool has_next = false, nxt_t = false, nxt_t1 = false, has_cur = false;
-    int parity = 0;               // event set of the call that posted the job
-    hipEvent_t first_after = nullptr;   // A waits for this before the job's first kernel (may be null)
-    std::atomic<bool> red_recorded{false};   // set by the posting thread once ev_red[parity] is recorded
-    hipEvent_t *ex_timing = nullptr;
-    int rc = FS_OK;
-};
 
 namespace {
 
-// Side stream A, in this order: index half of the next iteration (needs nothing of the current
-// one), then - once the reduce of the current iteration is done - its deferred pass, then the
-// event that the next call waits for before its priority pass.
-int enqueue_side_stream(fs_ctx *ctx, const fs_step_args *next, bool nxt_t, bool nxt_t1, const fs_step_args *cur,
-                        int parity, hipEvent_t first_after, std::atomic<bool> *red_recorded, hipEvent_t *ex_timing) {
+fs_worker *get_worker(fs_ctx *ctx, int which) {
+    fs_host *h = ctx->host;
+    if (!h->worker[which]) {
+        fs_worker *w = new (std::nothrow) fs_worker();
+        if (!w) return nullptr;
+        const int device = ctx->device;
+        w->thread = std::thread([w, device] { w->main_loop(device); });
+        h->worker[which] = w;
+    }
+    return h->worker[which];
+}
+
+int workers_wait(fs_ctx *ctx) {
+    int rc = FS_OK;
+    for (int k = 0; k < 2; ++k)
+        if (ctx->host && ctx->host->worker[k]) {
+            const int r = ctx->host->worker[k]->wait();
+            if (rc == FS_OK) rc = r;
+        }
+    if (rc != FS_OK && ctx->err[0] == 0) snprintf(ctx->err, sizeof(ctx->err), "side-stream enqueue failed");
+    return rc;
+}
+
+void worker_stop(fs_ctx *ctx) {
+    if (!ctx->host) return;
+    for (int k = 0; k < 2; ++k) {
+        fs_worker *w = ctx->host->worker[k];
+        if (!w) continue;
+        {
+            std::lock_guard<std::mutex> lk(w->mu);
+            w->quit = true;
+            w->cv.notify_all();
+        }
+        if (w->thread.joinable()) w->thread.join();
+        delete w;
+        ctx->host->worker[k] = nullptr;
+    }
+}
+
+// the outstanding ahead-of-time dedup that writes `unique`, if any (calling thread only)
+fs_ahead *find_ahead(fs_ctx *ctx, const int64_t *unique) {
+    if (!unique) return nullptr;
+    for (fs_ahead &e : ctx->host->ahead)
+        if (e.unique == unique && e.state.load(std::memory_order_acquire) != kAheadFree) return &e;
+    return nullptr;
+}
+
+// stream `s` waits for the dedup of `e`; the slot is free afterwards (any thread; `e` was claimed)
+int consume_ahead(fs_ctx *ctx, fs_ahead *e, hipStream_t s) {
+    while (e->state.load(std::memory_order_acquire) != kAheadRecorded) std::this_thread::yield();
+    const hipError_t err = hipStreamWaitEvent(s, e->done, 0);
+    e->state.store(kAheadFree, std::memory_order_release);
+    if (err != hipSuccess) return hip_err(ctx, err, "hipStreamWaitEvent(ahead)");
+    return FS_OK;
+}
+
+// Forward of Algorithm 2 (index work): dedup of the lookahead IDs (unless done ahead of time), the
+// collision split of U_t, the class order of batch t
+int enqueue_index_work(fs_ctx *ctx, const fs_step_args *a, bool have_t, bool have_t1, fs_ahead *ahead,
+                       hipStream_t s) {
+    int rc;
+    if (have_t1) {
+        if (ahead) rc = consume_ahead(ctx, ahead, s);
+        else rc = launch_unique(ctx, a->values_t1, a->n_t1, a->num_rows, a->u_t1, a->seg_offsets_t1, a->perm_t1,
+                                a->inverse_t1, a->n_unique_t1_dev, s, 0);
+        if (rc != FS_OK) return rc;
+    }
+    rc = launch_split(ctx, a->u_t, have_t ? a->n_unique_t_dev : nullptr, a->u_t1,
+                      have_t1 ? a->n_unique_t1_dev : nullptr, have_t ? a->n_t : 0, have_t1 ? a->n_t1 : 0, a->co,
+                      a->co_slot, a->ex, a->ex_slot, a->ex_next, a->ex_next_slot, a->counts_dev, s,
+                      have_t ? a->seg_offsets_t : nullptr);
+    if (rc != FS_OK) return rc;
+    return launch_class_order(ctx, a->perm_t, a->inverse_t, a->seg_offsets_t, have_t ? a->n_t : 0,
+                              have_t ? a->n_t : 0, a->cperm, a->cslot, a->cstart, a->class_pos_dev, s);
+}
+
+// update_embedding for one class of rows of iteration t (0: priority pass, 1: deferred pass)
+int enqueue_class_pass(fs_ctx *ctx, const fs_step_args *a, int cls, hipStream_t s, hipEvent_t *timing) {
+    if (timing) (void)hipEventRecord(timing[0], s);
+    const int rc = launch_reduce_update(ctx, cls, a->grads_t, a->n_t, a->dim, a->cperm, a->cslot, a->class_pos_dev,
+                                        a->seg_offsets_t, a->cstart, a->u_t, a->table, a->dtype, a->state,
+                                        a->num_rows, a->lr, a->eps, a->reduced, s);
+    if (timing && rc == FS_OK) (void)hipEventRecord(timing[1], s);
+    return rc;
+}
+
+int enqueue_gather(fs_ctx *ctx, const fs_step_args *a, hipStream_t s) {
+    const int row_bytes = a->dim * (a->dtype == FS_F32 ? 4 : 2);
+    hipEvent_t *tg = timing_pair(ctx, FS_TIME_GATHER);
+    if (tg) (void)hipEventRecord(tg[0], s);
+    const int rc = launch_gather(ctx, a->table, a->num_rows, row_bytes, a->values_t1, a->offsets_t1, a->batch_t1,
+                                 a->n_t1, a->emb_t1, s);
+    if (tg && rc == FS_OK) (void)hipEventRecord(tg[1], s);
+    return rc;
+}
+
+// Side stream A for one pipelined call: after the caller's earlier work (the gradients of `cur`),
+// the deferred pass of `cur`, then the index half of `next`, then the event the next call waits for.
+int enqueue_side_stream(fs_ctx *ctx, const fs_step_args *cur, const fs_step_args *next, bool nxt_t, bool nxt_t1,
+                        fs_ahead *ahead, int parity, hipEvent_t *ex_timing) {
     hipStream_t sa = ctx->stream_a;
     int rc = FS_OK;
-    if (first_after) FS_HIP(ctx, hipStreamWaitEvent(sa, first_after, 0));
-    if (next) rc = enqueue_index_work(ctx, next, nxt_t, nxt_t1, sa);
+    FS_HIP(ctx, hipStreamWaitEvent(sa, ctx->ev_pfork[parity], 0));
+    if (cur) rc = enqueue_class_pass(ctx, cur, 1, sa, ex_timing);
+    if (rc == FS_OK && next) rc = enqueue_index_work(ctx, next, nxt_t, nxt_t1, ahead, sa);
+    else if (ahead) (void)consume_ahead(ctx, ahead, sa);
     if (rc != FS_OK) return rc;
-    if (cur) {
-        if (red_recorded)
-            while (!red_recorded->load(std::memory_order_acquire)) std::this_thread::yield();
-        FS_HIP(ctx, hipStreamWaitEvent(sa, ctx->ev_red[parity], 0));
-        if (ex_timing) (void)hipEventRecord(ex_timing[0], sa);
-        rc = launch_adagrad(ctx, cur->table, (fs_dtype)cur->dtype, cur->state, cur->num_rows, cur->dim, cur->ex,
-                            cur->ex_slot, cur->counts_dev + 1, cur->n_t, cur->reduced, cur->lr, cur->eps, sa);
-        if (rc != FS_OK) return rc;
-        if (ex_timing) (void)hipEventRecord(ex_timing[1], sa);
-    }
     FS_HIP(ctx, hipEventRecord(ctx->ev_side[parity], sa));
     return FS_OK;
 }
 
-void worker_main(fs_ctx *ctx) {
-    fs_worker *w = ctx->worker;
-    (void)hipSetDevice(ctx->device);
-    std::unique_lock<std::mutex> lk(w->mu);
-    for (;;) {
-        w->cv.wait(lk, [w] { return w->has_job || w->quit; });
-        if (w->quit) return;
-        w->has_job = false;
-        lk.unlock();
-        const double j0 = now_us();
-        const int rc = enqueue_side_stream(ctx, w->has_next ? &w->next : nullptr, w->nxt_t, w->nxt_t1,
-                                           w->has_cur ? &w->cur : nullptr, w->parity, w->first_after,
-                                           &w->red_recorded, w->ex_timing);
-        ctx->host_us[5] += now_us() - j0;                    // the worker's enqueueing
-        lk.lock();
-        w->rc = rc;
-        w->done = true;
-        w->cv.notify_all();
-    }
-}
-
-// hands the side-stream work of one call to the worker (started on first use); false if no worker
-bool worker_post(fs_ctx *ctx, const fs_step_args *next, bool nxt_t, bool nxt_t1, const fs_step_args *cur, int parity,
-                 hipEvent_t first_after, hipEvent_t *ex_timing) {
-    if (!ctx->worker) {
-        ctx->worker = new (std::nothrow) fs_worker();
-        if (!ctx->worker) return false;
-        ctx->worker->thread = std::thread(worker_main, ctx);
-    }
-    fs_worker *w = ctx->worker;
-    std::lock_guard<std::mutex> lk(w->mu);
-    w->has_next = next != nullptr;
-    if (next) w->next = *next;
-    w->nxt_t = nxt_t;
-    w->nxt_t1 = nxt_t1;
-    w->has_cur = cur != nullptr;
-    if (cur) w->cur = *cur;
-    w->parity = parity;
-    w->first_after = first_after;
-    w->ex_timing = ex_timing;
-    w->red_recorded.store(false, std::memory_order_relaxed);
-    w->has_job = true;
-    w->done = false;
-    w->cv.notify_all();
-    return true;
-}
-
-int worker_wait(fs_ctx *ctx) {
-    fs_worker *w = ctx->worker;
-    if (!w) return FS_OK;
-    std::unique_lock<std::mutex> lk(w->mu);
-    w->cv.wait(lk, [w] { return w->done; });
-    return w->rc;
-}
-
-void worker_stop(fs_ctx *ctx) {
-    fs_worker *w = ctx->worker;
-    if (!w) return;
-    {
-        std::lock_guard<std::mutex> lk(w->mu);
-        w->quit = true;
-        w->cv.notify_all();
-    }
-    if (w->thread.joinable()) w->thread.join();
-    delete w;
-    ctx->worker = nullptr;
-}
-
-// Makes `s` wait for what an earlier pipelined call left running on side stream A: the index half
-// of its `next` and the deferred pass of its `cur`.
+// Makes `s` wait for what earlier calls left running on the context's own streams: the side work of
+// the last pipelined call, and every ahead-of-time dedup no step has claimed yet (those stay
+// registered: a later step may still name their buffers).
 int join_pending_work(fs_ctx *ctx, hipStream_t s) {
-    int wrc = FS_OK;
+    const int wrc = workers_wait(ctx);
     if (ctx->side_pending) {
-        wrc = worker_wait(ctx);                              // its enqueueing (and event record) is complete
         ctx->side_pending = false;
         FS_HIP(ctx, hipStreamWaitEvent(s, ctx->ev_side[ctx->pipe_parity], 0));
     }
-    ctx->red_valid = false;                                  // the next pipelined call forks from its stream
+    if (!ctx->capturing)
+        for (fs_ahead &e : ctx->host->ahead)
+            if (e.unique != nullptr && e.state.load(std::memory_order_acquire) == kAheadRecorded)
+                FS_HIP(ctx, hipStreamWaitEvent(s, e.done, 0));
     return wrc;
+}
+
+// forget an ahead-of-time dedup of `unique` (its buffer is about to be rewritten by someone else)
+void drop_ahead(fs_ctx *ctx, const int64_t *unique) {
+    fs_ahead *e = find_ahead(ctx, unique);
+    if (e) {
+        e->unique = nullptr;
+        e->state.store(kAheadFree, std::memory_order_release);
+    }
 }
 
 }  // namespace
 
 extern "C" {
+
+int fs_collision_split_classes(fs_ctx *ctx, const int64_t *u_t, const int64_t *n_t_dev, const int64_t *u_t1,
+                               const int64_t *n_t1_dev, int64_t cap_t, int64_t cap_t1, const int32_t *seg_offsets_t,
+                               const int32_t *perm_t, const int32_t *inverse_t, int64_t n_t, int64_t *co,
+                               int32_t *co_slot, int64_t *ex, int32_t *ex_slot, int64_t *ex_next,
+                               int32_t *ex_next_slot, int64_t *counts_dev, int32_t *cperm, int32_t *cslot,
+                               int32_t *cstart, int32_t *class_pos_dev, fs_stream stream) {
+    if (!ctx) return FS_EINVAL;
+    FS_REQUIRE(ctx, cap_t >= 0 && cap_t1 >= 0 && n_t >= 0, "split: negative size");
+    if (cap_t > ctx->max_ids || cap_t1 > ctx->max_ids || n_t > ctx->max_ids)
+        return set_err(ctx, FS_ENOMEM, "split: capacity beyond the context capacity");
+    FS_REQUIRE(ctx, counts_dev && class_pos_dev, "split: null counts");
+    FS_REQUIRE(ctx, (n_t == 0) == (cap_t == 0), "split: n_t and cap_t must both be zero or both positive");
+    if (cap_t > 0)
+        FS_REQUIRE(ctx, u_t && n_t_dev && co && co_slot && ex && ex_slot && seg_offsets_t && perm_t && inverse_t &&
+                            cperm && cslot && cstart,
+                   "split: null pointer (t side)");
+    if (cap_t1 > 0) FS_REQUIRE(ctx, u_t1 && n_t1_dev && ex_next && ex_next_slot, "split: null pointer (t+1 side)");
+    int rc = join_pending_work(ctx, as_stream(stream));      // the workspace may still be in use on A
+    if (rc != FS_OK) return rc;
+    rc = launch_split(ctx, u_t, cap_t > 0 ? n_t_dev : nullptr, u_t1, cap_t1 > 0 ? n_t1_dev : nullptr, cap_t, cap_t1,
+                      co, co_slot, ex, ex_slot, ex_next, ex_next_slot, counts_dev, as_stream(stream),
+                      cap_t > 0 ? seg_offsets_t : nullptr);
+    if (rc != FS_OK) return rc;
+    return launch_class_order(ctx, perm_t, inverse_t, seg_offsets_t, n_t, cap_t, cperm, cslot, cstart, class_pos_dev,
+                              as_stream(stream));
+}
+
+int fs_reduce_update_class(fs_ctx *ctx, int cls, void *table, fs_dtype dt, float *state, int64_t num_rows,
+                           int32_t dim, float lr, float eps, const float *grads, int64_t n, const int64_t *u_t,
+                           const int32_t *seg_offsets, const int32_t *cperm, const int32_t *cslot,
+                           const int32_t *cstart, const int32_t *class_pos_dev, float *reduced, fs_stream stream) {
+    if (!ctx) return FS_EINVAL;
+    FS_REQUIRE(ctx, cls == 0 || cls == 1, "reduce+update: class must be 0 or 1");
+    FS_REQUIRE(ctx, dt == FS_F32 || dt == FS_BF16, "reduce+update: unknown dtype");
+    FS_REQUIRE(ctx, dim_ok(dim, dt), "reduce+update: dim must be a multiple of 4 (fp32) / 8 (bf16), at most FS_MAX_DIM");
+    FS_REQUIRE(ctx, num_rows >= 0 && n >= 0, "reduce+update: negative size");
+    if (n > ctx->max_ids || dim > ctx->max_dim)
+        return set_err(ctx, FS_ENOMEM, "reduce+update: beyond the context capacity");
+    if (n == 0) return FS_OK;
+    FS_REQUIRE(ctx, table && state && grads && u_t && seg_offsets && cperm && cslot && cstart && class_pos_dev,
+               "reduce+update: null pointer");
+    return launch_reduce_update(ctx, cls, grads, n, dim, cperm, cslot, class_pos_dev, seg_offsets, cstart, u_t, table,
+                                dt, state, num_rows, lr, eps, reduced, as_stream(stream));
+}
+
+int fs_unique_ids_ahead(fs_ctx *ctx, const int64_t *ids, int64_t n, int64_t num_rows, int64_t *unique,
+                        int32_t *seg_offsets, int32_t *perm, int32_t *inverse, int64_t *n_unique_dev,
+                        fs_stream stream) {
+    if (!ctx) return FS_EINVAL;
+    FS_REQUIRE(ctx, n >= 0 && num_rows >= 0, "unique: negative size");
+    if (n > ctx->max_ids) return set_err(ctx, FS_ENOMEM, "unique: n beyond the context capacity");
+    FS_REQUIRE(ctx, unique && seg_offsets && n_unique_dev, "unique: null pointer");
+    if (n > 0) FS_REQUIRE(ctx, ids && perm, "unique: null pointer");
+    FS_REQUIRE(ctx, !ctx->capturing, "unique ahead: not while a graph is being captured");
+    drop_ahead(ctx, unique);
+    fs_host *h = ctx->host;
+    fs_ahead *e = nullptr;
+    for (fs_ahead &c : h->ahead)
+        if (c.state.load(std::memory_order_acquire) == kAheadFree) { e = &c; break; }
+    if (!e) return set_err(ctx, FS_EINVAL, "unique ahead: four dedups are already outstanding");
+    const int x = h->x_turn;
+    h->x_turn ^= 1;
+    hipStream_t sx = ctx->stream_x[x];
+    FS_HIP(ctx, hipEventRecord(e->fork, as_stream(stream)));
+    e->unique = unique;
+    e->state.store(kAheadPosted, std::memory_order_release);
+    auto job = [=]() -> int {
+        int rc = FS_OK;
+        if (hipStreamWaitEvent(sx, e->fork, 0) != hipSuccess) rc = FS_EHIP;
+        if (rc == FS_OK)
+            rc = launch_unique(ctx, ids, n, num_rows, unique, seg_offsets, perm, inverse, n_unique_dev, sx, 1 + x);
+        if (hipEventRecord(e->done, sx) != hipSuccess && rc == FS_OK) rc = FS_EHIP;
+        e->state.store(kAheadRecorded, std::memory_order_release);   // also after a failure: nobody may spin forever
+        return rc;
+    };
+    fs_worker *w = ctx->use_worker ? get_worker(ctx, 1) : nullptr;
+    if (w) {
+        w->post(job);
+        return FS_OK;
+    }
+    return job();
+}
 
 int fs_step_forward(fs_ctx *ctx, const fs_step_args *a, fs_stream stream) {
     if (!ctx) return FS_EINVAL;
@@ -548,9 +652,11 @@ int fs_step_forward(fs_ctx *ctx, const fs_step_args *a, fs_stream stream) {
     hipStream_t sp = as_stream(stream), sa = ctx->stream_a;
     rc = join_pending_work(ctx, sp);
     if (rc != FS_OK) return rc;
+    fs_ahead *ahead = have_t1 ? find_ahead(ctx, a->u_t1) : nullptr;
+    if (ahead) ahead->unique = nullptr;
     FS_HIP(ctx, hipEventRecord(ctx->ev_fork, sp));
     FS_HIP(ctx, hipStreamWaitEvent(sa, ctx->ev_fork, 0));
-    rc = enqueue_index_work(ctx, a, have_t, have_t1, sa);
+    rc = enqueue_index_work(ctx, a, have_t, have_t1, ahead, sa);
     if (rc != FS_OK) return rc;
     FS_HIP(ctx, hipEventRecord(ctx->ev_split, sa));
     FS_HIP(ctx, hipStreamWaitEvent(sp, ctx->ev_split, 0));
@@ -566,25 +672,33 @@ int fs_prioritized_step(fs_ctx *ctx, const fs_step_args *a, fs_stream stream) {
     rc = join_pending_work(ctx, sp);
     if (rc != FS_OK) return rc;
     begin_step_timing(ctx);
+    fs_ahead *ahead = have_t1 ? find_ahead(ctx, a->u_t1) : nullptr;
+    if (ahead) ahead->unique = nullptr;
     // fork: the side streams start after whatever the caller already queued on `stream`
     FS_HIP(ctx, hipEventRecord(ctx->ev_fork, sp));
     FS_HIP(ctx, hipStreamWaitEvent(sa, ctx->ev_fork, 0));
     FS_HIP(ctx, hipStreamWaitEvent(sb, ctx->ev_fork, 0));
-    // main stream first (the host enqueues the bandwidth-heavy kernel before the many small ones):
-    // reduce the gradients of t while A works on the indices of t+1
-    if (have_t) {
-        rc = enqueue_reduce(ctx, a, sp);
-        if (rc != FS_OK) return rc;
-    }
-    FS_HIP(ctx, hipEventRecord(ctx->ev_reduce, sp));
-    rc = enqueue_index_work(ctx, a, have_t, have_t1, sa);
+    rc = enqueue_index_work(ctx, a, have_t, have_t1, ahead, sa);
     if (rc != FS_OK) return rc;
     FS_HIP(ctx, hipEventRecord(ctx->ev_split, sa));
     FS_HIP(ctx, hipStreamWaitEvent(sp, ctx->ev_split, 0));
-    // deferred pass on B: needs the split and the reduced gradients, nothing else
     FS_HIP(ctx, hipStreamWaitEvent(sb, ctx->ev_split, 0));
-    FS_HIP(ctx, hipStreamWaitEvent(sb, ctx->ev_reduce, 0));
-    return enqueue_updates_and_gather(ctx, a, have_t, have_t1, sp);
+    if (have_t) {
+        // priority pass: collision rows, strictly before the lookahead rows are read
+        rc = enqueue_class_pass(ctx, a, 0, sp, timing_pair(ctx, FS_TIME_UPDATE_CO));
+        if (rc != FS_OK) return rc;
+        // deferred pass on B: exclusive rows and lookahead rows are disjoint, so it may overlap the gather
+        rc = enqueue_class_pass(ctx, a, 1, sb, timing_pair(ctx, FS_TIME_UPDATE_EX));
+        if (rc != FS_OK) return rc;
+    }
+    FS_HIP(ctx, hipEventRecord(ctx->ev_ex, sb));
+    if (have_t1) {
+        rc = enqueue_gather(ctx, a, sp);
+        if (rc != FS_OK) return rc;
+    }
+    FS_HIP(ctx, hipStreamWaitEvent(sp, ctx->ev_ex, 0));
+    if (ctx->timing_now) ++ctx->timing_steps;
+    return FS_OK;
 }
 
 int fs_prioritized_step_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs_step_args *next, fs_stream stream) {
@@ -598,64 +712,51 @@ int fs_prioritized_step_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs
     }
     hipStream_t sp = as_stream(stream);
     begin_step_timing(ctx);
-    // Side stream A still runs what the previous call left there: the index half that produced the
-    // split of `cur`, then the previous deferred pass.  It is not waited for at the call boundary -
-    // the big kernels of consecutive iterations follow each other without a barrier packet - but
-    // once, right before the priority pass.  Cross-stream waits are the expensive host operation
-    // here (each makes the runtime flush the producer queue), so there are two per call: A waits
-    // for the reduce, `stream` waits for A.
+    // Side stream A still runs what the previous call left there (its deferred pass, the index half
+    // that produced the split and class order of `cur`).  It is waited for once, right before the
+    // priority pass.  Cross-stream waits are the expensive host operation here (each makes the
+    // runtime flush the producer queue): two per call - A waits for `stream` as it stands at the
+    // start of the call (the gradients), `stream` waits for A's previous job.
     const bool prev_side = ctx->side_pending;
     const int pp = ctx->pipe_parity, p = pp ^ 1;            // event set of the previous / this call
     const double h0 = now_us();
-    if (prev_side) {
-        rc = worker_wait(ctx);                               // host side only: its enqueueing is complete
-        if (rc != FS_OK) return rc;
+    fs_worker *w0 = (!ctx->capturing && ctx->use_worker) ? get_worker(ctx, 0) : nullptr;
+    if (ctx->host->worker[0]) {
+        rc = ctx->host->worker[0]->wait();                   // host side only: the previous job is enqueued
+        if (rc != FS_OK) return set_err(ctx, rc, "side-stream enqueue of the previous call failed");
     }
     const double h1 = now_us();
-    // The reduce overwrites cur->reduced: if the caller did not alternate that buffer, the
-    // previous deferred pass (which reads it) has to finish first.
-    bool joined_early = false;
-    if (prev_side && cur->reduced == ctx->prev_reduced) {
-        FS_HIP(ctx, hipStreamWaitEvent(sp, ctx->ev_side[pp], 0));
-        joined_early = true;
-    }
-    // Without a previous pipelined call the side stream forks from `stream`; otherwise its order
-    // after the previous deferred pass (which waited for the previous reduce) is all it needs.
-    hipEvent_t first_after = nullptr;
-    if (!ctx->red_valid) {
-        FS_HIP(ctx, hipEventRecord(ctx->ev_fork, sp));
-        first_after = ctx->ev_fork;
-    }
+    FS_HIP(ctx, hipEventRecord(ctx->ev_pfork[p], sp));
+    fs_ahead *ahead = (next && nxt_t1 && !ctx->capturing) ? find_ahead(ctx, next->u_t1) : nullptr;
+    if (ahead) ahead->unique = nullptr;                      // claimed: the side job frees the slot
     hipEvent_t *tex = have_t ? timing_pair(ctx, FS_TIME_UPDATE_EX) : nullptr;
-    const bool threaded = !ctx->capturing && ctx->use_worker &&
-                          worker_post(ctx, next, nxt_t, nxt_t1, have_t ? cur : nullptr, p, first_after, tex);
+    fs_step_args cur_copy = *cur, next_copy = next ? *next : *cur;
+    const bool has_next = next != nullptr;
+    auto side_job = [=]() -> int {
+        return enqueue_side_stream(ctx, have_t ? &cur_copy : nullptr, has_next ? &next_copy : nullptr, nxt_t, nxt_t1,
+                                   ahead, p, tex);
+    };
+    if (w0) w0->post(side_job);
     const double h2 = now_us();
     rc = FS_OK;
-    if (have_t) rc = enqueue_reduce(ctx, cur, sp);
-    if (rc == FS_OK && hipEventRecord(ctx->ev_red[p], sp) != hipSuccess) rc = FS_EHIP;
-    if (threaded) ctx->worker->red_recorded.store(true, std::memory_order_release);
-    ctx->red_valid = (rc == FS_OK) && !ctx->capturing;
-    const double h3 = now_us();
-    // from here on the split of `cur` is needed, and the rows the previous deferred pass wrote
-    // must be in place before the gather reads the table
-    if (rc == FS_OK && prev_side && !joined_early && hipStreamWaitEvent(sp, ctx->ev_side[pp], 0) != hipSuccess)
-        rc = FS_EHIP;
+    if (prev_side && hipStreamWaitEvent(sp, ctx->ev_side[pp], 0) != hipSuccess) rc = FS_EHIP;
     ctx->side_pending = false;
+    const double h3 = now_us();
+    if (rc == FS_OK && have_t) rc = enqueue_class_pass(ctx, cur, 0, sp, timing_pair(ctx, FS_TIME_UPDATE_CO));
+    if (rc == FS_OK && have_t1) rc = enqueue_gather(ctx, cur, sp);
     const double h4 = now_us();
-    if (rc == FS_OK) rc = enqueue_priority_and_gather(ctx, cur, have_t, have_t1, sp);
-    const double h5 = now_us();
-    if (!threaded && rc == FS_OK)
-        rc = enqueue_side_stream(ctx, next, nxt_t, nxt_t1, have_t ? cur : nullptr, p, first_after, nullptr, tex);
+    if (!w0) {
+        const int src = side_job();
+        if (rc == FS_OK) rc = src;
+    }
     if (ctx->timing_now) ++ctx->timing_steps;
-    ctx->host_us[0] += h1 - h0;      // waiting for the worker
-    ctx->host_us[1] += h2 - h1;      // posting the side-stream work
-    ctx->host_us[2] += h3 - h2;      // enqueueing the reduce, recording its event
-    ctx->host_us[3] += h4 - h3;      // waiting for the side stream
-    ctx->host_us[4] += h5 - h4;      // priority pass and gather
+    ctx->host_us[0] += h1 - h0;      // waiting for the side-stream thread
+    ctx->host_us[1] += h2 - h1;      // fork event, handing over the side work
+    ctx->host_us[2] += h3 - h2;      // wait for the previous side work
+    ctx->host_us[3] += h4 - h3;      // priority pass and gather
     ctx->host_us[6] += 1.0;
     ctx->pipe_parity = p;
-    ctx->prev_reduced = cur->reduced;
-    ctx->side_pending = (rc == FS_OK);
+    ctx->side_pending = true;        // also after a failure: a posted job still records its event
     // a captured graph must end with every stream joined
     if (ctx->capturing && rc == FS_OK) rc = join_pending_work(ctx, sp);
     return rc;
@@ -668,7 +769,14 @@ int fs_step_join(fs_ctx *ctx, fs_stream stream) {
 
 int fs_ctx_host_times(fs_ctx *ctx, double *out7_host, int reset) {
     if (!ctx || !out7_host) return FS_EINVAL;
-    (void)worker_wait(ctx);
+    (void)workers_wait(ctx);
+    for (int k = 0; k < 2; ++k) {
+        fs_worker *w = ctx->host->worker[k];
+        if (!w) continue;
+        std::lock_guard<std::mutex> lk(w->mu);
+        ctx->host_us[k == 0 ? 5 : 4] = w->busy_us;
+        if (reset) w->busy_us = 0.0;
+    }
     for (int i = 0; i < 7; ++i) out7_host[i] = ctx->host_us[i];
     if (reset)
         for (int i = 0; i < 7; ++i) ctx->host_us[i] = 0.0;
@@ -677,6 +785,7 @@ int fs_ctx_host_times(fs_ctx *ctx, double *out7_host, int reset) {
 
 int fs_ctx_set_threaded_enqueue(fs_ctx *ctx, int on) {
     if (!ctx) return FS_EINVAL;
+    (void)workers_wait(ctx);
     ctx->use_worker = on != 0;
     return FS_OK;
 }
@@ -688,12 +797,12 @@ int fs_graph_capture_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs_st
     if (!g) return FS_ENOMEM;
     g->graph = nullptr;
     g->exec = nullptr;
-    if (ctx->side_pending) {                                 // nothing from outside may leak into the capture
-        (void)worker_wait(ctx);
-        ctx->side_pending = false;
-        (void)hipStreamSynchronize(ctx->stream_a);
-    }
-    ctx->red_valid = false;
+    // nothing from outside may leak into the capture
+    (void)workers_wait(ctx);
+    ctx->side_pending = false;
+    (void)hipStreamSynchronize(ctx->stream_a);
+    (void)hipStreamSynchronize(ctx->stream_x[0]);
+    (void)hipStreamSynchronize(ctx->stream_x[1]);
     hipError_t e = hipStreamBeginCapture(ctx->stream_cap, hipStreamCaptureModeThreadLocal);
     if (e != hipSuccess) {
         delete g;

@@ -41,6 +41,15 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 }  // namespace fs
 
+// scratch of one dedup (radix sort + compaction); one set per stream that may run a dedup
+struct fs_sort_scratch {
+    uint64_t *keys[2];        // [max_ids] each (also used as uint32 keys)
+    int32_t *idx[2];          // [max_ids] each
+    uint32_t *tile_hist;      // [tiles * bins] per-tile digit counts
+    int32_t *tile_heads;      // [scan tiles] heads per compaction tile
+};
+constexpr int kSortSets = 3;  // 0: the caller's stream / side stream, 1 and 2: the two ahead-of-time index streams
+
 struct fs_ctx {
     int device;
     int64_t max_ids;
@@ -52,12 +61,7 @@ struct fs_ctx {
     size_t slab_bytes;
 
     int *d_flags;             // [4] device error flags
-    // sort
-    uint64_t *keys[2];        // [max_ids] each (also used as uint32 keys)
-    int32_t *idx[2];          // [max_ids] each
-    uint32_t *tile_hist;      // [tiles * 256] per-tile digit counts, then their exclusive prefix
-    uint32_t *digit_base;     // [256]
-    int32_t *tile_heads;      // [scan tiles] heads per compaction tile
+    fs_sort_scratch sort[kSortSets];
     // split
     uint8_t *split_flag_t;    // [max_ids]
     uint8_t *split_flag_t1;   // [max_ids]
@@ -66,23 +70,27 @@ struct fs_ctx {
     double *part_head;        // [chunks, max_dim] fp64 partial of the first run of each chunk
     double *part_last;        // [chunks, max_dim] fp64 partial of the last run of each chunk
     int32_t *chunk_desc;      // [chunks * 4]
+    // fused reduce+update, one set per class (0 = collision rows, 1 = exclusive rows) so that the
+    // priority pass of one iteration and the deferred pass of another may run side by side
+    double *fpart_head[2];    // [chunks, max_dim] piece of a cut segment that came in from the previous chunk
+    double *fpart_last[2];    // [chunks, max_dim] first piece of a cut segment that continues into the next chunk
+    int *fcounters[2];        // [chunks] pieces counted in per cut segment (indexed by its first chunk); rest at 0
+    // class order (scratch between the split launches and the scatter launch, same stream)
+    int32_t *cstart_local;    // [max_ids] occurrences of same-class rows before this row inside its split tile
+    int32_t *tile_len;        // [2 * scan tiles] occurrences per split tile: collision rows, then exclusive rows
     const int32_t *reduce_inverse;   // host-side: the caller's optional inverse map for the launch being enqueued
     int64_t *d_zero;          // device scalar that stays 0 (stands in for a missing lookahead)
 
-    hipStream_t stream_a;     // index work of the lookahead batch
-    hipStream_t stream_b;     // deferred update pass
-    hipEvent_t ev_fork, ev_split, ev_reduce, ev_co, ev_ex;
-    hipEvent_t ev_idx[2];     // (unused by the current schedule)
-    hipEvent_t ev_red[2];     // reduce of a pipelined call done on the caller's stream (alternating)
-    hipEvent_t ev_side[2];    // side-stream work of a pipelined call (index half of next, deferred pass of cur) done
+    hipStream_t stream_a;     // side stream: index half of the lookahead batch; deferred pass of a pipelined call
+    hipStream_t stream_b;     // deferred pass of the self-contained step
+    hipStream_t stream_x[2];  // ahead-of-time dedups, used in turn
+    hipEvent_t ev_fork, ev_split, ev_ex;   // self-contained step and fs_step_forward
+    hipEvent_t ev_pfork[2];   // position of the caller's stream at the start of a pipelined call (alternating)
+    hipEvent_t ev_side[2];    // side-stream work of a pipelined call (deferred pass of cur, index half of next) done
     int pipe_parity;          // event set used by the last pipelined call
     bool side_pending;        // host-side: side-stream work is in flight and not yet joined
-    bool red_valid;           // host-side: ev_red[pipe_parity] was recorded by the last pipelined call
-    const float *prev_reduced;   // host-side: reduced-gradient buffer of the last pipelined call
     double host_us[7];        // host-side time spent in the phases of the pipelined call (measurement aid)
-
-    // optional per-kernel timing of the step: events[(kind * slots + slot) * 2 + {0,1}]
-    struct fs_worker *worker; // second host thread that enqueues the index half (started on first use)
+    struct fs_host *host;     // host threads and the table of outstanding ahead-of-time dedups
     bool use_worker;
     hipStream_t stream_cap;   // capture stream of fs_graph_capture_pipelined
     bool capturing;           // host-side: a step is being recorded into a graph (no timing events)
@@ -142,11 +150,22 @@ inline hipEvent_t *timing_pair(fs_ctx *ctx, int kind) {
     return ctx->timing_events + ((size_t)kind * ctx->timing_slots + slot) * 2;
 }
 int launch_unique(fs_ctx *, const int64_t *ids, int64_t n, int64_t num_rows, int64_t *unique,
-                  int32_t *seg_offsets, int32_t *perm, int32_t *inverse, int64_t *n_unique_dev, hipStream_t s);
+                  int32_t *seg_offsets, int32_t *perm, int32_t *inverse, int64_t *n_unique_dev, hipStream_t s,
+                  int set = 0);
+// seg_offsets_t: optional; given, the per-tile occurrence counts that launch_class_order needs are left in
+// the context scratch
 int launch_split(fs_ctx *, const int64_t *u_t, const int64_t *n_t_dev, const int64_t *u_t1,
                  const int64_t *n_t1_dev, int64_t cap_t, int64_t cap_t1, int64_t *co, int32_t *co_slot,
                  int64_t *ex, int32_t *ex_slot, int64_t *ex_next, int32_t *ex_next_slot, int64_t *counts_dev,
-                 hipStream_t s);
+                 hipStream_t s, const int32_t *seg_offsets_t = nullptr);
+// right after launch_split(..., seg_offsets_t) on the same stream: occurrences of the batch in class order
+int launch_class_order(fs_ctx *, const int32_t *perm, const int32_t *inverse, const int32_t *seg_offsets, int64_t n,
+                       int64_t cap_u, int32_t *cperm, int32_t *cslot, int32_t *cstart, int32_t *class_pos_dev,
+                       hipStream_t s);
+int launch_reduce_update(fs_ctx *, int cls, const float *grads, int64_t n, int32_t dim, const int32_t *cperm,
+                         const int32_t *cslot, const int32_t *class_pos, const int32_t *seg_offsets,
+                         const int32_t *cstart, const int64_t *u_t, void *table, int dt, float *state,
+                         int64_t num_rows, float lr, float eps, float *reduced, hipStream_t s);
 // `timing`: optional event pair recorded around the main (chunk) kernel only
 int launch_reduce(fs_ctx *, const float *grads, int64_t n, int32_t dim, const int32_t *perm,
                   const int32_t *seg_offsets, const int64_t *n_unique_dev, float *reduced, hipStream_t s,

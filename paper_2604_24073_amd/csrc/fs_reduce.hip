@@ -13,6 +13,7 @@
 // rows, and a second launch adds the partials of each cut segment in a fixed order.  The
 // summation order depends on the layout alone: results are reproducible.
 #include "fs_common.h"
+#include "fs_device.h"
 
 namespace fs {
 
@@ -22,34 +23,6 @@ namespace fs {
 constexpr int kFixThreads = 1024;
 constexpr int kDescInts = 4;   // per chunk: first segment, number of flushes, last chunk of the cut segment that
                                // starts here (-1: none), flags
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-
-// x + (x of the lane 32 away) in every lane: one cross-half swap per 32-bit word, no LDS traffic
-__device__ __forceinline__ double add_xor32(double x) {
-    const unsigned lo = (unsigned)__double2loint(x), hi = (unsigned)__double2hiint(x);
-    const u32x2 a = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
-    const u32x2 b = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
-    return __hiloint2double((int)b[0], (int)a[0]) + __hiloint2double((int)b[1], (int)a[1]);
-}
-
-// x + (x of the lane 16 away) in every lane
-__device__ __forceinline__ double add_xor16(double x) {
-    const unsigned lo = (unsigned)__double2loint(x), hi = (unsigned)__double2hiint(x);
-    const u32x2 a = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
-    const u32x2 b = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
-    return __hiloint2double((int)b[0], (int)a[0]) + __hiloint2double((int)b[1], (int)a[1]);
-}
-
-// sum over the 64/LPR groups of a wavefront, result in every lane; fixed order
-template <int LPR>
-__device__ __forceinline__ double across_groups(double x) {
-    if (LPR == 32) return add_xor32(x);
-    if (LPR == 16) return add_xor32(add_xor16(x));
-#pragma unroll
-    for (int m = LPR; m < kWave; m <<= 1) x += __shfl_xor(x, m, kWave);
-    return x;
-}
-
 template <int LPR, int UNR, bool HAS_INV>
 __global__ __launch_bounds__(kReduceWavesPerBlock *kWave) void reduce_chunk_kernel(
     const f32x4 *__restrict__ grads, int n, int gvec, const int32_t *__restrict__ perm,

@@ -134,7 +134,8 @@ __global__ __launch_bounds__(kScanThreads) void split_compact_kernel(
     const int64_t *__restrict__ n_t1_dev, int64_t cap_t, int64_t cap_t1, int tiles_t, int tiles_t1,
     const uint8_t *__restrict__ flag_t, const uint8_t *__restrict__ flag_t1, const int32_t *__restrict__ tile_cnt,
     int64_t *__restrict__ co, int32_t *__restrict__ co_slot, int64_t *__restrict__ ex, int32_t *__restrict__ ex_slot,
-    int64_t *__restrict__ ex_next, int32_t *__restrict__ ex_next_slot, int64_t *__restrict__ counts_dev) {
+    int64_t *__restrict__ ex_next, int32_t *__restrict__ ex_next_slot, int64_t *__restrict__ counts_dev,
+    const int32_t *__restrict__ seg_offsets_t, int32_t *__restrict__ cstart_local, int32_t *__restrict__ tile_len) {
     __shared__ int sh[kScanThreads / kWave];
     const int n_t = clamp_count(n_t_dev, cap_t), n_t1 = clamp_count(n_t1_dev, cap_t1);
     const bool side_t = (int)blockIdx.x < tiles_t;
@@ -174,6 +175,33 @@ __global__ __launch_bounds__(kScanThreads) void split_compact_kernel(
             r_found += f[i] ? 1 : 0;
         }
     }
+    // For the class order of the batch: occurrences (segment lengths) of the same-class rows that
+    // precede each row inside this tile, and the tile's occurrence totals per class.
+    if (side_t && seg_offsets_t != nullptr) {
+        int len[kScanIpt];
+        int co_len = 0, ex_len = 0;
+#pragma unroll
+        for (int i = 0; i < kScanIpt; ++i) {
+            const int p = p0 + i;
+            len[i] = (p < n_mine) ? seg_offsets_t[p + 1] - seg_offsets_t[p] : 0;
+            co_len += f[i] ? len[i] : 0;
+            ex_len += f[i] ? 0 : len[i];
+        }
+        int co_total, ex_total;
+        int co_before = block_excl_scan_i(co_len, sh, co_total);
+        int ex_before = block_excl_scan_i(ex_len, sh, ex_total);
+#pragma unroll
+        for (int i = 0; i < kScanIpt; ++i) {
+            const int p = p0 + i;
+            if (p < n_mine) cstart_local[p] = f[i] ? co_before : ex_before;
+            co_before += f[i] ? len[i] : 0;
+            ex_before += f[i] ? 0 : len[i];
+        }
+        if (threadIdx.x == 0) {
+            tile_len[tile] = co_total;
+            tile_len[tiles_t + tile] = ex_total;
+        }
+    }
     // the last tile of side t knows |co|; |ex| and |ex_next| follow from the list lengths
     if (side_t && tile == tiles_t - 1 && threadIdx.x == 0) {
         const int n_co = found_before + tile_total;
@@ -181,6 +209,73 @@ __global__ __launch_bounds__(kScanThreads) void split_compact_kernel(
         counts_dev[1] = n_t - n_co;
         counts_dev[2] = n_t1 - n_co;
     }
+}
+
+// Class order of the occurrences of batch t: sorted position q (row slot s, the j-th occurrence of
+// that row) goes to  [start of the class] + [occurrences of same-class rows before s] + j.
+// Every workgroup first turns the per-tile totals into tile bases (a few hundred values).
+__global__ __launch_bounds__(kScanThreads) void class_scatter_kernel(
+    const int32_t *__restrict__ perm, const int32_t *__restrict__ inverse, const int32_t *__restrict__ seg_offsets,
+    int n, int tiles_t, const uint8_t *__restrict__ flag_t, const int32_t *__restrict__ cstart_local,
+    const int32_t *__restrict__ tile_len, int32_t *__restrict__ cperm, int32_t *__restrict__ cslot,
+    int32_t *__restrict__ cstart, int32_t *__restrict__ class_pos_dev, int *__restrict__ flags) {
+    extern __shared__ int tile_base[];                      // [2 * tiles_t]
+    __shared__ int sh[kScanThreads / kWave];
+    int class_total[2];
+    for (int c = 0; c < 2; ++c) {
+        int carry = 0;
+        for (int t0 = 0; t0 < tiles_t; t0 += kScanThreads) {
+            const int t = t0 + threadIdx.x;
+            const int v = (t < tiles_t) ? tile_len[c * tiles_t + t] : 0;
+            int total;
+            const int before = block_excl_scan_i(v, sh, total);
+            if (t < tiles_t) tile_base[c * tiles_t + t] = carry + before;
+            carry += total;
+        }
+        class_total[c] = carry;
+    }
+    __syncthreads();
+    const int n_co_pos = class_total[0];
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        class_pos_dev[0] = n_co_pos;
+        class_pos_dev[1] = n_co_pos + class_total[1];
+    }
+    const int q0 = blockIdx.x * kScanTile + threadIdx.x;
+    int i[kScanIpt], s[kScanIpt];
+#pragma unroll
+    for (int k = 0; k < kScanIpt; ++k) {
+        const int q = q0 + k * kScanThreads;
+        i[k] = (q < n) ? perm[q] : 0;
+    }
+#pragma unroll
+    for (int k = 0; k < kScanIpt; ++k) {
+        const int q = q0 + k * kScanThreads;
+        s[k] = (q < n) ? inverse[i[k]] : 0;
+    }
+#pragma unroll
+    for (int k = 0; k < kScanIpt; ++k) {
+        const int q = q0 + k * kScanThreads;
+        if (q < n) {
+            const int slot = s[k];
+            const bool is_co = flag_t[slot] != 0;
+            const int tile = slot / kScanTile;
+            const int first = seg_offsets[slot];
+            const int dest = (is_co ? tile_base[tile] : n_co_pos + tile_base[tiles_t + tile]) + cstart_local[slot] +
+                             (q - first);
+            if (dest < 0 || dest >= n) {                     // cannot happen with a consistent layout and split
+                atomicOr(flags, kFlagInternal);
+                continue;
+            }
+            cperm[dest] = i[k];
+            cslot[dest] = slot;
+            if (q == first) cstart[slot] = dest;
+        }
+    }
+}
+
+__global__ void class_empty_kernel(int32_t *class_pos_dev) {
+    class_pos_dev[0] = 0;
+    class_pos_dev[1] = 0;
 }
 
 __global__ void split_empty_kernel(const int64_t *n_t1_dev, int64_t cap_t1, int64_t *counts_dev) {
@@ -192,7 +287,7 @@ __global__ void split_empty_kernel(const int64_t *n_t1_dev, int64_t cap_t1, int6
 int launch_split(fs_ctx *ctx, const int64_t *u_t, const int64_t *n_t_dev, const int64_t *u_t1,
                  const int64_t *n_t1_dev, int64_t cap_t, int64_t cap_t1, int64_t *co, int32_t *co_slot,
                  int64_t *ex, int32_t *ex_slot, int64_t *ex_next, int32_t *ex_next_slot, int64_t *counts_dev,
-                 hipStream_t s) {
+                 hipStream_t s, const int32_t *seg_offsets_t) {
     const int tiles_t = (int)ceil_div(cap_t, kScanTile);
     const int tiles_t1 = (int)ceil_div(cap_t1, kScanTile);
     if (tiles_t == 0 && tiles_t1 == 0) {
@@ -207,8 +302,27 @@ int launch_split(fs_ctx *ctx, const int64_t *u_t, const int64_t *n_t_dev, const 
     hipLaunchKernelGGL(split_compact_kernel, dim3(tt + tiles_t1), dim3(kScanThreads), 0, s, u_t, n_t_dev, u_t1,
                        n_t1_dev, cap_t, cap_t1, tt, tiles_t1, (const uint8_t *)ctx->split_flag_t,
                        (const uint8_t *)ctx->split_flag_t1, (const int32_t *)ctx->split_cnt, co, co_slot, ex, ex_slot,
-                       ex_next, ex_next_slot, counts_dev);
+                       ex_next, ex_next_slot, counts_dev, seg_offsets_t, ctx->cstart_local, ctx->tile_len);
     FS_LAUNCH_CHECK(ctx, "split kernels");
+    return FS_OK;
+}
+
+int launch_class_order(fs_ctx *ctx, const int32_t *perm, const int32_t *inverse, const int32_t *seg_offsets,
+                       int64_t n, int64_t cap_u, int32_t *cperm, int32_t *cslot, int32_t *cstart,
+                       int32_t *class_pos_dev, hipStream_t s) {
+    if (n == 0) {
+        hipLaunchKernelGGL(class_empty_kernel, dim3(1), dim3(1), 0, s, class_pos_dev);
+        FS_LAUNCH_CHECK(ctx, "class_empty_kernel");
+        return FS_OK;
+    }
+    const int tiles_t = (int)ceil_div(cap_u, kScanTile);     // the same tiling launch_split used for side t
+    if ((size_t)tiles_t * 2 * sizeof(int) > 60 * 1024)
+        return set_err(ctx, FS_ERANGE, "class order: more than 7.8M distinct rows in one batch");
+    hipLaunchKernelGGL(class_scatter_kernel, dim3((unsigned)ceil_div(n, kScanTile)), dim3(kScanThreads),
+                       (size_t)tiles_t * 2 * sizeof(int), s, perm, inverse, seg_offsets, (int)n, tiles_t,
+                       (const uint8_t *)ctx->split_flag_t, (const int32_t *)ctx->cstart_local,
+                       (const int32_t *)ctx->tile_len, cperm, cslot, cstart, class_pos_dev, ctx->d_flags);
+    FS_LAUNCH_CHECK(ctx, "class_scatter_kernel");
     return FS_OK;
 }
 

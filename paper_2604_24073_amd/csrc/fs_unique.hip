@@ -285,45 +285,47 @@ __global__ void unique_empty_kernel(int32_t *seg_offsets, int64_t *n_unique_dev)
 // ---- host side ------------------------------------------------------------------------------------------
 template <typename K>
 static int unique_impl(fs_ctx *ctx, const int64_t *ids, int n, int key_bits, int64_t num_rows, int64_t *unique,
-                       int32_t *seg_offsets, int32_t *perm, int32_t *inverse, int64_t *n_unique_dev, hipStream_t s) {
+                       int32_t *seg_offsets, int32_t *perm, int32_t *inverse, int64_t *n_unique_dev, hipStream_t s,
+                       const fs_sort_scratch &ws) {
     const int tiles = (int)ceil_div(n, kSortTile);
     const int passes = (key_bits + kRadixBits - 1) / kRadixBits;
     const int bits = (key_bits + passes - 1) / passes;            // <= kRadixBits, evenly spread
-    K *kbuf[2] = {(K *)ctx->keys[0], (K *)ctx->keys[1]};
+    K *kbuf[2] = {(K *)ws.keys[0], (K *)ws.keys[1]};
     int cur = 0;   // buffer holding the input of the next pass (unused for the first pass)
     for (int p = 0; p < passes; ++p) {
         const int shift = p * bits;
         const bool last = (p == passes - 1);
         K *kout = kbuf[cur ^ 1];
-        int32_t *iout = last ? perm : ctx->idx[cur ^ 1];
+        int32_t *iout = last ? perm : ws.idx[cur ^ 1];
         if (p == 0) {
             hipLaunchKernelGGL((radix_hist_kernel<K, true>), dim3(tiles), dim3(kSortThreads), 0, s, ids,
-                               (const K *)nullptr, n, shift, bits, num_rows, ctx->tile_hist, ctx->d_flags);
+                               (const K *)nullptr, n, shift, bits, num_rows, ws.tile_hist, ctx->d_flags);
             hipLaunchKernelGGL((radix_scatter_kernel<K, true>), dim3(tiles), dim3(kSortThreads), 0, s, ids,
                                (const K *)nullptr, (const int32_t *)nullptr, kout, iout, n, shift, bits, tiles,
-                               (const uint32_t *)ctx->tile_hist);
+                               (const uint32_t *)ws.tile_hist);
         } else {
             hipLaunchKernelGGL((radix_hist_kernel<K, false>), dim3(tiles), dim3(kSortThreads), 0, s,
                                (const int64_t *)nullptr, (const K *)kbuf[cur], n, shift, bits, num_rows,
-                               ctx->tile_hist, ctx->d_flags);
+                               ws.tile_hist, ctx->d_flags);
             hipLaunchKernelGGL((radix_scatter_kernel<K, false>), dim3(tiles), dim3(kSortThreads), 0, s,
-                               (const int64_t *)nullptr, (const K *)kbuf[cur], (const int32_t *)ctx->idx[cur], kout,
-                               iout, n, shift, bits, tiles, (const uint32_t *)ctx->tile_hist);
+                               (const int64_t *)nullptr, (const K *)kbuf[cur], (const int32_t *)ws.idx[cur], kout,
+                               iout, n, shift, bits, tiles, (const uint32_t *)ws.tile_hist);
         }
         cur ^= 1;
     }
     const int stiles = (int)ceil_div(n, kScanTile);
     hipLaunchKernelGGL((unique_count_kernel<K>), dim3(stiles), dim3(kScanThreads), 0, s, (const K *)kbuf[cur], n,
-                       ctx->tile_heads);
+                       ws.tile_heads);
     hipLaunchKernelGGL((unique_compact_kernel<K>), dim3(stiles), dim3(kScanThreads), 0, s, (const K *)kbuf[cur],
-                       (const int32_t *)perm, n, (const int32_t *)ctx->tile_heads, unique, seg_offsets, inverse,
+                       (const int32_t *)perm, n, (const int32_t *)ws.tile_heads, unique, seg_offsets, inverse,
                        n_unique_dev);
     FS_LAUNCH_CHECK(ctx, "unique kernels");
     return FS_OK;
 }
 
 int launch_unique(fs_ctx *ctx, const int64_t *ids, int64_t n, int64_t num_rows, int64_t *unique,
-                  int32_t *seg_offsets, int32_t *perm, int32_t *inverse, int64_t *n_unique_dev, hipStream_t s) {
+                  int32_t *seg_offsets, int32_t *perm, int32_t *inverse, int64_t *n_unique_dev, hipStream_t s,
+                  int set) {
     if (n == 0) {
         hipLaunchKernelGGL(unique_empty_kernel, dim3(1), dim3(1), 0, s, seg_offsets, n_unique_dev);
         FS_LAUNCH_CHECK(ctx, "unique_empty_kernel");
@@ -336,9 +338,9 @@ int launch_unique(fs_ctx *ctx, const int64_t *ids, int64_t n, int64_t num_rows, 
     }
     if (key_bits <= 32)
         return unique_impl<uint32_t>(ctx, ids, (int)n, key_bits, num_rows, unique, seg_offsets, perm, inverse,
-                                     n_unique_dev, s);
+                                     n_unique_dev, s, ctx->sort[set]);
     return unique_impl<uint64_t>(ctx, ids, (int)n, key_bits, num_rows, unique, seg_offsets, perm, inverse,
-                                 n_unique_dev, s);
+                                 n_unique_dev, s, ctx->sort[set]);
 }
 
 }  // namespace fs

@@ -269,10 +269,130 @@ def test_adagrad_skips_out_of_range_rows(ctx):
     assert np.all(got[2] != 1.0) and np.all(np.delete(got, 2, axis=0) == 1.0)
 
 
+# ------------------------------------------------------------------------------------ class order, fused pass
+def class_order_from_oracle(layout, sp):
+    """Class order written out from the oracle's layout and split: collision rows' occurrences first,
+    then the exclusive rows'; inside a class by ascending row, inside a row in batch order."""
+    seg, perm = layout["seg_offsets"].astype(np.int64), layout["perm"]
+    cperm, cslot, cstart = [], [], np.zeros(len(layout["unique"]), np.int32)
+    pos = 0
+    n_class0 = 0
+    for slots in (sp["co_slot"], sp["ex_slot"]):
+        for s in slots:
+            cstart[s] = pos
+            cperm.append(perm[seg[s]:seg[s + 1]])
+            cslot.append(np.full(seg[s + 1] - seg[s], s, np.int32))
+            pos += seg[s + 1] - seg[s]
+        if slots is sp["co_slot"]:
+            n_class0 = pos
+    cat = lambda xs: np.concatenate(xs) if xs else np.empty(0, np.int32)
+    return cat(cperm), cat(cslot), cstart, [n_class0, pos]
+
+
+def gpu_layout_and_classes(ctx, ids_t, ids_t1, num_rows):
+    lay = fs.fs_unique_ids(ctx, dev(ids_t), num_rows)
+    if ids_t1 is None:
+        sp = fs.fs_collision_split_classes(ctx, lay, None, None, 0)
+    else:
+        lay1 = fs.fs_unique_ids(ctx, dev(ids_t1), num_rows)
+        sp = fs.fs_collision_split_classes(ctx, lay, lay1["unique"], lay1["n_unique"], len(ids_t1))
+    return lay, sp
+
+
+@pytest.mark.parametrize("n0,n1,rows", [(1, 1, 2), (50, 80, 40), (3000, 2500, 3000), (70000, 90000, 200000),
+                                        (5000, 0, 1000), (4096, 4096, 100)])
+def test_class_order_bit_exact(ctx, n0, n1, rows):
+    rng = np.random.default_rng(n0 * 7 + n1)
+    ids_t = zipf_ids(rng, n0, rows, a=1.1)
+    ids_t1 = zipf_ids(rng, n1, rows, a=1.1) if n1 else None
+    lay_o = O.unique_ids(ids_t, rows)
+    sp_o = O.collision_split(lay_o["unique"], O.unique_ids(ids_t1, rows)["unique"] if n1 else np.empty(0, np.int64))
+    want = class_order_from_oracle(lay_o, sp_o)
+    lay, sp = gpu_layout_and_classes(ctx, ids_t, ids_t1, rows)
+    assert fs.fs_check_async(ctx) == fs.FS_OK
+    assert sp["class_pos"].cpu().numpy().tolist() == want[3]
+    assert np.array_equal(sp["cperm"][:n0].cpu().numpy(), want[0])
+    assert np.array_equal(sp["cslot"][:n0].cpu().numpy(), want[1])
+    assert np.array_equal(sp["cstart"][:len(want[2])].cpu().numpy(), want[2])
+    for name in ("co", "ex"):
+        cnt = len(sp_o[name])
+        assert np.array_equal(sp[name][:cnt].cpu().numpy(), sp_o[name])
+
+
+def check_fused(ctx, rng, ids_t, ids_t1, rows, dim, dtype, n_passes=1):
+    table = rand_table(rng, rows, dim, dtype)
+    state = (rng.random(rows) * 0.1).astype(np.float32)
+    d_table, d_state = table_to_dev(table), dev(state)
+    t_ref, s_ref = table.copy(), state.copy()
+    for _ in range(n_passes):
+        grads = rng.standard_normal((len(ids_t), dim)).astype(np.float32)
+        lay_o = O.unique_ids(ids_t, rows)
+        red_o = O.segment_reduce_grads(grads, lay_o["perm"], lay_o["seg_offsets"])
+        u = len(lay_o["unique"])
+        O.rowwise_adagrad_update(t_ref, s_ref, lay_o["unique"], np.arange(u, dtype=np.int32), red_o, 0.02, 1e-8)
+        lay, sp = gpu_layout_and_classes(ctx, ids_t, ids_t1, rows)
+        reduced = torch.full((max(len(ids_t), 1), dim), float("nan"), dtype=torch.float32, device="cuda")
+        for cls in (1, 0):
+            fs.fs_reduce_update_class(ctx, cls, d_table, d_state, 0.02, 1e-8, dev(grads), lay, sp, reduced)
+        assert fs.fs_check_async(ctx) == fs.FS_OK
+        assert_close_f32(reduced[:u].cpu().numpy(), red_o, "reduced gradients of the fused pass")
+    assert_close_f32(d_state.cpu().numpy(), s_ref, "adagrad state after the fused passes")
+    assert_rows_close(table_to_host(d_table), t_ref, "rows after the fused passes")
+
+
+@pytest.mark.parametrize("dim,dtype", [(128, "f32"), (64, "f32"), (256, "f32"), (4, "f32"), (20, "f32"), (32, "f32"),
+                                       (128, "bf16"), (8, "bf16"), (256, "bf16"), (72, "bf16")])
+@pytest.mark.parametrize("n", [1, 63, 64, 65, 1000, 20011])
+def test_fused_pass_matches_oracle(ctx, dim, dtype, n):
+    rng = np.random.default_rng(dim * 31 + n)
+    rows = 3000
+    check_fused(ctx, rng, zipf_ids(rng, n, rows, a=1.15), zipf_ids(rng, n, rows, a=1.15), rows, dim, dtype)
+
+
+@pytest.mark.parametrize("dim,dtype", [(128, "f32"), (64, "f32"), (128, "bf16")])
+def test_fused_pass_long_segments_and_aligned_cuts(ctx, dim, dtype):
+    """One row with thousands of occurrences (its pieces are added by whoever arrives last),
+    segments that end exactly on a chunk border, a run of singletons; two launches in a row on the
+    same context (the piece counters must be back at zero)."""
+    rng = np.random.default_rng(9)
+    rows = 500
+    ids = np.concatenate([np.full(6000, 7), np.full(64, 8), np.full(128, 9), np.arange(100, 300),
+                          np.full(63, 10), np.full(1, 11), np.full(2500, 12), np.arange(300, 364)]).astype(np.int64)
+    ids = ids[rng.permutation(len(ids))]
+    nxt = np.array([7, 9, 12, 150, 151, 152, 320, 499], dtype=np.int64)
+    check_fused(ctx, rng, ids, nxt, rows, dim, dtype, n_passes=3)
+
+
+def test_fused_pass_without_lookahead_and_with_full_overlap(ctx):
+    rng = np.random.default_rng(10)
+    ids = zipf_ids(rng, 5000, 800, a=1.1)
+    check_fused(ctx, rng, ids, None, 800, 128, "f32")           # every row exclusive
+    check_fused(ctx, rng, ids, ids.copy(), 800, 128, "f32")     # every row a collision row
+
+
+def test_fused_pass_is_reproducible(ctx):
+    rng = np.random.default_rng(11)
+    rows, dim, n = 2000, 128, 30000
+    ids, ids1 = zipf_ids(rng, n, rows, a=1.05), zipf_ids(rng, n, rows, a=1.05)
+    grads = dev(rng.standard_normal((n, dim)).astype(np.float32))
+    table = rand_table(rng, rows, dim, "f32")
+    results = []
+    for _ in range(3):
+        d_table, d_state = table_to_dev(table), torch.zeros(rows, device="cuda")
+        lay, sp = gpu_layout_and_classes(ctx, ids, ids1, rows)
+        for cls in (0, 1):
+            fs.fs_reduce_update_class(ctx, cls, d_table, d_state, 0.01, 1e-8, grads, lay, sp)
+        assert fs.fs_check_async(ctx) == fs.FS_OK
+        results.append((d_table.cpu().numpy().tobytes(), d_state.cpu().numpy().tobytes()))
+    assert results[0] == results[1] == results[2]
+
+
 # ------------------------------------------------------------------------------------ whole step
-def run_steps_gpu(ctx, table, state, its, lr, eps, use_step_call=True):
+def run_steps_gpu(ctx, table, state, its, lr, eps, mode="step"):
     """Runs every iteration of `its` (list of fs_workloads.Iteration) on the GPU.
 
+    mode "step": fs_prioritized_step; "fused_calls": its building blocks one after another on one
+    stream; "five_ops": the five plain operations (unfused reduce, then the two Adagrad passes).
     Returns the device table/state and, per iteration, the outputs copied to the host."""
     d_table, d_state = table_to_dev(table), dev(state)
     num_rows = table.shape[0]
@@ -290,10 +410,20 @@ def run_steps_gpu(ctx, table, state, its, lr, eps, use_step_call=True):
         split = fs.alloc_split(n_t, n_t1, "cuda")
         reduced = torch.empty((max(n_t, 1), table.shape[1]), dtype=torch.float32, device="cuda")
         emb = None if last else torch.empty((n_t1, table.shape[1]), dtype=d_table.dtype, device="cuda")
-        if use_step_call:
+        if mode == "step":
             args = fs.make_step_args(d_table, d_state, lr, eps, layout, d_grads[t], None if last else d_vals[t + 1],
                                      None if last else d_offs[t + 1], layout_next, split, reduced, emb)
             fs.fs_prioritized_step(ctx, args)
+        elif mode == "fused_calls":
+            if not last:
+                fs.fs_unique_ids(ctx, d_vals[t + 1], num_rows, out=layout_next)
+            layout["n"] = n_t
+            fs.fs_collision_split_classes(ctx, layout, None if last else layout_next["unique"],
+                                          None if last else layout_next["n_unique"], n_t1, out=split)
+            for cls in (0, 1):
+                fs.fs_reduce_update_class(ctx, cls, d_table, d_state, lr, eps, d_grads[t], layout, split, reduced)
+            if not last:
+                fs.fs_gather_jagged(ctx, d_table, d_vals[t + 1], d_offs[t + 1], out=emb)
         else:
             if not last:
                 fs.fs_unique_ids(ctx, d_vals[t + 1], num_rows, out=layout_next)
@@ -355,7 +485,7 @@ def compare_runs(got_outs, want_outs, got_table, got_state, want_table, want_sta
     assert_rows_close(got_table, want_table, "final table")
 
 
-@pytest.mark.parametrize("use_step_call", [True, False])
+@pytest.mark.parametrize("use_step_call", ["step", "fused_calls", "five_ops"])
 def test_config0_tiny_full_run(ctx, use_step_call):
     cfg = CONFIGS[0]
     tab = cfg.tables[0]
@@ -374,7 +504,8 @@ def test_config0_tiny_full_run(ctx, use_step_call):
 
 @pytest.mark.parametrize("dtype,dim", [("f32", 128), ("bf16", 128), ("f32", 64), ("f32", 256)])
 def test_multi_iteration_schedule_matches_sequential_calls_bitwise(ctx, dtype, dim):
-    """The two-stream schedule and the five calls issued one after another give identical bits."""
+    """The two-stream schedule and its building blocks issued one after another give identical bits;
+    the five plain operations (unfused, other summation grouping) agree within the tolerance."""
     rng = np.random.default_rng(77)
     rows = 20000
     table = rand_table(rng, rows, dim, dtype)
@@ -391,8 +522,13 @@ def test_multi_iteration_schedule_matches_sequential_calls_bitwise(ctx, dtype, d
         it.values = zipf_ids(rng, int(it.offsets[-1]), rows, a=1.1)
         it.grads = rng.standard_normal((len(it.values), dim)).astype(np.float32)
         its.append(it)
-    ta, sa, oa = run_steps_gpu(ctx, table, state, its, 0.01, 1e-8, True)
-    tb, sb, ob = run_steps_gpu(ctx, table, state, its, 0.01, 1e-8, False)
+    ta, sa, oa = run_steps_gpu(ctx, table, state, its, 0.01, 1e-8, "step")
+    tb, sb, ob = run_steps_gpu(ctx, table, state, its, 0.01, 1e-8, "fused_calls")
+    tc, sc, oc = run_steps_gpu(ctx, table, state, its, 0.01, 1e-8, "five_ops")
+    assert_rows_close(table_to_host(tc), table_to_host(ta), "five plain operations vs step: table")
+    assert_close_f32(sc.cpu().numpy(), sa.cpu().numpy(), "five plain operations vs step: state")
+    for a, c in zip(oa[1:], oc[1:]):
+        assert_close_f32(c["reduced"], a["reduced"], "five plain operations vs step: reduced gradients")
     assert torch.equal(ta.view(torch.int16 if dtype == "bf16" else torch.int32),
                        tb.view(torch.int16 if dtype == "bf16" else torch.int32))
     assert torch.equal(sa, sb)

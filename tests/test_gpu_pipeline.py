@@ -1,5 +1,6 @@
 """The software-pipelined form of the step (index half of the next iteration beside the gradient
-half of the current one) must give exactly the bits of the five calls issued one after another."""
+half of the current one, dedups optionally batches ahead) must give exactly the bits of its
+building blocks issued one after another."""
 import numpy as np
 import pytest
 import torch
@@ -27,7 +28,10 @@ def make_its(rng, rows, dim, n_iter, users=40, max_len=300):
     return its
 
 
-def run_pipelined(ctx, table, state, its, lr, eps):
+def run_pipelined(ctx, table, state, its, lr, eps, ahead=False, sync_each=True):
+    """ahead: dedup every batch with fs_unique_ids_ahead, three batches before the iteration that
+    gathers it (five layout buffers in rotation).  sync_each=False: no wait between the calls."""
+    L = 5 if ahead else 3
     d_table, d_state = table_to_dev(table), dev(state)
     num_rows, dim = table.shape
     T = len(its)
@@ -36,31 +40,41 @@ def run_pipelined(ctx, table, state, its, lr, eps):
     d_grads = [dev(it.grads) for it in its]
     n = [v.numel() for v in d_vals]
     nmax = max(n)
-    layouts = [fs.alloc_layout(nmax, "cuda") for _ in range(3)]         # rotation of three
+    layouts = [fs.alloc_layout(nmax, "cuda") for _ in range(L)]
     splits = [fs.alloc_split(nmax, nmax, "cuda") for _ in range(3)]     # rotation of three
     reduced = [torch.empty((nmax, dim), dtype=torch.float32, device="cuda") for _ in range(2)]
     embs = [torch.empty((nmax, dim), dtype=d_table.dtype, device="cuda") for _ in range(2)]
 
     def args_for(t):
-        lay_t = dict(layouts[t % 3]); lay_t["n"] = n[t]
+        lay_t = dict(layouts[t % L]); lay_t["n"] = n[t]
         last = t == T - 1
         return fs.make_step_args(d_table, d_state, lr, eps, lay_t, d_grads[t], None if last else d_vals[t + 1],
-                                 None if last else d_offs[t + 1], None if last else layouts[(t + 1) % 3],
+                                 None if last else d_offs[t + 1], None if last else layouts[(t + 1) % L],
                                  splits[t % 3], reduced[t % 2], None if last else embs[t % 2])
+
+    def dedup_ahead(t):
+        if ahead and t < T:
+            fs.fs_unique_ids_ahead(ctx, d_vals[t], num_rows, layouts[t % L])
 
     fs.fs_unique_ids(ctx, d_vals[0], num_rows, out=layouts[0])
     all_args = [args_for(t) for t in range(T)]
+    dedup_ahead(1)
     fs.fs_step_forward(ctx, all_args[0])                          # primes the pipeline: layout 1, split 0
+    dedup_ahead(2)
     outs = []
     for t in range(T):
         nxt = all_args[t + 1] if t + 1 < T else None
+        dedup_ahead(t + 3)
         fs.fs_prioritized_step_pipelined(ctx, all_args[t], nxt)
+        if not sync_each:
+            continue
         assert fs.fs_check_async(ctx) == fs.FS_OK
-        u = int(layouts[t % 3]["n_unique"].item())
+        u = int(layouts[t % L]["n_unique"].item())
         rec = {"reduced": reduced[t % 2][:u].cpu().numpy(), "counts": splits[t % 3]["counts"].cpu().numpy()}
         if t + 1 < T:
             rec["emb_next"] = table_to_host(embs[t % 2][:n[t + 1]])
         outs.append(rec)
+    assert fs.fs_check_async(ctx) == fs.FS_OK
     return d_table, d_state, outs
 
 
@@ -73,7 +87,7 @@ def test_pipelined_steps_match_sequential_calls_bitwise(dtype, dim):
     state = np.zeros(rows, np.float32)
     its = make_its(rng, rows, dim, 7)
     tp, sp_, op = run_pipelined(ctx, table, state, its, 0.01, 1e-8)
-    ts, ss, os_ = run_steps_gpu(ctx, table, state, its, 0.01, 1e-8, use_step_call=False)
+    ts, ss, os_ = run_steps_gpu(ctx, table, state, its, 0.01, 1e-8, mode="fused_calls")
     view = torch.int16 if dtype == "bf16" else torch.int32
     assert torch.equal(tp.view(view), ts.view(view))
     assert torch.equal(sp_, ss)
@@ -84,6 +98,19 @@ def test_pipelined_steps_match_sequential_calls_bitwise(dtype, dim):
             assert a["emb_next"].tobytes() == b["emb_next"].tobytes()
     t_ref, s_ref, want = run_steps_oracle(table, state, its, 0.01, 1e-8)
     compare_runs(os_, want, table_to_host(ts), ss.cpu().numpy(), t_ref, s_ref)
+    # dedups batches ahead on the index streams, with and without waits between the calls, with and
+    # without the enqueueing threads: always the same bits
+    for ahead, sync_each, threaded in ((True, True, True), (True, False, True), (False, False, True),
+                                       (True, False, False), (False, True, False)):
+        ctx.lib.fs_ctx_set_threaded_enqueue(ctx.handle, 1 if threaded else 0)
+        ta, sa, oa = run_pipelined(ctx, table, state, its, 0.01, 1e-8, ahead=ahead, sync_each=sync_each)
+        what = f"ahead={ahead} sync_each={sync_each} threaded={threaded}"
+        assert torch.equal(ta.view(view), ts.view(view)), what
+        assert torch.equal(sa, ss), what
+        for a, b in zip(oa, os_[1:]):
+            assert a["reduced"].tobytes() == b["reduced"].tobytes(), what
+            if "emb_next" in a:
+                assert a["emb_next"].tobytes() == b["emb_next"].tobytes(), what
     ctx.close()
 
 
