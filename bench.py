@@ -2,8 +2,9 @@
 """Throughput of the whole prioritized-update step on one MI355X.
 
 A "step" is one pass of the full hot path over one batch: dedup of the lookahead IDs, collision
-split, gradient segment-reduce, priority (collision-row) Adagrad pass, deferred (exclusive-row)
-Adagrad pass on its own stream, and the jagged gather of the lookahead batch.  The workload is
+split and class order, priority pass (gradient segment-reduce fused with row-wise Adagrad on the
+collision rows), deferred pass (the same on the exclusive rows) on its own stream, and the jagged
+gather of the lookahead batch.  The workload is
 BASELINE configs[1] (one 4M x 128 fp32 table shard, batch 1024, power-law UIH lengths, Zipf(1.05)
 IDs); its two consecutive iterations are stepped back and forth (t=0 with lookahead 1, then t=1
 with lookahead 0, ...) so that every step consumes the layout the previous step produced, as in
@@ -48,6 +49,12 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--time-every", type=int, default=8,
                     help="bracket the kernels of one timed step in this many with HIP event pairs")
+    ap.add_argument("--no-ahead", action="store_true",
+                    help="pipelined mode: dedup the lookahead IDs inside the step call instead of batches ahead on "
+                         "the index streams")
+    ap.add_argument("--keep-reduced", action="store_true",
+                    help="also write the summed gradients to memory in the timed steps (the step itself does not "
+                         "need them there)")
     ap.add_argument("--mode", choices=["pipelined", "graph", "sequential"], default="pipelined",
                     help="pipelined (default): index half of step s+1 beside the gradient half of step s, "
                          "eager launches; graph: the same step replayed as a HIP graph (measured slower: the "
@@ -86,40 +93,54 @@ def main() -> int:
     d_offs = [torch.from_numpy(it.offsets).to(dev) for it in its]
     d_grads = [torch.from_numpy(it.grads).to(dev) for it in its]
 
-    # Buffers: layouts and splits rotate over three buffers, reduced gradients over two: the index half of
-    # step s+1 (writes layout s+2, split s+1) runs beside the gradient half of step s (reads
-    # layout s, split s).  The two batches alternate, so the argument records repeat with period 6.
+    # Buffers.  The index half of step s+1 runs beside the gradient half of step s, and with
+    # ahead-of-time dedups the layout of batch s+3 is being written meanwhile: five layout buffers
+    # in rotation (three without), three split/class buffers.  The two batches alternate, so the
+    # argument records repeat with period lcm(L, 3, 2).
+    pipelined = args.mode in ("pipelined", "graph")
+    ahead = args.mode == "pipelined" and not args.no_ahead
+    L = 5 if ahead else 3
+    period = 30 if ahead else 6
     nmax = max(n)
-    layouts = [fs.alloc_layout(nmax, dev) for _ in range(3)]
+    layouts = [fs.alloc_layout(nmax, dev) for _ in range(L)]
     splits = [fs.alloc_split(nmax, nmax, dev) for _ in range(3)]
     reduced = [torch.empty((nmax, dim), dtype=torch.float32, device=dev) for _ in range(2)]
     embs = [torch.empty((n[0], dim), dtype=tdtype, device=dev), torch.empty((n[1], dim), dtype=tdtype, device=dev)]
 
-    def args_for(s):
-        lay = dict(layouts[s % 3]); lay["n"] = n[s % 2]
+    def args_for(s, with_reduced):
+        lay = dict(layouts[s % L]); lay["n"] = n[s % 2]
         nb = (s + 1) % 2
         return fs.make_step_args(table, state, cfg.lr, cfg.eps, lay, d_grads[s % 2], d_vals[nb], d_offs[nb],
-                                 layouts[(s + 1) % 3], splits[s % 3], reduced[s % 2], embs[nb])
+                                 layouts[(s + 1) % L], splits[s % 3], reduced[s % 2] if with_reduced else None,
+                                 embs[nb])
 
-    step_args = [args_for(s) for s in range(6)]
+    check_args = [args_for(s, True) for s in range(period)]
+    step_args = check_args if args.keep_reduced else [args_for(s, False) for s in range(period)]
     fs.fs_unique_ids(ctx, d_vals[0], tab.num_rows, out=layouts[0])
-    pipelined = args.mode in ("pipelined", "graph")
     graphs = None
 
-    def run(k0, k):
+    def dedup_ahead(s):
+        if ahead:
+            fs.fs_unique_ids_ahead(ctx, d_vals[s % 2], tab.num_rows, layouts[s % L])
+
+    def run(k0, k, records=None):
+        records = records or step_args
         for s in range(k0, k0 + k):
             if graphs is not None:
-                fs.fs_graph_launch(ctx, graphs[s % 6])
+                fs.fs_graph_launch(ctx, graphs[s % period])
             elif pipelined:
-                fs.fs_prioritized_step_pipelined(ctx, step_args[s % 6], step_args[(s + 1) % 6])
+                dedup_ahead(s + 3)
+                fs.fs_prioritized_step_pipelined(ctx, records[s % period], records[(s + 1) % period])
             else:
-                fs.fs_prioritized_step(ctx, step_args[s % 6])
+                fs.fs_prioritized_step(ctx, records[s % period])
 
     # ---- one untimed step from the fresh table, checked against the oracle on the touched rows
     cpu_baseline = None
     if pipelined:
-        fs.fs_step_forward(ctx, step_args[0])          # primes the pipeline: layout 1, split 0
-    run(0, 1)
+        dedup_ahead(1)
+        fs.fs_step_forward(ctx, check_args[0])         # primes the pipeline: layout 1, split and class order 0
+        dedup_ahead(2)
+    run(0, 1, check_args)
     assert fs.fs_check_async(ctx) == fs.FS_OK, ctx.last_error()
     u = [int(layouts[0]["n_unique"].item()), int(layouts[1]["n_unique"].item())]
     counts0 = splits[0]["counts"].cpu().numpy().tolist()
@@ -157,7 +178,8 @@ def main() -> int:
 
     # the ping-pong continues with t=1 -> 0, then t=0 -> 1, ...
     if args.mode == "graph":
-        graphs = [fs.fs_graph_capture_pipelined(ctx, step_args[s], step_args[(s + 1) % 6]) for s in range(6)]
+        graphs = [fs.fs_graph_capture_pipelined(ctx, step_args[s], step_args[(s + 1) % period])
+                  for s in range(period)]
     run(1, args.warmup)
     torch.cuda.synchronize()
     k0 = 1 + args.warmup
@@ -175,7 +197,8 @@ def main() -> int:
     ht = fs.fs_ctx_host_times(ctx)
     host_phases = None
     if ht[6] > 0:
-        names = ("wait_worker", "post", "reduce", "events", "updates_gather", "worker_enqueue")
+        names = ("wait_side_thread", "fork_and_post", "wait_side_stream", "priority_and_gather",
+                 "index_thread_enqueue", "side_thread_enqueue")
         host_phases = {k: ht[i] / ht[6] for i, k in enumerate(names)}
     if graphs is not None:
         # Per-kernel durations cannot be bracketed inside a replayed graph: the same kernels are
@@ -187,8 +210,7 @@ def main() -> int:
         torch.cuda.synchronize()
         graphs = saved
 
-    kinds = {"reduce": fs.FS_TIME_REDUCE, "gather": fs.FS_TIME_GATHER, "update_co": fs.FS_TIME_UPDATE_CO,
-             "update_ex": fs.FS_TIME_UPDATE_EX}
+    kinds = {"gather": fs.FS_TIME_GATHER, "priority_pass": fs.FS_TIME_UPDATE_CO, "deferred_pass": fs.FS_TIME_UPDATE_EX}
     kernel_ms = {}
     for name, kind in kinds.items():
         vals = fs.fs_ctx_get_kernel_timing(ctx, kind, args.steps)
@@ -205,21 +227,40 @@ def main() -> int:
     step_bytes = sum(by[s % 2]["total"] for s in range(k0, k0 + args.steps)) / args.steps
     step_gbps = step_bytes / (ms_per_step * 1e-3) / 1e9
 
+    # Occurrences and rows per class of the two alternating iterations (split buffers of the last
+    # step and of the index half that followed it).
+    s_last = k0 + args.steps - 1
+    cls_pos, cls_rows = {}, {}
+    for s in (s_last, s_last + 1):
+        cp = splits[s % 3]["class_pos"].cpu().numpy().tolist()
+        cn = splits[s % 3]["counts"].cpu().numpy().tolist()
+        cls_pos[s % 2] = (cp[0], cp[1] - cp[0])
+        cls_rows[s % 2] = (cn[0], cn[1])
+
+    def class_pass_bytes(b, c):
+        # gradient rows + two index words per occurrence; row read+write, state read+write, row id per row
+        return cls_pos[b][c] * (dim * 4 + 8) + cls_rows[b][c] * (2 * dim * w + 8 + 8)
+
     # dominant kernel = the instrumented kernel with the longest average launch
-    gather_bytes = sum(by[s % 2]["gather"] for s in range(k0, k0 + args.steps)) / args.steps
-    reduce_bytes = sum(n[s % 2] * dim * 4 + 4 * n[s % 2] + 4 * u[s % 2] for s in range(k0, k0 + args.steps)) / args.steps
+    avg = lambda f: sum(f(s % 2) for s in range(k0, k0 + args.steps)) / args.steps
     cand = []
     if kernel_ms.get("gather"):
-        cand.append(("gather_kernel", kernel_ms["gather"], gather_bytes))
-    if kernel_ms.get("reduce"):
-        cand.append(("reduce_chunk_kernel", kernel_ms["reduce"], reduce_bytes))
+        cand.append(("gather_kernel", kernel_ms["gather"], avg(lambda b: by[b]["gather"])))
+    if kernel_ms.get("priority_pass"):
+        cand.append(("reduce_update_kernel (priority pass)", kernel_ms["priority_pass"],
+                     avg(lambda b: class_pass_bytes(b, 0))))
+    if kernel_ms.get("deferred_pass"):
+        cand.append(("reduce_update_kernel (deferred pass)", kernel_ms["deferred_pass"],
+                     avg(lambda b: class_pass_bytes(b, 1))))
     roofline = None
     if cand:
         name, ms, nbytes = max(cand, key=lambda c: c[1])
         achieved = nbytes / (ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": name, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None, "avg_launch_us": ms * 1e3,
-                    "algorithmic_bytes_per_launch": nbytes}
+                    "algorithmic_bytes_per_launch": nbytes,
+                    "all_kernels": {nm: {"avg_launch_us": m * 1e3, "algorithmic_bytes": nb,
+                                         "GBps": nb / (m * 1e-3) / 1e9} for nm, m, nb in cand}}
 
     out = {
         "metric": "unique embedding rows updated/sec + achieved HBM GB/s (% of peak), 1 GPU",
@@ -231,7 +272,8 @@ def main() -> int:
                                f"{cfg.length_rule} UIH lengths [{cfg.length_lo},{cfg.length_hi}], Zipf({tab.zipf_alpha}) IDs, "
                                "2 consecutive iterations stepped back and forth",
                    "ids_per_iteration": n, "unique_rows": u, "collision_rows_first_step": counts0[0]},
-        "schedule": args.mode, "host_enqueue_us_per_step": t_enq / args.steps * 1e6,
+        "schedule": args.mode + ("+dedup_ahead" if ahead else ""), "reduced_gradients_in_memory": bool(args.keep_reduced),
+        "class_occurrences": cls_pos, "class_rows": cls_rows, "host_enqueue_us_per_step": t_enq / args.steps * 1e6,
         "host_phase_us_per_step": host_phases,
         "step_algorithmic_bytes": step_bytes, "step_algorithmic_GBps": step_gbps,
         "step_frac_of_hbm_peak": step_gbps / HBM_PEAK_GBPS,

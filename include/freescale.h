@@ -141,14 +141,21 @@ int fs_rowwise_adagrad_update(fs_ctx *ctx, void *table, fs_dtype dt, float *stat
 
 /* ---- the fused update path of the whole iteration ------------------------------------------ */
 
-/* Class order of the occurrences of batch t (input of fs_reduce_update_class): the occurrences
- * of collision rows first (class 0), then those of exclusive rows (class 1); inside a class by
- * ascending row, inside a row in batch order.  Does fs_collision_split (same arguments, same
- * outputs) and then lays the batch out:
+/* Rows with at most this many occurrences in a batch take the short path of the fused update (all
+ * their gradient rows are requested at once by one group of lanes); rows with more go through the
+ * class order below. */
+#define FS_SHORT_SEGMENT 8
+
+/* Class order of the occurrences of batch t (input of fs_reduce_update_class), for the rows with
+ * more than FS_SHORT_SEGMENT occurrences: the occurrences of such collision rows first (class
+ * 0), then those of such exclusive rows (class 1); inside a class by ascending row, inside a row
+ * in batch order.  Does fs_collision_split (same arguments, same outputs) and then lays the
+ * batch out:
  *   cperm [n_t]          occurrence (row of G_t) at each class position
  *   cslot [n_t]          slot in u_t of the row at each class position
- *   cstart[cap_t]        class position of the first occurrence of u_t[k]
- *   class_pos_dev [2]    int32: number of class-0 positions, number of positions (n_t)
+ *   cstart[cap_t]        class position of the first occurrence of u_t[k] (rows in the class
+ *                        order only; other entries are unspecified)
+ *   class_pos_dev [2]    int32: number of class-0 positions, number of class positions
  * seg_offsets_t, perm_t, inverse_t: the layout of batch t as written by fs_unique_ids (all three
  * required); cap_t is also the capacity of cstart.  This is the prioritization of Section 3.2
  * carried down to the gradient rows: the priority pass reads only what collision rows need. */
@@ -159,19 +166,23 @@ int fs_collision_split_classes(fs_ctx *ctx, const int64_t *u_t, const int64_t *n
                                int64_t *ex_next, int32_t *ex_next_slot, int64_t *counts_dev, int32_t *cperm,
                                int32_t *cslot, int32_t *cstart, int32_t *class_pos_dev, fs_stream stream);
 
-/* update_embedding(I, G) of Algorithm 2 for one class of rows in one launch: the segment reduce
- * of fs_segment_reduce_grads and the Adagrad update of fs_rowwise_adagrad_update fused, same
+/* update_embedding(I, G) of Algorithm 2 for one class of rows: the segment reduce of
+ * fs_segment_reduce_grads and the Adagrad update of fs_rowwise_adagrad_update fused, same
  * arithmetic (fp64 sums in a fixed order, one rounding to fp32, then the update), restricted to
  * the rows of class `cls` (0: collision rows = priority pass, 1: exclusive rows = deferred
- * pass).  The summed gradients do not go through memory unless `reduced` (OPTIONAL, [n_unique,
- * dim] fp32) is given, in which case the rows of this class are also written there.
- * Launches of the two classes may run side by side on different streams; launches of the same
- * class on one context must be ordered. */
+ * pass).  rows / slots / n_rows_dev: the class's row list as fs_collision_split wrote it (co,
+ * co_slot, counts_dev + 0, or ex, ex_slot, counts_dev + 1).  Two launches: the short path over
+ * the row list (sorted layout perm / seg_offsets), the position-cut path over the class order.
+ * The summed gradients do not go through memory unless `reduced` (OPTIONAL, [n_unique, dim]
+ * fp32) is given, in which case the rows of this class are also written there.
+ * Calls for the two classes may run side by side on different streams; calls for the same class
+ * on one context must be ordered. */
 int fs_reduce_update_class(fs_ctx *ctx, int cls, void *table, fs_dtype dt, float *state, int64_t num_rows,
                            int32_t dim, float lr, float eps, const float *grads, int64_t n,
-                           const int64_t *u_t, const int32_t *seg_offsets, const int32_t *cperm,
-                           const int32_t *cslot, const int32_t *cstart, const int32_t *class_pos_dev,
-                           float *reduced, fs_stream stream);
+                           const int64_t *u_t, const int32_t *seg_offsets, const int32_t *perm,
+                           const int64_t *rows, const int32_t *slots, const int64_t *n_rows_dev,
+                           const int32_t *cperm, const int32_t *cslot, const int32_t *cstart,
+                           const int32_t *class_pos_dev, float *reduced, fs_stream stream);
 
 /* ---- one whole iteration ------------------------------------------------------------------ */
 

@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libfreescale_hip.so")
 FS_F32, FS_BF16 = 0, 1
 FS_OK, FS_EINVAL, FS_ENOMEM, FS_EHIP, FS_ENOTIMPL, FS_ERANGE = 0, -1, -2, -3, -4, -5
 FS_MAX_DIM = 256
+FS_SHORT_SEGMENT = 8
 
 c_i64, c_i32, c_vp, c_f = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_float
 
@@ -76,7 +77,8 @@ def load_library() -> ctypes.CDLL:
                                                       c_i64, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp,
                                                       c_vp, c_vp, S]),
         "fs_reduce_update_class": (ctypes.c_int, [c_vp, ctypes.c_int, c_vp, ctypes.c_int, c_vp, c_i64, c_i32, c_f, c_f,
-                                                  c_vp, c_i64, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, S]),
+                                                  c_vp, c_i64, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp,
+                                                  c_vp, c_vp, S]),
         "fs_unique_ids_ahead": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i64, c_vp, c_vp, c_vp, c_vp, c_vp, S]),
         "fs_prioritized_step": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args), S]),
         "fs_step_forward": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args), S]),
@@ -262,7 +264,9 @@ def fs_reduce_update_class(ctx: Context, cls: int, table: torch.Tensor, state: t
     n, dim = grads.shape
     rc = ctx.lib.fs_reduce_update_class(
         ctx.handle, cls, _ptr(table), table_dtype_code(table), _ptr(state), table.shape[0], dim, lr, eps,
-        _ptr(grads), n, _ptr(layout_t["unique"]), _ptr(layout_t["seg_offsets"]), _ptr(split["cperm"]),
+        _ptr(grads), n, _ptr(layout_t["unique"]), _ptr(layout_t["seg_offsets"]), _ptr(layout_t["perm"]),
+        _ptr(split["co" if cls == 0 else "ex"]), _ptr(split["co_slot" if cls == 0 else "ex_slot"]),
+        split["counts"].data_ptr() + 8 * cls, _ptr(split["cperm"]),
         _ptr(split["cslot"]), _ptr(split["cstart"]), _ptr(split["class_pos"]), _ptr(reduced), _stream(stream))
     ctx.check(rc, "fs_reduce_update_class")
 

@@ -123,10 +123,12 @@ void carve(fs_ctx *c, char *base, size_t *total) {
     c->part_head = cv.take<double>(chunks * (size_t)c->max_dim);
     c->part_last = cv.take<double>(chunks * (size_t)c->max_dim);
     c->chunk_desc = cv.take<int32_t>(chunks * 4);
+    const size_t fchunks = (size_t)ceil_div(c->max_ids, kFusedMinChunk) + 2;
     for (int k = 0; k < 2; ++k) {
-        c->fpart_head[k] = cv.take<double>(chunks * (size_t)c->max_dim);
-        c->fpart_last[k] = cv.take<double>(chunks * (size_t)c->max_dim);
-        c->fcounters[k] = cv.take<int>(chunks);
+        c->fpart_head[k] = cv.take<double>(fchunks * (size_t)c->max_dim);
+        c->fpart_last[k] = cv.take<double>(fchunks * (size_t)c->max_dim);
+        c->fcounters[k] = cv.take<int>(fchunks);
+        c->fcounters_sup[k] = cv.take<int>(fchunks);
     }
     c->cstart_local = cv.take<int32_t>(n + 16);
     c->tile_len = cv.take<int32_t>(2 * scan_tiles);
@@ -179,8 +181,11 @@ int fs_ctx_create(fs_ctx **out, int device, int64_t max_ids, int32_t max_dim) {
     size_t total;
     carve(c, static_cast<char *>(c->slab), &total);
     bool ok = hipMemset(c->slab, 0, 4096) == hipSuccess;
-    for (int k = 0; k < 2; ++k)
-        ok = ok && hipMemset(c->fcounters[k], 0, ((size_t)ceil_div(c->max_ids, kReduceChunk) + 2) * sizeof(int)) == hipSuccess;
+    for (int k = 0; k < 2; ++k) {
+        const size_t bytes = ((size_t)ceil_div(c->max_ids, kFusedMinChunk) + 2) * sizeof(int);
+        ok = ok && hipMemset(c->fcounters[k], 0, bytes) == hipSuccess;
+        ok = ok && hipMemset(c->fcounters_sup[k], 0, bytes) == hipSuccess;
+    }
     c->host = new (std::nothrow) fs_host();
     ok = ok && c->host != nullptr;
     hipStream_t *streams[] = {&c->stream_a, &c->stream_b, &c->stream_cap, &c->stream_x[0], &c->stream_x[1]};
@@ -502,7 +507,9 @@ int enqueue_class_pass(fs_ctx *ctx, const fs_step_args *a, int cls, hipStream_t 
     if (timing) (void)hipEventRecord(timing[0], s);
     const int rc = launch_reduce_update(ctx, cls, a->grads_t, a->n_t, a->dim, a->cperm, a->cslot, a->class_pos_dev,
                                         a->seg_offsets_t, a->cstart, a->u_t, a->table, a->dtype, a->state,
-                                        a->num_rows, a->lr, a->eps, a->reduced, s);
+                                        a->num_rows, a->lr, a->eps, a->reduced, s, a->perm_t,
+                                        cls == 0 ? a->co : a->ex, cls == 0 ? a->co_slot : a->ex_slot,
+                                        a->counts_dev + cls);
     if (timing && rc == FS_OK) (void)hipEventRecord(timing[1], s);
     return rc;
 }
@@ -590,8 +597,10 @@ int fs_collision_split_classes(fs_ctx *ctx, const int64_t *u_t, const int64_t *n
 
 int fs_reduce_update_class(fs_ctx *ctx, int cls, void *table, fs_dtype dt, float *state, int64_t num_rows,
                            int32_t dim, float lr, float eps, const float *grads, int64_t n, const int64_t *u_t,
-                           const int32_t *seg_offsets, const int32_t *cperm, const int32_t *cslot,
-                           const int32_t *cstart, const int32_t *class_pos_dev, float *reduced, fs_stream stream) {
+                           const int32_t *seg_offsets, const int32_t *perm, const int64_t *rows,
+                           const int32_t *slots, const int64_t *n_rows_dev, const int32_t *cperm,
+                           const int32_t *cslot, const int32_t *cstart, const int32_t *class_pos_dev, float *reduced,
+                           fs_stream stream) {
     if (!ctx) return FS_EINVAL;
     FS_REQUIRE(ctx, cls == 0 || cls == 1, "reduce+update: class must be 0 or 1");
     FS_REQUIRE(ctx, dt == FS_F32 || dt == FS_BF16, "reduce+update: unknown dtype");
@@ -600,10 +609,12 @@ int fs_reduce_update_class(fs_ctx *ctx, int cls, void *table, fs_dtype dt, float
     if (n > ctx->max_ids || dim > ctx->max_dim)
         return set_err(ctx, FS_ENOMEM, "reduce+update: beyond the context capacity");
     if (n == 0) return FS_OK;
-    FS_REQUIRE(ctx, table && state && grads && u_t && seg_offsets && cperm && cslot && cstart && class_pos_dev,
+    FS_REQUIRE(ctx, table && state && grads && u_t && seg_offsets && perm && rows && slots && n_rows_dev && cperm &&
+                        cslot && cstart && class_pos_dev,
                "reduce+update: null pointer");
     return launch_reduce_update(ctx, cls, grads, n, dim, cperm, cslot, class_pos_dev, seg_offsets, cstart, u_t, table,
-                                dt, state, num_rows, lr, eps, reduced, as_stream(stream));
+                                dt, state, num_rows, lr, eps, reduced, as_stream(stream), perm, rows, slots,
+                                n_rows_dev);
 }
 
 int fs_unique_ids_ahead(fs_ctx *ctx, const int64_t *ids, int64_t n, int64_t num_rows, int64_t *unique,

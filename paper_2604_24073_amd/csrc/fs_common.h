@@ -30,6 +30,7 @@ constexpr int kScanTile = kScanThreads * kScanIpt;
 // entry per lane).  Short chunks = many wavefronts with short dependent-load chains.
 constexpr int kReduceChunk = 64;
 constexpr int kReduceWavesPerBlock = 4;
+constexpr int kFusedMinChunk = 16;                        // smallest chunk the fused pass may be built with
 
 // device-side error flag bits (ctx->d_flags[0])
 constexpr int kFlagRowRange = 1;
@@ -74,7 +75,8 @@ struct fs_ctx {
     // priority pass of one iteration and the deferred pass of another may run side by side
     double *fpart_head[2];    // [chunks, max_dim] piece of a cut segment that came in from the previous chunk
     double *fpart_last[2];    // [chunks, max_dim] first piece of a cut segment that continues into the next chunk
-    int *fcounters[2];        // [chunks] pieces counted in per cut segment (indexed by its first chunk); rest at 0
+    int *fcounters[2];        // [chunks] arrivals per cut segment (indexed by its first chunk); at 0 between launches
+    int *fcounters_sup[2];    // [chunks] arrivals per group of sixteen pieces (indexed by its first chunk)
     // class order (scratch between the split launches and the scatter launch, same stream)
     int32_t *cstart_local;    // [max_ids] occurrences of same-class rows before this row inside its split tile
     int32_t *tile_len;        // [2 * scan tiles] occurrences per split tile: collision rows, then exclusive rows
@@ -165,7 +167,8 @@ int launch_class_order(fs_ctx *, const int32_t *perm, const int32_t *inverse, co
 int launch_reduce_update(fs_ctx *, int cls, const float *grads, int64_t n, int32_t dim, const int32_t *cperm,
                          const int32_t *cslot, const int32_t *class_pos, const int32_t *seg_offsets,
                          const int32_t *cstart, const int64_t *u_t, void *table, int dt, float *state,
-                         int64_t num_rows, float lr, float eps, float *reduced, hipStream_t s);
+                         int64_t num_rows, float lr, float eps, float *reduced, hipStream_t s, const int32_t *perm,
+                         const int64_t *rows, const int32_t *slots, const int64_t *n_rows_dev);
 // `timing`: optional event pair recorded around the main (chunk) kernel only
 int launch_reduce(fs_ctx *, const float *grads, int64_t n, int32_t dim, const int32_t *perm,
                   const int32_t *seg_offsets, const int64_t *n_unique_dev, float *reduced, hipStream_t s,

@@ -7,23 +7,45 @@
 // class by ascending row, inside a row in batch order).  A launch walks the positions of its
 // class only, so the priority pass reads exactly the gradient rows of collision rows.
 //
-// Work is cut by POSITION (row popularity is Zipf, the hottest row has tens of thousands of
+// Rows with at most FS_SHORT_SEGMENT occurrences (the vast majority of rows) take the short path:
+// one group of lanes per row requests all gradient rows of its segment and the table row at once,
+// adds, updates, stores - four short dependent rounds, no LDS, nothing shared.  Only rows with more
+// occurrences go through the class order and the position-cut path below.
+//
+// There work is cut by POSITION (row popularity is Zipf, the hottest row has tens of thousands of
 // occurrences): one wavefront owns 64 consecutive class positions, streams their gradient rows
 // (16 bytes per lane, 64/LPR rows per instruction) into fp64 accumulators and, whenever a segment
 // ends, parks the finished sum (rounded once to fp32) in LDS.  Parked rows are updated in rounds
 // of eight or more, so the dependent loads of the update (table row, accumulator) of many rows
 // are in flight together.  A segment cut by a chunk border leaves fp64 partial rows; every
 // wavefront that contributed one counts itself in at the segment's counter, and the one that
-// arrives last adds the partials in chunk order and updates the row.  No wavefront ever waits for
-// another, and the order of every floating-point sum depends on the layout alone.
+// arrives last adds the partials in chunk order and updates the row - in two levels for the hot
+// rows (sixteen pieces at a time, then the sums of those), so that the last arriver of a row with
+// tens of thousands of occurrences has two short rounds of loads to do, not dozens.  No wavefront
+// ever waits for another, and the order of every floating-point sum depends on the layout alone.
+//
+// The pieces travel between wavefronts (possibly on different XCDs, each with its own L2) as
+// device-scope relaxed atomic stores and loads, which go through to the coherent level, ordered
+// against the counter by waiting for the stores to be acknowledged.  A device-scope fence would
+// do the same but writes back the whole dirty L2 every time - measured 10x the kernel's time.
 #include "fs_common.h"
 #include "fs_device.h"
 
 namespace fs {
 
+// build-time tuning knobs: row-group loads one wavefront issues per round; class positions per
+// wavefront in the priority / deferred pass (64, 32 or 16: collision rows have long segments,
+// exclusive rows short ones, and a short chunk means more wavefronts with shorter lives)
 #ifndef FS_FUSED_UNR
-#define FS_FUSED_UNR 4
+#define FS_FUSED_UNR 8
 #endif
+#ifndef FS_FUSED_CHUNK_CO
+#define FS_FUSED_CHUNK_CO 64
+#endif
+#ifndef FS_FUSED_CHUNK_EX
+#define FS_FUSED_CHUNK_EX 32
+#endif
+constexpr int kFusedSuper = 16;            // pieces of a cut segment that are added in one go (first level)
 constexpr int kFusedWaves = 4;             // wavefronts per workgroup (they never synchronise)
 constexpr int kFusedRound = 8;             // parked rows that trigger an update round
 
@@ -105,21 +127,30 @@ __device__ __forceinline__ void update_parked(const f32x4 *stage, const int64_t 
     }
 }
 
-// t += part[c] for c = c_begin, c_begin + stride, ... <= c_last (eight rows requested per round)
+__device__ __forceinline__ void store_piece(double *dst, const double (&t)[4]) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) __hip_atomic_store(dst + c, t[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ double load_piece(const double *src) {
+    return __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// t += part[c] for c = c_begin, c_begin + stride, ... <= c_last (four rows requested per round)
 __device__ __forceinline__ void add_partial_rows(double (&t)[4], const double *part, int dim, int lig, bool col_ok,
                                                  int c_begin, int c_last, int stride) {
-    for (int c = c_begin; c <= c_last; c += 8 * stride) {
-        double h[8][4];
+    for (int c = c_begin; c <= c_last; c += 4 * stride) {
+        double h[4][4];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < 4; ++j) {
             const int cj = c + j * stride;
             const bool ok = col_ok && cj <= c_last;
             const double *src = part + (int64_t)(ok ? cj : c_begin) * dim + lig * 4;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) h[j][i] = ok ? src[i] : 0.0;
+            for (int i = 0; i < 4; ++i) h[j][i] = ok ? load_piece(src + i) : 0.0;
         }
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int i = 0; i < 4; ++i) t[i] += h[j][i];
     }
@@ -132,19 +163,20 @@ __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <bool BF16, int LPR, int UNR>
-__global__ __launch_bounds__(kFusedWaves *kWave) void reduce_update_kernel(
+template <bool BF16, int LPR, int UNR, int CHUNK>
+__global__ __launch_bounds__(kFusedWaves *kWave) __attribute__((amdgpu_waves_per_eu(4, 4))) void reduce_update_kernel(
     const f32x4 *__restrict__ grads, const int32_t *__restrict__ cperm, const int32_t *__restrict__ cslot,
     const int32_t *__restrict__ class_pos, int cls, int n, const int32_t *__restrict__ seg_offsets,
     const int32_t *__restrict__ cstart, const int64_t *__restrict__ u_t, void *table, float *state, int64_t num_rows,
-    int gvec, float lr, float eps, f32x4 *reduced, double *part_head, double *part_last, int *counters, int *flags) {
+    int gvec, float lr, float eps, f32x4 *reduced, double *part_head, double *part_last, int *cnt_seg, int *cnt_sup,
+    int *flags) {
     constexpr int GPW = kWave / LPR;          // rows per wavefront instruction
     constexpr int BP = GPW * UNR;             // positions per batch
-    constexpr int NB = kWave / BP;            // batches per chunk
+    constexpr int NB = CHUNK / BP;            // batches per chunk
     constexpr int ROUND = GPW > kFusedRound ? GPW : kFusedRound;
     constexpr int CAP = ROUND + BP;           // a batch can park BP more rows before the next check
     constexpr int RU = (ROUND / GPW) < 4 ? ((ROUND / GPW) < 1 ? 1 : (ROUND / GPW)) : 4;
-    static_assert(kWave % BP == 0, "whole batches");
+    static_assert(CHUNK <= kWave && CHUNK % BP == 0, "one tail word, whole batches");
     __shared__ f32x4 stage[kFusedWaves][CAP * LPR];
     __shared__ int64_t stage_row[kFusedWaves][CAP];
     __shared__ int stage_slot[kFusedWaves][CAP];
@@ -160,10 +192,10 @@ __global__ __launch_bounds__(kFusedWaves *kWave) void reduce_update_kernel(
     if (lo < 0) lo = 0;
     if (hi > n) hi = n;
     const int chunk = blockIdx.x * kFusedWaves + wib;        // chunk number inside the class
-    const int64_t a64 = (int64_t)lo + (int64_t)chunk * kWave;
+    const int64_t a64 = (int64_t)lo + (int64_t)chunk * CHUNK;
     if (a64 >= hi) return;                                   // wave-uniform; wavefronts share nothing
     const int a = (int)a64;
-    const int b = (a + kWave < hi) ? a + kWave : hi;
+    const int b = (a + CHUNK < hi) ? a + CHUNK : hi;
     const int span = b - a;
     const bool col_ok = lig < gvec;
     const int dim = gvec * 4;
@@ -199,18 +231,14 @@ __global__ __launch_bounds__(kFusedWaves *kWave) void reduce_update_kernel(
     int nflush = 0;
     int nparked = 0;
     bool oob = false;
-    const int n_chunks = (n + kWave - 1) / kWave;
+    const int n_chunks = (n + CHUNK - 1) / CHUNK;
 
     auto flush = [&](int q) {                                 // the segment that ends at chunk position q
         double t[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) t[c] = across_groups<LPR>(acc[c]);
         if (nflush == 0 && !head_complete) {
-            if (grp == 0 && col_ok) {
-                double *dst = part_head + (int64_t)chunk * dim + lig * 4;
-#pragma unroll
-                for (int c = 0; c < 4; ++c) dst[c] = t[c];
-            }
+            if (grp == 0 && col_ok) store_piece(part_head + (int64_t)chunk * dim + lig * 4, t);
         } else {
             if (grp == 0 && col_ok)
                 stage[wib][nparked * LPR + lig] = f32x4{(float)t[0], (float)t[1], (float)t[2], (float)t[3]};
@@ -264,8 +292,10 @@ __global__ __launch_bounds__(kFusedWaves *kWave) void reduce_update_kernel(
         const bool last = (k + 1 == NB) || ((k + 1) * BP >= span);
         if (nparked >= ROUND || (last && nparked > 0)) {
             wave_lds_sync();
+#ifndef FS_EXP_NO_UPDATE
             update_parked<BF16, LPR, RU>(stage[wib], stage_row[wib], stage_slot[wib], nparked, table, state, num_rows,
                                          gvec, lr, eps, reduced, oob);
+#endif
             wave_lds_sync();
             nparked = 0;
         }
@@ -280,43 +310,67 @@ __global__ __launch_bounds__(kFusedWaves *kWave) void reduce_update_kernel(
         if (grp == 0 && col_ok) {
             // a chunk wholly inside one segment is a middle piece (head buffer); otherwise this
             // chunk is the FIRST piece of the segment that continues (last buffer)
-            double *dst = ((nflush == 0 && !head_complete) ? part_head : part_last) + (int64_t)chunk * dim + lig * 4;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) dst[c] = t[c];
+            store_piece(((nflush == 0 && !head_complete) ? part_head : part_last) + (int64_t)chunk * dim + lig * 4, t);
         }
     }
 
     // Count this chunk in at every cut segment it holds a piece of (at most two: the one that came
-    // in from the left, the one that leaves to the right).  The last piece to arrive finishes the row.
+    // in from the left, the one that leaves to the right).  A cut segment that starts in chunk f
+    // and ends in chunk l has its first piece in part_last[f] and one piece in part_head[c] for
+    // every c in (f, l].  Those are grouped sixteen at a time ("supers", the j-th starts at chunk
+    // f+1+16j): the last piece of a super to arrive adds the super up (chunk order) and leaves the
+    // sum in the super's first slot; the last of {first piece, supers} to arrive adds those up
+    // (same order) and updates the row.
     const bool head_cut = !head_complete;
     const bool tail_cut = has_rest && (nflush > 0 || head_complete);
     const int s_last = __shfl(sl, span - 1, kWave);
 #pragma unroll 1
     for (int which = 0; which < 2; ++which) {
+#ifdef FS_EXP_NO_FINISH
+        break;
+#endif
         if (!(which == 0 ? head_cut : tail_cut)) continue;    // wave-uniform
         const int s = which == 0 ? s_first : s_last;
         const int start = cstart[s];
         const int len = seg_offsets[s + 1] - seg_offsets[s];
-        const int c_first = (start - lo) / kWave;
-        const int c_last = (start + len - 1 - lo) / kWave;
-        if (start < lo || c_first > chunk || c_last < chunk || c_last >= n_chunks) {
+        const int c_first = (start - lo) / CHUNK;
+        const int c_last = (start + len - 1 - lo) / CHUNK;
+        if (start < lo || c_first > chunk || c_last < chunk || c_last >= n_chunks || c_last == c_first ||
+            (which == 0) != (chunk > c_first)) {
             bad = true;
             continue;
         }
-        __threadfence();                                      // my partial rows before my count
         int old = 0;
-        if (lane == 0) old = atomicAdd(&counters[c_first], 1);
+        if (which == 0) {
+            // a piece of a super
+            const int sup_first = c_first + 1 + ((chunk - c_first - 1) / kFusedSuper) * kFusedSuper;
+            const int sup_last = (sup_first + kFusedSuper - 1 < c_last) ? sup_first + kFusedSuper - 1 : c_last;
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // my piece is acknowledged before I count myself in
+            if (lane == 0)
+                old = __hip_atomic_fetch_add(&cnt_sup[sup_first], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            old = __builtin_amdgcn_readfirstlane(old);
+            if (old != sup_last - sup_first) continue;        // wave-uniform
+            if (lane == 0) __hip_atomic_store(&cnt_sup[sup_first], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            double t[4] = {0.0, 0.0, 0.0, 0.0};
+            add_partial_rows(t, part_head, dim, lig, col_ok, sup_first + grp, sup_last, GPW);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) t[i] = across_groups<LPR>(t[i]);
+            if (grp == 0 && col_ok) store_piece(part_head + (int64_t)sup_first * dim + lig * 4, t);
+        }
+        const int n_sup = (c_last - c_first + kFusedSuper - 1) / kFusedSuper;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        old = 0;
+        if (lane == 0) old = __hip_atomic_fetch_add(&cnt_seg[c_first], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         old = __builtin_amdgcn_readfirstlane(old);
-        if (old != c_last - c_first) continue;                // wave-uniform
-        __threadfence();                                      // everybody's partial rows after their counts
-        if (lane == 0) counters[c_first] = 0;                 // ready for the next launch
+        if (old != n_sup) continue;                           // wave-uniform: 1 + n_sup arrivals in all
+        if (lane == 0) __hip_atomic_store(&cnt_seg[c_first], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         double t[4] = {0.0, 0.0, 0.0, 0.0};
         if (grp == 0 && col_ok) {
             const double *x = part_last + (int64_t)c_first * dim + lig * 4;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) t[i] = x[i];
+            for (int i = 0; i < 4; ++i) t[i] = load_piece(x + i);
         }
-        add_partial_rows(t, part_head, dim, lig, col_ok, c_first + 1 + grp, c_last, GPW);
+        add_partial_rows(t, part_head, dim, lig, col_ok, c_first + 1 + grp * kFusedSuper, c_last, GPW * kFusedSuper);
 #pragma unroll
         for (int i = 0; i < 4; ++i) t[i] = across_groups<LPR>(t[i]);
         if (grp == 0 && col_ok) stage[wib][lig] = f32x4{(float)t[0], (float)t[1], (float)t[2], (float)t[3]};
@@ -333,41 +387,151 @@ __global__ __launch_bounds__(kFusedWaves *kWave) void reduce_update_kernel(
     if (bad) atomicOr(flags, kFlagInternal);
 }
 
+// Short path: rows of one class (list `rows`/`slots`, length *n_rows_dev) whose segment has at most
+// FS_SHORT_SEGMENT occurrences.  One group of LPR lanes per row and iteration; longer segments are
+// skipped (the position-cut launch owns them).  Sorted layout (perm, seg_offsets) is read directly.
 template <bool BF16, int LPR>
+__global__ __launch_bounds__(256) void short_rows_kernel(
+    const f32x4 *__restrict__ grads, int n, const int32_t *__restrict__ perm, const int32_t *__restrict__ seg_offsets,
+    const int64_t *__restrict__ rows, const int32_t *__restrict__ slots, const int64_t *__restrict__ n_rows_dev,
+    int64_t cap, void *table, float *state, int64_t num_rows, int gvec, float lr, float eps, f32x4 *reduced,
+    int *flags) {
+#pragma clang fp contract(off)
+    constexpr int GPW = kWave / LPR;
+    constexpr int T = FS_SHORT_SEGMENT;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int grp = lane / LPR;
+    const int lig = lane % LPR;
+    const bool col_ok = lig < gvec;
+    const int dim = gvec * 4;
+    int64_t n_rows = *n_rows_dev;
+    if (n_rows > cap) n_rows = cap;
+    const int64_t waves = (int64_t)gridDim.x * (blockDim.x / kWave);
+    const int64_t wave = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    u32x4 *t4 = reinterpret_cast<u32x4 *>(table);
+    u32x2 *t2 = reinterpret_cast<u32x2 *>(table);
+    bool oob = false, bad = false;
+    for (int64_t base = wave * GPW; base < n_rows; base += waves * GPW) {
+        const int64_t i = base + grp;
+        const bool in_list = i < n_rows;
+        const int64_t r = in_list ? rows[i] : 0;
+        int k = in_list ? slots[i] : 0;
+        if ((unsigned)k >= (unsigned)n) { bad |= in_list; k = 0; }
+        const int first = seg_offsets[k], len = seg_offsets[k + 1] - first;
+        const bool in_table = (r >= 0) && (r < num_rows);
+        oob |= in_list && !in_table;
+        const bool seg_ok = first >= 0 && len >= 1 && first + len <= n;
+        bad |= in_list && !seg_ok;
+        const bool live = in_list && in_table && seg_ok && len <= T;
+        const bool mine = live && col_ok;
+        // the table row and the accumulator are requested together with the occurrence list
+        u32x4 w = u32x4{0u, 0u, 0u, 0u};
+        if (mine) {
+            if (BF16) {
+                const u32x2 h = t2[r * gvec + lig];
+                w[0] = h[0];
+                w[1] = h[1];
+            } else {
+                w = t4[r * gvec + lig];
+            }
+        }
+        const float s_old = live ? state[r] : 0.f;
+        int pj[T];
+#pragma unroll
+        for (int j = 0; j < T; ++j) pj[j] = (live && j < len) ? perm[first + j] : 0;
+        f32x4 gj[T];
+#pragma unroll
+        for (int j = 0; j < T; ++j) {
+            gj[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if ((unsigned)pj[j] >= (unsigned)n) { bad = true; pj[j] = 0; }
+            if (mine && j < len) gj[j] = __builtin_nontemporal_load(&grads[(int64_t)pj[j] * gvec + lig]);
+        }
+        double acc[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int j = 0; j < T; ++j)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[c] += (double)gj[j][c];
+        const f32x4 g = {(float)acc[0], (float)acc[1], (float)acc[2], (float)acc[3]};
+        double ss = 0.0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) ss += (double)g[c] * (double)g[c];
+        ss = group_sum<LPR>(ss);
+        const float m = (float)(ss / (double)dim);
+        const float s_new = s_old + m;
+        const float c_step = __fdiv_rn(lr, __fsqrt_rn(s_new) + eps);
+        if (BF16) {
+            const float c0 = bf16_lo(w[0]) - c_step * g[0];
+            const float c1 = bf16_hi(w[0]) - c_step * g[1];
+            const float c2 = bf16_lo(w[1]) - c_step * g[2];
+            const float c3 = bf16_hi(w[1]) - c_step * g[3];
+            const u32x2 o = {f32_to_bf16_bits(c0) | (f32_to_bf16_bits(c1) << 16),
+                             f32_to_bf16_bits(c2) | (f32_to_bf16_bits(c3) << 16)};
+            if (mine) t2[r * gvec + lig] = o;
+        } else {
+            u32x4 o;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) o[c] = __float_as_uint(__uint_as_float(w[c]) - c_step * g[c]);
+            if (mine) t4[r * gvec + lig] = o;
+        }
+        if (live && lig == 0) state[r] = s_new;
+        if (reduced != nullptr && mine) reduced[(int64_t)k * gvec + lig] = g;
+    }
+    if (oob) atomicOr(flags, kFlagRowRange);
+    if (bad) atomicOr(flags, kFlagInternal);
+}
+
+template <bool BF16, int LPR, int CHUNK>
 static void fused_launch(fs_ctx *ctx, int cls, const float *grads, int n, int gvec, const int32_t *cperm,
                          const int32_t *cslot, const int32_t *class_pos, const int32_t *seg_offsets,
                          const int32_t *cstart, const int64_t *u_t, void *table, float *state, int64_t num_rows,
-                         float lr, float eps, float *reduced, hipStream_t s) {
+                         float lr, float eps, float *reduced, hipStream_t s, const int32_t *perm,
+                         const int64_t *rows, const int32_t *slots, const int64_t *n_rows_dev) {
     constexpr int GPW = kWave / LPR;
-    constexpr int UNR = (kWave / GPW) < FS_FUSED_UNR ? (kWave / GPW) : FS_FUSED_UNR;
-    const int n_chunks = (int)ceil_div(n, kWave);
+    {
+        // short path first: it is the larger part of the rows and its wavefronts are short-lived
+        int64_t sblocks = ceil_div(n, (int64_t)GPW * 4);
+        if (sblocks > 8192) sblocks = 8192;                   // grid-stride beyond this; the list length lives on the device
+        hipLaunchKernelGGL((short_rows_kernel<BF16, LPR>), dim3((unsigned)sblocks), dim3(256), 0, s,
+                           (const f32x4 *)grads, n, perm, seg_offsets, rows, slots, n_rows_dev, (int64_t)n, table,
+                           state, num_rows, gvec, lr, eps, (f32x4 *)reduced, ctx->d_flags);
+    }
+    constexpr int UNR = (CHUNK / GPW) < FS_FUSED_UNR ? ((CHUNK / GPW) < 1 ? 1 : (CHUNK / GPW)) : FS_FUSED_UNR;
+    constexpr int CH = CHUNK < GPW ? GPW : CHUNK;             // at least one row group per chunk
+    const int n_chunks = (int)ceil_div(n, CH);
     const int blocks = (int)ceil_div(n_chunks, kFusedWaves);
-    hipLaunchKernelGGL((reduce_update_kernel<BF16, LPR, UNR>), dim3(blocks), dim3(kFusedWaves * kWave), 0, s,
+    hipLaunchKernelGGL((reduce_update_kernel<BF16, LPR, UNR, CH>), dim3(blocks), dim3(kFusedWaves * kWave), 0, s,
                        (const f32x4 *)grads, cperm, cslot, class_pos, cls, n, seg_offsets, cstart, u_t, table, state,
                        num_rows, gvec, lr, eps, (f32x4 *)reduced, ctx->fpart_head[cls], ctx->fpart_last[cls],
-                       ctx->fcounters[cls], ctx->d_flags);
+                       ctx->fcounters[cls], ctx->fcounters_sup[cls], ctx->d_flags);
 }
 
 int launch_reduce_update(fs_ctx *ctx, int cls, const float *grads, int64_t n, int32_t dim, const int32_t *cperm,
                          const int32_t *cslot, const int32_t *class_pos, const int32_t *seg_offsets,
                          const int32_t *cstart, const int64_t *u_t, void *table, int dt, float *state,
-                         int64_t num_rows, float lr, float eps, float *reduced, hipStream_t s) {
+                         int64_t num_rows, float lr, float eps, float *reduced, hipStream_t s, const int32_t *perm,
+                         const int64_t *rows, const int32_t *slots, const int64_t *n_rows_dev) {
     if (n == 0) return FS_OK;
     const int gvec = dim / 4;
     const bool bf = dt == FS_BF16;
-#define FS_CASE(L)                                                                                                   \
-    case L:                                                                                                          \
-        if (bf) fused_launch<true, L>(ctx, cls, grads, (int)n, gvec, cperm, cslot, class_pos, seg_offsets, cstart,   \
-                                      u_t, table, state, num_rows, lr, eps, reduced, s);                             \
-        else fused_launch<false, L>(ctx, cls, grads, (int)n, gvec, cperm, cslot, class_pos, seg_offsets, cstart,     \
-                                    u_t, table, state, num_rows, lr, eps, reduced, s);                               \
+#define FS_ARGS ctx, cls, grads, (int)n, gvec, cperm, cslot, class_pos, seg_offsets, cstart, u_t, table, state, num_rows, \
+                lr, eps, reduced, s, perm, rows, slots, n_rows_dev
+#define FS_CASE(L)                                                                   \
+    case L:                                                                          \
+        if (cls == 0) {                                                              \
+            if (bf) fused_launch<true, L, FS_FUSED_CHUNK_CO>(FS_ARGS);               \
+            else fused_launch<false, L, FS_FUSED_CHUNK_CO>(FS_ARGS);                 \
+        } else {                                                                     \
+            if (bf) fused_launch<true, L, FS_FUSED_CHUNK_EX>(FS_ARGS);               \
+            else fused_launch<false, L, FS_FUSED_CHUNK_EX>(FS_ARGS);                 \
+        }                                                                            \
         break;
     switch (lanes_per_row(gvec)) {
         FS_CASE(1) FS_CASE(2) FS_CASE(4) FS_CASE(8) FS_CASE(16) FS_CASE(32) FS_CASE(64)
         default: return set_err(ctx, FS_EINVAL, "reduce+update: dim beyond 256");
     }
 #undef FS_CASE
-    FS_LAUNCH_CHECK(ctx, "reduce_update_kernel");
+#undef FS_ARGS
+    FS_LAUNCH_CHECK(ctx, "reduce+update kernels");
     return FS_OK;
 }
 

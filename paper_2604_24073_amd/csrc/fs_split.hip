@@ -175,8 +175,9 @@ __global__ __launch_bounds__(kScanThreads) void split_compact_kernel(
             r_found += f[i] ? 1 : 0;
         }
     }
-    // For the class order of the batch: occurrences (segment lengths) of the same-class rows that
-    // precede each row inside this tile, and the tile's occurrence totals per class.
+    // For the class order of the batch (rows with more than FS_SHORT_SEGMENT occurrences only):
+    // occurrences of the same-class rows that precede each row inside this tile, and the tile's
+    // occurrence totals per class.
     if (side_t && seg_offsets_t != nullptr) {
         int len[kScanIpt];
         int co_len = 0, ex_len = 0;
@@ -184,6 +185,7 @@ __global__ __launch_bounds__(kScanThreads) void split_compact_kernel(
         for (int i = 0; i < kScanIpt; ++i) {
             const int p = p0 + i;
             len[i] = (p < n_mine) ? seg_offsets_t[p + 1] - seg_offsets_t[p] : 0;
+            if (len[i] <= FS_SHORT_SEGMENT) len[i] = 0;      // short segments are not part of the class order
             co_len += f[i] ? len[i] : 0;
             ex_len += f[i] ? 0 : len[i];
         }
@@ -211,8 +213,8 @@ __global__ __launch_bounds__(kScanThreads) void split_compact_kernel(
     }
 }
 
-// Class order of the occurrences of batch t: sorted position q (row slot s, the j-th occurrence of
-// that row) goes to  [start of the class] + [occurrences of same-class rows before s] + j.
+// Class order of the occurrences of batch t that belong to rows with more than FS_SHORT_SEGMENT
+// occurrences: sorted position q (row slot s, the j-th occurrence of that row) goes to  [start of the class] + [occurrences of same-class rows before s] + j.
 // Every workgroup first turns the per-tile totals into tile bases (a few hundred values).
 __global__ __launch_bounds__(kScanThreads) void class_scatter_kernel(
     const int32_t *__restrict__ perm, const int32_t *__restrict__ inverse, const int32_t *__restrict__ seg_offsets,
@@ -260,6 +262,7 @@ __global__ __launch_bounds__(kScanThreads) void class_scatter_kernel(
             const bool is_co = flag_t[slot] != 0;
             const int tile = slot / kScanTile;
             const int first = seg_offsets[slot];
+            if (seg_offsets[slot + 1] - first <= FS_SHORT_SEGMENT) continue;
             const int dest = (is_co ? tile_base[tile] : n_co_pos + tile_base[tiles_t + tile]) + cstart_local[slot] +
                              (q - first);
             if (dest < 0 || dest >= n) {                     // cannot happen with a consistent layout and split
