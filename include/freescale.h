@@ -156,6 +156,11 @@ int fs_rowwise_adagrad_update(fs_ctx *ctx, void *table, fs_dtype dt, float *stat
  *   cstart[cap_t]        class position of the first occurrence of u_t[k] (rows in the class
  *                        order only; other entries are unspecified)
  *   class_pos_dev [2]    int32: number of class-0 positions, number of class positions
+ *   short_rec [2 * cap_t * 12] int32: one 12-word record per row of U_t, at the row's place in
+ *                        its class list (co rows from word 0, ex rows from word 12 * cap_t):
+ *                        row (2 words, low first), slot, number of occurrences, and for rows
+ *                        with at most FS_SHORT_SEGMENT occurrences the occurrences (rows of G_t)
+ *                        in batch order
  * seg_offsets_t, perm_t, inverse_t: the layout of batch t as written by fs_unique_ids (all three
  * required); cap_t is also the capacity of cstart.  This is the prioritization of Section 3.2
  * carried down to the gradient rows: the priority pass reads only what collision rows need. */
@@ -164,24 +169,24 @@ int fs_collision_split_classes(fs_ctx *ctx, const int64_t *u_t, const int64_t *n
                                const int32_t *seg_offsets_t, const int32_t *perm_t, const int32_t *inverse_t,
                                int64_t n_t, int64_t *co, int32_t *co_slot, int64_t *ex, int32_t *ex_slot,
                                int64_t *ex_next, int32_t *ex_next_slot, int64_t *counts_dev, int32_t *cperm,
-                               int32_t *cslot, int32_t *cstart, int32_t *class_pos_dev, fs_stream stream);
+                               int32_t *cslot, int32_t *cstart, int32_t *class_pos_dev, int32_t *short_rec,
+                               fs_stream stream);
 
 /* update_embedding(I, G) of Algorithm 2 for one class of rows: the segment reduce of
  * fs_segment_reduce_grads and the Adagrad update of fs_rowwise_adagrad_update fused, same
  * arithmetic (fp64 sums in a fixed order, one rounding to fp32, then the update), restricted to
  * the rows of class `cls` (0: collision rows = priority pass, 1: exclusive rows = deferred
- * pass).  rows / slots / n_rows_dev: the class's row list as fs_collision_split wrote it (co,
- * co_slot, counts_dev + 0, or ex, ex_slot, counts_dev + 1).  Two launches: the short path over
- * the row list (sorted layout perm / seg_offsets), the position-cut path over the class order.
+ * pass).  short_rec_cls / n_rows_dev: the records of this class (short_rec + cls * 12 * cap_t)
+ * and the number of its rows (counts_dev + cls).  Two launches: the short path over the
+ * records, the position-cut path over the class order.
  * The summed gradients do not go through memory unless `reduced` (OPTIONAL, [n_unique, dim]
  * fp32) is given, in which case the rows of this class are also written there.
  * Calls for the two classes may run side by side on different streams; calls for the same class
  * on one context must be ordered. */
 int fs_reduce_update_class(fs_ctx *ctx, int cls, void *table, fs_dtype dt, float *state, int64_t num_rows,
                            int32_t dim, float lr, float eps, const float *grads, int64_t n,
-                           const int64_t *u_t, const int32_t *seg_offsets, const int32_t *perm,
-                           const int64_t *rows, const int32_t *slots, const int64_t *n_rows_dev,
-                           const int32_t *cperm, const int32_t *cslot, const int32_t *cstart,
+                           const int64_t *u_t, const int32_t *seg_offsets, const int32_t *short_rec_cls,
+                           const int64_t *n_rows_dev, const int32_t *cperm, const int32_t *cslot, const int32_t *cstart,
                            const int32_t *class_pos_dev, float *reduced, fs_stream stream);
 
 /* ---- one whole iteration ------------------------------------------------------------------ */
@@ -203,7 +208,7 @@ typedef struct fs_step_args {
     int64_t *co; int32_t *co_slot; int64_t *ex; int32_t *ex_slot; int64_t *ex_next; int32_t *ex_next_slot;
     int64_t *counts_dev;        /* [3] */
     /* outputs: class order of batch t: [n_t], [n_t], [n_t], [2] (see fs_collision_split_classes) */
-    int32_t *cperm; int32_t *cslot; int32_t *cstart; int32_t *class_pos_dev;
+    int32_t *cperm; int32_t *cslot; int32_t *cstart; int32_t *class_pos_dev; int32_t *short_rec /* [24 * n_t] */;
     /* outputs: reduced gradients [n_t, dim] capacity (OPTIONAL, may be NULL: the step does not need
      * them in memory), and gathered rows of t+1 [n_t1, dim] */
     float *reduced; void *emb_t1;

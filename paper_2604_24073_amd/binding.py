@@ -21,6 +21,7 @@ FS_F32, FS_BF16 = 0, 1
 FS_OK, FS_EINVAL, FS_ENOMEM, FS_EHIP, FS_ENOTIMPL, FS_ERANGE = 0, -1, -2, -3, -4, -5
 FS_MAX_DIM = 256
 FS_SHORT_SEGMENT = 8
+SHORT_REC_INTS = 12
 
 c_i64, c_i32, c_vp, c_f = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_float
 
@@ -35,7 +36,7 @@ class fs_step_args(ctypes.Structure):
         ("u_t1", c_vp), ("seg_offsets_t1", c_vp), ("perm_t1", c_vp), ("inverse_t1", c_vp), ("n_unique_t1_dev", c_vp),
         ("co", c_vp), ("co_slot", c_vp), ("ex", c_vp), ("ex_slot", c_vp), ("ex_next", c_vp), ("ex_next_slot", c_vp),
         ("counts_dev", c_vp),
-        ("cperm", c_vp), ("cslot", c_vp), ("cstart", c_vp), ("class_pos_dev", c_vp),
+        ("cperm", c_vp), ("cslot", c_vp), ("cstart", c_vp), ("class_pos_dev", c_vp), ("short_rec", c_vp),
         ("reduced", c_vp), ("emb_t1", c_vp),
     ]
 
@@ -75,10 +76,9 @@ def load_library() -> ctypes.CDLL:
                                                      c_i64, c_vp, c_f, c_f, S]),
         "fs_collision_split_classes": (ctypes.c_int, [c_vp, c_vp, c_vp, c_vp, c_vp, c_i64, c_i64, c_vp, c_vp, c_vp,
                                                       c_i64, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp,
-                                                      c_vp, c_vp, S]),
+                                                      c_vp, c_vp, c_vp, S]),
         "fs_reduce_update_class": (ctypes.c_int, [c_vp, ctypes.c_int, c_vp, ctypes.c_int, c_vp, c_i64, c_i32, c_f, c_f,
-                                                  c_vp, c_i64, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp,
-                                                  c_vp, c_vp, S]),
+                                                  c_vp, c_i64, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, S]),
         "fs_unique_ids_ahead": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i64, c_vp, c_vp, c_vp, c_vp, c_vp, S]),
         "fs_prioritized_step": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args), S]),
         "fs_step_forward": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args), S]),
@@ -253,7 +253,7 @@ def fs_collision_split_classes(ctx: Context, layout_t: Dict[str, torch.Tensor], 
         _ptr(layout_t["seg_offsets"]), _ptr(layout_t["perm"]), _ptr(layout_t["inverse"]), n_t,
         _ptr(out["co"]), _ptr(out["co_slot"]), _ptr(out["ex"]), _ptr(out["ex_slot"]), _ptr(out["ex_next"]),
         _ptr(out["ex_next_slot"]), _ptr(out["counts"]), _ptr(out["cperm"]), _ptr(out["cslot"]), _ptr(out["cstart"]),
-        _ptr(out["class_pos"]), _stream(stream))
+        _ptr(out["class_pos"]), _ptr(out["short_rec"]), _stream(stream))
     ctx.check(rc, "fs_collision_split_classes")
     return out
 
@@ -264,8 +264,8 @@ def fs_reduce_update_class(ctx: Context, cls: int, table: torch.Tensor, state: t
     n, dim = grads.shape
     rc = ctx.lib.fs_reduce_update_class(
         ctx.handle, cls, _ptr(table), table_dtype_code(table), _ptr(state), table.shape[0], dim, lr, eps,
-        _ptr(grads), n, _ptr(layout_t["unique"]), _ptr(layout_t["seg_offsets"]), _ptr(layout_t["perm"]),
-        _ptr(split["co" if cls == 0 else "ex"]), _ptr(split["co_slot" if cls == 0 else "ex_slot"]),
+        _ptr(grads), n, _ptr(layout_t["unique"]), _ptr(layout_t["seg_offsets"]),
+        split["short_rec"].data_ptr() + cls * 4 * SHORT_REC_INTS * n,
         split["counts"].data_ptr() + 8 * cls, _ptr(split["cperm"]),
         _ptr(split["cslot"]), _ptr(split["cstart"]), _ptr(split["class_pos"]), _ptr(reduced), _stream(stream))
     ctx.check(rc, "fs_reduce_update_class")
@@ -376,6 +376,7 @@ def alloc_split(cap_t: int, cap_t1: int, device) -> Dict[str, torch.Tensor]:
             "ex_next": i64(cap_t1), "ex_next_slot": i32(cap_t1),
             "counts": torch.zeros(3, dtype=torch.int64, device=device),
             "cperm": i32(cap_t), "cslot": i32(cap_t), "cstart": i32(cap_t),
+            "short_rec": i32(2 * SHORT_REC_INTS * cap_t),
             "class_pos": torch.zeros(2, dtype=torch.int32, device=device)}
 
 
@@ -409,5 +410,6 @@ def make_step_args(table: torch.Tensor, state: torch.Tensor, lr: float, eps: flo
     a.counts_dev = _ptr(split["counts"])
     a.cperm, a.cslot, a.cstart = _ptr(split["cperm"]), _ptr(split["cslot"]), _ptr(split["cstart"])
     a.class_pos_dev = _ptr(split["class_pos"])
+    a.short_rec = _ptr(split["short_rec"])
     a.reduced = _ptr(reduced)
     return a

@@ -8,6 +8,7 @@
 #include <functional>
 #include <mutex>
 #include <new>
+#include <stdlib.h>
 #include <thread>
 
 #include "fs_common.h"
@@ -132,6 +133,7 @@ void carve(fs_ctx *c, char *base, size_t *total) {
     }
     c->cstart_local = cv.take<int32_t>(n + 16);
     c->tile_len = cv.take<int32_t>(2 * scan_tiles);
+    c->cidx = cv.take<int32_t>(n + 16);
     *total = align_up(cv.off, 256);
 }
 
@@ -163,6 +165,7 @@ int fs_ctx_create(fs_ctx **out, int device, int64_t max_ids, int32_t max_dim) {
     c->max_ids = max_ids;
     c->max_dim = max_dim;
     c->use_worker = true;
+    if (const char *e = getenv("FS_DEFERRED_ON")) c->deferred_on = atoi(e);
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || device >= ndev) {
         delete c;
@@ -406,7 +409,7 @@ int check_step_args(fs_ctx *ctx, const fs_step_args *a, bool *have_t, bool *have
     *have_t1 = a->values_t1 != nullptr && a->n_t1 > 0;
     if (*have_t)
         FS_REQUIRE(ctx, a->u_t && a->seg_offsets_t && a->perm_t && a->inverse_t && a->n_unique_t_dev && a->grads_t &&
-                            a->co && a->co_slot && a->ex && a->ex_slot && a->cperm && a->cslot && a->cstart,
+                            a->co && a->co_slot && a->ex && a->ex_slot && a->cperm && a->cslot && a->cstart && a->short_rec,
                    "step: null pointer (iteration t)");
     if (*have_t1)
         FS_REQUIRE(ctx, a->u_t1 && a->seg_offsets_t1 && a->perm_t1 && a->inverse_t1 && a->n_unique_t1_dev &&
@@ -499,7 +502,8 @@ int enqueue_index_work(fs_ctx *ctx, const fs_step_args *a, bool have_t, bool hav
                       have_t ? a->seg_offsets_t : nullptr);
     if (rc != FS_OK) return rc;
     return launch_class_order(ctx, a->perm_t, a->inverse_t, a->seg_offsets_t, have_t ? a->n_t : 0,
-                              have_t ? a->n_t : 0, a->cperm, a->cslot, a->cstart, a->class_pos_dev, s);
+                              have_t ? a->n_t : 0, a->cperm, a->cslot, a->cstart, a->class_pos_dev, a->u_t,
+                              a->short_rec, s);
 }
 
 // update_embedding for one class of rows of iteration t (0: priority pass, 1: deferred pass)
@@ -507,9 +511,8 @@ int enqueue_class_pass(fs_ctx *ctx, const fs_step_args *a, int cls, hipStream_t 
     if (timing) (void)hipEventRecord(timing[0], s);
     const int rc = launch_reduce_update(ctx, cls, a->grads_t, a->n_t, a->dim, a->cperm, a->cslot, a->class_pos_dev,
                                         a->seg_offsets_t, a->cstart, a->u_t, a->table, a->dtype, a->state,
-                                        a->num_rows, a->lr, a->eps, a->reduced, s, a->perm_t,
-                                        cls == 0 ? a->co : a->ex, cls == 0 ? a->co_slot : a->ex_slot,
-                                        a->counts_dev + cls);
+                                        a->num_rows, a->lr, a->eps, a->reduced, s,
+                                        a->short_rec + (int64_t)cls * a->n_t * kShortRecInts, a->counts_dev + cls);
     if (timing && rc == FS_OK) (void)hipEventRecord(timing[1], s);
     return rc;
 }
@@ -573,7 +576,7 @@ int fs_collision_split_classes(fs_ctx *ctx, const int64_t *u_t, const int64_t *n
                                const int32_t *perm_t, const int32_t *inverse_t, int64_t n_t, int64_t *co,
                                int32_t *co_slot, int64_t *ex, int32_t *ex_slot, int64_t *ex_next,
                                int32_t *ex_next_slot, int64_t *counts_dev, int32_t *cperm, int32_t *cslot,
-                               int32_t *cstart, int32_t *class_pos_dev, fs_stream stream) {
+                               int32_t *cstart, int32_t *class_pos_dev, int32_t *short_rec, fs_stream stream) {
     if (!ctx) return FS_EINVAL;
     FS_REQUIRE(ctx, cap_t >= 0 && cap_t1 >= 0 && n_t >= 0, "split: negative size");
     if (cap_t > ctx->max_ids || cap_t1 > ctx->max_ids || n_t > ctx->max_ids)
@@ -582,7 +585,7 @@ int fs_collision_split_classes(fs_ctx *ctx, const int64_t *u_t, const int64_t *n
     FS_REQUIRE(ctx, (n_t == 0) == (cap_t == 0), "split: n_t and cap_t must both be zero or both positive");
     if (cap_t > 0)
         FS_REQUIRE(ctx, u_t && n_t_dev && co && co_slot && ex && ex_slot && seg_offsets_t && perm_t && inverse_t &&
-                            cperm && cslot && cstart,
+                            cperm && cslot && cstart && short_rec,
                    "split: null pointer (t side)");
     if (cap_t1 > 0) FS_REQUIRE(ctx, u_t1 && n_t1_dev && ex_next && ex_next_slot, "split: null pointer (t+1 side)");
     int rc = join_pending_work(ctx, as_stream(stream));      // the workspace may still be in use on A
@@ -592,15 +595,14 @@ int fs_collision_split_classes(fs_ctx *ctx, const int64_t *u_t, const int64_t *n
                       cap_t > 0 ? seg_offsets_t : nullptr);
     if (rc != FS_OK) return rc;
     return launch_class_order(ctx, perm_t, inverse_t, seg_offsets_t, n_t, cap_t, cperm, cslot, cstart, class_pos_dev,
-                              as_stream(stream));
+                              u_t, short_rec, as_stream(stream));
 }
 
 int fs_reduce_update_class(fs_ctx *ctx, int cls, void *table, fs_dtype dt, float *state, int64_t num_rows,
                            int32_t dim, float lr, float eps, const float *grads, int64_t n, const int64_t *u_t,
-                           const int32_t *seg_offsets, const int32_t *perm, const int64_t *rows,
-                           const int32_t *slots, const int64_t *n_rows_dev, const int32_t *cperm,
-                           const int32_t *cslot, const int32_t *cstart, const int32_t *class_pos_dev, float *reduced,
-                           fs_stream stream) {
+                           const int32_t *seg_offsets, const int32_t *short_rec_cls, const int64_t *n_rows_dev,
+                           const int32_t *cperm, const int32_t *cslot, const int32_t *cstart,
+                           const int32_t *class_pos_dev, float *reduced, fs_stream stream) {
     if (!ctx) return FS_EINVAL;
     FS_REQUIRE(ctx, cls == 0 || cls == 1, "reduce+update: class must be 0 or 1");
     FS_REQUIRE(ctx, dt == FS_F32 || dt == FS_BF16, "reduce+update: unknown dtype");
@@ -609,12 +611,11 @@ int fs_reduce_update_class(fs_ctx *ctx, int cls, void *table, fs_dtype dt, float
     if (n > ctx->max_ids || dim > ctx->max_dim)
         return set_err(ctx, FS_ENOMEM, "reduce+update: beyond the context capacity");
     if (n == 0) return FS_OK;
-    FS_REQUIRE(ctx, table && state && grads && u_t && seg_offsets && perm && rows && slots && n_rows_dev && cperm &&
-                        cslot && cstart && class_pos_dev,
+    FS_REQUIRE(ctx, table && state && grads && u_t && seg_offsets && short_rec_cls && n_rows_dev && cperm && cslot &&
+                        cstart && class_pos_dev,
                "reduce+update: null pointer");
     return launch_reduce_update(ctx, cls, grads, n, dim, cperm, cslot, class_pos_dev, seg_offsets, cstart, u_t, table,
-                                dt, state, num_rows, lr, eps, reduced, as_stream(stream), perm, rows, slots,
-                                n_rows_dev);
+                                dt, state, num_rows, lr, eps, reduced, as_stream(stream), short_rec_cls, n_rows_dev);
 }
 
 int fs_unique_ids_ahead(fs_ctx *ctx, const int64_t *ids, int64_t n, int64_t num_rows, int64_t *unique,
@@ -743,9 +744,10 @@ int fs_prioritized_step_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs
     hipEvent_t *tex = have_t ? timing_pair(ctx, FS_TIME_UPDATE_EX) : nullptr;
     fs_step_args cur_copy = *cur, next_copy = next ? *next : *cur;
     const bool has_next = next != nullptr;
+    const bool ex_on_side = ctx->deferred_on == 0;
     auto side_job = [=]() -> int {
-        return enqueue_side_stream(ctx, have_t ? &cur_copy : nullptr, has_next ? &next_copy : nullptr, nxt_t, nxt_t1,
-                                   ahead, p, tex);
+        return enqueue_side_stream(ctx, (have_t && ex_on_side) ? &cur_copy : nullptr,
+                                   has_next ? &next_copy : nullptr, nxt_t, nxt_t1, ahead, p, tex);
     };
     if (w0) w0->post(side_job);
     const double h2 = now_us();
@@ -755,6 +757,7 @@ int fs_prioritized_step_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs
     const double h3 = now_us();
     if (rc == FS_OK && have_t) rc = enqueue_class_pass(ctx, cur, 0, sp, timing_pair(ctx, FS_TIME_UPDATE_CO));
     if (rc == FS_OK && have_t1) rc = enqueue_gather(ctx, cur, sp);
+    if (rc == FS_OK && have_t && !ex_on_side) rc = enqueue_class_pass(ctx, cur, 1, sp, tex);
     const double h4 = now_us();
     if (!w0) {
         const int src = side_job();

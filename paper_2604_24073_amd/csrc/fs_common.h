@@ -30,6 +30,8 @@ constexpr int kScanTile = kScanThreads * kScanIpt;
 // entry per lane).  Short chunks = many wavefronts with short dependent-load chains.
 constexpr int kReduceChunk = 64;
 constexpr int kReduceWavesPerBlock = 4;
+constexpr int kShortRecInts = 12;                         // row (2), slot, occurrences, occurrence list (FS_SHORT_SEGMENT)
+static_assert(FS_SHORT_SEGMENT == 8, "record layout");
 constexpr int kFusedMinChunk = 16;                        // smallest chunk the fused pass may be built with
 
 // device-side error flag bits (ctx->d_flags[0])
@@ -80,6 +82,7 @@ struct fs_ctx {
     // class order (scratch between the split launches and the scatter launch, same stream)
     int32_t *cstart_local;    // [max_ids] occurrences of same-class rows before this row inside its split tile
     int32_t *tile_len;        // [2 * scan tiles] occurrences per split tile: collision rows, then exclusive rows
+    int32_t *cidx;            // [max_ids] place of every row of U_t in its class list
     const int32_t *reduce_inverse;   // host-side: the caller's optional inverse map for the launch being enqueued
     int64_t *d_zero;          // device scalar that stays 0 (stands in for a missing lookahead)
 
@@ -94,6 +97,8 @@ struct fs_ctx {
     double host_us[7];        // host-side time spent in the phases of the pipelined call (measurement aid)
     struct fs_host *host;     // host threads and the table of outstanding ahead-of-time dedups
     bool use_worker;
+    int deferred_on;          // where the pipelined call runs the deferred pass: 0 side stream (beside the priority
+                              // pass), 1 the caller's stream after the gather
     hipStream_t stream_cap;   // capture stream of fs_graph_capture_pipelined
     bool capturing;           // host-side: a step is being recorded into a graph (no timing events)
     int timing_slots;
@@ -163,12 +168,12 @@ int launch_split(fs_ctx *, const int64_t *u_t, const int64_t *n_t_dev, const int
 // right after launch_split(..., seg_offsets_t) on the same stream: occurrences of the batch in class order
 int launch_class_order(fs_ctx *, const int32_t *perm, const int32_t *inverse, const int32_t *seg_offsets, int64_t n,
                        int64_t cap_u, int32_t *cperm, int32_t *cslot, int32_t *cstart, int32_t *class_pos_dev,
-                       hipStream_t s);
+                       const int64_t *u_t, int32_t *short_rec, hipStream_t s);
 int launch_reduce_update(fs_ctx *, int cls, const float *grads, int64_t n, int32_t dim, const int32_t *cperm,
                          const int32_t *cslot, const int32_t *class_pos, const int32_t *seg_offsets,
                          const int32_t *cstart, const int64_t *u_t, void *table, int dt, float *state,
-                         int64_t num_rows, float lr, float eps, float *reduced, hipStream_t s, const int32_t *perm,
-                         const int64_t *rows, const int32_t *slots, const int64_t *n_rows_dev);
+                         int64_t num_rows, float lr, float eps, float *reduced, hipStream_t s,
+                         const int32_t *short_rec, const int64_t *n_rows_dev);
 // `timing`: optional event pair recorded around the main (chunk) kernel only
 int launch_reduce(fs_ctx *, const float *grads, int64_t n, int32_t dim, const int32_t *perm,
                   const int32_t *seg_offsets, const int64_t *n_unique_dev, float *reduced, hipStream_t s,

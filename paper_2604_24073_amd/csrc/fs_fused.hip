@@ -15,9 +15,9 @@
 // There work is cut by POSITION (row popularity is Zipf, the hottest row has tens of thousands of
 // occurrences): one wavefront owns 64 consecutive class positions, streams their gradient rows
 // (16 bytes per lane, 64/LPR rows per instruction) into fp64 accumulators and, whenever a segment
-// ends, parks the finished sum (rounded once to fp32) in LDS.  Parked rows are updated in rounds
-// of eight or more, so the dependent loads of the update (table row, accumulator) of many rows
-// are in flight together.  A segment cut by a chunk border leaves fp64 partial rows; every
+// ends, parks the finished sum (rounded once to fp32) in LDS.  The parked rows (a handful: every
+// segment here is long) are updated together at the end of the chunk, so the dependent loads of
+// the update (table row, accumulator) are in flight together.  A segment cut by a chunk border leaves fp64 partial rows; every
 // wavefront that contributed one counts itself in at the segment's counter, and the one that
 // arrives last adds the partials in chunk order and updates the row - in two levels for the hot
 // rows (sixteen pieces at a time, then the sums of those), so that the last arriver of a row with
@@ -37,17 +37,25 @@ namespace fs {
 // wavefront in the priority / deferred pass (64, 32 or 16: collision rows have long segments,
 // exclusive rows short ones, and a short chunk means more wavefronts with shorter lives)
 #ifndef FS_FUSED_UNR
-#define FS_FUSED_UNR 8
+#define FS_FUSED_UNR 4
+#endif
+#ifndef FS_FUSED_RU
+#define FS_FUSED_RU 2                      // parked rows one group of lanes updates per round
 #endif
 #ifndef FS_FUSED_CHUNK_CO
 #define FS_FUSED_CHUNK_CO 64
 #endif
 #ifndef FS_FUSED_CHUNK_EX
-#define FS_FUSED_CHUNK_EX 32
+#define FS_FUSED_CHUNK_EX 64
+#endif
+#ifndef FS_SHORT_MAX_BLOCKS
+#define FS_SHORT_MAX_BLOCKS 4096
+#endif
+#ifndef FS_SHORT_UNR
+#define FS_SHORT_UNR 1                     // short path: rows one group of lanes takes per iteration
 #endif
 constexpr int kFusedSuper = 16;            // pieces of a cut segment that are added in one go (first level)
 constexpr int kFusedWaves = 4;             // wavefronts per workgroup (they never synchronise)
-constexpr int kFusedRound = 8;             // parked rows that trigger an update round
 
 // Adagrad on `nrows` parked rows of one wavefront.  Group g of the wavefront takes rows g, g+GPW, ...
 // stage: [row][LPR] fp32 sums (4 columns per lane), stage_row: table row, stage_slot: slot in U_t.
@@ -164,8 +172,8 @@ __device__ __forceinline__ void wave_lds_sync() {
 }
 
 template <bool BF16, int LPR, int UNR, int CHUNK>
-__global__ __launch_bounds__(kFusedWaves *kWave) __attribute__((amdgpu_waves_per_eu(4, 4))) void reduce_update_kernel(
-    const f32x4 *__restrict__ grads, const int32_t *__restrict__ cperm, const int32_t *__restrict__ cslot,
+__device__ __forceinline__ void long_segments_body(
+    const int block, const f32x4 *__restrict__ grads, const int32_t *__restrict__ cperm, const int32_t *__restrict__ cslot,
     const int32_t *__restrict__ class_pos, int cls, int n, const int32_t *__restrict__ seg_offsets,
     const int32_t *__restrict__ cstart, const int64_t *__restrict__ u_t, void *table, float *state, int64_t num_rows,
     int gvec, float lr, float eps, f32x4 *reduced, double *part_head, double *part_last, int *cnt_seg, int *cnt_sup,
@@ -173,9 +181,10 @@ __global__ __launch_bounds__(kFusedWaves *kWave) __attribute__((amdgpu_waves_per
     constexpr int GPW = kWave / LPR;          // rows per wavefront instruction
     constexpr int BP = GPW * UNR;             // positions per batch
     constexpr int NB = CHUNK / BP;            // batches per chunk
-    constexpr int ROUND = GPW > kFusedRound ? GPW : kFusedRound;
-    constexpr int CAP = ROUND + BP;           // a batch can park BP more rows before the next check
-    constexpr int RU = (ROUND / GPW) < 4 ? ((ROUND / GPW) < 1 ? 1 : (ROUND / GPW)) : 4;
+    // every segment here has more than FS_SHORT_SEGMENT positions, so only a few end inside one chunk:
+    // their sums wait in LDS and are all applied in one round at the end of the chunk
+    constexpr int CAP = CHUNK / (FS_SHORT_SEGMENT + 1) + 1;
+    constexpr int RU = FS_FUSED_RU;
     static_assert(CHUNK <= kWave && CHUNK % BP == 0, "one tail word, whole batches");
     __shared__ f32x4 stage[kFusedWaves][CAP * LPR];
     __shared__ int64_t stage_row[kFusedWaves][CAP];
@@ -191,7 +200,7 @@ __global__ __launch_bounds__(kFusedWaves *kWave) __attribute__((amdgpu_waves_per
     // an error flag instead of a wild access.
     if (lo < 0) lo = 0;
     if (hi > n) hi = n;
-    const int chunk = blockIdx.x * kFusedWaves + wib;        // chunk number inside the class
+    const int chunk = block * kFusedWaves + wib;             // chunk number inside the class
     const int64_t a64 = (int64_t)lo + (int64_t)chunk * CHUNK;
     if (a64 >= hi) return;                                   // wave-uniform; wavefronts share nothing
     const int a = (int)a64;
@@ -240,13 +249,15 @@ __global__ __launch_bounds__(kFusedWaves *kWave) __attribute__((amdgpu_waves_per
         if (nflush == 0 && !head_complete) {
             if (grp == 0 && col_ok) store_piece(part_head + (int64_t)chunk * dim + lig * 4, t);
         } else {
-            if (grp == 0 && col_ok)
-                stage[wib][nparked * LPR + lig] = f32x4{(float)t[0], (float)t[1], (float)t[2], (float)t[3]};
-            const int s_q = __shfl(sl, q, kWave);
-            const int64_t r_q = __shfl(rid, q, kWave);
-            if (lane == 0) {
-                stage_slot[wib][nparked] = s_q;
-                stage_row[wib][nparked] = r_q;
+            if (nparked < CAP) {
+                if (grp == 0 && col_ok)
+                    stage[wib][nparked * LPR + lig] = f32x4{(float)t[0], (float)t[1], (float)t[2], (float)t[3]};
+                const int s_q = __shfl(sl, q, kWave);
+                const int64_t r_q = __shfl(rid, q, kWave);
+                if (lane == 0) {
+                    stage_slot[wib][nparked] = s_q;
+                    stage_row[wib][nparked] = r_q;
+                }
             }
             ++nparked;
         }
@@ -289,16 +300,16 @@ __global__ __launch_bounds__(kFusedWaves *kWave) __attribute__((amdgpu_waves_per
             load_batch(v, k);
         }
         add_batch(v, k);
-        const bool last = (k + 1 == NB) || ((k + 1) * BP >= span);
-        if (nparked >= ROUND || (last && nparked > 0)) {
-            wave_lds_sync();
-#ifndef FS_EXP_NO_UPDATE
-            update_parked<BF16, LPR, RU>(stage[wib], stage_row[wib], stage_slot[wib], nparked, table, state, num_rows,
-                                         gvec, lr, eps, reduced, oob);
-#endif
-            wave_lds_sync();
-            nparked = 0;
-        }
+    }
+    if (nparked > CAP) {                                      // cannot happen with a consistent class order
+        bad = true;
+        nparked = 0;
+    }
+    if (nparked > 0) {
+        wave_lds_sync();
+        update_parked<BF16, LPR, RU>(stage[wib], stage_row[wib], stage_slot[wib], nparked, table, state, num_rows,
+                                     gvec, lr, eps, reduced, oob);
+        wave_lds_sync();
     }
 
     // positions after the last segment end of the chunk (the chunk's last position is not a tail)
@@ -326,9 +337,6 @@ __global__ __launch_bounds__(kFusedWaves *kWave) __attribute__((amdgpu_waves_per
     const int s_last = __shfl(sl, span - 1, kWave);
 #pragma unroll 1
     for (int which = 0; which < 2; ++which) {
-#ifdef FS_EXP_NO_FINISH
-        break;
-#endif
         if (!(which == 0 ? head_cut : tail_cut)) continue;    // wave-uniform
         const int s = which == 0 ? s_first : s_last;
         const int start = cstart[s];
@@ -387,18 +395,20 @@ __global__ __launch_bounds__(kFusedWaves *kWave) __attribute__((amdgpu_waves_per
     if (bad) atomicOr(flags, kFlagInternal);
 }
 
-// Short path: rows of one class (list `rows`/`slots`, length *n_rows_dev) whose segment has at most
-// FS_SHORT_SEGMENT occurrences.  One group of LPR lanes per row and iteration; longer segments are
-// skipped (the position-cut launch owns them).  Sorted layout (perm, seg_offsets) is read directly.
-template <bool BF16, int LPR>
-__global__ __launch_bounds__(256) void short_rows_kernel(
-    const f32x4 *__restrict__ grads, int n, const int32_t *__restrict__ perm, const int32_t *__restrict__ seg_offsets,
-    const int64_t *__restrict__ rows, const int32_t *__restrict__ slots, const int64_t *__restrict__ n_rows_dev,
+// Short path: the rows of one class whose segment has at most FS_SHORT_SEGMENT occurrences.  The
+// index half left one record per row of the class (row, slot, number of occurrences, the
+// occurrences themselves), so a group of LPR lanes needs two dependent rounds per row: the record,
+// then table row + accumulator + all gradient rows of the segment at once.  Rows with longer
+// segments are skipped (the position-cut launch owns them).
+template <bool BF16, int LPR, int UNR>
+__device__ __forceinline__ void short_rows_body(
+    const int block, const int nblocks, const f32x4 *__restrict__ grads, int n, const int32_t *__restrict__ recs, const int64_t *__restrict__ n_rows_dev,
     int64_t cap, void *table, float *state, int64_t num_rows, int gvec, float lr, float eps, f32x4 *reduced,
     int *flags) {
 #pragma clang fp contract(off)
     constexpr int GPW = kWave / LPR;
     constexpr int T = FS_SHORT_SEGMENT;
+    typedef int i32x4 __attribute__((ext_vector_type(4)));
     const int lane = threadIdx.x & (kWave - 1);
     const int grp = lane / LPR;
     const int lig = lane % LPR;
@@ -406,115 +416,177 @@ __global__ __launch_bounds__(256) void short_rows_kernel(
     const int dim = gvec * 4;
     int64_t n_rows = *n_rows_dev;
     if (n_rows > cap) n_rows = cap;
-    const int64_t waves = (int64_t)gridDim.x * (blockDim.x / kWave);
-    const int64_t wave = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    const int64_t waves = (int64_t)nblocks * kFusedWaves;
+    const int64_t wave = (int64_t)block * kFusedWaves + (threadIdx.x / kWave);
     u32x4 *t4 = reinterpret_cast<u32x4 *>(table);
     u32x2 *t2 = reinterpret_cast<u32x2 *>(table);
     bool oob = false, bad = false;
-    for (int64_t base = wave * GPW; base < n_rows; base += waves * GPW) {
-        const int64_t i = base + grp;
-        const bool in_list = i < n_rows;
-        const int64_t r = in_list ? rows[i] : 0;
-        int k = in_list ? slots[i] : 0;
-        if ((unsigned)k >= (unsigned)n) { bad |= in_list; k = 0; }
-        const int first = seg_offsets[k], len = seg_offsets[k + 1] - first;
-        const bool in_table = (r >= 0) && (r < num_rows);
-        oob |= in_list && !in_table;
-        const bool seg_ok = first >= 0 && len >= 1 && first + len <= n;
-        bad |= in_list && !seg_ok;
-        const bool live = in_list && in_table && seg_ok && len <= T;
-        const bool mine = live && col_ok;
-        // the table row and the accumulator are requested together with the occurrence list
-        u32x4 w = u32x4{0u, 0u, 0u, 0u};
-        if (mine) {
-            if (BF16) {
-                const u32x2 h = t2[r * gvec + lig];
-                w[0] = h[0];
-                w[1] = h[1];
-            } else {
-                w = t4[r * gvec + lig];
+    for (int64_t base = wave * (GPW * UNR); base < n_rows; base += waves * (GPW * UNR)) {
+        i32x4 hd[UNR], pa[UNR], pb[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int64_t i = base + u * GPW + grp;
+            const i32x4 *rec = reinterpret_cast<const i32x4 *>(recs + i * kShortRecInts);
+            hd[u] = i32x4{0, 0, 0, 0};
+            pa[u] = i32x4{0, 0, 0, 0};
+            pb[u] = i32x4{0, 0, 0, 0};
+            if (i < n_rows) {
+                hd[u] = rec[0];
+                pa[u] = rec[1];
+                pb[u] = rec[2];
             }
         }
-        const float s_old = live ? state[r] : 0.f;
-        int pj[T];
+        int64_t r[UNR];
+        int len[UNR];
+        bool mine[UNR];
+        u32x4 w[UNR];
+        float s_old[UNR];
+        f32x4 g[UNR][4];
+        bool any_more = false;
 #pragma unroll
-        for (int j = 0; j < T; ++j) pj[j] = (live && j < len) ? perm[first + j] : 0;
-        f32x4 gj[T];
+        for (int u = 0; u < UNR; ++u) {
+            r[u] = ((int64_t)hd[u][1] << 32) | (uint32_t)hd[u][0];
+            len[u] = hd[u][3];
+            const bool in_list = base + u * GPW + grp < n_rows;
+            const bool in_table = (r[u] >= 0) && (r[u] < num_rows);
+            oob |= in_list && !in_table;
+            const bool is_short = len[u] >= 1 && len[u] <= T;
+            const bool slot_ok = (unsigned)hd[u][2] < (unsigned)n;
+            bad |= in_list && (len[u] < 1 || !slot_ok);
+            const bool live = in_list && in_table && is_short && slot_ok;
+            if (!live) len[u] = 0;
+            mine[u] = live && col_ok;
+            any_more |= len[u] > 4;
+            w[u] = u32x4{0u, 0u, 0u, 0u};
+            if (mine[u]) {
+                if (BF16) {
+                    const u32x2 h = t2[r[u] * gvec + lig];
+                    w[u][0] = h[0];
+                    w[u][1] = h[1];
+                } else {
+                    w[u] = t4[r[u] * gvec + lig];
+                }
+            }
+            s_old[u] = live ? state[r[u]] : 0.f;
 #pragma unroll
-        for (int j = 0; j < T; ++j) {
-            gj[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-            if ((unsigned)pj[j] >= (unsigned)n) { bad = true; pj[j] = 0; }
-            if (mine && j < len) gj[j] = __builtin_nontemporal_load(&grads[(int64_t)pj[j] * gvec + lig]);
+            for (int j = 0; j < 4; ++j) {
+                g[u][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+                int p = pa[u][j];
+                if ((unsigned)p >= (unsigned)n) { bad |= j < len[u]; p = 0; }
+                if (mine[u] && j < len[u]) g[u][j] = __builtin_nontemporal_load(&grads[(int64_t)p * gvec + lig]);
+            }
         }
-        double acc[4] = {0.0, 0.0, 0.0, 0.0};
+        double acc[UNR][4];
 #pragma unroll
-        for (int j = 0; j < T; ++j)
+        for (int u = 0; u < UNR; ++u)
 #pragma unroll
-            for (int c = 0; c < 4; ++c) acc[c] += (double)gj[j][c];
-        const f32x4 g = {(float)acc[0], (float)acc[1], (float)acc[2], (float)acc[3]};
-        double ss = 0.0;
+            for (int c = 0; c < 4; ++c) {
+                acc[u][c] = (double)g[u][0][c];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) ss += (double)g[c] * (double)g[c];
-        ss = group_sum<LPR>(ss);
-        const float m = (float)(ss / (double)dim);
-        const float s_new = s_old + m;
-        const float c_step = __fdiv_rn(lr, __fsqrt_rn(s_new) + eps);
-        if (BF16) {
-            const float c0 = bf16_lo(w[0]) - c_step * g[0];
-            const float c1 = bf16_hi(w[0]) - c_step * g[1];
-            const float c2 = bf16_lo(w[1]) - c_step * g[2];
-            const float c3 = bf16_hi(w[1]) - c_step * g[3];
-            const u32x2 o = {f32_to_bf16_bits(c0) | (f32_to_bf16_bits(c1) << 16),
-                             f32_to_bf16_bits(c2) | (f32_to_bf16_bits(c3) << 16)};
-            if (mine) t2[r * gvec + lig] = o;
-        } else {
-            u32x4 o;
+                for (int j = 1; j < 4; ++j) acc[u][c] += (double)g[u][j][c];
+            }
+        if (__ballot(any_more) != 0) {                        // wave-uniform: some row has 5..8 occurrences
 #pragma unroll
-            for (int c = 0; c < 4; ++c) o[c] = __float_as_uint(__uint_as_float(w[c]) - c_step * g[c]);
-            if (mine) t4[r * gvec + lig] = o;
+            for (int u = 0; u < UNR; ++u)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    g[u][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    int p = pb[u][j];
+                    if ((unsigned)p >= (unsigned)n) { bad |= 4 + j < len[u]; p = 0; }
+                    if (mine[u] && 4 + j < len[u]) g[u][j] = __builtin_nontemporal_load(&grads[(int64_t)p * gvec + lig]);
+                }
+#pragma unroll
+            for (int u = 0; u < UNR; ++u)
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[u][c] += (double)g[u][j][c];
         }
-        if (live && lig == 0) state[r] = s_new;
-        if (reduced != nullptr && mine) reduced[(int64_t)k * gvec + lig] = g;
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const f32x4 gs = {(float)acc[u][0], (float)acc[u][1], (float)acc[u][2], (float)acc[u][3]};
+            double ss = 0.0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) ss += (double)gs[c] * (double)gs[c];
+            ss = group_sum<LPR>(ss);
+            const float m = (float)(ss / (double)dim);
+            const float s_new = s_old[u] + m;
+            const float c_step = __fdiv_rn(lr, __fsqrt_rn(s_new) + eps);
+            if (BF16) {
+                const float c0 = bf16_lo(w[u][0]) - c_step * gs[0];
+                const float c1 = bf16_hi(w[u][0]) - c_step * gs[1];
+                const float c2 = bf16_lo(w[u][1]) - c_step * gs[2];
+                const float c3 = bf16_hi(w[u][1]) - c_step * gs[3];
+                const u32x2 o = {f32_to_bf16_bits(c0) | (f32_to_bf16_bits(c1) << 16),
+                                 f32_to_bf16_bits(c2) | (f32_to_bf16_bits(c3) << 16)};
+                if (mine[u]) t2[r[u] * gvec + lig] = o;
+            } else {
+                u32x4 o;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) o[c] = __float_as_uint(__uint_as_float(w[u][c]) - c_step * gs[c]);
+                if (mine[u]) t4[r[u] * gvec + lig] = o;
+            }
+            if (len[u] > 0 && lig == 0) state[r[u]] = s_new;
+            if (reduced != nullptr && mine[u]) reduced[(int64_t)hd[u][2] * gvec + lig] = gs;
+        }
     }
     if (oob) atomicOr(flags, kFlagRowRange);
     if (bad) atomicOr(flags, kFlagInternal);
+}
+
+// One launch per class: the first `long_blocks` workgroups walk the class order (rows with many
+// occurrences, position-cut), the others the records of the rows with few.  The long part goes
+// first because its last arrivers have the longest dependent chains; workgroups past the end of
+// either part leave at once, so an empty part costs nothing but their dispatch.
+template <bool BF16, int LPR, int UNR, int CHUNK, int SU>
+__global__ __launch_bounds__(kFusedWaves *kWave) void class_pass_kernel(
+    const f32x4 *__restrict__ grads, int n, int long_blocks, const int32_t *__restrict__ cperm,
+    const int32_t *__restrict__ cslot, const int32_t *__restrict__ class_pos, int cls,
+    const int32_t *__restrict__ seg_offsets, const int32_t *__restrict__ cstart, const int64_t *__restrict__ u_t,
+    const int32_t *__restrict__ recs, const int64_t *__restrict__ n_rows_dev, void *table, float *state,
+    int64_t num_rows, int gvec, float lr, float eps, f32x4 *reduced, double *part_head, double *part_last,
+    int *cnt_seg, int *cnt_sup, int *flags) {
+    if ((int)blockIdx.x < long_blocks)
+        long_segments_body<BF16, LPR, UNR, CHUNK>((int)blockIdx.x, grads, cperm, cslot, class_pos, cls, n, seg_offsets,
+                                                  cstart, u_t, table, state, num_rows, gvec, lr, eps, reduced,
+                                                  part_head, part_last, cnt_seg, cnt_sup, flags);
+    else
+        short_rows_body<BF16, LPR, SU>((int)blockIdx.x - long_blocks, (int)gridDim.x - long_blocks, grads, n, recs,
+                                       n_rows_dev, (int64_t)n, table, state, num_rows, gvec, lr, eps, reduced, flags);
 }
 
 template <bool BF16, int LPR, int CHUNK>
 static void fused_launch(fs_ctx *ctx, int cls, const float *grads, int n, int gvec, const int32_t *cperm,
                          const int32_t *cslot, const int32_t *class_pos, const int32_t *seg_offsets,
                          const int32_t *cstart, const int64_t *u_t, void *table, float *state, int64_t num_rows,
-                         float lr, float eps, float *reduced, hipStream_t s, const int32_t *perm,
-                         const int64_t *rows, const int32_t *slots, const int64_t *n_rows_dev) {
+                         float lr, float eps, float *reduced, hipStream_t s, const int32_t *short_rec,
+                         const int64_t *n_rows_dev) {
     constexpr int GPW = kWave / LPR;
-    {
-        // short path first: it is the larger part of the rows and its wavefronts are short-lived
-        int64_t sblocks = ceil_div(n, (int64_t)GPW * 4);
-        if (sblocks > 8192) sblocks = 8192;                   // grid-stride beyond this; the list length lives on the device
-        hipLaunchKernelGGL((short_rows_kernel<BF16, LPR>), dim3((unsigned)sblocks), dim3(256), 0, s,
-                           (const f32x4 *)grads, n, perm, seg_offsets, rows, slots, n_rows_dev, (int64_t)n, table,
-                           state, num_rows, gvec, lr, eps, (f32x4 *)reduced, ctx->d_flags);
-    }
+    constexpr int SU = FS_SHORT_UNR;
     constexpr int UNR = (CHUNK / GPW) < FS_FUSED_UNR ? ((CHUNK / GPW) < 1 ? 1 : (CHUNK / GPW)) : FS_FUSED_UNR;
     constexpr int CH = CHUNK < GPW ? GPW : CHUNK;             // at least one row group per chunk
-    const int n_chunks = (int)ceil_div(n, CH);
-    const int blocks = (int)ceil_div(n_chunks, kFusedWaves);
-    hipLaunchKernelGGL((reduce_update_kernel<BF16, LPR, UNR, CH>), dim3(blocks), dim3(kFusedWaves * kWave), 0, s,
-                       (const f32x4 *)grads, cperm, cslot, class_pos, cls, n, seg_offsets, cstart, u_t, table, state,
-                       num_rows, gvec, lr, eps, (f32x4 *)reduced, ctx->fpart_head[cls], ctx->fpart_last[cls],
-                       ctx->fcounters[cls], ctx->fcounters_sup[cls], ctx->d_flags);
+    // Both parts are sized for the worst case the host can know (every occurrence in a long
+    // segment / every occurrence a row of its own); the real sizes live on the device.
+    const int long_blocks = (int)ceil_div(ceil_div(n, CH), kFusedWaves);
+    int64_t short_blocks = ceil_div(n, (int64_t)GPW * SU * kFusedWaves);
+    if (short_blocks > FS_SHORT_MAX_BLOCKS) short_blocks = FS_SHORT_MAX_BLOCKS;   // grid-stride beyond this
+    hipLaunchKernelGGL((class_pass_kernel<BF16, LPR, UNR, CH, SU>), dim3((unsigned)(long_blocks + short_blocks)),
+                       dim3(kFusedWaves * kWave), 0, s, (const f32x4 *)grads, n, long_blocks, cperm, cslot, class_pos,
+                       cls, seg_offsets, cstart, u_t, short_rec, n_rows_dev, table, state, num_rows, gvec, lr, eps,
+                       (f32x4 *)reduced, ctx->fpart_head[cls], ctx->fpart_last[cls], ctx->fcounters[cls],
+                       ctx->fcounters_sup[cls], ctx->d_flags);
 }
 
 int launch_reduce_update(fs_ctx *ctx, int cls, const float *grads, int64_t n, int32_t dim, const int32_t *cperm,
                          const int32_t *cslot, const int32_t *class_pos, const int32_t *seg_offsets,
                          const int32_t *cstart, const int64_t *u_t, void *table, int dt, float *state,
-                         int64_t num_rows, float lr, float eps, float *reduced, hipStream_t s, const int32_t *perm,
-                         const int64_t *rows, const int32_t *slots, const int64_t *n_rows_dev) {
+                         int64_t num_rows, float lr, float eps, float *reduced, hipStream_t s,
+                         const int32_t *short_rec, const int64_t *n_rows_dev) {
     if (n == 0) return FS_OK;
     const int gvec = dim / 4;
     const bool bf = dt == FS_BF16;
 #define FS_ARGS ctx, cls, grads, (int)n, gvec, cperm, cslot, class_pos, seg_offsets, cstart, u_t, table, state, num_rows, \
-                lr, eps, reduced, s, perm, rows, slots, n_rows_dev
+                lr, eps, reduced, s, short_rec, n_rows_dev
 #define FS_CASE(L)                                                                   \
     case L:                                                                          \
         if (cls == 0) {                                                              \
@@ -531,7 +603,7 @@ int launch_reduce_update(fs_ctx *ctx, int cls, const float *grads, int64_t n, in
     }
 #undef FS_CASE
 #undef FS_ARGS
-    FS_LAUNCH_CHECK(ctx, "reduce+update kernels");
+    FS_LAUNCH_CHECK(ctx, "class_pass_kernel");
     return FS_OK;
 }
 

@@ -135,7 +135,8 @@ __global__ __launch_bounds__(kScanThreads) void split_compact_kernel(
     const uint8_t *__restrict__ flag_t, const uint8_t *__restrict__ flag_t1, const int32_t *__restrict__ tile_cnt,
     int64_t *__restrict__ co, int32_t *__restrict__ co_slot, int64_t *__restrict__ ex, int32_t *__restrict__ ex_slot,
     int64_t *__restrict__ ex_next, int32_t *__restrict__ ex_next_slot, int64_t *__restrict__ counts_dev,
-    const int32_t *__restrict__ seg_offsets_t, int32_t *__restrict__ cstart_local, int32_t *__restrict__ tile_len) {
+    const int32_t *__restrict__ seg_offsets_t, int32_t *__restrict__ cstart_local, int32_t *__restrict__ tile_len,
+    int32_t *__restrict__ cidx) {
     __shared__ int sh[kScanThreads / kWave];
     const int n_t = clamp_count(n_t_dev, cap_t), n_t1 = clamp_count(n_t1_dev, cap_t1);
     const bool side_t = (int)blockIdx.x < tiles_t;
@@ -169,6 +170,7 @@ __global__ __launch_bounds__(kScanThreads) void split_compact_kernel(
             if (side_t) {
                 if (f[i]) { co[r_found] = id; co_slot[r_found] = p; }
                 else { ex[p - r_found] = id; ex_slot[p - r_found] = p; }
+                if (seg_offsets_t != nullptr) cidx[p] = f[i] ? r_found : p - r_found;   // place in its class list
             } else if (!f[i]) {
                 ex_next[p - r_found] = id; ex_next_slot[p - r_found] = p;
             }
@@ -220,7 +222,8 @@ __global__ __launch_bounds__(kScanThreads) void class_scatter_kernel(
     const int32_t *__restrict__ perm, const int32_t *__restrict__ inverse, const int32_t *__restrict__ seg_offsets,
     int n, int tiles_t, const uint8_t *__restrict__ flag_t, const int32_t *__restrict__ cstart_local,
     const int32_t *__restrict__ tile_len, int32_t *__restrict__ cperm, int32_t *__restrict__ cslot,
-    int32_t *__restrict__ cstart, int32_t *__restrict__ class_pos_dev, int *__restrict__ flags) {
+    int32_t *__restrict__ cstart, int32_t *__restrict__ class_pos_dev, int *__restrict__ flags,
+    const int64_t *__restrict__ u_t, const int32_t *__restrict__ cidx, int32_t *__restrict__ short_rec, int cap) {
     extern __shared__ int tile_base[];                      // [2 * tiles_t]
     __shared__ int sh[kScanThreads / kWave];
     int class_total[2];
@@ -262,7 +265,24 @@ __global__ __launch_bounds__(kScanThreads) void class_scatter_kernel(
             const bool is_co = flag_t[slot] != 0;
             const int tile = slot / kScanTile;
             const int first = seg_offsets[slot];
-            if (seg_offsets[slot + 1] - first <= FS_SHORT_SEGMENT) continue;
+            const int len = seg_offsets[slot + 1] - first;
+            // one record per row of the batch, at the row's place in its class list: header (row,
+            // slot, occurrences) from the row's first position, occurrences only for short segments
+            const int li = cidx[slot];
+            if (li < 0 || li >= cap) {
+                atomicOr(flags, kFlagInternal);
+                continue;
+            }
+            int32_t *rec = short_rec + ((int64_t)(is_co ? 0 : cap) + li) * kShortRecInts;
+            if (q == first) {
+                const int64_t row = u_t[slot];
+                typedef int i32x4 __attribute__((ext_vector_type(4)));
+                *reinterpret_cast<i32x4 *>(rec) = i32x4{(int)(row & 0xFFFFFFFFll), (int)(row >> 32), slot, len};
+            }
+            if (len <= FS_SHORT_SEGMENT) {
+                rec[4 + (q - first)] = i[k];
+                continue;
+            }
             const int dest = (is_co ? tile_base[tile] : n_co_pos + tile_base[tiles_t + tile]) + cstart_local[slot] +
                              (q - first);
             if (dest < 0 || dest >= n) {                     // cannot happen with a consistent layout and split
@@ -305,14 +325,15 @@ int launch_split(fs_ctx *ctx, const int64_t *u_t, const int64_t *n_t_dev, const 
     hipLaunchKernelGGL(split_compact_kernel, dim3(tt + tiles_t1), dim3(kScanThreads), 0, s, u_t, n_t_dev, u_t1,
                        n_t1_dev, cap_t, cap_t1, tt, tiles_t1, (const uint8_t *)ctx->split_flag_t,
                        (const uint8_t *)ctx->split_flag_t1, (const int32_t *)ctx->split_cnt, co, co_slot, ex, ex_slot,
-                       ex_next, ex_next_slot, counts_dev, seg_offsets_t, ctx->cstart_local, ctx->tile_len);
+                       ex_next, ex_next_slot, counts_dev, seg_offsets_t, ctx->cstart_local, ctx->tile_len,
+                       ctx->cidx);
     FS_LAUNCH_CHECK(ctx, "split kernels");
     return FS_OK;
 }
 
 int launch_class_order(fs_ctx *ctx, const int32_t *perm, const int32_t *inverse, const int32_t *seg_offsets,
                        int64_t n, int64_t cap_u, int32_t *cperm, int32_t *cslot, int32_t *cstart,
-                       int32_t *class_pos_dev, hipStream_t s) {
+                       int32_t *class_pos_dev, const int64_t *u_t, int32_t *short_rec, hipStream_t s) {
     if (n == 0) {
         hipLaunchKernelGGL(class_empty_kernel, dim3(1), dim3(1), 0, s, class_pos_dev);
         FS_LAUNCH_CHECK(ctx, "class_empty_kernel");
@@ -324,7 +345,8 @@ int launch_class_order(fs_ctx *ctx, const int32_t *perm, const int32_t *inverse,
     hipLaunchKernelGGL(class_scatter_kernel, dim3((unsigned)ceil_div(n, kScanTile)), dim3(kScanThreads),
                        (size_t)tiles_t * 2 * sizeof(int), s, perm, inverse, seg_offsets, (int)n, tiles_t,
                        (const uint8_t *)ctx->split_flag_t, (const int32_t *)ctx->cstart_local,
-                       (const int32_t *)ctx->tile_len, cperm, cslot, cstart, class_pos_dev, ctx->d_flags);
+                       (const int32_t *)ctx->tile_len, cperm, cslot, cstart, class_pos_dev, ctx->d_flags, u_t,
+                       (const int32_t *)ctx->cidx, short_rec, (int)cap_u);
     FS_LAUNCH_CHECK(ctx, "class_scatter_kernel");
     return FS_OK;
 }

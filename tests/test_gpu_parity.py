@@ -322,6 +322,19 @@ def test_class_order_bit_exact(ctx, n0, n1, rows):
     for name in ("co", "ex"):
         cnt = len(sp_o[name])
         assert np.array_equal(sp[name][:cnt].cpu().numpy(), sp_o[name])
+    # one record per row, at the row's place in its class list
+    rec = sp["short_rec"][:2 * 12 * n0].cpu().numpy().reshape(2, n0, 12)
+    seg = lay_o["seg_offsets"].astype(np.int64)
+    for cls, name in enumerate(("co", "ex")):
+        rows_c, slots_c = sp_o[name], sp_o[name + "_slot"]
+        got = rec[cls, :len(rows_c)]
+        assert np.array_equal(got[:, 0:2].copy().view(np.int64).ravel(), rows_c)
+        assert np.array_equal(got[:, 2], slots_c)
+        lens = (seg[slots_c + 1] - seg[slots_c]).astype(np.int32)
+        assert np.array_equal(got[:, 3], lens)
+        for li in np.nonzero(lens <= fs.FS_SHORT_SEGMENT)[0]:
+            s_ = slots_c[li]
+            assert np.array_equal(got[li, 4:4 + lens[li]], lay_o["perm"][seg[s_]:seg[s_ + 1]])
 
 
 def check_fused(ctx, rng, ids_t, ids_t1, rows, dim, dtype, n_passes=1):
