@@ -8,7 +8,6 @@
 #include <functional>
 #include <mutex>
 #include <new>
-#include <stdlib.h>
 #include <thread>
 
 #include "fs_common.h"
@@ -165,7 +164,6 @@ int fs_ctx_create(fs_ctx **out, int device, int64_t max_ids, int32_t max_dim) {
     c->max_ids = max_ids;
     c->max_dim = max_dim;
     c->use_worker = true;
-    if (const char *e = getenv("FS_DEFERRED_ON")) c->deferred_on = atoi(e);
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || device >= ndev) {
         delete c;
@@ -744,9 +742,8 @@ int fs_prioritized_step_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs
     hipEvent_t *tex = have_t ? timing_pair(ctx, FS_TIME_UPDATE_EX) : nullptr;
     fs_step_args cur_copy = *cur, next_copy = next ? *next : *cur;
     const bool has_next = next != nullptr;
-    const bool ex_on_side = ctx->deferred_on == 0;
     auto side_job = [=]() -> int {
-        return enqueue_side_stream(ctx, (have_t && ex_on_side) ? &cur_copy : nullptr,
+        return enqueue_side_stream(ctx, have_t ? &cur_copy : nullptr,
                                    has_next ? &next_copy : nullptr, nxt_t, nxt_t1, ahead, p, tex);
     };
     if (w0) w0->post(side_job);
@@ -757,7 +754,6 @@ int fs_prioritized_step_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs
     const double h3 = now_us();
     if (rc == FS_OK && have_t) rc = enqueue_class_pass(ctx, cur, 0, sp, timing_pair(ctx, FS_TIME_UPDATE_CO));
     if (rc == FS_OK && have_t1) rc = enqueue_gather(ctx, cur, sp);
-    if (rc == FS_OK && have_t && !ex_on_side) rc = enqueue_class_pass(ctx, cur, 1, sp, tex);
     const double h4 = now_us();
     if (!w0) {
         const int src = side_job();

@@ -97,8 +97,6 @@ struct fs_ctx {
     double host_us[7];        // host-side time spent in the phases of the pipelined call (measurement aid)
     struct fs_host *host;     // host threads and the table of outstanding ahead-of-time dedups
     bool use_worker;
-    int deferred_on;          // where the pipelined call runs the deferred pass: 0 side stream (beside the priority
-                              // pass), 1 the caller's stream after the gather
     hipStream_t stream_cap;   // capture stream of fs_graph_capture_pipelined
     bool capturing;           // host-side: a step is being recorded into a graph (no timing events)
     int timing_slots;
