@@ -28,6 +28,15 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 
+# HBM bytes per launch measured with hardware counters (FETCH_SIZE, WRITE_SIZE, each scaled by what
+# the same counter reads for a plain copy of known size) in separate counter runs of this file on
+# the default workload; the runs and their figures are summarised under profiles/.
+MEASURED_TRAFFIC_BYTES = {
+    ("configs[1]", "class_pass_kernel (priority pass)"): 156.5e6,
+    ("configs[1]", "class_pass_kernel (deferred pass)"): 109.5e6,
+    ("configs[1]", "gather_kernel"): 202.3e6,
+}
+
 
 def algorithmic_bytes(n_t, u_t, n_t1, u_t1, dim, w):
     """Compulsory bytes of one step (each distinct row counted once per pass; the sort's
@@ -49,6 +58,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--time-every", type=int, default=8,
                     help="bracket the kernels of one timed step in this many with HIP event pairs")
+    ap.add_argument("--calibration-copy", type=int, default=0, metavar="MiB",
+                    help="also launch one plain copy of this many MiB before the steps: the known-size dispatch that "
+                         "hardware byte counters are scaled by in a counter run")
     ap.add_argument("--no-ahead", action="store_true",
                     help="pipelined mode: dedup the lookahead IDs inside the step call instead of batches ahead on "
                          "the index streams")
@@ -133,6 +145,13 @@ def main() -> int:
                 fs.fs_prioritized_step_pipelined(ctx, records[s % period], records[(s + 1) % period])
             else:
                 fs.fs_prioritized_step(ctx, records[s % period])
+
+    if args.calibration_copy > 0:
+        src = torch.empty(args.calibration_copy << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        fs.fs_stream_copy(ctx, src, dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- one untimed step from the fresh table, checked against the oracle on the touched rows
     cpu_baseline = None
@@ -227,14 +246,17 @@ def main() -> int:
     step_bytes = sum(by[s % 2]["total"] for s in range(k0, k0 + args.steps)) / args.steps
     step_gbps = step_bytes / (ms_per_step * 1e-3) / 1e9
 
-    # Occurrences and rows per class of the two alternating iterations (split buffers of the last
-    # step and of the index half that followed it).
+    # Occurrences and rows per class of the two alternating iterations: from the layout of each batch
+    # and the split buffers of the last step and of the index half that followed it.
     s_last = k0 + args.steps - 1
     cls_pos, cls_rows = {}, {}
     for s in (s_last, s_last + 1):
-        cp = splits[s % 3]["class_pos"].cpu().numpy().tolist()
-        cn = splits[s % 3]["counts"].cpu().numpy().tolist()
-        cls_pos[s % 2] = (cp[0], cp[1] - cp[0])
+        lay, sp = layouts[s % L], splits[s % 3]
+        cn = sp["counts"].cpu().numpy().tolist()
+        seg = lay["seg_offsets"][:u[s % 2] + 1].cpu().numpy().astype(np.int64)
+        lens = seg[1:] - seg[:-1]
+        co_pos = int(lens[sp["co_slot"][:cn[0]].cpu().numpy()].sum())
+        cls_pos[s % 2] = (co_pos, n[s % 2] - co_pos)
         cls_rows[s % 2] = (cn[0], cn[1])
 
     def class_pass_bytes(b, c):
@@ -247,17 +269,18 @@ def main() -> int:
     if kernel_ms.get("gather"):
         cand.append(("gather_kernel", kernel_ms["gather"], avg(lambda b: by[b]["gather"])))
     if kernel_ms.get("priority_pass"):
-        cand.append(("reduce_update_kernel (priority pass)", kernel_ms["priority_pass"],
+        cand.append(("class_pass_kernel (priority pass)", kernel_ms["priority_pass"],
                      avg(lambda b: class_pass_bytes(b, 0))))
     if kernel_ms.get("deferred_pass"):
-        cand.append(("reduce_update_kernel (deferred pass)", kernel_ms["deferred_pass"],
+        cand.append(("class_pass_kernel (deferred pass)", kernel_ms["deferred_pass"],
                      avg(lambda b: class_pass_bytes(b, 1))))
     roofline = None
     if cand:
         name, ms, nbytes = max(cand, key=lambda c: c[1])
         achieved = nbytes / (ms * 1e-3) / 1e9
+        traffic = MEASURED_TRAFFIC_BYTES.get((f"configs[{cfg.index}]", name)) if pipelined and ahead else None
         roofline = {"bound": "hbm", "kernel": name, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBPS, "traffic": None, "avg_launch_us": ms * 1e3,
+                    "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "avg_launch_us": ms * 1e3,
                     "algorithmic_bytes_per_launch": nbytes,
                     "all_kernels": {nm: {"avg_launch_us": m * 1e3, "algorithmic_bytes": nb,
                                          "GBps": nb / (m * 1e-3) / 1e9} for nm, m, nb in cand}}
