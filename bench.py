@@ -56,11 +56,17 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=1, help="index into the workload configurations (default 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-isolated", action="store_true",
+                    help="skip the extra launches that time every kernel alone on the chip after the timed steps")
     ap.add_argument("--time-every", type=int, default=8,
                     help="bracket the kernels of one timed step in this many with HIP event pairs")
     ap.add_argument("--calibration-copy", type=int, default=0, metavar="MiB",
                     help="also launch one plain copy of this many MiB before the steps: the known-size dispatch that "
                          "hardware byte counters are scaled by in a counter run")
+    ap.add_argument("--ahead-order", choices=["last_step", "stream"], default="last_step",
+                    help="what an ahead-of-time dedup is ordered after: the start of the most recent pipelined call "
+                         "(no event on the caller's stream, six layout buffers) or the caller's stream as it stands "
+                         "(one more event per step on it, five layout buffers)")
     ap.add_argument("--no-ahead", action="store_true",
                     help="pipelined mode: dedup the lookahead IDs inside the step call instead of batches ahead on "
                          "the index streams")
@@ -107,12 +113,14 @@ def main() -> int:
 
     # Buffers.  The index half of step s+1 runs beside the gradient half of step s, and with
     # ahead-of-time dedups the layout of batch s+3 is being written meanwhile: five layout buffers
-    # in rotation (three without), three split/class buffers.  The two batches alternate, so the
+    # in rotation (six when the dedup is only ordered after the start of the previous call, three
+    # without ahead-of-time dedups), three split/class buffers.  The two batches alternate, so the
     # argument records repeat with period lcm(L, 3, 2).
     pipelined = args.mode in ("pipelined", "graph")
     ahead = args.mode == "pipelined" and not args.no_ahead
-    L = 5 if ahead else 3
-    period = 30 if ahead else 6
+    last_step_order = ahead and args.ahead_order == "last_step"
+    L = (6 if last_step_order else 5) if ahead else 3
+    period = (6 if last_step_order else 30) if ahead else 6
     nmax = max(n)
     layouts = [fs.alloc_layout(nmax, dev) for _ in range(L)]
     splits = [fs.alloc_split(nmax, nmax, dev) for _ in range(3)]
@@ -131,9 +139,12 @@ def main() -> int:
     fs.fs_unique_ids(ctx, d_vals[0], tab.num_rows, out=layouts[0])
     graphs = None
 
+    stepped = [False]
+
     def dedup_ahead(s):
         if ahead:
-            fs.fs_unique_ids_ahead(ctx, d_vals[s % 2], tab.num_rows, layouts[s % L])
+            fs.fs_unique_ids_ahead(ctx, d_vals[s % 2], tab.num_rows, layouts[s % L],
+                                   stream=fs.FS_STREAM_LAST_STEP if (last_step_order and stepped[0]) else None)
 
     def run(k0, k, records=None):
         records = records or step_args
@@ -143,6 +154,7 @@ def main() -> int:
             elif pipelined:
                 dedup_ahead(s + 3)
                 fs.fs_prioritized_step_pipelined(ctx, records[s % period], records[(s + 1) % period])
+                stepped[0] = True
             else:
                 fs.fs_prioritized_step(ctx, records[s % period])
 
@@ -285,6 +297,44 @@ def main() -> int:
                     "all_kernels": {nm: {"avg_launch_us": m * 1e3, "algorithmic_bytes": nb,
                                          "GBps": nb / (m * 1e-3) / 1e9} for nm, m, nb in cand}}
 
+    # ---- the same kernels alone on the chip: each operation launched 20 times back to back on one
+    # stream with nothing beside it (after the timed region; the table keeps being updated, which
+    # does not change what the kernels move)
+    isolated = None
+    if not args.no_isolated:
+        def alone(f, reps=20):
+            for _ in range(3):
+                f()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                f()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps * 1e3
+
+        fs.fs_step_join(ctx)
+        torch.cuda.synchronize()
+        lay_a = fs.fs_unique_ids(ctx, d_vals[0], tab.num_rows)
+        lay_b = fs.fs_unique_ids(ctx, d_vals[1], tab.num_rows)
+        sp_a = fs.fs_collision_split_classes(ctx, lay_a, lay_b["unique"], lay_b["n_unique"], n[1])
+        iso = {
+            "class_pass_kernel (priority pass)": (alone(lambda: fs.fs_reduce_update_class(
+                ctx, 0, table, state, cfg.lr, cfg.eps, d_grads[0], lay_a, sp_a)), class_pass_bytes(0, 0)),
+            "class_pass_kernel (deferred pass)": (alone(lambda: fs.fs_reduce_update_class(
+                ctx, 1, table, state, cfg.lr, cfg.eps, d_grads[0], lay_a, sp_a)), class_pass_bytes(0, 1)),
+            "gather_kernel": (alone(lambda: fs.fs_gather_jagged(ctx, table, d_vals[1], d_offs[1], out=embs[1])),
+                              by[0]["gather"]),
+            "dedup (8 launches)": (alone(lambda: fs.fs_unique_ids(ctx, d_vals[1], tab.num_rows, out=lay_b)),
+                                   by[0]["unique"]),
+            "split + class order + records (3 launches)": (alone(lambda: fs.fs_collision_split_classes(
+                ctx, lay_a, lay_b["unique"], lay_b["n_unique"], n[1], out=sp_a)), by[0]["split"]),
+        }
+        assert fs.fs_check_async(ctx) == fs.FS_OK, ctx.last_error()
+        isolated = {k: {"us": t, "algorithmic_bytes": nb, "GBps": nb / (t * 1e-6) / 1e9,
+                        "frac_of_hbm_peak": nb / (t * 1e-6) / 1e9 / HBM_PEAK_GBPS} for k, (t, nb) in iso.items()}
+
     out = {
         "metric": "unique embedding rows updated/sec + achieved HBM GB/s (% of peak), 1 GPU",
         "value": rows / elapsed, "unit": "rows/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -302,6 +352,7 @@ def main() -> int:
         "step_frac_of_hbm_peak": step_gbps / HBM_PEAK_GBPS,
         "kernel_avg_us": {k: (v * 1e3 if v is not None else None) for k, v in kernel_ms.items()},
         "roofline": roofline,
+        "isolated_kernels": isolated,
         "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(out))

@@ -241,7 +241,12 @@ int fs_step_forward(fs_ctx *ctx, const fs_step_args *args, fs_stream stream);
  * itself); anyone else must call fs_step_join or fs_check_async first.  The outputs must not be
  * in use by work that is not ordered before `stream`'s current position; in a loop of pipelined
  * calls that means five layout buffers in rotation when the dedup runs two batches ahead of the
- * call that consumes it as u_t1.  At most four such dedups may be outstanding. */
+ * call that consumes it as u_t1.  At most four such dedups may be outstanding.
+ * stream == FS_STREAM_LAST_STEP: no event is recorded on any stream of the caller; the dedup is
+ * ordered after the position the caller's stream had at the START of the most recent
+ * fs_prioritized_step_pipelined call (its deferred pass may still be running: one more layout
+ * buffer in the rotation, six).  The caller vouches that `ids` are complete by then. */
+#define FS_STREAM_LAST_STEP ((fs_stream)(intptr_t)-1)
 int fs_unique_ids_ahead(fs_ctx *ctx, const int64_t *ids, int64_t n, int64_t num_rows,
                         int64_t *unique, int32_t *seg_offsets, int32_t *perm, int32_t *inverse,
                         int64_t *n_unique_dev, fs_stream stream);

@@ -271,12 +271,16 @@ def fs_reduce_update_class(ctx: Context, cls: int, table: torch.Tensor, state: t
     ctx.check(rc, "fs_reduce_update_class")
 
 
+FS_STREAM_LAST_STEP = "last_step"
+
+
 def fs_unique_ids_ahead(ctx: Context, ids: torch.Tensor, num_rows: int, out: Dict[str, torch.Tensor],
                         stream=None) -> Dict[str, torch.Tensor]:
     n = ids.numel()
+    stream_arg = ctypes.c_void_p(-1) if stream == FS_STREAM_LAST_STEP else _stream(stream)
     rc = ctx.lib.fs_unique_ids_ahead(ctx.handle, _ptr(ids), n, num_rows, _ptr(out["unique"]),
                                      _ptr(out["seg_offsets"]), _ptr(out["perm"]), _ptr(out["inverse"]),
-                                     _ptr(out["n_unique"]), _stream(stream))
+                                     _ptr(out["n_unique"]), stream_arg)
     ctx.check(rc, "fs_unique_ids_ahead")
     out["n"] = n
     return out

@@ -634,12 +634,20 @@ int fs_unique_ids_ahead(fs_ctx *ctx, const int64_t *ids, int64_t n, int64_t num_
     const int x = h->x_turn;
     h->x_turn ^= 1;
     hipStream_t sx = ctx->stream_x[x];
-    FS_HIP(ctx, hipEventRecord(e->fork, as_stream(stream)));
+    // what the dedup is ordered after: the caller's stream as it stands, or - no new event on the
+    // caller's stream - its position at the start of the most recent pipelined call
+    hipEvent_t after = e->fork;
+    if (stream == FS_STREAM_LAST_STEP) {
+        FS_REQUIRE(ctx, ctx->pfork_valid, "unique ahead: FS_STREAM_LAST_STEP before any pipelined call");
+        after = ctx->ev_pfork[ctx->pipe_parity];
+    } else {
+        FS_HIP(ctx, hipEventRecord(e->fork, as_stream(stream)));
+    }
     e->unique = unique;
     e->state.store(kAheadPosted, std::memory_order_release);
     auto job = [=]() -> int {
         int rc = FS_OK;
-        if (hipStreamWaitEvent(sx, e->fork, 0) != hipSuccess) rc = FS_EHIP;
+        if (hipStreamWaitEvent(sx, after, 0) != hipSuccess) rc = FS_EHIP;
         if (rc == FS_OK)
             rc = launch_unique(ctx, ids, n, num_rows, unique, seg_offsets, perm, inverse, n_unique_dev, sx, 1 + x);
         if (hipEventRecord(e->done, sx) != hipSuccess && rc == FS_OK) rc = FS_EHIP;
@@ -735,8 +743,14 @@ int fs_prioritized_step_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs
         rc = ctx->host->worker[0]->wait();                   // host side only: the previous job is enqueued
         if (rc != FS_OK) return set_err(ctx, rc, "side-stream enqueue of the previous call failed");
     }
+    if (ctx->host->worker[1]) {
+        // an ahead-of-time dedup may still have to enqueue its wait for the event recorded next
+        rc = ctx->host->worker[1]->wait();
+        if (rc != FS_OK) return set_err(ctx, rc, "index-stream enqueue failed");
+    }
     const double h1 = now_us();
     FS_HIP(ctx, hipEventRecord(ctx->ev_pfork[p], sp));
+    ctx->pfork_valid = true;
     fs_ahead *ahead = (next && nxt_t1 && !ctx->capturing) ? find_ahead(ctx, next->u_t1) : nullptr;
     if (ahead) ahead->unique = nullptr;                      // claimed: the side job frees the slot
     hipEvent_t *tex = have_t ? timing_pair(ctx, FS_TIME_UPDATE_EX) : nullptr;

@@ -93,6 +93,7 @@ struct fs_ctx {
     hipEvent_t ev_pfork[2];   // position of the caller's stream at the start of a pipelined call (alternating)
     hipEvent_t ev_side[2];    // side-stream work of a pipelined call (deferred pass of cur, index half of next) done
     int pipe_parity;          // event set used by the last pipelined call
+    bool pfork_valid;         // host-side: ev_pfork[pipe_parity] has been recorded
     bool side_pending;        // host-side: side-stream work is in flight and not yet joined
     double host_us[7];        // host-side time spent in the phases of the pipelined call (measurement aid)
     struct fs_host *host;     // host threads and the table of outstanding ahead-of-time dedups

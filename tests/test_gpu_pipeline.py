@@ -30,8 +30,10 @@ def make_its(rng, rows, dim, n_iter, users=40, max_len=300):
 
 def run_pipelined(ctx, table, state, its, lr, eps, ahead=False, sync_each=True):
     """ahead: dedup every batch with fs_unique_ids_ahead, three batches before the iteration that
-    gathers it (five layout buffers in rotation).  sync_each=False: no wait between the calls."""
-    L = 5 if ahead else 3
+    gathers it (five layout buffers in rotation; ahead="last_step": ordered after the start of the
+    previous pipelined call instead of the stream's current position, six layout buffers).
+    sync_each=False: no wait between the calls."""
+    L = (6 if ahead == "last_step" else 5) if ahead else 3
     d_table, d_state = table_to_dev(table), dev(state)
     num_rows, dim = table.shape
     T = len(its)
@@ -52,9 +54,12 @@ def run_pipelined(ctx, table, state, its, lr, eps, ahead=False, sync_each=True):
                                  None if last else d_offs[t + 1], None if last else layouts[(t + 1) % L],
                                  splits[t % 3], reduced[t % 2], None if last else embs[t % 2])
 
+    stepped = [False]
+
     def dedup_ahead(t):
         if ahead and t < T:
-            fs.fs_unique_ids_ahead(ctx, d_vals[t], num_rows, layouts[t % L])
+            order = fs.FS_STREAM_LAST_STEP if (ahead == "last_step" and stepped[0]) else None
+            fs.fs_unique_ids_ahead(ctx, d_vals[t], num_rows, layouts[t % L], stream=order)
 
     fs.fs_unique_ids(ctx, d_vals[0], num_rows, out=layouts[0])
     all_args = [args_for(t) for t in range(T)]
@@ -66,6 +71,7 @@ def run_pipelined(ctx, table, state, its, lr, eps, ahead=False, sync_each=True):
         nxt = all_args[t + 1] if t + 1 < T else None
         dedup_ahead(t + 3)
         fs.fs_prioritized_step_pipelined(ctx, all_args[t], nxt)
+        stepped[0] = True
         if not sync_each:
             continue
         assert fs.fs_check_async(ctx) == fs.FS_OK
@@ -101,7 +107,8 @@ def test_pipelined_steps_match_sequential_calls_bitwise(dtype, dim):
     # dedups batches ahead on the index streams, with and without waits between the calls, with and
     # without the enqueueing threads: always the same bits
     for ahead, sync_each, threaded in ((True, True, True), (True, False, True), (False, False, True),
-                                       (True, False, False), (False, True, False)):
+                                       (True, False, False), (False, True, False), ("last_step", False, True),
+                                       ("last_step", True, False)):
         ctx.lib.fs_ctx_set_threaded_enqueue(ctx.handle, 1 if threaded else 0)
         ta, sa, oa = run_pipelined(ctx, table, state, its, 0.01, 1e-8, ahead=ahead, sync_each=sync_each)
         what = f"ahead={ahead} sync_each={sync_each} threaded={threaded}"
