@@ -67,9 +67,10 @@ def main() -> int:
                     help="what an ahead-of-time dedup is ordered after: the start of the most recent pipelined call "
                          "(no event on the caller's stream, six layout buffers) or the caller's stream as it stands "
                          "(one more event per step on it, five layout buffers)")
-    ap.add_argument("--no-ahead", action="store_true",
-                    help="pipelined mode: dedup the lookahead IDs inside the step call instead of batches ahead on "
-                         "the index streams")
+    ap.add_argument("--ahead", choices=["index", "dedup", "none"], default="index",
+                    help="pipelined mode, what runs ahead of time on the index streams: the whole index half of an "
+                         "iteration two iterations ahead (default), only the dedup of the lookahead IDs, or nothing "
+                         "(the side stream of the step call does it all)")
     ap.add_argument("--keep-reduced", action="store_true",
                     help="also write the summed gradients to memory in the timed steps (the step itself does not "
                          "need them there)")
@@ -117,13 +118,15 @@ def main() -> int:
     # without ahead-of-time dedups), three split/class buffers.  The two batches alternate, so the
     # argument records repeat with period lcm(L, 3, 2).
     pipelined = args.mode in ("pipelined", "graph")
-    ahead = args.mode == "pipelined" and not args.no_ahead
+    ahead = args.mode == "pipelined" and args.ahead != "none"
+    index_ahead = ahead and args.ahead == "index"
     last_step_order = ahead and args.ahead_order == "last_step"
-    L = (6 if last_step_order else 5) if ahead else 3
-    period = (6 if last_step_order else 30) if ahead else 6
+    L = (6 if (last_step_order or index_ahead) else 5) if ahead else 3
+    P = 5 if index_ahead else 3
+    period = 30 if (ahead and (index_ahead or not last_step_order)) else 6
     nmax = max(n)
     layouts = [fs.alloc_layout(nmax, dev) for _ in range(L)]
-    splits = [fs.alloc_split(nmax, nmax, dev) for _ in range(3)]
+    splits = [fs.alloc_split(nmax, nmax, dev) for _ in range(P)]
     reduced = [torch.empty((nmax, dim), dtype=torch.float32, device=dev) for _ in range(2)]
     embs = [torch.empty((n[0], dim), dtype=tdtype, device=dev), torch.empty((n[1], dim), dtype=tdtype, device=dev)]
 
@@ -131,7 +134,7 @@ def main() -> int:
         lay = dict(layouts[s % L]); lay["n"] = n[s % 2]
         nb = (s + 1) % 2
         return fs.make_step_args(table, state, cfg.lr, cfg.eps, lay, d_grads[s % 2], d_vals[nb], d_offs[nb],
-                                 layouts[(s + 1) % L], splits[s % 3], reduced[s % 2] if with_reduced else None,
+                                 layouts[(s + 1) % L], splits[s % P], reduced[s % 2] if with_reduced else None,
                                  embs[nb])
 
     check_args = [args_for(s, True) for s in range(period)]
@@ -141,10 +144,16 @@ def main() -> int:
 
     stepped = [False]
 
+    def order():
+        return fs.FS_STREAM_LAST_STEP if (last_step_order and stepped[0]) else None
+
     def dedup_ahead(s):
-        if ahead:
-            fs.fs_unique_ids_ahead(ctx, d_vals[s % 2], tab.num_rows, layouts[s % L],
-                                   stream=fs.FS_STREAM_LAST_STEP if (last_step_order and stepped[0]) else None)
+        if ahead and not index_ahead:
+            fs.fs_unique_ids_ahead(ctx, d_vals[s % 2], tab.num_rows, layouts[s % L], stream=order())
+
+    def index_half_ahead(s, records):
+        if index_ahead:
+            fs.fs_step_forward_ahead(ctx, records[s % period], stream=order())
 
     def run(k0, k, records=None):
         records = records or step_args
@@ -153,6 +162,7 @@ def main() -> int:
                 fs.fs_graph_launch(ctx, graphs[s % period])
             elif pipelined:
                 dedup_ahead(s + 3)
+                index_half_ahead(s + 2, records)
                 fs.fs_prioritized_step_pipelined(ctx, records[s % period], records[(s + 1) % period])
                 stepped[0] = True
             else:
@@ -167,7 +177,10 @@ def main() -> int:
 
     # ---- one untimed step from the fresh table, checked against the oracle on the touched rows
     cpu_baseline = None
-    if pipelined:
+    if pipelined and index_ahead:
+        index_half_ahead(0, check_args)                # layout 1, split and class order 0
+        index_half_ahead(1, check_args)
+    elif pipelined:
         dedup_ahead(1)
         fs.fs_step_forward(ctx, check_args[0])         # primes the pipeline: layout 1, split and class order 0
         dedup_ahead(2)
@@ -238,8 +251,12 @@ def main() -> int:
         saved, graphs = graphs, None
         fs.fs_ctx_set_kernel_timing(ctx, args.steps)
         run(k1, args.steps)
+        fs.fs_step_join(ctx)
         torch.cuda.synchronize()
         graphs = saved
+        s_executed = k1 + args.steps - 1
+    else:
+        s_executed = k0 + args.steps - 1
 
     kinds = {"gather": fs.FS_TIME_GATHER, "priority_pass": fs.FS_TIME_UPDATE_CO, "deferred_pass": fs.FS_TIME_UPDATE_EX}
     kernel_ms = {}
@@ -259,13 +276,16 @@ def main() -> int:
     step_gbps = step_bytes / (ms_per_step * 1e-3) / 1e9
 
     # Occurrences and rows per class of the two alternating iterations: from the layout of each batch
-    # and the split buffers of the last step and of the index half that followed it.
-    s_last = k0 + args.steps - 1
+    # and the split buffers of two consecutive iterations that are still in place (pipelined: the last
+    # step and the iteration whose index half it ran; self-contained steps: the last two).
+    s_last = s_executed
     cls_pos, cls_rows = {}, {}
-    for s in (s_last, s_last + 1):
-        lay, sp = layouts[s % L], splits[s % 3]
+    for s in ((s_last, s_last + 1) if pipelined else (s_last - 1, s_last)):
+        lay, sp = layouts[s % L], splits[s % P]
         cn = sp["counts"].cpu().numpy().tolist()
-        seg = lay["seg_offsets"][:u[s % 2] + 1].cpu().numpy().astype(np.int64)
+        uu = int(lay["n_unique"].item())
+        assert uu == u[s % 2] and cn[0] + cn[1] == uu, (s, uu, u, cn)
+        seg = lay["seg_offsets"][:uu + 1].cpu().numpy().astype(np.int64)
         lens = seg[1:] - seg[:-1]
         co_pos = int(lens[sp["co_slot"][:cn[0]].cpu().numpy()].sum())
         cls_pos[s % 2] = (co_pos, n[s % 2] - co_pos)
@@ -345,7 +365,7 @@ def main() -> int:
                                f"{cfg.length_rule} UIH lengths [{cfg.length_lo},{cfg.length_hi}], Zipf({tab.zipf_alpha}) IDs, "
                                "2 consecutive iterations stepped back and forth",
                    "ids_per_iteration": n, "unique_rows": u, "collision_rows_first_step": counts0[0]},
-        "schedule": args.mode + ("+dedup_ahead" if ahead else ""), "reduced_gradients_in_memory": bool(args.keep_reduced),
+        "schedule": args.mode + (("+index_half_ahead" if index_ahead else "+dedup_ahead") if ahead else ""), "reduced_gradients_in_memory": bool(args.keep_reduced),
         "class_occurrences": cls_pos, "class_rows": cls_rows, "host_enqueue_us_per_step": t_enq / args.steps * 1e6,
         "host_phase_us_per_step": host_phases,
         "step_algorithmic_bytes": step_bytes, "step_algorithmic_GBps": step_gbps,

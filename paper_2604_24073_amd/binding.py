@@ -82,6 +82,7 @@ def load_library() -> ctypes.CDLL:
         "fs_unique_ids_ahead": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i64, c_vp, c_vp, c_vp, c_vp, c_vp, S]),
         "fs_prioritized_step": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args), S]),
         "fs_step_forward": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args), S]),
+        "fs_step_forward_ahead": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args), S]),
         "fs_prioritized_step_pipelined": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args),
                                                          ctypes.POINTER(fs_step_args), S]),
         "fs_graph_capture_pipelined": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args), ctypes.POINTER(fs_step_args),
@@ -315,6 +316,12 @@ def fs_prioritized_step(ctx: Context, args: fs_step_args, stream=None) -> None:
 def fs_step_forward(ctx: Context, args: fs_step_args, stream=None) -> None:
     rc = ctx.lib.fs_step_forward(ctx.handle, ctypes.byref(args), _stream(stream))
     ctx.check(rc, "fs_step_forward")
+
+
+def fs_step_forward_ahead(ctx: Context, args: fs_step_args, stream=None) -> None:
+    stream_arg = ctypes.c_void_p(-1) if stream == FS_STREAM_LAST_STEP else _stream(stream)
+    rc = ctx.lib.fs_step_forward_ahead(ctx.handle, ctypes.byref(args), stream_arg)
+    ctx.check(rc, "fs_step_forward_ahead")
 
 
 def fs_prioritized_step_pipelined(ctx: Context, cur: fs_step_args, nxt: Optional[fs_step_args], stream=None) -> None:

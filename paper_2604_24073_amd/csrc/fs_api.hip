@@ -34,6 +34,7 @@ struct fs_worker {
     bool busy = false, quit = false;
     int rc = FS_OK;               // first failure since the last wait()
     double busy_us = 0.0;
+    uint64_t posted = 0, completed = 0;
 
     void main_loop(int device) {
         (void)hipSetDevice(device);
@@ -52,13 +53,26 @@ struct fs_worker {
             busy_us += t1 - t0;
             if (r != FS_OK && rc == FS_OK) rc = r;
             busy = false;
+            ++completed;
             cv.notify_all();
         }
     }
     void post(std::function<int()> job) {
         std::lock_guard<std::mutex> lk(mu);
         jobs.push_back(std::move(job));
+        ++posted;
         cv.notify_all();
+    }
+    uint64_t posted_so_far() {
+        std::lock_guard<std::mutex> lk(mu);
+        return posted;
+    }
+    int wait_for(uint64_t count) {    // the first `count` jobs ever posted have been enqueued on their streams
+        std::unique_lock<std::mutex> lk(mu);
+        cv.wait(lk, [this, count] { return completed >= count; });
+        const int r = rc;
+        rc = FS_OK;
+        return r;
     }
     int wait() {                  // everything posted so far has been enqueued on its stream
         std::unique_lock<std::mutex> lk(mu);
@@ -69,18 +83,22 @@ struct fs_worker {
     }
 };
 
-// An ahead-of-time dedup whose results a later step consumes
+// Work done ahead of time on an index stream whose results a later call consumes: a dedup (key: its
+// `unique` output buffer) or the whole index half of an iteration (key: its `counts_dev`).
 enum { kAheadFree = 0, kAheadPosted = 1, kAheadRecorded = 2 };
 struct fs_ahead {
-    const int64_t *unique = nullptr;   // key: the output buffer (calling thread only); null once claimed by a step
+    const void *key = nullptr;         // calling thread only; null once a consumer has claimed the entry
     hipEvent_t fork = nullptr, done = nullptr;
     std::atomic<int> state{kAheadFree};
+    uint64_t stamp = 0;                // calling thread only: allocation order
 };
-constexpr int kAheadSlots = 4;
+constexpr int kAheadSlots = 8;
 
 struct fs_host {
     fs_worker *worker[2] = {nullptr, nullptr};   // 0: side stream A, 1: index streams
     fs_ahead ahead[kAheadSlots];
+    uint64_t ahead_clock = 0;
+    uint64_t x_posted_before_call[2] = {0, 0};   // index-stream jobs posted before the pipelined call of each parity
     int x_turn = 0;
 };
 
@@ -117,9 +135,15 @@ void carve(fs_ctx *c, char *base, size_t *total) {
         ws.tile_hist = cv.take<uint32_t>(sort_tiles * kRadix);
         ws.tile_heads = cv.take<int32_t>(scan_tiles);
     }
-    c->split_flag_t = cv.take<uint8_t>(n + 16);
-    c->split_flag_t1 = cv.take<uint8_t>(n + 16);
-    c->split_cnt = cv.take<int32_t>(2 * scan_tiles);
+    for (int k = 0; k < kSortSets; ++k) {
+        fs_split_scratch &ws = c->split[k];
+        ws.flag_t = cv.take<uint8_t>(n + 16);
+        ws.flag_t1 = cv.take<uint8_t>(n + 16);
+        ws.cnt = cv.take<int32_t>(2 * scan_tiles);
+        ws.cstart_local = cv.take<int32_t>(n + 16);
+        ws.tile_len = cv.take<int32_t>(2 * scan_tiles);
+        ws.cidx = cv.take<int32_t>(n + 16);
+    }
     c->part_head = cv.take<double>(chunks * (size_t)c->max_dim);
     c->part_last = cv.take<double>(chunks * (size_t)c->max_dim);
     c->chunk_desc = cv.take<int32_t>(chunks * 4);
@@ -130,9 +154,6 @@ void carve(fs_ctx *c, char *base, size_t *total) {
         c->fcounters[k] = cv.take<int>(fchunks);
         c->fcounters_sup[k] = cv.take<int>(fchunks);
     }
-    c->cstart_local = cv.take<int32_t>(n + 16);
-    c->tile_len = cv.take<int32_t>(2 * scan_tiles);
-    c->cidx = cv.take<int32_t>(n + 16);
     *total = align_up(cv.off, 256);
 }
 
@@ -140,7 +161,7 @@ hipStream_t as_stream(fs_stream s) { return reinterpret_cast<hipStream_t>(s); }
 
 void worker_stop(fs_ctx *ctx);
 int join_pending_work(fs_ctx *ctx, hipStream_t s);
-void drop_ahead(fs_ctx *ctx, const int64_t *unique);
+void drop_ahead(fs_ctx *ctx, const void *key);
 
 #define FS_REQUIRE(ctx, cond, msg)                          \
     do {                                                    \
@@ -466,15 +487,46 @@ void worker_stop(fs_ctx *ctx) {
     }
 }
 
-// the outstanding ahead-of-time dedup that writes `unique`, if any (calling thread only)
-fs_ahead *find_ahead(fs_ctx *ctx, const int64_t *unique) {
-    if (!unique) return nullptr;
+// the outstanding ahead-of-time work registered under `key`, if any (calling thread only)
+fs_ahead *find_ahead(fs_ctx *ctx, const void *key) {
+    if (!key) return nullptr;
     for (fs_ahead &e : ctx->host->ahead)
-        if (e.unique == unique && e.state.load(std::memory_order_acquire) != kAheadFree) return &e;
+        if (e.key == key && e.state.load(std::memory_order_acquire) != kAheadFree) return &e;
     return nullptr;
 }
 
-// stream `s` waits for the dedup of `e`; the slot is free afterwards (any thread; `e` was claimed)
+// find_ahead + claim: the caller hands the entry to exactly one consumer (consume_ahead)
+fs_ahead *claim_ahead(fs_ctx *ctx, const void *key) {
+    fs_ahead *e = find_ahead(ctx, key);
+    if (e) e->key = nullptr;
+    return e;
+}
+
+// a free entry, registered under `key` (calling thread only).  When all are taken, the oldest finished
+// one that nobody claimed is given up: its results are complete, whoever names its buffers later
+// simply finds no entry and redoes or skips the work as if it had never been done ahead.
+fs_ahead *alloc_ahead(fs_ctx *ctx, const void *key) {
+    fs_host *h = ctx->host;
+    fs_ahead *e = nullptr;
+    for (fs_ahead &c : h->ahead)
+        if (c.state.load(std::memory_order_acquire) == kAheadFree) { e = &c; break; }
+    if (!e) {
+        (void)workers_wait(ctx);
+        for (fs_ahead &c : h->ahead)
+            if (c.key != nullptr && c.state.load(std::memory_order_acquire) == kAheadRecorded &&
+                (e == nullptr || c.stamp < e->stamp))
+                e = &c;
+        if (!e) return nullptr;
+        (void)hipEventSynchronize(e->done);
+        e->state.store(kAheadFree, std::memory_order_release);
+    }
+    e->key = key;
+    e->stamp = ++h->ahead_clock;
+    e->state.store(kAheadPosted, std::memory_order_release);
+    return e;
+}
+
+// stream `s` waits for the work of `e`; the slot is free afterwards (any thread; `e` was claimed)
 int consume_ahead(fs_ctx *ctx, fs_ahead *e, hipStream_t s) {
     while (e->state.load(std::memory_order_acquire) != kAheadRecorded) std::this_thread::yield();
     const hipError_t err = hipStreamWaitEvent(s, e->done, 0);
@@ -486,22 +538,32 @@ int consume_ahead(fs_ctx *ctx, fs_ahead *e, hipStream_t s) {
 // Forward of Algorithm 2 (index work): dedup of the lookahead IDs (unless done ahead of time), the
 // collision split of U_t, the class order of batch t
 int enqueue_index_work(fs_ctx *ctx, const fs_step_args *a, bool have_t, bool have_t1, fs_ahead *ahead,
-                       hipStream_t s) {
+                       hipStream_t s, int set = 0, fs_ahead *dedup_out = nullptr, fs_ahead *layout_in = nullptr) {
     int rc;
     if (have_t1) {
         if (ahead) rc = consume_ahead(ctx, ahead, s);
         else rc = launch_unique(ctx, a->values_t1, a->n_t1, a->num_rows, a->u_t1, a->seg_offsets_t1, a->perm_t1,
-                                a->inverse_t1, a->n_unique_t1_dev, s, 0);
+                                a->inverse_t1, a->n_unique_t1_dev, s, set);
+        if (dedup_out) {
+            // the layout of t+1 stands from here on: the index half of t+1 (other stream) waits for this
+            const hipError_t e = hipEventRecord(dedup_out->done, s);
+            dedup_out->state.store(kAheadRecorded, std::memory_order_release);
+            if (e != hipSuccess && rc == FS_OK) rc = hip_err(ctx, e, "hipEventRecord(dedup)");
+        }
+        if (rc != FS_OK) return rc;
+    }
+    if (layout_in) {
+        rc = consume_ahead(ctx, layout_in, s);                // the layout of t comes from another index stream
         if (rc != FS_OK) return rc;
     }
     rc = launch_split(ctx, a->u_t, have_t ? a->n_unique_t_dev : nullptr, a->u_t1,
                       have_t1 ? a->n_unique_t1_dev : nullptr, have_t ? a->n_t : 0, have_t1 ? a->n_t1 : 0, a->co,
                       a->co_slot, a->ex, a->ex_slot, a->ex_next, a->ex_next_slot, a->counts_dev, s,
-                      have_t ? a->seg_offsets_t : nullptr);
+                      have_t ? a->seg_offsets_t : nullptr, set);
     if (rc != FS_OK) return rc;
     return launch_class_order(ctx, a->perm_t, a->inverse_t, a->seg_offsets_t, have_t ? a->n_t : 0,
                               have_t ? a->n_t : 0, a->cperm, a->cslot, a->cstart, a->class_pos_dev, a->u_t,
-                              a->short_rec, s);
+                              a->short_rec, s, set);
 }
 
 // update_embedding for one class of rows of iteration t (0: priority pass, 1: deferred pass)
@@ -528,13 +590,20 @@ int enqueue_gather(fs_ctx *ctx, const fs_step_args *a, hipStream_t s) {
 // Side stream A for one pipelined call: after the caller's earlier work (the gradients of `cur`),
 // the deferred pass of `cur`, then the index half of `next`, then the event the next call waits for.
 int enqueue_side_stream(fs_ctx *ctx, const fs_step_args *cur, const fs_step_args *next, bool nxt_t, bool nxt_t1,
-                        fs_ahead *ahead, int parity, hipEvent_t *ex_timing) {
+                        fs_ahead *ahead, fs_ahead *index_ahead, int parity, hipEvent_t *ex_timing) {
     hipStream_t sa = ctx->stream_a;
     int rc = FS_OK;
     FS_HIP(ctx, hipStreamWaitEvent(sa, ctx->ev_pfork[parity], 0));
     if (cur) rc = enqueue_class_pass(ctx, cur, 1, sa, ex_timing);
-    if (rc == FS_OK && next) rc = enqueue_index_work(ctx, next, nxt_t, nxt_t1, ahead, sa);
-    else if (ahead) (void)consume_ahead(ctx, ahead, sa);
+    // the index half of `next`: done ahead of time on an index stream (then only waited for), or here
+    if (index_ahead) {
+        const int irc = consume_ahead(ctx, index_ahead, sa);
+        if (rc == FS_OK) rc = irc;
+    } else if (rc == FS_OK && next) {
+        rc = enqueue_index_work(ctx, next, nxt_t, nxt_t1, ahead, sa);
+    } else if (ahead) {
+        (void)consume_ahead(ctx, ahead, sa);
+    }
     if (rc != FS_OK) return rc;
     FS_HIP(ctx, hipEventRecord(ctx->ev_side[parity], sa));
     return FS_OK;
@@ -551,16 +620,17 @@ int join_pending_work(fs_ctx *ctx, hipStream_t s) {
     }
     if (!ctx->capturing)
         for (fs_ahead &e : ctx->host->ahead)
-            if (e.unique != nullptr && e.state.load(std::memory_order_acquire) == kAheadRecorded)
+            if (e.key != nullptr && e.state.load(std::memory_order_acquire) == kAheadRecorded)
                 FS_HIP(ctx, hipStreamWaitEvent(s, e.done, 0));
     return wrc;
 }
 
-// forget an ahead-of-time dedup of `unique` (its buffer is about to be rewritten by someone else)
-void drop_ahead(fs_ctx *ctx, const int64_t *unique) {
-    fs_ahead *e = find_ahead(ctx, unique);
+// forget ahead-of-time work registered under `key` (its buffers are about to be rewritten by someone
+// else); only after join_pending_work, so the entry is finished
+void drop_ahead(fs_ctx *ctx, const void *key) {
+    fs_ahead *e = find_ahead(ctx, key);
     if (e) {
-        e->unique = nullptr;
+        e->key = nullptr;
         e->state.store(kAheadFree, std::memory_order_release);
     }
 }
@@ -625,12 +695,13 @@ int fs_unique_ids_ahead(fs_ctx *ctx, const int64_t *ids, int64_t n, int64_t num_
     FS_REQUIRE(ctx, unique && seg_offsets && n_unique_dev, "unique: null pointer");
     if (n > 0) FS_REQUIRE(ctx, ids && perm, "unique: null pointer");
     FS_REQUIRE(ctx, !ctx->capturing, "unique ahead: not while a graph is being captured");
-    drop_ahead(ctx, unique);
     fs_host *h = ctx->host;
-    fs_ahead *e = nullptr;
-    for (fs_ahead &c : h->ahead)
-        if (c.state.load(std::memory_order_acquire) == kAheadFree) { e = &c; break; }
-    if (!e) return set_err(ctx, FS_EINVAL, "unique ahead: four dedups are already outstanding");
+    if (find_ahead(ctx, unique)) {
+        (void)workers_wait(ctx);
+        drop_ahead(ctx, unique);
+    }
+    fs_ahead *e = alloc_ahead(ctx, unique);
+    if (!e) return set_err(ctx, FS_EINVAL, "unique ahead: too much ahead-of-time work is outstanding");
     const int x = h->x_turn;
     h->x_turn ^= 1;
     hipStream_t sx = ctx->stream_x[x];
@@ -643,8 +714,6 @@ int fs_unique_ids_ahead(fs_ctx *ctx, const int64_t *ids, int64_t n, int64_t num_
     } else {
         FS_HIP(ctx, hipEventRecord(e->fork, as_stream(stream)));
     }
-    e->unique = unique;
-    e->state.store(kAheadPosted, std::memory_order_release);
     auto job = [=]() -> int {
         int rc = FS_OK;
         if (hipStreamWaitEvent(sx, after, 0) != hipSuccess) rc = FS_EHIP;
@@ -662,6 +731,62 @@ int fs_unique_ids_ahead(fs_ctx *ctx, const int64_t *ids, int64_t n, int64_t num_
     return job();
 }
 
+int fs_step_forward_ahead(fs_ctx *ctx, const fs_step_args *a, fs_stream stream) {
+    if (!ctx) return FS_EINVAL;
+    bool have_t, have_t1;
+    int rc = check_step_args(ctx, a, &have_t, &have_t1);
+    if (rc != FS_OK) return rc;
+    FS_REQUIRE(ctx, !ctx->capturing, "index half ahead: not while a graph is being captured");
+    fs_host *h = ctx->host;
+    if (find_ahead(ctx, a->counts_dev)) {
+        (void)workers_wait(ctx);
+        drop_ahead(ctx, a->counts_dev);
+    }
+    // the dedup of the lookahead batch may already be under way (fs_unique_ids_ahead), the layout of
+    // batch t may still be in the making (index half of t-1, on the other index stream)
+    fs_ahead *dedup_in = have_t1 ? claim_ahead(ctx, a->u_t1) : nullptr;
+    fs_ahead *layout_in = have_t ? claim_ahead(ctx, a->u_t) : nullptr;
+    fs_ahead *e_idx = alloc_ahead(ctx, a->counts_dev);
+    fs_ahead *e_ded = (e_idx && have_t1) ? alloc_ahead(ctx, a->u_t1) : nullptr;
+    if (!e_idx || (have_t1 && !e_ded)) {
+        // the claimed entries still have to be waited for by somebody: let the index streams do it
+        if (dedup_in) (void)consume_ahead(ctx, dedup_in, ctx->stream_x[0]);
+        if (layout_in) (void)consume_ahead(ctx, layout_in, ctx->stream_x[0]);
+        if (e_idx) { e_idx->key = nullptr; e_idx->state.store(kAheadFree, std::memory_order_release); }
+        return set_err(ctx, FS_EINVAL, "index half ahead: too much ahead-of-time work is outstanding");
+    }
+    const int x = h->x_turn;
+    h->x_turn ^= 1;
+    hipStream_t sx = ctx->stream_x[x];
+    hipEvent_t after = e_idx->fork;
+    if (stream == FS_STREAM_LAST_STEP) {
+        FS_REQUIRE(ctx, ctx->pfork_valid, "index half ahead: FS_STREAM_LAST_STEP before any pipelined call");
+        after = ctx->ev_pfork[ctx->pipe_parity];
+    } else {
+        FS_HIP(ctx, hipEventRecord(e_idx->fork, as_stream(stream)));
+    }
+    const fs_step_args args = *a;
+    auto job = [=]() -> int {
+        int jrc = FS_OK;
+        if (hipStreamWaitEvent(sx, after, 0) != hipSuccess) jrc = FS_EHIP;
+        const int irc = enqueue_index_work(ctx, &args, have_t, have_t1, dedup_in, sx, 1 + x, e_ded, layout_in);
+        if (jrc == FS_OK) jrc = irc;
+        if (e_ded && e_ded->state.load(std::memory_order_acquire) != kAheadRecorded) {
+            (void)hipEventRecord(e_ded->done, sx);            // only after an early failure: nobody may spin forever
+            e_ded->state.store(kAheadRecorded, std::memory_order_release);
+        }
+        if (hipEventRecord(e_idx->done, sx) != hipSuccess && jrc == FS_OK) jrc = FS_EHIP;
+        e_idx->state.store(kAheadRecorded, std::memory_order_release);
+        return jrc;
+    };
+    fs_worker *w = ctx->use_worker ? get_worker(ctx, 1) : nullptr;
+    if (w) {
+        w->post(job);
+        return FS_OK;
+    }
+    return job();
+}
+
 int fs_step_forward(fs_ctx *ctx, const fs_step_args *a, fs_stream stream) {
     if (!ctx) return FS_EINVAL;
     bool have_t, have_t1;
@@ -670,11 +795,12 @@ int fs_step_forward(fs_ctx *ctx, const fs_step_args *a, fs_stream stream) {
     hipStream_t sp = as_stream(stream), sa = ctx->stream_a;
     rc = join_pending_work(ctx, sp);
     if (rc != FS_OK) return rc;
-    fs_ahead *ahead = have_t1 ? find_ahead(ctx, a->u_t1) : nullptr;
-    if (ahead) ahead->unique = nullptr;
+    // already done ahead of time (and joined above): nothing left to do but to give the entry back
+    fs_ahead *index_ahead = claim_ahead(ctx, a->counts_dev);
+    fs_ahead *ahead = (!index_ahead && have_t1) ? claim_ahead(ctx, a->u_t1) : nullptr;
     FS_HIP(ctx, hipEventRecord(ctx->ev_fork, sp));
     FS_HIP(ctx, hipStreamWaitEvent(sa, ctx->ev_fork, 0));
-    rc = enqueue_index_work(ctx, a, have_t, have_t1, ahead, sa);
+    rc = index_ahead ? consume_ahead(ctx, index_ahead, sa) : enqueue_index_work(ctx, a, have_t, have_t1, ahead, sa);
     if (rc != FS_OK) return rc;
     FS_HIP(ctx, hipEventRecord(ctx->ev_split, sa));
     FS_HIP(ctx, hipStreamWaitEvent(sp, ctx->ev_split, 0));
@@ -690,13 +816,13 @@ int fs_prioritized_step(fs_ctx *ctx, const fs_step_args *a, fs_stream stream) {
     rc = join_pending_work(ctx, sp);
     if (rc != FS_OK) return rc;
     begin_step_timing(ctx);
-    fs_ahead *ahead = have_t1 ? find_ahead(ctx, a->u_t1) : nullptr;
-    if (ahead) ahead->unique = nullptr;
+    fs_ahead *index_ahead = claim_ahead(ctx, a->counts_dev);
+    fs_ahead *ahead = (!index_ahead && have_t1) ? claim_ahead(ctx, a->u_t1) : nullptr;
     // fork: the side streams start after whatever the caller already queued on `stream`
     FS_HIP(ctx, hipEventRecord(ctx->ev_fork, sp));
     FS_HIP(ctx, hipStreamWaitEvent(sa, ctx->ev_fork, 0));
     FS_HIP(ctx, hipStreamWaitEvent(sb, ctx->ev_fork, 0));
-    rc = enqueue_index_work(ctx, a, have_t, have_t1, ahead, sa);
+    rc = index_ahead ? consume_ahead(ctx, index_ahead, sa) : enqueue_index_work(ctx, a, have_t, have_t1, ahead, sa);
     if (rc != FS_OK) return rc;
     FS_HIP(ctx, hipEventRecord(ctx->ev_split, sa));
     FS_HIP(ctx, hipStreamWaitEvent(sp, ctx->ev_split, 0));
@@ -744,21 +870,34 @@ int fs_prioritized_step_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs
         if (rc != FS_OK) return set_err(ctx, rc, "side-stream enqueue of the previous call failed");
     }
     if (ctx->host->worker[1]) {
-        // an ahead-of-time dedup may still have to enqueue its wait for the event recorded next
-        rc = ctx->host->worker[1]->wait();
+        // Ahead-of-time jobs posted before the PREVIOUS pipelined call may refer to the fork event that is
+        // recorded again below (FS_STREAM_LAST_STEP): their waits must be on their streams by now.  Jobs
+        // posted since then refer to the other event of the pair and are left alone.
+        rc = ctx->host->worker[1]->wait_for(ctx->host->x_posted_before_call[pp]);
         if (rc != FS_OK) return set_err(ctx, rc, "index-stream enqueue failed");
+        ctx->host->x_posted_before_call[p] = ctx->host->worker[1]->posted_so_far();
     }
     const double h1 = now_us();
+    if (!ctx->capturing) {
+        // the index half of `cur` done ahead of time and not yet waited for by anybody (first call of a
+        // run): the caller's stream waits for it, and through the fork event so does the side stream
+        fs_ahead *index_cur = claim_ahead(ctx, cur->counts_dev);
+        if (index_cur) {
+            rc = consume_ahead(ctx, index_cur, sp);
+            if (rc != FS_OK) return rc;
+        }
+    }
     FS_HIP(ctx, hipEventRecord(ctx->ev_pfork[p], sp));
     ctx->pfork_valid = true;
-    fs_ahead *ahead = (next && nxt_t1 && !ctx->capturing) ? find_ahead(ctx, next->u_t1) : nullptr;
-    if (ahead) ahead->unique = nullptr;                      // claimed: the side job frees the slot
+    // claimed entries: the side job waits for them and gives them back
+    fs_ahead *index_ahead = (next && !ctx->capturing) ? claim_ahead(ctx, next->counts_dev) : nullptr;
+    fs_ahead *ahead = (next && nxt_t1 && !index_ahead && !ctx->capturing) ? claim_ahead(ctx, next->u_t1) : nullptr;
     hipEvent_t *tex = have_t ? timing_pair(ctx, FS_TIME_UPDATE_EX) : nullptr;
     fs_step_args cur_copy = *cur, next_copy = next ? *next : *cur;
     const bool has_next = next != nullptr;
     auto side_job = [=]() -> int {
         return enqueue_side_stream(ctx, have_t ? &cur_copy : nullptr,
-                                   has_next ? &next_copy : nullptr, nxt_t, nxt_t1, ahead, p, tex);
+                                   has_next ? &next_copy : nullptr, nxt_t, nxt_t1, ahead, index_ahead, p, tex);
     };
     if (w0) w0->post(side_job);
     const double h2 = now_us();

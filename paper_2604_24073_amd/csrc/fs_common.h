@@ -53,6 +53,16 @@ struct fs_sort_scratch {
 };
 constexpr int kSortSets = 3;  // 0: the caller's stream / side stream, 1 and 2: the two ahead-of-time index streams
 
+// scratch between the launches of one split + class order (same stream); one set per stream that may run one
+struct fs_split_scratch {
+    uint8_t *flag_t;          // [max_ids] membership flags of U_t
+    uint8_t *flag_t1;         // [max_ids] membership flags of U_t1
+    int32_t *cnt;             // [2 * scan tiles] collisions per tile
+    int32_t *cstart_local;    // [max_ids] occurrences of same-class rows before this row inside its split tile
+    int32_t *tile_len;        // [2 * scan tiles] occurrences per split tile: collision rows, then exclusive rows
+    int32_t *cidx;            // [max_ids] place of every row of U_t in its class list
+};
+
 struct fs_ctx {
     int device;
     int64_t max_ids;
@@ -65,10 +75,7 @@ struct fs_ctx {
 
     int *d_flags;             // [4] device error flags
     fs_sort_scratch sort[kSortSets];
-    // split
-    uint8_t *split_flag_t;    // [max_ids]
-    uint8_t *split_flag_t1;   // [max_ids]
-    int32_t *split_cnt;       // [3 * scan tiles]
+    fs_split_scratch split[kSortSets];
     // segment reduce
     double *part_head;        // [chunks, max_dim] fp64 partial of the first run of each chunk
     double *part_last;        // [chunks, max_dim] fp64 partial of the last run of each chunk
@@ -79,10 +86,6 @@ struct fs_ctx {
     double *fpart_last[2];    // [chunks, max_dim] first piece of a cut segment that continues into the next chunk
     int *fcounters[2];        // [chunks] arrivals per cut segment (indexed by its first chunk); at 0 between launches
     int *fcounters_sup[2];    // [chunks] arrivals per group of sixteen pieces (indexed by its first chunk)
-    // class order (scratch between the split launches and the scatter launch, same stream)
-    int32_t *cstart_local;    // [max_ids] occurrences of same-class rows before this row inside its split tile
-    int32_t *tile_len;        // [2 * scan tiles] occurrences per split tile: collision rows, then exclusive rows
-    int32_t *cidx;            // [max_ids] place of every row of U_t in its class list
     const int32_t *reduce_inverse;   // host-side: the caller's optional inverse map for the launch being enqueued
     int64_t *d_zero;          // device scalar that stays 0 (stands in for a missing lookahead)
 
@@ -163,11 +166,11 @@ int launch_unique(fs_ctx *, const int64_t *ids, int64_t n, int64_t num_rows, int
 int launch_split(fs_ctx *, const int64_t *u_t, const int64_t *n_t_dev, const int64_t *u_t1,
                  const int64_t *n_t1_dev, int64_t cap_t, int64_t cap_t1, int64_t *co, int32_t *co_slot,
                  int64_t *ex, int32_t *ex_slot, int64_t *ex_next, int32_t *ex_next_slot, int64_t *counts_dev,
-                 hipStream_t s, const int32_t *seg_offsets_t = nullptr);
+                 hipStream_t s, const int32_t *seg_offsets_t = nullptr, int set = 0);
 // right after launch_split(..., seg_offsets_t) on the same stream: occurrences of the batch in class order
 int launch_class_order(fs_ctx *, const int32_t *perm, const int32_t *inverse, const int32_t *seg_offsets, int64_t n,
                        int64_t cap_u, int32_t *cperm, int32_t *cslot, int32_t *cstart, int32_t *class_pos_dev,
-                       const int64_t *u_t, int32_t *short_rec, hipStream_t s);
+                       const int64_t *u_t, int32_t *short_rec, hipStream_t s, int set = 0);
 int launch_reduce_update(fs_ctx *, int cls, const float *grads, int64_t n, int32_t dim, const int32_t *cperm,
                          const int32_t *cslot, const int32_t *class_pos, const int32_t *seg_offsets,
                          const int32_t *cstart, const int64_t *u_t, void *table, int dt, float *state,

@@ -310,7 +310,8 @@ __global__ void split_empty_kernel(const int64_t *n_t1_dev, int64_t cap_t1, int6
 int launch_split(fs_ctx *ctx, const int64_t *u_t, const int64_t *n_t_dev, const int64_t *u_t1,
                  const int64_t *n_t1_dev, int64_t cap_t, int64_t cap_t1, int64_t *co, int32_t *co_slot,
                  int64_t *ex, int32_t *ex_slot, int64_t *ex_next, int32_t *ex_next_slot, int64_t *counts_dev,
-                 hipStream_t s, const int32_t *seg_offsets_t) {
+                 hipStream_t s, const int32_t *seg_offsets_t, int set) {
+    const fs_split_scratch &ws = ctx->split[set];
     const int tiles_t = (int)ceil_div(cap_t, kScanTile);
     const int tiles_t1 = (int)ceil_div(cap_t1, kScanTile);
     if (tiles_t == 0 && tiles_t1 == 0) {
@@ -321,19 +322,20 @@ int launch_split(fs_ctx *ctx, const int64_t *u_t, const int64_t *n_t_dev, const 
     // With cap_t == 0 a single (empty) tile on side t keeps the count logic in one place.
     const int tt = tiles_t > 0 ? tiles_t : 1;
     hipLaunchKernelGGL(split_flag_kernel, dim3(tt + tiles_t1), dim3(kScanThreads), 0, s, u_t, n_t_dev, u_t1, n_t1_dev,
-                       cap_t, cap_t1, tt, ctx->split_flag_t, ctx->split_flag_t1, ctx->split_cnt);
+                       cap_t, cap_t1, tt, ws.flag_t, ws.flag_t1, ws.cnt);
     hipLaunchKernelGGL(split_compact_kernel, dim3(tt + tiles_t1), dim3(kScanThreads), 0, s, u_t, n_t_dev, u_t1,
-                       n_t1_dev, cap_t, cap_t1, tt, tiles_t1, (const uint8_t *)ctx->split_flag_t,
-                       (const uint8_t *)ctx->split_flag_t1, (const int32_t *)ctx->split_cnt, co, co_slot, ex, ex_slot,
-                       ex_next, ex_next_slot, counts_dev, seg_offsets_t, ctx->cstart_local, ctx->tile_len,
-                       ctx->cidx);
+                       n_t1_dev, cap_t, cap_t1, tt, tiles_t1, (const uint8_t *)ws.flag_t,
+                       (const uint8_t *)ws.flag_t1, (const int32_t *)ws.cnt, co, co_slot, ex, ex_slot,
+                       ex_next, ex_next_slot, counts_dev, seg_offsets_t, ws.cstart_local, ws.tile_len,
+                       ws.cidx);
     FS_LAUNCH_CHECK(ctx, "split kernels");
     return FS_OK;
 }
 
 int launch_class_order(fs_ctx *ctx, const int32_t *perm, const int32_t *inverse, const int32_t *seg_offsets,
                        int64_t n, int64_t cap_u, int32_t *cperm, int32_t *cslot, int32_t *cstart,
-                       int32_t *class_pos_dev, const int64_t *u_t, int32_t *short_rec, hipStream_t s) {
+                       int32_t *class_pos_dev, const int64_t *u_t, int32_t *short_rec, hipStream_t s, int set) {
+    const fs_split_scratch &ws = ctx->split[set];
     if (n == 0) {
         hipLaunchKernelGGL(class_empty_kernel, dim3(1), dim3(1), 0, s, class_pos_dev);
         FS_LAUNCH_CHECK(ctx, "class_empty_kernel");
@@ -344,9 +346,9 @@ int launch_class_order(fs_ctx *ctx, const int32_t *perm, const int32_t *inverse,
         return set_err(ctx, FS_ERANGE, "class order: more than 7.8M distinct rows in one batch");
     hipLaunchKernelGGL(class_scatter_kernel, dim3((unsigned)ceil_div(n, kScanTile)), dim3(kScanThreads),
                        (size_t)tiles_t * 2 * sizeof(int), s, perm, inverse, seg_offsets, (int)n, tiles_t,
-                       (const uint8_t *)ctx->split_flag_t, (const int32_t *)ctx->cstart_local,
-                       (const int32_t *)ctx->tile_len, cperm, cslot, cstart, class_pos_dev, ctx->d_flags, u_t,
-                       (const int32_t *)ctx->cidx, short_rec, (int)cap_u);
+                       (const uint8_t *)ws.flag_t, (const int32_t *)ws.cstart_local,
+                       (const int32_t *)ws.tile_len, cperm, cslot, cstart, class_pos_dev, ctx->d_flags, u_t,
+                       (const int32_t *)ws.cidx, short_rec, (int)cap_u);
     FS_LAUNCH_CHECK(ctx, "class_scatter_kernel");
     return FS_OK;
 }

@@ -29,11 +29,15 @@ def make_its(rng, rows, dim, n_iter, users=40, max_len=300):
 
 
 def run_pipelined(ctx, table, state, its, lr, eps, ahead=False, sync_each=True):
-    """ahead: dedup every batch with fs_unique_ids_ahead, three batches before the iteration that
-    gathers it (five layout buffers in rotation; ahead="last_step": ordered after the start of the
-    previous pipelined call instead of the stream's current position, six layout buffers).
-    sync_each=False: no wait between the calls."""
-    L = (6 if ahead == "last_step" else 5) if ahead else 3
+    """ahead: True / "last_step": dedup every batch with fs_unique_ids_ahead, three batches before the
+    iteration that gathers it (five layout buffers in rotation; "last_step": ordered after the start
+    of the previous pipelined call instead of the stream's current position, six layout buffers).
+    "index" / "index_last_step": the whole index half of every iteration with fs_step_forward_ahead,
+    two iterations ahead (six layouts, five split bundles).  sync_each=False: no wait between the calls."""
+    index_ahead = ahead in ("index", "index_last_step")
+    last_step = ahead in ("last_step", "index_last_step")
+    L = (6 if (last_step or index_ahead) else 5) if ahead else 3
+    P = 5 if index_ahead else 3
     d_table, d_state = table_to_dev(table), dev(state)
     num_rows, dim = table.shape
     T = len(its)
@@ -43,7 +47,7 @@ def run_pipelined(ctx, table, state, its, lr, eps, ahead=False, sync_each=True):
     n = [v.numel() for v in d_vals]
     nmax = max(n)
     layouts = [fs.alloc_layout(nmax, "cuda") for _ in range(L)]
-    splits = [fs.alloc_split(nmax, nmax, "cuda") for _ in range(3)]     # rotation of three
+    splits = [fs.alloc_split(nmax, nmax, "cuda") for _ in range(P)]
     reduced = [torch.empty((nmax, dim), dtype=torch.float32, device="cuda") for _ in range(2)]
     embs = [torch.empty((nmax, dim), dtype=d_table.dtype, device="cuda") for _ in range(2)]
 
@@ -52,31 +56,42 @@ def run_pipelined(ctx, table, state, its, lr, eps, ahead=False, sync_each=True):
         last = t == T - 1
         return fs.make_step_args(d_table, d_state, lr, eps, lay_t, d_grads[t], None if last else d_vals[t + 1],
                                  None if last else d_offs[t + 1], None if last else layouts[(t + 1) % L],
-                                 splits[t % 3], reduced[t % 2], None if last else embs[t % 2])
+                                 splits[t % P], reduced[t % 2], None if last else embs[t % 2])
 
     stepped = [False]
 
+    def order():
+        return fs.FS_STREAM_LAST_STEP if (last_step and stepped[0]) else None
+
     def dedup_ahead(t):
-        if ahead and t < T:
-            order = fs.FS_STREAM_LAST_STEP if (ahead == "last_step" and stepped[0]) else None
-            fs.fs_unique_ids_ahead(ctx, d_vals[t], num_rows, layouts[t % L], stream=order)
+        if ahead and not index_ahead and t < T:
+            fs.fs_unique_ids_ahead(ctx, d_vals[t], num_rows, layouts[t % L], stream=order())
+
+    def index_half_ahead(t):
+        if index_ahead and t < T:
+            fs.fs_step_forward_ahead(ctx, all_args[t], stream=order())
 
     fs.fs_unique_ids(ctx, d_vals[0], num_rows, out=layouts[0])
     all_args = [args_for(t) for t in range(T)]
     dedup_ahead(1)
-    fs.fs_step_forward(ctx, all_args[0])                          # primes the pipeline: layout 1, split 0
+    if index_ahead:
+        index_half_ahead(0)                                       # dedup of batch 1, split and class order of 0
+        index_half_ahead(1)
+    else:
+        fs.fs_step_forward(ctx, all_args[0])                      # primes the pipeline: layout 1, split 0
     dedup_ahead(2)
     outs = []
     for t in range(T):
         nxt = all_args[t + 1] if t + 1 < T else None
         dedup_ahead(t + 3)
+        index_half_ahead(t + 2)
         fs.fs_prioritized_step_pipelined(ctx, all_args[t], nxt)
         stepped[0] = True
         if not sync_each:
             continue
         assert fs.fs_check_async(ctx) == fs.FS_OK
         u = int(layouts[t % L]["n_unique"].item())
-        rec = {"reduced": reduced[t % 2][:u].cpu().numpy(), "counts": splits[t % 3]["counts"].cpu().numpy()}
+        rec = {"reduced": reduced[t % 2][:u].cpu().numpy(), "counts": splits[t % P]["counts"].cpu().numpy()}
         if t + 1 < T:
             rec["emb_next"] = table_to_host(embs[t % 2][:n[t + 1]])
         outs.append(rec)
@@ -108,7 +123,9 @@ def test_pipelined_steps_match_sequential_calls_bitwise(dtype, dim):
     # without the enqueueing threads: always the same bits
     for ahead, sync_each, threaded in ((True, True, True), (True, False, True), (False, False, True),
                                        (True, False, False), (False, True, False), ("last_step", False, True),
-                                       ("last_step", True, False)):
+                                       ("last_step", True, False), ("index", False, True), ("index", True, True),
+                                       ("index_last_step", False, True), ("index_last_step", False, False),
+                                       ("index", True, False)):
         ctx.lib.fs_ctx_set_threaded_enqueue(ctx.handle, 1 if threaded else 0)
         ta, sa, oa = run_pipelined(ctx, table, state, its, 0.01, 1e-8, ahead=ahead, sync_each=sync_each)
         what = f"ahead={ahead} sync_each={sync_each} threaded={threaded}"
