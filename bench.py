@@ -7,8 +7,10 @@ collision rows), deferred pass (the same on the exclusive rows) on its own strea
 gather of the lookahead batch.  The workload is
 BASELINE configs[1] (one 4M x 128 fp32 table shard, batch 1024, power-law UIH lengths, Zipf(1.05)
 IDs); its two consecutive iterations are stepped back and forth (t=0 with lookahead 1, then t=1
-with lookahead 0, ...) so that every step consumes the layout the previous step produced, as in
-steady-state training.  Inputs are resident in HBM before the timed region.
+with lookahead 0, ...) so that every step consumes the layout and class order an earlier step's index half produced,
+as in steady-state training (default schedule: the index half of iteration s+2 is enqueued on the
+library's index streams before the pipelined call of iteration s).  Inputs are resident in HBM
+before the timed region.
 
 Prints ONE JSON line: rows/s, ms/step, the roofline of the dominant kernel (HIP events around it
 inside the timed steps) and the CPU oracle timed on this machine's host cores.

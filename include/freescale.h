@@ -278,7 +278,9 @@ int fs_step_forward_ahead(fs_ctx *ctx, const fs_step_args *args, fs_stream strea
  * fs_check_async and every call that reuses the index workspace.  Use consecutive pipelined
  * calls on ONE stream.  The buffers of consecutive calls must be distinct: three split/class
  * buffers in rotation, and three layout buffers (five with fs_unique_ids_ahead two batches
- * ahead). */
+ * ahead; see fs_step_forward_ahead for its rotation).  If the index half of `next` (or, on the
+ * first call of a run, of `cur`) was done ahead of time with fs_step_forward_ahead, the call only
+ * waits for it. */
 int fs_prioritized_step_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs_step_args *next,
                                   fs_stream stream);
 
