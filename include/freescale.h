@@ -239,7 +239,8 @@ int fs_step_forward(fs_ctx *ctx, const fs_step_args *args, fs_stream stream);
  * it hides behind the bandwidth-bound passes of earlier iterations.  The results are consumed by
  * a step call whose u_t1 is this `unique` buffer (it waits for them instead of doing the dedup
  * itself); anyone else must call fs_step_join or fs_check_async first.  The outputs must not be
- * in use by work that is not ordered before `stream`'s current position; in a loop of pipelined
+ * in use by work that is not ordered before `stream`'s current position, and `ids` must stay in
+ * place until the dedup has run (it is only enqueued when the call returns); in a loop of pipelined
  * calls that means five layout buffers in rotation when the dedup runs two batches ahead of the
  * call that consumes it as u_t1.  At most four such dedups may be outstanding.
  * stream == FS_STREAM_LAST_STEP: no event is recorded on any stream of the caller; the dedup is

@@ -1,6 +1,6 @@
-// C-ABI entry points: argument validation, context/workspace management and the two-stream
-// schedule of one prioritized iteration (Section 3.2 / Algorithm 2 of the paper, collectives
-// removed).  No kernel lives here.
+// C-ABI entry points: argument validation, context/workspace management and the schedules of one
+// prioritized iteration (Section 3.2 / Algorithm 2 of the paper, collectives removed): which stream
+// runs what, which event orders whom, which host thread enqueues it.  No kernel lives here.
 #include <atomic>
 #include <chrono>
 #include <condition_variable>

@@ -556,3 +556,52 @@ def test_multi_iteration_schedule_matches_sequential_calls_bitwise(ctx, dtype, d
             assert a["emb_next"].tobytes() == b["emb_next"].tobytes()
     t_ref, s_ref, want = run_steps_oracle(table, state, its, 0.01, 1e-8)
     compare_runs(oa, want, table_to_host(ta), sa.cpu().numpy(), t_ref, s_ref)
+
+
+# ------------------------------------------------------------------------------------ host-visible errors of the step entry points
+def test_step_entry_points_reject_bad_arguments(ctx):
+    rng = np.random.default_rng(3)
+    rows, dim = 1000, 64
+    ids = zipf_ids(rng, 500, rows)
+    table, state = table_to_dev(rand_table(rng, rows, dim, "f32")), torch.zeros(rows, device="cuda")
+    grads = dev(rng.standard_normal((500, dim)).astype(np.float32))
+    lay, sp = gpu_layout_and_classes(ctx, ids, ids, rows)
+    with pytest.raises(fs.FreeScaleError) as e:
+        fs.fs_reduce_update_class(ctx, 2, table, state, 0.01, 1e-8, grads, lay, sp)           # no such class
+    assert e.value.code == fs.FS_EINVAL
+    args = fs.make_step_args(table, state, 0.01, 1e-8, lay, grads, None, None, None, sp, None, None)
+    args.cperm = None                                                                        # class order missing
+    with pytest.raises(fs.FreeScaleError) as e:
+        fs.fs_prioritized_step(ctx, args)
+    assert e.value.code == fs.FS_EINVAL
+    fresh = fs.Context(max_ids=1000, max_dim=64)
+    out = fs.alloc_layout(500, "cuda")
+    with pytest.raises(fs.FreeScaleError) as e:                                              # no pipelined call yet
+        fs.fs_unique_ids_ahead(fresh, dev(ids), rows, out, stream=fs.FS_STREAM_LAST_STEP)
+    assert e.value.code == fs.FS_EINVAL
+    with pytest.raises(fs.FreeScaleError) as e:                                              # beyond the capacity
+        big = dev(zipf_ids(rng, 2000, rows))
+        fs.fs_unique_ids_ahead(fresh, big, rows, fs.alloc_layout(2000, "cuda"))
+    assert e.value.code == fs.FS_ENOMEM
+    assert fs.fs_check_async(fresh) == fs.FS_OK
+    fresh.close()
+    assert fs.fs_check_async(ctx) == fs.FS_OK
+
+
+def test_many_ahead_dedups_outstanding(ctx):
+    """More ahead-of-time dedups than the context tracks at once: the oldest finished ones are given up,
+    every result is still correct."""
+    rng = np.random.default_rng(4)
+    rows = 5000
+    batches = [zipf_ids(rng, 3000 + 100 * k, rows) for k in range(12)]
+    outs = [fs.alloc_layout(len(b), "cuda") for b in batches]
+    d_batches = [dev(b) for b in batches]                      # the IDs must stay in place until the dedups ran
+    for d, o in zip(d_batches, outs):
+        fs.fs_unique_ids_ahead(ctx, d, rows, o)
+    assert fs.fs_check_async(ctx) == fs.FS_OK
+    for b, o in zip(batches, outs):
+        want = O.unique_ids(b, rows)
+        u = int(o["n_unique"].item())
+        assert np.array_equal(o["unique"][:u].cpu().numpy(), want["unique"])
+        assert np.array_equal(o["perm"][:len(b)].cpu().numpy(), want["perm"])
+        assert np.array_equal(o["inverse"][:len(b)].cpu().numpy(), want["inverse"])
