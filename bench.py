@@ -51,6 +51,153 @@ def algorithmic_bytes(n_t, u_t, n_t1, u_t1, dim, w):
             "total": unique + split + gather + reduce_update}
 
 
+def bench_tables(args, cfg) -> int:
+    """Several tables per shard (BASELINE configs[2]): one independent problem per table (table-local
+    IDs), each with its own context, buffers and stream, all stepped in every step with the default
+    schedule (index half two iterations ahead, pipelined calls)."""
+    import numpy as np
+    import torch
+    import paper_2604_24073_amd as fs
+    from fs_workloads import make_iterations, hash_init_rows, compact_rows
+
+    dev = torch.device("cuda:0")
+    its_all = make_iterations(cfg, iterations=2)
+    L, P, period = 6, 5, 30
+
+    class T:
+        pass
+
+    tabs = []
+    for ti, tab in enumerate(cfg.tables):
+        t = T()
+        t.tab, t.its = tab, [its_all[0][ti], its_all[1][ti]]
+        t.dim, t.w = tab.dim, (4 if tab.dtype == "f32" else 2)
+        tdtype = torch.float32 if tab.dtype == "f32" else torch.bfloat16
+        t.n = [int(it.values.shape[0]) for it in t.its]
+        t.ctx = fs.Context(max_ids=max(t.n), max_dim=t.dim)
+        t.table = torch.empty((tab.num_rows, t.dim), dtype=tdtype, device=dev)
+        fs.fs_init_table_hash(t.ctx, t.table)
+        t.state = torch.zeros(tab.num_rows, dtype=torch.float32, device=dev)
+        t.vals = [torch.from_numpy(it.values).to(dev) for it in t.its]
+        t.offs = [torch.from_numpy(it.offsets).to(dev) for it in t.its]
+        t.grads = [torch.from_numpy(it.grads).to(dev) for it in t.its]
+        nmax = max(t.n)
+        t.layouts = [fs.alloc_layout(nmax, dev) for _ in range(L)]
+        t.splits = [fs.alloc_split(nmax, nmax, dev) for _ in range(P)]
+        t.embs = [torch.empty((t.n[0], t.dim), dtype=tdtype, device=dev),
+                  torch.empty((t.n[1], t.dim), dtype=tdtype, device=dev)]
+        t.stream = torch.cuda.Stream()
+
+        def args_for(s, t=t):
+            lay = dict(t.layouts[s % L]); lay["n"] = t.n[s % 2]
+            nb = (s + 1) % 2
+            return fs.make_step_args(t.table, t.state, cfg.lr, cfg.eps, lay, t.grads[s % 2], t.vals[nb], t.offs[nb],
+                                     t.layouts[(s + 1) % L], t.splits[s % P], None, t.embs[nb])
+
+        t.args = [args_for(s) for s in range(period)]
+        t.stepped = False
+        tabs.append(t)
+    torch.cuda.synchronize()
+
+    def ahead(t, s):
+        fs.fs_step_forward_ahead(t.ctx, t.args[s % period], stream=fs.FS_STREAM_LAST_STEP if t.stepped else t.stream)
+
+    def run(k0, k):
+        for s in range(k0, k0 + k):
+            for t in tabs:
+                ahead(t, s + 2)
+                fs.fs_prioritized_step_pipelined(t.ctx, t.args[s % period], t.args[(s + 1) % period], stream=t.stream)
+                t.stepped = True
+
+    for t in tabs:
+        fs.fs_unique_ids(t.ctx, t.vals[0], t.tab.num_rows, out=t.layouts[0], stream=t.stream)
+        ahead(t, 0)
+        ahead(t, 1)
+    run(0, 1)
+    cpu_s, u_all = 0.0, []
+    for ti, t in enumerate(tabs):
+        assert fs.fs_check_async(t.ctx, t.stream) == fs.FS_OK, t.ctx.last_error()
+        t.u = [int(t.layouts[0]["n_unique"].item()), int(t.layouts[1]["n_unique"].item())]
+        u_all.append(t.u)
+        if not args.no_cpu_baseline:
+            import oracle as O
+            touched, (v0c, v1c) = compact_rows([t.its[0].values, t.its[1].values])
+            w0 = hash_init_rows(touched, t.dim, t.tab.dtype)
+            times = []
+            for _ in range(3):
+                t_ref, s_ref = w0.copy(), np.zeros(len(touched), np.float32)
+                lay0 = O.unique_ids(v0c, len(touched))
+                t0 = time.perf_counter()
+                O.step(t_ref, s_ref, lay0, t.its[0].grads, v1c, t.its[1].offsets, cfg.lr, cfg.eps)
+                times.append(time.perf_counter() - t0)
+            got_rows = t.table[torch.from_numpy(touched).to(dev)].float().cpu().numpy()
+            if not (t.u[0] == len(lay0["unique"]) and np.allclose(got_rows, t_ref, rtol=1e-5, atol=1e-6)):
+                print(f"bench.py: GPU step of table {ti} does not match the oracle", file=sys.stderr)
+                return 4
+            cpu_s += statistics.median(times)
+    run(1, args.warmup)
+    for t in tabs:
+        fs.fs_step_join(t.ctx, t.stream)
+    torch.cuda.synchronize()
+    k0 = 1 + args.warmup
+    fs.fs_ctx_set_kernel_timing(tabs[0].ctx, args.steps, args.time_every)
+    t0 = time.perf_counter()
+    run(k0, args.steps)
+    for t in tabs:
+        fs.fs_step_join(t.ctx, t.stream)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    for t in tabs:
+        assert fs.fs_check_async(t.ctx, t.stream) == fs.FS_OK, t.ctx.last_error()
+    kinds = {"gather": fs.FS_TIME_GATHER, "priority_pass": fs.FS_TIME_UPDATE_CO, "deferred_pass": fs.FS_TIME_UPDATE_EX}
+    kernel_ms = {}
+    for name, kind in kinds.items():
+        vals = fs.fs_ctx_get_kernel_timing(tabs[0].ctx, kind, args.steps)
+        kernel_ms[name] = (sum(vals) / len(vals)) if vals else None
+    rows = sum(t.u[s % 2] for t in tabs for s in range(k0, k0 + args.steps))
+    step_bytes = 0.0
+    for t in tabs:
+        by = [algorithmic_bytes(t.n[0], t.u[0], t.n[1], t.u[1], t.dim, t.w),
+              algorithmic_bytes(t.n[1], t.u[1], t.n[0], t.u[0], t.dim, t.w)]
+        step_bytes += sum(by[s % 2]["total"] for s in range(k0, k0 + args.steps)) / args.steps
+    ms_per_step = elapsed / args.steps * 1e3
+    step_gbps = step_bytes / (ms_per_step * 1e-3) / 1e9
+    t = tabs[0]
+    by0 = algorithmic_bytes(t.n[0], t.u[0], t.n[1], t.u[1], t.dim, t.w)["gather"]
+    by1 = algorithmic_bytes(t.n[1], t.u[1], t.n[0], t.u[0], t.dim, t.w)["gather"]
+    roofline = None
+    if kernel_ms.get("gather"):
+        gb = (by0 + by1) / 2 / (kernel_ms["gather"] * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "gather_kernel (table 0)", "achieved": gb, "peak": HBM_PEAK_GBPS,
+                    "unit": "GB/s", "frac": gb / HBM_PEAK_GBPS, "traffic": None,
+                    "avg_launch_us": kernel_ms["gather"] * 1e3, "algorithmic_bytes_per_launch": (by0 + by1) / 2}
+    out = {
+        "metric": "unique embedding rows updated/sec + achieved HBM GB/s (% of peak), 1 GPU",
+        "value": rows / elapsed, "unit": "rows/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"configs[{cfg.index}] {cfg.name}: {len(tabs)} tables per shard, rows "
+                               f"{[t.tab.num_rows for t in tabs]}, dims {[t.dim for t in tabs]}, batch {cfg.batch}, "
+                               f"{cfg.length_rule} UIH lengths [{cfg.length_lo},{cfg.length_hi}], a step = one "
+                               "iteration of every table; 2 consecutive iterations stepped back and forth",
+                   "ids_per_iteration": [t.n for t in tabs], "unique_rows": u_all},
+        "schedule": "pipelined+index_half_ahead, one context and stream per table",
+        "step_algorithmic_bytes": step_bytes, "step_algorithmic_GBps": step_gbps,
+        "step_frac_of_hbm_peak": step_gbps / HBM_PEAK_GBPS,
+        "kernel_avg_us": {k: (v * 1e3 if v is not None else None) for k, v in kernel_ms.items()},
+        "roofline": roofline,
+        "cpu_baseline": None if args.no_cpu_baseline else {
+            "value": sum(t.u[0] for t in tabs) / cpu_s, "unit": "rows/s", "cores": 1, "kind": "oracle",
+            "ms_per_step": cpu_s * 1e3,
+            "sample": "the full step t=0 of every table, median of 3 runs each of the single-threaded C oracle on "
+                      "tables holding only the touched rows", "host_cpus": os.cpu_count()},
+    }
+    print(json.dumps(out))
+    for t in tabs:
+        t.ctx.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -98,8 +245,7 @@ def main() -> int:
     dev = torch.device("cuda:0")
     cfg = CONFIGS[args.config]
     if len(cfg.tables) != 1:
-        print("bench.py: single-table configurations only", file=sys.stderr)
-        return 2
+        return bench_tables(args, cfg)
     tab = cfg.tables[0]
     its = [x[0] for x in make_iterations(cfg, iterations=2)]
     dim, w = tab.dim, (4 if tab.dtype == "f32" else 2)
