@@ -228,6 +228,16 @@ __device__ __forceinline__ void long_segments_body(
     f32x4 v[UNR];
     load_batch(v, 0);
     const int64_t rid = (lane < span) ? u_t[sl] : 0;          // table row of every position (used where a segment ends)
+    // extents of the first and the last segment of the chunk (lanes 0-2 / 3-5: class position of its
+    // first occurrence, its sorted positions): only needed if the chunk border cuts them
+    int meta = 0;
+    {
+        const int s_edge = __shfl(sl, lane < 3 ? 0 : span - 1, kWave);
+        if (lane < 6) {
+            const int f = lane % 3;
+            meta = f == 0 ? cstart[s_edge] : seg_offsets[s_edge + (f - 1)];
+        }
+    }
 
     const int sl_prev = __shfl(edge, 0, kWave), sl_after = __shfl(edge, 1, kWave);
     int nxt = __shfl_down(sl, 1, kWave);
@@ -332,53 +342,49 @@ __device__ __forceinline__ void long_segments_body(
     // f+1+16j): the last piece of a super to arrive adds the super up (chunk order) and leaves the
     // sum in the super's first slot; the last of {first piece, supers} to arrive adds those up
     // (same order) and updates the row.
+    // The extents of the two candidate segments were requested at the start of the chunk (meta, below
+    // the first batch of loads); both first arrivals are counted with ONE atomic instruction (lane 0:
+    // the piece of a super, lane 1: the first piece of the segment that leaves to the right), so the
+    // common case costs one store acknowledgement and one atomic round trip per chunk.
     const bool head_cut = !head_complete;
     const bool tail_cut = has_rest && (nflush > 0 || head_complete);
     const int s_last = __shfl(sl, span - 1, kWave);
-#pragma unroll 1
-    for (int which = 0; which < 2; ++which) {
-        if (!(which == 0 ? head_cut : tail_cut)) continue;    // wave-uniform
-        const int s = which == 0 ? s_first : s_last;
-        const int start = cstart[s];
-        const int len = seg_offsets[s + 1] - seg_offsets[s];
-        const int c_first = (start - lo) / CHUNK;
-        const int c_last = (start + len - 1 - lo) / CHUNK;
-        if (start < lo || c_first > chunk || c_last < chunk || c_last >= n_chunks || c_last == c_first ||
-            (which == 0) != (chunk > c_first)) {
-            bad = true;
-            continue;
-        }
-        int old = 0;
-        if (which == 0) {
-            // a piece of a super
-            const int sup_first = c_first + 1 + ((chunk - c_first - 1) / kFusedSuper) * kFusedSuper;
-            const int sup_last = (sup_first + kFusedSuper - 1 < c_last) ? sup_first + kFusedSuper - 1 : c_last;
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // my piece is acknowledged before I count myself in
-            if (lane == 0)
-                old = __hip_atomic_fetch_add(&cnt_sup[sup_first], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            old = __builtin_amdgcn_readfirstlane(old);
-            if (old != sup_last - sup_first) continue;        // wave-uniform
-            if (lane == 0) __hip_atomic_store(&cnt_sup[sup_first], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            double t[4] = {0.0, 0.0, 0.0, 0.0};
-            add_partial_rows(t, part_head, dim, lig, col_ok, sup_first + grp, sup_last, GPW);
+    int seg_s[2] = {s_first, s_last}, c_first[2], c_last[2];
+    bool valid[2] = {head_cut, tail_cut};
 #pragma unroll
-            for (int i = 0; i < 4; ++i) t[i] = across_groups<LPR>(t[i]);
-            if (grp == 0 && col_ok) store_piece(part_head + (int64_t)sup_first * dim + lig * 4, t);
+    for (int which = 0; which < 2; ++which) {
+        const int start = __shfl(meta, which * 3 + 0, kWave);
+        const int len = __shfl(meta, which * 3 + 2, kWave) - __shfl(meta, which * 3 + 1, kWave);
+        c_first[which] = (start - lo) / CHUNK;
+        c_last[which] = (start + len - 1 - lo) / CHUNK;
+        if (valid[which] && (start < lo || c_first[which] > chunk || c_last[which] < chunk || c_last[which] >= n_chunks ||
+                             c_last[which] == c_first[which] || (which == 0) != (chunk > c_first[which]))) {
+            bad = true;
+            valid[which] = false;
         }
-        const int n_sup = (c_last - c_first + kFusedSuper - 1) / kFusedSuper;
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        old = 0;
-        if (lane == 0) old = __hip_atomic_fetch_add(&cnt_seg[c_first], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        old = __builtin_amdgcn_readfirstlane(old);
-        if (old != n_sup) continue;                           // wave-uniform: 1 + n_sup arrivals in all
-        if (lane == 0) __hip_atomic_store(&cnt_seg[c_first], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    const int sup_first = c_first[0] + 1 + ((chunk - c_first[0] - 1) / kFusedSuper) * kFusedSuper;
+    const int sup_last = (sup_first + kFusedSuper - 1 < c_last[0]) ? sup_first + kFusedSuper - 1 : c_last[0];
+    int old = 0;
+    if (valid[0] || valid[1]) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // my pieces are acknowledged before I count myself in
+        if (lane == 0 && valid[0])
+            old = __hip_atomic_fetch_add(&cnt_sup[sup_first], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (lane == 1 && valid[1])
+            old = __hip_atomic_fetch_add(&cnt_seg[c_first[1]], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    const int old_head = __shfl(old, 0, kWave), old_tail = __shfl(old, 1, kWave);
+
+    // last arrival at a segment: first piece + the sums of the supers, in chunk order; update the row
+    auto finish_segment = [&](int s, int cf, int cl) {
+        if (lane == 0) __hip_atomic_store(&cnt_seg[cf], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         double t[4] = {0.0, 0.0, 0.0, 0.0};
         if (grp == 0 && col_ok) {
-            const double *x = part_last + (int64_t)c_first * dim + lig * 4;
+            const double *x = part_last + (int64_t)cf * dim + lig * 4;
 #pragma unroll
             for (int i = 0; i < 4; ++i) t[i] = load_piece(x + i);
         }
-        add_partial_rows(t, part_head, dim, lig, col_ok, c_first + 1 + grp * kFusedSuper, c_last, GPW * kFusedSuper);
+        add_partial_rows(t, part_head, dim, lig, col_ok, cf + 1 + grp * kFusedSuper, cl, GPW * kFusedSuper);
 #pragma unroll
         for (int i = 0; i < 4; ++i) t[i] = across_groups<LPR>(t[i]);
         if (grp == 0 && col_ok) stage[wib][lig] = f32x4{(float)t[0], (float)t[1], (float)t[2], (float)t[3]};
@@ -390,6 +396,25 @@ __device__ __forceinline__ void long_segments_body(
         update_parked<BF16, LPR, 1>(stage[wib], stage_row[wib], stage_slot[wib], 1, table, state, num_rows, gvec, lr,
                                     eps, reduced, oob);
         wave_lds_sync();
+    };
+
+    if (valid[0] && old_head == sup_last - sup_first) {       // wave-uniform: last piece of its super
+        if (lane == 0) __hip_atomic_store(&cnt_sup[sup_first], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        double t[4] = {0.0, 0.0, 0.0, 0.0};
+        add_partial_rows(t, part_head, dim, lig, col_ok, sup_first + grp, sup_last, GPW);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) t[i] = across_groups<LPR>(t[i]);
+        if (grp == 0 && col_ok) store_piece(part_head + (int64_t)sup_first * dim + lig * 4, t);
+        const int n_sup = (c_last[0] - c_first[0] + kFusedSuper - 1) / kFusedSuper;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        int o2 = 0;
+        if (lane == 0) o2 = __hip_atomic_fetch_add(&cnt_seg[c_first[0]], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        o2 = __builtin_amdgcn_readfirstlane(o2);
+        if (o2 == n_sup) finish_segment(seg_s[0], c_first[0], c_last[0]);   // 1 + n_sup arrivals in all
+    }
+    if (valid[1]) {
+        const int n_sup = (c_last[1] - c_first[1] + kFusedSuper - 1) / kFusedSuper;
+        if (old_tail == n_sup) finish_segment(seg_s[1], c_first[1], c_last[1]);
     }
     if (oob) atomicOr(flags, kFlagRowRange);
     if (bad) atomicOr(flags, kFlagInternal);
