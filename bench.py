@@ -443,27 +443,43 @@ def main() -> int:
         # gradient rows + two index words per occurrence; row read+write, state read+write, row id per row
         return cls_pos[b][c] * (dim * 4 + 8) + cls_rows[b][c] * (2 * dim * w + 8 + 8)
 
-    # dominant kernel = the instrumented kernel with the longest average launch
+    # Dominant kernel = the kernel that takes the most GPU time per step: class_pass_kernel, launched
+    # twice per step (priority pass on the caller's stream, deferred pass on the side stream, usually
+    # side by side), against the gather.  For class_pass_kernel the figures are per launch, averaged
+    # over both launches; the two passes are also listed on their own.
     avg = lambda f: sum(f(s % 2) for s in range(k0, k0 + args.steps)) / args.steps
-    cand = []
+    per_kernel = {}
     if kernel_ms.get("gather"):
-        cand.append(("gather_kernel", kernel_ms["gather"], avg(lambda b: by[b]["gather"])))
+        per_kernel["gather_kernel"] = (kernel_ms["gather"], avg(lambda b: by[b]["gather"]), 1)
     if kernel_ms.get("priority_pass"):
-        cand.append(("class_pass_kernel (priority pass)", kernel_ms["priority_pass"],
-                     avg(lambda b: class_pass_bytes(b, 0))))
+        per_kernel["class_pass_kernel (priority pass)"] = (kernel_ms["priority_pass"],
+                                                           avg(lambda b: class_pass_bytes(b, 0)), 1)
     if kernel_ms.get("deferred_pass"):
-        cand.append(("class_pass_kernel (deferred pass)", kernel_ms["deferred_pass"],
-                     avg(lambda b: class_pass_bytes(b, 1))))
+        per_kernel["class_pass_kernel (deferred pass)"] = (kernel_ms["deferred_pass"],
+                                                           avg(lambda b: class_pass_bytes(b, 1)), 1)
+    cand = dict(per_kernel)
+    both = [v for k, v in per_kernel.items() if k.startswith("class_pass_kernel")]
+    if len(both) == 2:
+        cand = {k: v for k, v in per_kernel.items() if not k.startswith("class_pass_kernel")}
+        cand["class_pass_kernel"] = ((both[0][0] + both[1][0]) / 2, (both[0][1] + both[1][1]) / 2, 2)
     roofline = None
     if cand:
-        name, ms, nbytes = max(cand, key=lambda c: c[1])
+        name = max(cand, key=lambda k: cand[k][0] * cand[k][2])
+        ms, nbytes, launches = cand[name]
         achieved = nbytes / (ms * 1e-3) / 1e9
-        traffic = MEASURED_TRAFFIC_BYTES.get((f"configs[{cfg.index}]", name)) if pipelined and ahead else None
-        roofline = {"bound": "hbm", "kernel": name, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "avg_launch_us": ms * 1e3,
-                    "algorithmic_bytes_per_launch": nbytes,
+        traffic = None
+        if pipelined and ahead:
+            key = f"configs[{cfg.index}]"
+            if name == "class_pass_kernel":
+                t2 = [MEASURED_TRAFFIC_BYTES.get((key, name + sfx)) for sfx in (" (priority pass)", " (deferred pass)")]
+                traffic = (t2[0] + t2[1]) / 2 if all(t2) else None
+            else:
+                traffic = MEASURED_TRAFFIC_BYTES.get((key, name))
+        roofline = {"bound": "hbm", "kernel": name, "launches_per_step": launches, "achieved": achieved,
+                    "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+                    "avg_launch_us": ms * 1e3, "algorithmic_bytes_per_launch": nbytes,
                     "all_kernels": {nm: {"avg_launch_us": m * 1e3, "algorithmic_bytes": nb,
-                                         "GBps": nb / (m * 1e-3) / 1e9} for nm, m, nb in cand}}
+                                         "GBps": nb / (m * 1e-3) / 1e9} for nm, (m, nb, _) in per_kernel.items()}}
 
     # ---- the same kernels alone on the chip: each operation launched 20 times back to back on one
     # stream with nothing beside it (after the timed region; the table keeps being updated, which
