@@ -210,8 +210,9 @@ int fs_ctx_create(fs_ctx **out, int device, int64_t max_ids, int32_t max_dim) {
     }
     c->host = new (std::nothrow) fs_host();
     ok = ok && c->host != nullptr;
-    hipStream_t *streams[] = {&c->stream_a, &c->stream_b, &c->stream_cap, &c->stream_x[0], &c->stream_x[1]};
+    hipStream_t *streams[] = {&c->stream_a, &c->stream_b, &c->stream_cap};
     for (hipStream_t *st : streams) ok = ok && hipStreamCreateWithFlags(st, hipStreamNonBlocking) == hipSuccess;
+    for (hipStream_t &st : c->stream_x) ok = ok && hipStreamCreateWithFlags(&st, hipStreamNonBlocking) == hipSuccess;
     hipEvent_t *evs[] = {&c->ev_fork, &c->ev_split, &c->ev_ex, &c->ev_pfork[0], &c->ev_pfork[1], &c->ev_side[0],
                          &c->ev_side[1]};
     for (hipEvent_t *e : evs) ok = ok && hipEventCreateWithFlags(e, hipEventDisableTiming) == hipSuccess;
@@ -232,8 +233,10 @@ int fs_ctx_destroy(fs_ctx *c) {
     if (!c) return FS_OK;
     (void)hipSetDevice(c->device);
     worker_stop(c);
-    hipStream_t streams[] = {c->stream_a, c->stream_b, c->stream_x[0], c->stream_x[1], c->stream_cap};
+    hipStream_t streams[] = {c->stream_a, c->stream_b, c->stream_cap};
     for (hipStream_t st : streams)
+        if (st) { (void)hipStreamSynchronize(st); (void)hipStreamDestroy(st); }
+    for (hipStream_t st : c->stream_x)
         if (st) { (void)hipStreamSynchronize(st); (void)hipStreamDestroy(st); }
     hipEvent_t evs[] = {c->ev_fork, c->ev_split, c->ev_ex, c->ev_pfork[0], c->ev_pfork[1], c->ev_side[0], c->ev_side[1]};
     for (hipEvent_t e : evs)
@@ -263,8 +266,7 @@ int fs_check_async(fs_ctx *ctx, fs_stream stream) {
     FS_HIP(ctx, hipStreamSynchronize(as_stream(stream)));
     FS_HIP(ctx, hipStreamSynchronize(ctx->stream_a));
     FS_HIP(ctx, hipStreamSynchronize(ctx->stream_b));
-    FS_HIP(ctx, hipStreamSynchronize(ctx->stream_x[0]));
-    FS_HIP(ctx, hipStreamSynchronize(ctx->stream_x[1]));
+    for (hipStream_t sx : ctx->stream_x) FS_HIP(ctx, hipStreamSynchronize(sx));
     int flags[4] = {0, 0, 0, 0};
     FS_HIP(ctx, hipMemcpy(flags, ctx->d_flags, sizeof(flags), hipMemcpyDeviceToHost));
     if (flags[0] == 0) return FS_OK;
@@ -703,7 +705,7 @@ int fs_unique_ids_ahead(fs_ctx *ctx, const int64_t *ids, int64_t n, int64_t num_
     fs_ahead *e = alloc_ahead(ctx, unique);
     if (!e) return set_err(ctx, FS_EINVAL, "unique ahead: too much ahead-of-time work is outstanding");
     const int x = h->x_turn;
-    h->x_turn ^= 1;
+    h->x_turn = (x + 1) % kIndexStreams;
     hipStream_t sx = ctx->stream_x[x];
     // what the dedup is ordered after: the caller's stream as it stands, or - no new event on the
     // caller's stream - its position at the start of the most recent pipelined call
@@ -756,7 +758,7 @@ int fs_step_forward_ahead(fs_ctx *ctx, const fs_step_args *a, fs_stream stream) 
         return set_err(ctx, FS_EINVAL, "index half ahead: too much ahead-of-time work is outstanding");
     }
     const int x = h->x_turn;
-    h->x_turn ^= 1;
+    h->x_turn = (x + 1) % kIndexStreams;
     hipStream_t sx = ctx->stream_x[x];
     hipEvent_t after = e_idx->fork;
     if (stream == FS_STREAM_LAST_STEP) {
@@ -930,6 +932,25 @@ int fs_step_join(fs_ctx *ctx, fs_stream stream) {
     return join_pending_work(ctx, as_stream(stream));
 }
 
+#ifdef FS_TRACE
+// Diagnostic builds only: `buf_dev` = zeroed device array of 64-bit words with [1] = records per lane
+// (layout beside the tracer in fs_device.h); nullptr switches the trace off.
+void fs_set_trace_unique(unsigned long long *);
+void fs_set_trace_split(unsigned long long *);
+void fs_set_trace_gather(unsigned long long *);
+void fs_set_trace_fused(unsigned long long *);
+int fs_debug_trace(fs_ctx *ctx, void *buf_dev) {
+    if (!ctx) return FS_EINVAL;
+    FS_HIP(ctx, hipDeviceSynchronize());
+    fs_set_trace_unique((unsigned long long *)buf_dev);
+    fs_set_trace_split((unsigned long long *)buf_dev);
+    fs_set_trace_gather((unsigned long long *)buf_dev);
+    fs_set_trace_fused((unsigned long long *)buf_dev);
+    FS_HIP(ctx, hipDeviceSynchronize());
+    return FS_OK;
+}
+#endif
+
 int fs_ctx_host_times(fs_ctx *ctx, double *out7_host, int reset) {
     if (!ctx || !out7_host) return FS_EINVAL;
     (void)workers_wait(ctx);
@@ -964,8 +985,7 @@ int fs_graph_capture_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs_st
     (void)workers_wait(ctx);
     ctx->side_pending = false;
     (void)hipStreamSynchronize(ctx->stream_a);
-    (void)hipStreamSynchronize(ctx->stream_x[0]);
-    (void)hipStreamSynchronize(ctx->stream_x[1]);
+    for (hipStream_t sx : ctx->stream_x) (void)hipStreamSynchronize(sx);
     hipError_t e = hipStreamBeginCapture(ctx->stream_cap, hipStreamCaptureModeThreadLocal);
     if (e != hipSuccess) {
         delete g;

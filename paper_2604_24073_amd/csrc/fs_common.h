@@ -16,10 +16,14 @@ constexpr int kWave = 64;
 // radix sort geometry
 constexpr int kRadixBits = 9;                             // most bits one pass may sort
 constexpr int kRadix = 1 << kRadixBits;                   // most bins of one pass
-constexpr int kSortThreads = 1024;
-constexpr int kSortKpt = 4;                               // keys per thread
-constexpr int kSortTile = kSortThreads * kSortKpt;        // keys per tile
+#ifndef FS_SORT_THREADS
+#define FS_SORT_THREADS 1024
+#endif
+constexpr int kSortThreads = FS_SORT_THREADS;
+constexpr int kSortTile = 4096;                           // keys per tile
+constexpr int kSortKpt = kSortTile / kSortThreads;        // keys per thread
 constexpr int kSortWaves = kSortThreads / kWave;
+constexpr int kSortScan = kSortThreads > kRadix ? kSortThreads : kRadix;
 
 // unique / split compaction geometry
 constexpr int kScanThreads = 256;
@@ -51,7 +55,11 @@ struct fs_sort_scratch {
     uint32_t *tile_hist;      // [tiles * bins] per-tile digit counts
     int32_t *tile_heads;      // [scan tiles] heads per compaction tile
 };
-constexpr int kSortSets = 3;  // 0: the caller's stream / side stream, 1 and 2: the two ahead-of-time index streams
+#ifndef FS_INDEX_STREAMS
+#define FS_INDEX_STREAMS 2
+#endif
+constexpr int kIndexStreams = FS_INDEX_STREAMS;   // streams that run ahead-of-time index work, used in turn
+constexpr int kSortSets = 1 + kIndexStreams;      // 0: the caller's stream / side stream, then one per index stream
 
 // scratch between the launches of one split + class order (same stream); one set per stream that may run one
 struct fs_split_scratch {
@@ -91,7 +99,7 @@ struct fs_ctx {
 
     hipStream_t stream_a;     // side stream: index half of the lookahead batch; deferred pass of a pipelined call
     hipStream_t stream_b;     // deferred pass of the self-contained step
-    hipStream_t stream_x[2];  // ahead-of-time dedups, used in turn
+    hipStream_t stream_x[kIndexStreams];   // ahead-of-time dedups and index halves, used in turn
     hipEvent_t ev_fork, ev_split, ev_ex;   // self-contained step and fs_step_forward
     hipEvent_t ev_pfork[2];   // position of the caller's stream at the start of a pipelined call (alternating)
     hipEvent_t ev_side[2];    // side-stream work of a pipelined call (deferred pass of cur, index half of next) done

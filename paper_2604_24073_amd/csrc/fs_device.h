@@ -52,4 +52,44 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
     return u >> 16;
 }
 
+
+// ---- optional workgroup trace (diagnostic builds with -DFS_TRACE only) ------------------------------
+// Every workgroup of a traced kernel appends {kind, gridDim.x << 32 | blockIdx.x, first and last reading
+// of the 100 MHz wall clock by its thread 0} to a buffer the host sets with fs_debug_trace.  The buffer
+// is cut into 1024 lanes with a counter each (128 bytes apart) so that the appends do not queue up on one
+// address.  Layout in 64-bit words: [1] = records per lane; counter of lane l at [16 + 16 l]; record i of
+// lane l at [16 + 16*1024 + 4 (l * per_lane + i)].  One variable per translation unit;
+// fs_set_trace_<unit> stores the buffer into it.
+#ifdef FS_TRACE
+static __device__ unsigned long long *g_trace_buf;
+struct wg_trace {
+    unsigned long long t0;
+    int kind;
+    __device__ __forceinline__ wg_trace(int k) : t0(wall_clock64()), kind(k) {}
+    __device__ __forceinline__ ~wg_trace() {
+        unsigned long long *buf = g_trace_buf;
+        if (threadIdx.x == 0 && buf != nullptr) {
+            const unsigned long long per_lane = buf[1];
+            const unsigned long long l = (blockIdx.x + 131u * (unsigned)kind) & 1023u;
+            const unsigned long long i = atomicAdd(&buf[16 + 16 * l], 1ull);
+            if (i < per_lane) {
+                unsigned long long *r = buf + 16 + 16 * 1024 + 4 * (l * per_lane + i);
+                r[0] = (unsigned long long)kind;
+                r[1] = ((unsigned long long)gridDim.x << 32) | blockIdx.x;
+                r[2] = t0;
+                r[3] = wall_clock64();
+            }
+        }
+    }
+};
+#define FS_WG_TRACE(kind) fs::wg_trace wg_trace_((kind))
+#define FS_TRACE_SETTER(unit)                                                                   \
+    extern "C" void fs_set_trace_##unit(unsigned long long *buf) {                                            \
+        (void)hipMemcpyToSymbol(HIP_SYMBOL(g_trace_buf), &buf, sizeof(buf), 0, hipMemcpyHostToDevice); \
+    }
+#else
+#define FS_WG_TRACE(kind)
+#define FS_TRACE_SETTER(unit)
+#endif
+
 }  // namespace fs

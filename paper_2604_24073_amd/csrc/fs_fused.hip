@@ -571,6 +571,7 @@ __global__ __launch_bounds__(kFusedWaves *kWave) void class_pass_kernel(
     const int32_t *__restrict__ recs, const int64_t *__restrict__ n_rows_dev, void *table, float *state,
     int64_t num_rows, int gvec, float lr, float eps, f32x4 *reduced, double *part_head, double *part_last,
     int *cnt_seg, int *cnt_sup, int *flags) {
+    FS_WG_TRACE(8 + cls);
     if ((int)blockIdx.x < long_blocks)
         long_segments_body<BF16, LPR, UNR, CHUNK>((int)blockIdx.x, grads, cperm, cslot, class_pos, cls, n, seg_offsets,
                                                   cstart, u_t, table, state, num_rows, gvec, lr, eps, reduced,
@@ -631,5 +632,7 @@ int launch_reduce_update(fs_ctx *ctx, int cls, const float *grads, int64_t n, in
     FS_LAUNCH_CHECK(ctx, "class_pass_kernel");
     return FS_OK;
 }
+
+FS_TRACE_SETTER(fused)
 
 }  // namespace fs

@@ -6,6 +6,7 @@
 // 64 fp32 or 128 bf16, 1 row of 256 fp32).  Work is flat over the N occurrences, never one
 // workgroup per user, so a 16K-item sequence costs the same per item as a short one.
 #include "fs_common.h"
+#include "fs_device.h"
 
 #ifndef FS_GATHER_UNR
 #define FS_GATHER_UNR 4
@@ -21,6 +22,7 @@ __global__ __launch_bounds__(256) void gather_kernel(const u32x4 *__restrict__ t
                                                      int granules, const int64_t *__restrict__ values,
                                                      const int64_t *__restrict__ offsets, int64_t batch, int64_t n,
                                                      u32x4 *__restrict__ out, int *__restrict__ flags) {
+    FS_WG_TRACE(10);
     constexpr int GPW = kWave / LPR;                  // rows per wavefront instruction
     constexpr int ROWS_PER_WAVE = GPW * UNR;
     const int lane = threadIdx.x & (kWave - 1);
@@ -175,5 +177,7 @@ int launch_copy(fs_ctx *ctx, const void *src, void *dst, int64_t n_bytes, hipStr
     FS_LAUNCH_CHECK(ctx, "copy_kernel");
     return FS_OK;
 }
+
+FS_TRACE_SETTER(gather)
 
 }  // namespace fs

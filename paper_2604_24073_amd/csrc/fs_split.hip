@@ -8,6 +8,7 @@
 // second launch compacts with tile prefixes.  The list lengths are device scalars; the launch is
 // sized by the host-side caps and tiles past the end do nothing.
 #include "fs_common.h"
+#include "fs_device.h"
 
 namespace fs {
 
@@ -84,6 +85,7 @@ __global__ __launch_bounds__(kScanThreads) void split_flag_kernel(const int64_t 
                                                                   uint8_t *__restrict__ flag_t,
                                                                   uint8_t *__restrict__ flag_t1,
                                                                   int32_t *__restrict__ tile_cnt) {
+    FS_WG_TRACE(5);
     __shared__ int sh[kScanThreads / kWave];
     __shared__ int win[2];
     __shared__ int64_t window[kSplitWindow];
@@ -137,6 +139,7 @@ __global__ __launch_bounds__(kScanThreads) void split_compact_kernel(
     int64_t *__restrict__ ex_next, int32_t *__restrict__ ex_next_slot, int64_t *__restrict__ counts_dev,
     const int32_t *__restrict__ seg_offsets_t, int32_t *__restrict__ cstart_local, int32_t *__restrict__ tile_len,
     int32_t *__restrict__ cidx) {
+    FS_WG_TRACE(6);
     __shared__ int sh[kScanThreads / kWave];
     const int n_t = clamp_count(n_t_dev, cap_t), n_t1 = clamp_count(n_t1_dev, cap_t1);
     const bool side_t = (int)blockIdx.x < tiles_t;
@@ -224,6 +227,7 @@ __global__ __launch_bounds__(kScanThreads) void class_scatter_kernel(
     const int32_t *__restrict__ tile_len, int32_t *__restrict__ cperm, int32_t *__restrict__ cslot,
     int32_t *__restrict__ cstart, int32_t *__restrict__ class_pos_dev, int *__restrict__ flags,
     const int64_t *__restrict__ u_t, const int32_t *__restrict__ cidx, int32_t *__restrict__ short_rec, int cap) {
+    FS_WG_TRACE(7);
     extern __shared__ int tile_base[];                      // [2 * tiles_t]
     __shared__ int sh[kScanThreads / kWave];
     int class_total[2];
@@ -352,5 +356,7 @@ int launch_class_order(fs_ctx *ctx, const int32_t *perm, const int32_t *inverse,
     FS_LAUNCH_CHECK(ctx, "class_scatter_kernel");
     return FS_OK;
 }
+
+FS_TRACE_SETTER(split)
 
 }  // namespace fs

@@ -10,6 +10,7 @@
 // two launches (histogram, scan+rank+scatter) and no workgroup ever waits for another.  Ranking
 // uses wavefront ballots, so equal digits keep their order.
 #include "fs_common.h"
+#include "fs_device.h"
 
 namespace fs {
 
@@ -52,8 +53,9 @@ __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(const int64_t 
                                                                   uint32_t *__restrict__ tile_hist,
                                                                   int *__restrict__ flags) {
     __shared__ uint32_t hist[kRadix];
+    FS_WG_TRACE(1);
     const int bins = 1 << bits;
-    if ((int)threadIdx.x < bins) hist[threadIdx.x] = 0;
+    for (int d = threadIdx.x; d < bins; d += kSortThreads) hist[d] = 0;
     __syncthreads();
     const int base = blockIdx.x * kSortTile;
     bool bad = false;
@@ -73,7 +75,7 @@ __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(const int64_t 
         }
     }
     __syncthreads();
-    if ((int)threadIdx.x < bins) tile_hist[blockIdx.x * bins + threadIdx.x] = hist[threadIdx.x];
+    for (int d = threadIdx.x; d < bins; d += kSortThreads) tile_hist[blockIdx.x * bins + d] = hist[d];
     if (bad) atomicOr(flags, kFlagRowRange);
 }
 
@@ -88,9 +90,10 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(const int64
                                                                      int bits, int tiles,
                                                                      const uint32_t *__restrict__ tile_hist) {
     __shared__ uint32_t cnt[kSortWaves][kRadix];       // per-wave digit counters, then wave bases
-    __shared__ uint32_t sh_below[kSortThreads];
-    __shared__ uint32_t sh_total[kSortThreads];
+    __shared__ uint32_t sh_below[kSortScan];
+    __shared__ uint32_t sh_total[kSortScan];
     __shared__ uint32_t gbase[kRadix];
+    FS_WG_TRACE(2);
     const int bins = 1 << bits;
     const int lane = threadIdx.x & (kWave - 1);
     const int w = threadIdx.x / kWave;
@@ -107,34 +110,38 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(const int64
     }
     for (int i = threadIdx.x; i < kSortWaves * kRadix; i += kSortThreads) (&cnt[0][0])[i] = 0;
 
-    // (1) every workgroup scans the table by itself: thread (q, d) adds the tiles t = q, q+groups, ...
+    // (1) every workgroup scans the table by itself: virtual thread (q, d) adds the tiles t = q, q+groups, ...
+    // (a thread stands for several virtual threads when there are more digits than threads)
     {
-        const int groups = kSortThreads / bins;            // >= 2
-        const int d = threadIdx.x & (bins - 1);
-        const int q = threadIdx.x / bins;
-        uint32_t below = 0, total = 0;
-        for (int t = q; t < tiles; t += groups * 8) {       // eight independent loads in flight
-            uint32_t v[8];
+        const int groups = kSortThreads >= bins ? kSortThreads / bins : 1;
+        for (int vt = threadIdx.x; vt < groups * bins; vt += kSortThreads) {
+            const int d = vt & (bins - 1);
+            const int q = vt / bins;
+            uint32_t below = 0, total = 0;
+            for (int t = q; t < tiles; t += groups * 8) {       // eight independent loads in flight
+                uint32_t v[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int tt = t + j * groups;
-                v[j] = (tt < tiles) ? tile_hist[tt * bins + d] : 0u;
-            }
+                for (int j = 0; j < 8; ++j) {
+                    const int tt = t + j * groups;
+                    v[j] = (tt < tiles) ? tile_hist[tt * bins + d] : 0u;
+                }
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                total += v[j];
-                below += (t + j * groups < tile) ? v[j] : 0u;
+                for (int j = 0; j < 8; ++j) {
+                    total += v[j];
+                    below += (t + j * groups < tile) ? v[j] : 0u;
+                }
             }
+            sh_below[vt] = below;
+            sh_total[vt] = total;
         }
-        sh_below[threadIdx.x] = below;
-        sh_total[threadIdx.x] = total;
         __syncthreads();
-        if (q == 0) {
+        for (int d = threadIdx.x; d < bins; d += kSortThreads) {
+            uint32_t below = sh_below[d], total = sh_total[d];
             for (int g = 1; g < groups; ++g) {
                 below += sh_below[g * bins + d];
                 total += sh_total[g * bins + d];
             }
-            sh_below[d] = below;
+            sh_below[d] = below;       // only this thread reads or writes entry d of group 0 in this loop
             sh_total[d] = total;
         }
         __syncthreads();
@@ -182,12 +189,12 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(const int64
     }
     __syncthreads();
     // (3) exclusive prefix over the waves of this tile, per digit
-    if ((int)threadIdx.x < bins) {
-        uint32_t run = gbase[threadIdx.x];
+    for (int d = threadIdx.x; d < bins; d += kSortThreads) {
+        uint32_t run = gbase[d];
 #pragma unroll
         for (int i = 0; i < kSortWaves; ++i) {
-            const uint32_t v = cnt[i][threadIdx.x];
-            cnt[i][threadIdx.x] = run;
+            const uint32_t v = cnt[i][d];
+            cnt[i][d] = run;
             run += v;
         }
     }
@@ -224,6 +231,7 @@ __device__ __forceinline__ int load_heads(const K *__restrict__ keys, int n, int
 template <typename K>
 __global__ __launch_bounds__(kScanThreads) void unique_count_kernel(const K *__restrict__ keys, int n,
                                                                     int32_t *__restrict__ tile_heads) {
+    FS_WG_TRACE(3);
     __shared__ int sh[kScanThreads / kWave];
     K k[kScanIpt];
     bool head[kScanIpt];
@@ -242,6 +250,7 @@ __global__ __launch_bounds__(kScanThreads) void unique_compact_kernel(const K *_
                                                                       int32_t *__restrict__ seg_offsets,
                                                                       int32_t *__restrict__ inverse,
                                                                       int64_t *__restrict__ n_unique_dev) {
+    FS_WG_TRACE(4);
     __shared__ int sh[kScanThreads / kWave];
     const int p0 = blockIdx.x * kScanTile + threadIdx.x * kScanIpt;
     int pm[kScanIpt];
@@ -342,5 +351,7 @@ int launch_unique(fs_ctx *ctx, const int64_t *ids, int64_t n, int64_t num_rows, 
     return unique_impl<uint64_t>(ctx, ids, (int)n, key_bits, num_rows, unique, seg_offsets, perm, inverse,
                                  n_unique_dev, s, ctx->sort[set]);
 }
+
+FS_TRACE_SETTER(unique)
 
 }  // namespace fs
