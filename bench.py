@@ -18,6 +18,7 @@ inside the timed steps) and the CPU oracle timed on this machine's host cores.
 from __future__ import annotations
 
 import argparse
+import math
 import json
 import os
 import statistics
@@ -220,6 +221,10 @@ def main() -> int:
                     help="pipelined mode, what runs ahead of time on the index streams: the whole index half of an "
                          "iteration two iterations ahead (default), only the dedup of the lookahead IDs, or nothing "
                          "(the side stream of the step call does it all)")
+    ap.add_argument("--ahead-batch", type=int, default=2, metavar="K",
+                    help="with --ahead index: index halves of K consecutive iterations share their launches "
+                         "(fs_step_forward_ahead_batch), issued K+1 iterations before the first of them is stepped; "
+                         "1 = one chain of launches per iteration")
     ap.add_argument("--keep-reduced", action="store_true",
                     help="also write the summed gradients to memory in the timed steps (the step itself does not "
                          "need them there)")
@@ -269,9 +274,11 @@ def main() -> int:
     ahead = args.mode == "pipelined" and args.ahead != "none"
     index_ahead = ahead and args.ahead == "index"
     last_step_order = ahead and args.ahead_order == "last_step"
-    L = (6 if (last_step_order or index_ahead) else 5) if ahead else 3
-    P = 5 if index_ahead else 3
-    period = 30 if (ahead and (index_ahead or not last_step_order)) else 6
+    K = max(1, min(args.ahead_batch, fs.FS_MAX_AHEAD_BATCH)) if index_ahead else 1
+    D = K + 1                                  # iterations between issuing a batch and stepping its first record
+    L = (K + D + 3 if index_ahead else (6 if last_step_order else 5)) if ahead else 3
+    P = K + D + 2 if index_ahead else 3
+    period = math.lcm(L, P, 2)
     nmax = max(n)
     layouts = [fs.alloc_layout(nmax, dev) for _ in range(L)]
     splits = [fs.alloc_split(nmax, nmax, dev) for _ in range(P)]
@@ -299,9 +306,10 @@ def main() -> int:
         if ahead and not index_ahead:
             fs.fs_unique_ids_ahead(ctx, d_vals[s % 2], tab.num_rows, layouts[s % L], stream=order())
 
-    def index_half_ahead(s, records):
-        if index_ahead:
-            fs.fs_step_forward_ahead(ctx, records[s % period], stream=order())
+    def index_half_ahead(first, records):
+        # the index halves of iterations first .. first+K-1, when `first` starts a batch
+        if index_ahead and first >= 0 and first % K == 0:
+            fs.fs_step_forward_ahead_batch(ctx, [records[(first + k) % period] for k in range(K)], stream=order())
 
     def run(k0, k, records=None):
         records = records or step_args
@@ -310,7 +318,7 @@ def main() -> int:
                 fs.fs_graph_launch(ctx, graphs[s % period])
             elif pipelined:
                 dedup_ahead(s + 3)
-                index_half_ahead(s + 2, records)
+                index_half_ahead(s + D, records)
                 fs.fs_prioritized_step_pipelined(ctx, records[s % period], records[(s + 1) % period])
                 stepped[0] = True
             else:
@@ -326,8 +334,8 @@ def main() -> int:
     # ---- one untimed step from the fresh table, checked against the oracle on the touched rows
     cpu_baseline = None
     if pipelined and index_ahead:
-        index_half_ahead(0, check_args)                # layout 1, split and class order 0
-        index_half_ahead(1, check_args)
+        for first in range(0, D):                      # the batches a loop that had run forever would have issued
+            index_half_ahead(first, check_args)
     elif pipelined:
         dedup_ahead(1)
         fs.fs_step_forward(ctx, check_args[0])         # primes the pipeline: layout 1, split and class order 0
@@ -529,7 +537,7 @@ def main() -> int:
                                f"{cfg.length_rule} UIH lengths [{cfg.length_lo},{cfg.length_hi}], Zipf({tab.zipf_alpha}) IDs, "
                                "2 consecutive iterations stepped back and forth",
                    "ids_per_iteration": n, "unique_rows": u, "collision_rows_first_step": counts0[0]},
-        "schedule": args.mode + (("+index_half_ahead" if index_ahead else "+dedup_ahead") if ahead else ""), "reduced_gradients_in_memory": bool(args.keep_reduced),
+        "schedule": args.mode + ((f"+index_half_ahead(batches of {K})" if index_ahead else "+dedup_ahead") if ahead else ""), "reduced_gradients_in_memory": bool(args.keep_reduced),
         "class_occurrences": cls_pos, "class_rows": cls_rows, "host_enqueue_us_per_step": t_enq / args.steps * 1e6,
         "host_phase_us_per_step": host_phases,
         "step_algorithmic_bytes": step_bytes, "step_algorithmic_GBps": step_gbps,

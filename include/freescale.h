@@ -264,6 +264,21 @@ int fs_unique_ids_ahead(fs_ctx *ctx, const int64_t *ids, int64_t n, int64_t num_
  * layouts and five split/class bundles with FS_STREAM_LAST_STEP, five and four with `stream`. */
 int fs_step_forward_ahead(fs_ctx *ctx, const fs_step_args *args, fs_stream stream);
 
+/* The index halves of `count` (1..FS_MAX_AHEAD_BATCH) argument records ahead of time in SHARED
+ * launches: every kernel of the chain (three radix passes, compaction, split, class order) runs once
+ * for all of them.  A launch disturbs whatever runs beside it on the chip by about as much however
+ * small it is, so what the index work costs the bandwidth-bound passes falls with the number of
+ * iterations - or tables - that share a chain.  The records may be consecutive iterations of one table
+ * (args[k+1].u_t == args[k].u_t1: the layout that record k+1 splits is the one the dedup of record k
+ * produces in this very call) or belong to different tables; each is found and waited for by the
+ * pipelined call that names its counts_dev, like the result of fs_step_forward_ahead, which is this
+ * call with count == 1.  Ordering, `stream` and the lifetime of the inputs are as for
+ * fs_step_forward_ahead.  Buffers in rotation when a batch of K consecutive iterations is issued D
+ * iterations before the pipelined call of its first one, with FS_STREAM_LAST_STEP: K + D + 3 layouts
+ * and K + D + 2 split/class bundles. */
+#define FS_MAX_AHEAD_BATCH 4
+int fs_step_forward_ahead_batch(fs_ctx *ctx, const fs_step_args *args, int count, fs_stream stream);
+
 /* Steady-state form of the iteration, software-pipelined by one batch exactly as Algorithm 2
  * interleaves its Forward and Backward.  For iteration `cur`:
  *   `stream`      : wait for the side work of the previous call; priority pass of cur

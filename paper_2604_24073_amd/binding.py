@@ -21,6 +21,7 @@ FS_F32, FS_BF16 = 0, 1
 FS_OK, FS_EINVAL, FS_ENOMEM, FS_EHIP, FS_ENOTIMPL, FS_ERANGE = 0, -1, -2, -3, -4, -5
 FS_MAX_DIM = 256
 FS_SHORT_SEGMENT = 8
+FS_MAX_AHEAD_BATCH = 4
 SHORT_REC_INTS = 12
 
 c_i64, c_i32, c_vp, c_f = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_float
@@ -83,6 +84,7 @@ def load_library() -> ctypes.CDLL:
         "fs_prioritized_step": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args), S]),
         "fs_step_forward": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args), S]),
         "fs_step_forward_ahead": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args), S]),
+        "fs_step_forward_ahead_batch": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args), ctypes.c_int, S]),
         "fs_prioritized_step_pipelined": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args),
                                                          ctypes.POINTER(fs_step_args), S]),
         "fs_graph_capture_pipelined": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args), ctypes.POINTER(fs_step_args),
@@ -322,6 +324,14 @@ def fs_step_forward_ahead(ctx: Context, args: fs_step_args, stream=None) -> None
     stream_arg = ctypes.c_void_p(-1) if stream == FS_STREAM_LAST_STEP else _stream(stream)
     rc = ctx.lib.fs_step_forward_ahead(ctx.handle, ctypes.byref(args), stream_arg)
     ctx.check(rc, "fs_step_forward_ahead")
+
+
+def fs_step_forward_ahead_batch(ctx: Context, args, stream=None) -> None:
+    """args: sequence of 1..FS_MAX_AHEAD_BATCH argument records (copied into one contiguous array)."""
+    arr = (fs_step_args * len(args))(*args)
+    stream_arg = ctypes.c_void_p(-1) if stream == FS_STREAM_LAST_STEP else _stream(stream)
+    rc = ctx.lib.fs_step_forward_ahead_batch(ctx.handle, arr, len(args), stream_arg)
+    ctx.check(rc, "fs_step_forward_ahead_batch")
 
 
 def fs_prioritized_step_pipelined(ctx: Context, cur: fs_step_args, nxt: Optional[fs_step_args], stream=None) -> None:

@@ -92,7 +92,7 @@ struct fs_ahead {
     std::atomic<int> state{kAheadFree};
     uint64_t stamp = 0;                // calling thread only: allocation order
 };
-constexpr int kAheadSlots = 8;
+constexpr int kAheadSlots = 8 * kMaxBatch;
 
 struct fs_host {
     fs_worker *worker[2] = {nullptr, nullptr};   // 0: side stream A, 1: index streams
@@ -537,35 +537,69 @@ int consume_ahead(fs_ctx *ctx, fs_ahead *e, hipStream_t s) {
     return FS_OK;
 }
 
-// Forward of Algorithm 2 (index work): dedup of the lookahead IDs (unless done ahead of time), the
-// collision split of U_t, the class order of batch t
+// Forward of Algorithm 2 (index work) for `count` argument records in shared launches: dedup of the
+// lookahead IDs (unless done ahead of time), the collision split of U_t, the class order of batch t.
+// Per record: `ahead` = its dedup was done by fs_unique_ids_ahead (only waited for); `dedup_out` =
+// entry to signal once its layout of t+1 stands; `layout_in` = the layout of t is still in the making
+// on another index stream.  Record k works in scratch set set0 + k.
+int enqueue_index_work_batch(fs_ctx *ctx, int count, const fs_step_args *a, const bool *have_t, const bool *have_t1,
+                             fs_ahead *const *ahead, hipStream_t s, int set0, fs_ahead *const *dedup_out,
+                             fs_ahead *const *layout_in) {
+    int rc = FS_OK;
+    // dedups: those not done ahead of time share their launches (each keeps the scratch set of its record:
+    // a job list with gaps is passed as separate runs)
+    for (int k = 0; k < count; ++k)
+        if (have_t1[k] && ahead && ahead[k]) {
+            const int r = consume_ahead(ctx, ahead[k], s);
+            if (rc == FS_OK) rc = r;
+        }
+    for (int k0 = 0; k0 < count && rc == FS_OK;) {
+        if (!(have_t1[k0] && !(ahead && ahead[k0]))) { ++k0; continue; }
+        fs_unique_job jobs[kMaxBatch];
+        int m = 0;
+        while (k0 + m < count && have_t1[k0 + m] && !(ahead && ahead[k0 + m])) {
+            const fs_step_args &x = a[k0 + m];
+            jobs[m] = fs_unique_job{x.values_t1, x.n_t1, x.num_rows, x.u_t1, x.seg_offsets_t1, x.perm_t1, x.inverse_t1,
+                                    x.n_unique_t1_dev};
+            ++m;
+        }
+        rc = launch_unique_batch(ctx, m, jobs, s, set0 + k0);
+        k0 += m;
+    }
+    if (dedup_out)
+        for (int k = 0; k < count; ++k)
+            if (dedup_out[k]) {
+                // the layout of t+1 stands from here on: the index half of t+1 (other stream) waits for this
+                const hipError_t e = hipEventRecord(dedup_out[k]->done, s);
+                dedup_out[k]->state.store(kAheadRecorded, std::memory_order_release);
+                if (e != hipSuccess && rc == FS_OK) rc = hip_err(ctx, e, "hipEventRecord(dedup)");
+            }
+    if (layout_in)
+        for (int k = 0; k < count; ++k)
+            if (layout_in[k]) {                               // the layout of t comes from another index stream
+                const int r = consume_ahead(ctx, layout_in[k], s);
+                if (rc == FS_OK) rc = r;
+            }
+    if (rc != FS_OK) return rc;
+    fs_split_job sj[kMaxBatch];
+    fs_class_job cj[kMaxBatch];
+    for (int k = 0; k < count; ++k) {
+        const fs_step_args &x = a[k];
+        const bool t = have_t[k], t1 = have_t1[k];
+        sj[k] = fs_split_job{x.u_t, t ? x.n_unique_t_dev : nullptr, x.u_t1, t1 ? x.n_unique_t1_dev : nullptr,
+                             t ? x.n_t : 0, t1 ? x.n_t1 : 0, x.co, x.co_slot, x.ex, x.ex_slot, x.ex_next,
+                             x.ex_next_slot, x.counts_dev, t ? x.seg_offsets_t : nullptr};
+        cj[k] = fs_class_job{x.perm_t, x.inverse_t, x.seg_offsets_t, t ? x.n_t : 0, t ? x.n_t : 0, x.cperm, x.cslot,
+                             x.cstart, x.class_pos_dev, x.u_t, x.short_rec};
+    }
+    rc = launch_split_batch(ctx, count, sj, s, set0);
+    if (rc != FS_OK) return rc;
+    return launch_class_order_batch(ctx, count, cj, s, set0);
+}
+
 int enqueue_index_work(fs_ctx *ctx, const fs_step_args *a, bool have_t, bool have_t1, fs_ahead *ahead,
                        hipStream_t s, int set = 0, fs_ahead *dedup_out = nullptr, fs_ahead *layout_in = nullptr) {
-    int rc;
-    if (have_t1) {
-        if (ahead) rc = consume_ahead(ctx, ahead, s);
-        else rc = launch_unique(ctx, a->values_t1, a->n_t1, a->num_rows, a->u_t1, a->seg_offsets_t1, a->perm_t1,
-                                a->inverse_t1, a->n_unique_t1_dev, s, set);
-        if (dedup_out) {
-            // the layout of t+1 stands from here on: the index half of t+1 (other stream) waits for this
-            const hipError_t e = hipEventRecord(dedup_out->done, s);
-            dedup_out->state.store(kAheadRecorded, std::memory_order_release);
-            if (e != hipSuccess && rc == FS_OK) rc = hip_err(ctx, e, "hipEventRecord(dedup)");
-        }
-        if (rc != FS_OK) return rc;
-    }
-    if (layout_in) {
-        rc = consume_ahead(ctx, layout_in, s);                // the layout of t comes from another index stream
-        if (rc != FS_OK) return rc;
-    }
-    rc = launch_split(ctx, a->u_t, have_t ? a->n_unique_t_dev : nullptr, a->u_t1,
-                      have_t1 ? a->n_unique_t1_dev : nullptr, have_t ? a->n_t : 0, have_t1 ? a->n_t1 : 0, a->co,
-                      a->co_slot, a->ex, a->ex_slot, a->ex_next, a->ex_next_slot, a->counts_dev, s,
-                      have_t ? a->seg_offsets_t : nullptr, set);
-    if (rc != FS_OK) return rc;
-    return launch_class_order(ctx, a->perm_t, a->inverse_t, a->seg_offsets_t, have_t ? a->n_t : 0,
-                              have_t ? a->n_t : 0, a->cperm, a->cslot, a->cstart, a->class_pos_dev, a->u_t,
-                              a->short_rec, s, set);
+    return enqueue_index_work_batch(ctx, 1, a, &have_t, &have_t1, &ahead, s, set, &dedup_out, &layout_in);
 }
 
 // update_embedding for one class of rows of iteration t (0: priority pass, 1: deferred pass)
@@ -720,7 +754,7 @@ int fs_unique_ids_ahead(fs_ctx *ctx, const int64_t *ids, int64_t n, int64_t num_
         int rc = FS_OK;
         if (hipStreamWaitEvent(sx, after, 0) != hipSuccess) rc = FS_EHIP;
         if (rc == FS_OK)
-            rc = launch_unique(ctx, ids, n, num_rows, unique, seg_offsets, perm, inverse, n_unique_dev, sx, 1 + x);
+            rc = launch_unique(ctx, ids, n, num_rows, unique, seg_offsets, perm, inverse, n_unique_dev, sx, 1 + x * kMaxBatch);
         if (hipEventRecord(e->done, sx) != hipSuccess && rc == FS_OK) rc = FS_EHIP;
         e->state.store(kAheadRecorded, std::memory_order_release);   // also after a failure: nobody may spin forever
         return rc;
@@ -734,51 +768,85 @@ int fs_unique_ids_ahead(fs_ctx *ctx, const int64_t *ids, int64_t n, int64_t num_
 }
 
 int fs_step_forward_ahead(fs_ctx *ctx, const fs_step_args *a, fs_stream stream) {
+    return fs_step_forward_ahead_batch(ctx, a, 1, stream);
+}
+
+int fs_step_forward_ahead_batch(fs_ctx *ctx, const fs_step_args *a, int count, fs_stream stream) {
     if (!ctx) return FS_EINVAL;
-    bool have_t, have_t1;
-    int rc = check_step_args(ctx, a, &have_t, &have_t1);
-    if (rc != FS_OK) return rc;
-    FS_REQUIRE(ctx, !ctx->capturing, "index half ahead: not while a graph is being captured");
-    fs_host *h = ctx->host;
-    if (find_ahead(ctx, a->counts_dev)) {
-        (void)workers_wait(ctx);
-        drop_ahead(ctx, a->counts_dev);
+    FS_REQUIRE(ctx, a && count >= 1 && count <= FS_MAX_AHEAD_BATCH, "index half ahead: batch of 1..FS_MAX_AHEAD_BATCH records");
+    struct batch_state {
+        fs_step_args args[kMaxBatch];
+        bool have_t[kMaxBatch], have_t1[kMaxBatch];
+        fs_ahead *dedup_in[kMaxBatch], *layout_in[kMaxBatch], *e_idx[kMaxBatch], *e_ded[kMaxBatch];
+    } b;
+    for (int k = 0; k < count; ++k) {
+        const int rc = check_step_args(ctx, &a[k], &b.have_t[k], &b.have_t1[k]);
+        if (rc != FS_OK) return rc;
+        b.args[k] = a[k];
+        b.dedup_in[k] = b.layout_in[k] = b.e_idx[k] = b.e_ded[k] = nullptr;
     }
-    // the dedup of the lookahead batch may already be under way (fs_unique_ids_ahead), the layout of
-    // batch t may still be in the making (index half of t-1, on the other index stream)
-    fs_ahead *dedup_in = have_t1 ? claim_ahead(ctx, a->u_t1) : nullptr;
-    fs_ahead *layout_in = have_t ? claim_ahead(ctx, a->u_t) : nullptr;
-    fs_ahead *e_idx = alloc_ahead(ctx, a->counts_dev);
-    fs_ahead *e_ded = (e_idx && have_t1) ? alloc_ahead(ctx, a->u_t1) : nullptr;
-    if (!e_idx || (have_t1 && !e_ded)) {
+    FS_REQUIRE(ctx, !ctx->capturing, "index half ahead: not while a graph is being captured");
+    if (stream == FS_STREAM_LAST_STEP)
+        FS_REQUIRE(ctx, ctx->pfork_valid, "index half ahead: FS_STREAM_LAST_STEP before any pipelined call");
+    fs_host *h = ctx->host;
+    for (int k = 0; k < count; ++k)
+        if (find_ahead(ctx, a[k].counts_dev)) {
+            (void)workers_wait(ctx);
+            drop_ahead(ctx, a[k].counts_dev);
+        }
+    // the dedup of a lookahead batch may already be under way (fs_unique_ids_ahead); the layout of a
+    // batch t may still be in the making (index half of t-1 on the other index stream) unless an earlier
+    // record of this very batch produces it
+    bool failed = false;
+    for (int k = 0; k < count && !failed; ++k) {
+        bool internal = false;
+        for (int q = 0; q < k; ++q) internal = internal || (b.have_t1[q] && a[q].u_t1 == a[k].u_t);
+        b.dedup_in[k] = b.have_t1[k] ? claim_ahead(ctx, a[k].u_t1) : nullptr;
+        b.layout_in[k] = (b.have_t[k] && !internal) ? claim_ahead(ctx, a[k].u_t) : nullptr;
+    }
+    for (int k = 0; k < count && !failed; ++k) {
+        // a layout that a later record of this batch splits needs no entry of its own: nobody else waits
+        // for it before that record's index half is done
+        bool wanted = b.have_t1[k];
+        for (int q = k + 1; q < count; ++q) wanted = wanted && a[q].u_t != a[k].u_t1;
+        b.e_idx[k] = alloc_ahead(ctx, a[k].counts_dev);
+        b.e_ded[k] = (b.e_idx[k] && wanted) ? alloc_ahead(ctx, a[k].u_t1) : nullptr;
+        failed = !b.e_idx[k] || (wanted && !b.e_ded[k]);
+    }
+    if (failed) {
         // the claimed entries still have to be waited for by somebody: let the index streams do it
-        if (dedup_in) (void)consume_ahead(ctx, dedup_in, ctx->stream_x[0]);
-        if (layout_in) (void)consume_ahead(ctx, layout_in, ctx->stream_x[0]);
-        if (e_idx) { e_idx->key = nullptr; e_idx->state.store(kAheadFree, std::memory_order_release); }
+        for (int k = 0; k < count; ++k) {
+            if (b.dedup_in[k]) (void)consume_ahead(ctx, b.dedup_in[k], ctx->stream_x[0]);
+            if (b.layout_in[k]) (void)consume_ahead(ctx, b.layout_in[k], ctx->stream_x[0]);
+            fs_ahead *mine[2] = {b.e_idx[k], b.e_ded[k]};
+            for (fs_ahead *e : mine)
+                if (e) { e->key = nullptr; e->state.store(kAheadFree, std::memory_order_release); }
+        }
         return set_err(ctx, FS_EINVAL, "index half ahead: too much ahead-of-time work is outstanding");
     }
     const int x = h->x_turn;
     h->x_turn = (x + 1) % kIndexStreams;
     hipStream_t sx = ctx->stream_x[x];
-    hipEvent_t after = e_idx->fork;
-    if (stream == FS_STREAM_LAST_STEP) {
-        FS_REQUIRE(ctx, ctx->pfork_valid, "index half ahead: FS_STREAM_LAST_STEP before any pipelined call");
-        after = ctx->ev_pfork[ctx->pipe_parity];
-    } else {
-        FS_HIP(ctx, hipEventRecord(e_idx->fork, as_stream(stream)));
-    }
-    const fs_step_args args = *a;
+    hipEvent_t after = b.e_idx[0]->fork;
+    if (stream == FS_STREAM_LAST_STEP) after = ctx->ev_pfork[ctx->pipe_parity];
+    else FS_HIP(ctx, hipEventRecord(b.e_idx[0]->fork, as_stream(stream)));
     auto job = [=]() -> int {
         int jrc = FS_OK;
         if (hipStreamWaitEvent(sx, after, 0) != hipSuccess) jrc = FS_EHIP;
-        const int irc = enqueue_index_work(ctx, &args, have_t, have_t1, dedup_in, sx, 1 + x, e_ded, layout_in);
+        const int irc = enqueue_index_work_batch(ctx, count, b.args, b.have_t, b.have_t1, b.dedup_in, sx,
+                                                 1 + x * kMaxBatch, b.e_ded, b.layout_in);
         if (jrc == FS_OK) jrc = irc;
-        if (e_ded && e_ded->state.load(std::memory_order_acquire) != kAheadRecorded) {
-            (void)hipEventRecord(e_ded->done, sx);            // only after an early failure: nobody may spin forever
-            e_ded->state.store(kAheadRecorded, std::memory_order_release);
+        for (int k = 0; k < count; ++k) {
+            fs_ahead *e = b.e_ded[k];
+            if (e && e->state.load(std::memory_order_acquire) != kAheadRecorded) {
+                (void)hipEventRecord(e->done, sx);            // only after an early failure: nobody may spin forever
+                e->state.store(kAheadRecorded, std::memory_order_release);
+            }
         }
-        if (hipEventRecord(e_idx->done, sx) != hipSuccess && jrc == FS_OK) jrc = FS_EHIP;
-        e_idx->state.store(kAheadRecorded, std::memory_order_release);
+        for (int k = 0; k < count; ++k) {
+            if (hipEventRecord(b.e_idx[k]->done, sx) != hipSuccess && jrc == FS_OK) jrc = FS_EHIP;
+            b.e_idx[k]->state.store(kAheadRecorded, std::memory_order_release);
+        }
         return jrc;
     };
     fs_worker *w = ctx->use_worker ? get_worker(ctx, 1) : nullptr;

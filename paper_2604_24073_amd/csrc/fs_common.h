@@ -59,7 +59,9 @@ struct fs_sort_scratch {
 #define FS_INDEX_STREAMS 2
 #endif
 constexpr int kIndexStreams = FS_INDEX_STREAMS;   // streams that run ahead-of-time index work, used in turn
-constexpr int kSortSets = 1 + kIndexStreams;      // 0: the caller's stream / side stream, then one per index stream
+constexpr int kMaxBatch = FS_MAX_AHEAD_BATCH;     // (freescale.h)     // index halves that may share their launches
+// scratch sets: 0 for the caller's stream / side stream, then kMaxBatch per index stream
+constexpr int kSortSets = 1 + kIndexStreams * kMaxBatch;
 
 // scratch between the launches of one split + class order (same stream); one set per stream that may run one
 struct fs_split_scratch {
@@ -69,6 +71,34 @@ struct fs_split_scratch {
     int32_t *cstart_local;    // [max_ids] occurrences of same-class rows before this row inside its split tile
     int32_t *tile_len;        // [2 * scan tiles] occurrences per split tile: collision rows, then exclusive rows
     int32_t *cidx;            // [max_ids] place of every row of U_t in its class list
+};
+
+// one dedup / one collision split / one class order of a batch that shares its launches (host side)
+struct fs_unique_job {
+    const int64_t *ids;
+    int64_t n, num_rows;
+    int64_t *unique;
+    int32_t *seg_offsets, *perm, *inverse;
+    int64_t *n_unique_dev;
+};
+struct fs_split_job {
+    const int64_t *u_t, *n_t_dev, *u_t1, *n_t1_dev;
+    int64_t cap_t, cap_t1;
+    int64_t *co;
+    int32_t *co_slot;
+    int64_t *ex;
+    int32_t *ex_slot;
+    int64_t *ex_next;
+    int32_t *ex_next_slot;
+    int64_t *counts_dev;
+    const int32_t *seg_offsets_t;   // optional; given, the per-tile occurrence counts the class order needs are left in the scratch
+};
+struct fs_class_job {
+    const int32_t *perm, *inverse, *seg_offsets;
+    int64_t n, cap_u;
+    int32_t *cperm, *cslot, *cstart, *class_pos_dev;
+    const int64_t *u_t;
+    int32_t *short_rec;
 };
 
 struct fs_ctx {
@@ -169,6 +199,11 @@ inline hipEvent_t *timing_pair(fs_ctx *ctx, int kind) {
 int launch_unique(fs_ctx *, const int64_t *ids, int64_t n, int64_t num_rows, int64_t *unique,
                   int32_t *seg_offsets, int32_t *perm, int32_t *inverse, int64_t *n_unique_dev, hipStream_t s,
                   int set = 0);
+// `count` (1..kMaxBatch) independent jobs in shared launches; job k uses scratch set set0 + k
+int launch_unique_batch(fs_ctx *, int count, const fs_unique_job *jobs, hipStream_t s, int set0);
+int launch_split_batch(fs_ctx *, int count, const fs_split_job *jobs, hipStream_t s, int set0);
+// right after launch_split_batch(..., seg_offsets_t given) with the same jobs order and sets, on the same stream
+int launch_class_order_batch(fs_ctx *, int count, const fs_class_job *jobs, hipStream_t s, int set0);
 // seg_offsets_t: optional; given, the per-tile occurrence counts that launch_class_order needs are left in
 // the context scratch
 int launch_split(fs_ctx *, const int64_t *u_t, const int64_t *n_t_dev, const int64_t *u_t1,
@@ -184,6 +219,13 @@ int launch_reduce_update(fs_ctx *, int cls, const float *grads, int64_t n, int32
                          const int32_t *cstart, const int64_t *u_t, void *table, int dt, float *state,
                          int64_t num_rows, float lr, float eps, float *reduced, hipStream_t s,
                          const int32_t *short_rec, const int64_t *n_rows_dev);
+// the deferred pass (class 1) of iteration t and the gather of the lookahead rows in one launch
+int launch_deferred_gather(fs_ctx *, const float *grads, int64_t n, int32_t dim, const int32_t *cperm,
+                           const int32_t *cslot, const int32_t *class_pos, const int32_t *seg_offsets,
+                           const int32_t *cstart, const int64_t *u_t, void *table, int dt, float *state,
+                           int64_t num_rows, float lr, float eps, float *reduced, hipStream_t s,
+                           const int32_t *short_rec, const int64_t *n_rows_dev, const int64_t *values,
+                           const int64_t *offsets, int64_t batch, int64_t n_values, void *out);
 // `timing`: optional event pair recorded around the main (chunk) kernel only
 int launch_reduce(fs_ctx *, const float *grads, int64_t n, int32_t dim, const int32_t *perm,
                   const int32_t *seg_offsets, const int64_t *n_unique_dev, float *reduced, hipStream_t s,

@@ -76,16 +76,51 @@ __device__ __forceinline__ int clamp_count(const int64_t *dev, int64_t cap) {
     return (int)v;
 }
 
+// One collision split + class order of a batch that shares its launches (blockIdx.y picks the job), as
+// the kernels see it.
+struct split_dev_job {
+    const int64_t *u_t, *n_t_dev, *u_t1, *n_t1_dev;
+    int64_t cap_t, cap_t1;
+    int tiles_t, tiles_t1;        // tiles_t is at least 1: an empty U_t still has its counts written
+    uint8_t *flag_t, *flag_t1;
+    int32_t *tile_cnt;
+    int64_t *co;
+    int32_t *co_slot;
+    int64_t *ex;
+    int32_t *ex_slot;
+    int64_t *ex_next;
+    int32_t *ex_next_slot;
+    int64_t *counts_dev;
+    const int32_t *seg_offsets_t;
+    int32_t *cstart_local, *tile_len, *cidx;
+};
+struct split_dev_batch {
+    split_dev_job j[kMaxBatch];
+};
+struct class_dev_job {
+    const int32_t *perm, *inverse, *seg_offsets;
+    int n, tiles_t, blocks, cap;  // blocks is at least 1: an empty batch still has its class extents written
+    const uint8_t *flag_t;
+    const int32_t *cstart_local, *tile_len, *cidx;
+    int32_t *cperm, *cslot, *cstart, *class_pos_dev;
+    const int64_t *u_t;
+    int32_t *short_rec;
+};
+struct class_dev_batch {
+    class_dev_job j[kMaxBatch];
+};
+
 // blocks [0, tiles_t) flag U_t against U_t1; blocks [tiles_t, tiles_t + tiles_t1) flag U_t1 against U_t
-__global__ __launch_bounds__(kScanThreads) void split_flag_kernel(const int64_t *__restrict__ u_t,
-                                                                  const int64_t *__restrict__ n_t_dev,
-                                                                  const int64_t *__restrict__ u_t1,
-                                                                  const int64_t *__restrict__ n_t1_dev, int64_t cap_t,
-                                                                  int64_t cap_t1, int tiles_t,
-                                                                  uint8_t *__restrict__ flag_t,
-                                                                  uint8_t *__restrict__ flag_t1,
-                                                                  int32_t *__restrict__ tile_cnt) {
+__global__ __launch_bounds__(kScanThreads) void split_flag_kernel(const split_dev_batch batch) {
     FS_WG_TRACE(5);
+    const split_dev_job &job = batch.j[blockIdx.y];
+    if ((int)blockIdx.x >= job.tiles_t + job.tiles_t1) return;
+    const int64_t *__restrict__ u_t = job.u_t, *__restrict__ u_t1 = job.u_t1;
+    const int64_t *__restrict__ n_t_dev = job.n_t_dev, *__restrict__ n_t1_dev = job.n_t1_dev;
+    const int64_t cap_t = job.cap_t, cap_t1 = job.cap_t1;
+    const int tiles_t = job.tiles_t;
+    uint8_t *__restrict__ flag_t = job.flag_t, *__restrict__ flag_t1 = job.flag_t1;
+    int32_t *__restrict__ tile_cnt = job.tile_cnt;
     __shared__ int sh[kScanThreads / kWave];
     __shared__ int win[2];
     __shared__ int64_t window[kSplitWindow];
@@ -131,15 +166,23 @@ __global__ __launch_bounds__(kScanThreads) void split_flag_kernel(const int64_t 
     if (threadIdx.x == 0) tile_cnt[blockIdx.x] = total;      // number of collisions in this tile
 }
 
-__global__ __launch_bounds__(kScanThreads) void split_compact_kernel(
-    const int64_t *__restrict__ u_t, const int64_t *__restrict__ n_t_dev, const int64_t *__restrict__ u_t1,
-    const int64_t *__restrict__ n_t1_dev, int64_t cap_t, int64_t cap_t1, int tiles_t, int tiles_t1,
-    const uint8_t *__restrict__ flag_t, const uint8_t *__restrict__ flag_t1, const int32_t *__restrict__ tile_cnt,
-    int64_t *__restrict__ co, int32_t *__restrict__ co_slot, int64_t *__restrict__ ex, int32_t *__restrict__ ex_slot,
-    int64_t *__restrict__ ex_next, int32_t *__restrict__ ex_next_slot, int64_t *__restrict__ counts_dev,
-    const int32_t *__restrict__ seg_offsets_t, int32_t *__restrict__ cstart_local, int32_t *__restrict__ tile_len,
-    int32_t *__restrict__ cidx) {
+__global__ __launch_bounds__(kScanThreads) void split_compact_kernel(const split_dev_batch batch) {
     FS_WG_TRACE(6);
+    const split_dev_job &job = batch.j[blockIdx.y];
+    if ((int)blockIdx.x >= job.tiles_t + job.tiles_t1) return;
+    const int64_t *__restrict__ u_t = job.u_t, *__restrict__ u_t1 = job.u_t1;
+    const int64_t *__restrict__ n_t_dev = job.n_t_dev, *__restrict__ n_t1_dev = job.n_t1_dev;
+    const int64_t cap_t = job.cap_t, cap_t1 = job.cap_t1;
+    const int tiles_t = job.tiles_t;
+    const uint8_t *__restrict__ flag_t = job.flag_t, *__restrict__ flag_t1 = job.flag_t1;
+    const int32_t *__restrict__ tile_cnt = job.tile_cnt;
+    int64_t *__restrict__ co = job.co, *__restrict__ ex = job.ex, *__restrict__ ex_next = job.ex_next;
+    int32_t *__restrict__ co_slot = job.co_slot, *__restrict__ ex_slot = job.ex_slot;
+    int32_t *__restrict__ ex_next_slot = job.ex_next_slot;
+    int64_t *__restrict__ counts_dev = job.counts_dev;
+    const int32_t *__restrict__ seg_offsets_t = job.seg_offsets_t;
+    int32_t *__restrict__ cstart_local = job.cstart_local, *__restrict__ tile_len = job.tile_len;
+    int32_t *__restrict__ cidx = job.cidx;
     __shared__ int sh[kScanThreads / kWave];
     const int n_t = clamp_count(n_t_dev, cap_t), n_t1 = clamp_count(n_t1_dev, cap_t1);
     const bool side_t = (int)blockIdx.x < tiles_t;
@@ -221,13 +264,21 @@ __global__ __launch_bounds__(kScanThreads) void split_compact_kernel(
 // Class order of the occurrences of batch t that belong to rows with more than FS_SHORT_SEGMENT
 // occurrences: sorted position q (row slot s, the j-th occurrence of that row) goes to  [start of the class] + [occurrences of same-class rows before s] + j.
 // Every workgroup first turns the per-tile totals into tile bases (a few hundred values).
-__global__ __launch_bounds__(kScanThreads) void class_scatter_kernel(
-    const int32_t *__restrict__ perm, const int32_t *__restrict__ inverse, const int32_t *__restrict__ seg_offsets,
-    int n, int tiles_t, const uint8_t *__restrict__ flag_t, const int32_t *__restrict__ cstart_local,
-    const int32_t *__restrict__ tile_len, int32_t *__restrict__ cperm, int32_t *__restrict__ cslot,
-    int32_t *__restrict__ cstart, int32_t *__restrict__ class_pos_dev, int *__restrict__ flags,
-    const int64_t *__restrict__ u_t, const int32_t *__restrict__ cidx, int32_t *__restrict__ short_rec, int cap) {
+__global__ __launch_bounds__(kScanThreads) void class_scatter_kernel(const class_dev_batch batch,
+                                                                     int *__restrict__ flags) {
     FS_WG_TRACE(7);
+    const class_dev_job &job = batch.j[blockIdx.y];
+    if ((int)blockIdx.x >= job.blocks) return;
+    const int32_t *__restrict__ perm = job.perm, *__restrict__ inverse = job.inverse;
+    const int32_t *__restrict__ seg_offsets = job.seg_offsets;
+    const int n = job.n, tiles_t = job.tiles_t, cap = job.cap;
+    const uint8_t *__restrict__ flag_t = job.flag_t;
+    const int32_t *__restrict__ cstart_local = job.cstart_local, *__restrict__ tile_len = job.tile_len;
+    const int32_t *__restrict__ cidx = job.cidx;
+    int32_t *__restrict__ cperm = job.cperm, *__restrict__ cslot = job.cslot, *__restrict__ cstart = job.cstart;
+    int32_t *__restrict__ class_pos_dev = job.class_pos_dev;
+    const int64_t *__restrict__ u_t = job.u_t;
+    int32_t *__restrict__ short_rec = job.short_rec;
     extern __shared__ int tile_base[];                      // [2 * tiles_t]
     __shared__ int sh[kScanThreads / kWave];
     int class_total[2];
@@ -311,50 +362,90 @@ __global__ void split_empty_kernel(const int64_t *n_t1_dev, int64_t cap_t1, int6
     counts_dev[2] = clamp_count(n_t1_dev, cap_t1);
 }
 
+int launch_split_batch(fs_ctx *ctx, int count, const fs_split_job *jobs, hipStream_t s, int set0) {
+    if (count < 1 || count > kMaxBatch || set0 < 0 || set0 + count > kSortSets)
+        return set_err(ctx, FS_EINVAL, "split: batch size");
+    if (count == 1 && jobs[0].cap_t == 0 && jobs[0].cap_t1 == 0) {
+        hipLaunchKernelGGL(split_empty_kernel, dim3(1), dim3(1), 0, s, jobs[0].n_t1_dev, jobs[0].cap_t1,
+                           jobs[0].counts_dev);
+        FS_LAUNCH_CHECK(ctx, "split_empty_kernel");
+        return FS_OK;
+    }
+    split_dev_batch batch;
+    memset(&batch, 0, sizeof(batch));
+    int blocks = 0;
+    for (int k = 0; k < count; ++k) {
+        const fs_split_job &in = jobs[k];
+        const fs_split_scratch &ws = ctx->split[set0 + k];
+        split_dev_job &j = batch.j[k];
+        const int tiles_t = (int)ceil_div(in.cap_t, kScanTile);
+        j.u_t = in.u_t; j.n_t_dev = in.n_t_dev; j.u_t1 = in.u_t1; j.n_t1_dev = in.n_t1_dev;
+        j.cap_t = in.cap_t; j.cap_t1 = in.cap_t1;
+        // With cap_t == 0 a single (empty) tile on side t keeps the count logic in one place.
+        j.tiles_t = tiles_t > 0 ? tiles_t : 1;
+        j.tiles_t1 = (int)ceil_div(in.cap_t1, kScanTile);
+        j.flag_t = ws.flag_t; j.flag_t1 = ws.flag_t1; j.tile_cnt = ws.cnt;
+        j.co = in.co; j.co_slot = in.co_slot; j.ex = in.ex; j.ex_slot = in.ex_slot;
+        j.ex_next = in.ex_next; j.ex_next_slot = in.ex_next_slot; j.counts_dev = in.counts_dev;
+        j.seg_offsets_t = in.seg_offsets_t;
+        j.cstart_local = ws.cstart_local; j.tile_len = ws.tile_len; j.cidx = ws.cidx;
+        blocks = (j.tiles_t + j.tiles_t1) > blocks ? (j.tiles_t + j.tiles_t1) : blocks;
+    }
+    const dim3 grid((unsigned)blocks, (unsigned)count);
+    hipLaunchKernelGGL(split_flag_kernel, grid, dim3(kScanThreads), 0, s, batch);
+    hipLaunchKernelGGL(split_compact_kernel, grid, dim3(kScanThreads), 0, s, batch);
+    FS_LAUNCH_CHECK(ctx, "split kernels");
+    return FS_OK;
+}
+
 int launch_split(fs_ctx *ctx, const int64_t *u_t, const int64_t *n_t_dev, const int64_t *u_t1,
                  const int64_t *n_t1_dev, int64_t cap_t, int64_t cap_t1, int64_t *co, int32_t *co_slot,
                  int64_t *ex, int32_t *ex_slot, int64_t *ex_next, int32_t *ex_next_slot, int64_t *counts_dev,
                  hipStream_t s, const int32_t *seg_offsets_t, int set) {
-    const fs_split_scratch &ws = ctx->split[set];
-    const int tiles_t = (int)ceil_div(cap_t, kScanTile);
-    const int tiles_t1 = (int)ceil_div(cap_t1, kScanTile);
-    if (tiles_t == 0 && tiles_t1 == 0) {
-        hipLaunchKernelGGL(split_empty_kernel, dim3(1), dim3(1), 0, s, n_t1_dev, cap_t1, counts_dev);
-        FS_LAUNCH_CHECK(ctx, "split_empty_kernel");
+    const fs_split_job job = {u_t, n_t_dev, u_t1, n_t1_dev, cap_t, cap_t1, co, co_slot, ex, ex_slot,
+                              ex_next, ex_next_slot, counts_dev, seg_offsets_t};
+    return launch_split_batch(ctx, 1, &job, s, set);
+}
+
+int launch_class_order_batch(fs_ctx *ctx, int count, const fs_class_job *jobs, hipStream_t s, int set0) {
+    if (count < 1 || count > kMaxBatch || set0 < 0 || set0 + count > kSortSets)
+        return set_err(ctx, FS_EINVAL, "class order: batch size");
+    if (count == 1 && jobs[0].n == 0) {
+        hipLaunchKernelGGL(class_empty_kernel, dim3(1), dim3(1), 0, s, jobs[0].class_pos_dev);
+        FS_LAUNCH_CHECK(ctx, "class_empty_kernel");
         return FS_OK;
     }
-    // With cap_t == 0 a single (empty) tile on side t keeps the count logic in one place.
-    const int tt = tiles_t > 0 ? tiles_t : 1;
-    hipLaunchKernelGGL(split_flag_kernel, dim3(tt + tiles_t1), dim3(kScanThreads), 0, s, u_t, n_t_dev, u_t1, n_t1_dev,
-                       cap_t, cap_t1, tt, ws.flag_t, ws.flag_t1, ws.cnt);
-    hipLaunchKernelGGL(split_compact_kernel, dim3(tt + tiles_t1), dim3(kScanThreads), 0, s, u_t, n_t_dev, u_t1,
-                       n_t1_dev, cap_t, cap_t1, tt, tiles_t1, (const uint8_t *)ws.flag_t,
-                       (const uint8_t *)ws.flag_t1, (const int32_t *)ws.cnt, co, co_slot, ex, ex_slot,
-                       ex_next, ex_next_slot, counts_dev, seg_offsets_t, ws.cstart_local, ws.tile_len,
-                       ws.cidx);
-    FS_LAUNCH_CHECK(ctx, "split kernels");
+    class_dev_batch batch;
+    memset(&batch, 0, sizeof(batch));
+    int blocks = 1, max_tiles = 0;
+    for (int k = 0; k < count; ++k) {
+        const fs_class_job &in = jobs[k];
+        const fs_split_scratch &ws = ctx->split[set0 + k];
+        class_dev_job &j = batch.j[k];
+        j.perm = in.perm; j.inverse = in.inverse; j.seg_offsets = in.seg_offsets;
+        j.n = (int)in.n;
+        j.tiles_t = (int)ceil_div(in.cap_u, kScanTile);      // the same tiling the split used for side t
+        j.blocks = in.n > 0 ? (int)ceil_div(in.n, kScanTile) : 1;
+        j.cap = (int)in.cap_u;
+        j.flag_t = ws.flag_t; j.cstart_local = ws.cstart_local; j.tile_len = ws.tile_len; j.cidx = ws.cidx;
+        j.cperm = in.cperm; j.cslot = in.cslot; j.cstart = in.cstart; j.class_pos_dev = in.class_pos_dev;
+        j.u_t = in.u_t; j.short_rec = in.short_rec;
+        blocks = j.blocks > blocks ? j.blocks : blocks;
+        max_tiles = j.tiles_t > max_tiles ? j.tiles_t : max_tiles;
+    }
+    if ((size_t)max_tiles * 2 * sizeof(int) > 60 * 1024)
+        return set_err(ctx, FS_ERANGE, "class order: more than 7.8M distinct rows in one batch");
+    hipLaunchKernelGGL(class_scatter_kernel, dim3((unsigned)blocks, (unsigned)count), dim3(kScanThreads),
+                       (size_t)max_tiles * 2 * sizeof(int), s, batch, ctx->d_flags);
+    FS_LAUNCH_CHECK(ctx, "class_scatter_kernel");
     return FS_OK;
 }
 
 int launch_class_order(fs_ctx *ctx, const int32_t *perm, const int32_t *inverse, const int32_t *seg_offsets,
                        int64_t n, int64_t cap_u, int32_t *cperm, int32_t *cslot, int32_t *cstart,
                        int32_t *class_pos_dev, const int64_t *u_t, int32_t *short_rec, hipStream_t s, int set) {
-    const fs_split_scratch &ws = ctx->split[set];
-    if (n == 0) {
-        hipLaunchKernelGGL(class_empty_kernel, dim3(1), dim3(1), 0, s, class_pos_dev);
-        FS_LAUNCH_CHECK(ctx, "class_empty_kernel");
-        return FS_OK;
-    }
-    const int tiles_t = (int)ceil_div(cap_u, kScanTile);     // the same tiling launch_split used for side t
-    if ((size_t)tiles_t * 2 * sizeof(int) > 60 * 1024)
-        return set_err(ctx, FS_ERANGE, "class order: more than 7.8M distinct rows in one batch");
-    hipLaunchKernelGGL(class_scatter_kernel, dim3((unsigned)ceil_div(n, kScanTile)), dim3(kScanThreads),
-                       (size_t)tiles_t * 2 * sizeof(int), s, perm, inverse, seg_offsets, (int)n, tiles_t,
-                       (const uint8_t *)ws.flag_t, (const int32_t *)ws.cstart_local,
-                       (const int32_t *)ws.tile_len, cperm, cslot, cstart, class_pos_dev, ctx->d_flags, u_t,
-                       (const int32_t *)ws.cidx, short_rec, (int)cap_u);
-    FS_LAUNCH_CHECK(ctx, "class_scatter_kernel");
-    return FS_OK;
+    const fs_class_job job = {perm, inverse, seg_offsets, n, cap_u, cperm, cslot, cstart, class_pos_dev, u_t, short_rec};
+    return launch_class_order_batch(ctx, 1, &job, s, set);
 }
 
 FS_TRACE_SETTER(split)

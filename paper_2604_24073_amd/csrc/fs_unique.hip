@@ -9,6 +9,10 @@
 // [tile][digit] table small enough that every scatter workgroup scans it by itself - a pass is
 // two launches (histogram, scan+rank+scatter) and no workgroup ever waits for another.  Ranking
 // uses wavefront ballots, so equal digits keep their order.
+//
+// Every launch handles up to kMaxBatch independent dedups (blockIdx.y picks the job): the lookahead
+// batches of several iterations, or of several tables, share their launches - what a launch costs the
+// rest of the chip (its start and end disturb every kernel that runs beside it) is paid once.
 #include "fs_common.h"
 #include "fs_device.h"
 
@@ -45,15 +49,36 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int *sh, int &total) 
     return base + inc - v;
 }
 
+// ---- one dedup of a batch, as the kernels see it ----------------------------------------------------
+struct unique_dev_job {
+    const int64_t *ids;
+    int n, tiles, stiles;         // IDs, sort tiles, compaction tiles (at least 1: the empty dedup writes its counts too)
+    int64_t num_rows;
+    void *keys[2];                // ping-pong key buffers (K words)
+    int32_t *idx[2];              // ping-pong position buffers
+    uint32_t *tile_hist;
+    int32_t *tile_heads;
+    int64_t *unique;
+    int32_t *seg_offsets, *perm, *inverse;
+    int64_t *n_unique_dev;
+};
+struct unique_dev_batch {
+    unique_dev_job j[kMaxBatch];
+};
+
 // ---- radix pass 1/2: per-tile digit histogram ---------------------------------------------------
 template <typename K, bool FIRST>
-__global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(const int64_t *__restrict__ ids,
-                                                                  const K *__restrict__ keys_in, int n, int shift,
-                                                                  int bits, int64_t num_rows,
-                                                                  uint32_t *__restrict__ tile_hist,
-                                                                  int *__restrict__ flags) {
-    __shared__ uint32_t hist[kRadix];
+__global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(const unique_dev_batch batch, int src, int shift,
+                                                                  int bits, int *__restrict__ flags) {
     FS_WG_TRACE(1);
+    const unique_dev_job &job = batch.j[blockIdx.y];
+    if ((int)blockIdx.x >= job.tiles) return;
+    const int64_t *__restrict__ ids = job.ids;
+    const K *__restrict__ keys_in = (const K *)job.keys[src];
+    const int n = job.n;
+    const int64_t num_rows = job.num_rows;
+    uint32_t *__restrict__ tile_hist = job.tile_hist;
+    __shared__ uint32_t hist[kRadix];
     const int bins = 1 << bits;
     for (int d = threadIdx.x; d < bins; d += kSortThreads) hist[d] = 0;
     __syncthreads();
@@ -82,18 +107,22 @@ __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(const int64_t 
 // ---- radix pass 2/2: scan of the [tile][digit] table, stable ranking, scatter ---------------------
 // Tile order is (wave, round, lane): wave w owns 64*KPT consecutive keys, read 64 at a time.
 template <typename K, bool FIRST>
-__global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(const int64_t *__restrict__ ids,
-                                                                     const K *__restrict__ keys_in,
-                                                                     const int32_t *__restrict__ idx_in,
-                                                                     K *__restrict__ keys_out,
-                                                                     int32_t *__restrict__ idx_out, int n, int shift,
-                                                                     int bits, int tiles,
-                                                                     const uint32_t *__restrict__ tile_hist) {
+__global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(const unique_dev_batch batch, int src, int shift,
+                                                                     int bits, int last) {
+    FS_WG_TRACE(2);
+    const unique_dev_job &job = batch.j[blockIdx.y];
+    if ((int)blockIdx.x >= job.tiles) return;
+    const int64_t *__restrict__ ids = job.ids;
+    const K *__restrict__ keys_in = (const K *)job.keys[src];
+    const int32_t *__restrict__ idx_in = job.idx[src];
+    K *__restrict__ keys_out = (K *)job.keys[src ^ 1];
+    int32_t *__restrict__ idx_out = last ? job.perm : job.idx[src ^ 1];
+    const int n = job.n, tiles = job.tiles;
+    const uint32_t *__restrict__ tile_hist = job.tile_hist;
     __shared__ uint32_t cnt[kSortWaves][kRadix];       // per-wave digit counters, then wave bases
     __shared__ uint32_t sh_below[kSortScan];
     __shared__ uint32_t sh_total[kSortScan];
     __shared__ uint32_t gbase[kRadix];
-    FS_WG_TRACE(2);
     const int bins = 1 << bits;
     const int lane = threadIdx.x & (kWave - 1);
     const int w = threadIdx.x / kWave;
@@ -229,9 +258,13 @@ __device__ __forceinline__ int load_heads(const K *__restrict__ keys, int n, int
 }
 
 template <typename K>
-__global__ __launch_bounds__(kScanThreads) void unique_count_kernel(const K *__restrict__ keys, int n,
-                                                                    int32_t *__restrict__ tile_heads) {
+__global__ __launch_bounds__(kScanThreads) void unique_count_kernel(const unique_dev_batch batch, int src) {
     FS_WG_TRACE(3);
+    const unique_dev_job &job = batch.j[blockIdx.y];
+    if ((int)blockIdx.x >= job.stiles) return;
+    const K *__restrict__ keys = (const K *)job.keys[src];
+    const int n = job.n;
+    int32_t *__restrict__ tile_heads = job.tile_heads;
     __shared__ int sh[kScanThreads / kWave];
     K k[kScanIpt];
     bool head[kScanIpt];
@@ -243,14 +276,18 @@ __global__ __launch_bounds__(kScanThreads) void unique_count_kernel(const K *__r
 
 // ---- unique 2/2: compaction -------------------------------------------------------------------------
 template <typename K>
-__global__ __launch_bounds__(kScanThreads) void unique_compact_kernel(const K *__restrict__ keys,
-                                                                      const int32_t *__restrict__ perm, int n,
-                                                                      const int32_t *__restrict__ tile_heads,
-                                                                      int64_t *__restrict__ unique,
-                                                                      int32_t *__restrict__ seg_offsets,
-                                                                      int32_t *__restrict__ inverse,
-                                                                      int64_t *__restrict__ n_unique_dev) {
+__global__ __launch_bounds__(kScanThreads) void unique_compact_kernel(const unique_dev_batch batch, int src) {
     FS_WG_TRACE(4);
+    const unique_dev_job &job = batch.j[blockIdx.y];
+    if ((int)blockIdx.x >= job.stiles) return;
+    const K *__restrict__ keys = (const K *)job.keys[src];
+    const int32_t *__restrict__ perm = job.perm;
+    const int n = job.n;
+    const int32_t *__restrict__ tile_heads = job.tile_heads;
+    int64_t *__restrict__ unique = job.unique;
+    int32_t *__restrict__ seg_offsets = job.seg_offsets;
+    int32_t *__restrict__ inverse = job.inverse;
+    int64_t *__restrict__ n_unique_dev = job.n_unique_dev;
     __shared__ int sh[kScanThreads / kWave];
     const int p0 = blockIdx.x * kScanTile + threadIdx.x * kScanIpt;
     int pm[kScanIpt];
@@ -279,7 +316,7 @@ __global__ __launch_bounds__(kScanThreads) void unique_compact_kernel(const K *_
             if (inverse != nullptr) inverse[pm[i]] = rank - 1;
         }
     }
-    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+    if ((int)blockIdx.x == job.stiles - 1 && threadIdx.x == 0) {
         const int total = tile_base + tile_total;
         seg_offsets[total] = n;
         *n_unique_dev = total;
@@ -293,63 +330,89 @@ __global__ void unique_empty_kernel(int32_t *seg_offsets, int64_t *n_unique_dev)
 
 // ---- host side ------------------------------------------------------------------------------------------
 template <typename K>
-static int unique_impl(fs_ctx *ctx, const int64_t *ids, int n, int key_bits, int64_t num_rows, int64_t *unique,
-                       int32_t *seg_offsets, int32_t *perm, int32_t *inverse, int64_t *n_unique_dev, hipStream_t s,
-                       const fs_sort_scratch &ws) {
-    const int tiles = (int)ceil_div(n, kSortTile);
+static int unique_batch_impl(fs_ctx *ctx, const unique_dev_batch &batch, int count, int key_bits, hipStream_t s) {
+    int tiles = 0, stiles = 0;
+    for (int k = 0; k < count; ++k) {
+        tiles = batch.j[k].tiles > tiles ? batch.j[k].tiles : tiles;
+        stiles = batch.j[k].stiles > stiles ? batch.j[k].stiles : stiles;
+    }
     const int passes = (key_bits + kRadixBits - 1) / kRadixBits;
     const int bits = (key_bits + passes - 1) / passes;            // <= kRadixBits, evenly spread
-    K *kbuf[2] = {(K *)ws.keys[0], (K *)ws.keys[1]};
     int cur = 0;   // buffer holding the input of the next pass (unused for the first pass)
-    for (int p = 0; p < passes; ++p) {
-        const int shift = p * bits;
-        const bool last = (p == passes - 1);
-        K *kout = kbuf[cur ^ 1];
-        int32_t *iout = last ? perm : ws.idx[cur ^ 1];
-        if (p == 0) {
-            hipLaunchKernelGGL((radix_hist_kernel<K, true>), dim3(tiles), dim3(kSortThreads), 0, s, ids,
-                               (const K *)nullptr, n, shift, bits, num_rows, ws.tile_hist, ctx->d_flags);
-            hipLaunchKernelGGL((radix_scatter_kernel<K, true>), dim3(tiles), dim3(kSortThreads), 0, s, ids,
-                               (const K *)nullptr, (const int32_t *)nullptr, kout, iout, n, shift, bits, tiles,
-                               (const uint32_t *)ws.tile_hist);
-        } else {
-            hipLaunchKernelGGL((radix_hist_kernel<K, false>), dim3(tiles), dim3(kSortThreads), 0, s,
-                               (const int64_t *)nullptr, (const K *)kbuf[cur], n, shift, bits, num_rows,
-                               ws.tile_hist, ctx->d_flags);
-            hipLaunchKernelGGL((radix_scatter_kernel<K, false>), dim3(tiles), dim3(kSortThreads), 0, s,
-                               (const int64_t *)nullptr, (const K *)kbuf[cur], (const int32_t *)ws.idx[cur], kout,
-                               iout, n, shift, bits, tiles, (const uint32_t *)ws.tile_hist);
+    if (tiles > 0) {
+        const dim3 grid((unsigned)tiles, (unsigned)count);
+        for (int p = 0; p < passes; ++p) {
+            const int shift = p * bits;
+            const int last = (p == passes - 1) ? 1 : 0;
+            if (p == 0) {
+                hipLaunchKernelGGL((radix_hist_kernel<K, true>), grid, dim3(kSortThreads), 0, s, batch, cur, shift,
+                                   bits, ctx->d_flags);
+                hipLaunchKernelGGL((radix_scatter_kernel<K, true>), grid, dim3(kSortThreads), 0, s, batch, cur, shift,
+                                   bits, last);
+            } else {
+                hipLaunchKernelGGL((radix_hist_kernel<K, false>), grid, dim3(kSortThreads), 0, s, batch, cur, shift,
+                                   bits, ctx->d_flags);
+                hipLaunchKernelGGL((radix_scatter_kernel<K, false>), grid, dim3(kSortThreads), 0, s, batch, cur,
+                                   shift, bits, last);
+            }
+            cur ^= 1;
         }
-        cur ^= 1;
     }
-    const int stiles = (int)ceil_div(n, kScanTile);
-    hipLaunchKernelGGL((unique_count_kernel<K>), dim3(stiles), dim3(kScanThreads), 0, s, (const K *)kbuf[cur], n,
-                       ws.tile_heads);
-    hipLaunchKernelGGL((unique_compact_kernel<K>), dim3(stiles), dim3(kScanThreads), 0, s, (const K *)kbuf[cur],
-                       (const int32_t *)perm, n, (const int32_t *)ws.tile_heads, unique, seg_offsets, inverse,
-                       n_unique_dev);
+    const dim3 sgrid((unsigned)stiles, (unsigned)count);
+    hipLaunchKernelGGL((unique_count_kernel<K>), sgrid, dim3(kScanThreads), 0, s, batch, cur);
+    hipLaunchKernelGGL((unique_compact_kernel<K>), sgrid, dim3(kScanThreads), 0, s, batch, cur);
     FS_LAUNCH_CHECK(ctx, "unique kernels");
     return FS_OK;
+}
+
+int launch_unique_batch(fs_ctx *ctx, int count, const fs_unique_job *jobs, hipStream_t s, int set0) {
+    if (count < 1 || count > kMaxBatch || set0 < 0 || set0 + count > kSortSets)
+        return set_err(ctx, FS_EINVAL, "unique: batch size");
+    if (count == 1 && jobs[0].n == 0) {
+        hipLaunchKernelGGL(unique_empty_kernel, dim3(1), dim3(1), 0, s, jobs[0].seg_offsets, jobs[0].n_unique_dev);
+        FS_LAUNCH_CHECK(ctx, "unique_empty_kernel");
+        return FS_OK;
+    }
+    // one sort geometry for the whole batch: the widest key decides (sorting zero bits is harmless)
+    int key_bits = 1;
+    unique_dev_batch batch;
+    memset(&batch, 0, sizeof(batch));
+    for (int k = 0; k < count; ++k) {
+        const fs_unique_job &in = jobs[k];
+        int kb = 63;
+        if (in.num_rows > 0) {
+            kb = 1;
+            while (kb < 63 && (1ll << kb) < in.num_rows) ++kb;
+        }
+        key_bits = kb > key_bits ? kb : key_bits;
+        const fs_sort_scratch &ws = ctx->sort[set0 + k];
+        unique_dev_job &j = batch.j[k];
+        j.ids = in.ids;
+        j.n = (int)in.n;
+        j.tiles = (int)ceil_div(in.n, kSortTile);
+        j.stiles = in.n > 0 ? (int)ceil_div(in.n, kScanTile) : 1;
+        j.num_rows = in.num_rows;
+        j.keys[0] = ws.keys[0];
+        j.keys[1] = ws.keys[1];
+        j.idx[0] = ws.idx[0];
+        j.idx[1] = ws.idx[1];
+        j.tile_hist = ws.tile_hist;
+        j.tile_heads = ws.tile_heads;
+        j.unique = in.unique;
+        j.seg_offsets = in.seg_offsets;
+        j.perm = in.perm;
+        j.inverse = in.inverse;
+        j.n_unique_dev = in.n_unique_dev;
+    }
+    if (key_bits <= 32) return unique_batch_impl<uint32_t>(ctx, batch, count, key_bits, s);
+    return unique_batch_impl<uint64_t>(ctx, batch, count, key_bits, s);
 }
 
 int launch_unique(fs_ctx *ctx, const int64_t *ids, int64_t n, int64_t num_rows, int64_t *unique,
                   int32_t *seg_offsets, int32_t *perm, int32_t *inverse, int64_t *n_unique_dev, hipStream_t s,
                   int set) {
-    if (n == 0) {
-        hipLaunchKernelGGL(unique_empty_kernel, dim3(1), dim3(1), 0, s, seg_offsets, n_unique_dev);
-        FS_LAUNCH_CHECK(ctx, "unique_empty_kernel");
-        return FS_OK;
-    }
-    int key_bits = 63;
-    if (num_rows > 0) {
-        key_bits = 1;
-        while (key_bits < 63 && (1ll << key_bits) < num_rows) ++key_bits;
-    }
-    if (key_bits <= 32)
-        return unique_impl<uint32_t>(ctx, ids, (int)n, key_bits, num_rows, unique, seg_offsets, perm, inverse,
-                                     n_unique_dev, s, ctx->sort[set]);
-    return unique_impl<uint64_t>(ctx, ids, (int)n, key_bits, num_rows, unique, seg_offsets, perm, inverse,
-                                 n_unique_dev, s, ctx->sort[set]);
+    const fs_unique_job job = {ids, n, num_rows, unique, seg_offsets, perm, inverse, n_unique_dev};
+    return launch_unique_batch(ctx, 1, &job, s, set);
 }
 
 FS_TRACE_SETTER(unique)

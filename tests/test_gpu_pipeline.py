@@ -33,11 +33,20 @@ def run_pipelined(ctx, table, state, its, lr, eps, ahead=False, sync_each=True):
     iteration that gathers it (five layout buffers in rotation; "last_step": ordered after the start
     of the previous pipelined call instead of the stream's current position, six layout buffers).
     "index" / "index_last_step": the whole index half of every iteration with fs_step_forward_ahead,
-    two iterations ahead (six layouts, five split bundles).  sync_each=False: no wait between the calls."""
+    two iterations ahead (six layouts, five split bundles).
+    "batchK" / "batchK_last_step": the index halves of K consecutive iterations in shared launches
+    (fs_step_forward_ahead_batch), issued D = K + 1 iterations before the first of them is stepped
+    (K + D + 3 layouts, K + D + 2 split bundles).
+    sync_each=False: no wait between the calls."""
+    batch = int(ahead[5]) if isinstance(ahead, str) and ahead.startswith("batch") else 0
     index_ahead = ahead in ("index", "index_last_step")
-    last_step = ahead in ("last_step", "index_last_step")
-    L = (6 if (last_step or index_ahead) else 5) if ahead else 3
-    P = 5 if index_ahead else 3
+    last_step = isinstance(ahead, str) and ahead.endswith("last_step")
+    D = batch + 1
+    if batch:
+        L, P = batch + D + 3, batch + D + 2
+    else:
+        L = (6 if (last_step or index_ahead) else 5) if ahead else 3
+        P = 5 if index_ahead else 3
     d_table, d_state = table_to_dev(table), dev(state)
     num_rows, dim = table.shape
     T = len(its)
@@ -64,12 +73,16 @@ def run_pipelined(ctx, table, state, its, lr, eps, ahead=False, sync_each=True):
         return fs.FS_STREAM_LAST_STEP if (last_step and stepped[0]) else None
 
     def dedup_ahead(t):
-        if ahead and not index_ahead and t < T:
+        if ahead and not index_ahead and not batch and t < T:
             fs.fs_unique_ids_ahead(ctx, d_vals[t], num_rows, layouts[t % L], stream=order())
 
     def index_half_ahead(t):
         if index_ahead and t < T:
             fs.fs_step_forward_ahead(ctx, all_args[t], stream=order())
+
+    def index_batch_ahead(first):
+        if batch and first % batch == 0 and 0 <= first < T:
+            fs.fs_step_forward_ahead_batch(ctx, all_args[first:min(first + batch, T)], stream=order())
 
     fs.fs_unique_ids(ctx, d_vals[0], num_rows, out=layouts[0])
     all_args = [args_for(t) for t in range(T)]
@@ -77,6 +90,9 @@ def run_pipelined(ctx, table, state, its, lr, eps, ahead=False, sync_each=True):
     if index_ahead:
         index_half_ahead(0)                                       # dedup of batch 1, split and class order of 0
         index_half_ahead(1)
+    elif batch:
+        for first in range(0, D):
+            index_batch_ahead(first)
     else:
         fs.fs_step_forward(ctx, all_args[0])                      # primes the pipeline: layout 1, split 0
     dedup_ahead(2)
@@ -85,6 +101,7 @@ def run_pipelined(ctx, table, state, its, lr, eps, ahead=False, sync_each=True):
         nxt = all_args[t + 1] if t + 1 < T else None
         dedup_ahead(t + 3)
         index_half_ahead(t + 2)
+        index_batch_ahead(t + D)
         fs.fs_prioritized_step_pipelined(ctx, all_args[t], nxt)
         stepped[0] = True
         if not sync_each:
@@ -125,7 +142,9 @@ def test_pipelined_steps_match_sequential_calls_bitwise(dtype, dim):
                                        (True, False, False), (False, True, False), ("last_step", False, True),
                                        ("last_step", True, False), ("index", False, True), ("index", True, True),
                                        ("index_last_step", False, True), ("index_last_step", False, False),
-                                       ("index", True, False)):
+                                       ("index", True, False), ("batch2", False, True), ("batch2_last_step", False, True),
+                                       ("batch3_last_step", False, True), ("batch4_last_step", False, False),
+                                       ("batch2", True, True), ("batch4", True, False)):
         ctx.lib.fs_ctx_set_threaded_enqueue(ctx.handle, 1 if threaded else 0)
         ta, sa, oa = run_pipelined(ctx, table, state, its, 0.01, 1e-8, ahead=ahead, sync_each=sync_each)
         what = f"ahead={ahead} sync_each={sync_each} threaded={threaded}"
