@@ -253,15 +253,16 @@ int fs_unique_ids_ahead(fs_ctx *ctx, const int64_t *ids, int64_t n, int64_t num_
                         int64_t *n_unique_dev, fs_stream stream);
 
 /* The whole index half of an iteration ahead of time - fs_step_forward on one of the context's
- * two index streams (used in turn), ordered like fs_unique_ids_ahead (`stream`, or
- * FS_STREAM_LAST_STEP).  It dedups args->values_t1 (unless fs_unique_ids_ahead already did), waits
- * for the layout of batch t if that is still in the making on the other index stream (the index
- * half of t-1 produces it), splits, and lays batch t out in class order with its records.
- * fs_prioritized_step_pipelined then finds the index half of its `next` (or of its `cur`, on the
- * first call) done and only waits for it; its side stream is left with the deferred pass alone.
- * Issued for iteration t+2 before the pipelined call of iteration t, the chain of a dozen small
- * launches has two iterations' time to finish.  Buffers in rotation for that pattern: six
- * layouts and five split/class bundles with FS_STREAM_LAST_STEP, five and four with `stream`. */
+ * index streams, ordered like fs_unique_ids_ahead (`stream`, or FS_STREAM_LAST_STEP).  It dedups
+ * args->values_t1 (unless fs_unique_ids_ahead already did), waits for the layout of batch t if that
+ * is still in the making (the index half of t-1 produces it), splits, and lays batch t out in class
+ * order with its records.  fs_prioritized_step_pipelined then finds the index half of its `next`
+ * (or of its `cur`, on the first call) done and only waits for it; its side stream is left with
+ * the deferred pass alone.  Issued for iteration t+2 before the pipelined call of iteration t,
+ * the chain of a dozen small launches has two iterations' time to finish.  Buffers in rotation
+ * for that pattern: six layouts and five split/class bundles with FS_STREAM_LAST_STEP, five and
+ * four with `stream`.  A chain of launches per iteration costs the bandwidth-bound passes more
+ * than chains shared by several iterations: prefer fs_step_forward_ahead_batch. */
 int fs_step_forward_ahead(fs_ctx *ctx, const fs_step_args *args, fs_stream stream);
 
 /* The index halves of `count` (1..FS_MAX_AHEAD_BATCH) argument records ahead of time in SHARED
