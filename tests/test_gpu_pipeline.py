@@ -5,8 +5,9 @@ import numpy as np
 import pytest
 import torch
 
+import oracle as O
 import paper_2604_24073_amd as fs
-from helpers import dev, table_to_dev, table_to_host
+from helpers import assert_rows_close, dev, table_to_dev, table_to_host
 from test_gpu_parity import compare_runs, rand_table, run_steps_gpu, run_steps_oracle, zipf_ids
 
 pytestmark = pytest.mark.gpu
@@ -154,6 +155,66 @@ def test_pipelined_steps_match_sequential_calls_bitwise(dtype, dim):
             assert a["reduced"].tobytes() == b["reduced"].tobytes(), what
             if "emb_next" in a:
                 assert a["emb_next"].tobytes() == b["emb_next"].tobytes(), what
+    ctx.close()
+
+
+def test_index_halves_of_different_tables_share_their_launches():
+    """One fs_step_forward_ahead_batch call for records of four different tables (rows, dims, dtypes, batch sizes
+    all different, one of them without a lookahead batch); each table's step then only waits for its part.
+    Everything bit for bit as with one self-contained step per table."""
+    rng = np.random.default_rng(77)
+    specs = [(30000, 128, "f32", 5000, 4000), (700, 64, "bf16", 9000, 9500), (100000, 32, "f32", 300, 0),
+             (5000, 256, "f32", 1, 7)]
+    ctx = fs.Context(max_ids=10000, max_dim=256)
+    tabs = []
+    for rows, dim, dtype, n, n1 in specs:
+        t = It()
+        t.table, t.state = rand_table(rng, rows, dim, dtype), (rng.random(rows) * 0.1).astype(np.float32)
+        t.rows, t.dim, t.dtype = rows, dim, dtype
+        t.ids = zipf_ids(rng, n, rows, a=1.1)
+        t.ids1 = zipf_ids(rng, n1, rows, a=1.1) if n1 else None
+        t.offs1 = np.array([0, n1 // 3, n1], dtype=np.int64) if n1 else None
+        t.grads = rng.standard_normal((n, dim)).astype(np.float32)
+        tabs.append(t)
+
+    def run(batched):
+        outs = []
+        bufs = []
+        for t in tabs:
+            d_table, d_state = table_to_dev(t.table), dev(t.state)
+            lay = fs.fs_unique_ids(ctx, dev(t.ids), t.rows)
+            n1 = 0 if t.ids1 is None else len(t.ids1)
+            lay1 = fs.alloc_layout(n1, "cuda") if n1 else None
+            sp = fs.alloc_split(len(t.ids), n1, "cuda")
+            emb = torch.empty((n1, t.dim), dtype=d_table.dtype, device="cuda") if n1 else None
+            # the record holds plain pointers: the inputs stay alive (and in place) until everything has run
+            keep = (dev(t.grads), dev(t.ids1) if n1 else None, dev(t.offs1) if n1 else None)
+            args = fs.make_step_args(d_table, d_state, 0.02, 1e-8, lay, keep[0], keep[1], keep[2], lay1, sp, None, emb)
+            bufs.append((d_table, d_state, lay, lay1, sp, emb, args, keep))
+        if batched:
+            fs.fs_step_forward_ahead_batch(ctx, [b[6] for b in bufs])
+        for b in bufs:
+            fs.fs_prioritized_step(ctx, b[6])
+        assert fs.fs_check_async(ctx) == fs.FS_OK, ctx.last_error()
+        for d_table, d_state, lay, lay1, sp, emb, args, _ in bufs:
+            view = torch.int16 if d_table.dtype == torch.bfloat16 else torch.int32
+            outs.append((d_table.view(view).cpu().numpy(), d_state.cpu().numpy(), sp["counts"].cpu().numpy(),
+                         None if emb is None else emb.view(view).cpu().numpy(),
+                         None if lay1 is None else lay1["unique"][:int(lay1["n_unique"].item())].cpu().numpy()))
+        return outs
+
+    plain, shared = run(False), run(True)
+    for a, b in zip(plain, shared):
+        for x, y in zip(a, b):
+            assert (x is None and y is None) or x.tobytes() == y.tobytes()
+    # and the plain run is right: final rows of the first table against the oracle
+    t = tabs[0]
+    t_ref, s_ref = t.table.copy(), t.state.copy()
+    O.step(t_ref, s_ref, O.unique_ids(t.ids, t.rows), t.grads, t.ids1, t.offs1, 0.02, 1e-8)
+    assert_rows_close(plain[0][0].view(np.float32).reshape(t.table.shape), t_ref, "rows of table 0")
+    with pytest.raises(fs.FreeScaleError) as e:                     # more records than a batch takes
+        fs.fs_step_forward_ahead_batch(ctx, [fs.fs_step_args()] * (fs.FS_MAX_AHEAD_BATCH + 1))
+    assert e.value.code == fs.FS_EINVAL
     ctx.close()
 
 
