@@ -219,13 +219,6 @@ int launch_reduce_update(fs_ctx *, int cls, const float *grads, int64_t n, int32
                          const int32_t *cstart, const int64_t *u_t, void *table, int dt, float *state,
                          int64_t num_rows, float lr, float eps, float *reduced, hipStream_t s,
                          const int32_t *short_rec, const int64_t *n_rows_dev);
-// the deferred pass (class 1) of iteration t and the gather of the lookahead rows in one launch
-int launch_deferred_gather(fs_ctx *, const float *grads, int64_t n, int32_t dim, const int32_t *cperm,
-                           const int32_t *cslot, const int32_t *class_pos, const int32_t *seg_offsets,
-                           const int32_t *cstart, const int64_t *u_t, void *table, int dt, float *state,
-                           int64_t num_rows, float lr, float eps, float *reduced, hipStream_t s,
-                           const int32_t *short_rec, const int64_t *n_rows_dev, const int64_t *values,
-                           const int64_t *offsets, int64_t batch, int64_t n_values, void *out);
 // `timing`: optional event pair recorded around the main (chunk) kernel only
 int launch_reduce(fs_ctx *, const float *grads, int64_t n, int32_t dim, const int32_t *perm,
                   const int32_t *seg_offsets, const int64_t *n_unique_dev, float *reduced, hipStream_t s,

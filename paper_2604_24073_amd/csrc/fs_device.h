@@ -53,65 +53,6 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
 }
 
 
-// ---- jagged row gather, the part of a launch played by workgroup `block` of `blocks` (256 threads each) ----
-// A row is `granules` 16-byte pieces; LPR = next power of two >= granules lanes cover one row, so one
-// wavefront instruction moves 64/LPR rows.  Work is flat over the n occurrences (grid-stride), never one
-// workgroup per user.  The offsets check rides along.
-#ifndef FS_GATHER_UNR
-#define FS_GATHER_UNR 4
-#endif
-#ifndef FS_GATHER_MAX_BLOCKS
-#define FS_GATHER_MAX_BLOCKS 1024
-#endif
-template <int LPR, int UNR>
-__device__ __forceinline__ void gather_rows_body(const int block, const int blocks, const u32x4 *__restrict__ table,
-                                                 int64_t num_rows, int granules, const int64_t *__restrict__ values,
-                                                 const int64_t *__restrict__ offsets, int64_t batch, int64_t n,
-                                                 u32x4 *__restrict__ out, int *__restrict__ flags) {
-    constexpr int GPW = kWave / LPR;                  // rows per wavefront instruction
-    constexpr int ROWS_PER_WAVE = GPW * UNR;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int grp = lane / LPR;
-    const int lig = lane % LPR;
-    const int64_t wave = (int64_t)block * (blockDim.x / kWave) + (threadIdx.x / kWave);
-    const int64_t waves = (int64_t)blocks * (blockDim.x / kWave);
-
-    // offsets validation rides along (grid-stride over the batch; almost free)
-    if (offsets != nullptr) {
-        const int64_t gtid = (int64_t)block * blockDim.x + threadIdx.x;
-        const int64_t gsz = (int64_t)blocks * blockDim.x;
-        bool bad = false;
-        for (int64_t b = gtid; b < batch; b += gsz) bad |= offsets[b + 1] < offsets[b];
-        if (gtid == 0) bad |= (offsets[0] != 0) || (offsets[batch] != n);
-        if (bad) atomicOr(flags, kFlagOffsets);
-    }
-    bool oob = false;
-    for (int64_t row0 = wave * ROWS_PER_WAVE; row0 < n; row0 += waves * ROWS_PER_WAVE) {
-        int64_t id[UNR];
-        bool live[UNR];
-#pragma unroll
-        for (int u = 0; u < UNR; ++u) {
-            const int64_t j = row0 + u * GPW + grp;
-            live[u] = (j < n) && (lig < granules);
-            id[u] = live[u] ? values[j] : 0;
-        }
-        u32x4 v[UNR];
-#pragma unroll
-        for (int u = 0; u < UNR; ++u) {
-            const bool in = (id[u] >= 0) && (id[u] < num_rows);
-            oob |= live[u] && !in;
-            v[u] = u32x4{0u, 0u, 0u, 0u};
-            if (live[u] && in) v[u] = table[id[u] * granules + lig];
-        }
-#pragma unroll
-        for (int u = 0; u < UNR; ++u) {
-            const int64_t j = row0 + u * GPW + grp;
-            if (live[u]) __builtin_nontemporal_store(v[u], &out[j * granules + lig]);
-        }
-    }
-    if (oob) atomicOr(flags, kFlagRowRange);
-}
-
 // ---- optional workgroup trace (diagnostic builds with -DFS_TRACE only) ------------------------------
 // Every workgroup of a traced kernel appends {kind, workgroups of the launch << 32 | linear workgroup id, first and last reading
 // of the 100 MHz wall clock by its thread 0} to a buffer the host sets with fs_debug_trace.  The buffer

@@ -581,52 +581,12 @@ __global__ __launch_bounds__(kFusedWaves *kWave) void class_pass_kernel(
                                        n_rows_dev, (int64_t)n, table, state, num_rows, gvec, lr, eps, reduced, flags);
 }
 
-// The gather of the lookahead rows as the first workgroups of a deferred pass: the rows the deferred pass
-// writes (ex_t = U_t \ U_t1) are by construction none of the rows the gather reads (U_t1), so the two share
-// one launch - and the caller's stream, with no second stream to order against it.
-struct gather_part {
-    const u32x4 *table;
-    const int64_t *values, *offsets;
-    int64_t batch, n;
-    u32x4 *out;
-    int granules, blocks;
-};
-
-template <bool BF16, int LPR, int UNR, int CHUNK, int SU>
-__global__ __launch_bounds__(kFusedWaves *kWave) void class_pass_gather_kernel(
-    const f32x4 *__restrict__ grads, int n, int long_blocks, const int32_t *__restrict__ cperm,
-    const int32_t *__restrict__ cslot, const int32_t *__restrict__ class_pos, int cls,
-    const int32_t *__restrict__ seg_offsets, const int32_t *__restrict__ cstart, const int64_t *__restrict__ u_t,
-    const int32_t *__restrict__ recs, const int64_t *__restrict__ n_rows_dev, void *table, float *state,
-    int64_t num_rows, int gvec, float lr, float eps, f32x4 *reduced, double *part_head, double *part_last,
-    int *cnt_seg, int *cnt_sup, int *flags, const gather_part gp) {
-    constexpr int GL = BF16 ? (LPR > 1 ? LPR / 2 : 1) : LPR;      // lanes per table row (half as wide in bf16)
-    FS_WG_TRACE(11);
-    const int b = (int)blockIdx.x - gp.blocks;
-    if (b < 0) {
-        gather_rows_body<GL, FS_GATHER_UNR>((int)blockIdx.x, gp.blocks, gp.table, num_rows, gp.granules, gp.values,
-                                            gp.offsets, gp.batch, gp.n, gp.out, flags);
-        return;
-    }
-    if (b < long_blocks)
-        long_segments_body<BF16, LPR, UNR, CHUNK>(b, grads, cperm, cslot, class_pos, cls, n, seg_offsets, cstart, u_t,
-                                                  table, state, num_rows, gvec, lr, eps, reduced, part_head,
-                                                  part_last, cnt_seg, cnt_sup, flags);
-    else
-        short_rows_body<BF16, LPR, SU>(b - long_blocks, (int)gridDim.x - gp.blocks - long_blocks, grads, n, recs,
-                                       n_rows_dev, (int64_t)n, table, state, num_rows, gvec, lr, eps, reduced, flags);
-}
-
-#ifndef FS_FUSED_GATHER_BLOCKS
-#define FS_FUSED_GATHER_BLOCKS FS_GATHER_MAX_BLOCKS
-#endif
-
 template <bool BF16, int LPR, int CHUNK>
 static void fused_launch(fs_ctx *ctx, int cls, const float *grads, int n, int gvec, const int32_t *cperm,
                          const int32_t *cslot, const int32_t *class_pos, const int32_t *seg_offsets,
                          const int32_t *cstart, const int64_t *u_t, void *table, float *state, int64_t num_rows,
                          float lr, float eps, float *reduced, hipStream_t s, const int32_t *short_rec,
-                         const int64_t *n_rows_dev, const gather_part *gather) {
+                         const int64_t *n_rows_dev) {
     constexpr int GPW = kWave / LPR;
     constexpr int SU = FS_SHORT_UNR;
     constexpr int UNR = (CHUNK / GPW) < FS_FUSED_UNR ? ((CHUNK / GPW) < 1 ? 1 : (CHUNK / GPW)) : FS_FUSED_UNR;
@@ -636,20 +596,6 @@ static void fused_launch(fs_ctx *ctx, int cls, const float *grads, int n, int gv
     const int long_blocks = (int)ceil_div(ceil_div(n, CH), kFusedWaves);
     int64_t short_blocks = ceil_div(n, (int64_t)GPW * SU * kFusedWaves);
     if (short_blocks > FS_SHORT_MAX_BLOCKS) short_blocks = FS_SHORT_MAX_BLOCKS;   // grid-stride beyond this
-    if (gather != nullptr) {
-        constexpr int GL = BF16 ? (LPR > 1 ? LPR / 2 : 1) : LPR;
-        gather_part gp = *gather;
-        int64_t gblocks = ceil_div(gp.n, (int64_t)(kWave / GL) * FS_GATHER_UNR * kFusedWaves);
-        if (gblocks > FS_FUSED_GATHER_BLOCKS) gblocks = FS_FUSED_GATHER_BLOCKS;
-        gp.blocks = (int)gblocks;
-        hipLaunchKernelGGL((class_pass_gather_kernel<BF16, LPR, UNR, CH, SU>),
-                           dim3((unsigned)(gp.blocks + long_blocks + short_blocks)), dim3(kFusedWaves * kWave), 0, s,
-                           (const f32x4 *)grads, n, long_blocks, cperm, cslot, class_pos, cls, seg_offsets, cstart, u_t,
-                           short_rec, n_rows_dev, table, state, num_rows, gvec, lr, eps, (f32x4 *)reduced,
-                           ctx->fpart_head[cls], ctx->fpart_last[cls], ctx->fcounters[cls], ctx->fcounters_sup[cls],
-                           ctx->d_flags, gp);
-        return;
-    }
     hipLaunchKernelGGL((class_pass_kernel<BF16, LPR, UNR, CH, SU>), dim3((unsigned)(long_blocks + short_blocks)),
                        dim3(kFusedWaves * kWave), 0, s, (const f32x4 *)grads, n, long_blocks, cperm, cslot, class_pos,
                        cls, seg_offsets, cstart, u_t, short_rec, n_rows_dev, table, state, num_rows, gvec, lr, eps,
@@ -657,12 +603,12 @@ static void fused_launch(fs_ctx *ctx, int cls, const float *grads, int n, int gv
                        ctx->fcounters_sup[cls], ctx->d_flags);
 }
 
-// `gather` (only with cls == 1): the jagged gather of the lookahead rows rides in the same launch
-static int launch_class_pass(fs_ctx *ctx, int cls, const float *grads, int64_t n, int32_t dim, const int32_t *cperm,
-                             const int32_t *cslot, const int32_t *class_pos, const int32_t *seg_offsets,
-                             const int32_t *cstart, const int64_t *u_t, void *table, int dt, float *state,
-                             int64_t num_rows, float lr, float eps, float *reduced, hipStream_t s,
-                             const int32_t *short_rec, const int64_t *n_rows_dev, const gather_part *gather) {
+int launch_reduce_update(fs_ctx *ctx, int cls, const float *grads, int64_t n, int32_t dim, const int32_t *cperm,
+                         const int32_t *cslot, const int32_t *class_pos, const int32_t *seg_offsets,
+                         const int32_t *cstart, const int64_t *u_t, void *table, int dt, float *state,
+                         int64_t num_rows, float lr, float eps, float *reduced, hipStream_t s,
+                         const int32_t *short_rec, const int64_t *n_rows_dev) {
+    if (n == 0) return FS_OK;
     const int gvec = dim / 4;
     const bool bf = dt == FS_BF16;
 #define FS_ARGS ctx, cls, grads, (int)n, gvec, cperm, cslot, class_pos, seg_offsets, cstart, u_t, table, state, num_rows, \
@@ -670,11 +616,11 @@ static int launch_class_pass(fs_ctx *ctx, int cls, const float *grads, int64_t n
 #define FS_CASE(L)                                                                   \
     case L:                                                                          \
         if (cls == 0) {                                                              \
-            if (bf) fused_launch<true, L, FS_FUSED_CHUNK_CO>(FS_ARGS, nullptr);      \
-            else fused_launch<false, L, FS_FUSED_CHUNK_CO>(FS_ARGS, nullptr);        \
+            if (bf) fused_launch<true, L, FS_FUSED_CHUNK_CO>(FS_ARGS);               \
+            else fused_launch<false, L, FS_FUSED_CHUNK_CO>(FS_ARGS);                 \
         } else {                                                                     \
-            if (bf) fused_launch<true, L, FS_FUSED_CHUNK_EX>(FS_ARGS, gather);       \
-            else fused_launch<false, L, FS_FUSED_CHUNK_EX>(FS_ARGS, gather);         \
+            if (bf) fused_launch<true, L, FS_FUSED_CHUNK_EX>(FS_ARGS);               \
+            else fused_launch<false, L, FS_FUSED_CHUNK_EX>(FS_ARGS);                 \
         }                                                                            \
         break;
     switch (lanes_per_row(gvec)) {
@@ -685,32 +631,6 @@ static int launch_class_pass(fs_ctx *ctx, int cls, const float *grads, int64_t n
 #undef FS_ARGS
     FS_LAUNCH_CHECK(ctx, "class_pass_kernel");
     return FS_OK;
-}
-
-int launch_reduce_update(fs_ctx *ctx, int cls, const float *grads, int64_t n, int32_t dim, const int32_t *cperm,
-                         const int32_t *cslot, const int32_t *class_pos, const int32_t *seg_offsets,
-                         const int32_t *cstart, const int64_t *u_t, void *table, int dt, float *state,
-                         int64_t num_rows, float lr, float eps, float *reduced, hipStream_t s,
-                         const int32_t *short_rec, const int64_t *n_rows_dev) {
-    if (n == 0) return FS_OK;
-    return launch_class_pass(ctx, cls, grads, n, dim, cperm, cslot, class_pos, seg_offsets, cstart, u_t, table, dt,
-                             state, num_rows, lr, eps, reduced, s, short_rec, n_rows_dev, nullptr);
-}
-
-int launch_deferred_gather(fs_ctx *ctx, const float *grads, int64_t n, int32_t dim, const int32_t *cperm,
-                           const int32_t *cslot, const int32_t *class_pos, const int32_t *seg_offsets,
-                           const int32_t *cstart, const int64_t *u_t, void *table, int dt, float *state,
-                           int64_t num_rows, float lr, float eps, float *reduced, hipStream_t s,
-                           const int32_t *short_rec, const int64_t *n_rows_dev, const int64_t *values,
-                           const int64_t *offsets, int64_t batch, int64_t n_values, void *out) {
-    const int row_bytes = dim * (dt == FS_F32 ? 4 : 2);
-    if (n == 0) return launch_gather(ctx, table, num_rows, row_bytes, values, offsets, batch, n_values, out, s);
-    if (n_values == 0)
-        return launch_reduce_update(ctx, 1, grads, n, dim, cperm, cslot, class_pos, seg_offsets, cstart, u_t, table, dt,
-                                    state, num_rows, lr, eps, reduced, s, short_rec, n_rows_dev);
-    const gather_part gp = {(const u32x4 *)table, values, offsets, batch, n_values, (u32x4 *)out, row_bytes / 16, 0};
-    return launch_class_pass(ctx, 1, grads, n, dim, cperm, cslot, class_pos, seg_offsets, cstart, u_t, table, dt, state,
-                             num_rows, lr, eps, reduced, s, short_rec, n_rows_dev, &gp);
 }
 
 FS_TRACE_SETTER(fused)

@@ -8,6 +8,13 @@
 #include "fs_common.h"
 #include "fs_device.h"
 
+#ifndef FS_GATHER_UNR
+#define FS_GATHER_UNR 4
+#endif
+#ifndef FS_GATHER_MAX_BLOCKS
+#define FS_GATHER_MAX_BLOCKS 1024
+#endif
+
 namespace fs {
 
 template <int LPR, int UNR>
@@ -16,8 +23,48 @@ __global__ __launch_bounds__(256) void gather_kernel(const u32x4 *__restrict__ t
                                                      const int64_t *__restrict__ offsets, int64_t batch, int64_t n,
                                                      u32x4 *__restrict__ out, int *__restrict__ flags) {
     FS_WG_TRACE(10);
-    gather_rows_body<LPR, UNR>((int)blockIdx.x, (int)gridDim.x, table, num_rows, granules, values, offsets, batch, n,
-                               out, flags);
+    constexpr int GPW = kWave / LPR;                  // rows per wavefront instruction
+    constexpr int ROWS_PER_WAVE = GPW * UNR;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int grp = lane / LPR;
+    const int lig = lane % LPR;
+    const int64_t wave = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    const int64_t waves = (int64_t)gridDim.x * (blockDim.x / kWave);
+
+    // offsets validation rides along (grid-stride over the batch; almost free)
+    if (offsets != nullptr) {
+        const int64_t gtid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+        const int64_t gsz = (int64_t)gridDim.x * blockDim.x;
+        bool bad = false;
+        for (int64_t b = gtid; b < batch; b += gsz) bad |= offsets[b + 1] < offsets[b];
+        if (gtid == 0) bad |= (offsets[0] != 0) || (offsets[batch] != n);
+        if (bad) atomicOr(flags, kFlagOffsets);
+    }
+    bool oob = false;
+    for (int64_t row0 = wave * ROWS_PER_WAVE; row0 < n; row0 += waves * ROWS_PER_WAVE) {
+        int64_t id[UNR];
+        bool live[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int64_t j = row0 + u * GPW + grp;
+            live[u] = (j < n) && (lig < granules);
+            id[u] = live[u] ? values[j] : 0;
+        }
+        u32x4 v[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const bool in = (id[u] >= 0) && (id[u] < num_rows);
+            oob |= live[u] && !in;
+            v[u] = u32x4{0u, 0u, 0u, 0u};
+            if (live[u] && in) v[u] = table[id[u] * granules + lig];
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int64_t j = row0 + u * GPW + grp;
+            if (live[u]) __builtin_nontemporal_store(v[u], &out[j * granules + lig]);
+        }
+    }
+    if (oob) atomicOr(flags, kFlagRowRange);
 }
 
 template <int LPR>
