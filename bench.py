@@ -35,9 +35,11 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 # the same counter reads for a plain copy of known size) in separate counter runs of this file on
 # the default workload; the runs and their figures are summarised under profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    ("configs[1]", "class_pass_kernel (priority pass)"): 156.5e6,
+    ("configs[1]", "class_pass_kernel (priority pass)"): 156.6e6,
     ("configs[1]", "class_pass_kernel (deferred pass)"): 109.5e6,
-    ("configs[1]", "gather_kernel"): 202.3e6,
+    ("configs[1]", "gather_kernel"): 202.1e6,
+    # the eleven index kernels of one iteration (half of what a chain for two iterations moves)
+    ("configs[1]", "index kernels"): 56.2e6,
 }
 
 
@@ -489,6 +491,14 @@ def main() -> int:
                     "all_kernels": {nm: {"avg_launch_us": m * 1e3, "algorithmic_bytes": nb,
                                          "GBps": nb / (m * 1e-3) / 1e9} for nm, (m, nb, _) in per_kernel.items()}}
 
+    # what the counters say the whole step moves (all kernels of one iteration), where they were read
+    step_traffic = None
+    if pipelined and ahead:
+        parts = [MEASURED_TRAFFIC_BYTES.get((f"configs[{cfg.index}]", k)) for k in
+                 ("class_pass_kernel (priority pass)", "class_pass_kernel (deferred pass)", "gather_kernel",
+                  "index kernels")]
+        step_traffic = sum(parts) if all(parts) else None
+
     # ---- the same kernels alone on the chip: each operation launched 20 times back to back on one
     # stream with nothing beside it (after the timed region; the table keeps being updated, which
     # does not change what the kernels move)
@@ -542,6 +552,9 @@ def main() -> int:
         "host_phase_us_per_step": host_phases,
         "step_algorithmic_bytes": step_bytes, "step_algorithmic_GBps": step_gbps,
         "step_frac_of_hbm_peak": step_gbps / HBM_PEAK_GBPS,
+        "step_measured_traffic_bytes": step_traffic,
+        "step_measured_traffic_frac_of_hbm_peak": (step_traffic / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS
+                                                   if step_traffic else None),
         "kernel_avg_us": {k: (v * 1e3 if v is not None else None) for k, v in kernel_ms.items()},
         "roofline": roofline,
         "isolated_kernels": isolated,
