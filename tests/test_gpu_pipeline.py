@@ -218,6 +218,48 @@ def test_index_halves_of_different_tables_share_their_launches():
     ctx.close()
 
 
+def test_batch_of_index_halves_with_empty_records():
+    """A batch whose records are degenerate in every way a record can be: no gradients (empty iteration) but a
+    lookahead batch, gradients but no lookahead, both empty, and an ordinary one: counts, class extents and the
+    layouts of the lookahead batches must come out as from the plain calls."""
+    rng = np.random.default_rng(5)
+    rows, dim = 900, 32
+    ctx = fs.Context(max_ids=4000, max_dim=dim)
+    d_table, d_state = table_to_dev(rand_table(rng, rows, dim, "f32")), torch.zeros(rows, device="cuda")
+    cases = [(0, 700), (600, 0), (0, 0), (3000, 2500)]
+    keep, recs, want = [], [], []
+    for n, n1 in cases:
+        ids = zipf_ids(rng, n, rows, a=1.1) if n else np.empty(0, np.int64)
+        ids1 = zipf_ids(rng, n1, rows, a=1.1) if n1 else None
+        lay = fs.fs_unique_ids(ctx, dev(ids), rows) if n else fs.alloc_layout(0, "cuda")
+        lay["n"] = n
+        lay1 = fs.alloc_layout(n1, "cuda") if n1 else None
+        sp = fs.alloc_split(max(n, 1), max(n1, 1), "cuda")
+        sp["counts"].fill_(-7); sp["class_pos"].fill_(-7)
+        bufs = (dev(rng.standard_normal((max(n, 1), dim)).astype(np.float32)), dev(ids1) if n1 else None,
+                dev(np.array([0, n1], dtype=np.int64)) if n1 else None,
+                torch.empty((n1, dim), device="cuda") if n1 else None)
+        keep.append((lay, lay1, sp, bufs))
+        recs.append(fs.make_step_args(d_table, d_state, 0.01, 1e-8, lay, bufs[0], bufs[1], bufs[2], lay1, sp, None, bufs[3]))
+        lay_o = O.unique_ids(ids, rows)
+        lay1_o = O.unique_ids(ids1, rows) if n1 else None
+        sp_o = O.collision_split(lay_o["unique"], lay1_o["unique"] if n1 else np.empty(0, np.int64))
+        want.append((lay1_o, sp_o))
+    fs.fs_step_forward_ahead_batch(ctx, recs)
+    assert fs.fs_check_async(ctx) == fs.FS_OK, ctx.last_error()
+    for (lay, lay1, sp, _), (lay1_o, sp_o), (n, n1) in zip(keep, want, cases):
+        assert sp["counts"].cpu().tolist() == [len(sp_o["co"]), len(sp_o["ex"]), len(sp_o["ex_next"])], (n, n1)
+        cp = sp["class_pos"].cpu().tolist()
+        assert 0 <= cp[0] <= cp[1] <= n, (n, n1, cp)
+        if n1:
+            u1 = int(lay1["n_unique"].item())
+            assert u1 == len(lay1_o["unique"])
+            assert np.array_equal(lay1["unique"][:u1].cpu().numpy(), lay1_o["unique"])
+            assert np.array_equal(lay1["perm"][:n1].cpu().numpy(), lay1_o["perm"])
+            assert np.array_equal(sp["ex_next"][:len(sp_o["ex_next"])].cpu().numpy(), sp_o["ex_next"])
+    ctx.close()
+
+
 def _ping_pong(ctx, table, state, its, steps, use_graph):
     """Two batches stepped back and forth (three layout buffers, two split buffers: period 6)."""
     d_table, d_state = table_to_dev(table), dev(state)
