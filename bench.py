@@ -55,9 +55,9 @@ def algorithmic_bytes(n_t, u_t, n_t1, u_t1, dim, w):
 
 
 def bench_tables(args, cfg) -> int:
-    """Several tables per shard (BASELINE configs[2]): one independent problem per table (table-local
-    IDs), each with its own context, buffers and stream, all stepped in every step with the default
-    schedule (index half two iterations ahead, pipelined calls)."""
+    """Several tables per shard (BASELINE configs[2]): one independent problem per table (table-local IDs, own
+    buffers), ONE context and stream for the shard: per step the index halves of all tables two iterations
+    ahead in shared launches (fs_step_forward_ahead_batch) and one fs_prioritized_step_pipelined_multi."""
     import numpy as np
     import torch
     import paper_2604_24073_amd as fs
@@ -65,7 +65,12 @@ def bench_tables(args, cfg) -> int:
 
     dev = torch.device("cuda:0")
     its_all = make_iterations(cfg, iterations=2)
-    L, P, period = 6, 5, 30
+    D = 2                                      # iterations between issuing the index halves and stepping them
+    L, P = 1 + D + 3, 1 + D + 2
+    period = math.lcm(L, P, 2)
+    if len(cfg.tables) > min(fs.FS_MAX_AHEAD_BATCH, fs.FS_MAX_STEP_TABLES):
+        print("bench.py: more tables per shard than one call takes", file=sys.stderr)
+        return 4
 
     class T:
         pass
@@ -75,11 +80,19 @@ def bench_tables(args, cfg) -> int:
         t = T()
         t.tab, t.its = tab, [its_all[0][ti], its_all[1][ti]]
         t.dim, t.w = tab.dim, (4 if tab.dtype == "f32" else 2)
-        tdtype = torch.float32 if tab.dtype == "f32" else torch.bfloat16
         t.n = [int(it.values.shape[0]) for it in t.its]
-        t.ctx = fs.Context(max_ids=max(t.n), max_dim=t.dim)
+        tabs.append(t)
+    # the tables of the shard in G groups, each with its own context and stream (G = 1: one call per step for all)
+    G = max(1, min(args.table_groups, len(tabs)))
+    groups = [tabs[g::G] for g in range(G)]
+    ctxs = [fs.Context(max_ids=max(max(t.n) for t in grp), max_dim=max(t.dim for t in grp)) for grp in groups]
+    streams = [torch.cuda.Stream() for _ in groups]
+    ctx = ctxs[0]
+    for t in tabs:
+        tab = t.tab
+        tdtype = torch.float32 if tab.dtype == "f32" else torch.bfloat16
         t.table = torch.empty((tab.num_rows, t.dim), dtype=tdtype, device=dev)
-        fs.fs_init_table_hash(t.ctx, t.table)
+        fs.fs_init_table_hash(ctx, t.table)
         t.state = torch.zeros(tab.num_rows, dtype=torch.float32, device=dev)
         t.vals = [torch.from_numpy(it.values).to(dev) for it in t.its]
         t.offs = [torch.from_numpy(it.offsets).to(dev) for it in t.its]
@@ -89,7 +102,6 @@ def bench_tables(args, cfg) -> int:
         t.splits = [fs.alloc_split(nmax, nmax, dev) for _ in range(P)]
         t.embs = [torch.empty((t.n[0], t.dim), dtype=tdtype, device=dev),
                   torch.empty((t.n[1], t.dim), dtype=tdtype, device=dev)]
-        t.stream = torch.cuda.Stream()
 
         def args_for(s, t=t):
             lay = dict(t.layouts[s % L]); lay["n"] = t.n[s % 2]
@@ -98,28 +110,39 @@ def bench_tables(args, cfg) -> int:
                                      t.layouts[(s + 1) % L], t.splits[s % P], None, t.embs[nb])
 
         t.args = [args_for(s) for s in range(period)]
-        t.stepped = False
-        tabs.append(t)
+    # one contiguous array of records per group and iteration of the period: what the two calls of a step take
+    step_records = [[fs.step_args_array([t.args[s] for t in grp]) for s in range(period)] for grp in groups]
     torch.cuda.synchronize()
+    stepped = [False]
 
-    def ahead(t, s):
-        fs.fs_step_forward_ahead(t.ctx, t.args[s % period], stream=fs.FS_STREAM_LAST_STEP if t.stepped else t.stream)
+    def ahead(s):
+        for c, st, grp in zip(ctxs, streams, groups):
+            fs.fs_step_forward_ahead_batch(c, [t.args[s % period] for t in grp],
+                                           stream=fs.FS_STREAM_LAST_STEP if stepped[0] else st)
 
     def run(k0, k):
         for s in range(k0, k0 + k):
-            for t in tabs:
-                ahead(t, s + 2)
-                fs.fs_prioritized_step_pipelined(t.ctx, t.args[s % period], t.args[(s + 1) % period], stream=t.stream)
-                t.stepped = True
+            ahead(s + D)
+            for c, st, rec in zip(ctxs, streams, step_records):
+                fs.fs_prioritized_step_pipelined_multi(c, rec[s % period], rec[(s + 1) % period], stream=st)
+            stepped[0] = True
 
-    for t in tabs:
-        fs.fs_unique_ids(t.ctx, t.vals[0], t.tab.num_rows, out=t.layouts[0], stream=t.stream)
-        ahead(t, 0)
-        ahead(t, 1)
+    def join_all(check=False):
+        for c, st in zip(ctxs, streams):
+            if check:
+                assert fs.fs_check_async(c, st) == fs.FS_OK, c.last_error()
+            else:
+                fs.fs_step_join(c, st)
+
+    for c, st, grp in zip(ctxs, streams, groups):
+        for t in grp:
+            fs.fs_unique_ids(c, t.vals[0], t.tab.num_rows, out=t.layouts[0], stream=st)
+    for s in range(D):
+        ahead(s)
     run(0, 1)
     cpu_s, u_all = 0.0, []
+    join_all(check=True)
     for ti, t in enumerate(tabs):
-        assert fs.fs_check_async(t.ctx, t.stream) == fs.FS_OK, t.ctx.last_error()
         t.u = [int(t.layouts[0]["n_unique"].item()), int(t.layouts[1]["n_unique"].item())]
         u_all.append(t.u)
         if not args.no_cpu_baseline:
@@ -139,23 +162,21 @@ def bench_tables(args, cfg) -> int:
                 return 4
             cpu_s += statistics.median(times)
     run(1, args.warmup)
-    for t in tabs:
-        fs.fs_step_join(t.ctx, t.stream)
+    join_all()
     torch.cuda.synchronize()
     k0 = 1 + args.warmup
-    fs.fs_ctx_set_kernel_timing(tabs[0].ctx, args.steps, args.time_every)
+    fs.fs_ctx_set_kernel_timing(ctx, args.steps, args.time_every)
     t0 = time.perf_counter()
     run(k0, args.steps)
-    for t in tabs:
-        fs.fs_step_join(t.ctx, t.stream)
+    t_enq = time.perf_counter() - t0
+    join_all()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    for t in tabs:
-        assert fs.fs_check_async(t.ctx, t.stream) == fs.FS_OK, t.ctx.last_error()
+    join_all(check=True)
     kinds = {"gather": fs.FS_TIME_GATHER, "priority_pass": fs.FS_TIME_UPDATE_CO, "deferred_pass": fs.FS_TIME_UPDATE_EX}
     kernel_ms = {}
     for name, kind in kinds.items():
-        vals = fs.fs_ctx_get_kernel_timing(tabs[0].ctx, kind, args.steps)
+        vals = fs.fs_ctx_get_kernel_timing(ctx, kind, args.steps)
         kernel_ms[name] = (sum(vals) / len(vals)) if vals else None
     rows = sum(t.u[s % 2] for t in tabs for s in range(k0, k0 + args.steps))
     step_bytes = 0.0
@@ -184,7 +205,9 @@ def bench_tables(args, cfg) -> int:
                                f"{cfg.length_rule} UIH lengths [{cfg.length_lo},{cfg.length_hi}], a step = one "
                                "iteration of every table; 2 consecutive iterations stepped back and forth",
                    "ids_per_iteration": [t.n for t in tabs], "unique_rows": u_all},
-        "schedule": "pipelined+index_half_ahead, one context and stream per table",
+        "schedule": f"the tables in {G} group(s), each with a context and a stream: per step and group one multi-table "
+                    "pipelined call + the index halves of its tables two iterations ahead in shared launches",
+        "host_enqueue_us_per_step": t_enq / args.steps * 1e6,
         "step_algorithmic_bytes": step_bytes, "step_algorithmic_GBps": step_gbps,
         "step_frac_of_hbm_peak": step_gbps / HBM_PEAK_GBPS,
         "kernel_avg_us": {k: (v * 1e3 if v is not None else None) for k, v in kernel_ms.items()},
@@ -196,8 +219,8 @@ def bench_tables(args, cfg) -> int:
                       "tables holding only the touched rows", "host_cpus": os.cpu_count()},
     }
     print(json.dumps(out))
-    for t in tabs:
-        t.ctx.close()
+    for c in ctxs:
+        c.close()
     return 0
 
 
@@ -227,6 +250,10 @@ def main() -> int:
                     help="with --ahead index: index halves of K consecutive iterations share their launches "
                          "(fs_step_forward_ahead_batch), issued K+1 iterations before the first of them is stepped; "
                          "1 = one chain of launches per iteration")
+    ap.add_argument("--table-groups", type=int, default=2, metavar="G",
+                    help="configurations with several tables per shard: the tables are stepped in G groups, each "
+                         "with its own context and stream (1 = one call per step for all tables; 2 measured best: "
+                         "two tables' passes side by side, and no more streams than the hardware has queues for)")
     ap.add_argument("--keep-reduced", action="store_true",
                     help="also write the summed gradients to memory in the timed steps (the step itself does not "
                          "need them there)")

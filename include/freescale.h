@@ -242,7 +242,8 @@ int fs_step_forward(fs_ctx *ctx, const fs_step_args *args, fs_stream stream);
  * in use by work that is not ordered before `stream`'s current position, and `ids` must stay in
  * place until the dedup has run (it is only enqueued when the call returns); in a loop of pipelined
  * calls that means five layout buffers in rotation when the dedup runs two batches ahead of the
- * call that consumes it as u_t1.  At most four such dedups may be outstanding.
+ * call that consumes it as u_t1.  When more ahead-of-time results are outstanding than the context
+ * tracks, the oldest finished one that no call has asked for is forgotten (its data stay valid).
  * stream == FS_STREAM_LAST_STEP: no event is recorded on any stream of the caller; the dedup is
  * ordered after the position the caller's stream had at the START of the most recent
  * fs_prioritized_step_pipelined call (its deferred pass may still be running: one more layout
@@ -277,7 +278,7 @@ int fs_step_forward_ahead(fs_ctx *ctx, const fs_step_args *args, fs_stream strea
  * fs_step_forward_ahead.  Buffers in rotation when a batch of K consecutive iterations is issued D
  * iterations before the pipelined call of its first one, with FS_STREAM_LAST_STEP: K + D + 3 layouts
  * and K + D + 2 split/class bundles. */
-#define FS_MAX_AHEAD_BATCH 4
+#define FS_MAX_AHEAD_BATCH 8
 int fs_step_forward_ahead_batch(fs_ctx *ctx, const fs_step_args *args, int count, fs_stream stream);
 
 /* Steady-state form of the iteration, software-pipelined by one batch exactly as Algorithm 2
@@ -300,6 +301,19 @@ int fs_step_forward_ahead_batch(fs_ctx *ctx, const fs_step_args *args, int count
  * waits for it. */
 int fs_prioritized_step_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs_step_args *next,
                                   fs_stream stream);
+
+/* The same for `count` (1..FS_MAX_STEP_TABLES) tables of one shard in ONE call: cur[k] / next[k] are the
+ * records of table k (next == NULL: last iteration of all of them).  The tables are independent
+ * problems (table-local IDs, own buffers); what they share is the schedule: one fork event, one wait for
+ * the side stream per call instead of one per table - the cross-stream waits are what a call costs the
+ * host - priority pass and gather of every table on `stream`, the deferred passes of all of them on
+ * side stream A.  With fs_step_forward_ahead_batch taking the index halves of the same tables in shared
+ * launches, an iteration of a shard with eight tables is two calls.  Results are those of one
+ * fs_prioritized_step_pipelined call per table, bit for bit; the context must be sized for the largest
+ * table's batch and dim. */
+#define FS_MAX_STEP_TABLES 16
+int fs_prioritized_step_pipelined_multi(fs_ctx *ctx, const fs_step_args *cur, const fs_step_args *next,
+                                        int count, fs_stream stream);
 
 /* Makes `stream` wait for everything earlier calls left running on the context's own streams
  * (side work of the last pipelined call, outstanding ahead-of-time dedups); no-op if there is

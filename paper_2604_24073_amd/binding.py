@@ -21,7 +21,8 @@ FS_F32, FS_BF16 = 0, 1
 FS_OK, FS_EINVAL, FS_ENOMEM, FS_EHIP, FS_ENOTIMPL, FS_ERANGE = 0, -1, -2, -3, -4, -5
 FS_MAX_DIM = 256
 FS_SHORT_SEGMENT = 8
-FS_MAX_AHEAD_BATCH = 4
+FS_MAX_AHEAD_BATCH = 8
+FS_MAX_STEP_TABLES = 16
 SHORT_REC_INTS = 12
 
 c_i64, c_i32, c_vp, c_f = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_float
@@ -85,6 +86,8 @@ def load_library() -> ctypes.CDLL:
         "fs_step_forward": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args), S]),
         "fs_step_forward_ahead": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args), S]),
         "fs_step_forward_ahead_batch": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args), ctypes.c_int, S]),
+        "fs_prioritized_step_pipelined_multi": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args),
+                                                                ctypes.POINTER(fs_step_args), ctypes.c_int, S]),
         "fs_prioritized_step_pipelined": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args),
                                                          ctypes.POINTER(fs_step_args), S]),
         "fs_graph_capture_pipelined": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args), ctypes.POINTER(fs_step_args),
@@ -338,6 +341,17 @@ def fs_prioritized_step_pipelined(ctx: Context, cur: fs_step_args, nxt: Optional
     rc = ctx.lib.fs_prioritized_step_pipelined(ctx.handle, ctypes.byref(cur),
                                                ctypes.byref(nxt) if nxt is not None else None, _stream(stream))
     ctx.check(rc, "fs_prioritized_step_pipelined")
+
+
+def step_args_array(records):
+    """Contiguous copy of a sequence of argument records (for the calls that take several)."""
+    return (fs_step_args * len(records))(*records)
+
+
+def fs_prioritized_step_pipelined_multi(ctx: Context, cur, nxt, stream=None) -> None:
+    """cur / nxt: fs_step_args arrays from step_args_array (nxt may be None), one record per table."""
+    rc = ctx.lib.fs_prioritized_step_pipelined_multi(ctx.handle, cur, nxt, len(cur), _stream(stream))
+    ctx.check(rc, "fs_prioritized_step_pipelined_multi")
 
 
 def fs_ctx_host_times(ctx: Context, reset: bool = False):

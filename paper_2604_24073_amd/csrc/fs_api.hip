@@ -6,6 +6,7 @@
 #include <condition_variable>
 #include <deque>
 #include <functional>
+#include <memory>
 #include <mutex>
 #include <new>
 #include <thread>
@@ -613,9 +614,9 @@ int enqueue_class_pass(fs_ctx *ctx, const fs_step_args *a, int cls, hipStream_t 
     return rc;
 }
 
-int enqueue_gather(fs_ctx *ctx, const fs_step_args *a, hipStream_t s) {
+int enqueue_gather(fs_ctx *ctx, const fs_step_args *a, hipStream_t s, bool timed = true) {
     const int row_bytes = a->dim * (a->dtype == FS_F32 ? 4 : 2);
-    hipEvent_t *tg = timing_pair(ctx, FS_TIME_GATHER);
+    hipEvent_t *tg = timed ? timing_pair(ctx, FS_TIME_GATHER) : nullptr;
     if (tg) (void)hipEventRecord(tg[0], s);
     const int rc = launch_gather(ctx, a->table, a->num_rows, row_bytes, a->values_t1, a->offsets_t1, a->batch_t1,
                                  a->n_t1, a->emb_t1, s);
@@ -623,25 +624,40 @@ int enqueue_gather(fs_ctx *ctx, const fs_step_args *a, hipStream_t s) {
     return rc;
 }
 
-// Side stream A for one pipelined call: after the caller's earlier work (the gradients of `cur`),
-// the deferred pass of `cur`, then the index half of `next`, then the event the next call waits for.
-int enqueue_side_stream(fs_ctx *ctx, const fs_step_args *cur, const fs_step_args *next, bool nxt_t, bool nxt_t1,
-                        fs_ahead *ahead, fs_ahead *index_ahead, int parity, hipEvent_t *ex_timing) {
+// What one pipelined call hands to side stream A: for each of its tables the deferred pass of `cur` and the
+// index half of `next` (done ahead of time on an index stream: only waited for; else done here).
+constexpr int kMaxTables = FS_MAX_STEP_TABLES;
+struct side_work {
+    int count = 0, parity = 0;
+    hipEvent_t *ex_timing = nullptr;
+    fs_step_args cur[kMaxTables], next[kMaxTables];
+    bool have_t[kMaxTables], has_next[kMaxTables], nxt_t[kMaxTables], nxt_t1[kMaxTables];
+    fs_ahead *ahead[kMaxTables], *index_ahead[kMaxTables];
+};
+
+// Side stream A for one pipelined call: after the caller's earlier work (the gradients of `cur`), the
+// deferred passes, then the index halves of `next`, then the event the next call waits for.
+int enqueue_side_stream(fs_ctx *ctx, const side_work &w) {
     hipStream_t sa = ctx->stream_a;
     int rc = FS_OK;
-    FS_HIP(ctx, hipStreamWaitEvent(sa, ctx->ev_pfork[parity], 0));
-    if (cur) rc = enqueue_class_pass(ctx, cur, 1, sa, ex_timing);
-    // the index half of `next`: done ahead of time on an index stream (then only waited for), or here
-    if (index_ahead) {
-        const int irc = consume_ahead(ctx, index_ahead, sa);
-        if (rc == FS_OK) rc = irc;
-    } else if (rc == FS_OK && next) {
-        rc = enqueue_index_work(ctx, next, nxt_t, nxt_t1, ahead, sa);
-    } else if (ahead) {
-        (void)consume_ahead(ctx, ahead, sa);
+    FS_HIP(ctx, hipStreamWaitEvent(sa, ctx->ev_pfork[w.parity], 0));
+    for (int k = 0; k < w.count; ++k)
+        if (w.have_t[k]) {
+            const int r = enqueue_class_pass(ctx, &w.cur[k], 1, sa, k == 0 ? w.ex_timing : nullptr);
+            if (rc == FS_OK) rc = r;
+        }
+    for (int k = 0; k < w.count; ++k) {
+        if (w.index_ahead[k]) {
+            const int r = consume_ahead(ctx, w.index_ahead[k], sa);
+            if (rc == FS_OK) rc = r;
+        } else if (rc == FS_OK && w.has_next[k]) {
+            rc = enqueue_index_work(ctx, &w.next[k], w.nxt_t[k], w.nxt_t1[k], w.ahead[k], sa);
+        } else if (w.ahead[k]) {
+            (void)consume_ahead(ctx, w.ahead[k], sa);
+        }
     }
     if (rc != FS_OK) return rc;
-    FS_HIP(ctx, hipEventRecord(ctx->ev_side[parity], sa));
+    FS_HIP(ctx, hipEventRecord(ctx->ev_side[w.parity], sa));
     return FS_OK;
 }
 
@@ -916,23 +932,39 @@ int fs_prioritized_step(fs_ctx *ctx, const fs_step_args *a, fs_stream stream) {
 }
 
 int fs_prioritized_step_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs_step_args *next, fs_stream stream) {
+    return fs_prioritized_step_pipelined_multi(ctx, cur, next, 1, stream);
+}
+
+int fs_prioritized_step_pipelined_multi(fs_ctx *ctx, const fs_step_args *cur, const fs_step_args *next, int count,
+                                        fs_stream stream) {
     if (!ctx) return FS_EINVAL;
-    bool have_t, have_t1, nxt_t = false, nxt_t1 = false;
-    int rc = check_step_args(ctx, cur, &have_t, &have_t1);
-    if (rc != FS_OK) return rc;
-    if (next) {
-        rc = check_step_args(ctx, next, &nxt_t, &nxt_t1);
+    FS_REQUIRE(ctx, cur && count >= 1 && count <= FS_MAX_STEP_TABLES, "pipelined step: 1..FS_MAX_STEP_TABLES tables");
+    std::shared_ptr<side_work> w = std::make_shared<side_work>();
+    bool have_t1[kMaxTables];
+    w->count = count;
+    for (int k = 0; k < count; ++k) {
+        int rc = check_step_args(ctx, &cur[k], &w->have_t[k], &have_t1[k]);
         if (rc != FS_OK) return rc;
+        w->has_next[k] = next != nullptr;
+        w->nxt_t[k] = w->nxt_t1[k] = false;
+        if (next) {
+            rc = check_step_args(ctx, &next[k], &w->nxt_t[k], &w->nxt_t1[k]);
+            if (rc != FS_OK) return rc;
+        }
+        w->cur[k] = cur[k];
+        w->next[k] = next ? next[k] : cur[k];
+        w->ahead[k] = w->index_ahead[k] = nullptr;
     }
     hipStream_t sp = as_stream(stream);
     begin_step_timing(ctx);
-    // Side stream A still runs what the previous call left there (its deferred pass, the index half
-    // that produced the split and class order of `cur`).  It is waited for once, right before the
+    // Side stream A still runs what the previous call left there (its deferred passes, the index halves
+    // that produced the split and class order of `cur`).  It is waited for once, right before the first
     // priority pass.  Cross-stream waits are the expensive host operation here (each makes the
-    // runtime flush the producer queue): two per call - A waits for `stream` as it stands at the
-    // start of the call (the gradients), `stream` waits for A's previous job.
+    // runtime flush the producer queue): two per call, whatever the number of tables - A waits for `stream`
+    // as it stands at the start of the call (the gradients), `stream` waits for A's previous job.
     const bool prev_side = ctx->side_pending;
     const int pp = ctx->pipe_parity, p = pp ^ 1;            // event set of the previous / this call
+    int rc = FS_OK;
     const double h0 = now_us();
     fs_worker *w0 = (!ctx->capturing && ctx->use_worker) ? get_worker(ctx, 0) : nullptr;
     if (ctx->host->worker[0]) {
@@ -949,34 +981,38 @@ int fs_prioritized_step_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs
     }
     const double h1 = now_us();
     if (!ctx->capturing) {
-        // the index half of `cur` done ahead of time and not yet waited for by anybody (first call of a
-        // run): the caller's stream waits for it, and through the fork event so does the side stream
-        fs_ahead *index_cur = claim_ahead(ctx, cur->counts_dev);
-        if (index_cur) {
-            rc = consume_ahead(ctx, index_cur, sp);
-            if (rc != FS_OK) return rc;
+        // index halves of `cur` done ahead of time and not yet waited for by anybody (first call of a
+        // run): the caller's stream waits for them, and through the fork event so does the side stream
+        for (int k = 0; k < count; ++k) {
+            fs_ahead *index_cur = claim_ahead(ctx, cur[k].counts_dev);
+            if (index_cur) {
+                rc = consume_ahead(ctx, index_cur, sp);
+                if (rc != FS_OK) return rc;
+            }
         }
     }
     FS_HIP(ctx, hipEventRecord(ctx->ev_pfork[p], sp));
     ctx->pfork_valid = true;
     // claimed entries: the side job waits for them and gives them back
-    fs_ahead *index_ahead = (next && !ctx->capturing) ? claim_ahead(ctx, next->counts_dev) : nullptr;
-    fs_ahead *ahead = (next && nxt_t1 && !index_ahead && !ctx->capturing) ? claim_ahead(ctx, next->u_t1) : nullptr;
-    hipEvent_t *tex = have_t ? timing_pair(ctx, FS_TIME_UPDATE_EX) : nullptr;
-    fs_step_args cur_copy = *cur, next_copy = next ? *next : *cur;
-    const bool has_next = next != nullptr;
-    auto side_job = [=]() -> int {
-        return enqueue_side_stream(ctx, have_t ? &cur_copy : nullptr,
-                                   has_next ? &next_copy : nullptr, nxt_t, nxt_t1, ahead, index_ahead, p, tex);
-    };
+    if (next && !ctx->capturing)
+        for (int k = 0; k < count; ++k) {
+            w->index_ahead[k] = claim_ahead(ctx, next[k].counts_dev);
+            w->ahead[k] = (w->nxt_t1[k] && !w->index_ahead[k]) ? claim_ahead(ctx, next[k].u_t1) : nullptr;
+        }
+    w->parity = p;
+    w->ex_timing = w->have_t[0] ? timing_pair(ctx, FS_TIME_UPDATE_EX) : nullptr;
+    auto side_job = [ctx, w]() -> int { return enqueue_side_stream(ctx, *w); };
     if (w0) w0->post(side_job);
     const double h2 = now_us();
     rc = FS_OK;
     if (prev_side && hipStreamWaitEvent(sp, ctx->ev_side[pp], 0) != hipSuccess) rc = FS_EHIP;
     ctx->side_pending = false;
     const double h3 = now_us();
-    if (rc == FS_OK && have_t) rc = enqueue_class_pass(ctx, cur, 0, sp, timing_pair(ctx, FS_TIME_UPDATE_CO));
-    if (rc == FS_OK && have_t1) rc = enqueue_gather(ctx, cur, sp);
+    for (int k = 0; k < count && rc == FS_OK; ++k) {
+        if (w->have_t[k])
+            rc = enqueue_class_pass(ctx, &cur[k], 0, sp, k == 0 ? timing_pair(ctx, FS_TIME_UPDATE_CO) : nullptr);
+        if (rc == FS_OK && have_t1[k]) rc = enqueue_gather(ctx, &cur[k], sp, k == 0);
+    }
     const double h4 = now_us();
     if (!w0) {
         const int src = side_job();
@@ -986,7 +1022,7 @@ int fs_prioritized_step_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs
     ctx->host_us[0] += h1 - h0;      // waiting for the side-stream thread
     ctx->host_us[1] += h2 - h1;      // fork event, handing over the side work
     ctx->host_us[2] += h3 - h2;      // wait for the previous side work
-    ctx->host_us[3] += h4 - h3;      // priority pass and gather
+    ctx->host_us[3] += h4 - h3;      // priority passes and gathers
     ctx->host_us[6] += 1.0;
     ctx->pipe_parity = p;
     ctx->side_pending = true;        // also after a failure: a posted job still records its event

@@ -59,7 +59,7 @@ struct fs_sort_scratch {
 #define FS_INDEX_STREAMS 2
 #endif
 constexpr int kIndexStreams = FS_INDEX_STREAMS;   // streams that run ahead-of-time index work, used in turn
-constexpr int kMaxBatch = FS_MAX_AHEAD_BATCH;     // (freescale.h)     // index halves that may share their launches
+constexpr int kMaxBatch = FS_MAX_AHEAD_BATCH;     // index halves that may share their launches (freescale.h)
 // scratch sets: 0 for the caller's stream / side stream, then kMaxBatch per index stream
 constexpr int kSortSets = 1 + kIndexStreams * kMaxBatch;
 

@@ -218,6 +218,70 @@ def test_index_halves_of_different_tables_share_their_launches():
     ctx.close()
 
 
+@pytest.mark.parametrize("ahead", [True, False])
+def test_multi_table_step_matches_one_call_per_table(ahead):
+    """fs_prioritized_step_pipelined_multi over three tables (different rows, dims, dtypes, batch sizes), the index
+    halves of all of them in shared launches two iterations ahead (or done by the calls themselves): tables,
+    states and gathered rows bit for bit as from one pipelined call per table."""
+    rng = np.random.default_rng(99)
+    specs = [(30000, 128, "f32", 300), (2000, 64, "bf16", 120), (50000, 32, "f32", 40)]
+    T = 6
+    ctx = fs.Context(max_ids=20000, max_dim=128)
+    tabs = []
+    for rows, dim, dtype, max_len in specs:
+        t = It()
+        t.table, t.state = rand_table(rng, rows, dim, dtype), np.zeros(rows, np.float32)
+        t.its = make_its(rng, rows, dim, T, users=30, max_len=max_len)
+        tabs.append(t)
+    # reference: one pipelined call per table and iteration
+    ref = [run_pipelined(ctx, t.table, t.state, t.its, 0.01, 1e-8, ahead="index" if ahead else False, sync_each=False)
+           for t in tabs]
+    L, P = 6, 5
+    for t in tabs:
+        t.d_table, t.d_state = table_to_dev(t.table), dev(t.state)
+        t.vals = [dev(it.values) for it in t.its]
+        t.offs = [dev(it.offsets) for it in t.its]
+        t.grads = [dev(it.grads) for it in t.its]
+        nmax = max(v.numel() for v in t.vals)
+        t.layouts = [fs.alloc_layout(nmax, "cuda") for _ in range(L)]
+        t.splits = [fs.alloc_split(nmax, nmax, "cuda") for _ in range(P)]
+        t.embs = [torch.empty((nmax, t.table.shape[1]), dtype=t.d_table.dtype, device="cuda") for _ in range(2)]
+        t.args = []
+        for s_ in range(T):
+            lay = dict(t.layouts[s_ % L]); lay["n"] = t.vals[s_].numel()
+            last = s_ == T - 1
+            t.args.append(fs.make_step_args(t.d_table, t.d_state, 0.01, 1e-8, lay, t.grads[s_],
+                                            None if last else t.vals[s_ + 1], None if last else t.offs[s_ + 1],
+                                            None if last else t.layouts[(s_ + 1) % L], t.splits[s_ % P], None,
+                                            None if last else t.embs[s_ % 2]))
+        fs.fs_unique_ids(ctx, t.vals[0], t.table.shape[0], out=t.layouts[0])
+
+    def index_halves(s_):
+        if ahead and s_ < T:
+            fs.fs_step_forward_ahead_batch(ctx, [t.args[s_] for t in tabs])
+
+    if ahead:
+        index_halves(0)
+        index_halves(1)
+    else:
+        for t in tabs:
+            fs.fs_step_forward(ctx, t.args[0])
+    for s_ in range(T):
+        index_halves(s_ + 2)
+        cur = fs.step_args_array([t.args[s_] for t in tabs])
+        nxt = fs.step_args_array([t.args[s_ + 1] for t in tabs]) if s_ + 1 < T else None
+        fs.fs_prioritized_step_pipelined_multi(ctx, cur, nxt)
+    assert fs.fs_check_async(ctx) == fs.FS_OK, ctx.last_error()
+    for t, (r_table, r_state, _) in zip(tabs, ref):
+        view = torch.int16 if t.d_table.dtype == torch.bfloat16 else torch.int32
+        assert torch.equal(t.d_table.view(view), r_table.view(view))
+        assert torch.equal(t.d_state, r_state)
+    with pytest.raises(fs.FreeScaleError) as e:                     # more tables than a call takes
+        fs.fs_prioritized_step_pipelined_multi(ctx, fs.step_args_array([tabs[0].args[0]] * (fs.FS_MAX_STEP_TABLES + 1)), None)
+    assert e.value.code == fs.FS_EINVAL
+    ctx.close()
+
+
 def test_batch_of_index_halves_with_empty_records():
     """A batch whose records are degenerate in every way a record can be: no gradients (empty iteration) but a
     lookahead batch, gradients but no lookahead, both empty, and an ordinary one: counts, class extents and the
