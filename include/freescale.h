@@ -307,7 +307,9 @@ int fs_prioritized_step_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs
  * problems (table-local IDs, own buffers); what they share is the schedule: one fork event, one wait for
  * the side stream per call instead of one per table - the cross-stream waits are what a call costs the
  * host - priority pass and gather of every table on `stream`, the deferred passes of all of them on
- * side stream A.  With fs_step_forward_ahead_batch taking the index halves of the same tables in shared
+ * side stream A; and the launches: tables of one dtype and row width take their priority passes in
+ * one launch, their deferred passes in one and their gathers in one (as many as fit the context's
+ * partial-row space at a time).  With fs_step_forward_ahead_batch taking the index halves of the same tables in shared
  * launches, an iteration of a shard with eight tables is two calls.  Results are those of one
  * fs_prioritized_step_pipelined call per table, bit for bit; the context must be sized for the largest
  * table's batch and dim. */

@@ -603,25 +603,50 @@ int enqueue_index_work(fs_ctx *ctx, const fs_step_args *a, bool have_t, bool hav
     return enqueue_index_work_batch(ctx, 1, a, &have_t, &have_t1, &ahead, s, set, &dedup_out, &layout_in);
 }
 
-// update_embedding for one class of rows of iteration t (0: priority pass, 1: deferred pass)
-int enqueue_class_pass(fs_ctx *ctx, const fs_step_args *a, int cls, hipStream_t s, hipEvent_t *timing) {
+// update_embedding for one class of rows of iteration t (0: priority pass, 1: deferred pass) of `count`
+// tables (`use[k]`: table k has gradients); tables of one row width share their launches
+fs_class_pass_job class_job(const fs_step_args *a, int cls) {
+    return fs_class_pass_job{a->grads_t, a->n_t, a->dim, a->cperm, a->cslot, a->class_pos_dev, a->seg_offsets_t,
+                             a->cstart, a->u_t, a->table, a->dtype, a->state, a->num_rows, a->lr, a->eps, a->reduced,
+                             a->short_rec + (int64_t)cls * a->n_t * kShortRecInts, a->counts_dev + cls};
+}
+
+int enqueue_class_passes(fs_ctx *ctx, const fs_step_args *a, const bool *use, int count, int cls, hipStream_t s,
+                         hipEvent_t *timing) {
+    fs_class_pass_job jobs[FS_MAX_STEP_TABLES];
+    int m = 0;
+    for (int k = 0; k < count; ++k)
+        if (use[k]) jobs[m++] = class_job(&a[k], cls);
+    if (m == 0) return FS_OK;
     if (timing) (void)hipEventRecord(timing[0], s);
-    const int rc = launch_reduce_update(ctx, cls, a->grads_t, a->n_t, a->dim, a->cperm, a->cslot, a->class_pos_dev,
-                                        a->seg_offsets_t, a->cstart, a->u_t, a->table, a->dtype, a->state,
-                                        a->num_rows, a->lr, a->eps, a->reduced, s,
-                                        a->short_rec + (int64_t)cls * a->n_t * kShortRecInts, a->counts_dev + cls);
+    const int rc = launch_reduce_update_batch(ctx, cls, m, jobs, s);
     if (timing && rc == FS_OK) (void)hipEventRecord(timing[1], s);
     return rc;
 }
 
-int enqueue_gather(fs_ctx *ctx, const fs_step_args *a, hipStream_t s, bool timed = true) {
-    const int row_bytes = a->dim * (a->dtype == FS_F32 ? 4 : 2);
-    hipEvent_t *tg = timed ? timing_pair(ctx, FS_TIME_GATHER) : nullptr;
+int enqueue_class_pass(fs_ctx *ctx, const fs_step_args *a, int cls, hipStream_t s, hipEvent_t *timing) {
+    const bool use = true;
+    return enqueue_class_passes(ctx, a, &use, 1, cls, s, timing);
+}
+
+int enqueue_gathers(fs_ctx *ctx, const fs_step_args *a, const bool *use, int count, hipStream_t s) {
+    fs_gather_job jobs[FS_MAX_STEP_TABLES];
+    int m = 0;
+    for (int k = 0; k < count; ++k)
+        if (use[k])
+            jobs[m++] = fs_gather_job{a[k].table, a[k].num_rows, a[k].dim * (a[k].dtype == FS_F32 ? 4 : 2), a[k].values_t1,
+                                      a[k].offsets_t1, a[k].batch_t1, a[k].n_t1, a[k].emb_t1};
+    if (m == 0) return FS_OK;
+    hipEvent_t *tg = timing_pair(ctx, FS_TIME_GATHER);
     if (tg) (void)hipEventRecord(tg[0], s);
-    const int rc = launch_gather(ctx, a->table, a->num_rows, row_bytes, a->values_t1, a->offsets_t1, a->batch_t1,
-                                 a->n_t1, a->emb_t1, s);
+    const int rc = launch_gather_batch(ctx, m, jobs, s);
     if (tg && rc == FS_OK) (void)hipEventRecord(tg[1], s);
     return rc;
+}
+
+int enqueue_gather(fs_ctx *ctx, const fs_step_args *a, hipStream_t s) {
+    const bool use = true;
+    return enqueue_gathers(ctx, a, &use, 1, s);
 }
 
 // What one pipelined call hands to side stream A: for each of its tables the deferred pass of `cur` and the
@@ -641,11 +666,7 @@ int enqueue_side_stream(fs_ctx *ctx, const side_work &w) {
     hipStream_t sa = ctx->stream_a;
     int rc = FS_OK;
     FS_HIP(ctx, hipStreamWaitEvent(sa, ctx->ev_pfork[w.parity], 0));
-    for (int k = 0; k < w.count; ++k)
-        if (w.have_t[k]) {
-            const int r = enqueue_class_pass(ctx, &w.cur[k], 1, sa, k == 0 ? w.ex_timing : nullptr);
-            if (rc == FS_OK) rc = r;
-        }
+    rc = enqueue_class_passes(ctx, w.cur, w.have_t, w.count, 1, sa, w.ex_timing);
     for (int k = 0; k < w.count; ++k) {
         if (w.index_ahead[k]) {
             const int r = consume_ahead(ctx, w.index_ahead[k], sa);
@@ -1000,7 +1021,7 @@ int fs_prioritized_step_pipelined_multi(fs_ctx *ctx, const fs_step_args *cur, co
             w->ahead[k] = (w->nxt_t1[k] && !w->index_ahead[k]) ? claim_ahead(ctx, next[k].u_t1) : nullptr;
         }
     w->parity = p;
-    w->ex_timing = w->have_t[0] ? timing_pair(ctx, FS_TIME_UPDATE_EX) : nullptr;
+    w->ex_timing = timing_pair(ctx, FS_TIME_UPDATE_EX);
     auto side_job = [ctx, w]() -> int { return enqueue_side_stream(ctx, *w); };
     if (w0) w0->post(side_job);
     const double h2 = now_us();
@@ -1008,11 +1029,9 @@ int fs_prioritized_step_pipelined_multi(fs_ctx *ctx, const fs_step_args *cur, co
     if (prev_side && hipStreamWaitEvent(sp, ctx->ev_side[pp], 0) != hipSuccess) rc = FS_EHIP;
     ctx->side_pending = false;
     const double h3 = now_us();
-    for (int k = 0; k < count && rc == FS_OK; ++k) {
-        if (w->have_t[k])
-            rc = enqueue_class_pass(ctx, &cur[k], 0, sp, k == 0 ? timing_pair(ctx, FS_TIME_UPDATE_CO) : nullptr);
-        if (rc == FS_OK && have_t1[k]) rc = enqueue_gather(ctx, &cur[k], sp, k == 0);
-    }
+    // every priority pass before every gather: a gather may only read what its table's priority pass left
+    if (rc == FS_OK) rc = enqueue_class_passes(ctx, cur, w->have_t, count, 0, sp, timing_pair(ctx, FS_TIME_UPDATE_CO));
+    if (rc == FS_OK) rc = enqueue_gathers(ctx, cur, have_t1, count, sp);
     const double h4 = now_us();
     if (!w0) {
         const int src = side_job();

@@ -101,6 +101,31 @@ struct fs_class_job {
     int32_t *short_rec;
 };
 
+// one class pass / one gather of a launch shared by several tables (host side)
+struct fs_class_pass_job {
+    const float *grads;
+    int64_t n;
+    int32_t dim;
+    const int32_t *cperm, *cslot, *class_pos, *seg_offsets, *cstart;
+    const int64_t *u_t;
+    void *table;
+    int dt;
+    float *state;
+    int64_t num_rows;
+    float lr, eps;
+    float *reduced;
+    const int32_t *short_rec;       // the records of the class
+    const int64_t *n_rows_dev;      // the number of rows of the class
+};
+struct fs_gather_job {
+    const void *table;
+    int64_t num_rows;
+    int row_bytes;
+    const int64_t *values, *offsets;
+    int64_t batch, n;
+    void *out;
+};
+
 struct fs_ctx {
     int device;
     int64_t max_ids;
@@ -219,6 +244,9 @@ int launch_reduce_update(fs_ctx *, int cls, const float *grads, int64_t n, int32
                          const int32_t *cstart, const int64_t *u_t, void *table, int dt, float *state,
                          int64_t num_rows, float lr, float eps, float *reduced, hipStream_t s,
                          const int32_t *short_rec, const int64_t *n_rows_dev);
+// the class passes (class `cls`) / the gathers of `count` tables: tables of one dtype and row width share launches
+int launch_reduce_update_batch(fs_ctx *, int cls, int count, const fs_class_pass_job *jobs, hipStream_t s);
+int launch_gather_batch(fs_ctx *, int count, const fs_gather_job *jobs, hipStream_t s);
 // `timing`: optional event pair recorded around the main (chunk) kernel only
 int launch_reduce(fs_ctx *, const float *grads, int64_t n, int32_t dim, const int32_t *perm,
                   const int32_t *seg_offsets, const int64_t *n_unique_dev, float *reduced, hipStream_t s,

@@ -563,44 +563,122 @@ __device__ __forceinline__ void short_rows_body(
 // occurrences, position-cut), the others the records of the rows with few.  The long part goes
 // first because its last arrivers have the longest dependent chains; workgroups past the end of
 // either part leave at once, so an empty part costs nothing but their dispatch.
+// A launch takes the class passes of up to kMaxBatch tables of one row width (blockIdx.y picks the table):
+// a pass is about one residency round of the chip however small it is, so the tables of a shard are
+// better walked side by side than one after the other.
+struct class_pass_job {
+    const f32x4 *grads;
+    int n, long_blocks, blocks, cls, gvec;
+    float lr, eps;
+    const int32_t *cperm, *cslot, *class_pos, *seg_offsets, *cstart, *recs;
+    const int64_t *u_t, *n_rows_dev;
+    void *table;
+    float *state;
+    int64_t num_rows;
+    f32x4 *reduced;
+    double *part_head, *part_last;      // this table's stretch of the class's partial rows and counters
+    int *cnt_seg, *cnt_sup;
+};
+struct class_pass_batch {
+    class_pass_job j[kMaxBatch];
+};
+
 template <bool BF16, int LPR, int UNR, int CHUNK, int SU>
-__global__ __launch_bounds__(kFusedWaves *kWave) void class_pass_kernel(
-    const f32x4 *__restrict__ grads, int n, int long_blocks, const int32_t *__restrict__ cperm,
-    const int32_t *__restrict__ cslot, const int32_t *__restrict__ class_pos, int cls,
-    const int32_t *__restrict__ seg_offsets, const int32_t *__restrict__ cstart, const int64_t *__restrict__ u_t,
-    const int32_t *__restrict__ recs, const int64_t *__restrict__ n_rows_dev, void *table, float *state,
-    int64_t num_rows, int gvec, float lr, float eps, f32x4 *reduced, double *part_head, double *part_last,
-    int *cnt_seg, int *cnt_sup, int *flags) {
-    FS_WG_TRACE(8 + cls);
-    if ((int)blockIdx.x < long_blocks)
-        long_segments_body<BF16, LPR, UNR, CHUNK>((int)blockIdx.x, grads, cperm, cslot, class_pos, cls, n, seg_offsets,
-                                                  cstart, u_t, table, state, num_rows, gvec, lr, eps, reduced,
-                                                  part_head, part_last, cnt_seg, cnt_sup, flags);
+__global__ __launch_bounds__(kFusedWaves *kWave) void class_pass_kernel(const class_pass_batch batch, int *flags) {
+    const class_pass_job &job = batch.j[blockIdx.y];
+    FS_WG_TRACE(8 + job.cls);
+    if ((int)blockIdx.x >= job.blocks) return;
+    if ((int)blockIdx.x < job.long_blocks)
+        long_segments_body<BF16, LPR, UNR, CHUNK>((int)blockIdx.x, job.grads, job.cperm, job.cslot, job.class_pos, job.cls,
+                                                  job.n, job.seg_offsets, job.cstart, job.u_t, job.table, job.state,
+                                                  job.num_rows, job.gvec, job.lr, job.eps, job.reduced, job.part_head,
+                                                  job.part_last, job.cnt_seg, job.cnt_sup, flags);
     else
-        short_rows_body<BF16, LPR, SU>((int)blockIdx.x - long_blocks, (int)gridDim.x - long_blocks, grads, n, recs,
-                                       n_rows_dev, (int64_t)n, table, state, num_rows, gvec, lr, eps, reduced, flags);
+        short_rows_body<BF16, LPR, SU>((int)blockIdx.x - job.long_blocks, job.blocks - job.long_blocks, job.grads, job.n,
+                                       job.recs, job.n_rows_dev, (int64_t)job.n, job.table, job.state, job.num_rows,
+                                       job.gvec, job.lr, job.eps, job.reduced, flags);
 }
 
+// `idx[0..m)`: the jobs of `jobs` (all of one dtype and row width, all with n > 0) that share this launch
 template <bool BF16, int LPR, int CHUNK>
-static void fused_launch(fs_ctx *ctx, int cls, const float *grads, int n, int gvec, const int32_t *cperm,
-                         const int32_t *cslot, const int32_t *class_pos, const int32_t *seg_offsets,
-                         const int32_t *cstart, const int64_t *u_t, void *table, float *state, int64_t num_rows,
-                         float lr, float eps, float *reduced, hipStream_t s, const int32_t *short_rec,
-                         const int64_t *n_rows_dev) {
+static void fused_launch(fs_ctx *ctx, int cls, const fs_class_pass_job *jobs, const int *idx, int m, hipStream_t s) {
     constexpr int GPW = kWave / LPR;
     constexpr int SU = FS_SHORT_UNR;
     constexpr int UNR = (CHUNK / GPW) < FS_FUSED_UNR ? ((CHUNK / GPW) < 1 ? 1 : (CHUNK / GPW)) : FS_FUSED_UNR;
     constexpr int CH = CHUNK < GPW ? GPW : CHUNK;             // at least one row group per chunk
-    // Both parts are sized for the worst case the host can know (every occurrence in a long
-    // segment / every occurrence a row of its own); the real sizes live on the device.
-    const int long_blocks = (int)ceil_div(ceil_div(n, CH), kFusedWaves);
-    int64_t short_blocks = ceil_div(n, (int64_t)GPW * SU * kFusedWaves);
-    if (short_blocks > FS_SHORT_MAX_BLOCKS) short_blocks = FS_SHORT_MAX_BLOCKS;   // grid-stride beyond this
-    hipLaunchKernelGGL((class_pass_kernel<BF16, LPR, UNR, CH, SU>), dim3((unsigned)(long_blocks + short_blocks)),
-                       dim3(kFusedWaves * kWave), 0, s, (const f32x4 *)grads, n, long_blocks, cperm, cslot, class_pos,
-                       cls, seg_offsets, cstart, u_t, short_rec, n_rows_dev, table, state, num_rows, gvec, lr, eps,
-                       (f32x4 *)reduced, ctx->fpart_head[cls], ctx->fpart_last[cls], ctx->fcounters[cls],
-                       ctx->fcounters_sup[cls], ctx->d_flags);
+    const size_t cap_chunks = (size_t)ceil_div(ctx->max_ids, kFusedMinChunk) + 2;
+    const size_t cap_doubles = cap_chunks * (size_t)ctx->max_dim;
+    int at = 0;
+    while (at < m) {
+        // as many jobs as fit the class's partial-row and counter space, each with its own stretch of it
+        class_pass_batch batch;
+        memset(&batch, 0, sizeof(batch));
+        size_t chunks = 0, doubles = 0;
+        int k = 0, blocks = 0;
+        for (; at + k < m && k < kMaxBatch; ++k) {
+            const fs_class_pass_job &in = jobs[idx[at + k]];
+            const int n = (int)in.n;
+            // Both parts are sized for the worst case the host can know (every occurrence in a long
+            // segment / every occurrence a row of its own); the real sizes live on the device.
+            const int long_blocks = (int)ceil_div(ceil_div(n, CH), kFusedWaves);
+            int64_t short_blocks = ceil_div(n, (int64_t)GPW * SU * kFusedWaves);
+            if (short_blocks > FS_SHORT_MAX_BLOCKS) short_blocks = FS_SHORT_MAX_BLOCKS;   // grid-stride beyond this
+            const size_t my_chunks = (size_t)long_blocks * kFusedWaves;
+            if (k > 0 && (chunks + my_chunks > cap_chunks || doubles + my_chunks * (size_t)in.dim > cap_doubles)) break;
+            class_pass_job &j = batch.j[k];
+            j.grads = (const f32x4 *)in.grads;
+            j.n = n; j.long_blocks = long_blocks; j.blocks = long_blocks + (int)short_blocks; j.cls = cls;
+            j.gvec = in.dim / 4; j.lr = in.lr; j.eps = in.eps;
+            j.cperm = in.cperm; j.cslot = in.cslot; j.class_pos = in.class_pos; j.seg_offsets = in.seg_offsets;
+            j.cstart = in.cstart; j.recs = in.short_rec; j.u_t = in.u_t; j.n_rows_dev = in.n_rows_dev;
+            j.table = in.table; j.state = in.state; j.num_rows = in.num_rows; j.reduced = (f32x4 *)in.reduced;
+            j.part_head = ctx->fpart_head[cls] + doubles;
+            j.part_last = ctx->fpart_last[cls] + doubles;
+            j.cnt_seg = ctx->fcounters[cls] + chunks;
+            j.cnt_sup = ctx->fcounters_sup[cls] + chunks;
+            chunks += my_chunks;
+            doubles += my_chunks * (size_t)in.dim;
+            blocks = j.blocks > blocks ? j.blocks : blocks;
+        }
+        hipLaunchKernelGGL((class_pass_kernel<BF16, LPR, UNR, CH, SU>), dim3((unsigned)blocks, (unsigned)k),
+                           dim3(kFusedWaves * kWave), 0, s, batch, ctx->d_flags);
+        at += k;
+    }
+}
+
+int launch_reduce_update_batch(fs_ctx *ctx, int cls, int count, const fs_class_pass_job *jobs, hipStream_t s) {
+    // one launch (or as few as fit) per dtype and row width; tables keep their order inside a launch
+    bool done[FS_MAX_STEP_TABLES];
+    if (count < 0 || count > FS_MAX_STEP_TABLES) return set_err(ctx, FS_EINVAL, "reduce+update: too many tables");
+    for (int k = 0; k < count; ++k) done[k] = jobs[k].n == 0;
+    for (int k0 = 0; k0 < count; ++k0) {
+        if (done[k0]) continue;
+        const bool bf = jobs[k0].dt == FS_BF16;
+        const int lpr = lanes_per_row(jobs[k0].dim / 4);
+        int idx[FS_MAX_STEP_TABLES], m = 0;
+        for (int k = k0; k < count; ++k)
+            if (!done[k] && (jobs[k].dt == FS_BF16) == bf && lanes_per_row(jobs[k].dim / 4) == lpr) {
+                idx[m++] = k;
+                done[k] = true;
+            }
+#define FS_CASE(L)                                                                              \
+    case L:                                                                                     \
+        if (cls == 0) {                                                                         \
+            if (bf) fused_launch<true, L, FS_FUSED_CHUNK_CO>(ctx, cls, jobs, idx, m, s);        \
+            else fused_launch<false, L, FS_FUSED_CHUNK_CO>(ctx, cls, jobs, idx, m, s);          \
+        } else {                                                                                \
+            if (bf) fused_launch<true, L, FS_FUSED_CHUNK_EX>(ctx, cls, jobs, idx, m, s);        \
+            else fused_launch<false, L, FS_FUSED_CHUNK_EX>(ctx, cls, jobs, idx, m, s);          \
+        }                                                                                       \
+        break;
+        switch (lpr) {
+            FS_CASE(1) FS_CASE(2) FS_CASE(4) FS_CASE(8) FS_CASE(16) FS_CASE(32) FS_CASE(64)
+            default: return set_err(ctx, FS_EINVAL, "reduce+update: dim beyond 256");
+        }
+#undef FS_CASE
+    }
+    FS_LAUNCH_CHECK(ctx, "class_pass_kernel");
+    return FS_OK;
 }
 
 int launch_reduce_update(fs_ctx *ctx, int cls, const float *grads, int64_t n, int32_t dim, const int32_t *cperm,
@@ -608,29 +686,9 @@ int launch_reduce_update(fs_ctx *ctx, int cls, const float *grads, int64_t n, in
                          const int32_t *cstart, const int64_t *u_t, void *table, int dt, float *state,
                          int64_t num_rows, float lr, float eps, float *reduced, hipStream_t s,
                          const int32_t *short_rec, const int64_t *n_rows_dev) {
-    if (n == 0) return FS_OK;
-    const int gvec = dim / 4;
-    const bool bf = dt == FS_BF16;
-#define FS_ARGS ctx, cls, grads, (int)n, gvec, cperm, cslot, class_pos, seg_offsets, cstart, u_t, table, state, num_rows, \
-                lr, eps, reduced, s, short_rec, n_rows_dev
-#define FS_CASE(L)                                                                   \
-    case L:                                                                          \
-        if (cls == 0) {                                                              \
-            if (bf) fused_launch<true, L, FS_FUSED_CHUNK_CO>(FS_ARGS);               \
-            else fused_launch<false, L, FS_FUSED_CHUNK_CO>(FS_ARGS);                 \
-        } else {                                                                     \
-            if (bf) fused_launch<true, L, FS_FUSED_CHUNK_EX>(FS_ARGS);               \
-            else fused_launch<false, L, FS_FUSED_CHUNK_EX>(FS_ARGS);                 \
-        }                                                                            \
-        break;
-    switch (lanes_per_row(gvec)) {
-        FS_CASE(1) FS_CASE(2) FS_CASE(4) FS_CASE(8) FS_CASE(16) FS_CASE(32) FS_CASE(64)
-        default: return set_err(ctx, FS_EINVAL, "reduce+update: dim beyond 256");
-    }
-#undef FS_CASE
-#undef FS_ARGS
-    FS_LAUNCH_CHECK(ctx, "class_pass_kernel");
-    return FS_OK;
+    const fs_class_pass_job job = {grads, n, dim, cperm, cslot, class_pos, seg_offsets, cstart, u_t, table, dt, state,
+                                   num_rows, lr, eps, reduced, short_rec, n_rows_dev};
+    return launch_reduce_update_batch(ctx, cls, 1, &job, s);
 }
 
 FS_TRACE_SETTER(fused)

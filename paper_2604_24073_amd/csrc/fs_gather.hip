@@ -17,24 +17,43 @@
 
 namespace fs {
 
+// one gather of a launch shared by several tables of one row width (blockIdx.y picks the table)
+struct gather_dev_job {
+    const u32x4 *table;
+    int64_t num_rows;
+    const int64_t *values, *offsets;
+    int64_t batch, n;
+    u32x4 *out;
+    int granules, blocks;
+};
+struct gather_dev_batch {
+    gather_dev_job j[kMaxBatch];
+};
+
 template <int LPR, int UNR>
-__global__ __launch_bounds__(256) void gather_kernel(const u32x4 *__restrict__ table, int64_t num_rows,
-                                                     int granules, const int64_t *__restrict__ values,
-                                                     const int64_t *__restrict__ offsets, int64_t batch, int64_t n,
-                                                     u32x4 *__restrict__ out, int *__restrict__ flags) {
+__global__ __launch_bounds__(256) void gather_kernel(const gather_dev_batch jobs, int *__restrict__ flags) {
+    const gather_dev_job &job = jobs.j[blockIdx.y];
     FS_WG_TRACE(10);
+    if ((int)blockIdx.x >= job.blocks) return;
+    const u32x4 *__restrict__ table = job.table;
+    const int64_t num_rows = job.num_rows;
+    const int granules = job.granules;
+    const int64_t *__restrict__ values = job.values;
+    const int64_t *__restrict__ offsets = job.offsets;
+    const int64_t batch = job.batch, n = job.n;
+    u32x4 *__restrict__ out = job.out;
     constexpr int GPW = kWave / LPR;                  // rows per wavefront instruction
     constexpr int ROWS_PER_WAVE = GPW * UNR;
     const int lane = threadIdx.x & (kWave - 1);
     const int grp = lane / LPR;
     const int lig = lane % LPR;
     const int64_t wave = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
-    const int64_t waves = (int64_t)gridDim.x * (blockDim.x / kWave);
+    const int64_t waves = (int64_t)job.blocks * (blockDim.x / kWave);
 
     // offsets validation rides along (grid-stride over the batch; almost free)
     if (offsets != nullptr) {
         const int64_t gtid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-        const int64_t gsz = (int64_t)gridDim.x * blockDim.x;
+        const int64_t gsz = (int64_t)job.blocks * blockDim.x;
         bool bad = false;
         for (int64_t b = gtid; b < batch; b += gsz) bad |= offsets[b + 1] < offsets[b];
         if (gtid == 0) bad |= (offsets[0] != 0) || (offsets[batch] != n);
@@ -68,34 +87,66 @@ __global__ __launch_bounds__(256) void gather_kernel(const u32x4 *__restrict__ t
 }
 
 template <int LPR>
-static void gather_launch(const void *table, int64_t num_rows, int granules, const int64_t *values,
-                          const int64_t *offsets, int64_t batch, int64_t n, void *out, int *flags, hipStream_t s) {
+static void gather_launch(const fs_gather_job *jobs, const int *idx, int m, int *flags, hipStream_t s) {
     // In-flight volume is a tuning knob: enough wavefronts x rows to saturate HBM, not so many that
     // the queueing delay they create slows the small latency-bound kernels running beside them.
     constexpr int UNR = FS_GATHER_UNR;
     constexpr int ROWS_PER_BLOCK = (kWave / LPR) * UNR * 4;
-    int64_t blocks = ceil_div(n, ROWS_PER_BLOCK);
-    if (blocks > FS_GATHER_MAX_BLOCKS) blocks = FS_GATHER_MAX_BLOCKS;
-    hipLaunchKernelGGL((gather_kernel<LPR, UNR>), dim3((unsigned)blocks), dim3(256), 0, s, (const u32x4 *)table,
-                       num_rows, granules, values, offsets, batch, n, (u32x4 *)out, flags);
+    for (int at = 0; at < m; at += kMaxBatch) {
+        const int k = (m - at) < kMaxBatch ? (m - at) : kMaxBatch;
+        gather_dev_batch batch;
+        memset(&batch, 0, sizeof(batch));
+        // the tables of a launch share the chip: FS_GATHER_MAX_BLOCKS workgroups in all, by their sizes
+        int64_t total = 0;
+        for (int i = 0; i < k; ++i) total += jobs[idx[at + i]].n;
+        int blocks = 0;
+        for (int i = 0; i < k; ++i) {
+            const fs_gather_job &in = jobs[idx[at + i]];
+            gather_dev_job &j = batch.j[i];
+            int64_t b = ceil_div(in.n, ROWS_PER_BLOCK);
+            int64_t share = ceil_div((int64_t)FS_GATHER_MAX_BLOCKS * in.n, total);
+            if (share < 1) share = 1;
+            if (b > share) b = share;
+            j.table = (const u32x4 *)in.table; j.num_rows = in.num_rows; j.values = in.values; j.offsets = in.offsets;
+            j.batch = in.batch; j.n = in.n; j.out = (u32x4 *)in.out; j.granules = in.row_bytes / 16; j.blocks = (int)b;
+            blocks = j.blocks > blocks ? j.blocks : blocks;
+        }
+        hipLaunchKernelGGL((gather_kernel<LPR, UNR>), dim3((unsigned)blocks, (unsigned)k), dim3(256), 0, s, batch, flags);
+    }
+}
+
+int launch_gather_batch(fs_ctx *ctx, int count, const fs_gather_job *jobs, hipStream_t s) {
+    bool done[FS_MAX_STEP_TABLES];
+    if (count < 0 || count > FS_MAX_STEP_TABLES) return set_err(ctx, FS_EINVAL, "gather: too many tables");
+    for (int k = 0; k < count; ++k) done[k] = jobs[k].n == 0;
+    for (int k0 = 0; k0 < count; ++k0) {
+        if (done[k0]) continue;
+        const int lpr = lanes_per_row(jobs[k0].row_bytes / 16);
+        int idx[FS_MAX_STEP_TABLES], m = 0;
+        for (int k = k0; k < count; ++k)
+            if (!done[k] && lanes_per_row(jobs[k].row_bytes / 16) == lpr) {
+                idx[m++] = k;
+                done[k] = true;
+            }
+        switch (lpr) {
+            case 1: gather_launch<1>(jobs, idx, m, ctx->d_flags, s); break;
+            case 2: gather_launch<2>(jobs, idx, m, ctx->d_flags, s); break;
+            case 4: gather_launch<4>(jobs, idx, m, ctx->d_flags, s); break;
+            case 8: gather_launch<8>(jobs, idx, m, ctx->d_flags, s); break;
+            case 16: gather_launch<16>(jobs, idx, m, ctx->d_flags, s); break;
+            case 32: gather_launch<32>(jobs, idx, m, ctx->d_flags, s); break;
+            case 64: gather_launch<64>(jobs, idx, m, ctx->d_flags, s); break;
+            default: return set_err(ctx, FS_EINVAL, "gather: row wider than 1024 bytes");
+        }
+    }
+    FS_LAUNCH_CHECK(ctx, "gather_kernel");
+    return FS_OK;
 }
 
 int launch_gather(fs_ctx *ctx, const void *table, int64_t num_rows, int row_bytes, const int64_t *values,
                   const int64_t *offsets, int64_t batch, int64_t n, void *out, hipStream_t s) {
-    if (n == 0) return FS_OK;
-    const int granules = row_bytes / 16;
-    switch (lanes_per_row(granules)) {
-        case 1: gather_launch<1>(table, num_rows, granules, values, offsets, batch, n, out, ctx->d_flags, s); break;
-        case 2: gather_launch<2>(table, num_rows, granules, values, offsets, batch, n, out, ctx->d_flags, s); break;
-        case 4: gather_launch<4>(table, num_rows, granules, values, offsets, batch, n, out, ctx->d_flags, s); break;
-        case 8: gather_launch<8>(table, num_rows, granules, values, offsets, batch, n, out, ctx->d_flags, s); break;
-        case 16: gather_launch<16>(table, num_rows, granules, values, offsets, batch, n, out, ctx->d_flags, s); break;
-        case 32: gather_launch<32>(table, num_rows, granules, values, offsets, batch, n, out, ctx->d_flags, s); break;
-        case 64: gather_launch<64>(table, num_rows, granules, values, offsets, batch, n, out, ctx->d_flags, s); break;
-        default: return set_err(ctx, FS_EINVAL, "gather: row wider than 1024 bytes");
-    }
-    FS_LAUNCH_CHECK(ctx, "gather_kernel");
-    return FS_OK;
+    const fs_gather_job job = {table, num_rows, row_bytes, values, offsets, batch, n, out};
+    return launch_gather_batch(ctx, 1, &job, s);
 }
 
 // ---- hash initialiser (input generator; mirrors the rule of the synthetic workloads) --------

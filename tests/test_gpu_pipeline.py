@@ -220,11 +220,13 @@ def test_index_halves_of_different_tables_share_their_launches():
 
 @pytest.mark.parametrize("ahead", [True, False])
 def test_multi_table_step_matches_one_call_per_table(ahead):
-    """fs_prioritized_step_pipelined_multi over three tables (different rows, dims, dtypes, batch sizes), the index
+    """fs_prioritized_step_pipelined_multi over six tables (different rows, dims, dtypes, batch sizes), the index
     halves of all of them in shared launches two iterations ahead (or done by the calls themselves): tables,
     states and gathered rows bit for bit as from one pipelined call per table."""
     rng = np.random.default_rng(99)
-    specs = [(30000, 128, "f32", 300), (2000, 64, "bf16", 120), (50000, 32, "f32", 40)]
+    # three tables of one row width and two of another share their launches; the sixth is on its own
+    specs = [(30000, 128, "f32", 300), (2000, 64, "bf16", 120), (50000, 128, "f32", 40), (7000, 128, "f32", 500),
+             (900, 64, "bf16", 200), (50000, 32, "f32", 40)]
     T = 6
     ctx = fs.Context(max_ids=20000, max_dim=128)
     tabs = []
