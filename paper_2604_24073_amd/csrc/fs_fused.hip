@@ -135,13 +135,17 @@ __device__ __forceinline__ void update_parked(const f32x4 *stage, const int64_t 
     }
 }
 
-__device__ __forceinline__ void store_piece(double *dst, const double (&t)[4]) {
+// A partial row in memory: four planes of gvec doubles (column 4*l + c of the row at plane c, place l), so
+// that each of the four instructions of a group of lanes writes or reads one contiguous run instead of
+// eight bytes out of every thirty-two (which the write-through stores paid for four times over).
+__device__ __forceinline__ void store_piece(double *row, int gvec, int lig, const double (&t)[4]) {
 #pragma unroll
-    for (int c = 0; c < 4; ++c) __hip_atomic_store(dst + c, t[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int c = 0; c < 4; ++c)
+        __hip_atomic_store(row + c * gvec + lig, t[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-__device__ __forceinline__ double load_piece(const double *src) {
-    return __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+__device__ __forceinline__ double load_piece(const double *row, int gvec, int lig, int c) {
+    return __hip_atomic_load(row + c * gvec + lig, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // t += part[c] for c = c_begin, c_begin + stride, ... <= c_last (four rows requested per round)
@@ -153,9 +157,9 @@ __device__ __forceinline__ void add_partial_rows(double (&t)[4], const double *p
         for (int j = 0; j < 4; ++j) {
             const int cj = c + j * stride;
             const bool ok = col_ok && cj <= c_last;
-            const double *src = part + (int64_t)(ok ? cj : c_begin) * dim + lig * 4;
+            const double *src = part + (int64_t)(ok ? cj : c_begin) * dim;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) h[j][i] = ok ? load_piece(src + i) : 0.0;
+            for (int i = 0; i < 4; ++i) h[j][i] = ok ? load_piece(src, dim / 4, lig, i) : 0.0;
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j)
@@ -257,7 +261,7 @@ __device__ __forceinline__ void long_segments_body(
 #pragma unroll
         for (int c = 0; c < 4; ++c) t[c] = across_groups<LPR>(acc[c]);
         if (nflush == 0 && !head_complete) {
-            if (grp == 0 && col_ok) store_piece(part_head + (int64_t)chunk * dim + lig * 4, t);
+            if (grp == 0 && col_ok) store_piece(part_head + (int64_t)chunk * dim, gvec, lig, t);
         } else {
             if (nparked < CAP) {
                 if (grp == 0 && col_ok)
@@ -331,7 +335,7 @@ __device__ __forceinline__ void long_segments_body(
         if (grp == 0 && col_ok) {
             // a chunk wholly inside one segment is a middle piece (head buffer); otherwise this
             // chunk is the FIRST piece of the segment that continues (last buffer)
-            store_piece(((nflush == 0 && !head_complete) ? part_head : part_last) + (int64_t)chunk * dim + lig * 4, t);
+            store_piece(((nflush == 0 && !head_complete) ? part_head : part_last) + (int64_t)chunk * dim, gvec, lig, t);
         }
     }
 
@@ -380,9 +384,9 @@ __device__ __forceinline__ void long_segments_body(
         if (lane == 0) __hip_atomic_store(&cnt_seg[cf], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         double t[4] = {0.0, 0.0, 0.0, 0.0};
         if (grp == 0 && col_ok) {
-            const double *x = part_last + (int64_t)cf * dim + lig * 4;
+            const double *x = part_last + (int64_t)cf * dim;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) t[i] = load_piece(x + i);
+            for (int i = 0; i < 4; ++i) t[i] = load_piece(x, gvec, lig, i);
         }
         add_partial_rows(t, part_head, dim, lig, col_ok, cf + 1 + grp * kFusedSuper, cl, GPW * kFusedSuper);
 #pragma unroll
@@ -404,7 +408,7 @@ __device__ __forceinline__ void long_segments_body(
         add_partial_rows(t, part_head, dim, lig, col_ok, sup_first + grp, sup_last, GPW);
 #pragma unroll
         for (int i = 0; i < 4; ++i) t[i] = across_groups<LPR>(t[i]);
-        if (grp == 0 && col_ok) store_piece(part_head + (int64_t)sup_first * dim + lig * 4, t);
+        if (grp == 0 && col_ok) store_piece(part_head + (int64_t)sup_first * dim, gvec, lig, t);
         const int n_sup = (c_last[0] - c_first[0] + kFusedSuper - 1) / kFusedSuper;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         int o2 = 0;
