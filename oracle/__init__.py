@@ -160,6 +160,18 @@ def rowwise_adagrad_update(table: np.ndarray, state: np.ndarray, rows: np.ndarra
     _check(rc, "fso_rowwise_adagrad_update")
 
 
+def gather_jagged_class(table: np.ndarray, values: np.ndarray, u_t: np.ndarray, which: int, out: np.ndarray) -> None:
+    """Lookup of the occurrences whose row is (which=1) / is not (which=0) in u_t, into ``out`` in place."""
+    assert table.ndim == 2 and table.flags.c_contiguous and out.flags.c_contiguous
+    assert out.dtype == table.dtype and out.shape == (values.shape[0], table.shape[1])
+    values = _c(values, np.int64)
+    u_t = _c(u_t, np.int64)
+    rc = lib().fso_gather_jagged_class(_p(table), ctypes.c_int64(table.shape[0]), ctypes.c_int32(table.shape[1]),
+                                       ctypes.c_int(dtype_code(table)), _p(values), ctypes.c_int64(values.shape[0]),
+                                       _p(u_t), ctypes.c_int64(u_t.shape[0]), ctypes.c_int(which), _p(out))
+    _check(rc, "fso_gather_jagged_class")
+
+
 # ---- one step of the prioritized schedule -------------------------------------------------
 SCHEDULES = ("co_then_ex", "ex_then_co", "all_at_once", "gather_between")
 
@@ -203,3 +215,50 @@ def step(table: np.ndarray, state: np.ndarray, layout_t: Dict[str, np.ndarray], 
     else:
         raise ValueError(schedule)
     return {"reduced": g, "split": sp, "layout_next": layout_next, "emb_next": emb}
+
+
+def run_two_phase(table: np.ndarray, state: np.ndarray, values_seq: Sequence[np.ndarray],
+                  grads_seq: Sequence[np.ndarray], lr: float, eps: float,
+                  prefetch_before_deferred: bool = False) -> List[np.ndarray]:
+    """Algorithm 2 over the iterations 0..T-1 of one shard, with its two-part lookup.
+
+    Iteration i owns batch ``values_seq[i]`` and receives ``grads_seq[i]``; ``values_seq`` has one
+    batch more than ``grads_seq`` has gradients or the same number (then the last iteration has no
+    lookahead).  In the order of the algorithm:
+
+      Forward(i+1's indices): finish update_embedding(I_ex^{i-1}, G_ex^{i-1}); compute_collision(I^i,
+        I^{i+1}); E_ex^{i+1} = Lookup(I_ex^{i+1})   - before the gradients of i exist;
+      Backward(G^i): E_co^{i+1} = update_embedding(I_co^i, G_co^i) - the rows as the update leaves them;
+      next Forward returns merge(E_ex^{i+1}, E_co^{i+1}).
+
+    Returns the merged input batch of every iteration 1..T (the batch of iteration 0 is a plain
+    lookup and not returned).  ``prefetch_before_deferred`` plants the mistake of fetching the
+    exclusive rows of i+1 before the deferred update of i-1 has landed (for the pins).
+    """
+    num_rows = table.shape[0]
+    layouts = [unique_ids(v, num_rows) for v in values_seq]
+    merged: List[np.ndarray] = []
+    pending = None                                   # (rows, slots, reduced) of the deferred update
+    for i, grads in enumerate(grads_seq):
+        lay = layouts[i]
+        has_next = i + 1 < len(values_seq)
+        nxt = layouts[i + 1]["unique"] if has_next else np.empty(0, dtype=np.int64)
+        sp = collision_split(lay["unique"], nxt)
+        batch = np.zeros((values_seq[i + 1].shape[0], table.shape[1]), dtype=table.dtype) if has_next else None
+        # Forward
+        if prefetch_before_deferred and has_next:
+            gather_jagged_class(table, values_seq[i + 1], lay["unique"], 0, batch)
+        if pending is not None:
+            rowwise_adagrad_update(table, state, pending[0], pending[1], pending[2], lr, eps)
+        if has_next and not prefetch_before_deferred:
+            gather_jagged_class(table, values_seq[i + 1], lay["unique"], 0, batch)
+        # Backward
+        g = segment_reduce_grads(grads, lay["perm"], lay["seg_offsets"])
+        rowwise_adagrad_update(table, state, sp["co"], sp["co_slot"], g, lr, eps)
+        if has_next:
+            gather_jagged_class(table, values_seq[i + 1], lay["unique"], 1, batch)
+            merged.append(batch)
+        pending = (sp["ex"], sp["ex_slot"], g)
+    if pending is not None:
+        rowwise_adagrad_update(table, state, pending[0], pending[1], pending[2], lr, eps)
+    return merged

@@ -22,6 +22,11 @@
  *                              fixes row-wise Adagrad (one accumulator per row that adds
  *                              the MEAN over columns of the squared summed gradient, eps
  *                              outside the square root, no decay, no clipping).
+ *   fso_gather_jagged_class    the lookup of Algorithm 2 taken in its two parts: Forward fetches the
+ *                              rows of I_ex^{i+1} ahead of time (they are untouched by iteration
+ *                              i), Backward returns the collision rows E_co^{i+1} as the priority
+ *                              update leaves them, and merge() puts both into one input batch.
+ *                              One call copies the occurrences of one of the two kinds of row.
  *
  * Pins (tests/test_oracle_pins.py): brute-force set logic on tiny inputs, dense one-hot
  * reduction, hand-computed Adagrad steps, element-wise Adagrad of a library on the
@@ -84,6 +89,36 @@ int fso_gather_jagged(const void *table, int64_t num_rows, int32_t dim, int dt,
         int64_t r = values[j];
         if (r < 0 || r >= num_rows) return FSO_ERANGE;
         memcpy((char *)out + (size_t)j * row_bytes, (const char *)table + (size_t)r * row_bytes, row_bytes);
+    }
+    return FSO_OK;
+}
+
+/* ---- O1b: lookup of one kind of row ---------------------------------------------------------- */
+/* For every occurrence j whose row values[j] IS (which = 1) or IS NOT (which = 0) a member of the
+ * ascending distinct list u_t: out[j, :] = table[values[j], :].  The other occurrences of `out` are
+ * left as they are: calling it for both kinds, in either order, on tables that agree on the rows
+ * each call reads, is merge() of Algorithm 2. */
+static int cmp_i64(const void *a, const void *b)
+{
+    int64_t x = *(const int64_t *)a, y = *(const int64_t *)b;
+    return (x > y) - (x < y);
+}
+
+int fso_gather_jagged_class(const void *table, int64_t num_rows, int32_t dim, int dt,
+                            const int64_t *values, int64_t n_values, const int64_t *u_t, int64_t n_t,
+                            int which, void *out)
+{
+    if (num_rows < 0 || dim <= 0 || n_values < 0 || n_t < 0) return FSO_EINVAL;
+    if (dt != FSO_F32 && dt != FSO_BF16) return FSO_EINVAL;
+    if (which != 0 && which != 1) return FSO_EINVAL;
+    for (int64_t i = 1; i < n_t; ++i) if (u_t[i] <= u_t[i - 1]) return FSO_EINVAL;
+    size_t row_bytes = (size_t)dim * elem_size(dt);
+    for (int64_t j = 0; j < n_values; ++j) {
+        int64_t r = values[j];
+        if (r < 0 || r >= num_rows) return FSO_ERANGE;
+        int member = n_t > 0 && bsearch(&r, u_t, (size_t)n_t, sizeof(int64_t), cmp_i64) != NULL;
+        if (member == which)
+            memcpy((char *)out + (size_t)j * row_bytes, (const char *)table + (size_t)r * row_bytes, row_bytes);
     }
     return FSO_OK;
 }

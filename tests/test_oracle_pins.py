@@ -361,3 +361,88 @@ def test_last_iteration_flushes_everything_in_one_pass():
     r = O.step(table, state, lay, g0, None, None, 0.01, 1e-8)
     assert len(r["split"]["co"]) == 0 and np.array_equal(r["split"]["ex"], lay["unique"])
     assert r["emb_next"] is None
+
+
+# ------------------------------------------------------------------ two-part lookup and merge
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_class_lookup_matches_brute_force(seed):
+    rng = np.random.default_rng(400 + seed)
+    rows, dim, n = 50, 4, 200
+    table = rng.standard_normal((rows, dim)).astype(np.float32)
+    values = rng.integers(0, rows, size=n).astype(np.int64)
+    u_t = np.unique(rng.integers(0, rows, size=20)).astype(np.int64)
+    members = [int(x) for x in u_t]
+    for which in (0, 1):
+        out = np.full((n, dim), -7.0, dtype=np.float32)
+        O.gather_jagged_class(table, values, u_t, which, out)
+        for j in range(n):
+            r = int(values[j])
+            if (r in members) == bool(which):
+                assert np.array_equal(out[j], table[r])
+            else:
+                assert np.all(out[j] == -7.0)
+    # both kinds into one buffer, in either order, is the whole lookup
+    for order in ((0, 1), (1, 0)):
+        out = np.full((n, dim), -7.0, dtype=np.float32)
+        for which in order:
+            O.gather_jagged_class(table, values, u_t, which, out)
+        assert np.array_equal(out, table[values])
+    with pytest.raises(O.OracleError):
+        O.gather_jagged_class(table, values, u_t[::-1].copy(), 0, np.zeros((n, dim), np.float32))
+    with pytest.raises(O.OracleError):
+        O.gather_jagged_class(table, np.array([rows], dtype=np.int64), u_t, 0, np.zeros((1, dim), np.float32))
+
+
+def _synchronous_baseline(table, state, values_seq, grads_seq, lr, eps):
+    """Fig. 1 of the paper on one shard: every update of iteration i lands, then iteration i+1 looks up."""
+    out = []
+    for i, g in enumerate(grads_seq):
+        lay = O.unique_ids(values_seq[i], table.shape[0])
+        red = O.segment_reduce_grads(g, lay["perm"], lay["seg_offsets"])
+        O.rowwise_adagrad_update(table, state, lay["unique"], np.arange(lay["unique"].shape[0], dtype=np.int32),
+                                 red, lr, eps)
+        if i + 1 < len(values_seq):
+            out.append(table[values_seq[i + 1]].copy())
+    return out
+
+
+@pytest.mark.parametrize("seed,tdtype", [(0, "f32"), (1, "f32"), (2, "bf16")])
+def test_two_part_lookup_keeps_parity_with_the_synchronous_baseline(seed, tdtype):
+    # Section 3.2: ordering only the collision rows keeps numerical parity with the synchronous run
+    rng = np.random.default_rng(500 + seed)
+    rows, dim, T = 40, 8, 6
+    w0 = (rng.standard_normal((rows, dim)) * 0.1).astype(np.float32)
+    if tdtype == "bf16":
+        w0 = O.f32_to_bf16_bits(w0)
+    values_seq = [rng.integers(0, rows, size=int(rng.integers(5, 60))).astype(np.int64) for _ in range(T + 1)]
+    grads_seq = [rng.standard_normal((values_seq[i].shape[0], dim)).astype(np.float32) for i in range(T)]
+    wa, sa = w0.copy(), np.zeros(rows, np.float32)
+    wb, sb = w0.copy(), np.zeros(rows, np.float32)
+    merged = O.run_two_phase(wa, sa, values_seq, grads_seq, 0.05, 1e-8)
+    want = _synchronous_baseline(wb, sb, values_seq, grads_seq, 0.05, 1e-8)
+    assert len(merged) == len(want) == T
+    for a, b in zip(merged, want):
+        assert np.array_equal(a, b)
+    assert np.array_equal(wa, wb) and np.array_equal(sa, sb)
+    # without a lookahead for the last iteration: one batch fewer comes back, same table
+    wc, sc = w0.copy(), np.zeros(rows, np.float32)
+    merged_c = O.run_two_phase(wc, sc, values_seq[:T], grads_seq, 0.05, 1e-8)
+    assert len(merged_c) == T - 1 and np.array_equal(wc, wb)
+
+
+def test_fetching_exclusive_rows_before_the_deferred_update_is_detected():
+    # row 3 is exclusive at iteration 0 (absent from batch 1) and looked up again by batch 2: its deferred
+    # update must land before Forward fetches the exclusive rows of batch 2
+    rows, dim = 6, 4
+    w0 = np.ones((rows, dim), np.float32)
+    values_seq = [np.array([3, 1], np.int64), np.array([1, 2], np.int64), np.array([3, 2], np.int64)]
+    grads_seq = [np.full((2, dim), 0.5, np.float32), np.full((2, dim), 0.25, np.float32)]
+    wa, sa = w0.copy(), np.zeros(rows, np.float32)
+    good = O.run_two_phase(wa, sa, values_seq, grads_seq, 0.1, 1e-8)
+    wb, sb = w0.copy(), np.zeros(rows, np.float32)
+    want = _synchronous_baseline(wb, sb, values_seq, grads_seq, 0.1, 1e-8)
+    assert all(np.array_equal(a, b) for a, b in zip(good, want))
+    wc, sc = w0.copy(), np.zeros(rows, np.float32)
+    bad = O.run_two_phase(wc, sc, values_seq, grads_seq, 0.1, 1e-8, prefetch_before_deferred=True)
+    assert not np.array_equal(bad[1], want[1])          # stale row 3 in the batch of iteration 2
+    assert np.array_equal(bad[1][1], want[1][1])        # row 2 (a collision row) is still fresh
