@@ -254,6 +254,9 @@ def main() -> int:
                     help="configurations with several tables per shard: the tables are stepped in G groups, each "
                          "with its own context and stream (1 = one call per step for all tables; 2 measured best: "
                          "two tables' passes side by side, and no more streams than the hardware has queues for)")
+    ap.add_argument("--two-part", action="store_true",
+                    help="the lookup in the two parts of Algorithm 2 (fs_prioritized_step_two_part_multi): exclusive "
+                         "rows of the batch after next fetched on the side stream, collision rows after the priority pass")
     ap.add_argument("--keep-reduced", action="store_true",
                     help="also write the summed gradients to memory in the timed steps (the step itself does not "
                          "need them there)")
@@ -325,6 +328,7 @@ def main() -> int:
     step_args = check_args if args.keep_reduced else [args_for(s, False) for s in range(period)]
     fs.fs_unique_ids(ctx, d_vals[0], tab.num_rows, out=layouts[0])
     graphs = None
+    arrays = {id(r): [fs.step_args_array([x]) for x in r] for r in (check_args, step_args)} if args.two_part else {}
 
     stepped = [False]
 
@@ -348,7 +352,11 @@ def main() -> int:
             elif pipelined:
                 dedup_ahead(s + 3)
                 index_half_ahead(s + D, records)
-                fs.fs_prioritized_step_pipelined(ctx, records[s % period], records[(s + 1) % period])
+                if args.two_part:
+                    arr = arrays[id(records)]
+                    fs.fs_prioritized_step_two_part_multi(ctx, arr[s % period], arr[(s + 1) % period])
+                else:
+                    fs.fs_prioritized_step_pipelined(ctx, records[s % period], records[(s + 1) % period])
                 stepped[0] = True
             else:
                 fs.fs_prioritized_step(ctx, records[s % period])
@@ -574,7 +582,7 @@ def main() -> int:
                                f"{cfg.length_rule} UIH lengths [{cfg.length_lo},{cfg.length_hi}], Zipf({tab.zipf_alpha}) IDs, "
                                "2 consecutive iterations stepped back and forth",
                    "ids_per_iteration": n, "unique_rows": u, "collision_rows_first_step": counts0[0]},
-        "schedule": args.mode + ((f"+index_half_ahead(batches of {K})" if index_ahead else "+dedup_ahead") if ahead else ""), "reduced_gradients_in_memory": bool(args.keep_reduced),
+        "schedule": args.mode + ((f"+index_half_ahead(batches of {K})" if index_ahead else "+dedup_ahead") if ahead else "") + ("+two_part_lookup" if args.two_part else ""), "reduced_gradients_in_memory": bool(args.keep_reduced),
         "class_occurrences": cls_pos, "class_rows": cls_rows, "host_enqueue_us_per_step": t_enq / args.steps * 1e6,
         "host_phase_us_per_step": host_phases,
         "step_algorithmic_bytes": step_bytes, "step_algorithmic_GBps": step_gbps,

@@ -139,6 +139,21 @@ int fs_rowwise_adagrad_update(fs_ctx *ctx, void *table, fs_dtype dt, float *stat
                               const int64_t *n_rows_dev, int64_t cap, const float *reduced,
                               float lr, float eps, fs_stream stream);
 
+/* One part of the lookup of Algorithm 2.  Forward fetches the rows of I_ex^{i+1} ahead of time (no
+ * update of iteration i touches them), Backward returns the collision rows E_co^{i+1} as the priority
+ * update leaves them, and merge() makes one input batch of both.  On one shard both parts land directly
+ * in the batch (`out`, [n, dim] in the order of `values`), so merge() is the two calls having finished:
+ *   which = 0: out[j, :] = table[values[j], :] for the occurrences j of rows NOT flagged (exclusive rows)
+ *   which = 1: the same for the occurrences of flagged rows (collision rows)
+ * where the flag of occurrence j is co_flag[inverse[j]]; the other occurrences of `out` are left alone.
+ * inverse [n] is the inverse map of fs_unique_ids(values); co_flag [n_unique] is the co_flag_t1 a step
+ * call wrote, or any byte per distinct row.  offsets (NULL allowed), range checks and errors as in
+ * fs_gather_jagged. */
+int fs_gather_jagged_class(fs_ctx *ctx, const void *table, int64_t num_rows, int32_t dim, fs_dtype dt,
+                           const int64_t *values, const int64_t *offsets, int64_t batch, int64_t n,
+                           const int32_t *inverse, const uint8_t *co_flag, int which, void *out,
+                           fs_stream stream);
+
 /* ---- the fused update path of the whole iteration ------------------------------------------ */
 
 /* Rows with at most this many occurrences in a batch take the short path of the fused update (all
@@ -212,6 +227,9 @@ typedef struct fs_step_args {
     /* outputs: reduced gradients [n_t, dim] capacity (OPTIONAL, may be NULL: the step does not need
      * them in memory), and gathered rows of t+1 [n_t1, dim] */
     float *reduced; void *emb_t1;
+    /* output (OPTIONAL, may be NULL; needed by the two-part lookup): [n_t1] bytes, for every row of u_t1
+     * 1 if it is a collision row (also in u_t), else 0; written with the split */
+    uint8_t *co_flag_t1;
 } fs_step_args;
 
 /* Iteration t on one shard, scheduled as Section 3.2 prescribes (strict write-read ordering
@@ -316,6 +334,24 @@ int fs_prioritized_step_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs
 #define FS_MAX_STEP_TABLES 16
 int fs_prioritized_step_pipelined_multi(fs_ctx *ctx, const fs_step_args *cur, const fs_step_args *next,
                                         int count, fs_stream stream);
+
+/* fs_prioritized_step_pipelined_multi with the lookup in its two parts, as Forward and Backward of
+ * Algorithm 2 have it:
+ *   `stream`      : wait for the side work of the previous call; priority pass of cur; lookup of the
+ *                   COLLISION rows of cur's lookahead batch (fs_gather_jagged_class, which = 1) - the
+ *                   only rows whose values the priority pass decides
+ *   side stream A : deferred pass of cur; index half of `next` (or the wait for it); then the lookup of
+ *                   the EXCLUSIVE rows of next's lookahead batch (which = 0) into next's emb_t1 - they are
+ *                   rows of neither cur's nor next's update sets, and every older deferred pass has landed
+ * so that between the arrival of the gradients and the complete input batch lie the priority pass and
+ * the collision rows only.  A lookahead batch of `cur` whose exclusive rows no previous call of this
+ * function fetched (first call of a run, or after fs_step_join / any other call on the context) gets its
+ * whole lookup on `stream`.  Every record with a lookahead batch needs co_flag_t1.  Results are those of
+ * fs_prioritized_step_pipelined_multi, bit for bit; emb_t1 of cur is complete when `stream` is.  The output
+ * batches of three consecutive iterations must be distinct buffers: while the caller consumes one, this call
+ * completes the next and the side stream already fills the one after. */
+int fs_prioritized_step_two_part_multi(fs_ctx *ctx, const fs_step_args *cur, const fs_step_args *next,
+                                       int count, fs_stream stream);
 
 /* Makes `stream` wait for everything earlier calls left running on the context's own streams
  * (side work of the last pipelined call, outstanding ahead-of-time dedups); no-op if there is

@@ -40,6 +40,7 @@ class fs_step_args(ctypes.Structure):
         ("counts_dev", c_vp),
         ("cperm", c_vp), ("cslot", c_vp), ("cstart", c_vp), ("class_pos_dev", c_vp), ("short_rec", c_vp),
         ("reduced", c_vp), ("emb_t1", c_vp),
+        ("co_flag_t1", c_vp),
     ]
 
 
@@ -70,6 +71,8 @@ def load_library() -> ctypes.CDLL:
         "fs_check_async": (ctypes.c_int, [c_vp, S]),
         "fs_ctx_workspace_bytes": (ctypes.c_size_t, [c_vp]),
         "fs_gather_jagged": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i32, ctypes.c_int, c_vp, c_vp, c_i64, c_i64, c_vp, S]),
+        "fs_gather_jagged_class": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i32, ctypes.c_int, c_vp, c_vp, c_i64, c_i64, c_vp,
+                                                  c_vp, ctypes.c_int, c_vp, S]),
         "fs_unique_ids": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i64, c_vp, c_vp, c_vp, c_vp, c_vp, S]),
         "fs_collision_split": (ctypes.c_int, [c_vp, c_vp, c_vp, c_vp, c_vp, c_i64, c_i64, c_vp, c_vp, c_vp, c_vp,
                                               c_vp, c_vp, c_vp, S]),
@@ -88,6 +91,8 @@ def load_library() -> ctypes.CDLL:
         "fs_step_forward_ahead_batch": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args), ctypes.c_int, S]),
         "fs_prioritized_step_pipelined_multi": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args),
                                                                 ctypes.POINTER(fs_step_args), ctypes.c_int, S]),
+        "fs_prioritized_step_two_part_multi": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args),
+                                                               ctypes.POINTER(fs_step_args), ctypes.c_int, S]),
         "fs_prioritized_step_pipelined": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args),
                                                          ctypes.POINTER(fs_step_args), S]),
         "fs_graph_capture_pipelined": (ctypes.c_int, [c_vp, ctypes.POINTER(fs_step_args), ctypes.POINTER(fs_step_args),
@@ -206,6 +211,18 @@ def fs_gather_jagged(ctx: Context, table: torch.Tensor, values: torch.Tensor, of
     rc = ctx.lib.fs_gather_jagged(ctx.handle, _ptr(table), table.shape[0], table.shape[1], table_dtype_code(table),
                                   _ptr(values), _ptr(offsets), batch, n, _ptr(out), _stream(stream))
     ctx.check(rc, "fs_gather_jagged")
+    return out
+
+
+def fs_gather_jagged_class(ctx: Context, table: torch.Tensor, values: torch.Tensor, offsets: Optional[torch.Tensor],
+                           inverse: torch.Tensor, co_flag: torch.Tensor, which: int, out: torch.Tensor,
+                           stream=None) -> torch.Tensor:
+    n = values.numel()
+    batch = 0 if offsets is None else offsets.numel() - 1
+    rc = ctx.lib.fs_gather_jagged_class(ctx.handle, _ptr(table), table.shape[0], table.shape[1],
+                                        table_dtype_code(table), _ptr(values), _ptr(offsets), batch, n, _ptr(inverse),
+                                        _ptr(co_flag), which, _ptr(out), _stream(stream))
+    ctx.check(rc, "fs_gather_jagged_class")
     return out
 
 
@@ -354,6 +371,12 @@ def fs_prioritized_step_pipelined_multi(ctx: Context, cur, nxt, stream=None) -> 
     ctx.check(rc, "fs_prioritized_step_pipelined_multi")
 
 
+def fs_prioritized_step_two_part_multi(ctx: Context, cur, nxt, stream=None) -> None:
+    """As fs_prioritized_step_pipelined_multi, the lookup taken in its two parts (records need co_flag_t1)."""
+    rc = ctx.lib.fs_prioritized_step_two_part_multi(ctx.handle, cur, nxt, len(cur), _stream(stream))
+    ctx.check(rc, "fs_prioritized_step_two_part_multi")
+
+
 def fs_ctx_host_times(ctx: Context, reset: bool = False):
     buf = (ctypes.c_double * 7)()
     ctx.check(ctx.lib.fs_ctx_host_times(ctx.handle, buf, 1 if reset else 0), "fs_ctx_host_times")
@@ -412,6 +435,7 @@ def alloc_split(cap_t: int, cap_t1: int, device) -> Dict[str, torch.Tensor]:
             "counts": torch.zeros(3, dtype=torch.int64, device=device),
             "cperm": i32(cap_t), "cslot": i32(cap_t), "cstart": i32(cap_t),
             "short_rec": i32(2 * SHORT_REC_INTS * cap_t),
+            "co_flag_t1": torch.empty(max(cap_t1, 1), dtype=torch.uint8, device=device),
             "class_pos": torch.zeros(2, dtype=torch.int32, device=device)}
 
 
@@ -446,5 +470,6 @@ def make_step_args(table: torch.Tensor, state: torch.Tensor, lr: float, eps: flo
     a.cperm, a.cslot, a.cstart = _ptr(split["cperm"]), _ptr(split["cslot"]), _ptr(split["cstart"])
     a.class_pos_dev = _ptr(split["class_pos"])
     a.short_rec = _ptr(split["short_rec"])
+    a.co_flag_t1 = _ptr(split.get("co_flag_t1"))
     a.reduced = _ptr(reduced)
     return a

@@ -337,6 +337,24 @@ int fs_gather_jagged(fs_ctx *ctx, const void *table, int64_t num_rows, int32_t d
     return launch_gather(ctx, table, num_rows, row_bytes, values, offsets, batch, n_values, out, as_stream(stream));
 }
 
+int fs_gather_jagged_class(fs_ctx *ctx, const void *table, int64_t num_rows, int32_t dim, fs_dtype dt,
+                           const int64_t *values, const int64_t *offsets, int64_t batch, int64_t n_values,
+                           const int32_t *inverse, const uint8_t *co_flag, int which, void *out, fs_stream stream) {
+    if (!ctx) return FS_EINVAL;
+    FS_REQUIRE(ctx, dt == FS_F32 || dt == FS_BF16, "gather: unknown dtype");
+    FS_REQUIRE(ctx, dim_ok(dim, dt), "gather: dim must be a multiple of 4 (fp32) / 8 (bf16), at most FS_MAX_DIM");
+    FS_REQUIRE(ctx, num_rows >= 0 && batch >= 0 && n_values >= 0, "gather: negative size");
+    FS_REQUIRE(ctx, n_values <= (1ll << 31) - 1, "gather: more than 2^31-1 values");
+    FS_REQUIRE(ctx, which == 0 || which == 1, "gather: which must be 0 (exclusive rows) or 1 (collision rows)");
+    if (n_values == 0) return FS_OK;
+    FS_REQUIRE(ctx, table && values && out && inverse && co_flag, "gather: null pointer");
+    fs_gather_job job;
+    job.table = table; job.num_rows = num_rows; job.row_bytes = dim * (dt == FS_F32 ? 4 : 2); job.values = values;
+    job.offsets = offsets; job.batch = batch; job.n = n_values; job.out = out;
+    job.inverse = inverse; job.row_flag = co_flag; job.which = which;
+    return launch_gather_batch(ctx, 1, &job, as_stream(stream));
+}
+
 int fs_unique_ids(fs_ctx *ctx, const int64_t *ids, int64_t n, int64_t num_rows, int64_t *unique,
                   int32_t *seg_offsets, int32_t *perm, int32_t *inverse, int64_t *n_unique_dev, fs_stream stream) {
     if (!ctx) return FS_EINVAL;
@@ -589,7 +607,7 @@ int enqueue_index_work_batch(fs_ctx *ctx, int count, const fs_step_args *a, cons
         const bool t = have_t[k], t1 = have_t1[k];
         sj[k] = fs_split_job{x.u_t, t ? x.n_unique_t_dev : nullptr, x.u_t1, t1 ? x.n_unique_t1_dev : nullptr,
                              t ? x.n_t : 0, t1 ? x.n_t1 : 0, x.co, x.co_slot, x.ex, x.ex_slot, x.ex_next,
-                             x.ex_next_slot, x.counts_dev, t ? x.seg_offsets_t : nullptr};
+                             x.ex_next_slot, x.counts_dev, t ? x.seg_offsets_t : nullptr, t1 ? x.co_flag_t1 : nullptr};
         cj[k] = fs_class_job{x.perm_t, x.inverse_t, x.seg_offsets_t, t ? x.n_t : 0, t ? x.n_t : 0, x.cperm, x.cslot,
                              x.cstart, x.class_pos_dev, x.u_t, x.short_rec};
     }
@@ -629,15 +647,22 @@ int enqueue_class_pass(fs_ctx *ctx, const fs_step_args *a, int cls, hipStream_t 
     return enqueue_class_passes(ctx, a, &use, 1, cls, s, timing);
 }
 
-int enqueue_gathers(fs_ctx *ctx, const fs_step_args *a, const bool *use, int count, hipStream_t s) {
+// `part` (optional): per table -1 = the whole lookup, 0 / 1 = the exclusive / collision rows only
+int enqueue_gathers(fs_ctx *ctx, const fs_step_args *a, const bool *use, int count, hipStream_t s,
+                    const int *part = nullptr, bool timed = true) {
     fs_gather_job jobs[FS_MAX_STEP_TABLES];
     int m = 0;
     for (int k = 0; k < count; ++k)
-        if (use[k])
-            jobs[m++] = fs_gather_job{a[k].table, a[k].num_rows, a[k].dim * (a[k].dtype == FS_F32 ? 4 : 2), a[k].values_t1,
-                                      a[k].offsets_t1, a[k].batch_t1, a[k].n_t1, a[k].emb_t1};
+        if (use[k]) {
+            fs_gather_job &j = jobs[m++];
+            j = fs_gather_job{a[k].table, a[k].num_rows, a[k].dim * (a[k].dtype == FS_F32 ? 4 : 2), a[k].values_t1,
+                              a[k].offsets_t1, a[k].batch_t1, a[k].n_t1, a[k].emb_t1};
+            if (part && part[k] >= 0) {
+                j.inverse = a[k].inverse_t1; j.row_flag = a[k].co_flag_t1; j.which = part[k];
+            }
+        }
     if (m == 0) return FS_OK;
-    hipEvent_t *tg = timing_pair(ctx, FS_TIME_GATHER);
+    hipEvent_t *tg = timed ? timing_pair(ctx, FS_TIME_GATHER) : nullptr;
     if (tg) (void)hipEventRecord(tg[0], s);
     const int rc = launch_gather_batch(ctx, m, jobs, s);
     if (tg && rc == FS_OK) (void)hipEventRecord(tg[1], s);
@@ -658,6 +683,7 @@ struct side_work {
     fs_step_args cur[kMaxTables], next[kMaxTables];
     bool have_t[kMaxTables], has_next[kMaxTables], nxt_t[kMaxTables], nxt_t1[kMaxTables];
     fs_ahead *ahead[kMaxTables], *index_ahead[kMaxTables];
+    bool fetch_next[kMaxTables];    // two-part lookup: fetch the exclusive rows of next's lookahead batch
 };
 
 // Side stream A for one pipelined call: after the caller's earlier work (the gradients of `cur`), the
@@ -678,6 +704,12 @@ int enqueue_side_stream(fs_ctx *ctx, const side_work &w) {
         }
     }
     if (rc != FS_OK) return rc;
+    // Forward of Algorithm 2 ends with Lookup(I_ex^{i+1}): every deferred pass so far has landed on this
+    // stream, and no priority pass writes a row that is not a collision row
+    int part[kMaxTables];
+    for (int k = 0; k < w.count; ++k) part[k] = 0;
+    rc = enqueue_gathers(ctx, w.next, w.fetch_next, w.count, sa, part, false);
+    if (rc != FS_OK) return rc;
     FS_HIP(ctx, hipEventRecord(ctx->ev_side[w.parity], sa));
     return FS_OK;
 }
@@ -687,6 +719,7 @@ int enqueue_side_stream(fs_ctx *ctx, const side_work &w) {
 // registered: a later step may still name their buffers).
 int join_pending_work(fs_ctx *ctx, hipStream_t s) {
     const int wrc = workers_wait(ctx);
+    for (int k = 0; k < kMaxTables; ++k) ctx->fetched_emb[k] = nullptr;    // the caller may touch the table next
     if (ctx->side_pending) {
         ctx->side_pending = false;
         FS_HIP(ctx, hipStreamWaitEvent(s, ctx->ev_side[ctx->pipe_parity], 0));
@@ -956,8 +989,21 @@ int fs_prioritized_step_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs
     return fs_prioritized_step_pipelined_multi(ctx, cur, next, 1, stream);
 }
 
+static int pipelined_impl(fs_ctx *ctx, const fs_step_args *cur, const fs_step_args *next, int count, fs_stream stream,
+                          bool two_part);
+
 int fs_prioritized_step_pipelined_multi(fs_ctx *ctx, const fs_step_args *cur, const fs_step_args *next, int count,
                                         fs_stream stream) {
+    return pipelined_impl(ctx, cur, next, count, stream, false);
+}
+
+int fs_prioritized_step_two_part_multi(fs_ctx *ctx, const fs_step_args *cur, const fs_step_args *next, int count,
+                                       fs_stream stream) {
+    return pipelined_impl(ctx, cur, next, count, stream, true);
+}
+
+static int pipelined_impl(fs_ctx *ctx, const fs_step_args *cur, const fs_step_args *next, int count, fs_stream stream,
+                          bool two_part) {
     if (!ctx) return FS_EINVAL;
     FS_REQUIRE(ctx, cur && count >= 1 && count <= FS_MAX_STEP_TABLES, "pipelined step: 1..FS_MAX_STEP_TABLES tables");
     std::shared_ptr<side_work> w = std::make_shared<side_work>();
@@ -975,6 +1021,19 @@ int fs_prioritized_step_pipelined_multi(fs_ctx *ctx, const fs_step_args *cur, co
         w->cur[k] = cur[k];
         w->next[k] = next ? next[k] : cur[k];
         w->ahead[k] = w->index_ahead[k] = nullptr;
+        w->fetch_next[k] = two_part && next && w->nxt_t1[k];
+        if (two_part) {
+            FS_REQUIRE(ctx, !ctx->capturing, "two-part step: not while a graph is being captured");
+            FS_REQUIRE(ctx, !have_t1[k] || cur[k].co_flag_t1, "two-part step: co_flag_t1 missing");
+            FS_REQUIRE(ctx, !w->fetch_next[k] || next[k].co_flag_t1, "two-part step: co_flag_t1 missing (next)");
+        }
+    }
+    // which part of cur's lookup is left to do: the collision rows if the previous call fetched the rest
+    int part[kMaxTables];
+    for (int k = 0; k < count; ++k) {
+        const bool fetched = two_part && have_t1[k] && ctx->fetched_emb[k] == cur[k].emb_t1 &&
+                             ctx->fetched_values[k] == cur[k].values_t1 && ctx->fetched_n[k] == cur[k].n_t1;
+        part[k] = fetched ? 1 : -1;
     }
     hipStream_t sp = as_stream(stream);
     begin_step_timing(ctx);
@@ -1031,7 +1090,7 @@ int fs_prioritized_step_pipelined_multi(fs_ctx *ctx, const fs_step_args *cur, co
     const double h3 = now_us();
     // every priority pass before every gather: a gather may only read what its table's priority pass left
     if (rc == FS_OK) rc = enqueue_class_passes(ctx, cur, w->have_t, count, 0, sp, timing_pair(ctx, FS_TIME_UPDATE_CO));
-    if (rc == FS_OK) rc = enqueue_gathers(ctx, cur, have_t1, count, sp);
+    if (rc == FS_OK) rc = enqueue_gathers(ctx, cur, have_t1, count, sp, part);
     const double h4 = now_us();
     if (!w0) {
         const int src = side_job();
@@ -1045,6 +1104,12 @@ int fs_prioritized_step_pipelined_multi(fs_ctx *ctx, const fs_step_args *cur, co
     ctx->host_us[6] += 1.0;
     ctx->pipe_parity = p;
     ctx->side_pending = true;        // also after a failure: a posted job still records its event
+    for (int k = 0; k < kMaxTables; ++k) {
+        const bool f = rc == FS_OK && k < count && w->fetch_next[k];
+        ctx->fetched_emb[k] = f ? next[k].emb_t1 : nullptr;
+        ctx->fetched_values[k] = f ? next[k].values_t1 : nullptr;
+        ctx->fetched_n[k] = f ? next[k].n_t1 : 0;
+    }
     // a captured graph must end with every stream joined
     if (ctx->capturing && rc == FS_OK) rc = join_pending_work(ctx, sp);
     return rc;

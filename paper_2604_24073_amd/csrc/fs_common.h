@@ -92,6 +92,7 @@ struct fs_split_job {
     int32_t *ex_next_slot;
     int64_t *counts_dev;
     const int32_t *seg_offsets_t;   // optional; given, the per-tile occurrence counts the class order needs are left in the scratch
+    uint8_t *flag_t1_out = nullptr; // optional [cap_t1]: 1 where the row of u_t1 is also in u_t (a collision row), else 0
 };
 struct fs_class_job {
     const int32_t *perm, *inverse, *seg_offsets;
@@ -124,6 +125,11 @@ struct fs_gather_job {
     const int64_t *values, *offsets;
     int64_t batch, n;
     void *out;
+    // one part of the two-part lookup (optional): only the occurrences j with (row_flag[inverse[j]] != 0) ==
+    // (which != 0) are copied; which < 0 or a null pointer: every occurrence
+    const int32_t *inverse = nullptr;
+    const uint8_t *row_flag = nullptr;
+    int which = -1;
 };
 
 struct fs_ctx {
@@ -161,6 +167,11 @@ struct fs_ctx {
     int pipe_parity;          // event set used by the last pipelined call
     bool pfork_valid;         // host-side: ev_pfork[pipe_parity] has been recorded
     bool side_pending;        // host-side: side-stream work is in flight and not yet joined
+    // two-part lookup: the lookahead batches whose exclusive rows the last pipelined call fetched on the side
+    // stream (output buffer, IDs, count), per table; forgotten whenever anything else touches the context
+    const void *fetched_emb[FS_MAX_STEP_TABLES];
+    const void *fetched_values[FS_MAX_STEP_TABLES];
+    int64_t fetched_n[FS_MAX_STEP_TABLES];
     double host_us[7];        // host-side time spent in the phases of the pipelined call (measurement aid)
     struct fs_host *host;     // host threads and the table of outstanding ahead-of-time dedups
     bool use_worker;

@@ -11,6 +11,9 @@
 #ifndef FS_GATHER_UNR
 #define FS_GATHER_UNR 4
 #endif
+#ifndef FS_PART_CHUNK
+#define FS_PART_CHUNK 64
+#endif
 #ifndef FS_GATHER_MAX_BLOCKS
 #define FS_GATHER_MAX_BLOCKS 1024
 #endif
@@ -25,6 +28,9 @@ struct gather_dev_job {
     int64_t batch, n;
     u32x4 *out;
     int granules, blocks;
+    const int32_t *inverse;       // gather_part_kernel: occurrence -> slot of its row in the distinct list
+    const uint8_t *row_flag;      //                     slot -> 1 for a collision row
+    int which;                    //                     copy the occurrences whose flag equals this
 };
 struct gather_dev_batch {
     gather_dev_job j[kMaxBatch];
@@ -86,8 +92,102 @@ __global__ __launch_bounds__(256) void gather_kernel(const gather_dev_batch jobs
     if (oob) atomicOr(flags, kFlagRowRange);
 }
 
+
+// One part of the two-part lookup of Algorithm 2 (the rows Forward fetches ahead of time, or the collision
+// rows the priority update of Backward returns): only the occurrences whose row flag equals `which` are
+// copied, the output rows of the others are left alone.  A wavefront takes FS_PART_CHUNK consecutive occurrences, one
+// per lane and round (coalesced reads of the IDs, the inverse map and the byte flags), squeezes the ones
+// of its part into a list in LDS and then copies rows from that list exactly as the plain kernel does -
+// the row traffic stays as dense as if the other part did not exist.
+constexpr int kPartChunk = FS_PART_CHUNK;
+template <int LPR, int UNR>
+__global__ __launch_bounds__(256) void gather_part_kernel(const gather_dev_batch jobs, int *__restrict__ flags) {
+    const gather_dev_job &job = jobs.j[blockIdx.y];
+    FS_WG_TRACE(10);
+    if ((int)blockIdx.x >= job.blocks) return;
+    const u32x4 *__restrict__ table = job.table;
+    const int64_t num_rows = job.num_rows;
+    const int granules = job.granules;
+    const int64_t *__restrict__ values = job.values;
+    const int64_t *__restrict__ offsets = job.offsets;
+    const int32_t *__restrict__ inverse = job.inverse;
+    const uint8_t *__restrict__ row_flag = job.row_flag;
+    const bool want = job.which != 0;
+    const int64_t batch = job.batch, n = job.n;
+    u32x4 *__restrict__ out = job.out;
+    constexpr int GPW = kWave / LPR;
+    constexpr int ROWS_PER_WAVE = GPW * UNR;
+    constexpr int WAVES = 256 / kWave;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = threadIdx.x / kWave;
+    const int grp = lane / LPR;
+    const int lig = lane % LPR;
+    __shared__ int64_t l_id[WAVES][kPartChunk];
+    __shared__ int32_t l_pos[WAVES][kPartChunk];
+
+    if (offsets != nullptr) {
+        const int64_t gtid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+        const int64_t gsz = (int64_t)job.blocks * blockDim.x;
+        bool bad = false;
+        for (int64_t b = gtid; b < batch; b += gsz) bad |= offsets[b + 1] < offsets[b];
+        if (gtid == 0) bad |= (offsets[0] != 0) || (offsets[batch] != n);
+        if (bad) atomicOr(flags, kFlagOffsets);
+    }
+    bool oob = false;
+    const uint64_t lt = (1ull << lane) - 1ull;
+    const int64_t chunks = (n + kPartChunk - 1) / kPartChunk;
+    // every wavefront of the workgroup makes the same number of rounds (the barriers below are met by all)
+    for (int64_t c0 = (int64_t)blockIdx.x * WAVES; c0 < chunks; c0 += (int64_t)job.blocks * WAVES) {
+        const int64_t base = (c0 + w) * kPartChunk;
+        int count = 0;
+#pragma unroll
+        for (int q = 0; q < kPartChunk / kWave; ++q) {
+            const int64_t j = base + q * kWave + lane;
+            int64_t id = 0;
+            bool mine = false;
+            if (j < n) {
+                id = values[j];
+                mine = (row_flag[inverse[j]] != 0) == want;
+            }
+            const uint64_t m = __ballot(mine);
+            if (mine) {
+                const int at = count + __popcll(m & lt);
+                l_id[w][at] = id;
+                l_pos[w][at] = (int32_t)j;
+            }
+            count += __popcll(m);
+        }
+        __syncthreads();
+        for (int r0 = 0; r0 < count; r0 += ROWS_PER_WAVE) {
+            int64_t id[UNR];
+            int32_t pos[UNR];
+            bool live[UNR];
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+                const int k = r0 + u * GPW + grp;
+                live[u] = (k < count) && (lig < granules);
+                id[u] = live[u] ? l_id[w][k] : 0;
+                pos[u] = live[u] ? l_pos[w][k] : 0;
+            }
+            u32x4 v[UNR];
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+                const bool in = (id[u] >= 0) && (id[u] < num_rows);
+                oob |= live[u] && !in;
+                v[u] = u32x4{0u, 0u, 0u, 0u};
+                if (live[u] && in) v[u] = table[id[u] * granules + lig];
+            }
+#pragma unroll
+            for (int u = 0; u < UNR; ++u)
+                if (live[u]) __builtin_nontemporal_store(v[u], &out[(int64_t)pos[u] * granules + lig]);
+        }
+        __syncthreads();
+    }
+    if (oob) atomicOr(flags, kFlagRowRange);
+}
+
 template <int LPR>
-static void gather_launch(const fs_gather_job *jobs, const int *idx, int m, int *flags, hipStream_t s) {
+static void gather_launch(const fs_gather_job *jobs, const int *idx, int m, bool part, int *flags, hipStream_t s) {
     // In-flight volume is a tuning knob: enough wavefronts x rows to saturate HBM, not so many that
     // the queueing delay they create slows the small latency-bound kernels running beside them.
     constexpr int UNR = FS_GATHER_UNR;
@@ -109,11 +209,17 @@ static void gather_launch(const fs_gather_job *jobs, const int *idx, int m, int 
             if (b > share) b = share;
             j.table = (const u32x4 *)in.table; j.num_rows = in.num_rows; j.values = in.values; j.offsets = in.offsets;
             j.batch = in.batch; j.n = in.n; j.out = (u32x4 *)in.out; j.granules = in.row_bytes / 16; j.blocks = (int)b;
+            j.inverse = in.inverse; j.row_flag = in.row_flag; j.which = in.which;
             blocks = j.blocks > blocks ? j.blocks : blocks;
         }
-        hipLaunchKernelGGL((gather_kernel<LPR, UNR>), dim3((unsigned)blocks, (unsigned)k), dim3(256), 0, s, batch, flags);
+        if (part)
+            hipLaunchKernelGGL((gather_part_kernel<LPR, UNR>), dim3((unsigned)blocks, (unsigned)k), dim3(256), 0, s, batch, flags);
+        else
+            hipLaunchKernelGGL((gather_kernel<LPR, UNR>), dim3((unsigned)blocks, (unsigned)k), dim3(256), 0, s, batch, flags);
     }
 }
+
+static bool is_part(const fs_gather_job &j) { return j.which >= 0 && j.inverse != nullptr && j.row_flag != nullptr; }
 
 int launch_gather_batch(fs_ctx *ctx, int count, const fs_gather_job *jobs, hipStream_t s) {
     bool done[FS_MAX_STEP_TABLES];
@@ -122,20 +228,21 @@ int launch_gather_batch(fs_ctx *ctx, int count, const fs_gather_job *jobs, hipSt
     for (int k0 = 0; k0 < count; ++k0) {
         if (done[k0]) continue;
         const int lpr = lanes_per_row(jobs[k0].row_bytes / 16);
+        const bool part = is_part(jobs[k0]);
         int idx[FS_MAX_STEP_TABLES], m = 0;
         for (int k = k0; k < count; ++k)
-            if (!done[k] && lanes_per_row(jobs[k].row_bytes / 16) == lpr) {
+            if (!done[k] && lanes_per_row(jobs[k].row_bytes / 16) == lpr && is_part(jobs[k]) == part) {
                 idx[m++] = k;
                 done[k] = true;
             }
         switch (lpr) {
-            case 1: gather_launch<1>(jobs, idx, m, ctx->d_flags, s); break;
-            case 2: gather_launch<2>(jobs, idx, m, ctx->d_flags, s); break;
-            case 4: gather_launch<4>(jobs, idx, m, ctx->d_flags, s); break;
-            case 8: gather_launch<8>(jobs, idx, m, ctx->d_flags, s); break;
-            case 16: gather_launch<16>(jobs, idx, m, ctx->d_flags, s); break;
-            case 32: gather_launch<32>(jobs, idx, m, ctx->d_flags, s); break;
-            case 64: gather_launch<64>(jobs, idx, m, ctx->d_flags, s); break;
+            case 1: gather_launch<1>(jobs, idx, m, part, ctx->d_flags, s); break;
+            case 2: gather_launch<2>(jobs, idx, m, part, ctx->d_flags, s); break;
+            case 4: gather_launch<4>(jobs, idx, m, part, ctx->d_flags, s); break;
+            case 8: gather_launch<8>(jobs, idx, m, part, ctx->d_flags, s); break;
+            case 16: gather_launch<16>(jobs, idx, m, part, ctx->d_flags, s); break;
+            case 32: gather_launch<32>(jobs, idx, m, part, ctx->d_flags, s); break;
+            case 64: gather_launch<64>(jobs, idx, m, part, ctx->d_flags, s); break;
             default: return set_err(ctx, FS_EINVAL, "gather: row wider than 1024 bytes");
         }
     }
@@ -145,7 +252,9 @@ int launch_gather_batch(fs_ctx *ctx, int count, const fs_gather_job *jobs, hipSt
 
 int launch_gather(fs_ctx *ctx, const void *table, int64_t num_rows, int row_bytes, const int64_t *values,
                   const int64_t *offsets, int64_t batch, int64_t n, void *out, hipStream_t s) {
-    const fs_gather_job job = {table, num_rows, row_bytes, values, offsets, batch, n, out};
+    fs_gather_job job;
+    job.table = table; job.num_rows = num_rows; job.row_bytes = row_bytes; job.values = values; job.offsets = offsets;
+    job.batch = batch; job.n = n; job.out = out;
     return launch_gather_batch(ctx, 1, &job, s);
 }
 

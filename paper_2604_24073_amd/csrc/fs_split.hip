@@ -384,7 +384,7 @@ int launch_split_batch(fs_ctx *ctx, int count, const fs_split_job *jobs, hipStre
         // With cap_t == 0 a single (empty) tile on side t keeps the count logic in one place.
         j.tiles_t = tiles_t > 0 ? tiles_t : 1;
         j.tiles_t1 = (int)ceil_div(in.cap_t1, kScanTile);
-        j.flag_t = ws.flag_t; j.flag_t1 = ws.flag_t1; j.tile_cnt = ws.cnt;
+        j.flag_t = ws.flag_t; j.flag_t1 = in.flag_t1_out ? in.flag_t1_out : ws.flag_t1; j.tile_cnt = ws.cnt;
         j.co = in.co; j.co_slot = in.co_slot; j.ex = in.ex; j.ex_slot = in.ex_slot;
         j.ex_next = in.ex_next; j.ex_next_slot = in.ex_next_slot; j.counts_dev = in.counts_dev;
         j.seg_offsets_t = in.seg_offsets_t;

@@ -7,7 +7,7 @@ import torch
 
 import oracle as O
 import paper_2604_24073_amd as fs
-from helpers import assert_rows_close, dev, table_to_dev, table_to_host
+from helpers import assert_bf16_within_1ulp, assert_close_f32, assert_rows_close, dev, table_to_dev, table_to_host
 from test_gpu_parity import compare_runs, rand_table, run_steps_gpu, run_steps_oracle, zipf_ids
 
 pytestmark = pytest.mark.gpu
@@ -29,7 +29,7 @@ def make_its(rng, rows, dim, n_iter, users=40, max_len=300):
     return its
 
 
-def run_pipelined(ctx, table, state, its, lr, eps, ahead=False, sync_each=True):
+def run_pipelined(ctx, table, state, its, lr, eps, ahead=False, sync_each=True, two_part=False, disturb=None):
     """ahead: True / "last_step": dedup every batch with fs_unique_ids_ahead, three batches before the
     iteration that gathers it (five layout buffers in rotation; "last_step": ordered after the start
     of the previous pipelined call instead of the stream's current position, six layout buffers).
@@ -38,7 +38,10 @@ def run_pipelined(ctx, table, state, its, lr, eps, ahead=False, sync_each=True):
     "batchK" / "batchK_last_step": the index halves of K consecutive iterations in shared launches
     (fs_step_forward_ahead_batch), issued D = K + 1 iterations before the first of them is stepped
     (K + D + 3 layouts, K + D + 2 split bundles).
-    sync_each=False: no wait between the calls."""
+    sync_each=False: no wait between the calls.
+    two_part: fs_prioritized_step_two_part_multi (exclusive rows of the lookahead batch fetched by the call
+    before, three output batches in rotation); disturb: iteration before whose call the pipeline is joined
+    and the already fetched part of its output batch overwritten (the call must then redo the whole lookup)."""
     batch = int(ahead[5]) if isinstance(ahead, str) and ahead.startswith("batch") else 0
     index_ahead = ahead in ("index", "index_last_step")
     last_step = isinstance(ahead, str) and ahead.endswith("last_step")
@@ -59,14 +62,15 @@ def run_pipelined(ctx, table, state, its, lr, eps, ahead=False, sync_each=True):
     layouts = [fs.alloc_layout(nmax, "cuda") for _ in range(L)]
     splits = [fs.alloc_split(nmax, nmax, "cuda") for _ in range(P)]
     reduced = [torch.empty((nmax, dim), dtype=torch.float32, device="cuda") for _ in range(2)]
-    embs = [torch.empty((nmax, dim), dtype=d_table.dtype, device="cuda") for _ in range(2)]
+    E = 3 if two_part else 2
+    embs = [torch.empty((nmax, dim), dtype=d_table.dtype, device="cuda") for _ in range(E)]
 
     def args_for(t):
         lay_t = dict(layouts[t % L]); lay_t["n"] = n[t]
         last = t == T - 1
         return fs.make_step_args(d_table, d_state, lr, eps, lay_t, d_grads[t], None if last else d_vals[t + 1],
                                  None if last else d_offs[t + 1], None if last else layouts[(t + 1) % L],
-                                 splits[t % P], reduced[t % 2], None if last else embs[t % 2])
+                                 splits[t % P], reduced[t % 2], None if last else embs[t % E])
 
     stepped = [False]
 
@@ -103,7 +107,15 @@ def run_pipelined(ctx, table, state, its, lr, eps, ahead=False, sync_each=True):
         dedup_ahead(t + 3)
         index_half_ahead(t + 2)
         index_batch_ahead(t + D)
-        fs.fs_prioritized_step_pipelined(ctx, all_args[t], nxt)
+        if two_part:
+            if disturb == t:
+                fs.fs_step_join(ctx)
+                torch.cuda.synchronize()
+                embs[t % E].view(torch.int16 if d_table.dtype == torch.bfloat16 else torch.int32).fill_(-1)
+            fs.fs_prioritized_step_two_part_multi(ctx, fs.step_args_array([all_args[t]]),
+                                                  fs.step_args_array([nxt]) if nxt is not None else None)
+        else:
+            fs.fs_prioritized_step_pipelined(ctx, all_args[t], nxt)
         stepped[0] = True
         if not sync_each:
             continue
@@ -111,7 +123,7 @@ def run_pipelined(ctx, table, state, its, lr, eps, ahead=False, sync_each=True):
         u = int(layouts[t % L]["n_unique"].item())
         rec = {"reduced": reduced[t % 2][:u].cpu().numpy(), "counts": splits[t % P]["counts"].cpu().numpy()}
         if t + 1 < T:
-            rec["emb_next"] = table_to_host(embs[t % 2][:n[t + 1]])
+            rec["emb_next"] = table_to_host(embs[t % E][:n[t + 1]])
         outs.append(rec)
     assert fs.fs_check_async(ctx) == fs.FS_OK
     return d_table, d_state, outs
@@ -155,6 +167,76 @@ def test_pipelined_steps_match_sequential_calls_bitwise(dtype, dim):
             assert a["reduced"].tobytes() == b["reduced"].tobytes(), what
             if "emb_next" in a:
                 assert a["emb_next"].tobytes() == b["emb_next"].tobytes(), what
+    ctx.close()
+
+
+@pytest.mark.parametrize("dtype,dim", [("f32", 128), ("bf16", 128), ("f32", 32)])
+def test_two_part_lookup_steps_match_the_plain_pipeline_and_the_oracle(dtype, dim):
+    """Algorithm 2 with its lookup in two parts (exclusive rows of batch t+2 fetched on the side stream during
+    iteration t, collision rows of batch t+1 after the priority pass): tables, states and merged batches bit for
+    bit as from the one-part pipeline, which in turn matches the oracle; the oracle's own two-part run agrees."""
+    ctx = fs.Context(max_ids=20000, max_dim=256)
+    rng = np.random.default_rng(4242)
+    rows = 30000
+    table = rand_table(rng, rows, dim, dtype)
+    state = np.zeros(rows, np.float32)
+    its = make_its(rng, rows, dim, 7)
+    ts, ss, os_ = run_pipelined(ctx, table, state, its, 0.01, 1e-8)
+    view = torch.int16 if dtype == "bf16" else torch.int32
+    # the oracle, taking the lookup in two parts as the algorithm does
+    wo, so = table.copy(), state.copy()
+    merged = O.run_two_phase(wo, so, [it.values for it in its], [it.grads for it in its], 0.01, 1e-8)
+    for ahead, sync_each, threaded, disturb in ((False, True, True, None), (False, False, True, None),
+                                                ("index", True, True, None), ("batch2", False, True, None),
+                                                ("batch2_last_step", False, False, None), ("batch3_last_step", True, True, None),
+                                                (True, True, False, None), ("batch2", True, True, 3), (False, True, True, 1)):
+        ctx.lib.fs_ctx_set_threaded_enqueue(ctx.handle, 1 if threaded else 0)
+        ta, sa, oa = run_pipelined(ctx, table, state, its, 0.01, 1e-8, ahead=ahead, sync_each=sync_each, two_part=True,
+                                   disturb=disturb)
+        what = f"ahead={ahead} sync_each={sync_each} threaded={threaded} disturb={disturb}"
+        assert torch.equal(ta.view(view), ts.view(view)), what
+        assert torch.equal(sa, ss), what
+        for t, (a, b) in enumerate(zip(oa, os_)):
+            assert a["reduced"].tobytes() == b["reduced"].tobytes(), what
+            assert a["counts"].tolist() == b["counts"].tolist(), what
+            if "emb_next" in a:
+                assert a["emb_next"].tobytes() == b["emb_next"].tobytes(), (what, t)
+                if dtype == "f32":
+                    assert_close_f32(a["emb_next"], merged[t], f"merged batch of iteration {t + 1}")
+                else:
+                    assert_bf16_within_1ulp(a["emb_next"], merged[t], f"merged batch of iteration {t + 1}")
+    ctx.lib.fs_ctx_set_threaded_enqueue(ctx.handle, 1)
+    ctx.close()
+
+
+@pytest.mark.parametrize("dtype,dim,n", [("f32", 128, 5000), ("bf16", 64, 3001), ("f32", 256, 700), ("f32", 8, 0)])
+def test_class_lookup_matches_oracle(dtype, dim, n):
+    """fs_gather_jagged_class: each part copies exactly the occurrences of its kind of row and leaves the
+    others alone; both parts together are the whole lookup."""
+    rng = np.random.default_rng(17 + n)
+    rows = 4000
+    ctx = fs.Context(max_ids=max(n, 16), max_dim=dim)
+    table = rand_table(rng, rows, dim, dtype)
+    values = zipf_ids(rng, n, rows, a=1.1) if n else np.empty(0, np.int64)
+    u_t = np.unique(zipf_ids(rng, 3000, rows, a=1.1))
+    lay = O.unique_ids(values, rows)
+    flag = np.isin(lay["unique"], u_t).astype(np.uint8)
+    d_table, d_values = table_to_dev(table), dev(values)
+    d_inv, d_flag = dev(lay["inverse"].astype(np.int32)), dev(flag if flag.size else np.zeros(1, np.uint8))
+    view = torch.int16 if dtype == "bf16" else torch.int32
+    for order in ((0,), (1,), (0, 1), (1, 0)):
+        out = torch.empty((n, dim), dtype=d_table.dtype, device="cuda")
+        out.view(view).fill_(-3)
+        want = table_to_host(out).copy()
+        for which in order:
+            fs.fs_gather_jagged_class(ctx, d_table, d_values, None, d_inv, d_flag, which, out)
+            O.gather_jagged_class(table, values, u_t, which, want)
+        assert fs.fs_check_async(ctx) == fs.FS_OK, ctx.last_error()
+        assert table_to_host(out).tobytes() == want.tobytes(), order
+    if n:
+        with pytest.raises(fs.FreeScaleError) as e:
+            fs.fs_gather_jagged_class(ctx, d_table, d_values, None, d_inv, d_flag, 2, out)
+        assert e.value.code == fs.FS_EINVAL
     ctx.close()
 
 
@@ -218,11 +300,12 @@ def test_index_halves_of_different_tables_share_their_launches():
     ctx.close()
 
 
-@pytest.mark.parametrize("ahead", [True, False])
-def test_multi_table_step_matches_one_call_per_table(ahead):
+@pytest.mark.parametrize("ahead,two_part", [(True, False), (False, False), (True, True), (False, True)])
+def test_multi_table_step_matches_one_call_per_table(ahead, two_part):
     """fs_prioritized_step_pipelined_multi over six tables (different rows, dims, dtypes, batch sizes), the index
     halves of all of them in shared launches two iterations ahead (or done by the calls themselves): tables,
-    states and gathered rows bit for bit as from one pipelined call per table."""
+    states and gathered rows bit for bit as from one pipelined call per table.  two_part: the same through
+    fs_prioritized_step_two_part_multi, every merged batch compared with the plain lookup on the table of its time."""
     rng = np.random.default_rng(99)
     # three tables of one row width and two of another share their launches; the sixth is on its own
     specs = [(30000, 128, "f32", 300), (2000, 64, "bf16", 120), (50000, 128, "f32", 40), (7000, 128, "f32", 500),
@@ -247,7 +330,7 @@ def test_multi_table_step_matches_one_call_per_table(ahead):
         nmax = max(v.numel() for v in t.vals)
         t.layouts = [fs.alloc_layout(nmax, "cuda") for _ in range(L)]
         t.splits = [fs.alloc_split(nmax, nmax, "cuda") for _ in range(P)]
-        t.embs = [torch.empty((nmax, t.table.shape[1]), dtype=t.d_table.dtype, device="cuda") for _ in range(2)]
+        t.embs = [torch.empty((nmax, t.table.shape[1]), dtype=t.d_table.dtype, device="cuda") for _ in range(3)]
         t.args = []
         for s_ in range(T):
             lay = dict(t.layouts[s_ % L]); lay["n"] = t.vals[s_].numel()
@@ -255,7 +338,7 @@ def test_multi_table_step_matches_one_call_per_table(ahead):
             t.args.append(fs.make_step_args(t.d_table, t.d_state, 0.01, 1e-8, lay, t.grads[s_],
                                             None if last else t.vals[s_ + 1], None if last else t.offs[s_ + 1],
                                             None if last else t.layouts[(s_ + 1) % L], t.splits[s_ % P], None,
-                                            None if last else t.embs[s_ % 2]))
+                                            None if last else t.embs[s_ % 3]))
         fs.fs_unique_ids(ctx, t.vals[0], t.table.shape[0], out=t.layouts[0])
 
     def index_halves(s_):
@@ -272,7 +355,18 @@ def test_multi_table_step_matches_one_call_per_table(ahead):
         index_halves(s_ + 2)
         cur = fs.step_args_array([t.args[s_] for t in tabs])
         nxt = fs.step_args_array([t.args[s_ + 1] for t in tabs]) if s_ + 1 < T else None
-        fs.fs_prioritized_step_pipelined_multi(ctx, cur, nxt)
+        if two_part:
+            fs.fs_prioritized_step_two_part_multi(ctx, cur, nxt)
+            if s_ + 1 < T:
+                # the merged batch of every table against the plain lookup on the table as it stands: the rows
+                # of the batch are final once the priority pass is through (stream order does the waiting)
+                for t in tabs:
+                    n1 = t.vals[s_ + 1].numel()
+                    want = fs.fs_gather_jagged(ctx, t.d_table, t.vals[s_ + 1], t.offs[s_ + 1])
+                    view = torch.int16 if t.d_table.dtype == torch.bfloat16 else torch.int32
+                    assert torch.equal(t.embs[s_ % 3][:n1].view(view), want.view(view)), (s_, t.table.shape)
+        else:
+            fs.fs_prioritized_step_pipelined_multi(ctx, cur, nxt)
     assert fs.fs_check_async(ctx) == fs.FS_OK, ctx.last_error()
     for t, (r_table, r_state, _) in zip(tabs, ref):
         view = torch.int16 if t.d_table.dtype == torch.bfloat16 else torch.int32
