@@ -172,6 +172,35 @@ def gather_jagged_class(table: np.ndarray, values: np.ndarray, u_t: np.ndarray, 
     _check(rc, "fso_gather_jagged_class")
 
 
+def partition_fbs(lengths: np.ndarray, n_ranks: int) -> Tuple[np.ndarray, np.ndarray]:
+    """FBS partitioner: (sample_of [B] rank-major, rank_offsets [n_ranks + 1])."""
+    lengths = _c(lengths, np.int64)
+    B = lengths.shape[0]
+    sample_of = np.empty(max(B, 1), dtype=np.int32)
+    rank_offsets = np.empty(n_ranks + 1, dtype=np.int64)
+    rc = lib().fso_partition_fbs(_p(lengths), ctypes.c_int64(B), ctypes.c_int32(n_ranks), _p(sample_of), _p(rank_offsets))
+    _check(rc, "fso_partition_fbs")
+    return sample_of[:B], rank_offsets
+
+
+def jagged_indexed_permute(values: np.ndarray, offsets: np.ndarray, sample_of: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """The samples sample_of[...] of the jagged tensor (values, offsets), concatenated: (out_values, out_offsets)."""
+    assert values.flags.c_contiguous
+    offsets = _c(offsets, np.int64)
+    sample_of = _c(sample_of, np.int32)
+    B = offsets.shape[0] - 1
+    lens = offsets[1:] - offsets[:-1]
+    in_range = sample_of[(sample_of >= 0) & (sample_of < B)]
+    total = int(lens[in_range].sum()) if B > 0 else 0
+    out = np.empty((total,) + values.shape[1:], dtype=values.dtype)
+    out_offsets = np.empty(sample_of.shape[0] + 1, dtype=np.int64)
+    elem = values.dtype.itemsize * int(np.prod(values.shape[1:], dtype=np.int64))
+    rc = lib().fso_jagged_indexed_permute(_p(values), ctypes.c_int32(elem), _p(offsets), ctypes.c_int64(B), _p(sample_of),
+                                          ctypes.c_int64(sample_of.shape[0]), _p(out), _p(out_offsets))
+    _check(rc, "fso_jagged_indexed_permute")
+    return out, out_offsets
+
+
 # ---- one step of the prioritized schedule -------------------------------------------------
 SCHEDULES = ("co_then_ex", "ex_then_co", "all_at_once", "gather_between")
 

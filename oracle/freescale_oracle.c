@@ -27,6 +27,11 @@
  *                              i), Backward returns the collision rows E_co^{i+1} as the priority
  *                              update leaves them, and merge() puts both into one input batch.
  *                              One call copies the occurrences of one of the two kinds of row.
+ *   fso_partition_fbs          the Fixed Batch Size partitioner of Section 4.1 ("Partitioning
+ *                              Algorithms"): samples sorted by UIH length, dealt to the ranks in a
+ *                              zig-zag.
+ *   fso_jagged_indexed_permute the indexed permute of Section 4.2 ("Triton Kernel Optimizations"):
+ *                              the samples of a jagged tensor laid out in a given order.
  *
  * Pins (tests/test_oracle_pins.py): brute-force set logic on tiny inputs, dense one-hot
  * reduction, hand-computed Adagrad steps, element-wise Adagrad of a library on the
@@ -258,6 +263,70 @@ int fso_rowwise_adagrad_update(void *table, int dt, float *state, int64_t num_ro
                 w[d] = f32_to_bf16_rne(v);
             }
         }
+    }
+    return FSO_OK;
+}
+
+/* ---- O7: FBS partitioner --------------------------------------------------------------------- */
+/* Samples are sorted by length (ascending; equal lengths keep their sample order) and rank i of n takes
+ * the sorted positions  i, 2n-1-i, 2n+i, 4n-1-i, 4n+i, ...  that exist: forth in even rounds of n, back
+ * in odd ones.  (The paper prints the pattern as [i, 2n-i, 2n+i, 4n-i, ...], which would give position
+ * 2n to rank 0 twice and position n to nobody; the zig-zag it describes is the one above.)
+ * sample_of [B]: the samples of rank 0 in the order they were dealt, then those of rank 1, ...;
+ * rank_offsets [n+1]: where each rank's samples start in sample_of. */
+typedef struct { int64_t len; int64_t idx; } lenidx;
+
+static int cmp_lenidx(const void *a, const void *b)
+{
+    const lenidx *x = (const lenidx *)a, *y = (const lenidx *)b;
+    if (x->len != y->len) return x->len < y->len ? -1 : 1;
+    return (x->idx > y->idx) - (x->idx < y->idx);
+}
+
+int fso_partition_fbs(const int64_t *lengths, int64_t B, int32_t n_ranks, int32_t *sample_of,
+                      int64_t *rank_offsets)
+{
+    if (B < 0 || n_ranks <= 0) return FSO_EINVAL;
+    lenidx *order = (lenidx *)malloc((size_t)(B > 0 ? B : 1) * sizeof(lenidx));
+    if (!order) return FSO_ENOMEM;
+    for (int64_t b = 0; b < B; ++b) {
+        if (lengths[b] < 0) { free(order); return FSO_ERANGE; }
+        order[b].len = lengths[b]; order[b].idx = b;
+    }
+    qsort(order, (size_t)B, sizeof(lenidx), cmp_lenidx);
+    int64_t n = n_ranks, at = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        rank_offsets[i] = at;
+        for (int64_t k = 0;; ++k) {
+            int64_t pos = (k % 2 == 0) ? k * n + i : (k + 1) * n - 1 - i;
+            if (k * n >= B) break;                  /* no sample left in round k for anybody */
+            if (pos < B) sample_of[at++] = (int32_t)order[pos].idx;
+        }
+    }
+    rank_offsets[n] = at;
+    free(order);
+    return at == B ? FSO_OK : FSO_EINVAL;
+}
+
+/* ---- O8: indexed permute of a jagged tensor ---------------------------------------------------- */
+/* out = the samples sample_of[0], sample_of[1], ... of (values, offsets) one after another;
+ * out_offsets [n_out + 1] their boundaries.  Elements are elem_bytes wide. */
+int fso_jagged_indexed_permute(const void *values, int32_t elem_bytes, const int64_t *offsets, int64_t B,
+                               const int32_t *sample_of, int64_t n_out, void *out_values, int64_t *out_offsets)
+{
+    if (B < 0 || n_out < 0 || elem_bytes <= 0) return FSO_EINVAL;
+    if (B > 0 && offsets[0] != 0) return FSO_ERANGE;
+    for (int64_t b = 0; b < B; ++b) if (offsets[b + 1] < offsets[b]) return FSO_ERANGE;
+    int64_t at = 0;
+    out_offsets[0] = 0;
+    for (int64_t k = 0; k < n_out; ++k) {
+        int64_t p = sample_of[k];
+        if (p < 0 || p >= B) return FSO_ERANGE;
+        int64_t len = offsets[p + 1] - offsets[p];
+        memcpy((char *)out_values + (size_t)at * elem_bytes, (const char *)values + (size_t)offsets[p] * elem_bytes,
+               (size_t)len * elem_bytes);
+        at += len;
+        out_offsets[k + 1] = at;
     }
     return FSO_OK;
 }

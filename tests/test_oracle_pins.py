@@ -446,3 +446,87 @@ def test_fetching_exclusive_rows_before_the_deferred_update_is_detected():
     bad = O.run_two_phase(wc, sc, values_seq, grads_seq, 0.1, 1e-8, prefetch_before_deferred=True)
     assert not np.array_equal(bad[1], want[1])          # stale row 3 in the batch of iteration 2
     assert np.array_equal(bad[1][1], want[1][1])        # row 2 (a collision row) is still fresh
+
+
+# ----------------------------------------------------------- FBS partitioner, indexed permute
+def test_fbs_zigzag_matches_the_printed_pattern():
+    want = {}
+    with open(os.path.join(GOLDEN, "fbs_zigzag_pattern.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            cols = [int(x) for x in line.split()]
+            want[cols[0]] = cols[1:]
+    lengths = np.arange(18, dtype=np.int64) * 3 + 5          # already sorted: sample index == sorted position
+    sample_of, rank_offsets = O.partition_fbs(lengths, 4)
+    for rank, positions in want.items():
+        assert sample_of[rank_offsets[rank]:rank_offsets[rank + 1]].tolist() == positions
+
+
+def _fbs_by_rounds(lengths, n):
+    """The same partition told by rounds: cut the sorted list into blocks of n, reverse every second block,
+    and give the c-th entry of a block to rank c (a short last block, reversed, ends at rank n-1)."""
+    order = sorted(range(len(lengths)), key=lambda b: (int(lengths[b]), b))
+    ranks = [[] for _ in range(n)]
+    for r in range(0, (len(order) + n - 1) // n):
+        block = order[r * n:(r + 1) * n]
+        if r % 2 == 0:
+            for c, smp in enumerate(block):
+                ranks[c].append(smp)
+        else:
+            for c, smp in enumerate(block):
+                ranks[n - 1 - c].append(smp)
+    return ranks
+
+
+@pytest.mark.parametrize("B,n", [(16, 4), (64, 8), (37, 5), (3, 8), (0, 4), (1, 1), (100, 1), (257, 16)])
+def test_fbs_partition_is_a_balanced_bijection(B, n):
+    rng = np.random.default_rng(B * 31 + n)
+    lengths = rng.integers(0, 50, size=B).astype(np.int64)            # many ties
+    sample_of, rank_offsets = O.partition_fbs(lengths, n)
+    assert sorted(sample_of.tolist()) == list(range(B))
+    assert rank_offsets[0] == 0 and rank_offsets[n] == B
+    ranks = [sample_of[rank_offsets[i]:rank_offsets[i + 1]].tolist() for i in range(n)]
+    assert ranks == _fbs_by_rounds(lengths, n)
+    sizes = [len(r) for r in ranks]
+    assert max(sizes) - min(sizes) <= 1
+    if B % n == 0 and B > 0:
+        # equal sample counts, and the summed lengths of two ranks differ by at most the spread of the
+        # lengths (the ranges of the double rounds telescope)
+        assert len(set(sizes)) == 1
+        totals = [int(lengths[r].sum()) for r in ranks]
+        assert max(totals) - min(totals) <= int(lengths.max() - lengths.min())
+    with pytest.raises(O.OracleError):
+        O.partition_fbs(np.array([3, -1], dtype=np.int64), 2)
+
+
+def test_fbs_beats_contiguous_blocks_on_skewed_lengths():
+    # what the zig-zag is for: sorted blocks would put all long samples on the last rank
+    rng = np.random.default_rng(9)
+    lengths = np.sort((rng.pareto(1.5, size=256) * 16 + 16).astype(np.int64).clip(16, 4096))
+    sample_of, ro = O.partition_fbs(lengths, 8)
+    totals = [int(lengths[sample_of[ro[i]:ro[i + 1]]].sum()) for i in range(8)]
+    blocks = [int(lengths[i * 32:(i + 1) * 32].sum()) for i in range(8)]
+    assert max(totals) - min(totals) <= int(lengths.max() - lengths.min())
+    assert max(blocks) - min(blocks) > 3 * (max(totals) - min(totals))
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_indexed_permute_matches_list_concatenation(seed):
+    rng = np.random.default_rng(700 + seed)
+    B = 23
+    lens = rng.integers(0, 9, size=B)
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    values = rng.integers(0, 10**12, size=int(offsets[-1])).astype(np.int64)
+    for sample_of in (rng.permutation(B).astype(np.int32), np.array([5, 5, 0], dtype=np.int32), np.empty(0, np.int32)):
+        out, out_offsets = O.jagged_indexed_permute(values, offsets, sample_of)
+        pieces = [values[offsets[p]:offsets[p + 1]].tolist() for p in sample_of]
+        assert out.tolist() == [x for piece in pieces for x in piece]
+        assert out_offsets.tolist() == [0] + list(np.cumsum([len(p) for p in pieces]))
+    # rows instead of scalars
+    rows = rng.standard_normal((int(offsets[-1]), 3)).astype(np.float32)
+    perm = rng.permutation(B).astype(np.int32)
+    out, _ = O.jagged_indexed_permute(rows, offsets, perm)
+    assert np.array_equal(out, np.concatenate([rows[offsets[p]:offsets[p + 1]] for p in perm]))
+    with pytest.raises(O.OracleError):
+        O.jagged_indexed_permute(values, offsets, np.array([B], dtype=np.int32))
