@@ -154,6 +154,35 @@ int fs_gather_jagged_class(fs_ctx *ctx, const void *table, int64_t num_rows, int
                            const int32_t *inverse, const uint8_t *co_flag, int which, void *out,
                            fs_stream stream);
 
+/* ---- the load balancer's data path on one GPU ------------------------------------------------ */
+
+/* Fixed Batch Size partitioner (Section 4.1, "Partitioning Algorithms"): the B samples are sorted by UIH
+ * length (ascending, equal lengths in sample order) and dealt to n_ranks ranks in a zig-zag - rank i takes
+ * the sorted positions i, 2n-1-i, 2n+i, 4n-1-i, ... that exist (forth in even rounds of n, back in odd ones;
+ * the paper prints 2n-i and 4n-i, which is not a partition).  Every rank gets B/n samples (one more for
+ * some when n does not divide B), and long and short samples are spread evenly.
+ *   lengths      [B] int64, device; each in [0, max_len] (max_len: host value that sizes the sort; a length
+ *                outside is reported as FS_ERANGE by fs_check_async)
+ *   sample_of    [B] int32 out: the samples of rank 0 in the order dealt, then those of rank 1, ...
+ *   rank_offsets [n_ranks + 1] int64 out: where each rank's samples start in sample_of
+ * B <= context max_ids.  Uses the context's index workspace like fs_unique_ids. */
+int fs_partition_fbs(fs_ctx *ctx, const int64_t *lengths, int64_t B, int64_t max_len, int32_t n_ranks,
+                     int32_t *sample_of, int64_t *rank_offsets, fs_stream stream);
+
+/* Indexed permute of a jagged tensor (Section 4.2, "Triton Kernel Optimizations": the kernel that applies a
+ * partitioning to the gathered IDs): output sample k is input sample sample_of[k], k < n_out.
+ *   values       [n_values] elements of elem_bytes bytes each (a multiple of 4: 8 for IDs, a row of
+ *                embeddings otherwise), offsets [B + 1] int64: the input
+ *   sample_of    [n_out] int32: any selection of input samples (a permutation, a rank's share, repeats)
+ *   out_values   [cap_out] elements, out_offsets [n_out + 1] int64: the output; cap_out is a host-side bound
+ *                on the number of output elements (it sizes the copy; for a permutation n_values)
+ * A sample index outside [0, B), a sample whose boundaries do not lie inside the values, or more output
+ * elements than cap_out (the copy stops there) are reported as FS_ERANGE by fs_check_async.
+ * n_out <= context max_ids. */
+int fs_jagged_indexed_permute(fs_ctx *ctx, const void *values, int64_t n_values, int32_t elem_bytes,
+                              const int64_t *offsets, int64_t B, const int32_t *sample_of, int64_t n_out,
+                              void *out_values, int64_t cap_out, int64_t *out_offsets, fs_stream stream);
+
 /* ---- the fused update path of the whole iteration ------------------------------------------ */
 
 /* Rows with at most this many occurrences in a batch take the short path of the fused update (all

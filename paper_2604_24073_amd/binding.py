@@ -74,6 +74,9 @@ def load_library() -> ctypes.CDLL:
         "fs_gather_jagged_class": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i32, ctypes.c_int, c_vp, c_vp, c_i64, c_i64, c_vp,
                                                   c_vp, ctypes.c_int, c_vp, S]),
         "fs_unique_ids": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i64, c_vp, c_vp, c_vp, c_vp, c_vp, S]),
+        "fs_partition_fbs": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i64, c_i32, c_vp, c_vp, S]),
+        "fs_jagged_indexed_permute": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i32, c_vp, c_i64, c_vp, c_i64, c_vp, c_i64,
+                                                     c_vp, S]),
         "fs_collision_split": (ctypes.c_int, [c_vp, c_vp, c_vp, c_vp, c_vp, c_i64, c_i64, c_vp, c_vp, c_vp, c_vp,
                                               c_vp, c_vp, c_vp, S]),
         "fs_segment_reduce_grads": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i32, c_vp, c_vp, c_vp, c_vp, c_vp, S]),
@@ -224,6 +227,34 @@ def fs_gather_jagged_class(ctx: Context, table: torch.Tensor, values: torch.Tens
                                         _ptr(co_flag), which, _ptr(out), _stream(stream))
     ctx.check(rc, "fs_gather_jagged_class")
     return out
+
+
+def fs_partition_fbs(ctx: Context, lengths: torch.Tensor, max_len: int, n_ranks: int, stream=None):
+    """(sample_of [B] int32, rank_offsets [n_ranks + 1] int64) of the FBS partitioner."""
+    B = lengths.numel()
+    sample_of = torch.empty(max(B, 1), dtype=torch.int32, device=lengths.device)
+    rank_offsets = torch.empty(n_ranks + 1, dtype=torch.int64, device=lengths.device)
+    rc = ctx.lib.fs_partition_fbs(ctx.handle, _ptr(lengths), B, max_len, n_ranks, _ptr(sample_of), _ptr(rank_offsets),
+                                  _stream(stream))
+    ctx.check(rc, "fs_partition_fbs")
+    return sample_of[:B], rank_offsets
+
+
+def fs_jagged_indexed_permute(ctx: Context, values: torch.Tensor, offsets: torch.Tensor, sample_of: torch.Tensor,
+                              cap_out: int, stream=None):
+    """(out_values [cap_out, ...], out_offsets [n_out + 1]); values is [n] or [n, width], any 4- or 8-byte dtype."""
+    n_values = values.shape[0]
+    elem = values.element_size()
+    for d in values.shape[1:]:
+        elem *= d
+    out = torch.empty((cap_out,) + tuple(values.shape[1:]), dtype=values.dtype, device=values.device)
+    n_out = sample_of.numel()
+    out_offsets = torch.empty(n_out + 1, dtype=torch.int64, device=values.device)
+    rc = ctx.lib.fs_jagged_indexed_permute(ctx.handle, _ptr(values), n_values, elem, _ptr(offsets), offsets.numel() - 1,
+                                           _ptr(sample_of), n_out, _ptr(out), cap_out, _ptr(out_offsets),
+                                           _stream(stream))
+    ctx.check(rc, "fs_jagged_indexed_permute")
+    return out, out_offsets
 
 
 def fs_unique_ids(ctx: Context, ids: torch.Tensor, num_rows: int, out: Optional[Dict[str, torch.Tensor]] = None,

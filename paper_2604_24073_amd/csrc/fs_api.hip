@@ -155,6 +155,11 @@ void carve(fs_ctx *c, char *base, size_t *total) {
         c->fcounters[k] = cv.take<int>(fchunks);
         c->fcounters_sup[k] = cv.take<int>(fchunks);
     }
+    c->jag_unique = cv.take<int64_t>(n + 16);
+    c->jag_seg = cv.take<int32_t>(n + 16);
+    c->jag_n = cv.take<int64_t>(1);
+    c->jag_sorted = cv.take<int32_t>(n + 16);
+    c->jag_tile_sum = cv.take<int64_t>(scan_tiles);
     *total = align_up(cv.off, 256);
 }
 
@@ -411,6 +416,32 @@ int fs_rowwise_adagrad_update(fs_ctx *ctx, void *table, fs_dtype dt, float *stat
     FS_REQUIRE(ctx, table && state && rows && slots && n_rows_dev && reduced, "adagrad: null pointer");
     return launch_adagrad(ctx, table, dt, state, num_rows, dim, rows, slots, n_rows_dev, cap, reduced, lr, eps,
                           as_stream(stream));
+}
+
+int fs_partition_fbs(fs_ctx *ctx, const int64_t *lengths, int64_t B, int64_t max_len, int32_t n_ranks,
+                     int32_t *sample_of, int64_t *rank_offsets, fs_stream stream) {
+    if (!ctx) return FS_EINVAL;
+    FS_REQUIRE(ctx, B >= 0 && max_len >= 0 && n_ranks >= 1, "fbs: negative size or no rank");
+    if (B > ctx->max_ids) return set_err(ctx, FS_ENOMEM, "fbs: B beyond the context capacity");
+    FS_REQUIRE(ctx, rank_offsets && (B == 0 || (lengths && sample_of)), "fbs: null pointer");
+    const int jrc = join_pending_work(ctx, as_stream(stream));      // the index workspace may still be in use
+    if (jrc != FS_OK) return jrc;
+    return launch_partition_fbs(ctx, lengths, B, max_len, n_ranks, sample_of, rank_offsets, as_stream(stream));
+}
+
+int fs_jagged_indexed_permute(fs_ctx *ctx, const void *values, int64_t n_values, int32_t elem_bytes,
+                              const int64_t *offsets, int64_t B, const int32_t *sample_of, int64_t n_out,
+                              void *out_values, int64_t cap_out, int64_t *out_offsets, fs_stream stream) {
+    if (!ctx) return FS_EINVAL;
+    FS_REQUIRE(ctx, n_values >= 0 && B >= 0 && n_out >= 0 && cap_out >= 0, "indexed permute: negative size");
+    FS_REQUIRE(ctx, elem_bytes > 0 && elem_bytes % 4 == 0, "indexed permute: elem_bytes must be a multiple of 4");
+    if (n_out > ctx->max_ids) return set_err(ctx, FS_ENOMEM, "indexed permute: n_out beyond the context capacity");
+    FS_REQUIRE(ctx, out_offsets && (n_out == 0 || (offsets && sample_of)), "indexed permute: null pointer");
+    FS_REQUIRE(ctx, cap_out == 0 || n_out == 0 || (values && out_values), "indexed permute: null pointer");
+    const int jrc = join_pending_work(ctx, as_stream(stream));
+    if (jrc != FS_OK) return jrc;
+    return launch_indexed_permute(ctx, values, n_values, elem_bytes, offsets, B, sample_of, n_out, out_values, cap_out,
+                                  out_offsets, as_stream(stream));
 }
 
 int fs_init_table_hash(fs_ctx *ctx, void *table, int64_t num_rows, int32_t dim, fs_dtype dt, fs_stream stream) {

@@ -157,6 +157,12 @@ struct fs_ctx {
     int *fcounters_sup[2];    // [chunks] arrivals per group of sixteen pieces (indexed by its first chunk)
     const int32_t *reduce_inverse;   // host-side: the caller's optional inverse map for the launch being enqueued
     int64_t *d_zero;          // device scalar that stays 0 (stands in for a missing lookahead)
+    // partitioner and jagged shuffles
+    int64_t *jag_unique;      // [max_ids] by-products of sorting the lengths (distinct lengths, their extents, count)
+    int32_t *jag_seg;         // [max_ids + 1]
+    int64_t *jag_n;           // [1]
+    int32_t *jag_sorted;      // [max_ids] samples in ascending order of length
+    int64_t *jag_tile_sum;    // [scan tiles] output elements per tile of output samples
 
     hipStream_t stream_a;     // side stream: index half of the lookahead batch; deferred pass of a pipelined call
     hipStream_t stream_b;     // deferred pass of the self-contained step
@@ -226,6 +232,11 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // launchers implemented in the kernel translation units (host side, argument-checked callers)
 int launch_gather(fs_ctx *, const void *table, int64_t num_rows, int row_bytes, const int64_t *values,
                   const int64_t *offsets, int64_t batch, int64_t n, void *out, hipStream_t s);
+int launch_partition_fbs(fs_ctx *, const int64_t *lengths, int64_t B, int64_t max_len, int32_t n_ranks,
+                         int32_t *sample_of, int64_t *rank_offsets, hipStream_t s);
+int launch_indexed_permute(fs_ctx *, const void *values, int64_t n_values, int32_t elem_bytes, const int64_t *offsets,
+                           int64_t B, const int32_t *sample_of, int64_t n_out, void *out_values, int64_t cap_out,
+                           int64_t *out_offsets, hipStream_t s);
 // event pair of timing kind `kind` for the step being enqueued, or nullptr when timing is off
 inline hipEvent_t *timing_pair(fs_ctx *ctx, int kind) {
     if (!ctx->timing_now) return nullptr;

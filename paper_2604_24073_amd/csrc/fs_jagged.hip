@@ -1,0 +1,270 @@
+// Load-balancer data path on one GPU: the Fixed Batch Size partitioner (Section 4.1 of the paper,
+// "Partitioning Algorithms") and the indexed permute of a jagged tensor (Section 4.2, "Triton Kernel
+// Optimizations": the kernel that applies a partitioning to the gathered IDs).
+//
+// FBS: samples sorted by UIH length (the stable radix sort of the dedup, on the lengths), then dealt to
+// the ranks in a zig-zag - rank i takes sorted positions i, 2n-1-i, 2n+i, 4n-1-i, ...  The deal is a
+// closed form per sorted position, one thread each.
+//
+// Indexed permute: output sample k is input sample sample_of[k].  Three launches: lengths summed per
+// tile of samples, the output offsets by a scan with tile prefixes, and the copy.  The copy is driven
+// by the OUTPUT (every lane writes consecutive pieces of the output, so a 16K-item sample costs per
+// item what a short one costs): a workgroup takes 2048 consecutive output pieces, finds the samples
+// they belong to with two 64-ary searches, stages their boundaries in LDS and lets every piece
+// binary-search LDS.
+#include "fs_common.h"
+#include "fs_device.h"
+
+namespace fs {
+
+// ---- FBS: the deal ------------------------------------------------------------------------------------
+// full rounds R = B / n, m = B % n samples in the last, partial round (round R): forth if R is even
+// (ranks 0..m-1 get one more), back if R is odd (ranks n-m..n-1 get one more)
+__device__ __forceinline__ int64_t fbs_rank_start(int64_t i, int64_t n, int64_t R, int64_t m) {
+    const int64_t extra = (R % 2 == 0) ? (i < m ? i : m) : (i > n - m ? i - (n - m) : 0);
+    return i * R + extra;
+}
+
+__global__ __launch_bounds__(256) void fbs_deal_kernel(const int32_t *__restrict__ sorted, int64_t B, int64_t n,
+                                                       int32_t *__restrict__ sample_of,
+                                                       int64_t *__restrict__ rank_offsets) {
+    const int64_t R = B / n, m = B % n;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t gtid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (int64_t i = gtid; i <= n; i += stride) rank_offsets[i] = fbs_rank_start(i, n, R, m);
+    for (int64_t s = gtid; s < B; s += stride) {
+        const int64_t r = s / n, c = s % n;
+        const int64_t i = (r % 2 == 0) ? c : n - 1 - c;
+        sample_of[fbs_rank_start(i, n, R, m) + r] = sorted[s];
+    }
+}
+
+int launch_partition_fbs(fs_ctx *ctx, const int64_t *lengths, int64_t B, int64_t max_len, int32_t n_ranks,
+                         int32_t *sample_of, int64_t *rank_offsets, hipStream_t s) {
+    if (B > 0) {
+        const int rc = launch_unique(ctx, lengths, B, max_len + 1, ctx->jag_unique, ctx->jag_seg, ctx->jag_sorted,
+                                     nullptr, ctx->jag_n, s, 0);
+        if (rc != FS_OK) return rc;
+    }
+    const int64_t work = B > n_ranks ? B : (int64_t)n_ranks + 1;
+    int64_t blocks = ceil_div(work, 256);
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(fbs_deal_kernel, dim3((unsigned)blocks), dim3(256), 0, s, ctx->jag_sorted, B, (int64_t)n_ranks,
+                       sample_of, rank_offsets);
+    FS_LAUNCH_CHECK(ctx, "fbs_deal_kernel");
+    return FS_OK;
+}
+
+// ---- indexed permute ------------------------------------------------------------------------------------
+__device__ __forceinline__ int64_t wave_incl_scan_i64(int64_t v) {
+    const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int64_t t = __shfl_up(v, d, kWave);
+        if (lane >= d) v += t;
+    }
+    return v;
+}
+
+// exclusive scan of one value per thread over a kScanThreads block; `sh` holds kScanThreads/kWave values
+__device__ __forceinline__ int64_t block_excl_scan_i64(int64_t v, int64_t *sh, int64_t &total) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = threadIdx.x / kWave;
+    const int64_t inc = wave_incl_scan_i64(v);
+    if (lane == kWave - 1) sh[w] = inc;
+    __syncthreads();
+    int64_t base = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < kScanThreads / kWave; ++i) {
+        const int64_t x = sh[i];
+        if (i < w) base += x;
+        tot += x;
+    }
+    __syncthreads();
+    total = tot;
+    return base + inc - v;
+}
+
+struct jagged_in {
+    const int64_t *offsets;   // [B + 1]
+    int64_t B, n_values;      // samples, elements behind them
+};
+
+// length of output sample k (0 past the end; 0 and a flag for a sample index out of range or a sample whose
+// boundaries are not inside the values: such a sample is never read)
+__device__ __forceinline__ int64_t out_len(const jagged_in &in, const int32_t *__restrict__ sample_of, int64_t k,
+                                           int64_t n_out, bool &bad) {
+    if (k >= n_out) return 0;
+    const int64_t p = sample_of[k];
+    if (p < 0 || p >= in.B) { bad = true; return 0; }
+    const int64_t a = in.offsets[p], b = in.offsets[p + 1];
+    if (a < 0 || b < a || b > in.n_values) { bad = true; return 0; }
+    return b - a;
+}
+
+__global__ __launch_bounds__(kScanThreads) void permute_tile_sum_kernel(const jagged_in in,
+                                                                        const int32_t *__restrict__ sample_of,
+                                                                        int64_t n_out, int64_t *__restrict__ tile_sum,
+                                                                        int *__restrict__ flags) {
+    __shared__ int64_t sh[kScanThreads / kWave];
+    const int64_t k0 = (int64_t)blockIdx.x * kScanTile + threadIdx.x * kScanIpt;
+    bool bad = false;
+    int64_t v = 0;
+#pragma unroll
+    for (int i = 0; i < kScanIpt; ++i) v += out_len(in, sample_of, k0 + i, n_out, bad);
+    int64_t total;
+    (void)block_excl_scan_i64(v, sh, total);
+    if (threadIdx.x == 0) tile_sum[blockIdx.x] = total;
+    if (bad) atomicOr(flags, kFlagOffsets);
+}
+
+__global__ __launch_bounds__(kScanThreads) void permute_offsets_kernel(const jagged_in in,
+                                                                       const int32_t *__restrict__ sample_of,
+                                                                       int64_t n_out,
+                                                                       const int64_t *__restrict__ tile_sum,
+                                                                       int64_t cap_out, int64_t *__restrict__ out_offsets,
+                                                                       int *__restrict__ flags) {
+    __shared__ int64_t sh[kScanThreads / kWave];
+    int64_t before = 0;
+    for (int t = threadIdx.x; t < (int)blockIdx.x; t += kScanThreads) before += tile_sum[t];
+    int64_t tile_base;
+    (void)block_excl_scan_i64(before, sh, tile_base);
+    const int64_t k0 = (int64_t)blockIdx.x * kScanTile + threadIdx.x * kScanIpt;
+    bool bad = false;
+    int64_t len[kScanIpt], v = 0;
+#pragma unroll
+    for (int i = 0; i < kScanIpt; ++i) {
+        len[i] = out_len(in, sample_of, k0 + i, n_out, bad);
+        v += len[i];
+    }
+    int64_t tile_total;
+    int64_t run = tile_base + block_excl_scan_i64(v, sh, tile_total);
+#pragma unroll
+    for (int i = 0; i < kScanIpt; ++i) {
+        if (k0 + i < n_out) out_offsets[k0 + i] = run;
+        run += len[i];
+    }
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+        const int64_t total = tile_base + tile_total;
+        out_offsets[n_out] = total;
+        if (total > cap_out) atomicOr(flags, kFlagOffsets);     // the copy stops at cap_out
+    }
+}
+
+// number of entries of a[0, n) that are <= key; executed by one whole wavefront (64-ary search)
+__device__ __forceinline__ int64_t wave_upper_bound(const int64_t *__restrict__ a, int64_t n, int64_t key) {
+    const int lane = threadIdx.x & (kWave - 1);
+    int64_t lo = 0, hi = n;                  // a[i] <= key for i < lo, a[i] > key for i >= hi
+    while (lo < hi) {
+        const int64_t step = (hi - lo + kWave - 1) / kWave;
+        const int64_t probe = lo + (lane + 1) * step - 1;      // last entry of my sub-block
+        const bool le = (probe < hi) && (a[probe] <= key);
+        const int cnt = __popcll(__ballot(le));
+        lo += cnt * step;
+        const int64_t nhi = lo + step - 1;
+        hi = nhi < hi ? nhi : hi;
+    }
+    return lo;
+}
+
+constexpr int kCopyPieces = 8;                                  // pieces per thread
+constexpr int kCopyTile = kScanThreads * kCopyPieces;           // pieces per workgroup
+constexpr int kCopyWindow = kCopyTile + 2;                      // sample boundaries staged in LDS
+
+// V: the piece, the widest of 4, 8, 16 bytes that divides the element; ppe pieces per element
+template <typename V>
+__global__ __launch_bounds__(kScanThreads) void permute_copy_kernel(const V *__restrict__ values, const jagged_in in,
+                                                                    const int32_t *__restrict__ sample_of,
+                                                                    int64_t n_out, const int64_t *__restrict__ out_offsets,
+                                                                    int64_t cap_out, int ppe, V *__restrict__ out) {
+    __shared__ int64_t w_start[kCopyWindow];    // out_offsets[k0 + j]
+    __shared__ int64_t w_delta[kCopyWindow];    // first input element of sample k0 + j minus its first output element
+    __shared__ int64_t win[2];
+    const int64_t *__restrict__ offsets = in.offsets;
+    int64_t total = out_offsets[n_out];
+    if (total > cap_out) total = cap_out;
+    const int64_t pieces = total * ppe;
+    const int64_t q0 = (int64_t)blockIdx.x * kCopyTile;
+    if (q0 >= pieces) return;                                   // whole workgroup
+    const int64_t q1 = (q0 + kCopyTile < pieces ? q0 + kCopyTile : pieces) - 1;      // last piece of the tile
+    if (threadIdx.x < kWave) {
+        // sample of an element e: the last k with out_offsets[k] <= e (empty samples in between are skipped)
+        const int64_t ka = wave_upper_bound(out_offsets, n_out + 1, q0 / ppe) - 1;
+        const int64_t kb = wave_upper_bound(out_offsets, n_out + 1, q1 / ppe) - 1;
+        if (threadIdx.x == 0) { win[0] = ka; win[1] = kb; }
+    }
+    __syncthreads();
+    const int64_t ka = win[0], kb = win[1];
+    const int64_t wn = kb - ka + 1;                             // samples touched by the tile
+    const bool staged = wn <= kCopyWindow;
+    if (staged)
+        for (int64_t j = threadIdx.x; j < wn; j += kScanThreads) {
+            const int64_t start = out_offsets[ka + j];
+            const int64_t p = sample_of[ka + j];
+            w_start[j] = start;
+            w_delta[j] = (p >= 0 && p < in.B) ? offsets[p] - start : 0;     // a flagged sample is empty: never used
+        }
+    __syncthreads();
+    V v[kCopyPieces];
+    bool live[kCopyPieces];
+#pragma unroll
+    for (int i = 0; i < kCopyPieces; ++i) {
+        const int64_t q = q0 + (int64_t)i * kScanThreads + threadIdx.x;
+        live[i] = q <= q1;
+        if (live[i]) {
+            const int64_t e = q / ppe;
+            int64_t lo = 0, hi = wn;                            // first j with start[j] > e
+            int64_t delta;
+            if (staged) {
+                while (lo < hi) {
+                    const int64_t mid = (lo + hi) >> 1;
+                    if (w_start[mid] <= e) lo = mid + 1; else hi = mid;
+                }
+                delta = w_delta[lo - 1];
+            } else {
+                while (lo < hi) {
+                    const int64_t mid = (lo + hi) >> 1;
+                    if (out_offsets[ka + mid] <= e) lo = mid + 1; else hi = mid;
+                }
+                delta = offsets[sample_of[ka + lo - 1]] - out_offsets[ka + lo - 1];
+            }
+            v[i] = values[(e + delta) * ppe + (q - e * ppe)];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < kCopyPieces; ++i) {
+        const int64_t q = q0 + (int64_t)i * kScanThreads + threadIdx.x;
+        if (live[i]) out[q] = v[i];
+    }
+}
+
+int launch_indexed_permute(fs_ctx *ctx, const void *values, int64_t n_values, int32_t elem_bytes,
+                           const int64_t *offsets, int64_t B, const int32_t *sample_of, int64_t n_out, void *out_values,
+                           int64_t cap_out, int64_t *out_offsets, hipStream_t s) {
+    const jagged_in in = {offsets, B, n_values};
+    const int tiles = (int)(n_out > 0 ? ceil_div(n_out, kScanTile) : 1);
+    hipLaunchKernelGGL(permute_tile_sum_kernel, dim3((unsigned)tiles), dim3(kScanThreads), 0, s, in, sample_of,
+                       n_out, ctx->jag_tile_sum, ctx->d_flags);
+    hipLaunchKernelGGL(permute_offsets_kernel, dim3((unsigned)tiles), dim3(kScanThreads), 0, s, in, sample_of,
+                       n_out, ctx->jag_tile_sum, cap_out, out_offsets, ctx->d_flags);
+    if (cap_out > 0 && n_out > 0) {
+        const int piece = elem_bytes % 16 == 0 ? 16 : (elem_bytes % 8 == 0 ? 8 : 4);
+        const int ppe = elem_bytes / piece;
+        const int64_t blocks = ceil_div(cap_out * ppe, kCopyTile);
+        if (blocks > 0x7fffffffll) return set_err(ctx, FS_EINVAL, "indexed permute: output too large for one launch");
+        const dim3 grid((unsigned)blocks);
+        if (piece == 16)
+            hipLaunchKernelGGL((permute_copy_kernel<u32x4>), grid, dim3(kScanThreads), 0, s, (const u32x4 *)values,
+                               in, sample_of, n_out, out_offsets, cap_out, ppe, (u32x4 *)out_values);
+        else if (piece == 8)
+            hipLaunchKernelGGL((permute_copy_kernel<uint64_t>), grid, dim3(kScanThreads), 0, s, (const uint64_t *)values,
+                               in, sample_of, n_out, out_offsets, cap_out, ppe, (uint64_t *)out_values);
+        else
+            hipLaunchKernelGGL((permute_copy_kernel<uint32_t>), grid, dim3(kScanThreads), 0, s, (const uint32_t *)values,
+                               in, sample_of, n_out, out_offsets, cap_out, ppe, (uint32_t *)out_values);
+    }
+    FS_LAUNCH_CHECK(ctx, "indexed permute kernels");
+    return FS_OK;
+}
+
+}  // namespace fs
