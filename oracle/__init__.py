@@ -201,6 +201,41 @@ def jagged_indexed_permute(values: np.ndarray, offsets: np.ndarray, sample_of: n
     return out, out_offsets
 
 
+def _shuffle(fn_name, values, offsets, F, B, rank_offsets=None, want_splits=False):
+    assert values.flags.c_contiguous
+    offsets = _c(offsets, np.int64)
+    assert offsets.shape[0] == F * B + 1
+    out = np.empty_like(values)
+    out_offsets = np.empty(F * B + 1, dtype=np.int64)
+    elem = values.dtype.itemsize * int(np.prod(values.shape[1:], dtype=np.int64))
+    args = [_p(values), ctypes.c_int32(elem), _p(offsets), ctypes.c_int64(F), ctypes.c_int64(B)]
+    splits = None
+    if rank_offsets is not None:
+        rank_offsets = _c(rank_offsets, np.int64)
+        args += [_p(rank_offsets), ctypes.c_int32(rank_offsets.shape[0] - 1)]
+    args += [_p(out), _p(out_offsets)]
+    if want_splits:
+        splits = np.empty(rank_offsets.shape[0] - 1, dtype=np.int64)
+        args.append(_p(splits))
+    _check(getattr(lib(), fn_name)(*args), fn_name)
+    return (out, out_offsets, splits) if want_splits else (out, out_offsets)
+
+
+def jagged_keyed_transpose(values, offsets, F, B):
+    """Feature-major [F keys x B samples] -> batch-major: (out_values, out_offsets)."""
+    return _shuffle("fso_jagged_keyed_transpose", values, offsets, F, B)
+
+
+def jagged_ranged_dispatch(values, offsets, F, B, rank_offsets):
+    """Feature-major -> AllToAll input (rank, key, sample): (out_values, out_offsets, splits)."""
+    return _shuffle("fso_jagged_ranged_dispatch", values, offsets, F, B, rank_offsets, want_splits=True)
+
+
+def jagged_ranged_combine(values, offsets, F, B, rank_offsets):
+    """AllToAll output (source rank, key, sample) -> feature-major: (out_values, out_offsets)."""
+    return _shuffle("fso_jagged_ranged_combine", values, offsets, F, B, rank_offsets)
+
+
 # ---- one step of the prioritized schedule -------------------------------------------------
 SCHEDULES = ("co_then_ex", "ex_then_co", "all_at_once", "gather_between")
 

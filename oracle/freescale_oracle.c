@@ -32,6 +32,11 @@
  *                              zig-zag.
  *   fso_jagged_indexed_permute the indexed permute of Section 4.2 ("Triton Kernel Optimizations"):
  *                              the samples of a jagged tensor laid out in a given order.
+ *   fso_jagged_keyed_transpose, fso_jagged_ranged_dispatch, fso_jagged_ranged_combine
+ *                              the other jagged shuffles Section 4.2 names.  The paper states their
+ *                              purpose only (feature-major to batch-major; input and output tensors of
+ *                              the ID and embedding AllToAll); the layouts are this build's reading,
+ *                              spelled out at each function.
  *
  * Pins (tests/test_oracle_pins.py): brute-force set logic on tiny inputs, dense one-hot
  * reduction, hand-computed Adagrad steps, element-wise Adagrad of a library on the
@@ -328,6 +333,92 @@ int fso_jagged_indexed_permute(const void *values, int32_t elem_bytes, const int
         at += len;
         out_offsets[k + 1] = at;
     }
+    return FSO_OK;
+}
+
+/* ---- O9: keyed transpose, ranged dispatch, ranged combine -------------------------------------- */
+/* A keyed jagged tensor has F keys (features) and B samples: F * B segments.  Feature-major: segment
+ * (f, b) is number f * B + b; batch-major: number b * F + f.  A partition of the samples into ranks is
+ * given as ranges: rank r owns the samples [rank_offsets[r], rank_offsets[r + 1]). */
+static void copy_segment(const void *values, int32_t elem_bytes, const int64_t *offsets, int64_t seg,
+                         void *out_values, int64_t *at)
+{
+    int64_t len = offsets[seg + 1] - offsets[seg];
+    memcpy((char *)out_values + (size_t)*at * elem_bytes, (const char *)values + (size_t)offsets[seg] * elem_bytes,
+           (size_t)len * elem_bytes);
+    *at += len;
+}
+
+static int check_segments(const int64_t *offsets, int64_t n_seg)
+{
+    if (n_seg > 0 && offsets[0] != 0) return FSO_ERANGE;
+    for (int64_t i = 0; i < n_seg; ++i) if (offsets[i + 1] < offsets[i]) return FSO_ERANGE;
+    return FSO_OK;
+}
+
+static int check_ranges(const int64_t *rank_offsets, int32_t n_ranks, int64_t B)
+{
+    if (n_ranks <= 0 || rank_offsets[0] != 0 || rank_offsets[n_ranks] != B) return FSO_ERANGE;
+    for (int32_t r = 0; r < n_ranks; ++r) if (rank_offsets[r + 1] < rank_offsets[r]) return FSO_ERANGE;
+    return FSO_OK;
+}
+
+/* feature-major in, batch-major out: the segments of sample 0 for every key, then those of sample 1, ... */
+int fso_jagged_keyed_transpose(const void *values, int32_t elem_bytes, const int64_t *offsets, int64_t F, int64_t B,
+                               void *out_values, int64_t *out_offsets)
+{
+    if (F < 0 || B < 0 || elem_bytes <= 0) return FSO_EINVAL;
+    if (check_segments(offsets, F * B) != FSO_OK) return FSO_ERANGE;
+    int64_t at = 0, j = 0;
+    out_offsets[0] = 0;
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t f = 0; f < F; ++f) {
+            copy_segment(values, elem_bytes, offsets, f * B + b, out_values, &at);
+            out_offsets[++j] = at;
+        }
+    return FSO_OK;
+}
+
+/* Input of the AllToAll: feature-major in; out holds, rank after rank, what each rank is sent - itself a
+ * feature-major keyed jagged tensor over that rank's samples.  splits[r] = elements sent to rank r. */
+int fso_jagged_ranged_dispatch(const void *values, int32_t elem_bytes, const int64_t *offsets, int64_t F, int64_t B,
+                               const int64_t *rank_offsets, int32_t n_ranks, void *out_values, int64_t *out_offsets,
+                               int64_t *splits)
+{
+    if (F < 0 || B < 0 || elem_bytes <= 0) return FSO_EINVAL;
+    if (check_segments(offsets, F * B) != FSO_OK || check_ranges(rank_offsets, n_ranks, B) != FSO_OK) return FSO_ERANGE;
+    int64_t at = 0, j = 0;
+    out_offsets[0] = 0;
+    for (int32_t r = 0; r < n_ranks; ++r) {
+        int64_t start = at;
+        for (int64_t f = 0; f < F; ++f)
+            for (int64_t b = rank_offsets[r]; b < rank_offsets[r + 1]; ++b) {
+                copy_segment(values, elem_bytes, offsets, f * B + b, out_values, &at);
+                out_offsets[++j] = at;
+            }
+        splits[r] = at - start;
+    }
+    return FSO_OK;
+}
+
+/* Output of the AllToAll: `values` holds, source rank after source rank, a feature-major keyed jagged tensor
+ * over that rank's samples (what fso_jagged_ranged_dispatch lays out); out is one feature-major tensor over
+ * all B samples. */
+int fso_jagged_ranged_combine(const void *values, int32_t elem_bytes, const int64_t *offsets, int64_t F, int64_t B,
+                              const int64_t *rank_offsets, int32_t n_ranks, void *out_values, int64_t *out_offsets)
+{
+    if (F < 0 || B < 0 || elem_bytes <= 0) return FSO_EINVAL;
+    if (check_segments(offsets, F * B) != FSO_OK || check_ranges(rank_offsets, n_ranks, B) != FSO_OK) return FSO_ERANGE;
+    int64_t at = 0, j = 0;
+    out_offsets[0] = 0;
+    for (int64_t f = 0; f < F; ++f)
+        for (int32_t r = 0; r < n_ranks; ++r) {
+            int64_t first = rank_offsets[r], count = rank_offsets[r + 1] - first;
+            for (int64_t i = 0; i < count; ++i) {
+                copy_segment(values, elem_bytes, offsets, F * first + f * count + i, out_values, &at);
+                out_offsets[++j] = at;
+            }
+        }
     return FSO_OK;
 }
 

@@ -530,3 +530,53 @@ def test_indexed_permute_matches_list_concatenation(seed):
     assert np.array_equal(out, np.concatenate([rows[offsets[p]:offsets[p + 1]] for p in perm]))
     with pytest.raises(O.OracleError):
         O.jagged_indexed_permute(values, offsets, np.array([B], dtype=np.int32))
+
+
+# ------------------------------------------- keyed transpose, ranged dispatch, ranged combine
+def _kjt(rng, F, B, width=0):
+    lens = rng.integers(0, 6, size=F * B)
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    n = int(offsets[-1])
+    values = rng.integers(0, 10**9, size=(n,) if width == 0 else (n, width)).astype(np.int64)
+    segs = [[values[offsets[f * B + b]:offsets[f * B + b + 1]] for b in range(B)] for f in range(F)]   # [f][b]
+    return values, offsets, segs
+
+
+def _cat(pieces, like):
+    pieces = list(pieces)
+    return np.concatenate(pieces) if pieces else like[:0]
+
+
+@pytest.mark.parametrize("F,B,width", [(3, 5, 0), (1, 7, 0), (4, 1, 2), (2, 0, 0), (6, 9, 3)])
+def test_keyed_transpose_matches_nested_lists(F, B, width):
+    rng = np.random.default_rng(F * 10 + B)
+    values, offsets, segs = _kjt(rng, F, B, width)
+    out, out_off = O.jagged_keyed_transpose(values, offsets, F, B)
+    want = [segs[f][b] for b in range(B) for f in range(F)]
+    assert np.array_equal(out, _cat(want, values))
+    assert out_off.tolist() == [0] + list(np.cumsum([len(x) for x in want]))
+    # transposing back (the roles of keys and samples swapped) gives the input
+    back, back_off = O.jagged_keyed_transpose(out, out_off, B, F)
+    assert np.array_equal(back, values) and back_off.tolist() == offsets.tolist()
+
+
+@pytest.mark.parametrize("F,B,cuts", [(3, 10, [0, 4, 4, 7, 10]), (1, 6, [0, 2, 6]), (2, 5, [0, 5]), (4, 8, [0, 1, 2, 3, 8])])
+def test_ranged_dispatch_and_combine_match_nested_lists_and_undo_each_other(F, B, cuts):
+    rng = np.random.default_rng(F * 100 + B)
+    values, offsets, segs = _kjt(rng, F, B, 0)
+    ro = np.array(cuts, dtype=np.int64)
+    out, out_off, splits = O.jagged_ranged_dispatch(values, offsets, F, B, ro)
+    per_rank = [[segs[f][b] for f in range(F) for b in range(cuts[r], cuts[r + 1])] for r in range(len(cuts) - 1)]
+    want = [x for rank in per_rank for x in rank]
+    assert np.array_equal(out, _cat(want, values))
+    assert out_off.tolist() == [0] + list(np.cumsum([len(x) for x in want]))
+    assert splits.tolist() == [sum(len(x) for x in rank) for rank in per_rank]
+    back, back_off = O.jagged_ranged_combine(out, out_off, F, B, ro)
+    assert np.array_equal(back, values) and back_off.tolist() == offsets.tolist()
+    if F == 1:
+        # one key: what every rank is sent already lies in rank order
+        assert np.array_equal(out, values) and out_off.tolist() == offsets.tolist()
+    with pytest.raises(O.OracleError):
+        O.jagged_ranged_dispatch(values, offsets, F, B, np.array([0, B + 1], dtype=np.int64))
+    with pytest.raises(O.OracleError):
+        O.jagged_ranged_combine(values, offsets, F, B, np.array([0, 3, 2, B], dtype=np.int64))
