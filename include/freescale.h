@@ -183,6 +183,34 @@ int fs_jagged_indexed_permute(fs_ctx *ctx, const void *values, int64_t n_values,
                               const int64_t *offsets, int64_t B, const int32_t *sample_of, int64_t n_out,
                               void *out_values, int64_t cap_out, int64_t *out_offsets, fs_stream stream);
 
+/* The other jagged shuffles Section 4.2 names, on a keyed jagged tensor: F keys (features) x B samples, F * B
+ * segments described by offsets [F * B + 1] over values [n_values] of elem_bytes bytes each (a multiple of 4).
+ * Feature-major: segment (f, b) is number f * B + b; batch-major: number b * F + f.  The paper states what
+ * these kernels are for, not their layouts; the layouts below are this library's.  Each writes out_values
+ * [n_values] and out_offsets [F * B + 1]; F * B <= context max_ids; malformed offsets or ranges are reported
+ * as FS_ERANGE by fs_check_async (the segments concerned come out empty).
+ *
+ * Keyed transpose: feature-major in, batch-major out. */
+int fs_jagged_keyed_transpose(fs_ctx *ctx, const void *values, int64_t n_values, int32_t elem_bytes,
+                              const int64_t *offsets, int64_t F, int64_t B, void *out_values, int64_t *out_offsets,
+                              fs_stream stream);
+
+/* Ranged dispatch: the input of the ID or embedding AllToAll.  Rank r of n_ranks owns the samples
+ * [rank_offsets[r], rank_offsets[r + 1]) (rank_offsets [n_ranks + 1] int64 on the device, ascending from 0 to
+ * B - what fs_partition_fbs and fs_jagged_indexed_permute leave).  Feature-major in; out holds, rank after
+ * rank, the feature-major tensor over that rank's samples; splits [n_ranks] int64 = elements sent to each. */
+int fs_jagged_ranged_dispatch(fs_ctx *ctx, const void *values, int64_t n_values, int32_t elem_bytes,
+                              const int64_t *offsets, int64_t F, int64_t B, const int64_t *rank_offsets,
+                              int32_t n_ranks, void *out_values, int64_t *out_offsets, int64_t *splits,
+                              fs_stream stream);
+
+/* Ranged combine: the output of the AllToAll.  `values` / `offsets` hold, source rank after source rank, the
+ * feature-major tensor over that rank's samples (the layout fs_jagged_ranged_dispatch produces); out is one
+ * feature-major tensor over all B samples.  Undoes fs_jagged_ranged_dispatch for the same ranges. */
+int fs_jagged_ranged_combine(fs_ctx *ctx, const void *values, int64_t n_values, int32_t elem_bytes,
+                             const int64_t *offsets, int64_t F, int64_t B, const int64_t *rank_offsets,
+                             int32_t n_ranks, void *out_values, int64_t *out_offsets, fs_stream stream);
+
 /* ---- the fused update path of the whole iteration ------------------------------------------ */
 
 /* Rows with at most this many occurrences in a batch take the short path of the fused update (all

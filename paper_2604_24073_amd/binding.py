@@ -74,6 +74,11 @@ def load_library() -> ctypes.CDLL:
         "fs_gather_jagged_class": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i32, ctypes.c_int, c_vp, c_vp, c_i64, c_i64, c_vp,
                                                   c_vp, ctypes.c_int, c_vp, S]),
         "fs_unique_ids": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i64, c_vp, c_vp, c_vp, c_vp, c_vp, S]),
+        "fs_jagged_keyed_transpose": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i32, c_vp, c_i64, c_i64, c_vp, c_vp, S]),
+        "fs_jagged_ranged_dispatch": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i32, c_vp, c_i64, c_i64, c_vp, c_i32, c_vp,
+                                                     c_vp, c_vp, S]),
+        "fs_jagged_ranged_combine": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i32, c_vp, c_i64, c_i64, c_vp, c_i32, c_vp,
+                                                    c_vp, S]),
         "fs_partition_fbs": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i64, c_i32, c_vp, c_vp, S]),
         "fs_jagged_indexed_permute": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i32, c_vp, c_i64, c_vp, c_i64, c_vp, c_i64,
                                                      c_vp, S]),
@@ -244,9 +249,7 @@ def fs_jagged_indexed_permute(ctx: Context, values: torch.Tensor, offsets: torch
                               cap_out: int, stream=None):
     """(out_values [cap_out, ...], out_offsets [n_out + 1]); values is [n] or [n, width], any 4- or 8-byte dtype."""
     n_values = values.shape[0]
-    elem = values.element_size()
-    for d in values.shape[1:]:
-        elem *= d
+    elem = _elem_bytes(values)
     out = torch.empty((cap_out,) + tuple(values.shape[1:]), dtype=values.dtype, device=values.device)
     n_out = sample_of.numel()
     out_offsets = torch.empty(n_out + 1, dtype=torch.int64, device=values.device)
@@ -254,6 +257,43 @@ def fs_jagged_indexed_permute(ctx: Context, values: torch.Tensor, offsets: torch
                                            _ptr(sample_of), n_out, _ptr(out), cap_out, _ptr(out_offsets),
                                            _stream(stream))
     ctx.check(rc, "fs_jagged_indexed_permute")
+    return out, out_offsets
+
+
+def _elem_bytes(values: torch.Tensor) -> int:
+    elem = values.element_size()
+    for d in values.shape[1:]:
+        elem *= d
+    return elem
+
+
+def fs_jagged_keyed_transpose(ctx: Context, values: torch.Tensor, offsets: torch.Tensor, F: int, B: int, stream=None):
+    out, out_offsets = torch.empty_like(values), torch.empty_like(offsets)
+    rc = ctx.lib.fs_jagged_keyed_transpose(ctx.handle, _ptr(values), values.shape[0], _elem_bytes(values), _ptr(offsets),
+                                           F, B, _ptr(out), _ptr(out_offsets), _stream(stream))
+    ctx.check(rc, "fs_jagged_keyed_transpose")
+    return out, out_offsets
+
+
+def fs_jagged_ranged_dispatch(ctx: Context, values: torch.Tensor, offsets: torch.Tensor, F: int, B: int,
+                              rank_offsets: torch.Tensor, stream=None):
+    out, out_offsets = torch.empty_like(values), torch.empty_like(offsets)
+    n_ranks = rank_offsets.numel() - 1
+    splits = torch.empty(max(n_ranks, 1), dtype=torch.int64, device=values.device)
+    rc = ctx.lib.fs_jagged_ranged_dispatch(ctx.handle, _ptr(values), values.shape[0], _elem_bytes(values), _ptr(offsets),
+                                           F, B, _ptr(rank_offsets), n_ranks, _ptr(out), _ptr(out_offsets), _ptr(splits),
+                                           _stream(stream))
+    ctx.check(rc, "fs_jagged_ranged_dispatch")
+    return out, out_offsets, splits[:n_ranks]
+
+
+def fs_jagged_ranged_combine(ctx: Context, values: torch.Tensor, offsets: torch.Tensor, F: int, B: int,
+                             rank_offsets: torch.Tensor, stream=None):
+    out, out_offsets = torch.empty_like(values), torch.empty_like(offsets)
+    rc = ctx.lib.fs_jagged_ranged_combine(ctx.handle, _ptr(values), values.shape[0], _elem_bytes(values), _ptr(offsets),
+                                          F, B, _ptr(rank_offsets), rank_offsets.numel() - 1, _ptr(out),
+                                          _ptr(out_offsets), _stream(stream))
+    ctx.check(rc, "fs_jagged_ranged_combine")
     return out, out_offsets
 
 

@@ -160,6 +160,7 @@ void carve(fs_ctx *c, char *base, size_t *total) {
     c->jag_n = cv.take<int64_t>(1);
     c->jag_sorted = cv.take<int32_t>(n + 16);
     c->jag_tile_sum = cv.take<int64_t>(scan_tiles);
+    c->jag_sel = cv.take<int32_t>(n + 16);
     *total = align_up(cv.off, 256);
 }
 
@@ -442,6 +443,45 @@ int fs_jagged_indexed_permute(fs_ctx *ctx, const void *values, int64_t n_values,
     if (jrc != FS_OK) return jrc;
     return launch_indexed_permute(ctx, values, n_values, elem_bytes, offsets, B, sample_of, n_out, out_values, cap_out,
                                   out_offsets, as_stream(stream));
+}
+
+namespace {
+int keyed_shuffle(fs_ctx *ctx, int mode, const void *values, int64_t n_values, int32_t elem_bytes, const int64_t *offsets,
+                  int64_t F, int64_t B, const int64_t *rank_offsets, int32_t n_ranks, void *out_values,
+                  int64_t *out_offsets, int64_t *splits, fs_stream stream) {
+    if (!ctx) return FS_EINVAL;
+    FS_REQUIRE(ctx, n_values >= 0 && F >= 0 && B >= 0, "keyed shuffle: negative size");
+    FS_REQUIRE(ctx, elem_bytes > 0 && elem_bytes % 4 == 0, "keyed shuffle: elem_bytes must be a multiple of 4");
+    if (F > 0 && B > ctx->max_ids / F) return set_err(ctx, FS_ENOMEM, "keyed shuffle: F * B beyond the context capacity");
+    FS_REQUIRE(ctx, offsets && out_offsets && (n_values == 0 || (values && out_values)), "keyed shuffle: null pointer");
+    if (mode != 0) FS_REQUIRE(ctx, n_ranks >= 1 && rank_offsets, "keyed shuffle: no ranks");
+    const int jrc = join_pending_work(ctx, as_stream(stream));
+    if (jrc != FS_OK) return jrc;
+    return launch_keyed_shuffle(ctx, mode, values, n_values, elem_bytes, offsets, F, B, rank_offsets, n_ranks, out_values,
+                                out_offsets, splits, as_stream(stream));
+}
+}  // namespace
+
+int fs_jagged_keyed_transpose(fs_ctx *ctx, const void *values, int64_t n_values, int32_t elem_bytes,
+                              const int64_t *offsets, int64_t F, int64_t B, void *out_values, int64_t *out_offsets,
+                              fs_stream stream) {
+    return keyed_shuffle(ctx, 0, values, n_values, elem_bytes, offsets, F, B, nullptr, 0, out_values, out_offsets, nullptr,
+                         stream);
+}
+
+int fs_jagged_ranged_dispatch(fs_ctx *ctx, const void *values, int64_t n_values, int32_t elem_bytes,
+                              const int64_t *offsets, int64_t F, int64_t B, const int64_t *rank_offsets, int32_t n_ranks,
+                              void *out_values, int64_t *out_offsets, int64_t *splits, fs_stream stream) {
+    if (ctx && !splits) return set_err(ctx, FS_EINVAL, "ranged dispatch: null splits");
+    return keyed_shuffle(ctx, 1, values, n_values, elem_bytes, offsets, F, B, rank_offsets, n_ranks, out_values,
+                         out_offsets, splits, stream);
+}
+
+int fs_jagged_ranged_combine(fs_ctx *ctx, const void *values, int64_t n_values, int32_t elem_bytes,
+                             const int64_t *offsets, int64_t F, int64_t B, const int64_t *rank_offsets, int32_t n_ranks,
+                             void *out_values, int64_t *out_offsets, fs_stream stream) {
+    return keyed_shuffle(ctx, 2, values, n_values, elem_bytes, offsets, F, B, rank_offsets, n_ranks, out_values,
+                         out_offsets, nullptr, stream);
 }
 
 int fs_init_table_hash(fs_ctx *ctx, void *table, int64_t num_rows, int32_t dim, fs_dtype dt, fs_stream stream) {

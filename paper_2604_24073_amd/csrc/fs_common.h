@@ -163,6 +163,7 @@ struct fs_ctx {
     int64_t *jag_n;           // [1]
     int32_t *jag_sorted;      // [max_ids] samples in ascending order of length
     int64_t *jag_tile_sum;    // [scan tiles] output elements per tile of output samples
+    int32_t *jag_sel;         // [max_ids] computed segment order of a keyed shuffle
 
     hipStream_t stream_a;     // side stream: index half of the lookahead batch; deferred pass of a pipelined call
     hipStream_t stream_b;     // deferred pass of the self-contained step
@@ -237,6 +238,10 @@ int launch_partition_fbs(fs_ctx *, const int64_t *lengths, int64_t B, int64_t ma
 int launch_indexed_permute(fs_ctx *, const void *values, int64_t n_values, int32_t elem_bytes, const int64_t *offsets,
                            int64_t B, const int32_t *sample_of, int64_t n_out, void *out_values, int64_t cap_out,
                            int64_t *out_offsets, hipStream_t s);
+// mode 0 keyed transpose, 1 ranged dispatch, 2 ranged combine (rank_offsets / splits unused by the transpose)
+int launch_keyed_shuffle(fs_ctx *, int mode, const void *values, int64_t n_values, int32_t elem_bytes,
+                         const int64_t *offsets, int64_t F, int64_t B, const int64_t *rank_offsets, int32_t n_ranks,
+                         void *out_values, int64_t *out_offsets, int64_t *splits, hipStream_t s);
 // event pair of timing kind `kind` for the step being enqueued, or nullptr when timing is off
 inline hipEvent_t *timing_pair(fs_ctx *ctx, int kind) {
     if (!ctx->timing_now) return nullptr;

@@ -12,6 +12,10 @@
 // item what a short one costs): a workgroup takes 2048 consecutive output pieces, finds the samples
 // they belong to with two 64-ary searches, stages their boundaries in LDS and lets every piece
 // binary-search LDS.
+//
+// Keyed transpose, ranged dispatch and ranged combine (same section of the paper) are the same copy
+// under a computed order of the F x B segments of a keyed jagged tensor: one more launch writes that
+// order down, then the three launches above run.
 #include "fs_common.h"
 #include "fs_device.h"
 
@@ -264,6 +268,85 @@ int launch_indexed_permute(fs_ctx *ctx, const void *values, int64_t n_values, in
                                in, sample_of, n_out, out_offsets, cap_out, ppe, (uint32_t *)out_values);
     }
     FS_LAUNCH_CHECK(ctx, "indexed permute kernels");
+    return FS_OK;
+}
+
+// ---- keyed transpose, ranged dispatch, ranged combine ---------------------------------------------------
+// Segment (f, b) of a keyed jagged tensor with F keys and B samples is number f * B + b in feature-major
+// form and b * F + f in batch-major form.  Ranks own sample ranges [ro[r], ro[r + 1]); what a rank is sent
+// (dispatch) or has sent (combine) is a feature-major tensor over its own samples, rank after rank.
+enum { kMapTranspose = 0, kMapDispatch = 1, kMapCombine = 2 };
+
+// the last r in [0, n) with scale * ro[r] <= x (ro ascending, ro[0] == 0)
+__device__ __forceinline__ int last_rank_at_or_before(const int64_t *__restrict__ ro, int n, int64_t scale, int64_t x) {
+    int lo = 0, hi = n;                      // first r with scale * ro[r] > x
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (scale * ro[mid] <= x) lo = mid + 1; else hi = mid;
+    }
+    return lo > 0 ? lo - 1 : 0;
+}
+
+__global__ __launch_bounds__(256) void segment_map_kernel(int mode, int64_t F, int64_t B,
+                                                          const int64_t *__restrict__ ro, int n_ranks,
+                                                          int32_t *__restrict__ sel, int *__restrict__ flags) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t gtid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (mode != kMapTranspose) {
+        bool bad = false;
+        for (int64_t r = gtid; r < n_ranks; r += stride) bad |= ro[r + 1] < ro[r];
+        if (gtid == 0) bad |= ro[0] != 0 || ro[n_ranks] != B;
+        if (bad) atomicOr(flags, kFlagOffsets);
+    }
+    for (int64_t j = gtid; j < F * B; j += stride) {
+        int64_t in = -1;                     // stays -1 for ranges that make no sense: the copy skips and reports it
+        if (mode == kMapTranspose) {
+            in = (j % F) * B + j / F;
+        } else if (mode == kMapDispatch) {
+            const int r = last_rank_at_or_before(ro, n_ranks, F, j);
+            const int64_t first = ro[r], cnt = ro[r + 1] - first, local = j - F * first;
+            if (cnt > 0 && local >= 0 && local < F * cnt) in = (local / cnt) * B + first + local % cnt;
+        } else {
+            const int64_t f = j / B, b = j % B;
+            const int r = last_rank_at_or_before(ro, n_ranks, 1, b);
+            const int64_t first = ro[r], cnt = ro[r + 1] - first;
+            if (cnt > 0 && b >= first && b < first + cnt) in = F * first + f * cnt + (b - first);
+        }
+        sel[j] = (in >= 0 && in < F * B) ? (int32_t)in : -1;
+    }
+}
+
+// elements each rank is sent: the extent of its F * count segments in the dispatched tensor
+__global__ __launch_bounds__(256) void dispatch_splits_kernel(int64_t F, int64_t B, const int64_t *__restrict__ ro,
+                                                              int n_ranks, const int64_t *__restrict__ out_offsets,
+                                                              int64_t *__restrict__ splits) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < n_ranks; r += stride) {
+        int64_t a = ro[r], b = ro[r + 1];
+        a = a < 0 ? 0 : (a > B ? B : a);
+        b = b < a ? a : (b > B ? B : b);
+        splits[r] = out_offsets[F * b] - out_offsets[F * a];
+    }
+}
+
+int launch_keyed_shuffle(fs_ctx *ctx, int mode, const void *values, int64_t n_values, int32_t elem_bytes,
+                         const int64_t *offsets, int64_t F, int64_t B, const int64_t *rank_offsets, int32_t n_ranks,
+                         void *out_values, int64_t *out_offsets, int64_t *splits, hipStream_t s) {
+    const int64_t segs = F * B;
+    if (segs > 0) {
+        int64_t blocks = ceil_div(segs, 256);
+        if (blocks > 1024) blocks = 1024;
+        hipLaunchKernelGGL(segment_map_kernel, dim3((unsigned)blocks), dim3(256), 0, s, mode, F, B, rank_offsets,
+                           (int)n_ranks, ctx->jag_sel, ctx->d_flags);
+    }
+    const int rc = launch_indexed_permute(ctx, values, n_values, elem_bytes, offsets, segs, ctx->jag_sel, segs,
+                                          out_values, n_values, out_offsets, s);
+    if (rc != FS_OK) return rc;
+    if (splits != nullptr && n_ranks > 0) {
+        hipLaunchKernelGGL(dispatch_splits_kernel, dim3((unsigned)ceil_div(n_ranks, 256)), dim3(256), 0, s, F, B,
+                           rank_offsets, (int)n_ranks, out_offsets, splits);
+        FS_LAUNCH_CHECK(ctx, "dispatch_splits_kernel");
+    }
     return FS_OK;
 }
 

@@ -131,3 +131,63 @@ def test_indexed_permute_reports_bad_selections_and_short_outputs():
                                      dev(np.array([0], dtype=np.int32)), 4)
     assert e.value.code == fs.FS_EINVAL
     ctx.close()
+
+
+def keyed(rng, F, B, dtype, width, hi=40):
+    lens = rng.integers(0, hi, size=F * B)
+    if F * B > 20:
+        lens[rng.integers(0, F * B, size=F * B // 8)] = 0
+    return jagged(rng, lens, dtype, width)
+
+
+@pytest.mark.parametrize("F,B,dtype,width", [(8, 512, np.int64, 0), (1, 3000, np.int64, 0), (26, 1, np.int32, 0),
+                                             (3, 700, np.float32, 16), (5, 0, np.int64, 0), (2, 4096, np.float32, 3)])
+def test_keyed_transpose_matches_oracle(F, B, dtype, width):
+    rng = np.random.default_rng(F * 1000 + B)
+    values, offsets = keyed(rng, F, B, dtype, width)
+    ctx = fs.Context(max_ids=max(F * B, 16), max_dim=8)
+    out, out_off = fs.fs_jagged_keyed_transpose(ctx, dev(values), dev(offsets), F, B)
+    assert fs.fs_check_async(ctx) == fs.FS_OK, ctx.last_error()
+    want, want_off = O.jagged_keyed_transpose(values, offsets, F, B)
+    assert out_off.cpu().numpy().tolist() == want_off.tolist()
+    assert out.cpu().numpy().tobytes() == want.tobytes()
+    ctx.close()
+
+
+@pytest.mark.parametrize("F,B,n_ranks,dtype,width", [(4, 1024, 8, np.int64, 0), (1, 2048, 512, np.int64, 0),
+                                                     (6, 333, 32, np.float32, 8), (2, 5, 8, np.int64, 0),
+                                                     (3, 1000, 1, np.int32, 0)])
+def test_ranged_dispatch_and_combine_match_oracle(F, B, n_ranks, dtype, width):
+    rng = np.random.default_rng(F * 77 + B + n_ranks)
+    values, offsets = keyed(rng, F, B, dtype, width)
+    # ranges as the FBS partitioner leaves them (some ranks may be empty when there are more ranks than samples)
+    _, ro = O.partition_fbs(rng.integers(1, 100, size=B).astype(np.int64), n_ranks)
+    ctx = fs.Context(max_ids=max(F * B, 16), max_dim=8)
+    d_ro = dev(ro)
+    out, out_off, splits = fs.fs_jagged_ranged_dispatch(ctx, dev(values), dev(offsets), F, B, d_ro)
+    assert fs.fs_check_async(ctx) == fs.FS_OK, ctx.last_error()
+    want, want_off, want_splits = O.jagged_ranged_dispatch(values, offsets, F, B, ro)
+    assert out_off.cpu().numpy().tolist() == want_off.tolist()
+    assert splits.cpu().numpy().tolist() == want_splits.tolist()
+    assert out.cpu().numpy().tobytes() == want.tobytes()
+    back, back_off = fs.fs_jagged_ranged_combine(ctx, out, out_off, F, B, d_ro)
+    assert fs.fs_check_async(ctx) == fs.FS_OK, ctx.last_error()
+    want_b, want_b_off = O.jagged_ranged_combine(want, want_off, F, B, ro)
+    assert back_off.cpu().numpy().tolist() == want_b_off.tolist() == offsets.tolist()
+    assert back.cpu().numpy().tobytes() == want_b.tobytes() == values.tobytes()
+    ctx.close()
+
+
+def test_ranged_dispatch_reports_ranges_that_do_not_cover_the_samples():
+    rng = np.random.default_rng(8)
+    values, offsets = keyed(rng, 2, 50, np.int64, 0)
+    ctx = fs.Context(max_ids=256, max_dim=8)
+    for ro in ([0, 20, 60], [0, 30, 20, 50], [5, 20, 50]):
+        fs.fs_jagged_ranged_dispatch(ctx, dev(values), dev(offsets), 2, 50, dev(np.array(ro, dtype=np.int64)))
+        assert fs.fs_check_async(ctx) == fs.FS_ERANGE, ro
+        fs.fs_jagged_ranged_combine(ctx, dev(values), dev(offsets), 2, 50, dev(np.array(ro, dtype=np.int64)))
+        assert fs.fs_check_async(ctx) == fs.FS_ERANGE, ro
+    with pytest.raises(fs.FreeScaleError) as e:
+        fs.fs_jagged_keyed_transpose(ctx, dev(values), dev(offsets), 2, 200)
+    assert e.value.code == fs.FS_ENOMEM
+    ctx.close()
