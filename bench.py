@@ -257,6 +257,8 @@ def main() -> int:
     ap.add_argument("--two-part", action="store_true",
                     help="the lookup in the two parts of Algorithm 2 (fs_prioritized_step_two_part_multi): exclusive "
                          "rows of the batch after next fetched on the side stream, collision rows after the priority pass")
+    ap.add_argument("--no-widening", action="store_true",
+                    help="skip the load balancer's data path (partitioner and jagged shuffles) timed after the step")
     ap.add_argument("--keep-reduced", action="store_true",
                     help="also write the summed gradients to memory in the timed steps (the step itself does not "
                          "need them there)")
@@ -572,6 +574,60 @@ def main() -> int:
         isolated = {k: {"us": t, "algorithmic_bytes": nb, "GBps": nb / (t * 1e-6) / 1e9,
                         "frac_of_hbm_peak": nb / (t * 1e-6) / 1e9 / HBM_PEAK_GBPS} for k, (t, nb) in iso.items()}
 
+    # ---- beside the metric: the load balancer's data path (Sections 4.1 and 4.2 of the paper) on the batch a
+    # job of 64 ranks with this configuration's local batch would balance; each operation alone on the chip
+    balancer = None
+    if not args.no_widening and tab.dtype == "f32" and cfg.batch * 64 <= nmax:
+        from fs_workloads.generators import powerlaw_lengths
+        fs.fs_step_join(ctx)
+        torch.cuda.synchronize()
+        ranks, keys = 64, 4
+        Bg = cfg.batch * ranks
+        rng = np.random.default_rng(20240)
+        lens = powerlaw_lengths(rng, Bg, 1.5, cfg.length_lo, cfg.length_hi)
+        offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+        ng = int(offs[-1])
+        d_len, d_off = torch.from_numpy(lens).to(dev), torch.from_numpy(offs).to(dev)
+        d_ids = torch.randint(0, tab.num_rows, (ng,), dtype=torch.int64, device=dev)
+
+        def timed(f, reps=10):
+            for _ in range(2):
+                f()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                f()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps * 1e3
+
+        sample_of, rank_off = fs.fs_partition_fbs(ctx, d_len, cfg.length_hi, ranks)
+        Bk = Bg // keys                                   # the same segments read as keys x samples
+        _, rank_off_k = fs.fs_partition_fbs(ctx, d_len[:Bk], cfg.length_hi, ranks)
+        disp, disp_off, _ = fs.fs_jagged_ranged_dispatch(ctx, d_ids, d_off, keys, Bk, rank_off_k)
+        emb_rows, emb_off = embs[1], d_offs[1]            # the gathered rows of one local batch, 512 bytes each
+        local_of, _ = fs.fs_partition_fbs(ctx, (emb_off[1:] - emb_off[:-1]).contiguous(), cfg.length_hi, 8)
+        seg_bytes = 3 * 8 * Bg
+        ops = {
+            f"fs_partition_fbs ({Bg} samples, {ranks} ranks)":
+                (timed(lambda: fs.fs_partition_fbs(ctx, d_len, cfg.length_hi, ranks)), 8 * Bg + 4 * Bg),
+            f"fs_jagged_indexed_permute ({ng} IDs of {Bg} samples, FBS order)":
+                (timed(lambda: fs.fs_jagged_indexed_permute(ctx, d_ids, d_off, sample_of, ng)), 16 * ng + seg_bytes),
+            f"fs_jagged_ranged_dispatch ({ng} IDs, {keys} keys x {Bk} samples, {ranks} ranks)":
+                (timed(lambda: fs.fs_jagged_ranged_dispatch(ctx, d_ids, d_off, keys, Bk, rank_off_k)), 16 * ng + seg_bytes),
+            f"fs_jagged_ranged_combine (the same, back)":
+                (timed(lambda: fs.fs_jagged_ranged_combine(ctx, disp, disp_off, keys, Bk, rank_off_k)), 16 * ng + seg_bytes),
+            f"fs_jagged_keyed_transpose ({ng} IDs, {keys} keys x {Bk} samples)":
+                (timed(lambda: fs.fs_jagged_keyed_transpose(ctx, d_ids, d_off, keys, Bk)), 16 * ng + seg_bytes),
+            f"fs_jagged_indexed_permute ({n[1]} embedding rows of {dim * 4} bytes, {cfg.batch} samples)":
+                (timed(lambda: fs.fs_jagged_indexed_permute(ctx, emb_rows, emb_off, local_of, n[1])), 2 * n[1] * dim * 4),
+        }
+        assert fs.fs_check_async(ctx) == fs.FS_OK, ctx.last_error()
+        balancer = {k: {"us": t, "algorithmic_bytes": nb, "GBps": nb / (t * 1e-6) / 1e9,
+                        "frac_of_hbm_peak": nb / (t * 1e-6) / 1e9 / HBM_PEAK_GBPS} for k, (t, nb) in ops.items()}
+        del d_ids, disp
+
     out = {
         "metric": "unique embedding rows updated/sec + achieved HBM GB/s (% of peak), 1 GPU",
         "value": rows / elapsed, "unit": "rows/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -593,6 +649,7 @@ def main() -> int:
         "kernel_avg_us": {k: (v * 1e3 if v is not None else None) for k, v in kernel_ms.items()},
         "roofline": roofline,
         "isolated_kernels": isolated,
+        "load_balancer_path": balancer,
         "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(out))

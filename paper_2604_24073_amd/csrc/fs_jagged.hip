@@ -9,7 +9,7 @@
 // Indexed permute: output sample k is input sample sample_of[k].  Three launches: lengths summed per
 // tile of samples, the output offsets by a scan with tile prefixes, and the copy.  The copy is driven
 // by the OUTPUT (every lane writes consecutive pieces of the output, so a 16K-item sample costs per
-// item what a short one costs): a workgroup takes 2048 consecutive output pieces, finds the samples
+// item what a short one costs): a workgroup takes 8192 consecutive output pieces, finds the samples
 // they belong to with two 64-ary searches, stages their boundaries in LDS and lets every piece
 // binary-search LDS.
 //
@@ -171,18 +171,22 @@ __device__ __forceinline__ int64_t wave_upper_bound(const int64_t *__restrict__ 
     return lo;
 }
 
-constexpr int kCopyPieces = 8;                                  // pieces per thread
-constexpr int kCopyTile = kScanThreads * kCopyPieces;           // pieces per workgroup
-constexpr int kCopyWindow = kCopyTile + 2;                      // sample boundaries staged in LDS
+constexpr int kCopyPieces = 8;                                  // pieces per thread and round
+constexpr int kCopyRounds = 4;                                  // rounds per workgroup: the searches that open a tile
+                                                                // are a chain of dependent loads, paid once per tile
+constexpr int kCopyTile = kScanThreads * kCopyPieces * kCopyRounds;   // pieces per workgroup
+constexpr int kCopyWindow = 2048 + 2;                           // sample boundaries staged in LDS
 
-// V: the piece, the widest of 4, 8, 16 bytes that divides the element; ppe pieces per element
+// V: the piece, the widest of 4, 8, 16 bytes that divides the element; ppe pieces per element.
+// Inside a tile everything is counted from the tile's first element in 32 bits (a 64-bit division per
+// piece would cost more than the copy).
 template <typename V>
 __global__ __launch_bounds__(kScanThreads) void permute_copy_kernel(const V *__restrict__ values, const jagged_in in,
                                                                     const int32_t *__restrict__ sample_of,
                                                                     int64_t n_out, const int64_t *__restrict__ out_offsets,
                                                                     int64_t cap_out, int ppe, V *__restrict__ out) {
-    __shared__ int64_t w_start[kCopyWindow];    // out_offsets[k0 + j]
-    __shared__ int64_t w_delta[kCopyWindow];    // first input element of sample k0 + j minus its first output element
+    __shared__ int32_t w_rel[kCopyWindow];      // out_offsets[ka + j] minus the tile's first element (at least -1)
+    __shared__ int64_t w_delta[kCopyWindow];    // first input element of sample ka + j minus its first output element
     __shared__ int64_t win[2];
     const int64_t *__restrict__ offsets = in.offsets;
     int64_t total = out_offsets[n_out];
@@ -190,55 +194,79 @@ __global__ __launch_bounds__(kScanThreads) void permute_copy_kernel(const V *__r
     const int64_t pieces = total * ppe;
     const int64_t q0 = (int64_t)blockIdx.x * kCopyTile;
     if (q0 >= pieces) return;                                   // whole workgroup
-    const int64_t q1 = (q0 + kCopyTile < pieces ? q0 + kCopyTile : pieces) - 1;      // last piece of the tile
-    if (threadIdx.x < kWave) {
-        // sample of an element e: the last k with out_offsets[k] <= e (empty samples in between are skipped)
-        const int64_t ka = wave_upper_bound(out_offsets, n_out + 1, q0 / ppe) - 1;
-        const int64_t kb = wave_upper_bound(out_offsets, n_out + 1, q1 / ppe) - 1;
-        if (threadIdx.x == 0) { win[0] = ka; win[1] = kb; }
+    const uint32_t tile_pieces = (uint32_t)((q0 + kCopyTile < pieces ? q0 + kCopyTile : pieces) - q0);
+    const int64_t e0 = q0 / ppe;                                // first element of the tile
+    const uint32_t rem0 = (uint32_t)(q0 - e0 * ppe);            // pieces of it that belong to the tile before
+    const int64_t e1 = (q0 + tile_pieces - 1) / ppe;            // last element of the tile
+    if (threadIdx.x < 2 * kWave) {
+        // sample of an element e: the last k with out_offsets[k] <= e (empty samples in between are skipped);
+        // the first wavefront looks for the sample of the tile's first element, the second for that of its last
+        const int w = threadIdx.x / kWave;
+        const int64_t k = wave_upper_bound(out_offsets, n_out + 1, w == 0 ? e0 : e1) - 1;
+        if ((threadIdx.x & (kWave - 1)) == 0) win[w] = k;
     }
     __syncthreads();
     const int64_t ka = win[0], kb = win[1];
-    const int64_t wn = kb - ka + 1;                             // samples touched by the tile
-    const bool staged = wn <= kCopyWindow;
+    const bool staged = kb - ka + 1 <= kCopyWindow;             // else: the samples touched by the tile do not fit
+    const int wn = staged ? (int)(kb - ka + 1) : 0;
     if (staged)
-        for (int64_t j = threadIdx.x; j < wn; j += kScanThreads) {
+        for (int j = threadIdx.x; j < wn; j += kScanThreads) {
             const int64_t start = out_offsets[ka + j];
             const int64_t p = sample_of[ka + j];
-            w_start[j] = start;
-            w_delta[j] = (p >= 0 && p < in.B) ? offsets[p] - start : 0;     // a flagged sample is empty: never used
+            w_rel[j] = start < e0 ? -1 : (int32_t)(start - e0);                // start - e0 <= kCopyTile
+            w_delta[j] = (p >= 0 && p < in.B) ? offsets[p] - start : 0;        // a flagged sample is empty: never used
         }
     __syncthreads();
-    V v[kCopyPieces];
-    bool live[kCopyPieces];
-#pragma unroll
-    for (int i = 0; i < kCopyPieces; ++i) {
-        const int64_t q = q0 + (int64_t)i * kScanThreads + threadIdx.x;
-        live[i] = q <= q1;
-        if (live[i]) {
-            const int64_t e = q / ppe;
-            int64_t lo = 0, hi = wn;                            // first j with start[j] > e
-            int64_t delta;
-            if (staged) {
-                while (lo < hi) {
-                    const int64_t mid = (lo + hi) >> 1;
-                    if (w_start[mid] <= e) lo = mid + 1; else hi = mid;
-                }
-                delta = w_delta[lo - 1];
-            } else {
-                while (lo < hi) {
-                    const int64_t mid = (lo + hi) >> 1;
-                    if (out_offsets[ka + mid] <= e) lo = mid + 1; else hi = mid;
-                }
-                delta = offsets[sample_of[ka + lo - 1]] - out_offsets[ka + lo - 1];
-            }
-            v[i] = values[(e + delta) * ppe + (q - e * ppe)];
+    // Wavefront w copies the w-th quarter of the tile, 64 consecutive pieces per instruction, front to back:
+    // the sample of a lane's piece only moves forward, so after one binary search per lane the boundary
+    // list is walked (a step every few instructions for samples of a few hundred elements; never more
+    // steps per lane and tile than the list is long).
+    const uint32_t uppe = (uint32_t)ppe;
+    constexpr uint32_t kWavePieces = kCopyTile / (kScanThreads / kWave);
+    const uint32_t lane = threadIdx.x & (kWave - 1);
+    const uint32_t w0 = (threadIdx.x / kWave) * kWavePieces;
+    const int64_t wn_all = kb - ka + 1;
+    int64_t j = 0;                                              // sample ka + j holds the lane's current piece
+    {
+        const uint32_t t = rem0 + w0 + lane;
+        const int64_t le = uppe == 1 ? t : t / uppe;
+        int64_t lo = 0, hi = wn_all;                            // first j with start[j] > element
+        while (lo < hi) {
+            const int64_t mid = (lo + hi) >> 1;
+            const bool le_mid = staged ? (w_rel[mid] <= (int32_t)le) : (out_offsets[ka + mid] <= e0 + le);
+            if (le_mid) lo = mid + 1; else hi = mid;
         }
+        j = lo - 1;
     }
+    for (uint32_t r0 = 0; r0 < kWavePieces; r0 += kWave * kCopyPieces) {
+        if (w0 + r0 >= tile_pieces) break;                      // whole wavefront
+        V v[kCopyPieces];
+        bool live[kCopyPieces];
 #pragma unroll
-    for (int i = 0; i < kCopyPieces; ++i) {
-        const int64_t q = q0 + (int64_t)i * kScanThreads + threadIdx.x;
-        if (live[i]) out[q] = v[i];
+        for (int i = 0; i < kCopyPieces; ++i) {
+            const uint32_t l = w0 + r0 + (uint32_t)i * kWave + lane;                // piece of the tile
+            live[i] = l < tile_pieces;
+            if (live[i]) {
+                const uint32_t t = rem0 + l;
+                const uint32_t le = uppe == 1 ? t : t / uppe;                       // element of the tile
+                const uint32_t pin = t - le * uppe;                                 // piece of the element
+                int64_t delta;
+                if (staged) {
+                    while (j + 1 < wn_all && w_rel[j + 1] <= (int32_t)le) ++j;
+                    delta = w_delta[j];
+                } else {
+                    const int64_t e = e0 + le;
+                    while (j + 1 < wn_all && out_offsets[ka + j + 1] <= e) ++j;
+                    delta = offsets[sample_of[ka + j]] - out_offsets[ka + j];
+                }
+                v[i] = values[(e0 + le + delta) * ppe + pin];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < kCopyPieces; ++i) {
+            const uint32_t l = w0 + r0 + (uint32_t)i * kWave + lane;
+            if (live[i]) out[q0 + l] = v[i];
+        }
     }
 }
 
