@@ -20,12 +20,14 @@ from helpers import assert_close_f32, assert_rows_close, exact_f32_to_bf16_bits,
 pytestmark = pytest.mark.gpu
 
 
-def run_pipelined_full(ctx, d_table, d_state, its, lr, eps, collect=True):
+def run_pipelined_full(ctx, d_table, d_state, its, lr, eps, collect=True, two_part=False):
     """All iterations through fs_prioritized_step_pipelined.
 
     collect=True: wait after every call and return host copies of everything it produced.
     collect=False: no wait between the calls (the way a training loop and bench.py drive it); only
     the table and the state are left to look at.
+    two_part: through fs_prioritized_step_two_part_multi (the lookup in the two parts of Algorithm 2; three
+    output batches in rotation).
     """
     dev = d_table.device
     num_rows, dim = d_table.shape
@@ -37,7 +39,8 @@ def run_pipelined_full(ctx, d_table, d_state, its, lr, eps, collect=True):
     layouts = [fs.alloc_layout(nmax, dev) for _ in range(3)]
     splits = [fs.alloc_split(nmax, nmax, dev) for _ in range(3)]
     reduced = [torch.empty((nmax, dim), dtype=torch.float32, device=dev) for _ in range(2)]
-    embs = [torch.empty((nmax, dim), dtype=d_table.dtype, device=dev) for _ in range(2)]
+    E = 3 if two_part else 2
+    embs = [torch.empty((nmax, dim), dtype=d_table.dtype, device=dev) for _ in range(E)]
     grads = [None, None]
 
     def args_for(t):
@@ -45,7 +48,7 @@ def run_pipelined_full(ctx, d_table, d_state, its, lr, eps, collect=True):
         last = t == T - 1
         return fs.make_step_args(d_table, d_state, lr, eps, lay_t, grads[t % 2], None if last else d_vals[t + 1],
                                  None if last else d_offs[t + 1], None if last else layouts[(t + 1) % 3],
-                                 splits[t % 3], reduced[t % 2], None if last else embs[t % 2])
+                                 splits[t % 3], reduced[t % 2], None if last else embs[t % E])
 
     fs.fs_unique_ids(ctx, d_vals[0], num_rows, out=layouts[0])
     emb0 = fs.fs_gather_jagged(ctx, d_table, d_vals[0], d_offs[0])
@@ -59,7 +62,11 @@ def run_pipelined_full(ctx, d_table, d_state, its, lr, eps, collect=True):
         if t + 1 < T:
             grads[(t + 1) % 2] = torch.from_numpy(its[t + 1].grads).to(dev)
             nxt = args_for(t + 1)
-        fs.fs_prioritized_step_pipelined(ctx, cur, nxt)
+        if two_part:
+            fs.fs_prioritized_step_two_part_multi(ctx, fs.step_args_array([cur]),
+                                                  fs.step_args_array([nxt]) if nxt is not None else None)
+        else:
+            fs.fs_prioritized_step_pipelined(ctx, cur, nxt)
         if not collect:
             cur = nxt
             continue
@@ -78,7 +85,7 @@ def run_pipelined_full(ctx, d_table, d_state, its, lr, eps, collect=True):
                                   "seg_offsets": ln["seg_offsets"][:u1 + 1].cpu().numpy(),
                                   "perm": ln["perm"][:n[t + 1]].cpu().numpy(),
                                   "inverse": ln["inverse"][:n[t + 1]].cpu().numpy()}
-            rec["emb_next"] = table_to_host(embs[t % 2][:n[t + 1]])
+            rec["emb_next"] = table_to_host(embs[t % E][:n[t + 1]])
         outs.append(rec)
         cur = nxt
     assert fs.fs_check_async(ctx) == fs.FS_OK, ctx.last_error()
@@ -161,6 +168,17 @@ def check_config_table(cfg_index, table_index):
         assert torch.equal(d_table[idx].view(torch.int16 if tab.dtype == "bf16" else torch.int32),
                            rows_1.view(torch.int16 if tab.dtype == "bf16" else torch.int32))
         assert torch.equal(d_state[idx], state_1)
+        if cfg_index in (1, 3):
+            # and with the lookup in its two parts: every merged batch, the table and the state bit for bit
+            fs.fs_init_table_hash(ctx, d_table)
+            d_state.zero_()
+            got2 = run_pipelined_full(ctx, d_table, d_state, its, cfg.lr, cfg.eps, two_part=True)
+            for t, (g2, g) in enumerate(zip(got2[1:], got[1:])):
+                if "emb_next" in g:
+                    assert g2["emb_next"].tobytes() == g["emb_next"].tobytes(), f"two-part lookup, iteration {t}"
+            assert torch.equal(d_table[idx].view(torch.int16 if tab.dtype == "bf16" else torch.int32),
+                               rows_1.view(torch.int16 if tab.dtype == "bf16" else torch.int32))
+            assert torch.equal(d_state[idx], state_1)
     n_it = [len(it.values) for it in its]
     print(f"config {cfg_index} table {table_index}: N={n_it[:3]} touched={len(touched)} ok")
     ctx.close()

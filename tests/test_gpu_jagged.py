@@ -191,3 +191,38 @@ def test_ranged_dispatch_reports_ranges_that_do_not_cover_the_samples():
         fs.fs_jagged_keyed_transpose(ctx, dev(values), dev(offsets), 2, 200)
     assert e.value.code == fs.FS_ENOMEM
     ctx.close()
+
+
+@pytest.mark.timeout(300)
+def test_balancer_path_at_the_size_the_bench_times():
+    """64 ranks x 1024 samples of configuration 1's length rule (16.7 M IDs): partition, permute, dispatch,
+    combine and transpose against the oracle, every byte."""
+    from fs_workloads.generators import powerlaw_lengths as cfg_lengths
+    rng = np.random.default_rng(20240)
+    ranks, keys, Bg = 64, 4, 65536
+    lens = cfg_lengths(rng, Bg, 1.5, 16, 4096)
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    ng = int(offsets[-1])
+    values = rng.integers(0, 4_000_000, size=ng).astype(np.int64)
+    ctx = fs.Context(max_ids=Bg, max_dim=8)
+    d_values, d_offsets = dev(values), dev(offsets)
+    sample_of, rank_off = fs.fs_partition_fbs(ctx, dev(lens), 4096, ranks)
+    want_s, want_r = O.partition_fbs(lens, ranks)
+    assert sample_of.cpu().numpy().tolist() == want_s.tolist() and rank_off.cpu().numpy().tolist() == want_r.tolist()
+    out, out_off = fs.fs_jagged_indexed_permute(ctx, d_values, d_offsets, sample_of, ng)
+    want, want_off = O.jagged_indexed_permute(values, offsets, want_s)
+    assert torch.equal(out_off.cpu(), torch.from_numpy(want_off)) and torch.equal(out.cpu(), torch.from_numpy(want))
+    Bk = Bg // keys
+    _, ro = O.partition_fbs(lens[:Bk], ranks)
+    d_ro = dev(ro)
+    disp, disp_off, splits = fs.fs_jagged_ranged_dispatch(ctx, d_values, d_offsets, keys, Bk, d_ro)
+    w_disp, w_off, w_splits = O.jagged_ranged_dispatch(values, offsets, keys, Bk, ro)
+    assert torch.equal(disp.cpu(), torch.from_numpy(w_disp)) and torch.equal(disp_off.cpu(), torch.from_numpy(w_off))
+    assert splits.cpu().numpy().tolist() == w_splits.tolist()
+    back, back_off = fs.fs_jagged_ranged_combine(ctx, disp, disp_off, keys, Bk, d_ro)
+    assert torch.equal(back, d_values) and torch.equal(back_off, d_offsets)
+    tr, tr_off = fs.fs_jagged_keyed_transpose(ctx, d_values, d_offsets, keys, Bk)
+    w_tr, w_tr_off = O.jagged_keyed_transpose(values, offsets, keys, Bk)
+    assert torch.equal(tr.cpu(), torch.from_numpy(w_tr)) and torch.equal(tr_off.cpu(), torch.from_numpy(w_tr_off))
+    assert fs.fs_check_async(ctx) == fs.FS_OK, ctx.last_error()
+    ctx.close()
