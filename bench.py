@@ -98,7 +98,7 @@ def bench_tables(args, cfg) -> int:
         t.offs = [torch.from_numpy(it.offsets).to(dev) for it in t.its]
         t.grads = [torch.from_numpy(it.grads).to(dev) for it in t.its]
         nmax = max(t.n)
-        t.layouts = [fs.alloc_layout(nmax, dev) for _ in range(L)]
+        t.layouts = [fs.alloc_layout(nmax, dev, inverse=False) for _ in range(L)]
         t.splits = [fs.alloc_split(nmax, nmax, dev) for _ in range(P)]
         t.embs = [torch.empty((t.n[0], t.dim), dtype=tdtype, device=dev),
                   torch.empty((t.n[1], t.dim), dtype=tdtype, device=dev)]
@@ -314,7 +314,7 @@ def main() -> int:
     P = K + D + 2 if index_ahead else 3
     period = math.lcm(L, P, 2)
     nmax = max(n)
-    layouts = [fs.alloc_layout(nmax, dev) for _ in range(L)]
+    layouts = [fs.alloc_layout(nmax, dev, inverse=args.two_part) for _ in range(L)]   # only the two-part lookup reads it
     splits = [fs.alloc_split(nmax, nmax, dev) for _ in range(P)]
     reduced = [torch.empty((nmax, dim), dtype=torch.float32, device=dev) for _ in range(2)]
     embs = [torch.empty((n[0], dim), dtype=tdtype, device=dev), torch.empty((n[1], dim), dtype=tdtype, device=dev)]

@@ -233,8 +233,9 @@ int fs_jagged_ranged_combine(fs_ctx *ctx, const void *values, int64_t n_values, 
  *                        row (2 words, low first), slot, number of occurrences, and for rows
  *                        with at most FS_SHORT_SEGMENT occurrences the occurrences (rows of G_t)
  *                        in batch order
- * seg_offsets_t, perm_t, inverse_t: the layout of batch t as written by fs_unique_ids (all three
- * required); cap_t is also the capacity of cstart.  This is the prioritization of Section 3.2
+ * seg_offsets_t, perm_t: the layout of batch t as written by fs_unique_ids (both required; inverse_t is
+ * not read and may be NULL: the row of a sorted position is found in seg_offsets_t, which costs no random
+ * access); cap_t is also the capacity of cstart.  This is the prioritization of Section 3.2
  * carried down to the gradient rows: the priority pass reads only what collision rows need. */
 int fs_collision_split_classes(fs_ctx *ctx, const int64_t *u_t, const int64_t *n_t_dev,
                                const int64_t *u_t1, const int64_t *n_t1_dev, int64_t cap_t, int64_t cap_t1,
@@ -268,13 +269,16 @@ int fs_reduce_update_class(fs_ctx *ctx, int cls, void *table, fs_dtype dt, float
 typedef struct fs_step_args {
     void *table; float *state; int64_t num_rows; int32_t dim; int32_t dtype; /* fs_dtype */
     float lr, eps;
-    /* iteration t: layout produced by the previous step (or by fs_unique_ids), gradients */
+    /* iteration t: layout produced by the previous step (or by fs_unique_ids), gradients.  inverse_t is not
+     * read by the step calls and may be NULL */
     const int64_t *u_t; const int32_t *seg_offsets_t; const int32_t *perm_t; const int32_t *inverse_t;
     const int64_t *n_unique_t_dev;
     const float *grads_t; int64_t n_t;
     /* lookahead batch t+1 (values_t1 == NULL: last iteration, every row is exclusive) */
     const int64_t *values_t1; const int64_t *offsets_t1; int64_t batch_t1; int64_t n_t1;
-    /* outputs: layout of t+1 (already there if fs_unique_ids_ahead was called on these buffers) */
+    /* outputs: layout of t+1 (already there if fs_unique_ids_ahead was called on these buffers).  inverse_t1
+     * is OPTIONAL (NULL: not written - a scattered 4-byte write per occurrence saved); only the two-part
+     * lookup reads it */
     int64_t *u_t1; int32_t *seg_offsets_t1; int32_t *perm_t1; int32_t *inverse_t1; int64_t *n_unique_t1_dev;
     /* outputs: the split of U_t */
     int64_t *co; int32_t *co_slot; int64_t *ex; int32_t *ex_slot; int64_t *ex_next; int32_t *ex_next_slot;

@@ -344,7 +344,7 @@ def fs_collision_split_classes(ctx: Context, layout_t: Dict[str, torch.Tensor], 
         out = alloc_split(n_t, cap_t1, dev)
     rc = ctx.lib.fs_collision_split_classes(
         ctx.handle, _ptr(layout_t["unique"]), _ptr(layout_t["n_unique"]), _ptr(u_t1), _ptr(n_t1_dev), n_t, cap_t1,
-        _ptr(layout_t["seg_offsets"]), _ptr(layout_t["perm"]), _ptr(layout_t["inverse"]), n_t,
+        _ptr(layout_t["seg_offsets"]), _ptr(layout_t["perm"]), _ptr(layout_t.get("inverse")), n_t,
         _ptr(out["co"]), _ptr(out["co_slot"]), _ptr(out["ex"]), _ptr(out["ex_slot"]), _ptr(out["ex_next"]),
         _ptr(out["ex_next_slot"]), _ptr(out["counts"]), _ptr(out["cperm"]), _ptr(out["cslot"]), _ptr(out["cstart"]),
         _ptr(out["class_pos"]), _ptr(out["short_rec"]), _stream(stream))
@@ -373,7 +373,7 @@ def fs_unique_ids_ahead(ctx: Context, ids: torch.Tensor, num_rows: int, out: Dic
     n = ids.numel()
     stream_arg = ctypes.c_void_p(-1) if stream == FS_STREAM_LAST_STEP else _stream(stream)
     rc = ctx.lib.fs_unique_ids_ahead(ctx.handle, _ptr(ids), n, num_rows, _ptr(out["unique"]),
-                                     _ptr(out["seg_offsets"]), _ptr(out["perm"]), _ptr(out["inverse"]),
+                                     _ptr(out["seg_offsets"]), _ptr(out["perm"]), _ptr(out.get("inverse")),
                                      _ptr(out["n_unique"]), stream_arg)
     ctx.check(rc, "fs_unique_ids_ahead")
     out["n"] = n
@@ -487,15 +487,18 @@ def fs_stream_copy(ctx: Context, src: torch.Tensor, dst: torch.Tensor, stream=No
 
 
 # ---- buffer bundles for the whole-iteration call (allocation only) -----------------------------
-def alloc_layout(n: int, device) -> Dict[str, torch.Tensor]:
-    return {
+def alloc_layout(n: int, device, inverse: bool = True) -> Dict[str, torch.Tensor]:
+    """inverse=False: no inverse map (the step calls do not need it; the two-part lookup does)."""
+    out = {
         "unique": torch.empty(max(n, 1), dtype=torch.int64, device=device),
         "seg_offsets": torch.empty(n + 1, dtype=torch.int32, device=device),
         "perm": torch.empty(max(n, 1), dtype=torch.int32, device=device),
-        "inverse": torch.empty(max(n, 1), dtype=torch.int32, device=device),
         "n_unique": torch.zeros(1, dtype=torch.int64, device=device),
         "n": n,
     }
+    if inverse:
+        out["inverse"] = torch.empty(max(n, 1), dtype=torch.int32, device=device)
+    return out
 
 
 def alloc_split(cap_t: int, cap_t1: int, device) -> Dict[str, torch.Tensor]:

@@ -519,11 +519,11 @@ int check_step_args(fs_ctx *ctx, const fs_step_args *a, bool *have_t, bool *have
     *have_t = a->n_t > 0;
     *have_t1 = a->values_t1 != nullptr && a->n_t1 > 0;
     if (*have_t)
-        FS_REQUIRE(ctx, a->u_t && a->seg_offsets_t && a->perm_t && a->inverse_t && a->n_unique_t_dev && a->grads_t &&
+        FS_REQUIRE(ctx, a->u_t && a->seg_offsets_t && a->perm_t && a->n_unique_t_dev && a->grads_t &&
                             a->co && a->co_slot && a->ex && a->ex_slot && a->cperm && a->cslot && a->cstart && a->short_rec,
                    "step: null pointer (iteration t)");
     if (*have_t1)
-        FS_REQUIRE(ctx, a->u_t1 && a->seg_offsets_t1 && a->perm_t1 && a->inverse_t1 && a->n_unique_t1_dev &&
+        FS_REQUIRE(ctx, a->u_t1 && a->seg_offsets_t1 && a->perm_t1 && a->n_unique_t1_dev &&
                             a->ex_next && a->ex_next_slot && a->emb_t1,
                    "step: null pointer (lookahead)");
     return FS_OK;
@@ -679,7 +679,7 @@ int enqueue_index_work_batch(fs_ctx *ctx, int count, const fs_step_args *a, cons
         sj[k] = fs_split_job{x.u_t, t ? x.n_unique_t_dev : nullptr, x.u_t1, t1 ? x.n_unique_t1_dev : nullptr,
                              t ? x.n_t : 0, t1 ? x.n_t1 : 0, x.co, x.co_slot, x.ex, x.ex_slot, x.ex_next,
                              x.ex_next_slot, x.counts_dev, t ? x.seg_offsets_t : nullptr, t1 ? x.co_flag_t1 : nullptr};
-        cj[k] = fs_class_job{x.perm_t, x.inverse_t, x.seg_offsets_t, t ? x.n_t : 0, t ? x.n_t : 0, x.cperm, x.cslot,
+        cj[k] = fs_class_job{x.perm_t, x.n_unique_t_dev, x.seg_offsets_t, t ? x.n_t : 0, t ? x.n_t : 0, x.cperm, x.cslot,
                              x.cstart, x.class_pos_dev, x.u_t, x.short_rec};
     }
     rc = launch_split_batch(ctx, count, sj, s, set0);
@@ -823,13 +823,14 @@ int fs_collision_split_classes(fs_ctx *ctx, const int64_t *u_t, const int64_t *n
                                int32_t *ex_next_slot, int64_t *counts_dev, int32_t *cperm, int32_t *cslot,
                                int32_t *cstart, int32_t *class_pos_dev, int32_t *short_rec, fs_stream stream) {
     if (!ctx) return FS_EINVAL;
+    (void)inverse_t;
     FS_REQUIRE(ctx, cap_t >= 0 && cap_t1 >= 0 && n_t >= 0, "split: negative size");
     if (cap_t > ctx->max_ids || cap_t1 > ctx->max_ids || n_t > ctx->max_ids)
         return set_err(ctx, FS_ENOMEM, "split: capacity beyond the context capacity");
     FS_REQUIRE(ctx, counts_dev && class_pos_dev, "split: null counts");
     FS_REQUIRE(ctx, (n_t == 0) == (cap_t == 0), "split: n_t and cap_t must both be zero or both positive");
     if (cap_t > 0)
-        FS_REQUIRE(ctx, u_t && n_t_dev && co && co_slot && ex && ex_slot && seg_offsets_t && perm_t && inverse_t &&
+        FS_REQUIRE(ctx, u_t && n_t_dev && co && co_slot && ex && ex_slot && seg_offsets_t && perm_t &&
                             cperm && cslot && cstart && short_rec,
                    "split: null pointer (t side)");
     if (cap_t1 > 0) FS_REQUIRE(ctx, u_t1 && n_t1_dev && ex_next && ex_next_slot, "split: null pointer (t+1 side)");
@@ -839,7 +840,7 @@ int fs_collision_split_classes(fs_ctx *ctx, const int64_t *u_t, const int64_t *n
                       co, co_slot, ex, ex_slot, ex_next, ex_next_slot, counts_dev, as_stream(stream),
                       cap_t > 0 ? seg_offsets_t : nullptr);
     if (rc != FS_OK) return rc;
-    return launch_class_order(ctx, perm_t, inverse_t, seg_offsets_t, n_t, cap_t, cperm, cslot, cstart, class_pos_dev,
+    return launch_class_order(ctx, perm_t, n_t_dev, seg_offsets_t, n_t, cap_t, cperm, cslot, cstart, class_pos_dev,
                               u_t, short_rec, as_stream(stream));
 }
 
@@ -1095,8 +1096,10 @@ static int pipelined_impl(fs_ctx *ctx, const fs_step_args *cur, const fs_step_ar
         w->fetch_next[k] = two_part && next && w->nxt_t1[k];
         if (two_part) {
             FS_REQUIRE(ctx, !ctx->capturing, "two-part step: not while a graph is being captured");
-            FS_REQUIRE(ctx, !have_t1[k] || cur[k].co_flag_t1, "two-part step: co_flag_t1 missing");
-            FS_REQUIRE(ctx, !w->fetch_next[k] || next[k].co_flag_t1, "two-part step: co_flag_t1 missing (next)");
+            FS_REQUIRE(ctx, !have_t1[k] || (cur[k].co_flag_t1 && cur[k].inverse_t1),
+                       "two-part step: co_flag_t1 or inverse_t1 missing");
+            FS_REQUIRE(ctx, !w->fetch_next[k] || (next[k].co_flag_t1 && next[k].inverse_t1),
+                       "two-part step: co_flag_t1 or inverse_t1 missing (next)");
         }
     }
     // which part of cur's lookup is left to do: the collision rows if the previous call fetched the rest

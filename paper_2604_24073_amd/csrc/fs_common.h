@@ -95,7 +95,9 @@ struct fs_split_job {
     uint8_t *flag_t1_out = nullptr; // optional [cap_t1]: 1 where the row of u_t1 is also in u_t (a collision row), else 0
 };
 struct fs_class_job {
-    const int32_t *perm, *inverse, *seg_offsets;
+    const int32_t *perm;
+    const int64_t *n_unique_dev;    // rows of the batch (bounds seg_offsets)
+    const int32_t *seg_offsets;
     int64_t n, cap_u;
     int32_t *cperm, *cslot, *cstart, *class_pos_dev;
     const int64_t *u_t;
@@ -263,7 +265,7 @@ int launch_split(fs_ctx *, const int64_t *u_t, const int64_t *n_t_dev, const int
                  int64_t *ex, int32_t *ex_slot, int64_t *ex_next, int32_t *ex_next_slot, int64_t *counts_dev,
                  hipStream_t s, const int32_t *seg_offsets_t = nullptr, int set = 0);
 // right after launch_split(..., seg_offsets_t) on the same stream: occurrences of the batch in class order
-int launch_class_order(fs_ctx *, const int32_t *perm, const int32_t *inverse, const int32_t *seg_offsets, int64_t n,
+int launch_class_order(fs_ctx *, const int32_t *perm, const int64_t *n_unique_dev, const int32_t *seg_offsets, int64_t n,
                        int64_t cap_u, int32_t *cperm, int32_t *cslot, int32_t *cstart, int32_t *class_pos_dev,
                        const int64_t *u_t, int32_t *short_rec, hipStream_t s, int set = 0);
 int launch_reduce_update(fs_ctx *, int cls, const float *grads, int64_t n, int32_t dim, const int32_t *cperm,

@@ -58,6 +58,22 @@ __device__ __forceinline__ int wave_lower_bound(const int64_t *__restrict__ a, i
     return lo;
 }
 
+// number of entries of a[0, n) that are <= key; executed by one whole wavefront (64-ary search)
+__device__ __forceinline__ int wave_upper_bound_i32(const int32_t *__restrict__ a, int n, int key) {
+    const int lane = threadIdx.x & (kWave - 1);
+    int lo = 0, hi = n;                      // a[i] <= key for i < lo, a[i] > key for i >= hi
+    while (lo < hi) {
+        const int step = (hi - lo + kWave - 1) / kWave;
+        const int probe = lo + (lane + 1) * step - 1;          // last entry of my sub-block
+        const bool le = (probe < hi) && (a[probe] <= key);
+        const int cnt = __popcll(__ballot(le));
+        lo += cnt * step;
+        const int nhi = lo + step - 1;
+        hi = nhi < hi ? nhi : hi;
+    }
+    return lo;
+}
+
 template <typename P>
 __device__ __forceinline__ bool sorted_contains(P a, int lo, int hi, int64_t key) {
     const int end = hi;
@@ -98,7 +114,8 @@ struct split_dev_batch {
     split_dev_job j[kMaxBatch];
 };
 struct class_dev_job {
-    const int32_t *perm, *inverse, *seg_offsets;
+    const int32_t *perm, *seg_offsets;
+    const int64_t *n_unique_dev;
     int n, tiles_t, blocks, cap;  // blocks is at least 1: an empty batch still has its class extents written
     const uint8_t *flag_t;
     const int32_t *cstart_local, *tile_len, *cidx;
@@ -263,15 +280,19 @@ __global__ __launch_bounds__(kScanThreads) void split_compact_kernel(const split
 
 // Class order of the occurrences of batch t that belong to rows with more than FS_SHORT_SEGMENT
 // occurrences: sorted position q (row slot s, the j-th occurrence of that row) goes to  [start of the class] + [occurrences of same-class rows before s] + j.
-// Every workgroup first turns the per-tile totals into tile bases (a few hundred values).
+// Every workgroup first turns the per-tile totals into tile bases (a few hundred values).  The row slot of a
+// sorted position is found in the segment boundaries themselves: a workgroup's 1024 consecutive sorted
+// positions touch at most 1024 consecutive rows, whose boundaries it stages in LDS (the inverse map would
+// give the same slot at the price of one random 4-byte read per occurrence).
 __global__ __launch_bounds__(kScanThreads) void class_scatter_kernel(const class_dev_batch batch,
                                                                      int *__restrict__ flags) {
     FS_WG_TRACE(7);
     const class_dev_job &job = batch.j[blockIdx.y];
     if ((int)blockIdx.x >= job.blocks) return;
-    const int32_t *__restrict__ perm = job.perm, *__restrict__ inverse = job.inverse;
+    const int32_t *__restrict__ perm = job.perm;
     const int32_t *__restrict__ seg_offsets = job.seg_offsets;
     const int n = job.n, tiles_t = job.tiles_t, cap = job.cap;
+    const int n_u = clamp_count(job.n_unique_dev, cap);
     const uint8_t *__restrict__ flag_t = job.flag_t;
     const int32_t *__restrict__ cstart_local = job.cstart_local, *__restrict__ tile_len = job.tile_len;
     const int32_t *__restrict__ cidx = job.cidx;
@@ -281,6 +302,26 @@ __global__ __launch_bounds__(kScanThreads) void class_scatter_kernel(const class
     int32_t *__restrict__ short_rec = job.short_rec;
     extern __shared__ int tile_base[];                      // [2 * tiles_t]
     __shared__ int sh[kScanThreads / kWave];
+    __shared__ int32_t seg_win[kScanTile + 2];              // seg_offsets[slot_a .. slot_b + 1]
+    __shared__ int win[2];
+    const int qa = blockIdx.x * kScanTile;
+    const int qb = (qa + kScanTile < n ? qa + kScanTile : n) - 1;          // last sorted position of the workgroup
+    if (threadIdx.x < 2 * kWave) {
+        // the row of a sorted position q: the last slot whose segment starts at or before q
+        const int w = threadIdx.x / kWave;
+        int k = 0;
+        if (qa < n && n_u > 0) k = wave_upper_bound_i32(seg_offsets, n_u + 1, w == 0 ? qa : qb) - 1;
+        k = k < 0 ? 0 : (k > n_u - 1 ? n_u - 1 : k);
+        if ((threadIdx.x & (kWave - 1)) == 0) win[w] = k;
+    }
+    __syncthreads();
+    const int slot_a = win[0];
+    int wn = (qa < n && n_u > 0) ? win[1] - slot_a + 2 : 0; // boundaries staged
+    if (wn > kScanTile + 2 || wn < 0) {                     // cannot happen: every row has an occurrence
+        if (threadIdx.x == 0) atomicOr(flags, kFlagInternal);
+        wn = 0;
+    }
+    for (int j = threadIdx.x; j < wn; j += kScanThreads) seg_win[j] = seg_offsets[slot_a + j];
     int class_total[2];
     for (int c = 0; c < 2; ++c) {
         int carry = 0;
@@ -310,17 +351,29 @@ __global__ __launch_bounds__(kScanThreads) void class_scatter_kernel(const class
 #pragma unroll
     for (int k = 0; k < kScanIpt; ++k) {
         const int q = q0 + k * kScanThreads;
-        s[k] = (q < n) ? inverse[i[k]] : 0;
+        s[k] = -1;
+        if (q < n && wn >= 2) {
+            int lo = 0, hi = wn - 1;                         // first j with seg_win[j] > q, among the row starts
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (seg_win[mid] <= q) lo = mid + 1; else hi = mid;
+            }
+            s[k] = lo - 1;                                   // place in the window, -1: before its first row
+        }
     }
 #pragma unroll
     for (int k = 0; k < kScanIpt; ++k) {
         const int q = q0 + k * kScanThreads;
         if (q < n) {
-            const int slot = s[k];
+            if (s[k] < 0 || q >= seg_win[s[k] + 1]) {        // layout and batch do not fit each other
+                atomicOr(flags, kFlagInternal);
+                continue;
+            }
+            const int slot = slot_a + s[k];
             const bool is_co = flag_t[slot] != 0;
             const int tile = slot / kScanTile;
-            const int first = seg_offsets[slot];
-            const int len = seg_offsets[slot + 1] - first;
+            const int first = seg_win[s[k]];
+            const int len = seg_win[s[k] + 1] - first;
             // one record per row of the batch, at the row's place in its class list: header (row,
             // slot, occurrences) from the row's first position, occurrences only for short segments
             const int li = cidx[slot];
@@ -422,7 +475,7 @@ int launch_class_order_batch(fs_ctx *ctx, int count, const fs_class_job *jobs, h
         const fs_class_job &in = jobs[k];
         const fs_split_scratch &ws = ctx->split[set0 + k];
         class_dev_job &j = batch.j[k];
-        j.perm = in.perm; j.inverse = in.inverse; j.seg_offsets = in.seg_offsets;
+        j.perm = in.perm; j.n_unique_dev = in.n_unique_dev; j.seg_offsets = in.seg_offsets;
         j.n = (int)in.n;
         j.tiles_t = (int)ceil_div(in.cap_u, kScanTile);      // the same tiling the split used for side t
         j.blocks = in.n > 0 ? (int)ceil_div(in.n, kScanTile) : 1;
@@ -441,10 +494,10 @@ int launch_class_order_batch(fs_ctx *ctx, int count, const fs_class_job *jobs, h
     return FS_OK;
 }
 
-int launch_class_order(fs_ctx *ctx, const int32_t *perm, const int32_t *inverse, const int32_t *seg_offsets,
+int launch_class_order(fs_ctx *ctx, const int32_t *perm, const int64_t *n_unique_dev, const int32_t *seg_offsets,
                        int64_t n, int64_t cap_u, int32_t *cperm, int32_t *cslot, int32_t *cstart,
                        int32_t *class_pos_dev, const int64_t *u_t, int32_t *short_rec, hipStream_t s, int set) {
-    const fs_class_job job = {perm, inverse, seg_offsets, n, cap_u, cperm, cslot, cstart, class_pos_dev, u_t, short_rec};
+    const fs_class_job job = {perm, n_unique_dev, seg_offsets, n, cap_u, cperm, cslot, cstart, class_pos_dev, u_t, short_rec};
     return launch_class_order_batch(ctx, 1, &job, s, set);
 }
 

@@ -29,7 +29,8 @@ def make_its(rng, rows, dim, n_iter, users=40, max_len=300):
     return its
 
 
-def run_pipelined(ctx, table, state, its, lr, eps, ahead=False, sync_each=True, two_part=False, disturb=None):
+def run_pipelined(ctx, table, state, its, lr, eps, ahead=False, sync_each=True, two_part=False, disturb=None,
+                  inverse=True):
     """ahead: True / "last_step": dedup every batch with fs_unique_ids_ahead, three batches before the
     iteration that gathers it (five layout buffers in rotation; "last_step": ordered after the start
     of the previous pipelined call instead of the stream's current position, six layout buffers).
@@ -41,7 +42,8 @@ def run_pipelined(ctx, table, state, its, lr, eps, ahead=False, sync_each=True, 
     sync_each=False: no wait between the calls.
     two_part: fs_prioritized_step_two_part_multi (exclusive rows of the lookahead batch fetched by the call
     before, three output batches in rotation); disturb: iteration before whose call the pipeline is joined
-    and the already fetched part of its output batch overwritten (the call must then redo the whole lookup)."""
+    and the already fetched part of its output batch overwritten (the call must then redo the whole lookup).
+    inverse=False: layouts without the inverse map (optional for everything but the two-part lookup)."""
     batch = int(ahead[5]) if isinstance(ahead, str) and ahead.startswith("batch") else 0
     index_ahead = ahead in ("index", "index_last_step")
     last_step = isinstance(ahead, str) and ahead.endswith("last_step")
@@ -59,7 +61,7 @@ def run_pipelined(ctx, table, state, its, lr, eps, ahead=False, sync_each=True, 
     d_grads = [dev(it.grads) for it in its]
     n = [v.numel() for v in d_vals]
     nmax = max(n)
-    layouts = [fs.alloc_layout(nmax, "cuda") for _ in range(L)]
+    layouts = [fs.alloc_layout(nmax, "cuda", inverse=inverse) for _ in range(L)]
     splits = [fs.alloc_split(nmax, nmax, "cuda") for _ in range(P)]
     reduced = [torch.empty((nmax, dim), dtype=torch.float32, device="cuda") for _ in range(2)]
     E = 3 if two_part else 2
@@ -167,6 +169,14 @@ def test_pipelined_steps_match_sequential_calls_bitwise(dtype, dim):
             assert a["reduced"].tobytes() == b["reduced"].tobytes(), what
             if "emb_next" in a:
                 assert a["emb_next"].tobytes() == b["emb_next"].tobytes(), what
+    # the inverse map is optional for the step calls: without it, the same bits
+    for ahead in (False, "batch2_last_step", "index"):
+        ta, sa, oa = run_pipelined(ctx, table, state, its, 0.01, 1e-8, ahead=ahead, inverse=False)
+        assert torch.equal(ta.view(view), ts.view(view)) and torch.equal(sa, ss), f"no inverse map, ahead={ahead}"
+        for a, b in zip(oa, os_[1:]):
+            assert a["reduced"].tobytes() == b["reduced"].tobytes() and a["counts"].tolist() == b["counts"].tolist()
+            if "emb_next" in a:
+                assert a["emb_next"].tobytes() == b["emb_next"].tobytes()
     ctx.close()
 
 
