@@ -119,7 +119,8 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(const uniqu
     int32_t *__restrict__ idx_out = last ? job.perm : job.idx[src ^ 1];
     const int n = job.n, tiles = job.tiles;
     const uint32_t *__restrict__ tile_hist = job.tile_hist;
-    __shared__ uint32_t cnt[kSortWaves][kRadix];       // per-wave digit counters, then wave bases
+    __shared__ uint16_t cnt[kSortWaves][kRadix];       // per-wave digit counters, then the waves' starts inside the
+                                                       // tile's share of the digit (a tile has 4096 keys: 16 bits do)
     __shared__ uint32_t sh_below[kSortScan];
     __shared__ uint32_t sh_total[kSortScan];
     __shared__ uint32_t gbase[kRadix];
@@ -137,7 +138,8 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(const uniqu
         key[r] = 0;
         if (e < n) key[r] = FIRST ? (K)ids[e] : keys_in[e];
     }
-    for (int i = threadIdx.x; i < kSortWaves * kRadix; i += kSortThreads) (&cnt[0][0])[i] = 0;
+    for (int i = threadIdx.x; i < kSortWaves * kRadix / 2; i += kSortThreads)
+        reinterpret_cast<uint32_t *>(&cnt[0][0])[i] = 0u;
 
     // (1) every workgroup scans the table by itself: virtual thread (q, d) adds the tiles t = q, q+groups, ...
     // (a thread stands for several virtual threads when there are more digits than threads)
@@ -213,17 +215,17 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(const uniqu
         }
         const uint32_t before = __popcll(peers & lt);
         const uint32_t old = valid ? cnt[w][digit] : 0u;              // all peers read ...
-        if (valid && before == 0) cnt[w][digit] = old + (uint32_t)__popcll(peers);   // ... then the first one writes
+        if (valid && before == 0) cnt[w][digit] = (uint16_t)(old + (uint32_t)__popcll(peers));   // ... then the first one writes
         rank[r] = old + before;
     }
     __syncthreads();
     // (3) exclusive prefix over the waves of this tile, per digit
     for (int d = threadIdx.x; d < bins; d += kSortThreads) {
-        uint32_t run = gbase[d];
+        uint32_t run = 0;
 #pragma unroll
         for (int i = 0; i < kSortWaves; ++i) {
             const uint32_t v = cnt[i][d];
-            cnt[i][d] = run;
+            cnt[i][d] = (uint16_t)run;
             run += v;
         }
     }
@@ -233,7 +235,7 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(const uniqu
         const int e = base + r * kWave + lane;
         if (e < n) {
             const uint32_t digit = (uint32_t)(key[r] >> shift) & (bins - 1);
-            const uint32_t pos = cnt[w][digit] + rank[r];
+            const uint32_t pos = gbase[digit] + cnt[w][digit] + rank[r];
             keys_out[pos] = key[r];
             idx_out[pos] = FIRST ? e : idx_in[e];
         }
