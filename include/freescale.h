@@ -405,14 +405,20 @@ int fs_prioritized_step_pipelined_multi(fs_ctx *ctx, const fs_step_args *cur, co
  *                   the EXCLUSIVE rows of next's lookahead batch (which = 0) into next's emb_t1 - they are
  *                   rows of neither cur's nor next's update sets, and every older deferred pass has landed
  * so that between the arrival of the gradients and the complete input batch lie the priority pass and
- * the collision rows only.  A lookahead batch of `cur` whose exclusive rows no previous call of this
- * function fetched (first call of a run, or after fs_step_join / any other call on the context) gets its
- * whole lookup on `stream`.  Every record with a lookahead batch needs co_flag_t1.  Results are those of
+ * the collision rows only.  A lookahead batch of `cur` whose exclusive rows the previous call of this
+ * function did not fetch (first call of a run; another pipelined or self-contained step, a stand-alone
+ * update or a table initialisation on the context in between; fs_two_part_forget) gets its whole lookup on
+ * `stream`.  fs_check_async, fs_step_join and the ahead-of-time index calls keep what was fetched.  Whoever
+ * changes table rows or the output batch by other means between two calls must call fs_two_part_forget.  Every record with a lookahead batch needs co_flag_t1.  Results are those of
  * fs_prioritized_step_pipelined_multi, bit for bit; emb_t1 of cur is complete when `stream` is.  The output
  * batches of three consecutive iterations must be distinct buffers: while the caller consumes one, this call
  * completes the next and the side stream already fills the one after. */
 int fs_prioritized_step_two_part_multi(fs_ctx *ctx, const fs_step_args *cur, const fs_step_args *next,
                                        int count, fs_stream stream);
+
+/* Forget what the last fs_prioritized_step_two_part_multi call fetched ahead of time: the next call does the
+ * whole lookup of its lookahead batch (host-side bookkeeping only). */
+int fs_two_part_forget(fs_ctx *ctx);
 
 /* Makes `stream` wait for everything earlier calls left running on the context's own streams
  * (side work of the last pipelined call, outstanding ahead-of-time dedups); no-op if there is

@@ -107,6 +107,7 @@ def load_library() -> ctypes.CDLL:
                                                       ctypes.POINTER(c_vp)]),
         "fs_ctx_set_threaded_enqueue": (ctypes.c_int, [c_vp, ctypes.c_int]),
         "fs_step_join": (ctypes.c_int, [c_vp, S]),
+        "fs_two_part_forget": (ctypes.c_int, [c_vp]),
         "fs_ctx_host_times": (ctypes.c_int, [c_vp, ctypes.POINTER(ctypes.c_double), ctypes.c_int]),
         "fs_graph_launch": (ctypes.c_int, [c_vp, c_vp, S]),
         "fs_graph_destroy": (ctypes.c_int, [c_vp]),
@@ -446,6 +447,10 @@ def fs_prioritized_step_two_part_multi(ctx: Context, cur, nxt, stream=None) -> N
     """As fs_prioritized_step_pipelined_multi, the lookup taken in its two parts (records need co_flag_t1)."""
     rc = ctx.lib.fs_prioritized_step_two_part_multi(ctx.handle, cur, nxt, len(cur), _stream(stream))
     ctx.check(rc, "fs_prioritized_step_two_part_multi")
+
+
+def fs_two_part_forget(ctx: Context) -> None:
+    ctx.check(ctx.lib.fs_two_part_forget(ctx.handle), "fs_two_part_forget")
 
 
 def fs_ctx_host_times(ctx: Context, reset: bool = False):

@@ -166,6 +166,11 @@ void carve(fs_ctx *c, char *base, size_t *total) {
 
 hipStream_t as_stream(fs_stream s) { return reinterpret_cast<hipStream_t>(s); }
 
+// two-part lookup: what the last call fetched ahead is void once anything else may have written a table
+void forget_fetched(fs_ctx *ctx) {
+    for (int k = 0; k < FS_MAX_STEP_TABLES; ++k) ctx->fetched_emb[k] = nullptr;
+}
+
 void worker_stop(fs_ctx *ctx);
 int join_pending_work(fs_ctx *ctx, hipStream_t s);
 void drop_ahead(fs_ctx *ctx, const void *key);
@@ -415,6 +420,7 @@ int fs_rowwise_adagrad_update(fs_ctx *ctx, void *table, fs_dtype dt, float *stat
     FS_REQUIRE(ctx, num_rows >= 0 && cap >= 0, "adagrad: negative size");
     if (cap == 0) return FS_OK;
     FS_REQUIRE(ctx, table && state && rows && slots && n_rows_dev && reduced, "adagrad: null pointer");
+    forget_fetched(ctx);
     return launch_adagrad(ctx, table, dt, state, num_rows, dim, rows, slots, n_rows_dev, cap, reduced, lr, eps,
                           as_stream(stream));
 }
@@ -490,6 +496,7 @@ int fs_init_table_hash(fs_ctx *ctx, void *table, int64_t num_rows, int32_t dim, 
     FS_REQUIRE(ctx, dim_ok(dim, dt) && num_rows >= 0, "init: bad shape");
     if (num_rows == 0) return FS_OK;
     FS_REQUIRE(ctx, table, "init: null pointer");
+    forget_fetched(ctx);
     return launch_init_hash(ctx, table, num_rows, dim, dt, as_stream(stream));
 }
 
@@ -790,7 +797,6 @@ int enqueue_side_stream(fs_ctx *ctx, const side_work &w) {
 // registered: a later step may still name their buffers).
 int join_pending_work(fs_ctx *ctx, hipStream_t s) {
     const int wrc = workers_wait(ctx);
-    for (int k = 0; k < kMaxTables; ++k) ctx->fetched_emb[k] = nullptr;    // the caller may touch the table next
     if (ctx->side_pending) {
         ctx->side_pending = false;
         FS_HIP(ctx, hipStreamWaitEvent(s, ctx->ev_side[ctx->pipe_parity], 0));
@@ -851,6 +857,7 @@ int fs_reduce_update_class(fs_ctx *ctx, int cls, void *table, fs_dtype dt, float
                            const int32_t *class_pos_dev, float *reduced, fs_stream stream) {
     if (!ctx) return FS_EINVAL;
     FS_REQUIRE(ctx, cls == 0 || cls == 1, "reduce+update: class must be 0 or 1");
+    forget_fetched(ctx);
     FS_REQUIRE(ctx, dt == FS_F32 || dt == FS_BF16, "reduce+update: unknown dtype");
     FS_REQUIRE(ctx, dim_ok(dim, dt), "reduce+update: dim must be a multiple of 4 (fp32) / 8 (bf16), at most FS_MAX_DIM");
     FS_REQUIRE(ctx, num_rows >= 0 && n >= 0, "reduce+update: negative size");
@@ -1025,6 +1032,7 @@ int fs_prioritized_step(fs_ctx *ctx, const fs_step_args *a, fs_stream stream) {
     int rc = check_step_args(ctx, a, &have_t, &have_t1);
     if (rc != FS_OK) return rc;
     hipStream_t sp = as_stream(stream), sa = ctx->stream_a, sb = ctx->stream_b;
+    forget_fetched(ctx);
     rc = join_pending_work(ctx, sp);
     if (rc != FS_OK) return rc;
     begin_step_timing(ctx);
@@ -1189,6 +1197,12 @@ static int pipelined_impl(fs_ctx *ctx, const fs_step_args *cur, const fs_step_ar
     return rc;
 }
 
+int fs_two_part_forget(fs_ctx *ctx) {
+    if (!ctx) return FS_EINVAL;
+    forget_fetched(ctx);
+    return FS_OK;
+}
+
 int fs_step_join(fs_ctx *ctx, fs_stream stream) {
     if (!ctx) return FS_EINVAL;
     return join_pending_work(ctx, as_stream(stream));
@@ -1274,6 +1288,7 @@ int fs_graph_capture_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs_st
 }
 
 int fs_graph_launch(fs_ctx *ctx, fs_graph *graph, fs_stream stream) {
+    if (ctx) forget_fetched(ctx);
     if (!ctx || !graph || !graph->exec) return FS_EINVAL;
     FS_HIP(ctx, hipGraphLaunch(graph->exec, as_stream(stream)));
     return FS_OK;

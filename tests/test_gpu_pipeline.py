@@ -41,8 +41,9 @@ def run_pipelined(ctx, table, state, its, lr, eps, ahead=False, sync_each=True, 
     (K + D + 3 layouts, K + D + 2 split bundles).
     sync_each=False: no wait between the calls.
     two_part: fs_prioritized_step_two_part_multi (exclusive rows of the lookahead batch fetched by the call
-    before, three output batches in rotation); disturb: iteration before whose call the pipeline is joined
-    and the already fetched part of its output batch overwritten (the call must then redo the whole lookup).
+    before, three output batches in rotation); disturb: iteration before whose call the pipeline is joined,
+    the library told to forget what it fetched and the fetched part of the output batch overwritten (the call
+    must then redo the whole lookup).
     inverse=False: layouts without the inverse map (optional for everything but the two-part lookup)."""
     batch = int(ahead[5]) if isinstance(ahead, str) and ahead.startswith("batch") else 0
     index_ahead = ahead in ("index", "index_last_step")
@@ -112,6 +113,7 @@ def run_pipelined(ctx, table, state, its, lr, eps, ahead=False, sync_each=True, 
         if two_part:
             if disturb == t:
                 fs.fs_step_join(ctx)
+                fs.fs_two_part_forget(ctx)
                 torch.cuda.synchronize()
                 embs[t % E].view(torch.int16 if d_table.dtype == torch.bfloat16 else torch.int32).fill_(-1)
             fs.fs_prioritized_step_two_part_multi(ctx, fs.step_args_array([all_args[t]]),
