@@ -183,6 +183,20 @@ def partition_fbs(lengths: np.ndarray, n_ranks: int) -> Tuple[np.ndarray, np.nda
     return sample_of[:B], rank_offsets
 
 
+def partition_vbs(lengths: np.ndarray, weight_of_len: np.ndarray, n_ranks: int) -> Tuple[np.ndarray, np.ndarray]:
+    """VBS partitioner: (sample_of [B] = the length-sorted order, rank_offsets [n_ranks + 1])."""
+    lengths = _c(lengths, np.int64)
+    weight_of_len = _c(weight_of_len, np.int64)
+    B = lengths.shape[0]
+    sample_of = np.empty(max(B, 1), dtype=np.int32)
+    rank_offsets = np.empty(n_ranks + 1, dtype=np.int64)
+    rc = lib().fso_partition_vbs(_p(lengths), ctypes.c_int64(B), _p(weight_of_len),
+                                 ctypes.c_int64(weight_of_len.shape[0] - 1), ctypes.c_int32(n_ranks), _p(sample_of),
+                                 _p(rank_offsets))
+    _check(rc, "fso_partition_vbs")
+    return sample_of[:B], rank_offsets
+
+
 def jagged_indexed_permute(values: np.ndarray, offsets: np.ndarray, sample_of: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
     """The samples sample_of[...] of the jagged tensor (values, offsets), concatenated: (out_values, out_offsets)."""
     assert values.flags.c_contiguous

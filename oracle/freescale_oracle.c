@@ -30,6 +30,10 @@
  *   fso_partition_fbs          the Fixed Batch Size partitioner of Section 4.1 ("Partitioning
  *                              Algorithms"): samples sorted by UIH length, dealt to the ranks in a
  *                              zig-zag.
+ *   fso_partition_vbs          the Variable Batch Size partitioner of the same section: samples sorted by
+ *                              length, cut into n runs of about equal total weight (weight = a function
+ *                              of the length, L^alpha in the paper; here an integer table so that every
+ *                              cut is exact).
  *   fso_jagged_indexed_permute the indexed permute of Section 4.2 ("Triton Kernel Optimizations"):
  *                              the samples of a jagged tensor laid out in a given order.
  *   fso_jagged_keyed_transpose, fso_jagged_ranged_dispatch, fso_jagged_ranged_combine
@@ -311,6 +315,44 @@ int fso_partition_fbs(const int64_t *lengths, int64_t B, int32_t n_ranks, int32_
     rank_offsets[n] = at;
     free(order);
     return at == B ? FSO_OK : FSO_EINVAL;
+}
+
+/* ---- O7b: VBS partitioner ---------------------------------------------------------------------- */
+/* Samples sorted as for FBS.  weight_of_len[L] >= 0 is the weight of a sample of length L (the caller tabulates
+ * its L^alpha, scaled to integers).  With W the total weight and w_before(s) the weight of the sorted
+ * positions before s, position s goes to rank min(n-1, floor(n * w_before(s) / W)) - every rank takes the
+ * run of samples whose starts fall into its n-th of the total weight (the paper asks for n runs of
+ * "approximately equivalent total weight" and does not state the rule; this one keeps every rank within one
+ * sample's weight of W/n).  W == 0: everything goes to rank 0.
+ * sample_of [B]: the sorted order; rank_offsets [n+1]: where each rank's run starts. */
+int fso_partition_vbs(const int64_t *lengths, int64_t B, const int64_t *weight_of_len, int64_t max_len,
+                      int32_t n_ranks, int32_t *sample_of, int64_t *rank_offsets)
+{
+    if (B < 0 || n_ranks <= 0 || max_len < 0) return FSO_EINVAL;
+    lenidx *order = (lenidx *)malloc((size_t)(B > 0 ? B : 1) * sizeof(lenidx));
+    if (!order) return FSO_ENOMEM;
+    unsigned __int128 total = 0;
+    for (int64_t b = 0; b < B; ++b) {
+        if (lengths[b] < 0 || lengths[b] > max_len || weight_of_len[lengths[b]] < 0) { free(order); return FSO_ERANGE; }
+        order[b].len = lengths[b]; order[b].idx = b;
+        total += (unsigned __int128)weight_of_len[lengths[b]];
+    }
+    qsort(order, (size_t)B, sizeof(lenidx), cmp_lenidx);
+    unsigned __int128 before = 0;
+    int64_t n = n_ranks, next_rank = 0;               /* ranks below next_rank have their start written */
+    for (int64_t s = 0; s < B; ++s) {
+        int64_t r = 0;
+        if (total > 0) {
+            unsigned __int128 q = (unsigned __int128)n * before / total;
+            r = q >= (unsigned __int128)n ? n - 1 : (int64_t)q;
+        }
+        while (next_rank <= r) rank_offsets[next_rank++] = s;
+        sample_of[s] = (int32_t)order[s].idx;
+        before += (unsigned __int128)weight_of_len[order[s].len];
+    }
+    while (next_rank <= n) rank_offsets[next_rank++] = B;
+    free(order);
+    return FSO_OK;
 }
 
 /* ---- O8: indexed permute of a jagged tensor ---------------------------------------------------- */

@@ -580,3 +580,55 @@ def test_ranged_dispatch_and_combine_match_nested_lists_and_undo_each_other(F, B
         O.jagged_ranged_dispatch(values, offsets, F, B, np.array([0, B + 1], dtype=np.int64))
     with pytest.raises(O.OracleError):
         O.jagged_ranged_combine(values, offsets, F, B, np.array([0, 3, 2, B], dtype=np.int64))
+
+
+# ----------------------------------------------------------------------- VBS partitioner
+def _vbs_brute(lengths, weights, n):
+    order = sorted(range(len(lengths)), key=lambda b: (int(lengths[b]), b))
+    total = sum(int(weights[lengths[b]]) for b in order)
+    ranks, before = [[] for _ in range(n)], 0
+    for b in order:
+        r = min(n - 1, n * before // total) if total > 0 else 0          # Python integers: exact
+        ranks[r].append(b)
+        before += int(weights[lengths[b]])
+    return order, ranks
+
+
+@pytest.mark.parametrize("B,n,alpha", [(40, 4, 1.0), (257, 8, 1.7), (5, 8, 2.0), (0, 3, 1.0), (100, 1, 1.3), (64, 64, 0.5)])
+def test_vbs_partition_matches_exact_integer_brute_force(B, n, alpha):
+    rng = np.random.default_rng(B * 13 + n)
+    max_len = 300
+    lengths = rng.integers(0, max_len + 1, size=B).astype(np.int64)
+    weights = np.round(np.arange(max_len + 1, dtype=np.float64) ** alpha * 1024).astype(np.int64)
+    sample_of, ro = O.partition_vbs(lengths, weights, n)
+    order, ranks = _vbs_brute(lengths, weights, n)
+    assert sample_of.tolist() == order
+    assert [sample_of[ro[r]:ro[r + 1]].tolist() for r in range(n)] == ranks
+    assert ro[0] == 0 and ro[n] == B and np.all(np.diff(ro) >= 0)
+    if B:
+        # every rank within one sample's weight of its share of the total
+        w = weights[lengths]
+        share = w.sum() / n
+        for r in range(n):
+            assert w[sample_of[ro[r]:ro[r + 1]]].sum() <= share + w.max() + 1
+
+
+def test_vbs_special_cases():
+    lengths = np.array([9, 3, 3, 7, 1, 5, 5, 2], dtype=np.int64)
+    # equal weights: the sorted order cut into equal runs
+    ones = np.ones(10, dtype=np.int64)
+    sample_of, ro = O.partition_vbs(lengths, ones, 4)
+    assert sample_of.tolist() == [4, 7, 1, 2, 5, 6, 3, 0] and ro.tolist() == [0, 2, 4, 6, 8]
+    # weight = length (alpha = 1): total 35 over 2 ranks, the cut falls where the running weight reaches 17.5
+    ident = np.arange(10, dtype=np.int64)
+    sample_of, ro = O.partition_vbs(lengths, ident, 2)
+    run = np.cumsum(lengths[sample_of]) - lengths[sample_of]
+    assert ro.tolist() == [0, int(np.searchsorted(run * 2, 35, side="left")), 8] == [0, 6, 8]
+    # all weights zero: one rank takes everything; heavier long samples: fewer of them per rank
+    _, ro = O.partition_vbs(lengths, np.zeros(10, dtype=np.int64), 3)
+    assert ro.tolist() == [0, 8, 8, 8]
+    sq = ident ** 2
+    _, ro = O.partition_vbs(lengths, sq, 2)
+    assert ro[1] - ro[0] > ro[2] - ro[1]
+    with pytest.raises(O.OracleError):
+        O.partition_vbs(np.array([11], dtype=np.int64), ident, 2)
