@@ -169,6 +169,20 @@ int fs_gather_jagged_class(fs_ctx *ctx, const void *table, int64_t num_rows, int
 int fs_partition_fbs(fs_ctx *ctx, const int64_t *lengths, int64_t B, int64_t max_len, int32_t n_ranks,
                      int32_t *sample_of, int64_t *rank_offsets, fs_stream stream);
 
+/* Variable Batch Size partitioner (same section): the samples sorted as for FBS are cut into n_ranks runs of
+ * about equal total weight, so that ranks get different numbers of samples of similar length.  The weight of
+ * a sample is a function of its length - L^alpha in the paper, here weight_of_len [max_len + 1] int64 on the
+ * device, tabulated and scaled to integers by the caller, which makes every cut exact.  With W the total and
+ * w_before(s) the weight of the sorted positions before s, position s goes to rank
+ * min(n_ranks - 1, floor(n_ranks * w_before(s) / W)) (the paper does not state its rule; this one keeps every
+ * rank within one sample's weight of W / n_ranks).  W == 0: rank 0 takes everything.
+ *   sample_of    [B] int32 out: the sorted order;  rank_offsets [n_ranks + 1] int64 out: the cuts
+ * n_ranks * W must stay below 2^63; that, a negative weight or a length outside [0, max_len] are reported as
+ * FS_ERANGE by fs_check_async.  The paper's AutoTune (batch sizes corrected from measured step times) is the
+ * caller's business: it changes the weights.  B <= context max_ids. */
+int fs_partition_vbs(fs_ctx *ctx, const int64_t *lengths, int64_t B, const int64_t *weight_of_len, int64_t max_len,
+                     int32_t n_ranks, int32_t *sample_of, int64_t *rank_offsets, fs_stream stream);
+
 /* Indexed permute of a jagged tensor (Section 4.2, "Triton Kernel Optimizations": the kernel that applies a
  * partitioning to the gathered IDs): output sample k is input sample sample_of[k], k < n_out.
  *   values       [n_values] elements of elem_bytes bytes each (a multiple of 4: 8 for IDs, a row of

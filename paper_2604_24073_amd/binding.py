@@ -79,6 +79,7 @@ def load_library() -> ctypes.CDLL:
                                                      c_vp, c_vp, S]),
         "fs_jagged_ranged_combine": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i32, c_vp, c_i64, c_i64, c_vp, c_i32, c_vp,
                                                     c_vp, S]),
+        "fs_partition_vbs": (ctypes.c_int, [c_vp, c_vp, c_i64, c_vp, c_i64, c_i32, c_vp, c_vp, S]),
         "fs_partition_fbs": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i64, c_i32, c_vp, c_vp, S]),
         "fs_jagged_indexed_permute": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i32, c_vp, c_i64, c_vp, c_i64, c_vp, c_i64,
                                                      c_vp, S]),
@@ -243,6 +244,18 @@ def fs_partition_fbs(ctx: Context, lengths: torch.Tensor, max_len: int, n_ranks:
     rc = ctx.lib.fs_partition_fbs(ctx.handle, _ptr(lengths), B, max_len, n_ranks, _ptr(sample_of), _ptr(rank_offsets),
                                   _stream(stream))
     ctx.check(rc, "fs_partition_fbs")
+    return sample_of[:B], rank_offsets
+
+
+def fs_partition_vbs(ctx: Context, lengths: torch.Tensor, weight_of_len: torch.Tensor, n_ranks: int, stream=None):
+    """(sample_of [B] int32 = the length-sorted order, rank_offsets [n_ranks + 1] int64) of the VBS partitioner;
+    weight_of_len [max_len + 1] int64."""
+    B = lengths.numel()
+    sample_of = torch.empty(max(B, 1), dtype=torch.int32, device=lengths.device)
+    rank_offsets = torch.empty(n_ranks + 1, dtype=torch.int64, device=lengths.device)
+    rc = ctx.lib.fs_partition_vbs(ctx.handle, _ptr(lengths), B, _ptr(weight_of_len), weight_of_len.numel() - 1, n_ranks,
+                                  _ptr(sample_of), _ptr(rank_offsets), _stream(stream))
+    ctx.check(rc, "fs_partition_vbs")
     return sample_of[:B], rank_offsets
 
 

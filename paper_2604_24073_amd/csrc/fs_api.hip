@@ -436,6 +436,18 @@ int fs_partition_fbs(fs_ctx *ctx, const int64_t *lengths, int64_t B, int64_t max
     return launch_partition_fbs(ctx, lengths, B, max_len, n_ranks, sample_of, rank_offsets, as_stream(stream));
 }
 
+int fs_partition_vbs(fs_ctx *ctx, const int64_t *lengths, int64_t B, const int64_t *weight_of_len, int64_t max_len,
+                     int32_t n_ranks, int32_t *sample_of, int64_t *rank_offsets, fs_stream stream) {
+    if (!ctx) return FS_EINVAL;
+    FS_REQUIRE(ctx, B >= 0 && max_len >= 0 && n_ranks >= 1, "vbs: negative size or no rank");
+    if (B > ctx->max_ids) return set_err(ctx, FS_ENOMEM, "vbs: B beyond the context capacity");
+    FS_REQUIRE(ctx, rank_offsets && (B == 0 || (lengths && sample_of && weight_of_len)), "vbs: null pointer");
+    const int jrc = join_pending_work(ctx, as_stream(stream));      // the index workspace may still be in use
+    if (jrc != FS_OK) return jrc;
+    return launch_partition_vbs(ctx, lengths, B, weight_of_len, max_len, n_ranks, sample_of, rank_offsets,
+                                as_stream(stream));
+}
+
 int fs_jagged_indexed_permute(fs_ctx *ctx, const void *values, int64_t n_values, int32_t elem_bytes,
                               const int64_t *offsets, int64_t B, const int32_t *sample_of, int64_t n_out,
                               void *out_values, int64_t cap_out, int64_t *out_offsets, fs_stream stream) {

@@ -243,6 +243,8 @@ int launch_gather(fs_ctx *, const void *table, int64_t num_rows, int row_bytes, 
                   const int64_t *offsets, int64_t batch, int64_t n, void *out, hipStream_t s);
 int launch_partition_fbs(fs_ctx *, const int64_t *lengths, int64_t B, int64_t max_len, int32_t n_ranks,
                          int32_t *sample_of, int64_t *rank_offsets, hipStream_t s);
+int launch_partition_vbs(fs_ctx *, const int64_t *lengths, int64_t B, const int64_t *weight_of_len, int64_t max_len,
+                         int32_t n_ranks, int32_t *sample_of, int64_t *rank_offsets, hipStream_t s);
 int launch_indexed_permute(fs_ctx *, const void *values, int64_t n_values, int32_t elem_bytes, const int64_t *offsets,
                            int64_t B, const int32_t *sample_of, int64_t n_out, void *out_values, int64_t cap_out,
                            int64_t *out_offsets, hipStream_t s);

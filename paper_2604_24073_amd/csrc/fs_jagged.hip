@@ -13,6 +13,8 @@
 // they belong to with two 64-ary searches, stages their boundaries in LDS and lets every piece
 // binary-search LDS.
 //
+// VBS: the same sort, then the sorted order is cut into n runs of about equal total weight.
+//
 // Keyed transpose, ranged dispatch and ranged combine (same section of the paper) are the same copy
 // under a computed order of the F x B segments of a keyed jagged tensor: one more launch writes that
 // order down, then the three launches above run.
@@ -296,6 +298,112 @@ int launch_indexed_permute(fs_ctx *ctx, const void *values, int64_t n_values, in
                                in, sample_of, n_out, out_offsets, cap_out, ppe, (uint32_t *)out_values);
     }
     FS_LAUNCH_CHECK(ctx, "indexed permute kernels");
+    return FS_OK;
+}
+
+// ---- VBS: cuts of about equal weight --------------------------------------------------------------------
+// Sorted position s goes to rank min(n - 1, floor(n * w_before(s) / W)): weights are integers (a table per
+// length), so every cut is exact.  Two launches after the sort: weights summed per tile of 1024 sorted
+// positions; then every workgroup adds up the tile sums (the total W and its own start), scans its tile and
+// writes the start of every rank whose first sample lies in it.
+__device__ __forceinline__ int64_t vbs_weight(const int64_t *__restrict__ lengths, const int32_t *__restrict__ sorted,
+                                              const int64_t *__restrict__ weight_of_len, int64_t max_len, int64_t s,
+                                              int64_t B, bool &bad) {
+    if (s < 0 || s >= B) return 0;
+    const int64_t len = lengths[sorted[s]];
+    if (len < 0 || len > max_len) return 0;              // the sort has reported it already
+    const int64_t w = weight_of_len[len];
+    if (w < 0) { bad = true; return 0; }
+    return w;
+}
+
+__global__ __launch_bounds__(kScanThreads) void vbs_tile_sum_kernel(const int64_t *__restrict__ lengths,
+                                                                    const int32_t *__restrict__ sorted, int64_t B,
+                                                                    const int64_t *__restrict__ weight_of_len,
+                                                                    int64_t max_len, int64_t *__restrict__ tile_sum,
+                                                                    int *__restrict__ flags) {
+    __shared__ int64_t sh[kScanThreads / kWave];
+    const int64_t s0 = (int64_t)blockIdx.x * kScanTile + threadIdx.x * kScanIpt;
+    bool bad = false;
+    int64_t v = 0;
+#pragma unroll
+    for (int i = 0; i < kScanIpt; ++i) v += vbs_weight(lengths, sorted, weight_of_len, max_len, s0 + i, B, bad);
+    int64_t total;
+    (void)block_excl_scan_i64(v, sh, total);
+    if (threadIdx.x == 0) tile_sum[blockIdx.x] = total;
+    if (bad) atomicOr(flags, kFlagRowRange);
+}
+
+__device__ __forceinline__ int64_t vbs_rank(int64_t before, int64_t total, int64_t n) {
+    if (total <= 0) return 0;
+    const int64_t q = (int64_t)((uint64_t)n * (uint64_t)before / (uint64_t)total);      // n * total < 2^63 (checked)
+    return q >= n ? n - 1 : q;
+}
+
+__global__ __launch_bounds__(kScanThreads) void vbs_cut_kernel(const int64_t *__restrict__ lengths,
+                                                               const int32_t *__restrict__ sorted, int64_t B,
+                                                               const int64_t *__restrict__ weight_of_len, int64_t max_len,
+                                                               const int64_t *__restrict__ tile_sum, int tiles, int64_t n,
+                                                               int64_t *__restrict__ rank_offsets,
+                                                               int *__restrict__ flags) {
+    __shared__ int64_t sh[kScanThreads / kWave];
+    if (B == 0) {                                          // one workgroup: every rank starts (and ends) at 0
+        for (int64_t r = threadIdx.x; r <= n; r += kScanThreads) rank_offsets[r] = 0;
+        return;
+    }
+    int64_t mine = 0, all = 0;
+    for (int t = threadIdx.x; t < tiles; t += kScanThreads) {
+        const int64_t v = tile_sum[t];
+        all += v;
+        if (t < (int)blockIdx.x) mine += v;
+    }
+    int64_t tile_base, total;
+    (void)block_excl_scan_i64(mine, sh, tile_base);
+    (void)block_excl_scan_i64(all, sh, total);
+    if (total < 0 || total > INT64_MAX / n) {              // n * w_before would not fit: refuse, one rank takes all
+        if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(flags, kFlagRowRange);
+        total = 0;
+    }
+    const int64_t s0 = (int64_t)blockIdx.x * kScanTile + threadIdx.x * kScanIpt;
+    bool bad = false;
+    int64_t w[kScanIpt], v = 0;
+#pragma unroll
+    for (int i = 0; i < kScanIpt; ++i) {
+        w[i] = vbs_weight(lengths, sorted, weight_of_len, max_len, s0 + i, B, bad);
+        v += w[i];
+    }
+    const int64_t w_prev = vbs_weight(lengths, sorted, weight_of_len, max_len, s0 - 1, B, bad);
+    int64_t tile_total;
+    int64_t before = tile_base + block_excl_scan_i64(v, sh, tile_total);
+    // rank of the position before mine (-1 before the first: rank 0 starts at position 0)
+    int64_t r_prev = s0 > 0 ? vbs_rank(before - w_prev, total, n) : -1;
+#pragma unroll
+    for (int i = 0; i < kScanIpt; ++i) {
+        const int64_t s = s0 + i;
+        if (s < B) {
+            const int64_t r = vbs_rank(before, total, n);
+            for (int64_t x = r_prev + 1; x <= r; ++x) rank_offsets[x] = s;
+            r_prev = r;
+            before += w[i];
+            if (s == B - 1)
+                for (int64_t x = r + 1; x <= n; ++x) rank_offsets[x] = B;
+        }
+    }
+}
+
+int launch_partition_vbs(fs_ctx *ctx, const int64_t *lengths, int64_t B, const int64_t *weight_of_len, int64_t max_len,
+                         int32_t n_ranks, int32_t *sample_of, int64_t *rank_offsets, hipStream_t s) {
+    const int tiles = (int)(B > 0 ? ceil_div(B, kScanTile) : 1);
+    if (B > 0) {
+        const int rc = launch_unique(ctx, lengths, B, max_len + 1, ctx->jag_unique, ctx->jag_seg, sample_of, nullptr,
+                                     ctx->jag_n, s, 0);
+        if (rc != FS_OK) return rc;
+        hipLaunchKernelGGL(vbs_tile_sum_kernel, dim3((unsigned)tiles), dim3(kScanThreads), 0, s, lengths, sample_of, B,
+                           weight_of_len, max_len, ctx->jag_tile_sum, ctx->d_flags);
+    }
+    hipLaunchKernelGGL(vbs_cut_kernel, dim3((unsigned)tiles), dim3(kScanThreads), 0, s, lengths, sample_of, B,
+                       weight_of_len, max_len, ctx->jag_tile_sum, tiles, (int64_t)n_ranks, rank_offsets, ctx->d_flags);
+    FS_LAUNCH_CHECK(ctx, "vbs kernels");
     return FS_OK;
 }
 

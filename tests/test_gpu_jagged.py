@@ -226,3 +226,37 @@ def test_balancer_path_at_the_size_the_bench_times():
     assert torch.equal(tr.cpu(), torch.from_numpy(w_tr)) and torch.equal(tr_off.cpu(), torch.from_numpy(w_tr_off))
     assert fs.fs_check_async(ctx) == fs.FS_OK, ctx.last_error()
     ctx.close()
+
+
+@pytest.mark.parametrize("B,n,hi,alpha", [(0, 4, 64, 1.0), (1, 3, 64, 1.0), (5, 8, 64, 2.0), (1024, 8, 4096, 1.5),
+                                          (5000, 64, 4096, 1.0), (20000, 512, 16384, 1.7), (4097, 3, 300, 0.0),
+                                          (65536, 64, 4096, 2.0)])
+def test_vbs_partition_matches_oracle(B, n, hi, alpha):
+    rng = np.random.default_rng(B * 3 + n)
+    lengths = powerlaw_lengths(rng, B, 1, hi) if B else np.empty(0, np.int64)
+    if B > 10:
+        lengths[rng.integers(0, B, size=B // 10)] = 0
+    weights = np.round(np.arange(hi + 1, dtype=np.float64) ** alpha * 1024).astype(np.int64)
+    ctx = fs.Context(max_ids=max(B, 16), max_dim=8)
+    sample_of, rank_offsets = fs.fs_partition_vbs(ctx, dev(lengths), dev(weights), n)
+    assert fs.fs_check_async(ctx) == fs.FS_OK, ctx.last_error()
+    want_s, want_r = O.partition_vbs(lengths, weights, n)
+    assert rank_offsets.cpu().numpy().tolist() == want_r.tolist()
+    assert sample_of.cpu().numpy().tolist() == want_s.tolist()
+    ctx.close()
+
+
+def test_vbs_partition_reports_bad_weights():
+    ctx = fs.Context(max_ids=64, max_dim=8)
+    lengths = dev(np.array([3, 9, 7, 1], dtype=np.int64))
+    w = np.arange(11, dtype=np.int64)
+    w[7] = -1
+    fs.fs_partition_vbs(ctx, lengths, dev(w), 2)                    # a negative weight
+    assert fs.fs_check_async(ctx) == fs.FS_ERANGE
+    big = np.full(11, 2**60, dtype=np.int64)
+    _, ro = fs.fs_partition_vbs(ctx, lengths, dev(big), 4)          # n_ranks * total weight beyond 2^63
+    assert fs.fs_check_async(ctx) == fs.FS_ERANGE
+    assert ro.cpu().numpy().tolist() == [0, 4, 4, 4, 4]
+    fs.fs_partition_vbs(ctx, dev(np.array([3, 11], dtype=np.int64)), dev(np.arange(11, dtype=np.int64)), 2)
+    assert fs.fs_check_async(ctx) == fs.FS_ERANGE                   # a length beyond the table
+    ctx.close()
