@@ -640,7 +640,13 @@ fs_ahead *alloc_ahead(fs_ctx *ctx, const void *key) {
 // stream `s` waits for the work of `e`; the slot is free afterwards (any thread; `e` was claimed)
 int consume_ahead(fs_ctx *ctx, fs_ahead *e, hipStream_t s) {
     while (e->state.load(std::memory_order_acquire) != kAheadRecorded) std::this_thread::yield();
-    const hipError_t err = hipStreamWaitEvent(s, e->done, 0);
+    // Work issued iterations ahead has usually finished by now: asking costs a microsecond, a cross-stream
+    // wait twenty (it makes the runtime flush the producer's queue)
+    hipError_t err = hipEventQuery(e->done);
+    if (err != hipSuccess) {
+        (void)hipGetLastError();                              // "not ready" is not an error to keep
+        err = hipStreamWaitEvent(s, e->done, 0);
+    }
     e->state.store(kAheadFree, std::memory_order_release);
     if (err != hipSuccess) return hip_err(ctx, err, "hipStreamWaitEvent(ahead)");
     return FS_OK;
