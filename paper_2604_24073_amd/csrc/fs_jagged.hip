@@ -173,16 +173,14 @@ __device__ __forceinline__ int64_t wave_upper_bound(const int64_t *__restrict__ 
     return lo;
 }
 
-constexpr int kCopyPieces = 8;                                  // pieces per thread and round
-constexpr int kCopyRounds = 4;                                  // rounds per workgroup: the searches that open a tile
-                                                                // are a chain of dependent loads, paid once per tile
-constexpr int kCopyTile = kScanThreads * kCopyPieces * kCopyRounds;   // pieces per workgroup
+constexpr int kCopyTile = 8192;                                 // pieces per workgroup: the searches that open a tile are
+                                                                // a chain of dependent loads, paid once per tile
 constexpr int kCopyWindow = 2048 + 2;                           // sample boundaries staged in LDS
 
 // V: the piece, the widest of 4, 8, 16 bytes that divides the element; ppe pieces per element.
 // Inside a tile everything is counted from the tile's first element in 32 bits (a 64-bit division per
 // piece would cost more than the copy).
-template <typename V>
+template <typename V, int PIECES>
 __global__ __launch_bounds__(kScanThreads) void permute_copy_kernel(const V *__restrict__ values, const jagged_in in,
                                                                     const int32_t *__restrict__ sample_of,
                                                                     int64_t n_out, const int64_t *__restrict__ out_offsets,
@@ -240,12 +238,13 @@ __global__ __launch_bounds__(kScanThreads) void permute_copy_kernel(const V *__r
         }
         j = lo - 1;
     }
-    for (uint32_t r0 = 0; r0 < kWavePieces; r0 += kWave * kCopyPieces) {
+    static_assert(kWavePieces % (kWave * PIECES) == 0, "a wavefront's quarter is a whole number of rounds");
+    for (uint32_t r0 = 0; r0 < kWavePieces; r0 += kWave * PIECES) {
         if (w0 + r0 >= tile_pieces) break;                      // whole wavefront
-        V v[kCopyPieces];
-        bool live[kCopyPieces];
+        V v[PIECES];                                            // 128 bytes per lane in flight whatever the piece
+        bool live[PIECES];
 #pragma unroll
-        for (int i = 0; i < kCopyPieces; ++i) {
+        for (int i = 0; i < PIECES; ++i) {
             const uint32_t l = w0 + r0 + (uint32_t)i * kWave + lane;                // piece of the tile
             live[i] = l < tile_pieces;
             if (live[i]) {
@@ -265,7 +264,7 @@ __global__ __launch_bounds__(kScanThreads) void permute_copy_kernel(const V *__r
             }
         }
 #pragma unroll
-        for (int i = 0; i < kCopyPieces; ++i) {
+        for (int i = 0; i < PIECES; ++i) {
             const uint32_t l = w0 + r0 + (uint32_t)i * kWave + lane;
             if (live[i]) out[q0 + l] = v[i];
         }
@@ -288,13 +287,13 @@ int launch_indexed_permute(fs_ctx *ctx, const void *values, int64_t n_values, in
         if (blocks > 0x7fffffffll) return set_err(ctx, FS_EINVAL, "indexed permute: output too large for one launch");
         const dim3 grid((unsigned)blocks);
         if (piece == 16)
-            hipLaunchKernelGGL((permute_copy_kernel<u32x4>), grid, dim3(kScanThreads), 0, s, (const u32x4 *)values,
+            hipLaunchKernelGGL((permute_copy_kernel<u32x4, 8>), grid, dim3(kScanThreads), 0, s, (const u32x4 *)values,
                                in, sample_of, n_out, out_offsets, cap_out, ppe, (u32x4 *)out_values);
         else if (piece == 8)
-            hipLaunchKernelGGL((permute_copy_kernel<uint64_t>), grid, dim3(kScanThreads), 0, s, (const uint64_t *)values,
+            hipLaunchKernelGGL((permute_copy_kernel<uint64_t, 16>), grid, dim3(kScanThreads), 0, s, (const uint64_t *)values,
                                in, sample_of, n_out, out_offsets, cap_out, ppe, (uint64_t *)out_values);
         else
-            hipLaunchKernelGGL((permute_copy_kernel<uint32_t>), grid, dim3(kScanThreads), 0, s, (const uint32_t *)values,
+            hipLaunchKernelGGL((permute_copy_kernel<uint32_t, 32>), grid, dim3(kScanThreads), 0, s, (const uint32_t *)values,
                                in, sample_of, n_out, out_offsets, cap_out, ppe, (uint32_t *)out_values);
     }
     FS_LAUNCH_CHECK(ctx, "indexed permute kernels");
