@@ -54,6 +54,28 @@ def algorithmic_bytes(n_t, u_t, n_t1, u_t1, dim, w):
             "total": unique + split + gather + reduce_update}
 
 
+def group_tables(tabs, G):
+    """The tables of a shard in G groups (one context, stream and call sequence each).  Tables of one row width
+    share the launches of their class passes and gathers inside a call, so a group should hold few widths, and
+    the groups run side by side, so they should be about equally heavy: every assignment is tried (a shard has a
+    handful of tables) and the one with the smallest (heaviest group / mean group + 0.05 x launch classes) kept."""
+    import itertools
+    if G == 1 or len(tabs) > 12:
+        return [tabs[g::G] for g in range(G)]
+    load = [sum(t.n) * t.dim * t.w for t in tabs]
+    mean = sum(load) / G
+    best, best_cost = None, None
+    for assign in itertools.product(range(G), repeat=len(tabs)):
+        if len(set(assign)) < G:
+            continue
+        heavy = max(sum(l for l, a in zip(load, assign) if a == g) for g in range(G))
+        classes = len({(a, t.dim * t.w) for a, t in zip(assign, tabs)})
+        cost = heavy / mean + 0.05 * classes
+        if best_cost is None or cost < best_cost - 1e-12:
+            best, best_cost = assign, cost
+    return [[t for t, a in zip(tabs, best) if a == g] for g in range(G)]
+
+
 def bench_tables(args, cfg) -> int:
     """Several tables per shard (BASELINE configs[2]): one independent problem per table (table-local IDs, own
     buffers), ONE context and stream for the shard: per step the index halves of all tables two iterations
@@ -84,7 +106,7 @@ def bench_tables(args, cfg) -> int:
         tabs.append(t)
     # the tables of the shard in G groups, each with its own context and stream (G = 1: one call per step for all)
     G = max(1, min(args.table_groups, len(tabs)))
-    groups = [tabs[g::G] for g in range(G)]
+    groups = group_tables(tabs, G)
     ctxs = [fs.Context(max_ids=max(max(t.n) for t in grp), max_dim=max(t.dim for t in grp)) for grp in groups]
     streams = [torch.cuda.Stream() for _ in groups]
     ctx = ctxs[0]
@@ -207,6 +229,7 @@ def bench_tables(args, cfg) -> int:
                    "ids_per_iteration": [t.n for t in tabs], "unique_rows": u_all},
         "schedule": f"the tables in {G} group(s), each with a context and a stream: per step and group one multi-table "
                     "pipelined call + the index halves of its tables two iterations ahead in shared launches",
+        "table_groups": [[tabs.index(t) for t in grp] for grp in groups],
         "host_enqueue_us_per_step": t_enq / args.steps * 1e6,
         "step_algorithmic_bytes": step_bytes, "step_algorithmic_GBps": step_gbps,
         "step_frac_of_hbm_peak": step_gbps / HBM_PEAK_GBPS,
