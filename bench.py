@@ -256,7 +256,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-isolated", action="store_true",
                     help="skip the extra launches that time every kernel alone on the chip after the timed steps")
-    ap.add_argument("--time-every", type=int, default=8,
+    ap.add_argument("--time-every", type=int, default=16,
                     help="bracket the kernels of one timed step in this many with HIP event pairs")
     ap.add_argument("--calibration-copy", type=int, default=0, metavar="MiB",
                     help="also launch one plain copy of this many MiB before the steps: the known-size dispatch that "
