@@ -30,7 +30,7 @@ def make_its(rng, rows, dim, n_iter, users=40, max_len=300):
 
 
 def run_pipelined(ctx, table, state, its, lr, eps, ahead=False, sync_each=True, two_part=False, disturb=None,
-                  inverse=True):
+                  inverse=True, between=None):
     """ahead: True / "last_step": dedup every batch with fs_unique_ids_ahead, three batches before the
     iteration that gathers it (five layout buffers in rotation; "last_step": ordered after the start
     of the previous pipelined call instead of the stream's current position, six layout buffers).
@@ -44,7 +44,8 @@ def run_pipelined(ctx, table, state, its, lr, eps, ahead=False, sync_each=True, 
     before, three output batches in rotation); disturb: iteration before whose call the pipeline is joined,
     the library told to forget what it fetched and the fetched part of the output batch overwritten (the call
     must then redo the whole lookup).
-    inverse=False: layouts without the inverse map (optional for everything but the two-part lookup)."""
+    inverse=False: layouts without the inverse map (optional for everything but the two-part lookup).
+    between: called after every step call (other work on the same context between the steps)."""
     batch = int(ahead[5]) if isinstance(ahead, str) and ahead.startswith("batch") else 0
     index_ahead = ahead in ("index", "index_last_step")
     last_step = isinstance(ahead, str) and ahead.endswith("last_step")
@@ -121,6 +122,8 @@ def run_pipelined(ctx, table, state, its, lr, eps, ahead=False, sync_each=True, 
         else:
             fs.fs_prioritized_step_pipelined(ctx, all_args[t], nxt)
         stepped[0] = True
+        if between is not None:
+            between(t)
         if not sync_each:
             continue
         assert fs.fs_check_async(ctx) == fs.FS_OK
@@ -249,6 +252,43 @@ def test_class_lookup_matches_oracle(dtype, dim, n):
         with pytest.raises(fs.FreeScaleError) as e:
             fs.fs_gather_jagged_class(ctx, d_table, d_values, None, d_inv, d_flag, 2, out)
         assert e.value.code == fs.FS_EINVAL
+    ctx.close()
+
+
+def test_balancer_calls_between_the_steps_leave_the_pipeline_alone():
+    """The partitioner and the jagged shuffles use the context's index workspace; called between pipelined
+    steps (they first wait for what the side streams still do with it) they must neither disturb the steps nor
+    be disturbed: same table, state and batches as without them, and their own results as from the oracle."""
+    ctx = fs.Context(max_ids=20000, max_dim=128)
+    rng = np.random.default_rng(31)
+    rows, dim = 30000, 64
+    table = rand_table(rng, rows, dim, "f32")
+    state = np.zeros(rows, np.float32)
+    its = make_its(rng, rows, dim, 6)
+    ts, ss, os_ = run_pipelined(ctx, table, state, its, 0.01, 1e-8)
+    lens = rng.integers(0, 500, size=3000).astype(np.int64)
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    values = rng.integers(0, rows, size=int(offsets[-1])).astype(np.int64)
+    d_lens, d_offsets, d_values = dev(lens), dev(offsets), dev(values)
+    want_s, want_r = O.partition_fbs(lens, 16)
+    want_v, want_o = O.jagged_indexed_permute(values, offsets, want_s)
+    got = []
+
+    def between(t):
+        sample_of, rank_off = fs.fs_partition_fbs(ctx, d_lens, 500, 16)
+        out, out_off = fs.fs_jagged_indexed_permute(ctx, d_values, d_offsets, sample_of, values.shape[0])
+        got.append((sample_of, rank_off, out, out_off))
+
+    for ahead, sync_each in (("batch2", False), (False, False), ("index", True)):
+        got.clear()
+        ta, sa, oa = run_pipelined(ctx, table, state, its, 0.01, 1e-8, ahead=ahead, sync_each=sync_each, between=between)
+        assert torch.equal(ta, ts) and torch.equal(sa, ss), ahead
+        for a, b in zip(oa, os_):
+            if "emb_next" in a:
+                assert a["emb_next"].tobytes() == b["emb_next"].tobytes(), ahead
+        for sample_of, rank_off, out, out_off in got:
+            assert sample_of.cpu().numpy().tolist() == want_s.tolist() and rank_off.cpu().numpy().tolist() == want_r.tolist()
+            assert out.cpu().numpy().tolist() == want_v.tolist() and out_off.cpu().numpy().tolist() == want_o.tolist()
     ctx.close()
 
 
