@@ -9,7 +9,7 @@
 // Indexed permute: output sample k is input sample sample_of[k].  Three launches: lengths summed per
 // tile of samples, the output offsets by a scan with tile prefixes, and the copy.  The copy is driven
 // by the OUTPUT (every lane writes consecutive pieces of the output, so a 16K-item sample costs per
-// item what a short one costs): a workgroup takes 8192 consecutive output pieces, finds the samples
+// item what a short one costs): a workgroup takes 4096 or 8192 consecutive output pieces, finds the samples
 // they belong to with two 64-ary searches, stages their boundaries in LDS and lets every piece
 // binary-search LDS.
 //
@@ -173,8 +173,11 @@ __device__ __forceinline__ int64_t wave_upper_bound(const int64_t *__restrict__ 
     return lo;
 }
 
-constexpr int kCopyTile = 8192;                                 // pieces per workgroup: the searches that open a tile are
-                                                                // a chain of dependent loads, paid once per tile
+// pieces per workgroup: the searches that open a tile are a chain of dependent loads, paid once per tile, and
+// the chip writes faster the more workgroups share a job.  Measured: 64 KB of output per workgroup for 8-byte
+// pieces (16.7 M IDs: 75 us with twice that), 128 KB for 16-byte pieces (250 k rows of 512 bytes: 50 us, and
+// 133 us with half of that)
+template <typename V> constexpr int copy_tile() { return sizeof(V) == 16 ? 8192 : 4096; }
 constexpr int kCopyWindow = 2048 + 2;                           // sample boundaries staged in LDS
 
 // V: the piece, the widest of 4, 8, 16 bytes that divides the element; ppe pieces per element.
@@ -185,6 +188,7 @@ __global__ __launch_bounds__(kScanThreads) void permute_copy_kernel(const V *__r
                                                                     const int32_t *__restrict__ sample_of,
                                                                     int64_t n_out, const int64_t *__restrict__ out_offsets,
                                                                     int64_t cap_out, int ppe, V *__restrict__ out) {
+    constexpr int kCopyTile = copy_tile<V>();
     __shared__ int32_t w_rel[kCopyWindow];      // out_offsets[ka + j] minus the tile's first element (at least -1)
     __shared__ int64_t w_delta[kCopyWindow];    // first input element of sample ka + j minus its first output element
     __shared__ int64_t win[2];
@@ -283,7 +287,7 @@ int launch_indexed_permute(fs_ctx *ctx, const void *values, int64_t n_values, in
     if (cap_out > 0 && n_out > 0) {
         const int piece = elem_bytes % 16 == 0 ? 16 : (elem_bytes % 8 == 0 ? 8 : 4);
         const int ppe = elem_bytes / piece;
-        const int64_t blocks = ceil_div(cap_out * ppe, kCopyTile);
+        const int64_t blocks = ceil_div(cap_out * ppe, piece == 16 ? copy_tile<u32x4>() : copy_tile<uint64_t>());
         if (blocks > 0x7fffffffll) return set_err(ctx, FS_EINVAL, "indexed permute: output too large for one launch");
         const dim3 grid((unsigned)blocks);
         if (piece == 16)
@@ -293,7 +297,7 @@ int launch_indexed_permute(fs_ctx *ctx, const void *values, int64_t n_values, in
             hipLaunchKernelGGL((permute_copy_kernel<uint64_t, 16>), grid, dim3(kScanThreads), 0, s, (const uint64_t *)values,
                                in, sample_of, n_out, out_offsets, cap_out, ppe, (uint64_t *)out_values);
         else
-            hipLaunchKernelGGL((permute_copy_kernel<uint32_t, 32>), grid, dim3(kScanThreads), 0, s, (const uint32_t *)values,
+            hipLaunchKernelGGL((permute_copy_kernel<uint32_t, 16>), grid, dim3(kScanThreads), 0, s, (const uint32_t *)values,
                                in, sample_of, n_out, out_offsets, cap_out, ppe, (uint32_t *)out_values);
     }
     FS_LAUNCH_CHECK(ctx, "indexed permute kernels");
