@@ -44,3 +44,21 @@ def test_step_args_layout_matches_header_order():
     body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
     names = re.findall(r"[\*\s]([a-z_0-9]+)\s*[;,]", body)
     assert names == [f[0] for f in fs.fs_step_args._fields_]
+
+
+def test_step_args_size_and_offsets_match_a_c_compiler(tmp_path):
+    # the header read by a plain C compiler must lay the record out exactly as the ctypes mirror does
+    import subprocess
+    root = os.path.join(os.path.dirname(fs.LIB_PATH), "..")
+    fields = [f[0] for f in fs.fs_step_args._fields_]
+    src = tmp_path / "layout.c"
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "freescale.h"\nint main(void) {\n'
+                   '  printf("%zu\\n", sizeof(fs_step_args));\n' +
+                   "".join(f'  printf("%zu\\n", offsetof(fs_step_args, {n}));\n' for n in fields) +
+                   "  return 0;\n}\n")
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(root, "include"), str(src),
+                    "-o", str(exe)], check=True)
+    out = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    assert out[0] == ctypes.sizeof(fs.fs_step_args)
+    assert out[1:] == [getattr(fs.fs_step_args, n).offset for n in fields]
