@@ -138,9 +138,8 @@ def bench_tables(args, cfg) -> int:
     stepped = [False]
 
     def ahead(s):
-        for c, st, grp in zip(ctxs, streams, groups):
-            fs.fs_step_forward_ahead_batch(c, [t.args[s % period] for t in grp],
-                                           stream=fs.FS_STREAM_LAST_STEP if stepped[0] else st)
+        for c, st, rec in zip(ctxs, streams, step_records):
+            fs.fs_step_forward_ahead_batch(c, rec[s % period], stream=fs.FS_STREAM_LAST_STEP if stepped[0] else st)
 
     def run(k0, k):
         for s in range(k0, k0 + k):
@@ -188,12 +187,20 @@ def bench_tables(args, cfg) -> int:
     torch.cuda.synchronize()
     k0 = 1 + args.warmup
     fs.fs_ctx_set_kernel_timing(ctx, args.steps, args.time_every)
+    for c in ctxs:
+        fs.fs_ctx_host_times(c, reset=True)
     t0 = time.perf_counter()
     run(k0, args.steps)
     t_enq = time.perf_counter() - t0
     join_all()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    names = ("wait_side_thread", "fork_and_post", "wait_side_stream", "priority_and_gather", "index_thread_enqueue",
+             "side_thread_enqueue")
+    host_phases = []
+    for c in ctxs:
+        ht = fs.fs_ctx_host_times(c)
+        host_phases.append({k: ht[i] / ht[6] for i, k in enumerate(names)} if ht[6] > 0 else None)
     join_all(check=True)
     kinds = {"gather": fs.FS_TIME_GATHER, "priority_pass": fs.FS_TIME_UPDATE_CO, "deferred_pass": fs.FS_TIME_UPDATE_EX}
     kernel_ms = {}
@@ -208,15 +215,19 @@ def bench_tables(args, cfg) -> int:
         step_bytes += sum(by[s % 2]["total"] for s in range(k0, k0 + args.steps)) / args.steps
     ms_per_step = elapsed / args.steps * 1e3
     step_gbps = step_bytes / (ms_per_step * 1e-3) / 1e9
-    t = tabs[0]
-    by0 = algorithmic_bytes(t.n[0], t.u[0], t.n[1], t.u[1], t.dim, t.w)["gather"]
-    by1 = algorithmic_bytes(t.n[1], t.u[1], t.n[0], t.u[0], t.dim, t.w)["gather"]
+    # the event pairs of the first group's context bracket everything that call enqueues of one kind: the gathers
+    # (or class passes of one class) of all its tables, one launch per row width
+    grp0 = groups[0]
     roofline = None
     if kernel_ms.get("gather"):
-        gb = (by0 + by1) / 2 / (kernel_ms["gather"] * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": "gather_kernel (table 0)", "achieved": gb, "peak": HBM_PEAK_GBPS,
-                    "unit": "GB/s", "frac": gb / HBM_PEAK_GBPS, "traffic": None,
-                    "avg_launch_us": kernel_ms["gather"] * 1e3, "algorithmic_bytes_per_launch": (by0 + by1) / 2}
+        gbytes = sum((algorithmic_bytes(t.n[0], t.u[0], t.n[1], t.u[1], t.dim, t.w)["gather"] +
+                      algorithmic_bytes(t.n[1], t.u[1], t.n[0], t.u[0], t.dim, t.w)["gather"]) / 2 for t in grp0)
+        widths = len({t.dim * t.w for t in grp0})
+        gb = gbytes / (kernel_ms["gather"] * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": f"gather_kernel (the {len(grp0)} tables of group 0: {widths} launch(es), "
+                                              "bracketed together)",
+                    "achieved": gb, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gb / HBM_PEAK_GBPS, "traffic": None,
+                    "avg_launch_us": kernel_ms["gather"] * 1e3, "algorithmic_bytes_per_launch": gbytes}
     out = {
         "metric": "unique embedding rows updated/sec + achieved HBM GB/s (% of peak), 1 GPU",
         "value": rows / elapsed, "unit": "rows/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -230,6 +241,7 @@ def bench_tables(args, cfg) -> int:
         "schedule": f"the tables in {G} group(s), each with a context and a stream: per step and group one multi-table "
                     "pipelined call + the index halves of its tables two iterations ahead in shared launches",
         "table_groups": [[tabs.index(t) for t in grp] for grp in groups],
+        "host_phase_us_per_step_and_group": host_phases,
         "host_enqueue_us_per_step": t_enq / args.steps * 1e6,
         "step_algorithmic_bytes": step_bytes, "step_algorithmic_GBps": step_gbps,
         "step_frac_of_hbm_peak": step_gbps / HBM_PEAK_GBPS,

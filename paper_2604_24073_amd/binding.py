@@ -432,8 +432,9 @@ def fs_step_forward_ahead(ctx: Context, args: fs_step_args, stream=None) -> None
 
 
 def fs_step_forward_ahead_batch(ctx: Context, args, stream=None) -> None:
-    """args: sequence of 1..FS_MAX_AHEAD_BATCH argument records (copied into one contiguous array)."""
-    arr = (fs_step_args * len(args))(*args)
+    """args: sequence of 1..FS_MAX_AHEAD_BATCH argument records (copied into one contiguous array), or such an
+    array from step_args_array (passed as it is)."""
+    arr = args if isinstance(args, ctypes.Array) else (fs_step_args * len(args))(*args)
     stream_arg = ctypes.c_void_p(-1) if stream == FS_STREAM_LAST_STEP else _stream(stream)
     rc = ctx.lib.fs_step_forward_ahead_batch(ctx.handle, arr, len(args), stream_arg)
     ctx.check(rc, "fs_step_forward_ahead_batch")
