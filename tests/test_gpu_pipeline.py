@@ -530,3 +530,38 @@ def test_graph_replays_match_eager_steps_bitwise(dtype):
         assert torch.equal(e[3].view(view), g[3].view(view)), f"gathered rows after replay {s}"
         assert torch.equal(e[4], g[4]), f"split counts after replay {s}"
     ctx.close()
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_shapes_and_schedules_match_the_oracle(seed):
+    """Seeded random table shapes, batch sizes, iteration counts and schedules (ahead mode, waits between the calls,
+    enqueueing threads, one-part or two-part lookup): every one must give the oracle's run."""
+    rng = np.random.default_rng(9000 + seed)
+    dtype = ("f32", "bf16")[int(rng.integers(0, 2))]
+    dim = int(rng.choice([8, 32, 64, 96, 128, 256]))
+    rows = int(rng.choice([50, 3000, 200000]))
+    T = int(rng.integers(2, 9))
+    users, max_len = int(rng.integers(1, 60)), int(rng.choice([3, 40, 400]))
+    ahead = [False, True, "last_step", "index", "index_last_step", "batch2", "batch3_last_step", "batch4"][int(rng.integers(0, 8))]
+    sync_each, threaded, two_part = bool(rng.integers(0, 2)), bool(rng.integers(0, 2)), seed % 2 == 1
+    what = f"seed={seed} {dtype} dim={dim} rows={rows} T={T} users={users} max_len={max_len} ahead={ahead} " \
+           f"sync_each={sync_each} threaded={threaded} two_part={two_part}"
+    print(what, flush=True)
+    table = rand_table(rng, rows, dim, dtype)
+    state = (rng.random(rows) * 0.1).astype(np.float32)
+    its = make_its(rng, rows, dim, T, users=users, max_len=max_len)
+    ctx = fs.Context(max_ids=max(max(len(it.values) for it in its), 16), max_dim=dim)
+    ctx.lib.fs_ctx_set_threaded_enqueue(ctx.handle, 1 if threaded else 0)
+    ta, sa, oa = run_pipelined(ctx, table, state, its, 0.01, 1e-8, ahead=ahead, sync_each=sync_each, two_part=two_part)
+    t_ref, s_ref, want = run_steps_oracle(table, state, its, 0.01, 1e-8)
+    assert_rows_close(table_to_host(ta), t_ref, what)
+    assert_close_f32(sa.cpu().numpy(), s_ref, what)
+    for t, a in enumerate(oa):
+        w = want[t + 1]
+        sp = w["split"]
+        assert a["counts"].tolist() == [len(sp["co"]), len(sp["ex"]), len(sp["ex_next"])], (what, t)
+        assert_close_f32(a["reduced"], w["reduced"], f"{what} reduced {t}")
+        if "emb_next" in a:
+            assert_rows_close(a["emb_next"], w["emb_next"], f"{what} emb {t}")
+    ctx.lib.fs_ctx_set_threaded_enqueue(ctx.handle, 1)
+    ctx.close()
