@@ -571,6 +571,50 @@ def main() -> int:
                   "index kernels")]
         step_traffic = sum(parts) if all(parts) else None
 
+    # ---- beside the metric: the chip's own copy rate (the achievable ceiling) and the step with the caches
+    # scrubbed between iterations (a 1 GiB -> 1 GiB copy, eight times the memory-side cache, before every step)
+    copy_ceiling = None
+    if not args.no_isolated and pipelined:
+        fs.fs_step_join(ctx)
+        torch.cuda.synchronize()
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+
+        def timed_loop(f, reps):
+            f(0)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(reps):
+                f(i + 1)
+            fs.fs_step_join(ctx)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / reps
+
+        def scrub(i):
+            fs.fs_stream_copy(ctx, src, dst)
+
+        t_copy = timed_loop(scrub, 20)
+        k1 = [k0 + args.steps]
+
+        def step_and_scrub(i):
+            fs.fs_stream_copy(ctx, src, dst)
+            run(k1[0], 1)
+            k1[0] += 1
+
+        if graphs is None:
+            t_both = timed_loop(step_and_scrub, 20)
+            cold_us = (t_both - t_copy) * 1e6
+        else:
+            cold_us = None
+        copy_gbps = 2 * src.numel() / t_copy / 1e9
+        copy_ceiling = {"stream_copy_GBps": copy_gbps, "stream_copy_frac_of_hbm_peak": copy_gbps / HBM_PEAK_GBPS,
+                        "bytes": 2 * src.numel(),
+                        "step_algorithmic_frac_of_stream_copy": step_gbps / copy_gbps,
+                        "cold_step_us": cold_us,
+                        "cold_step_note": "20 steps, each behind a 1 GiB -> 1 GiB copy on the same stream, minus the "
+                                          "time of the copies alone; the steady-state loop does not flush anything"}
+        del src, dst
+
     # ---- the same kernels alone on the chip: each operation launched 20 times back to back on one
     # stream with nothing beside it (after the timed region; the table keeps being updated, which
     # does not change what the kernels move)
@@ -683,6 +727,7 @@ def main() -> int:
                                                    if step_traffic else None),
         "kernel_avg_us": {k: (v * 1e3 if v is not None else None) for k, v in kernel_ms.items()},
         "roofline": roofline,
+        "achievable_ceiling": copy_ceiling,
         "isolated_kernels": isolated,
         "load_balancer_path": balancer,
         "cpu_baseline": cpu_baseline,
