@@ -461,13 +461,24 @@ def main() -> int:
         fs.fs_ctx_set_kernel_timing(ctx, args.steps, args.time_every)
     torch.cuda.synchronize()
     fs.fs_ctx_host_times(ctx, reset=True)
+    # ten marks on the caller's stream inside the timed region (an event record each, no wait): the spread of
+    # the step time over the run
+    nblk = 10 if args.steps >= 100 else 1
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(nblk + 1)]
+    bounds = [k0 + args.steps * b // nblk for b in range(nblk + 1)]
     t0 = time.perf_counter()
-    run(k0, args.steps)
+    for b in range(nblk):
+        marks[b].record()
+        run(bounds[b], bounds[b + 1] - bounds[b])
+    marks[nblk].record()
     t_enq = time.perf_counter() - t0
     fs.fs_step_join(ctx)                      # the index half of the last step is part of the timed work
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     assert fs.fs_check_async(ctx) == fs.FS_OK, ctx.last_error()
+    blk_us = sorted(marks[b].elapsed_time(marks[b + 1]) * 1e3 / (bounds[b + 1] - bounds[b]) for b in range(nblk))
+    step_spread = {"blocks": nblk, "min_us": blk_us[0], "median_us": blk_us[len(blk_us) // 2], "max_us": blk_us[-1],
+                   "note": "step time of each tenth of the timed region, from events on the caller's stream"}
     ht = fs.fs_ctx_host_times(ctx)
     host_phases = None
     if ht[6] > 0:
@@ -720,6 +731,7 @@ def main() -> int:
         "schedule": args.mode + ((f"+index_half_ahead(batches of {K})" if index_ahead else "+dedup_ahead") if ahead else "") + ("+two_part_lookup" if args.two_part else ""), "reduced_gradients_in_memory": bool(args.keep_reduced),
         "class_occurrences": cls_pos, "class_rows": cls_rows, "host_enqueue_us_per_step": t_enq / args.steps * 1e6,
         "host_phase_us_per_step": host_phases,
+        "step_time_spread": step_spread,
         "step_algorithmic_bytes": step_bytes, "step_algorithmic_GBps": step_gbps,
         "step_frac_of_hbm_peak": step_gbps / HBM_PEAK_GBPS,
         "step_measured_traffic_bytes": step_traffic,
