@@ -426,7 +426,7 @@ def main() -> int:
             w0 = (w0.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
         reps, times, want = 0, [], None
         t_budget = time.perf_counter()
-        while reps < 3 or (time.perf_counter() - t_budget < 10.0 and reps < 30):
+        while reps < 3 or (time.perf_counter() - t_budget < 10.0 and reps < 100):
             t_ref, s_ref = w0.copy(), np.zeros(len(touched), np.float32)
             lay0 = O.unique_ids(v0c, len(touched))          # produced by the previous step: not timed
             t0 = time.perf_counter()
