@@ -66,13 +66,26 @@ struct unique_dev_batch {
     unique_dev_job j[kMaxBatch];
 };
 
+// Workgroups go to the eight XCDs in turn, each with an L2 of its own.  Neighbouring tiles write neighbouring
+// runs of every bin; taken by the same XCD one after the other, their runs meet in one L2 and leave it as
+// whole lines instead of as eight partly filled ones.  XCD x takes the x-th eighth of the tiles; the grid is a
+// multiple of eight workgroups wide.  Returns -1 for a workgroup without a tile.
+__device__ __forceinline__ int xcd_tile(int tiles) {
+    const int per = (tiles + 7) / 8;
+    const int b = (int)blockIdx.x;
+    if (b / 8 >= per) return -1;
+    const int t = (b % 8) * per + b / 8;
+    return t < tiles ? t : -1;
+}
+
 // ---- radix pass 1/2: per-tile digit histogram ---------------------------------------------------
 template <typename K, bool FIRST>
 __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(const unique_dev_batch batch, int src, int shift,
                                                                   int bits, int *__restrict__ flags) {
     FS_WG_TRACE(1);
     const unique_dev_job &job = batch.j[blockIdx.y];
-    if ((int)blockIdx.x >= job.tiles) return;
+    const int tile_id = xcd_tile(job.tiles);
+    if (tile_id < 0) return;
     const int64_t *__restrict__ ids = job.ids;
     const K *__restrict__ keys_in = (const K *)job.keys[src];
     const int n = job.n;
@@ -82,7 +95,7 @@ __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(const unique_d
     const int bins = 1 << bits;
     for (int d = threadIdx.x; d < bins; d += kSortThreads) hist[d] = 0;
     __syncthreads();
-    const int base = blockIdx.x * kSortTile;
+    const int base = tile_id * kSortTile;
     bool bad = false;
 #pragma unroll
     for (int r = 0; r < kSortKpt; ++r) {
@@ -100,7 +113,7 @@ __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(const unique_d
         }
     }
     __syncthreads();
-    for (int d = threadIdx.x; d < bins; d += kSortThreads) tile_hist[blockIdx.x * bins + d] = hist[d];
+    for (int d = threadIdx.x; d < bins; d += kSortThreads) tile_hist[tile_id * bins + d] = hist[d];
     if (bad) atomicOr(flags, kFlagRowRange);
 }
 
@@ -111,7 +124,8 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(const uniqu
                                                                      int bits, int last) {
     FS_WG_TRACE(2);
     const unique_dev_job &job = batch.j[blockIdx.y];
-    if ((int)blockIdx.x >= job.tiles) return;
+    const int tile_id = xcd_tile(job.tiles);
+    if (tile_id < 0) return;
     const int64_t *__restrict__ ids = job.ids;
     const K *__restrict__ keys_in = (const K *)job.keys[src];
     const int32_t *__restrict__ idx_in = job.idx[src];
@@ -127,7 +141,7 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(const uniqu
     const int bins = 1 << bits;
     const int lane = threadIdx.x & (kWave - 1);
     const int w = threadIdx.x / kWave;
-    const int tile = blockIdx.x;
+    const int tile = tile_id;
 
     // keys first: their latency overlaps the table scan
     const int base = tile * kSortTile + w * (kWave * kSortKpt);
@@ -342,7 +356,7 @@ static int unique_batch_impl(fs_ctx *ctx, const unique_dev_batch &batch, int cou
     const int bits = (key_bits + passes - 1) / passes;            // <= kRadixBits, evenly spread
     int cur = 0;   // buffer holding the input of the next pass (unused for the first pass)
     if (tiles > 0) {
-        const dim3 grid((unsigned)tiles, (unsigned)count);
+        const dim3 grid((unsigned)((tiles + 7) / 8 * 8), (unsigned)count);
         for (int p = 0; p < passes; ++p) {
             const int shift = p * bits;
             const int last = (p == passes - 1) ? 1 : 0;
