@@ -159,7 +159,8 @@ int fs_gather_jagged_class(fs_ctx *ctx, const void *table, int64_t num_rows, int
 /* Fixed Batch Size partitioner (Section 4.1, "Partitioning Algorithms"): the B samples are sorted by UIH
  * length (ascending, equal lengths in sample order) and dealt to n_ranks ranks in a zig-zag - rank i takes
  * the sorted positions i, 2n-1-i, 2n+i, 4n-1-i, ... that exist (forth in even rounds of n, back in odd ones;
- * the paper prints 2n-i and 4n-i, which is not a partition).  Every rank gets B/n samples (one more for
+ * the index list printed in Section 4.1 starts the backward rounds one position later, which is not a
+ * partition).  Every rank gets B/n samples (one more for
  * some when n does not divide B), and long and short samples are spread evenly.
  *   lengths      [B] int64, device; each in [0, max_len] (max_len: host value that sizes the sort; a length
  *                outside is reported as FS_ERANGE by fs_check_async)

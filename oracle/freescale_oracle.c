@@ -279,8 +279,9 @@ int fso_rowwise_adagrad_update(void *table, int dt, float *state, int64_t num_ro
 /* ---- O7: FBS partitioner --------------------------------------------------------------------- */
 /* Samples are sorted by length (ascending; equal lengths keep their sample order) and rank i of n takes
  * the sorted positions  i, 2n-1-i, 2n+i, 4n-1-i, 4n+i, ...  that exist: forth in even rounds of n, back
- * in odd ones.  (The paper prints the pattern as [i, 2n-i, 2n+i, 4n-i, ...], which would give position
- * 2n to rank 0 twice and position n to nobody; the zig-zag it describes is the one above.)
+ * in odd ones.  (The index list printed in Section 4.1 starts its backward rounds one position too far:
+ * taken literally rank 0 would get position 2n twice and nobody position n; the zig-zag the section
+ * describes in words is the one above.)
  * sample_of [B]: the samples of rank 0 in the order they were dealt, then those of rank 1, ...;
  * rank_offsets [n+1]: where each rank's samples start in sample_of. */
 typedef struct { int64_t len; int64_t idx; } lenidx;
@@ -321,8 +322,8 @@ int fso_partition_fbs(const int64_t *lengths, int64_t B, int32_t n_ranks, int32_
 /* Samples sorted as for FBS.  weight_of_len[L] >= 0 is the weight of a sample of length L (the caller tabulates
  * its L^alpha, scaled to integers).  With W the total weight and w_before(s) the weight of the sorted
  * positions before s, position s goes to rank min(n-1, floor(n * w_before(s) / W)) - every rank takes the
- * run of samples whose starts fall into its n-th of the total weight (the paper asks for n runs of
- * "approximately equivalent total weight" and does not state the rule; this one keeps every rank within one
+ * run of samples whose starts fall into its n-th of the total weight (Section 4.1 asks for n runs whose
+ * summed weights are about equal and does not state the rule; this one keeps every rank within one
  * sample's weight of W/n).  W == 0: everything goes to rank 0.
  * sample_of [B]: the sorted order; rank_offsets [n+1]: where each rank's run starts. */
 int fso_partition_vbs(const int64_t *lengths, int64_t B, const int64_t *weight_of_len, int64_t max_len,

@@ -283,6 +283,15 @@ int fs_check_async(fs_ctx *ctx, fs_stream stream) {
     FS_HIP(ctx, hipMemcpy(flags, ctx->d_flags, sizeof(flags), hipMemcpyDeviceToHost));
     if (flags[0] == 0) return FS_OK;
     FS_HIP(ctx, hipMemset(ctx->d_flags, 0, sizeof(flags)));
+    if (flags[0] & kFlagInternal) {
+        // a fused pass that met an inconsistent class order left cut segments half counted in: the arrival
+        // counters must stand at zero again before the next pass (every stream is idle here)
+        const size_t bytes = ((size_t)ceil_div(ctx->max_ids, kFusedMinChunk) + 2) * sizeof(int);
+        for (int k = 0; k < 2; ++k) {
+            FS_HIP(ctx, hipMemset(ctx->fcounters[k], 0, bytes));
+            FS_HIP(ctx, hipMemset(ctx->fcounters_sup[k], 0, bytes));
+        }
+    }
     snprintf(ctx->err, sizeof(ctx->err), "device flags 0x%x:%s%s%s", flags[0],
              (flags[0] & kFlagRowRange) ? " row id out of range" : "",
              (flags[0] & kFlagOffsets) ? " malformed offsets" : "", (flags[0] & kFlagInternal) ? " internal" : "");

@@ -53,6 +53,40 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
 }
 
 
+// ---- scans shared by the index kernels ----------------------------------------------------------------
+// inclusive scan of one value per lane over the wavefront
+template <typename T>
+__device__ __forceinline__ T wave_inclusive_scan(T v) {
+    const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const T t = __shfl_up(v, d, kWave);
+        if (lane >= d) v += t;
+    }
+    return v;
+}
+
+// exclusive scan of one value per thread over a workgroup of kScanThreads threads; the total is returned
+// to all threads.  `sh` holds kScanThreads / kWave values.  Contains two barriers.
+template <typename T>
+__device__ __forceinline__ T block_exclusive_scan(T v, T *sh, T &total) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = threadIdx.x / kWave;
+    const T inc = wave_inclusive_scan<T>(v);
+    if (lane == kWave - 1) sh[w] = inc;
+    __syncthreads();
+    T base = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < kScanThreads / kWave; ++i) {
+        const T x = sh[i];
+        if (i < w) base += x;
+        tot += x;
+    }
+    __syncthreads();
+    total = tot;
+    return base + inc - v;
+}
+
 // ---- optional workgroup trace (diagnostic builds with -DFS_TRACE only) ------------------------------
 // Every workgroup of a traced kernel appends {kind, workgroups of the launch << 32 | linear workgroup id, first and last reading
 // of the 100 MHz wall clock by its thread 0} to a buffer the host sets with fs_debug_trace.  The buffer

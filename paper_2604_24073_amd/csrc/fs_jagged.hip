@@ -62,35 +62,6 @@ int launch_partition_fbs(fs_ctx *ctx, const int64_t *lengths, int64_t B, int64_t
 }
 
 // ---- indexed permute ------------------------------------------------------------------------------------
-__device__ __forceinline__ int64_t wave_incl_scan_i64(int64_t v) {
-    const int lane = threadIdx.x & (kWave - 1);
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const int64_t t = __shfl_up(v, d, kWave);
-        if (lane >= d) v += t;
-    }
-    return v;
-}
-
-// exclusive scan of one value per thread over a kScanThreads block; `sh` holds kScanThreads/kWave values
-__device__ __forceinline__ int64_t block_excl_scan_i64(int64_t v, int64_t *sh, int64_t &total) {
-    const int lane = threadIdx.x & (kWave - 1);
-    const int w = threadIdx.x / kWave;
-    const int64_t inc = wave_incl_scan_i64(v);
-    if (lane == kWave - 1) sh[w] = inc;
-    __syncthreads();
-    int64_t base = 0, tot = 0;
-#pragma unroll
-    for (int i = 0; i < kScanThreads / kWave; ++i) {
-        const int64_t x = sh[i];
-        if (i < w) base += x;
-        tot += x;
-    }
-    __syncthreads();
-    total = tot;
-    return base + inc - v;
-}
-
 struct jagged_in {
     const int64_t *offsets;   // [B + 1]
     int64_t B, n_values;      // samples, elements behind them
@@ -119,7 +90,7 @@ __global__ __launch_bounds__(kScanThreads) void permute_tile_sum_kernel(const ja
 #pragma unroll
     for (int i = 0; i < kScanIpt; ++i) v += out_len(in, sample_of, k0 + i, n_out, bad);
     int64_t total;
-    (void)block_excl_scan_i64(v, sh, total);
+    (void)block_exclusive_scan<int64_t>(v, sh, total);
     if (threadIdx.x == 0) tile_sum[blockIdx.x] = total;
     if (bad) atomicOr(flags, kFlagOffsets);
 }
@@ -134,7 +105,7 @@ __global__ __launch_bounds__(kScanThreads) void permute_offsets_kernel(const jag
     int64_t before = 0;
     for (int t = threadIdx.x; t < (int)blockIdx.x; t += kScanThreads) before += tile_sum[t];
     int64_t tile_base;
-    (void)block_excl_scan_i64(before, sh, tile_base);
+    (void)block_exclusive_scan<int64_t>(before, sh, tile_base);
     const int64_t k0 = (int64_t)blockIdx.x * kScanTile + threadIdx.x * kScanIpt;
     bool bad = false;
     int64_t len[kScanIpt], v = 0;
@@ -144,7 +115,7 @@ __global__ __launch_bounds__(kScanThreads) void permute_offsets_kernel(const jag
         v += len[i];
     }
     int64_t tile_total;
-    int64_t run = tile_base + block_excl_scan_i64(v, sh, tile_total);
+    int64_t run = tile_base + block_exclusive_scan<int64_t>(v, sh, tile_total);
 #pragma unroll
     for (int i = 0; i < kScanIpt; ++i) {
         if (k0 + i < n_out) out_offsets[k0 + i] = run;
@@ -332,7 +303,7 @@ __global__ __launch_bounds__(kScanThreads) void vbs_tile_sum_kernel(const int64_
 #pragma unroll
     for (int i = 0; i < kScanIpt; ++i) v += vbs_weight(lengths, sorted, weight_of_len, max_len, s0 + i, B, bad);
     int64_t total;
-    (void)block_excl_scan_i64(v, sh, total);
+    (void)block_exclusive_scan<int64_t>(v, sh, total);
     if (threadIdx.x == 0) tile_sum[blockIdx.x] = total;
     if (bad) atomicOr(flags, kFlagRowRange);
 }
@@ -361,8 +332,8 @@ __global__ __launch_bounds__(kScanThreads) void vbs_cut_kernel(const int64_t *__
         if (t < (int)blockIdx.x) mine += v;
     }
     int64_t tile_base, total;
-    (void)block_excl_scan_i64(mine, sh, tile_base);
-    (void)block_excl_scan_i64(all, sh, total);
+    (void)block_exclusive_scan<int64_t>(mine, sh, tile_base);
+    (void)block_exclusive_scan<int64_t>(all, sh, total);
     if (total < 0 || total > INT64_MAX / n) {              // n * w_before would not fit: refuse, one rank takes all
         if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(flags, kFlagRowRange);
         total = 0;
@@ -377,7 +348,7 @@ __global__ __launch_bounds__(kScanThreads) void vbs_cut_kernel(const int64_t *__
     }
     const int64_t w_prev = vbs_weight(lengths, sorted, weight_of_len, max_len, s0 - 1, B, bad);
     int64_t tile_total;
-    int64_t before = tile_base + block_excl_scan_i64(v, sh, tile_total);
+    int64_t before = tile_base + block_exclusive_scan<int64_t>(v, sh, tile_total);
     // rank of the position before mine (-1 before the first: rank 0 starts at position 0)
     int64_t r_prev = s0 > 0 ? vbs_rank(before - w_prev, total, n) : -1;
 #pragma unroll

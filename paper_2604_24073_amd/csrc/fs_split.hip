@@ -14,34 +14,6 @@ namespace fs {
 
 constexpr int kSplitWindow = 4096;       // elements of the other list staged in LDS (32 KB)
 
-__device__ __forceinline__ int wave_incl_scan_i(int v) {
-    const int lane = threadIdx.x & (kWave - 1);
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const int t = __shfl_up(v, d, kWave);
-        if (lane >= d) v += t;
-    }
-    return v;
-}
-
-__device__ __forceinline__ int block_excl_scan_i(int v, int *sh, int &total) {
-    const int lane = threadIdx.x & (kWave - 1);
-    const int w = threadIdx.x / kWave;
-    const int inc = wave_incl_scan_i(v);
-    if (lane == kWave - 1) sh[w] = inc;
-    __syncthreads();
-    int base = 0, tot = 0;
-#pragma unroll
-    for (int i = 0; i < kScanThreads / kWave; ++i) {
-        const int x = sh[i];
-        if (i < w) base += x;
-        tot += x;
-    }
-    __syncthreads();
-    total = tot;
-    return base + inc - v;
-}
-
 // number of elements of a[0, n) that are < key; executed by one whole wavefront (64-ary search)
 __device__ __forceinline__ int wave_lower_bound(const int64_t *__restrict__ a, int n, int64_t key) {
     const int lane = threadIdx.x & (kWave - 1);
@@ -59,7 +31,8 @@ __device__ __forceinline__ int wave_lower_bound(const int64_t *__restrict__ a, i
 }
 
 // number of entries of a[0, n) that are <= key; executed by one whole wavefront (64-ary search)
-__device__ __forceinline__ int wave_upper_bound_i32(const int32_t *__restrict__ a, int n, int key) {
+template <typename T>
+__device__ __forceinline__ int wave_upper_bound(const T *__restrict__ a, int n, T key) {
     const int lane = threadIdx.x & (kWave - 1);
     int lo = 0, hi = n;                      // a[i] <= key for i < lo, a[i] > key for i >= hi
     while (lo < hi) {
@@ -156,7 +129,9 @@ __global__ __launch_bounds__(kScanThreads) void split_flag_kernel(const split_de
     const int t_hi = (t_lo + kScanTile < n_mine) ? t_lo + kScanTile : n_mine;
     if (threadIdx.x < kWave) {
         const int j0 = wave_lower_bound(other, n_other, mine[t_lo]);
-        const int j1 = wave_lower_bound(other, n_other, mine[t_hi - 1] + 1);
+        // upper end: the entries <= the tile's last element (a search for "last + 1" would wrap around at the
+        // top of the ID range, which is legal when the table size is not given)
+        const int j1 = wave_upper_bound<int64_t>(other, n_other, mine[t_hi - 1]);
         if (threadIdx.x == 0) { win[0] = j0; win[1] = j1; }
     }
     __syncthreads();
@@ -179,7 +154,7 @@ __global__ __launch_bounds__(kScanThreads) void split_flag_kernel(const split_de
         }
     }
     int total;
-    (void)block_excl_scan_i(found, sh, total);
+    (void)block_exclusive_scan<int>(found, sh, total);
     if (threadIdx.x == 0) tile_cnt[blockIdx.x] = total;      // number of collisions in this tile
 }
 
@@ -209,7 +184,7 @@ __global__ __launch_bounds__(kScanThreads) void split_compact_kernel(const split
     int before = 0;
     for (int t = threadIdx.x; t < tile; t += kScanThreads) before += tile_cnt[first + t];
     int found_before;
-    (void)block_excl_scan_i(before, sh, found_before);
+    (void)block_exclusive_scan<int>(before, sh, found_before);
 
     const int64_t *mine = side_t ? u_t : u_t1;
     const uint8_t *flag = side_t ? flag_t : flag_t1;
@@ -224,7 +199,7 @@ __global__ __launch_bounds__(kScanThreads) void split_compact_kernel(const split
         found += f[i] ? 1 : 0;
     }
     int tile_total;
-    int r_found = found_before + block_excl_scan_i(found, sh, tile_total);   // collisions before p0
+    int r_found = found_before + block_exclusive_scan<int>(found, sh, tile_total);   // collisions before p0
 #pragma unroll
     for (int i = 0; i < kScanIpt; ++i) {
         const int p = p0 + i;
@@ -255,8 +230,8 @@ __global__ __launch_bounds__(kScanThreads) void split_compact_kernel(const split
             ex_len += f[i] ? 0 : len[i];
         }
         int co_total, ex_total;
-        int co_before = block_excl_scan_i(co_len, sh, co_total);
-        int ex_before = block_excl_scan_i(ex_len, sh, ex_total);
+        int co_before = block_exclusive_scan<int>(co_len, sh, co_total);
+        int ex_before = block_exclusive_scan<int>(ex_len, sh, ex_total);
 #pragma unroll
         for (int i = 0; i < kScanIpt; ++i) {
             const int p = p0 + i;
@@ -310,7 +285,7 @@ __global__ __launch_bounds__(kScanThreads) void class_scatter_kernel(const class
         // the row of a sorted position q: the last slot whose segment starts at or before q
         const int w = threadIdx.x / kWave;
         int k = 0;
-        if (qa < n && n_u > 0) k = wave_upper_bound_i32(seg_offsets, n_u + 1, w == 0 ? qa : qb) - 1;
+        if (qa < n && n_u > 0) k = wave_upper_bound<int32_t>(seg_offsets, n_u + 1, w == 0 ? qa : qb) - 1;
         k = k < 0 ? 0 : (k > n_u - 1 ? n_u - 1 : k);
         if ((threadIdx.x & (kWave - 1)) == 0) win[w] = k;
     }
@@ -329,7 +304,7 @@ __global__ __launch_bounds__(kScanThreads) void class_scatter_kernel(const class
             const int t = t0 + threadIdx.x;
             const int v = (t < tiles_t) ? tile_len[c * tiles_t + t] : 0;
             int total;
-            const int before = block_excl_scan_i(v, sh, total);
+            const int before = block_exclusive_scan<int>(v, sh, total);
             if (t < tiles_t) tile_base[c * tiles_t + t] = carry + before;
             carry += total;
         }

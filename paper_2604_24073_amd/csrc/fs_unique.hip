@@ -18,37 +18,6 @@
 
 namespace fs {
 
-// ---- small block-scan helper (kScanThreads threads) -----------------------------------------
-__device__ __forceinline__ int wave_inclusive_scan(int v) {
-    const int lane = threadIdx.x & (kWave - 1);
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const int t = __shfl_up(v, d, kWave);
-        if (lane >= d) v += t;
-    }
-    return v;
-}
-
-// exclusive scan of one int per thread over a kScanThreads block; total returned to all threads.
-// `sh` must hold kScanThreads/kWave ints.  Contains two barriers.
-__device__ __forceinline__ int block_exclusive_scan(int v, int *sh, int &total) {
-    const int lane = threadIdx.x & (kWave - 1);
-    const int w = threadIdx.x / kWave;
-    const int inc = wave_inclusive_scan(v);
-    if (lane == kWave - 1) sh[w] = inc;
-    __syncthreads();
-    int base = 0, tot = 0;
-#pragma unroll
-    for (int i = 0; i < kScanThreads / kWave; ++i) {
-        const int x = sh[i];
-        if (i < w) base += x;
-        tot += x;
-    }
-    __syncthreads();
-    total = tot;
-    return base + inc - v;
-}
-
 // ---- one dedup of a batch, as the kernels see it ----------------------------------------------------
 struct unique_dev_job {
     const int64_t *ids;

@@ -168,6 +168,23 @@ def test_split_degenerate(ctx):
     check_split(ctx, np.empty(0, dtype=np.int64), np.empty(0, dtype=np.int64))
 
 
+@pytest.mark.parametrize("n_t", [5, 1024, 1025, 3000])
+def test_split_at_the_top_of_the_id_range(ctx, n_t):
+    """Table size not given: IDs run up to 2^63 - 1.  The largest IDs are the last elements of the last tile
+    of either list (a tile is 1024 rows), where the window search must not step past the largest ID."""
+    top = 2**63 - 1
+    rng = np.random.default_rng(n_t)
+    low = np.unique(rng.integers(0, 2**62, size=n_t, dtype=np.int64))[:max(n_t - 4, 0)]
+    u_t = np.concatenate([low, np.array([top - 5, top - 2, top - 1, top], dtype=np.int64)])[-n_t:]
+    u_t1 = np.concatenate([low[::2], np.array([top - 4, top - 2, top], dtype=np.int64)])
+    check_split(ctx, u_t, u_t1)
+    check_split(ctx, u_t1, u_t)
+    check_split(ctx, u_t, u_t)
+    # and through the dedup: 63-bit keys with the largest values present
+    ids = np.concatenate([u_t[-3:], u_t[rng.integers(0, len(u_t), size=4000)], np.array([top, top], dtype=np.int64)])
+    check_unique(ctx, ids, 0)
+
+
 # ------------------------------------------------------------------------------------ reduce
 def check_reduce(ctx, ids, grads, num_rows):
     lay = O.unique_ids(ids, num_rows)

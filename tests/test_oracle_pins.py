@@ -83,6 +83,22 @@ def test_unique_full_64bit_keys():
     assert r["inverse"].tolist() == [3, 1, 2, 1, 3, 0]
 
 
+def test_unique_and_split_at_the_top_of_the_id_range():
+    """IDs up to 2^63 - 1 are legal when the table size is not given: brute force on both operations."""
+    top = 2**63 - 1
+    a = np.array([top, 7, top - 1, top, top - 3, 7], dtype=np.int64)
+    b = np.array([top - 1, top - 2, top, 3], dtype=np.int64)
+    ra, rb = O.unique_ids(a, 0), O.unique_ids(b, 0)
+    ua, sa, pa, ia = brute_unique(a)
+    assert ra["unique"].tolist() == ua == [7, top - 3, top - 1, top]
+    assert ra["seg_offsets"].tolist() == sa and ra["perm"].tolist() == pa and ra["inverse"].tolist() == ia
+    sp = O.collision_split(ra["unique"], rb["unique"])
+    co, ex, exn = brute_split(ra["unique"], rb["unique"])
+    assert list(zip(sp["co"].tolist(), sp["co_slot"].tolist())) == co == [(top - 1, 2), (top, 3)]
+    assert list(zip(sp["ex"].tolist(), sp["ex_slot"].tolist())) == ex
+    assert list(zip(sp["ex_next"].tolist(), sp["ex_next_slot"].tolist())) == exn == [(3, 0), (top - 2, 1)]
+
+
 def test_unique_rejects_out_of_range():
     with pytest.raises(O.OracleError) as e:
         O.unique_ids(np.array([1, 7, 3]), 7)
