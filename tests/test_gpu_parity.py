@@ -398,6 +398,60 @@ def test_fused_pass_long_segments_and_aligned_cuts(ctx, dim, dtype):
     check_fused(ctx, rng, ids, nxt, rows, dim, dtype, n_passes=3)
 
 
+def exact_sum_grads(rng, n, dim):
+    """Gradients whose sums are exact in any order: multiples of 2^-4 in [-4, 4].  A sum over fewer than 2^13
+    occurrences has at most 19 significant bits, its square 38, the sum of 256 squares 46: fp64 holds all of
+    them exactly and the fp32 sum is exact too, so the order in which a kernel adds cannot show."""
+    return (rng.integers(-64, 65, size=(n, dim)) / 16.0).astype(np.float32)
+
+
+@pytest.mark.parametrize("dim,dtype", [(128, "f32"), (64, "f32"), (20, "f32"), (256, "f32"),
+                                       (128, "bf16"), (256, "bf16"), (72, "bf16")])
+@pytest.mark.parametrize("shape", ["one_occurrence_per_row", "long_and_cut_segments"])
+def test_update_is_bit_exact_where_the_sums_are_exact(ctx, dim, dtype, shape):
+    """Where the summed gradient does not depend on the order of addition, kernel and oracle do the same IEEE
+    operations (fp64 sum of squares / dim rounded once, fp32 add, correctly rounded sqrt and divide, one
+    rounding per product and difference, no contraction, round-to-nearest-even to bf16): table and state must
+    agree bit for bit - for the stand-alone operations, for the record path of the fused pass (rows with one
+    occurrence) and for its position-cut path (rows with thousands, pieces added by the last arriver)."""
+    rng = np.random.default_rng(dim + len(shape))
+    rows = 20_000
+    if shape == "one_occurrence_per_row":
+        ids = rng.permutation(rows)[:6000].astype(np.int64)
+        nxt = np.concatenate([ids[::3], rng.permutation(rows)[:500]]).astype(np.int64)
+    else:
+        ids = np.concatenate([np.full(6000, 7), np.full(64, 8), np.full(128, 9), np.arange(100, 300),
+                              np.full(63, 10), np.full(1, 11), np.full(2500, 12), np.arange(300, 364),
+                              np.full(9, 13), np.full(8, 14)]).astype(np.int64)
+        ids = ids[rng.permutation(len(ids))]
+        nxt = np.array([7, 9, 12, 13, 150, 151, 152, 320, 499], dtype=np.int64)
+    table = rand_table(rng, rows, dim, dtype)
+    state = (rng.random(rows) * 0.1).astype(np.float32)
+    d_fused, s_fused = table_to_dev(table), dev(state)       # fs_reduce_update_class, both classes
+    d_alone, s_alone = table_to_dev(table), dev(state)       # fs_segment_reduce_grads + fs_rowwise_adagrad_update
+    t_ref, s_ref = table.copy(), state.copy()
+    lay_o = O.unique_ids(ids, rows)
+    u = len(lay_o["unique"])
+    lay, sp = gpu_layout_and_classes(ctx, ids, nxt, rows)
+    for _ in range(2):                                       # twice: the second step starts from a grown state
+        grads = exact_sum_grads(rng, len(ids), dim)
+        red_o = O.segment_reduce_grads(grads, lay_o["perm"], lay_o["seg_offsets"])
+        O.rowwise_adagrad_update(t_ref, s_ref, lay_o["unique"], np.arange(u, dtype=np.int32), red_o, 0.02, 1e-8)
+        d_grads = dev(grads)
+        reduced = torch.full((len(ids), dim), float("nan"), dtype=torch.float32, device="cuda")
+        for cls in (0, 1):
+            fs.fs_reduce_update_class(ctx, cls, d_fused, s_fused, 0.02, 1e-8, d_grads, lay, sp, reduced)
+        red_alone = fs.fs_segment_reduce_grads(ctx, d_grads, lay["perm"], lay["seg_offsets"], lay["n_unique"])
+        fs.fs_rowwise_adagrad_update(ctx, d_alone, s_alone, lay["unique"], dev(np.arange(u, dtype=np.int32)),
+                                     lay["n_unique"], u, red_alone, 0.02, 1e-8)
+        assert fs.fs_check_async(ctx) == fs.FS_OK
+        assert reduced[:u].cpu().numpy().tobytes() == red_o.tobytes()
+        assert red_alone[:u].cpu().numpy().tobytes() == red_o.tobytes()
+    for what, d_t, d_s in (("fused pass", d_fused, s_fused), ("stand-alone operations", d_alone, s_alone)):
+        assert d_s.cpu().numpy().tobytes() == s_ref.tobytes(), f"{what}: Adagrad state"
+        assert table_to_host(d_t).tobytes() == t_ref.tobytes(), f"{what}: rows"
+
+
 def test_fused_pass_without_lookahead_and_with_full_overlap(ctx):
     rng = np.random.default_rng(10)
     ids = zipf_ids(rng, 5000, 800, a=1.1)
