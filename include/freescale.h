@@ -61,7 +61,8 @@ enum {
 int fs_ctx_create(fs_ctx **out, int device, int64_t max_ids, int32_t max_dim);
 int fs_ctx_destroy(fs_ctx *ctx);
 
-/* Text of the last host-visible error on this context ("" if none).  Never NULL. */
+/* Text of the last host-visible error on this context ("" if none).  Never NULL.  ctx == NULL: the text of
+ * the calling thread's last failed call that takes no context. */
 const char *fs_last_error(const fs_ctx *ctx);
 
 /* Waits for `stream`, then reports and clears the device-side error flags:
@@ -112,6 +113,24 @@ int fs_collision_split(fs_ctx *ctx, const int64_t *u_t, const int64_t *n_t_dev,
                        const int64_t *u_t1, const int64_t *n_t1_dev, int64_t cap_t, int64_t cap_t1,
                        int64_t *co, int32_t *co_slot, int64_t *ex, int32_t *ex_slot,
                        int64_t *ex_next, int32_t *ex_next_slot, int64_t *counts_dev, fs_stream stream);
+
+/* fs_collision_split for callers that cannot allocate device memory or create a context where they stand:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (no
+ * context), same outputs bit for bit.  The membership flags and per-tile counts that fs_collision_split keeps
+ * in the context's workspace live in a fixed device array of the library instead (about 2.1 MB per GPU, held
+ * until the process ends); the call allocates and frees nothing.  Works on the CURRENT device, which must
+ * own every pointer.
+ *   cap_t, cap_t1 <= FS_STATIC_SPLIT_MAX_ROWS, else FS_ENOMEM and nothing is enqueued (use the context form).
+ *   Every call on a GPU shares that GPU's array: calls whose stream work may overlap on one GPU race with
+ *   each other - order them (one stream, or events).  Nothing in the array has to be cleared between calls.
+ *   The array's address is looked up once per GPU, by fs_ctx_create for its device or else by the first call
+ *   here on that GPU; make that first call outside a capture.
+ * Errors are returned as status codes; fs_last_error(NULL) has the text of the calling thread's last one. */
+#define FS_STATIC_SPLIT_MAX_ROWS (1 << 20)
+int fs_collision_split_static(const int64_t *u_t, const int64_t *n_t_dev, const int64_t *u_t1,
+                              const int64_t *n_t1_dev, int64_t cap_t, int64_t cap_t1, int64_t *co,
+                              int32_t *co_slot, int64_t *ex, int32_t *ex_slot, int64_t *ex_next,
+                              int32_t *ex_next_slot, int64_t *counts_dev, fs_stream stream);
 
 /* First half of update_embedding(I, G) of Algorithm 2: one summed gradient per distinct row,
  *   reduced[k, :] = sum over sorted positions p in [seg_offsets[k], seg_offsets[k+1]) of

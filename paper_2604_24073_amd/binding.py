@@ -85,6 +85,8 @@ def load_library() -> ctypes.CDLL:
                                                      c_vp, S]),
         "fs_collision_split": (ctypes.c_int, [c_vp, c_vp, c_vp, c_vp, c_vp, c_i64, c_i64, c_vp, c_vp, c_vp, c_vp,
                                               c_vp, c_vp, c_vp, S]),
+        "fs_collision_split_static": (ctypes.c_int, [c_vp, c_vp, c_vp, c_vp, c_i64, c_i64, c_vp, c_vp, c_vp, c_vp,
+                                                     c_vp, c_vp, c_vp, S]),
         "fs_segment_reduce_grads": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i32, c_vp, c_vp, c_vp, c_vp, c_vp, S]),
         "fs_rowwise_adagrad_update": (ctypes.c_int, [c_vp, c_vp, ctypes.c_int, c_vp, c_i64, c_i32, c_vp, c_vp, c_vp,
                                                      c_i64, c_vp, c_f, c_f, S]),
@@ -345,6 +347,24 @@ def fs_collision_split(ctx: Context, u_t: Optional[torch.Tensor], n_t_dev: Optio
                                     _ptr(out["ex_next"]), _ptr(out["ex_next_slot"]), _ptr(out["counts"]),
                                     _stream(stream))
     ctx.check(rc, "fs_collision_split")
+    return out
+
+
+FS_STATIC_SPLIT_MAX_ROWS = 1 << 20
+
+
+def fs_collision_split_static(u_t: Optional[torch.Tensor], n_t_dev: Optional[torch.Tensor],
+                              u_t1: Optional[torch.Tensor], n_t1_dev: Optional[torch.Tensor], cap_t: int, cap_t1: int,
+                              out: Dict[str, torch.Tensor], stream=None) -> Dict[str, torch.Tensor]:
+    """The split without a context and without any allocation: `out` (a bundle as fs_collision_split returns
+    it) is the caller's."""
+    lib = load_library()
+    rc = lib.fs_collision_split_static(_ptr(u_t), _ptr(n_t_dev), _ptr(u_t1), _ptr(n_t1_dev), cap_t, cap_t1,
+                                       _ptr(out["co"]), _ptr(out["co_slot"]), _ptr(out["ex"]), _ptr(out["ex_slot"]),
+                                       _ptr(out["ex_next"]), _ptr(out["ex_next_slot"]), _ptr(out["counts"]),
+                                       _stream(stream))
+    if rc != FS_OK:
+        raise FreeScaleError(rc, "fs_collision_split_static", lib.fs_last_error(None).decode())
     return out
 
 

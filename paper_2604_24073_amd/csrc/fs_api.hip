@@ -103,6 +103,17 @@ struct fs_host {
     int x_turn = 0;
 };
 
+namespace fs {
+char *static_err_buf() {
+    static thread_local char buf[256] = "";
+    return buf;
+}
+int set_static_err(int code, const char *msg) {
+    snprintf(static_err_buf(), 256, "%s", msg);
+    return code;
+}
+}  // namespace fs
+
 namespace {
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -206,6 +217,7 @@ int fs_ctx_create(fs_ctx **out, int device, int64_t max_ids, int32_t max_dim) {
         delete c;
         return FS_EHIP;
     }
+    (void)static_split_prepare(device);      // fs_collision_split_static's array on this GPU: looked up here, or at its first call
     carve(c, nullptr, &c->slab_bytes);
     if (hipMalloc(&c->slab, c->slab_bytes) != hipSuccess) {
         (void)hipGetLastError();
@@ -267,7 +279,7 @@ int fs_ctx_destroy(fs_ctx *c) {
     return FS_OK;
 }
 
-const char *fs_last_error(const fs_ctx *ctx) { return ctx ? ctx->err : "null context"; }
+const char *fs_last_error(const fs_ctx *ctx) { return ctx ? ctx->err : static_err_buf(); }
 
 size_t fs_ctx_workspace_bytes(const fs_ctx *ctx) { return ctx ? ctx->slab_bytes : 0; }
 

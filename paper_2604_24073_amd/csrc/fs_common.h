@@ -207,6 +207,12 @@ inline int set_err(fs_ctx *ctx, int code, const char *msg) {
     return code;
 }
 
+// error text of the calls that take no context (kept per calling thread; fs_last_error(NULL) returns it)
+char *static_err_buf();
+int set_static_err(int code, const char *msg);
+// looks up this GPU's copy of the fixed scratch array of fs_collision_split_static (`device` must be current)
+int static_split_prepare(int device);
+
 inline int hip_err(fs_ctx *ctx, hipError_t e, const char *what) {
     if (ctx) snprintf(ctx->err, sizeof(ctx->err), "%s: %s", what, hipGetErrorString(e));
     return FS_EHIP;

@@ -7,6 +7,8 @@
 // binary search only if the window does not fit).  Membership flags are counted per tile and a
 // second launch compacts with tile prefixes.  The list lengths are device scalars; the launch is
 // sized by the host-side caps and tiles past the end do nothing.
+#include <mutex>
+
 #include "fs_common.h"
 #include "fs_device.h"
 
@@ -478,4 +480,90 @@ int launch_class_order(fs_ctx *ctx, const int32_t *perm, const int64_t *n_unique
 
 FS_TRACE_SETTER(split)
 
+// ---- the collision split for callers that cannot allocate ----------------------------------------------------
+// Same two kernels as launch_split_batch; the membership flags and per-tile counts live in a fixed device array
+// instead of a context's slab.
+constexpr int64_t kStaticSplitRows = FS_STATIC_SPLIT_MAX_ROWS;
+constexpr size_t kStaticFlagBytes = ((size_t)kStaticSplitRows + 16 + 255) / 256 * 256;
+constexpr size_t kStaticTiles = (size_t)(kStaticSplitRows / kScanTile) + 2;
+constexpr size_t kStaticCntBytes = (2 * kStaticTiles * sizeof(int32_t) + 255) / 256 * 256;
+constexpr size_t kStaticScratchBytes = 2 * kStaticFlagBytes + kStaticCntBytes;
+static_assert(kStaticSplitRows % kScanTile == 0, "whole tiles");
+
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kStaticMaxDevices = 64;
+static std::mutex g_static_mu;
+static unsigned char *g_static_ptr[kStaticMaxDevices];      // device address of `scratch` on each GPU, once asked for
+
+// the address of this GPU's copy of `scratch` (each GPU holds its own); `device` must be current
+static hipError_t static_scratch_for(int device, unsigned char **out) {
+    std::lock_guard<std::mutex> lk(g_static_mu);
+    if (g_static_ptr[device] == nullptr) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (p == nullptr) return hipErrorInvalidSymbol;
+        g_static_ptr[device] = static_cast<unsigned char *>(p);
+    }
+    *out = g_static_ptr[device];
+    return hipSuccess;
+}
+
+int static_split_prepare(int device) {
+    if (device < 0 || device >= kStaticMaxDevices) return FS_EINVAL;
+    unsigned char *p = nullptr;
+    return static_scratch_for(device, &p) == hipSuccess ? FS_OK : FS_EHIP;
+}
+
 }  // namespace fs
+
+extern "C" int fs_collision_split_static(const int64_t *u_t, const int64_t *n_t_dev, const int64_t *u_t1,
+                                         const int64_t *n_t1_dev, int64_t cap_t, int64_t cap_t1, int64_t *co,
+                                         int32_t *co_slot, int64_t *ex, int32_t *ex_slot, int64_t *ex_next,
+                                         int32_t *ex_next_slot, int64_t *counts_dev, fs_stream stream) {
+    using namespace fs;
+    if (cap_t < 0 || cap_t1 < 0) return set_static_err(FS_EINVAL, "static split: negative capacity");
+    if (cap_t > kStaticSplitRows || cap_t1 > kStaticSplitRows)
+        return set_static_err(FS_ENOMEM, "static split: a list of more than FS_STATIC_SPLIT_MAX_ROWS rows does not fit "
+                                         "the fixed scratch array; use fs_collision_split with a context");
+    if (!counts_dev) return set_static_err(FS_EINVAL, "static split: null counts");
+    if (cap_t > 0 && !(u_t && n_t_dev && co && co_slot && ex && ex_slot))
+        return set_static_err(FS_EINVAL, "static split: null pointer (t side)");
+    if (cap_t1 > 0 && !(u_t1 && n_t1_dev && ex_next && ex_next_slot))
+        return set_static_err(FS_EINVAL, "static split: null pointer (t+1 side)");
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kStaticMaxDevices)
+        return set_static_err(FS_EHIP, "static split: no current device");
+    unsigned char *base = nullptr;
+    const hipError_t se = static_scratch_for(device, &base);
+    if (se != hipSuccess) return set_static_err(FS_EHIP, hipGetErrorString(se));
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    if (cap_t == 0 && cap_t1 == 0) {
+        hipLaunchKernelGGL(split_empty_kernel, dim3(1), dim3(1), 0, s, (const int64_t *)nullptr, (int64_t)0, counts_dev);
+    } else {
+        // Nothing has to start at zero: the flag launch writes every flag and every per-tile count that the
+        // compaction launch reads (tiles past the end of a list write a zero count).
+        split_dev_batch batch;
+        memset(&batch, 0, sizeof(batch));
+        split_dev_job &j = batch.j[0];
+        const int tiles_t = (int)ceil_div(cap_t, kScanTile);
+        j.u_t = u_t; j.n_t_dev = cap_t > 0 ? n_t_dev : nullptr;
+        j.u_t1 = u_t1; j.n_t1_dev = cap_t1 > 0 ? n_t1_dev : nullptr;
+        j.cap_t = cap_t; j.cap_t1 = cap_t1;
+        j.tiles_t = tiles_t > 0 ? tiles_t : 1;
+        j.tiles_t1 = (int)ceil_div(cap_t1, kScanTile);
+        j.flag_t = base;
+        j.flag_t1 = base + kStaticFlagBytes;
+        j.tile_cnt = reinterpret_cast<int32_t *>(base + 2 * kStaticFlagBytes);
+        j.co = co; j.co_slot = co_slot; j.ex = ex; j.ex_slot = ex_slot;
+        j.ex_next = ex_next; j.ex_next_slot = ex_next_slot; j.counts_dev = counts_dev;
+        j.seg_offsets_t = nullptr; j.cstart_local = nullptr; j.tile_len = nullptr; j.cidx = nullptr;
+        const dim3 grid((unsigned)(j.tiles_t + j.tiles_t1), 1u);
+        hipLaunchKernelGGL(split_flag_kernel, grid, dim3(kScanThreads), 0, s, batch);
+        hipLaunchKernelGGL(split_compact_kernel, grid, dim3(kScanThreads), 0, s, batch);
+    }
+    const hipError_t le = hipGetLastError();
+    if (le != hipSuccess) return set_static_err(FS_EHIP, hipGetErrorString(le));
+    return FS_OK;
+}

@@ -29,7 +29,16 @@ def test_version_and_null_context_are_errors_not_crashes():
     assert lib.fs_unique_ids(None, None, 0, 0, None, None, None, None, None, None) == fs.FS_EINVAL
     assert lib.fs_prioritized_step(None, None, None) == fs.FS_EINVAL
     assert lib.fs_ctx_destroy(None) == fs.FS_OK
-    assert lib.fs_last_error(None) == b"null context"
+    assert lib.fs_last_error(None) == b""                                         # no context-free call has failed yet
+    # the context-free split rejects what its fixed scratch array cannot hold before it touches the GPU
+    too_many = fs.FS_STATIC_SPLIT_MAX_ROWS + 1
+    assert lib.fs_collision_split_static(None, None, None, None, too_many, 0, None, None, None, None, None, None,
+                                         None, None) == fs.FS_ENOMEM
+    assert b"FS_STATIC_SPLIT_MAX_ROWS" in lib.fs_last_error(None)
+    assert lib.fs_collision_split_static(None, None, None, None, -1, 0, None, None, None, None, None, None,
+                                         None, None) == fs.FS_EINVAL
+    assert lib.fs_collision_split_static(None, None, None, None, 10, 0, None, None, None, None, None, None,
+                                         ctypes.c_void_p(8), None) == fs.FS_EINVAL   # null lists with cap_t > 0
     assert lib.fs_ctx_create(None, 0, 10, 64) == fs.FS_EINVAL
     h = ctypes.c_void_p()
     assert lib.fs_ctx_create(ctypes.byref(h), 0, 0, 64) == fs.FS_EINVAL          # max_ids < 1
