@@ -172,6 +172,23 @@ def gather_jagged_class(table: np.ndarray, values: np.ndarray, u_t: np.ndarray, 
     _check(rc, "fso_gather_jagged_class")
 
 
+def split_grads(grads: np.ndarray, values: np.ndarray, u_t1: np.ndarray) -> Dict[str, np.ndarray]:
+    """split(G, I_co, I_ex) of Algorithm 2's Backward: the gradient rows (batch order) of the occurrences whose
+    row is / is not in u_t1, with the occurrence numbers of both parts."""
+    grads = _c(grads, np.float32)
+    values, u_t1 = _c(values, np.int64), _c(u_t1, np.int64)
+    n, dim = grads.shape
+    assert values.shape[0] == n
+    co_i, ex_i = np.empty(max(n, 1), np.int32), np.empty(max(n, 1), np.int32)
+    g_co, g_ex = np.empty((max(n, 1), dim), np.float32), np.empty((max(n, 1), dim), np.float32)
+    counts = np.zeros(2, dtype=np.int64)
+    rc = lib().fso_split_grads(_p(grads), ctypes.c_int64(n), ctypes.c_int32(dim), _p(values), _p(u_t1),
+                               ctypes.c_int64(u_t1.shape[0]), _p(co_i), _p(g_co), _p(ex_i), _p(g_ex), _p(counts))
+    _check(rc, "fso_split_grads")
+    a, b = (int(x) for x in counts)
+    return {"co_index": co_i[:a].copy(), "g_co": g_co[:a].copy(), "ex_index": ex_i[:b].copy(), "g_ex": g_ex[:b].copy()}
+
+
 def partition_fbs(lengths: np.ndarray, n_ranks: int) -> Tuple[np.ndarray, np.ndarray]:
     """FBS partitioner: (sample_of [B] rank-major, rank_offsets [n_ranks + 1])."""
     lengths = _c(lengths, np.int64)

@@ -27,6 +27,9 @@
  *                              i), Backward returns the collision rows E_co^{i+1} as the priority
  *                              update leaves them, and merge() puts both into one input batch.
  *                              One call copies the occurrences of one of the two kinds of row.
+ *   fso_split_grads            split(G~^i, I~_co^i, I~_ex^i) at the start of Backward of Algorithm 2: the
+ *                              batch-major gradient rows separated into the collision part and the exclusive
+ *                              part, each in batch order.
  *   fso_partition_fbs          the Fixed Batch Size partitioner of Section 4.1 ("Partitioning
  *                              Algorithms"): samples sorted by UIH length, dealt to the ranks in a
  *                              zig-zag.
@@ -273,6 +276,39 @@ int fso_rowwise_adagrad_update(void *table, int dt, float *state, int64_t num_ro
             }
         }
     }
+    return FSO_OK;
+}
+
+/* ---- O6: split of the batch-major gradients ---------------------------------------------------- */
+/* Backward of Algorithm 2 begins with split(G~^i, I~_co^i, I~_ex^i): the gradient rows of the batch arrive in
+ * batch order, one row per occurrence, and are separated into the rows of collision occurrences and the rows of
+ * exclusive occurrences, each part keeping batch order.  (The collision part is what the exposed gradient
+ * AllToAll carries, the exclusive part travels with the deferred one.)  An occurrence j is a collision
+ * occurrence iff its row values[j] is a member of u_t1, the ascending distinct rows of the lookahead batch.
+ *   co_index [n_co], ex_index [n_ex]   the occurrence numbers of the two parts, ascending (I~_co^i, I~_ex^i)
+ *   g_co [n_co, dim], g_ex [n_ex, dim] the gradient rows in that order (G~_co^i, G~_ex^i)
+ *   counts = {n_co, n_ex} */
+int fso_split_grads(const float *grads, int64_t n, int32_t dim, const int64_t *values, const int64_t *u_t1,
+                    int64_t n_t1, int32_t *co_index, float *g_co, int32_t *ex_index, float *g_ex, int64_t *counts)
+{
+    if (n < 0 || n > INT32_MAX || dim <= 0 || n_t1 < 0) return FSO_EINVAL;
+    for (int64_t i = 1; i < n_t1; ++i) if (u_t1[i] <= u_t1[i - 1]) return FSO_EINVAL;
+    int64_t n_co = 0, n_ex = 0;
+    size_t row_bytes = (size_t)dim * sizeof(float);
+    for (int64_t j = 0; j < n; ++j) {
+        int64_t r = values[j];
+        int member = n_t1 > 0 && bsearch(&r, u_t1, (size_t)n_t1, sizeof(int64_t), cmp_i64) != NULL;
+        if (member) {
+            co_index[n_co] = (int32_t)j;
+            memcpy(g_co + (size_t)n_co * (size_t)dim, grads + (size_t)j * (size_t)dim, row_bytes);
+            ++n_co;
+        } else {
+            ex_index[n_ex] = (int32_t)j;
+            memcpy(g_ex + (size_t)n_ex * (size_t)dim, grads + (size_t)j * (size_t)dim, row_bytes);
+            ++n_ex;
+        }
+    }
+    counts[0] = n_co; counts[1] = n_ex;
     return FSO_OK;
 }
 

@@ -465,6 +465,52 @@ def test_fetching_exclusive_rows_before_the_deferred_update_is_detected():
 
 
 # ----------------------------------------------------------- FBS partitioner, indexed permute
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_split_grads_matches_list_filtering_and_keeps_the_row_sums(seed):
+    """split() of Algorithm 2's Backward against plain list filtering, and against what it is for: the summed
+    gradient of every row, taken from the part its row went to, equals the sum taken over the whole batch bit for
+    bit (each part keeps batch order, so the additions are the same ones)."""
+    rng = np.random.default_rng(100 + seed)
+    rows, n, dim = 40, int(rng.integers(1, 300)), 4 * int(rng.integers(1, 5))
+    values = rng.integers(0, rows, size=n).astype(np.int64)
+    nxt = np.unique(rng.integers(0, rows, size=int(rng.integers(0, 60)))).astype(np.int64)
+    grads = rng.standard_normal((n, dim)).astype(np.float32)
+    r = O.split_grads(grads, values, nxt)
+    members = set(int(x) for x in nxt)
+    co = [j for j in range(n) if int(values[j]) in members]
+    ex = [j for j in range(n) if int(values[j]) not in members]
+    assert r["co_index"].tolist() == co and r["ex_index"].tolist() == ex
+    assert r["g_co"].tobytes() == grads[co].tobytes() if co else r["g_co"].shape[0] == 0
+    assert r["g_ex"].tobytes() == grads[ex].tobytes() if ex else r["g_ex"].shape[0] == 0
+    # reduce(co part) and reduce(ex part) together are reduce(all)
+    lay = O.unique_ids(values, rows)
+    whole = O.segment_reduce_grads(grads, lay["perm"], lay["seg_offsets"])
+    seen = 0
+    for idx, g in ((r["co_index"], r["g_co"]), (r["ex_index"], r["g_ex"])):
+        if len(idx) == 0:
+            continue
+        lay_p = O.unique_ids(values[idx], rows)
+        red_p = O.segment_reduce_grads(g, lay_p["perm"], lay_p["seg_offsets"])
+        slot = np.searchsorted(lay["unique"], lay_p["unique"])
+        assert np.array_equal(lay["unique"][slot], lay_p["unique"])
+        assert red_p.tobytes() == whole[slot].tobytes()
+        seen += len(lay_p["unique"])
+    assert seen == lay["n_unique"]                       # every row is in exactly one part
+
+
+def test_split_grads_degenerate_cases():
+    grads = np.arange(12, dtype=np.float32).reshape(3, 4)
+    values = np.array([5, 2, 5], dtype=np.int64)
+    r = O.split_grads(grads, values, np.empty(0, np.int64))           # no lookahead batch: everything exclusive
+    assert r["co_index"].tolist() == [] and r["ex_index"].tolist() == [0, 1, 2] and r["g_ex"].tobytes() == grads.tobytes()
+    r = O.split_grads(grads, values, np.array([2, 5, 9], dtype=np.int64))   # everything collides
+    assert r["co_index"].tolist() == [0, 1, 2] and r["ex_index"].tolist() == [] and r["g_co"].tobytes() == grads.tobytes()
+    r = O.split_grads(grads, values, np.array([5], dtype=np.int64))
+    assert r["co_index"].tolist() == [0, 2] and r["ex_index"].tolist() == [1]
+    with pytest.raises(O.OracleError):
+        O.split_grads(grads, values, np.array([5, 2], dtype=np.int64))      # membership list not ascending
+
+
 def test_fbs_zigzag_matches_the_printed_pattern():
     want = {}
     with open(os.path.join(GOLDEN, "fbs_zigzag_pattern.txt")) as f:
