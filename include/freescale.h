@@ -325,6 +325,11 @@ typedef struct fs_step_args {
     /* output (OPTIONAL, may be NULL; needed by the two-part lookup): [n_t1] bytes, for every row of u_t1
      * 1 if it is a collision row (also in u_t), else 0; written with the split */
     uint8_t *co_flag_t1;
+    /* output (OPTIONAL, may be NULL): [n_t1] the IDs of the lookahead batch in ascending order, every occurrence
+     * listed (sorted_ids_t1[p] is the row of the occurrence perm_t1[p]); written with the layout of t+1.  Given,
+     * the lookup of the lookahead batch walks the batch row by row instead of occurrence by occurrence: all
+     * occurrences of a row are neighbours, so a row is fetched once however far apart its occurrences lie */
+    int64_t *sorted_ids_t1;
 } fs_step_args;
 
 /* Iteration t on one shard, scheduled as Section 3.2 prescribes (strict write-read ordering

@@ -41,6 +41,7 @@ class fs_step_args(ctypes.Structure):
         ("cperm", c_vp), ("cslot", c_vp), ("cstart", c_vp), ("class_pos_dev", c_vp), ("short_rec", c_vp),
         ("reduced", c_vp), ("emb_t1", c_vp),
         ("co_flag_t1", c_vp),
+        ("sorted_ids_t1", c_vp),
     ]
 
 
@@ -238,11 +239,14 @@ def fs_gather_jagged_class(ctx: Context, table: torch.Tensor, values: torch.Tens
     return out
 
 
-def fs_partition_fbs(ctx: Context, lengths: torch.Tensor, max_len: int, n_ranks: int, stream=None):
-    """(sample_of [B] int32, rank_offsets [n_ranks + 1] int64) of the FBS partitioner."""
+def fs_partition_fbs(ctx: Context, lengths: torch.Tensor, max_len: int, n_ranks: int, stream=None, out=None):
+    """(sample_of [B] int32, rank_offsets [n_ranks + 1] int64) of the FBS partitioner; `out`: the caller's pair."""
     B = lengths.numel()
-    sample_of = torch.empty(max(B, 1), dtype=torch.int32, device=lengths.device)
-    rank_offsets = torch.empty(n_ranks + 1, dtype=torch.int64, device=lengths.device)
+    if out is not None:
+        sample_of, rank_offsets = out
+    else:
+        sample_of = torch.empty(max(B, 1), dtype=torch.int32, device=lengths.device)
+        rank_offsets = torch.empty(n_ranks + 1, dtype=torch.int64, device=lengths.device)
     rc = ctx.lib.fs_partition_fbs(ctx.handle, _ptr(lengths), B, max_len, n_ranks, _ptr(sample_of), _ptr(rank_offsets),
                                   _stream(stream))
     ctx.check(rc, "fs_partition_fbs")
@@ -262,13 +266,17 @@ def fs_partition_vbs(ctx: Context, lengths: torch.Tensor, weight_of_len: torch.T
 
 
 def fs_jagged_indexed_permute(ctx: Context, values: torch.Tensor, offsets: torch.Tensor, sample_of: torch.Tensor,
-                              cap_out: int, stream=None):
-    """(out_values [cap_out, ...], out_offsets [n_out + 1]); values is [n] or [n, width], any 4- or 8-byte dtype."""
+                              cap_out: int, stream=None, out=None):
+    """(out_values [cap_out, ...], out_offsets [n_out + 1]); values is [n] or [n, width], any 4- or 8-byte dtype.
+    `out`: the caller's (out_values, out_offsets)."""
     n_values = values.shape[0]
     elem = _elem_bytes(values)
-    out = torch.empty((cap_out,) + tuple(values.shape[1:]), dtype=values.dtype, device=values.device)
     n_out = sample_of.numel()
-    out_offsets = torch.empty(n_out + 1, dtype=torch.int64, device=values.device)
+    if out is not None:
+        out, out_offsets = out
+    else:
+        out = torch.empty((cap_out,) + tuple(values.shape[1:]), dtype=values.dtype, device=values.device)
+        out_offsets = torch.empty(n_out + 1, dtype=torch.int64, device=values.device)
     rc = ctx.lib.fs_jagged_indexed_permute(ctx.handle, _ptr(values), n_values, elem, _ptr(offsets), offsets.numel() - 1,
                                            _ptr(sample_of), n_out, _ptr(out), cap_out, _ptr(out_offsets),
                                            _stream(stream))
@@ -283,8 +291,9 @@ def _elem_bytes(values: torch.Tensor) -> int:
     return elem
 
 
-def fs_jagged_keyed_transpose(ctx: Context, values: torch.Tensor, offsets: torch.Tensor, F: int, B: int, stream=None):
-    out, out_offsets = torch.empty_like(values), torch.empty_like(offsets)
+def fs_jagged_keyed_transpose(ctx: Context, values: torch.Tensor, offsets: torch.Tensor, F: int, B: int, stream=None,
+                              out=None):
+    out, out_offsets = out if out is not None else (torch.empty_like(values), torch.empty_like(offsets))
     rc = ctx.lib.fs_jagged_keyed_transpose(ctx.handle, _ptr(values), values.shape[0], _elem_bytes(values), _ptr(offsets),
                                            F, B, _ptr(out), _ptr(out_offsets), _stream(stream))
     ctx.check(rc, "fs_jagged_keyed_transpose")
@@ -292,10 +301,14 @@ def fs_jagged_keyed_transpose(ctx: Context, values: torch.Tensor, offsets: torch
 
 
 def fs_jagged_ranged_dispatch(ctx: Context, values: torch.Tensor, offsets: torch.Tensor, F: int, B: int,
-                              rank_offsets: torch.Tensor, stream=None):
-    out, out_offsets = torch.empty_like(values), torch.empty_like(offsets)
+                              rank_offsets: torch.Tensor, stream=None, out=None):
+    """`out`: the caller's (out_values, out_offsets, splits [n_ranks])."""
     n_ranks = rank_offsets.numel() - 1
-    splits = torch.empty(max(n_ranks, 1), dtype=torch.int64, device=values.device)
+    if out is not None:
+        out, out_offsets, splits = out
+    else:
+        out, out_offsets = torch.empty_like(values), torch.empty_like(offsets)
+        splits = torch.empty(max(n_ranks, 1), dtype=torch.int64, device=values.device)
     rc = ctx.lib.fs_jagged_ranged_dispatch(ctx.handle, _ptr(values), values.shape[0], _elem_bytes(values), _ptr(offsets),
                                            F, B, _ptr(rank_offsets), n_ranks, _ptr(out), _ptr(out_offsets), _ptr(splits),
                                            _stream(stream))
@@ -304,8 +317,8 @@ def fs_jagged_ranged_dispatch(ctx: Context, values: torch.Tensor, offsets: torch
 
 
 def fs_jagged_ranged_combine(ctx: Context, values: torch.Tensor, offsets: torch.Tensor, F: int, B: int,
-                             rank_offsets: torch.Tensor, stream=None):
-    out, out_offsets = torch.empty_like(values), torch.empty_like(offsets)
+                             rank_offsets: torch.Tensor, stream=None, out=None):
+    out, out_offsets = out if out is not None else (torch.empty_like(values), torch.empty_like(offsets))
     rc = ctx.lib.fs_jagged_ranged_combine(ctx.handle, _ptr(values), values.shape[0], _elem_bytes(values), _ptr(offsets),
                                           F, B, _ptr(rank_offsets), rank_offsets.numel() - 1, _ptr(out),
                                           _ptr(out_offsets), _stream(stream))
@@ -526,8 +539,9 @@ def fs_stream_copy(ctx: Context, src: torch.Tensor, dst: torch.Tensor, stream=No
 
 
 # ---- buffer bundles for the whole-iteration call (allocation only) -----------------------------
-def alloc_layout(n: int, device, inverse: bool = True) -> Dict[str, torch.Tensor]:
-    """inverse=False: no inverse map (the step calls do not need it; the two-part lookup does)."""
+def alloc_layout(n: int, device, inverse: bool = True, sorted_ids: bool = False) -> Dict[str, torch.Tensor]:
+    """inverse=False: no inverse map (the step calls do not need it; the two-part lookup does).
+    sorted_ids=True: room for the ascending list of all IDs (the row-ordered lookup of the step calls reads it)."""
     out = {
         "unique": torch.empty(max(n, 1), dtype=torch.int64, device=device),
         "seg_offsets": torch.empty(n + 1, dtype=torch.int32, device=device),
@@ -537,6 +551,8 @@ def alloc_layout(n: int, device, inverse: bool = True) -> Dict[str, torch.Tensor
     }
     if inverse:
         out["inverse"] = torch.empty(max(n, 1), dtype=torch.int32, device=device)
+    if sorted_ids:
+        out["sorted_ids"] = torch.empty(max(n, 1), dtype=torch.int64, device=device)
     return out
 
 
@@ -574,6 +590,7 @@ def make_step_args(table: torch.Tensor, state: torch.Tensor, lr: float, eps: flo
         a.u_t1, a.seg_offsets_t1 = _ptr(layout_t1["unique"]), _ptr(layout_t1["seg_offsets"])
         a.perm_t1, a.inverse_t1 = _ptr(layout_t1["perm"]), _ptr(layout_t1.get("inverse"))
         a.n_unique_t1_dev = _ptr(layout_t1["n_unique"])
+        a.sorted_ids_t1 = _ptr(layout_t1.get("sorted_ids"))
         a.emb_t1 = _ptr(emb_t1)
     else:
         a.n_t1, a.batch_t1 = 0, 0

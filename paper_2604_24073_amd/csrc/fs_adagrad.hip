@@ -73,7 +73,7 @@ __global__ __launch_bounds__(256) void adagrad_kernel(u32x4 *__restrict__ table,
             ss = group_sum<LPR>(ss);
             const float m = (float)(ss / (double)dim);
             const float s_new = s_old[u] + m;
-            const float c_step = __fdiv_rn(lr, __fsqrt_rn(s_new) + eps);
+            const float c_step = __fdiv_rn(lr, sqrt_rn_f32(s_new) + eps);
             const bool mine = live[u] && (lig < granules);
             if (BF16) {
                 u32x4 o;

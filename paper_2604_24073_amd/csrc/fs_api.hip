@@ -234,8 +234,11 @@ int fs_ctx_create(fs_ctx **out, int device, int64_t max_ids, int32_t max_dim) {
     }
     c->host = new (std::nothrow) fs_host();
     ok = ok && c->host != nullptr;
-    hipStream_t *streams[] = {&c->stream_a, &c->stream_b, &c->stream_cap};
-    for (hipStream_t *st : streams) ok = ok && hipStreamCreateWithFlags(st, hipStreamNonBlocking) == hipSuccess;
+    // The chip gives a process four hardware queues; streams beyond that share them, and two streams on one
+    // queue run one after the other.  Only the streams of the steady-state step exist from the start (side
+    // stream, index streams: with the caller's stream that makes four); the self-contained step's second side
+    // stream and the capture stream are created when first needed.
+    ok = ok && hipStreamCreateWithFlags(&c->stream_a, hipStreamNonBlocking) == hipSuccess;
     for (hipStream_t &st : c->stream_x) ok = ok && hipStreamCreateWithFlags(&st, hipStreamNonBlocking) == hipSuccess;
     hipEvent_t *evs[] = {&c->ev_fork, &c->ev_split, &c->ev_ex, &c->ev_pfork[0], &c->ev_pfork[1], &c->ev_side[0],
                          &c->ev_side[1]};
@@ -289,7 +292,7 @@ int fs_check_async(fs_ctx *ctx, fs_stream stream) {
     if (jrc != FS_OK) return jrc;
     FS_HIP(ctx, hipStreamSynchronize(as_stream(stream)));
     FS_HIP(ctx, hipStreamSynchronize(ctx->stream_a));
-    FS_HIP(ctx, hipStreamSynchronize(ctx->stream_b));
+    if (ctx->stream_b) FS_HIP(ctx, hipStreamSynchronize(ctx->stream_b));
     for (hipStream_t sx : ctx->stream_x) FS_HIP(ctx, hipStreamSynchronize(sx));
     int flags[4] = {0, 0, 0, 0};
     FS_HIP(ctx, hipMemcpy(flags, ctx->d_flags, sizeof(flags), hipMemcpyDeviceToHost));
@@ -688,6 +691,10 @@ int enqueue_index_work_batch(fs_ctx *ctx, int count, const fs_step_args *a, cons
         if (have_t1[k] && ahead && ahead[k]) {
             const int r = consume_ahead(ctx, ahead[k], s);
             if (rc == FS_OK) rc = r;
+            // fs_unique_ids_ahead has no place for the ascending ID list: a lookup that walked it would read junk
+            if (a[k].sorted_ids_t1 != nullptr && rc == FS_OK)
+                rc = set_err(ctx, FS_EINVAL, "step: sorted_ids_t1 given, but the dedup of this batch was done by "
+                                             "fs_unique_ids_ahead, which does not write it");
         }
     for (int k0 = 0; k0 < count && rc == FS_OK;) {
         if (!(have_t1[k0] && !(ahead && ahead[k0]))) { ++k0; continue; }
@@ -696,7 +703,7 @@ int enqueue_index_work_batch(fs_ctx *ctx, int count, const fs_step_args *a, cons
         while (k0 + m < count && have_t1[k0 + m] && !(ahead && ahead[k0 + m])) {
             const fs_step_args &x = a[k0 + m];
             jobs[m] = fs_unique_job{x.values_t1, x.n_t1, x.num_rows, x.u_t1, x.seg_offsets_t1, x.perm_t1, x.inverse_t1,
-                                    x.n_unique_t1_dev};
+                                    x.n_unique_t1_dev, x.sorted_ids_t1};
             ++m;
         }
         rc = launch_unique_batch(ctx, m, jobs, s, set0 + k0);
@@ -776,6 +783,8 @@ int enqueue_gathers(fs_ctx *ctx, const fs_step_args *a, const bool *use, int cou
                               a[k].offsets_t1, a[k].batch_t1, a[k].n_t1, a[k].emb_t1};
             if (part && part[k] >= 0) {
                 j.inverse = a[k].inverse_t1; j.row_flag = a[k].co_flag_t1; j.which = part[k];
+            } else if (a[k].sorted_ids_t1 != nullptr) {
+                j.sorted_ids = a[k].sorted_ids_t1; j.perm = a[k].perm_t1;
             }
         }
     if (m == 0) return FS_OK;
@@ -1070,6 +1079,7 @@ int fs_prioritized_step(fs_ctx *ctx, const fs_step_args *a, fs_stream stream) {
     bool have_t, have_t1;
     int rc = check_step_args(ctx, a, &have_t, &have_t1);
     if (rc != FS_OK) return rc;
+    if (!ctx->stream_b) FS_HIP(ctx, hipStreamCreateWithFlags(&ctx->stream_b, hipStreamNonBlocking));
     hipStream_t sp = as_stream(stream), sa = ctx->stream_a, sb = ctx->stream_b;
     forget_fetched(ctx);
     rc = join_pending_work(ctx, sp);
@@ -1301,6 +1311,10 @@ int fs_graph_capture_pipelined(fs_ctx *ctx, const fs_step_args *cur, const fs_st
     ctx->side_pending = false;
     (void)hipStreamSynchronize(ctx->stream_a);
     for (hipStream_t sx : ctx->stream_x) (void)hipStreamSynchronize(sx);
+    if (!ctx->stream_cap && hipStreamCreateWithFlags(&ctx->stream_cap, hipStreamNonBlocking) != hipSuccess) {
+        delete g;
+        return set_err(ctx, FS_EHIP, "hipStreamCreateWithFlags(capture stream)");
+    }
     hipError_t e = hipStreamBeginCapture(ctx->stream_cap, hipStreamCaptureModeThreadLocal);
     if (e != hipSuccess) {
         delete g;

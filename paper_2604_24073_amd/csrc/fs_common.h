@@ -86,6 +86,7 @@ struct fs_unique_job {
     int64_t *unique;
     int32_t *seg_offsets, *perm, *inverse;
     int64_t *n_unique_dev;
+    int64_t *sorted_ids = nullptr;  // optional [n]: all IDs in ascending order
 };
 struct fs_split_job {
     const int64_t *u_t, *n_t_dev, *u_t1, *n_t1_dev;
@@ -138,6 +139,10 @@ struct fs_gather_job {
     const int32_t *inverse = nullptr;
     const uint8_t *row_flag = nullptr;
     int which = -1;
+    // row order (optional, whole lookups only): position p of the ascending list holds row sorted_ids[p], whose
+    // occurrence is perm[p]
+    const int64_t *sorted_ids = nullptr;
+    const int32_t *perm = nullptr;
 };
 
 struct fs_ctx {

@@ -113,7 +113,7 @@ __device__ __forceinline__ void update_parked(const f32x4 *stage, const int64_t 
             ss = group_sum<LPR>(ss);
             const float m = (float)(ss / (double)dim);
             const float s_new = s_old[u] + m;
-            const float c_step = __fdiv_rn(lr, __fsqrt_rn(s_new) + eps);
+            const float c_step = __fdiv_rn(lr, sqrt_rn_f32(s_new) + eps);
             const bool mine = live[u] && col_ok;
             if (BF16) {
                 const float c0 = bf16_lo(w[u][0]) - c_step * g[u][0];
@@ -540,7 +540,7 @@ __device__ __forceinline__ void short_rows_body(
             ss = group_sum<LPR>(ss);
             const float m = (float)(ss / (double)dim);
             const float s_new = s_old[u] + m;
-            const float c_step = __fdiv_rn(lr, __fsqrt_rn(s_new) + eps);
+            const float c_step = __fdiv_rn(lr, sqrt_rn_f32(s_new) + eps);
             if (BF16) {
                 const float c0 = bf16_lo(w[u][0]) - c_step * gs[0];
                 const float c1 = bf16_hi(w[u][0]) - c_step * gs[1];
@@ -587,13 +587,15 @@ struct class_pass_batch {
     class_pass_job j[kMaxBatch];
 };
 
-template <bool BF16, int LPR, int UNR, int CHUNK, int SU>
+// CLS (0: priority pass, 1: deferred pass) is a template parameter so that the two passes are two kernels by name
+// in a profile; the code is the same.
+template <bool BF16, int LPR, int UNR, int CHUNK, int SU, int CLS>
 __global__ __launch_bounds__(kFusedWaves *kWave) void class_pass_kernel(const class_pass_batch batch, int *flags) {
     const class_pass_job &job = batch.j[blockIdx.y];
-    FS_WG_TRACE(8 + job.cls);
+    FS_WG_TRACE(8 + CLS);
     if ((int)blockIdx.x >= job.blocks) return;
     if ((int)blockIdx.x < job.long_blocks)
-        long_segments_body<BF16, LPR, UNR, CHUNK>((int)blockIdx.x, job.grads, job.cperm, job.cslot, job.class_pos, job.cls,
+        long_segments_body<BF16, LPR, UNR, CHUNK>((int)blockIdx.x, job.grads, job.cperm, job.cslot, job.class_pos, CLS,
                                                   job.n, job.seg_offsets, job.cstart, job.u_t, job.table, job.state,
                                                   job.num_rows, job.gvec, job.lr, job.eps, job.reduced, job.part_head,
                                                   job.part_last, job.cnt_seg, job.cnt_sup, flags);
@@ -604,8 +606,9 @@ __global__ __launch_bounds__(kFusedWaves *kWave) void class_pass_kernel(const cl
 }
 
 // `idx[0..m)`: the jobs of `jobs` (all of one dtype and row width, all with n > 0) that share this launch
-template <bool BF16, int LPR, int CHUNK>
-static void fused_launch(fs_ctx *ctx, int cls, const fs_class_pass_job *jobs, const int *idx, int m, hipStream_t s) {
+template <bool BF16, int LPR, int CHUNK, int CLS>
+static void fused_launch(fs_ctx *ctx, const fs_class_pass_job *jobs, const int *idx, int m, hipStream_t s) {
+    constexpr int cls = CLS;
     constexpr int GPW = kWave / LPR;
     constexpr int SU = FS_SHORT_UNR;
     constexpr int UNR = (CHUNK / GPW) < FS_FUSED_UNR ? ((CHUNK / GPW) < 1 ? 1 : (CHUNK / GPW)) : FS_FUSED_UNR;
@@ -644,7 +647,7 @@ static void fused_launch(fs_ctx *ctx, int cls, const fs_class_pass_job *jobs, co
             doubles += my_chunks * (size_t)in.dim;
             blocks = j.blocks > blocks ? j.blocks : blocks;
         }
-        hipLaunchKernelGGL((class_pass_kernel<BF16, LPR, UNR, CH, SU>), dim3((unsigned)blocks, (unsigned)k),
+        hipLaunchKernelGGL((class_pass_kernel<BF16, LPR, UNR, CH, SU, CLS>), dim3((unsigned)blocks, (unsigned)k),
                            dim3(kFusedWaves * kWave), 0, s, batch, ctx->d_flags);
         at += k;
     }
@@ -668,11 +671,11 @@ int launch_reduce_update_batch(fs_ctx *ctx, int cls, int count, const fs_class_p
 #define FS_CASE(L)                                                                              \
     case L:                                                                                     \
         if (cls == 0) {                                                                         \
-            if (bf) fused_launch<true, L, FS_FUSED_CHUNK_CO>(ctx, cls, jobs, idx, m, s);        \
-            else fused_launch<false, L, FS_FUSED_CHUNK_CO>(ctx, cls, jobs, idx, m, s);          \
+            if (bf) fused_launch<true, L, FS_FUSED_CHUNK_CO, 0>(ctx, jobs, idx, m, s);          \
+            else fused_launch<false, L, FS_FUSED_CHUNK_CO, 0>(ctx, jobs, idx, m, s);            \
         } else {                                                                                \
-            if (bf) fused_launch<true, L, FS_FUSED_CHUNK_EX>(ctx, cls, jobs, idx, m, s);        \
-            else fused_launch<false, L, FS_FUSED_CHUNK_EX>(ctx, cls, jobs, idx, m, s);          \
+            if (bf) fused_launch<true, L, FS_FUSED_CHUNK_EX, 1>(ctx, jobs, idx, m, s);          \
+            else fused_launch<false, L, FS_FUSED_CHUNK_EX, 1>(ctx, jobs, idx, m, s);            \
         }                                                                                       \
         break;
         switch (lpr) {

@@ -30,6 +30,7 @@ struct unique_dev_job {
     int64_t *unique;
     int32_t *seg_offsets, *perm, *inverse;
     int64_t *n_unique_dev;
+    int64_t *sorted_ids;
 };
 struct unique_dev_batch {
     unique_dev_job j[kMaxBatch];
@@ -273,6 +274,7 @@ __global__ __launch_bounds__(kScanThreads) void unique_compact_kernel(const uniq
     int32_t *__restrict__ seg_offsets = job.seg_offsets;
     int32_t *__restrict__ inverse = job.inverse;
     int64_t *__restrict__ n_unique_dev = job.n_unique_dev;
+    int64_t *__restrict__ sorted_ids = job.sorted_ids;
     __shared__ int sh[kScanThreads / kWave];
     const int p0 = blockIdx.x * kScanTile + threadIdx.x * kScanIpt;
     int pm[kScanIpt];
@@ -299,6 +301,7 @@ __global__ __launch_bounds__(kScanThreads) void unique_compact_kernel(const uniq
                 ++rank;
             }
             if (inverse != nullptr) inverse[pm[i]] = rank - 1;
+            if (sorted_ids != nullptr) sorted_ids[p] = (int64_t)k[i];
         }
     }
     if ((int)blockIdx.x == job.stiles - 1 && threadIdx.x == 0) {
@@ -388,6 +391,7 @@ int launch_unique_batch(fs_ctx *ctx, int count, const fs_unique_job *jobs, hipSt
         j.perm = in.perm;
         j.inverse = in.inverse;
         j.n_unique_dev = in.n_unique_dev;
+        j.sorted_ids = in.sorted_ids;
     }
     if (key_bits <= 32) return unique_batch_impl<uint32_t>(ctx, batch, count, key_bits, s);
     return unique_batch_impl<uint64_t>(ctx, batch, count, key_bits, s);

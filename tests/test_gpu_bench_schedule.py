@@ -1,0 +1,144 @@
+"""Full-size parity on the schedule that bench.py times.
+
+bench.py and this file drive the same object (paper_2604_24073_amd.schedule.StepLoop): index halves of K
+iterations per chain of launches, issued ahead of time on the library's index streams and ordered after the
+start of the most recent pipelined call, one multi-table pipelined call per step and group, worker-thread
+enqueue, several layouts in flight, and NO wait between the calls.  Configurations 1, 3 and 4 are one table
+(chains of two iterations); configuration 2 is stepped as bench.py steps it: eight tables in two groups, each
+group with its own context and stream, the tables of a group sharing launches.
+
+The steps cycle through the configuration's batches exactly as the timed loop does (step s: batch s mod T with
+batch (s + 1) mod T as lookahead) and the oracle takes the same steps on a table that holds only the touched
+rows.  Compared: every gathered batch (each step writes into a buffer of its own here, so all of them are still
+there at the end), the final rows and the final Adagrad state of every touched row, a sample of untouched rows.
+
+The bar is BIT FOR BIT, for fp32 and bf16 tables alike.  A run of many steps on the same rows cannot be held to
+"one bf16 ulp" (a weight that legitimately differs by one ulp after one step differs by that much after the next
+update too, whatever its new magnitude), so this test removes the one source of legitimate difference instead:
+its gradients are the configuration's N(0,1) draws rounded to multiples of 1/16 and clipped to [-4, 4].  Every
+sum over the occurrences of a row (up to 90 k of them: below 2^23 sixteenths) and every sum of squares over the
+columns is then exact in fp64 in whatever order it is taken, both sides do identical IEEE operations after
+that, and ANY difference - a race between passes, a pass that ran before what it depends on, a stale buffer of
+the rotation - shows as a wrong bit.  IDs, lengths, tables and sizes are the configuration's own.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import paper_2604_24073_amd as fs
+from paper_2604_24073_amd.schedule import StepLoop, TableBuffers
+from fs_workloads import CONFIGS, compact_rows, hash_init_rows, make_iterations
+from helpers import exact_f32_to_bf16_bits, table_to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def oracle_steps(tab, its, steps, lr, eps):
+    """The same `steps` cyclic steps on the touched rows: (touched, gathered batch of every step, rows, state)."""
+    T = len(its)
+    touched, remapped = compact_rows([it.values for it in its])
+    if tab.init == "hash":
+        w0 = np.concatenate([hash_init_rows(touched[i:i + 65536], tab.dim, tab.dtype)
+                             for i in range(0, len(touched), 65536)])
+    else:
+        full = (np.random.default_rng(0xF5CA1E00).standard_normal((tab.num_rows, tab.dim)) * 0.01).astype(np.float32)
+        w0 = full[touched]
+    t_ref = exact_f32_to_bf16_bits(w0) if tab.dtype == "bf16" else w0.copy()
+    s_ref = np.zeros(len(touched), np.float32)
+    layouts = [O.unique_ids(remapped[b], len(touched)) for b in range(T)]
+    embs = []
+    for s in range(steps):
+        b, nb = s % T, (s + 1) % T
+        r = O.step(t_ref, s_ref, layouts[b], its[b].grads, remapped[nb], its[nb].offsets, lr, eps)
+        embs.append(r["emb_next"])
+    return touched, embs, t_ref, s_ref
+
+
+def exact_sum_gradients(g):
+    return (np.clip(np.rint(g * 16.0), -64, 64) / 16.0).astype(np.float32)
+
+
+def same_bits(got, want, what):
+    assert got.dtype == want.dtype and got.shape == want.shape, what
+    if got.tobytes() != want.tobytes():
+        bad = np.nonzero(got.view(np.uint16 if got.dtype == np.uint16 else np.uint32) !=
+                         want.view(np.uint16 if want.dtype == np.uint16 else np.uint32))
+        raise AssertionError(f"{what}: {len(bad[0])} of {got.size} elements differ, first at {[int(x[0]) for x in bad]}")
+
+
+def check_on_bench_schedule(cfg_index, steps, groups):
+    cfg = CONFIGS[cfg_index]
+    its_all = make_iterations(cfg)
+    for per_table in its_all:
+        for it in per_table:
+            it.grads = exact_sum_gradients(it.grads)
+    dev = torch.device("cuda")
+    bufs = []
+    for ti, tab in enumerate(cfg.tables):
+        its = [x[ti] for x in its_all]
+        tdtype = torch.float32 if tab.dtype == "f32" else torch.bfloat16
+        table = torch.empty((tab.num_rows, tab.dim), dtype=tdtype, device=dev)
+        state = torch.zeros(tab.num_rows, dtype=torch.float32, device=dev)
+        bufs.append(TableBuffers(table, state, [torch.from_numpy(it.values).to(dev) for it in its],
+                                 [torch.from_numpy(it.offsets).to(dev) for it in its],
+                                 [torch.from_numpy(it.grads).to(dev) for it in its], cfg.lr, cfg.eps))
+    loop = StepLoop(bufs, groups=groups, emb_rotation=steps)
+    assert steps <= loop.period
+    for tab, b in zip(cfg.tables, bufs):
+        if tab.init == "hash":
+            fs.fs_init_table_hash(loop.ctxs[0], b.table)
+        else:
+            full = (np.random.default_rng(0xF5CA1E00).standard_normal((tab.num_rows, tab.dim)) * 0.01).astype(np.float32)
+            b.table.copy_(torch.from_numpy(full))
+    torch.cuda.synchronize()
+    loop.run(0, steps)                      # bench.py's loop: no wait between the calls
+    loop.join(check=True)
+    rng = np.random.default_rng(5)
+    for ti, (tab, b) in enumerate(zip(cfg.tables, bufs)):
+        its = [x[ti] for x in its_all]
+        touched, embs, t_ref, s_ref = oracle_steps(tab, its, steps, cfg.lr, cfg.eps)
+        for s in range(steps):
+            n_next = b.n[(s + 1) % b.T]
+            same_bits(table_to_host(b.emb_of_step(s)[:n_next]), embs[s],
+                      f"configs[{cfg_index}] table {ti}: batch gathered by step {s}")
+        idx = torch.from_numpy(touched).cuda()
+        same_bits(table_to_host(b.table[idx]), t_ref, f"configs[{cfg_index}] table {ti}: final rows")
+        same_bits(b.state[idx].cpu().numpy(), s_ref, f"configs[{cfg_index}] table {ti}: final Adagrad state")
+        if tab.init == "hash":
+            cand = np.setdiff1d(rng.integers(0, tab.num_rows, size=4000), touched)[:2000]
+            rule = hash_init_rows(cand, tab.dim, tab.dtype)
+            rule = exact_f32_to_bf16_bits(rule) if tab.dtype == "bf16" else rule
+            cidx = torch.from_numpy(cand).cuda()
+            assert table_to_host(b.table[cidx]).tobytes() == rule.tobytes()
+            assert float(b.state[cidx].abs().max().item()) == 0.0
+        print(f"configs[{cfg_index}] table {ti}: {steps} steps on the timed schedule, N={b.n[:3]}, "
+              f"touched={len(touched)} ok", flush=True)
+    loop.close()
+    del bufs, loop
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.timeout(300)
+def test_config0_on_the_timed_schedule():
+    check_on_bench_schedule(0, steps=7, groups=1)
+
+
+@pytest.mark.timeout(600)
+def test_config1_on_the_timed_schedule():
+    check_on_bench_schedule(1, steps=6, groups=1)
+
+
+@pytest.mark.timeout(900)
+def test_config2_eight_tables_in_two_groups_on_the_timed_schedule():
+    check_on_bench_schedule(2, steps=4, groups=2)
+
+
+@pytest.mark.timeout(600)
+def test_config3_on_the_timed_schedule():
+    check_on_bench_schedule(3, steps=6, groups=1)
+
+
+@pytest.mark.timeout(900)
+def test_config4_ten_batches_cycled_on_the_timed_schedule():
+    check_on_bench_schedule(4, steps=12, groups=1)
