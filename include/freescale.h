@@ -279,6 +279,31 @@ int fs_collision_split_classes(fs_ctx *ctx, const int64_t *u_t, const int64_t *n
                                int32_t *cslot, int32_t *cstart, int32_t *class_pos_dev, int32_t *short_rec,
                                fs_stream stream);
 
+/* split(G~^i, I~_co^i, I~_ex^i) at the start of Backward of Algorithm 2: the batch-major gradient rows (one per
+ * occurrence, in batch order) packed into the collision part and the exclusive part, each in batch order - the
+ * tensors that the exposed and the deferred gradient AllToAll of Section 3.2 are fed with.  An occurrence belongs
+ * to the collision part iff its row is a collision row of the batch (co_slot / counts_dev[0] as fs_collision_split
+ * left them; inverse_t [n] is the inverse map of fs_unique_ids for the batch, REQUIRED here; cap_u bounds the
+ * number of distinct rows and is at most n).
+ *   co_index [n] / ex_index [n]   int32 out: occurrence numbers of the two parts, ascending (I~_co^i, I~_ex^i)
+ *   g_co [n, dim] / g_ex [n, dim] fp32 out: the gradient rows in that order (only the first counts are written)
+ *   part_pos [n]                  int32 out: for occurrence j its row number in g_co, or -1 - its row number in g_ex
+ *   part_counts_dev [2]           int64 out: occurrences in the collision part, in the exclusive part
+ * n <= context max_ids; uses the context's index workspace like fs_collision_split. */
+int fs_split_grads(fs_ctx *ctx, const float *grads, int64_t n, int32_t dim, const int32_t *inverse_t,
+                   const int32_t *co_slot, const int64_t *n_co_dev, int64_t cap_u, int32_t *co_index, float *g_co,
+                   int32_t *ex_index, float *g_ex, int32_t *part_pos, int64_t *part_counts_dev, fs_stream stream);
+
+/* Lets the fused passes read the packed parts of fs_split_grads instead of the batch-major gradients: rewrites
+ * the class order (cperm) and the occurrence lists of the records (short_rec, both as fs_collision_split_classes
+ * left them for a batch of n_t occurrences; counts_dev its row counts) through part_pos into cperm_parts [n_t] and
+ * short_rec_parts [2 * n_t * 12].  fs_reduce_update_class(0, grads = g_co, ..., short_rec_parts, cperm_parts) and
+ * fs_reduce_update_class(1, grads = g_ex, ..., short_rec_parts + 12 * n_t, cperm_parts) then give the results of
+ * the same calls on the batch-major tensor bit for bit (pass n = n_t to both). */
+int fs_class_order_for_parts(fs_ctx *ctx, const int32_t *part_pos, int64_t n_t, const int32_t *cperm,
+                             const int32_t *class_pos_dev, const int32_t *short_rec, const int64_t *counts_dev,
+                             int32_t *cperm_parts, int32_t *short_rec_parts, fs_stream stream);
+
 /* update_embedding(I, G) of Algorithm 2 for one class of rows: the segment reduce of
  * fs_segment_reduce_grads and the Adagrad update of fs_rowwise_adagrad_update fused, same
  * arithmetic (fp64 sums in a fixed order, one rounding to fp32, then the update), restricted to

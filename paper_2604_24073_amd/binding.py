@@ -88,6 +88,9 @@ def load_library() -> ctypes.CDLL:
                                               c_vp, c_vp, c_vp, S]),
         "fs_collision_split_static": (ctypes.c_int, [c_vp, c_vp, c_vp, c_vp, c_i64, c_i64, c_vp, c_vp, c_vp, c_vp,
                                                      c_vp, c_vp, c_vp, S]),
+        "fs_split_grads": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i32, c_vp, c_vp, c_vp, c_i64, c_vp, c_vp, c_vp, c_vp, c_vp,
+                                          c_vp, S]),
+        "fs_class_order_for_parts": (ctypes.c_int, [c_vp, c_vp, c_i64, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, S]),
         "fs_segment_reduce_grads": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i32, c_vp, c_vp, c_vp, c_vp, c_vp, S]),
         "fs_rowwise_adagrad_update": (ctypes.c_int, [c_vp, c_vp, ctypes.c_int, c_vp, c_i64, c_i32, c_vp, c_vp, c_vp,
                                                      c_i64, c_vp, c_f, c_f, S]),
@@ -396,6 +399,38 @@ def fs_collision_split_classes(ctx: Context, layout_t: Dict[str, torch.Tensor], 
         _ptr(out["ex_next_slot"]), _ptr(out["counts"]), _ptr(out["cperm"]), _ptr(out["cslot"]), _ptr(out["cstart"]),
         _ptr(out["class_pos"]), _ptr(out["short_rec"]), _stream(stream))
     ctx.check(rc, "fs_collision_split_classes")
+    return out
+
+
+def fs_split_grads(ctx: Context, grads: torch.Tensor, layout_t: Dict[str, torch.Tensor], split: Dict[str, torch.Tensor],
+                   out: Optional[Dict[str, torch.Tensor]] = None, stream=None) -> Dict[str, torch.Tensor]:
+    """split() of Algorithm 2's Backward.  layout_t: the batch's layout with its inverse map; split: its collision
+    split (co_slot, counts).  Returns co_index, g_co, ex_index, g_ex, part_pos, counts ([2] occurrences per part)."""
+    n, dim = grads.shape
+    dev = grads.device
+    if out is None:
+        i32 = lambda: torch.empty(max(n, 1), dtype=torch.int32, device=dev)
+        f32 = lambda: torch.empty((max(n, 1), dim), dtype=torch.float32, device=dev)
+        out = {"co_index": i32(), "g_co": f32(), "ex_index": i32(), "g_ex": f32(), "part_pos": i32(),
+               "counts": torch.zeros(2, dtype=torch.int64, device=dev)}
+    rc = ctx.lib.fs_split_grads(ctx.handle, _ptr(grads), n, dim, _ptr(layout_t.get("inverse")), _ptr(split["co_slot"]),
+                                _ptr(split["counts"]), n, _ptr(out["co_index"]), _ptr(out["g_co"]),
+                                _ptr(out["ex_index"]), _ptr(out["g_ex"]), _ptr(out["part_pos"]), _ptr(out["counts"]),
+                                _stream(stream))
+    ctx.check(rc, "fs_split_grads")
+    return out
+
+
+def fs_class_order_for_parts(ctx: Context, parts: Dict[str, torch.Tensor], n_t: int, split: Dict[str, torch.Tensor],
+                             stream=None) -> Dict[str, torch.Tensor]:
+    """A copy of `split` whose class order and records address the packed parts of fs_split_grads."""
+    out = dict(split)
+    out["cperm"] = torch.empty_like(split["cperm"])
+    out["short_rec"] = torch.empty_like(split["short_rec"])
+    rc = ctx.lib.fs_class_order_for_parts(ctx.handle, _ptr(parts["part_pos"]), n_t, _ptr(split["cperm"]),
+                                          _ptr(split["class_pos"]), _ptr(split["short_rec"]), _ptr(split["counts"]),
+                                          _ptr(out["cperm"]), _ptr(out["short_rec"]), _stream(stream))
+    ctx.check(rc, "fs_class_order_for_parts")
     return out
 
 

@@ -919,6 +919,36 @@ int fs_reduce_update_class(fs_ctx *ctx, int cls, void *table, fs_dtype dt, float
                                 dt, state, num_rows, lr, eps, reduced, as_stream(stream), short_rec_cls, n_rows_dev);
 }
 
+int fs_split_grads(fs_ctx *ctx, const float *grads, int64_t n, int32_t dim, const int32_t *inverse_t,
+                   const int32_t *co_slot, const int64_t *n_co_dev, int64_t cap_u, int32_t *co_index, float *g_co,
+                   int32_t *ex_index, float *g_ex, int32_t *part_pos, int64_t *part_counts_dev, fs_stream stream) {
+    if (!ctx) return FS_EINVAL;
+    FS_REQUIRE(ctx, n >= 0 && cap_u >= 0 && cap_u <= n, "split grads: negative size, or more distinct rows than occurrences");
+    FS_REQUIRE(ctx, dim_ok(dim, FS_F32), "split grads: dim must be a multiple of 4, at most FS_MAX_DIM");
+    if (n > ctx->max_ids) return set_err(ctx, FS_ENOMEM, "split grads: n beyond the context capacity");
+    FS_REQUIRE(ctx, part_counts_dev, "split grads: null counts");
+    if (n > 0)
+        FS_REQUIRE(ctx, grads && inverse_t && co_slot && n_co_dev && co_index && g_co && ex_index && g_ex && part_pos,
+                   "split grads: null pointer");
+    const int jrc = join_pending_work(ctx, as_stream(stream));      // the index workspace may still be in use
+    if (jrc != FS_OK) return jrc;
+    return launch_split_grads(ctx, grads, n, dim, inverse_t, co_slot, n_co_dev, cap_u, co_index, g_co, ex_index, g_ex,
+                              part_pos, part_counts_dev, as_stream(stream));
+}
+
+int fs_class_order_for_parts(fs_ctx *ctx, const int32_t *part_pos, int64_t n_t, const int32_t *cperm,
+                             const int32_t *class_pos_dev, const int32_t *short_rec, const int64_t *counts_dev,
+                             int32_t *cperm_parts, int32_t *short_rec_parts, fs_stream stream) {
+    if (!ctx) return FS_EINVAL;
+    FS_REQUIRE(ctx, n_t >= 0, "class order for parts: negative size");
+    if (n_t > ctx->max_ids) return set_err(ctx, FS_ENOMEM, "class order for parts: n_t beyond the context capacity");
+    if (n_t == 0) return FS_OK;
+    FS_REQUIRE(ctx, part_pos && cperm && class_pos_dev && short_rec && counts_dev && cperm_parts && short_rec_parts,
+               "class order for parts: null pointer");
+    return launch_class_order_for_parts(ctx, part_pos, n_t, n_t, cperm, class_pos_dev, short_rec, counts_dev,
+                                        cperm_parts, short_rec_parts, as_stream(stream));
+}
+
 int fs_unique_ids_ahead(fs_ctx *ctx, const int64_t *ids, int64_t n, int64_t num_rows, int64_t *unique,
                         int32_t *seg_offsets, int32_t *perm, int32_t *inverse, int64_t *n_unique_dev,
                         fs_stream stream) {

@@ -302,6 +302,12 @@ int launch_reduce(fs_ctx *, const float *grads, int64_t n, int32_t dim, const in
 int launch_adagrad(fs_ctx *, void *table, int dt, float *state, int64_t num_rows, int32_t dim,
                    const int64_t *rows, const int32_t *slots, const int64_t *n_rows_dev, int64_t cap,
                    const float *reduced, float lr, float eps, hipStream_t s);
+int launch_split_grads(fs_ctx *, const float *grads, int64_t n, int32_t dim, const int32_t *inverse,
+                       const int32_t *co_slot, const int64_t *n_co_dev, int64_t cap_u, int32_t *co_index, float *g_co,
+                       int32_t *ex_index, float *g_ex, int32_t *part_pos, int64_t *counts_dev, hipStream_t s);
+int launch_class_order_for_parts(fs_ctx *, const int32_t *part_pos, int64_t n, int64_t cap_u, const int32_t *cperm,
+                                 const int32_t *class_pos_dev, const int32_t *short_rec, const int64_t *counts_dev,
+                                 int32_t *cperm_parts, int32_t *short_rec_parts, hipStream_t s);
 int launch_init_hash(fs_ctx *, void *table, int64_t num_rows, int32_t dim, int dt, hipStream_t s);
 int launch_copy(fs_ctx *, const void *src, void *dst, int64_t n_bytes, hipStream_t s);
 
