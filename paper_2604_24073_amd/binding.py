@@ -131,13 +131,18 @@ def load_library() -> ctypes.CDLL:
     return lib
 
 
-def declared_symbols(header_path: Optional[str] = None):
-    """Names of the functions declared in include/freescale.h."""
-    if header_path is None:
-        header_path = os.path.join(os.path.dirname(_HERE), "include", "freescale.h")
-    text = open(header_path).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(fs_[a-z0-9_]+)\s*\(", text)))
+def declared_symbols(header_paths=None):
+    """Names of the functions declared in include/*.h (what a -DFS_TRACE build adds is left out)."""
+    if header_paths is None:
+        inc = os.path.join(os.path.dirname(_HERE), "include")
+        header_paths = sorted(os.path.join(inc, f) for f in os.listdir(inc) if f.endswith(".h"))
+    names = set()
+    for path in header_paths:
+        text = open(path).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        text = re.sub(r"#ifdef FS_TRACE.*?#endif", "", text, flags=re.S)
+        names.update(re.findall(r"\b(fs_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:

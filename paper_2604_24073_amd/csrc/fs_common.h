@@ -7,7 +7,7 @@
 #include <stdio.h>
 #include <string.h>
 
-#include "freescale.h"
+#include "freescale_aux.h"
 
 namespace fs {
 
