@@ -378,13 +378,31 @@ def measure_extras(args, cfg, loop, t, stats, s_next, step_gbps):
         k1[0] += 1
 
     t_both = timed_loop(step_and_scrub, 20)
+    # the step's access pattern with nothing else in the way: the gradient rows of one batch read in a random order
+    # (what the class passes do with them), cold (behind the same 1 GiB copy) and back to back
+    order = torch.randperm(t.n[0], device=dev)
+    sink = torch.zeros(1024, dtype=torch.int32, device=dev)
+
+    def read_and_scrub(i):
+        fs.fs_stream_copy(ctx, src, dst, stream=stream)
+        fs.fs_stream_row_read(ctx, t.grads[0], order, sink, stream=stream)
+
+    t_rows_cold = timed_loop(read_and_scrub, 20) - t_copy
+    t_rows_warm = timed_loop(lambda i: fs.fs_stream_row_read(ctx, t.grads[0], order, sink, stream=stream), 20)
+    row_bytes_read = t.n[0] * t.grads[0].shape[1] * 4
     copy_gbps = 2 * src.numel() / t_copy / 1e9
     out["achievable_ceiling"] = {
         "stream_copy_GBps": copy_gbps, "stream_copy_frac_of_hbm_peak": copy_gbps / HBM_PEAK_GBPS,
         "bytes": 2 * src.numel(), "step_algorithmic_frac_of_stream_copy": step_gbps / copy_gbps,
         "cold_step_us": (t_both - t_copy) * 1e6,
         "cold_step_note": "20 steps, each behind a 1 GiB -> 1 GiB copy on the same stream, minus the time of the copies "
-                          "alone; the steady-state loop does not flush anything"}
+                          "alone; the steady-state loop does not flush anything",
+        "random_row_read_GBps_cold": row_bytes_read / t_rows_cold / 1e9,
+        "random_row_read_GBps_back_to_back": row_bytes_read / t_rows_warm / 1e9,
+        "random_row_read_note": f"{t.n[0]} rows of {t.grads[0].shape[1] * 4} bytes (the gradient rows of one batch) read in "
+                                "a random order by one launch of fs_stream_row_read and thrown away; cold = behind the "
+                                "1 GiB copy, its time subtracted",
+        "step_algorithmic_frac_of_random_row_read": step_gbps / (row_bytes_read / t_rows_cold / 1e9)}
     del src, dst
 
     def alone(f, reps=20):

@@ -45,6 +45,13 @@ int fs_ctx_host_times(fs_ctx *ctx, double *out7_host, int reset);
  * fp32: ((h & 0xFFFF) - 32768) * 2^-22;  bf16: ((h & 0xFF) - 128) * 2^-14. */
 int fs_init_table_hash(fs_ctx *ctx, void *table, int64_t num_rows, int32_t dim, fs_dtype dt, fs_stream stream);
 
+/* Reads the rows rows[index[j], :] for j in [0, n) and throws them away (one folded word per wavefront goes to
+ * sink [1024] uint32): what the memory system gives whole rows at indexed addresses with nothing else in the way -
+ * the ceiling of the step's access pattern, measured beside the step.  rows [num_rows] of row_bytes bytes each
+ * (a multiple of 16, at most 1024); an index outside [0, num_rows) reads row 0. */
+int fs_stream_row_read(fs_ctx *ctx, const void *rows, int64_t num_rows, int32_t row_bytes, const int64_t *index,
+                       int64_t n, uint32_t *sink, fs_stream stream);
+
 /* Plain 16-byte-per-lane copy of n_bytes (multiple of 16) from src to dst: the calibration
  * kernel for bandwidth counters and the achievable-copy ceiling. */
 int fs_stream_copy(fs_ctx *ctx, const void *src, void *dst, int64_t n_bytes, fs_stream stream);

@@ -123,6 +123,7 @@ def load_library() -> ctypes.CDLL:
                                                     ctypes.POINTER(ctypes.c_int)]),
         "fs_init_table_hash": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i32, ctypes.c_int, S]),
         "fs_stream_copy": (ctypes.c_int, [c_vp, c_vp, c_vp, c_i64, S]),
+        "fs_stream_row_read": (ctypes.c_int, [c_vp, c_vp, c_i64, c_i32, c_vp, c_i64, c_vp, S]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -576,6 +577,14 @@ def fs_stream_copy(ctx: Context, src: torch.Tensor, dst: torch.Tensor, stream=No
     nbytes = src.numel() * src.element_size()
     rc = ctx.lib.fs_stream_copy(ctx.handle, _ptr(src), _ptr(dst), nbytes, _stream(stream))
     ctx.check(rc, "fs_stream_copy")
+
+
+def fs_stream_row_read(ctx: Context, rows: torch.Tensor, index: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    """rows [num_rows, width] of any dtype with width * itemsize a multiple of 16; index int64; sink [1024] int32."""
+    row_bytes = rows.shape[1] * rows.element_size()
+    rc = ctx.lib.fs_stream_row_read(ctx.handle, _ptr(rows), rows.shape[0], row_bytes, _ptr(index), index.numel(),
+                                    _ptr(sink), _stream(stream))
+    ctx.check(rc, "fs_stream_row_read")
 
 
 # ---- buffer bundles for the whole-iteration call (allocation only) -----------------------------

@@ -536,6 +536,16 @@ int fs_init_table_hash(fs_ctx *ctx, void *table, int64_t num_rows, int32_t dim, 
     return launch_init_hash(ctx, table, num_rows, dim, dt, as_stream(stream));
 }
 
+int fs_stream_row_read(fs_ctx *ctx, const void *rows, int64_t num_rows, int32_t row_bytes, const int64_t *index,
+                       int64_t n, uint32_t *sink, fs_stream stream) {
+    if (!ctx) return FS_EINVAL;
+    FS_REQUIRE(ctx, num_rows >= 0 && n >= 0, "row read: negative size");
+    FS_REQUIRE(ctx, row_bytes > 0 && row_bytes % 16 == 0 && row_bytes <= 1024, "row read: rows of 16..1024 bytes, a multiple of 16");
+    if (n == 0 || num_rows == 0) return FS_OK;
+    FS_REQUIRE(ctx, rows && index && sink, "row read: null pointer");
+    return launch_row_read(ctx, rows, num_rows, row_bytes, index, n, sink, as_stream(stream));
+}
+
 int fs_stream_copy(fs_ctx *ctx, const void *src, void *dst, int64_t n_bytes, fs_stream stream) {
     if (!ctx) return FS_EINVAL;
     FS_REQUIRE(ctx, n_bytes >= 0 && n_bytes % 16 == 0, "copy: size must be a non-negative multiple of 16");

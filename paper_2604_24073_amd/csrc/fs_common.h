@@ -310,5 +310,7 @@ int launch_class_order_for_parts(fs_ctx *, const int32_t *part_pos, int64_t n, i
                                  int32_t *cperm_parts, int32_t *short_rec_parts, hipStream_t s);
 int launch_init_hash(fs_ctx *, void *table, int64_t num_rows, int32_t dim, int dt, hipStream_t s);
 int launch_copy(fs_ctx *, const void *src, void *dst, int64_t n_bytes, hipStream_t s);
+int launch_row_read(fs_ctx *, const void *rows, int64_t num_rows, int row_bytes, const int64_t *index, int64_t n,
+                    uint32_t *sink, hipStream_t s);
 
 }  // namespace fs

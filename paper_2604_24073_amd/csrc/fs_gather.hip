@@ -103,9 +103,7 @@ __global__ __launch_bounds__(256) void gather_kernel(const gather_dev_batch jobs
 // are whole 128-byte lines either way; only their order in time changes.  Offsets are validated as in the
 // batch-order kernel.
 template <int LPR, int UNR>
-__global__ __launch_bounds__(256) void gather_rows_kernel(const gather_dev_batch jobs, int *__restrict__ flags) {
-    const gather_dev_job &job = jobs.j[blockIdx.y];
-    FS_WG_TRACE(10);
+__device__ __forceinline__ void gather_rows_body(const gather_dev_job &job, int *__restrict__ flags) {
     if ((int)blockIdx.x >= job.blocks) return;
     const u32x4 *__restrict__ table = job.table;
     const int64_t num_rows = job.num_rows;
@@ -159,6 +157,12 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const gather_dev_batch
     }
     if (oob) atomicOr(flags, kFlagRowRange);
     if (bad_perm) atomicOr(flags, kFlagInternal);
+}
+
+template <int LPR, int UNR>
+__global__ __launch_bounds__(256) void gather_rows_kernel(const gather_dev_batch jobs, int *__restrict__ flags) {
+    FS_WG_TRACE(10);
+    gather_rows_body<LPR, UNR>(jobs.j[blockIdx.y], flags);
 }
 
 
@@ -411,6 +415,62 @@ int launch_copy(fs_ctx *ctx, const void *src, void *dst, int64_t n_bytes, hipStr
     const int64_t blocks = ceil_div(n_vec, 1024);
     hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const u32x4 *)src, (u32x4 *)dst, n_vec);
     FS_LAUNCH_CHECK(ctx, "copy_kernel");
+    return FS_OK;
+}
+
+// ---- rows read and thrown away (bandwidth calibration) ----------------------------------------------------
+// What the memory system gives the access pattern of the step - whole rows at addresses that follow an index
+// list - with nothing else in the way: a wavefront takes 64 consecutive entries of `index`, requests the rows in
+// rounds of UNR row groups exactly as the position-cut pass does, and folds them into one word per wavefront.
+template <int LPR, int UNR>
+__global__ __launch_bounds__(256) void row_read_kernel(const u32x4 *__restrict__ rows, int64_t num_rows, int granules,
+                                                       const int64_t *__restrict__ index, int64_t n,
+                                                       uint32_t *__restrict__ sink) {
+    constexpr int GPW = kWave / LPR;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int grp = lane / LPR;
+    const int lig = lane % LPR;
+    const int64_t wave = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    const int64_t a = wave * kWave;
+    if (a >= n) return;
+    const int span = (int)((n - a) < kWave ? (n - a) : kWave);
+    int64_t id = lane < span ? index[a + lane] : 0;
+    if (id < 0 || id >= num_rows) id = 0;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    for (int k = 0; k * GPW * UNR < span; ++k) {
+        u32x4 v[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int q = k * GPW * UNR + u * GPW + grp;
+            const int64_t r = __shfl(id, q & (kWave - 1), kWave);
+            v[u] = u32x4{0u, 0u, 0u, 0u};
+            if (q < span && lig < granules) v[u] = __builtin_nontemporal_load(&rows[r * granules + lig]);
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) acc ^= v[u];
+    }
+    uint32_t x = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
+#pragma unroll
+    for (int m = 1; m < kWave; m <<= 1) x ^= __shfl_xor(x, m, kWave);
+    if (lane == 0) sink[wave & 1023] = x;
+}
+
+int launch_row_read(fs_ctx *ctx, const void *rows, int64_t num_rows, int row_bytes, const int64_t *index, int64_t n,
+                    uint32_t *sink, hipStream_t s) {
+    if (n == 0) return FS_OK;
+    const int granules = row_bytes / 16;
+    const unsigned blocks = (unsigned)ceil_div(n, 4 * kWave);
+#define FS_CASE(L)                                                                                            \
+    case L:                                                                                                   \
+        hipLaunchKernelGGL((row_read_kernel<L, 4>), dim3(blocks), dim3(256), 0, s, (const u32x4 *)rows, num_rows, \
+                           granules, index, n, sink);                                                         \
+        break;
+    switch (lanes_per_row(granules)) {
+        FS_CASE(1) FS_CASE(2) FS_CASE(4) FS_CASE(8) FS_CASE(16) FS_CASE(32) FS_CASE(64)
+        default: return set_err(ctx, FS_EINVAL, "row read: row wider than 1024 bytes");
+    }
+#undef FS_CASE
+    FS_LAUNCH_CHECK(ctx, "row_read_kernel");
     return FS_OK;
 }
 

@@ -87,6 +87,19 @@ def test_host_visible_errors(ctx):
     assert "gather" in ctx.last_error()
 
 
+def test_row_read_calibration_kernel_reads_the_rows_it_is_given(ctx):
+    """fs_stream_row_read (a measurement aid): the folded word of one wavefront is the xor of every 32-bit word of
+    the rows it was pointed at."""
+    rng = np.random.default_rng(2)
+    rows = rng.integers(0, 2**31, size=(500, 128), dtype=np.int64).astype(np.int32)
+    index = rng.integers(0, 500, size=37).astype(np.int64)
+    sink = torch.zeros(1024, dtype=torch.int32, device="cuda")
+    fs.fs_stream_row_read(ctx, dev(rows), dev(index), sink)
+    torch.cuda.synchronize()
+    want = np.bitwise_xor.reduce(rows[index].reshape(-1))
+    assert int(sink[0].item()) == int(want)
+
+
 # ------------------------------------------------------------------------------------ unique
 def check_unique(ctx, ids, num_rows):
     want = O.unique_ids(ids, num_rows)
