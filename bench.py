@@ -52,9 +52,10 @@ def algorithmic_bytes(n_t, u_t, n_t1, u_t1, dim, w):
 
 
 def read_traffic(path=TRAFFIC_FILE):
-    """profiles/hbm_traffic_per_launch.txt -> {(workload, kernel): HBM bytes per launch}.  Columns (tab or
-    spaces; '#' starts a comment): workload, kernel (no blanks), dispatches, iterations per launch, FETCH_SIZE KiB,
-    WRITE_SIZE KiB, the two calibration factors.  Bytes = (FETCH * f_fetch + WRITE * f_write) * 1024 per launch."""
+    """profiles/hbm_traffic_per_launch.txt -> {(workload, kernel): HBM bytes per launch, launches per step}.
+    Columns (blanks; '#' starts a comment): workload, kernel (no blanks; "/LPRnn" marks the launch of one row
+    width), dispatches averaged over, launches per step, FETCH_SIZE KiB, WRITE_SIZE KiB, the two calibration
+    factors.  Bytes = (FETCH * f_fetch + WRITE * f_write) * 1024 per launch."""
     out = {}
     if not os.path.exists(path):
         return out
@@ -66,15 +67,24 @@ def read_traffic(path=TRAFFIC_FILE):
         if len(f) < 8:
             continue
         out[(f[0], f[1])] = {"bytes": (float(f[4]) * float(f[6]) + float(f[5]) * float(f[7])) * 1024.0,
-                             "iterations_per_launch": float(f[3])}
+                             "launches_per_step": float(f[3])}
     return out
 
 
 def summarize_counters(dirs) -> int:
-    """Mean counter value per kernel over the dispatches of rocprofv3 --pmc runs (CSV output)."""
+    """Mean counter value per kernel over the dispatches of rocprofv3 --pmc runs (CSV output); for a
+    --kernel-trace --stats run the per-kernel durations of its kernel_stats CSV."""
     import collections
     agg = collections.defaultdict(lambda: collections.defaultdict(list))
     for d in dirs:
+        for path in glob.glob(os.path.join(d, "**", "*kernel_stats.csv"), recursive=True):
+            print(f"# {path}: kernel, calls, avg us, min us, max us, % of kernel time")
+            for r in csv.DictReader(open(path)):
+                if not r["Name"].replace("void ", "").startswith("fs::"):
+                    continue
+                name = r["Name"].replace("void ", "").replace("fs::", "").split("(")[0].strip().replace(" ", "")
+                print(f"{name:60s} {int(r['Calls']):6d} {float(r['AverageNs']) / 1e3:8.1f} {float(r['MinNs']) / 1e3:8.1f} "
+                      f"{float(r['MaxNs']) / 1e3:8.1f} {float(r['Percentage']):6.1f}")
         for path in glob.glob(os.path.join(d, "**", "*counter_collection.csv"), recursive=True):
             for r in csv.DictReader(open(path)):
                 name = r["Kernel_Name"].replace("void ", "").replace("fs::", "").split("(")[0].strip()
@@ -262,7 +272,7 @@ def bench_config(args, ci, extras):
     if kernel_ms.get("gather"):
         gb = sum(sum(algorithmic_bytes(t.n[b], s[b]["u"], t.n[(b + 1) % T], s[(b + 1) % T]["u"], t.dim, t.w)["gather"]
                      for b in range(T)) / T for t, s in grp0)
-        per_kernel["gather_kernel"] = (kernel_ms["gather"], gb, 1)
+        per_kernel["gather_rows_kernel"] = (kernel_ms["gather"], gb, 1)
     if kernel_ms.get("priority_pass"):
         per_kernel["class_pass_kernel(priority_pass)"] = (kernel_ms["priority_pass"], class_pass_bytes(grp0, 0), 1)
     if kernel_ms.get("deferred_pass"):
@@ -276,11 +286,12 @@ def bench_config(args, ci, extras):
     wl = f"configs[{ci}]"
 
     def traffic_of(name):
+        # measured bytes of what one event pair brackets: the launches of every row width of that kind
         if name == "class_pass_kernel":
-            t2 = [traffic_tab.get((wl, name + sfx)) for sfx in ("(priority_pass)", "(deferred_pass)")]
-            return (t2[0]["bytes"] + t2[1]["bytes"]) / 2 if all(t2) else None
-        t = traffic_tab.get((wl, name))
-        return t["bytes"] if t else None
+            t2 = [traffic_of(name + sfx) for sfx in ("(priority_pass)", "(deferred_pass)")]
+            return (t2[0] + t2[1]) / 2 if all(t2) else None
+        t = [v["bytes"] for (w_, k_), v in traffic_tab.items() if w_ == wl and k_.split("/")[0] == name]
+        return sum(t) if t else None
 
     roofline = None
     if cand:
@@ -302,7 +313,7 @@ def bench_config(args, ci, extras):
     if traffic_tab:
         rows_t = [v for (w_, _k), v in traffic_tab.items() if w_ == wl]
         if rows_t:
-            step_traffic = sum(v["bytes"] / v["iterations_per_launch"] for v in rows_t)
+            step_traffic = sum(v["bytes"] * v["launches_per_step"] for v in rows_t)
 
     res = {
         "workload": (f"configs[{ci}] {cfg.name}: " +
@@ -335,12 +346,65 @@ def bench_config(args, ci, extras):
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
     }
+    if not args.no_extras:
+        res["row_access_ceiling"] = measure_row_ceiling(loop, bufs, step_gbps)
     if extras and not multi:
         res.update(measure_extras(args, cfg, loop, bufs[0], stats[0], k0 + total_steps, step_gbps))
     loop.close()
     del loop, bufs
     torch.cuda.empty_cache()
     return res
+
+
+def measure_row_ceiling(loop, bufs, step_gbps):
+    """The step's access pattern with nothing else in the way, on this workload's own tables: the distinct rows that
+    the batches of a table touch, in a shuffled order, read whole by fs_stream_row_read and thrown away (one launch per
+    table, no row twice, so no launch finds a row in a cache).  What the step could reach if every one
+    of its bytes moved at this rate is `step_algorithmic_frac_of_ceiling`."""
+    import torch
+    import paper_2604_24073_amd as fs
+    ctx, stream = loop.ctxs[0], loop.streams[0]
+    dev = bufs[0].table.device
+    sink = torch.zeros(1024, dtype=torch.int32, device=dev)
+    jobs = []
+    for t in bufs:
+        u = torch.unique(torch.cat([t.values[b][:t.n[b]] for b in range(t.T)]))
+        jobs.append((t.table, u[torch.randperm(u.numel(), device=dev)].contiguous()))
+    by_batch = [sum(idx.numel() * tb.shape[1] * tb.element_size() for tb, idx in jobs)]
+    reps = max(2, 40 // max(1, len(jobs)))
+    # a sweep of less than 1 GiB could find its rows in the 256 MB memory-side cache: such a sweep runs behind a
+    # 1 GiB copy on the same stream, whose own time is measured the same way and subtracted
+    scrub = by_batch[0] < (1 << 30)
+    if scrub:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+    loop.join()
+
+    def timed(f):
+        f()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            f()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps
+
+    def sweep():
+        if scrub:
+            fs.fs_stream_copy(ctx, src, dst, stream=stream)
+        for tb, idx in jobs:
+            fs.fs_stream_row_read(ctx, tb, idx, sink, stream=stream)
+
+    dt = timed(sweep)
+    if scrub:
+        dt -= timed(lambda: fs.fs_stream_copy(ctx, src, dst, stream=stream))
+        del src, dst
+    gbps = by_batch[0] / dt / 1e9
+    return {"random_row_read_GBps": gbps, "frac_of_hbm_peak": gbps / HBM_PEAK_GBPS, "launches": len(jobs),
+            "bytes_per_sweep": by_batch[0], "step_algorithmic_frac_of_ceiling": step_gbps / gbps,
+            "note": "the distinct rows touched by the batches of each table of this workload, shuffled, read whole and thrown away "
+                    "(fs_stream_row_read), launches back to back on the step's stream" +
+                    ("; each sweep behind a 1 GiB copy, the copy's time subtracted" if scrub else "")}
 
 
 def measure_extras(args, cfg, loop, t, stats, s_next, step_gbps):
@@ -431,7 +495,7 @@ def measure_extras(args, cfg, loop, t, stats, s_next, step_gbps):
             ctx, 0, t.table, t.state, cfg.lr, cfg.eps, t.grads[0], lay_a, sp_a)), cpb(0)),
         "class_pass_kernel(deferred_pass)": (alone(lambda: fs.fs_reduce_update_class(
             ctx, 1, t.table, t.state, cfg.lr, cfg.eps, t.grads[0], lay_a, sp_a)), cpb(1)),
-        "gather_kernel": (alone(lambda: fs.fs_gather_jagged(ctx, t.table, t.values[1], t.offsets[1], out=emb)), by["gather"]),
+        "gather_rows_kernel": (alone(lambda: fs.fs_gather_jagged(ctx, t.table, t.values[1], t.offsets[1], out=emb)), by["gather"]),
         "dedup (8 launches)": (alone(lambda: fs.fs_unique_ids(ctx, t.values[1], tab.num_rows, out=lay_b)), by["unique"]),
         "split + class order + records (3 launches)": (alone(lambda: fs.fs_collision_split_classes(
             ctx, lay_a, lay_b["unique"], lay_b["n_unique"], n[1], out=sp_a)), by["split"]),
