@@ -371,40 +371,36 @@ def measure_row_ceiling(loop, bufs, step_gbps):
         u = torch.unique(torch.cat([t.values[b][:t.n[b]] for b in range(t.T)]))
         jobs.append((t.table, u[torch.randperm(u.numel(), device=dev)].contiguous()))
     by_batch = [sum(idx.numel() * tb.shape[1] * tb.element_size() for tb, idx in jobs)]
-    reps = max(2, 40 // max(1, len(jobs)))
+    reps = 10
     # a sweep of less than 1 GiB could find its rows in the 256 MB memory-side cache: such a sweep runs behind a
-    # 1 GiB copy on the same stream, whose own time is measured the same way and subtracted
+    # 1 GiB copy on the same stream; only the sweep itself is between the two events
     scrub = by_batch[0] < (1 << 30)
     if scrub:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
     loop.join()
-
-    def timed(f):
-        f()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(reps):
-            f()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / reps
-
-    def sweep():
+    torch.cuda.synchronize()
+    pairs = []
+    for rep in range(reps + 1):
         if scrub:
             fs.fs_stream_copy(ctx, src, dst, stream=stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
         for tb, idx in jobs:
             fs.fs_stream_row_read(ctx, tb, idx, sink, stream=stream)
-
-    dt = timed(sweep)
+        e1.record(stream)
+        if rep > 0:
+            pairs.append((e0, e1))
+    torch.cuda.synchronize()
+    dt = sorted(a_.elapsed_time(b_) for a_, b_ in pairs)[len(pairs) // 2] * 1e-3
     if scrub:
-        dt -= timed(lambda: fs.fs_stream_copy(ctx, src, dst, stream=stream))
         del src, dst
     gbps = by_batch[0] / dt / 1e9
     return {"random_row_read_GBps": gbps, "frac_of_hbm_peak": gbps / HBM_PEAK_GBPS, "launches": len(jobs),
             "bytes_per_sweep": by_batch[0], "step_algorithmic_frac_of_ceiling": step_gbps / gbps,
             "note": "the distinct rows touched by the batches of each table of this workload, shuffled, read whole and thrown away "
                     "(fs_stream_row_read), launches back to back on the step's stream" +
-                    ("; each sweep behind a 1 GiB copy, the copy's time subtracted" if scrub else "")}
+                    "; median of ten sweeps, each between two events" + ("; a 1 GiB copy before every sweep" if scrub else "")}
 
 
 def measure_extras(args, cfg, loop, t, stats, s_next, step_gbps):

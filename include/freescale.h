@@ -309,8 +309,8 @@ int fs_class_order_for_parts(fs_ctx *ctx, const int32_t *part_pos, int64_t n_t, 
  * arithmetic (fp64 sums in a fixed order, one rounding to fp32, then the update), restricted to
  * the rows of class `cls` (0: collision rows = priority pass, 1: exclusive rows = deferred
  * pass).  short_rec_cls / n_rows_dev: the records of this class (short_rec + cls * 12 * cap_t)
- * and the number of its rows (counts_dev + cls).  Two launches: the short path over the
- * records, the position-cut path over the class order.
+ * and the number of its rows (counts_dev + cls).  One launch: its first workgroups take the
+ * position-cut path over the class order, the others the short path over the records.
  * The summed gradients do not go through memory unless `reduced` (OPTIONAL, [n_unique, dim]
  * fp32) is given, in which case the rows of this class are also written there.
  * Calls for the two classes may run side by side on different streams; calls for the same class
