@@ -37,7 +37,7 @@ namespace fs {
 // wavefront in the priority / deferred pass (64, 32 or 16: collision rows have long segments,
 // exclusive rows short ones, and a short chunk means more wavefronts with shorter lives)
 #ifndef FS_FUSED_UNR
-#define FS_FUSED_UNR 4
+#define FS_FUSED_UNR 8
 #endif
 #ifndef FS_FUSED_RU
 #define FS_FUSED_RU 2                      // parked rows one group of lanes updates per round

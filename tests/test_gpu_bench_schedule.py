@@ -4,8 +4,9 @@ bench.py and this file drive the same object (paper_2604_24073_amd.schedule.Step
 iterations per chain of launches, issued ahead of time on the library's index streams and ordered after the
 start of the most recent pipelined call, one multi-table pipelined call per step and group, worker-thread
 enqueue, several layouts in flight, and NO wait between the calls.  Configurations 1, 3 and 4 are one table
-(chains of two iterations); configuration 2 is stepped as bench.py steps it: eight tables in two groups, each
-group with its own context and stream, the tables of a group sharing launches.
+(chains of two iterations); configuration 2 is stepped as bench.py steps it: eight tables in one group on the
+default stream, the tables of one row width sharing launches (and once more in two groups, each with its own
+context and stream, which bench.py offers as --table-groups 2).
 
 The steps cycle through the configuration's batches exactly as the timed loop does (step s: batch s mod T with
 batch (s + 1) mod T as lookahead) and the oracle takes the same steps on a table that holds only the touched
@@ -130,8 +131,13 @@ def test_config1_on_the_timed_schedule():
 
 
 @pytest.mark.timeout(900)
-def test_config2_eight_tables_in_two_groups_on_the_timed_schedule():
-    check_on_bench_schedule(2, steps=4, groups=2)
+def test_config2_eight_tables_in_one_group_on_the_timed_schedule():
+    check_on_bench_schedule(2, steps=4, groups=1)
+
+
+@pytest.mark.timeout(900)
+def test_config2_eight_tables_in_two_groups():
+    check_on_bench_schedule(2, steps=3, groups=2)
 
 
 @pytest.mark.timeout(600)
