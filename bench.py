@@ -138,7 +138,8 @@ def bench_config(args, ci, extras):
     multi = len(bufs) > 1
     loop = StepLoop(bufs, groups=args.table_groups if multi else 1,
                     iters_per_chain=None if multi else args.ahead_batch, keep_reduced=args.keep_reduced,
-                    two_part=args.two_part, emb_rotation=3 if args.two_part else None, lookahead=args.lookahead)
+                    two_part=args.two_part, emb_rotation=3 if args.two_part else None, lookahead=args.lookahead,
+                    row_ordered_lookup=args.lookup_order == "row")
     ctx = loop.ctxs[0]
     for b in bufs:
         fs.fs_init_table_hash(ctx, b.table)
@@ -348,6 +349,7 @@ def bench_config(args, ci, extras):
     }
     if not args.no_extras:
         res["row_access_ceiling"] = measure_row_ceiling(loop, bufs, step_gbps)
+        res["step_without_index_chains"] = measure_without_index(loop, k0 + total_steps, step_bytes, ms_per_step)
     if extras and not multi:
         res.update(measure_extras(args, cfg, loop, bufs[0], stats[0], k0 + total_steps, step_gbps))
     loop.close()
@@ -401,6 +403,38 @@ def measure_row_ceiling(loop, bufs, step_gbps):
             "note": "the distinct rows touched by the batches of each table of this workload, shuffled, read whole and thrown away "
                     "(fs_stream_row_read), launches back to back on the step's stream" +
                     "; median of ten sweeps, each between two events" + ("; a 1 GiB copy before every sweep" if scrub else "")}
+
+
+def measure_without_index(loop, s_next, step_bytes, ms_per_step):
+    """What the index chains cost the step: the class passes and lookups of the two newest iterations replayed in
+    turn with NO index work beside them (their layouts, splits and class orders are still in the rotating buffers, so
+    every launch does the work it did in the timed region; the tables go on being updated).  Not a step of the
+    method - the index half is part of the step - but it separates the row work from the index work."""
+    import torch
+    import paper_2604_24073_amd as fs
+    P = loop.n_records
+    window = [(s_next - 2) % P, (s_next - 1) % P]
+    reps = 200
+
+    def replay(n):
+        for i in range(n):
+            for c, st, rec in zip(loop.ctxs, loop.streams, loop.step_records):
+                fs.fs_prioritized_step_pipelined_multi(c, rec[window[i % 2]], None, stream=st)
+
+    loop.join()
+    replay(4)
+    loop.join()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    replay(reps)
+    loop.join()
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t0) / reps * 1e6
+    loop.join(check=True)
+    return {"us_per_step": us, "frac_of_hbm_peak_on_the_step's_algorithmic_bytes": step_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS,
+            "index_chains_cost_us_per_step": ms_per_step * 1e3 - us,
+            "note": "priority pass, deferred pass and lookup of the two newest iterations replayed in turn, no index "
+                    "launches beside them; 200 calls"}
 
 
 def measure_extras(args, cfg, loop, t, stats, s_next, step_gbps):
@@ -578,6 +612,9 @@ def main() -> int:
     ap.add_argument("--table-groups", type=int, default=1, metavar="G",
                     help="workloads with several tables per shard: the tables are stepped in G groups, each with its "
                          "own context and stream")
+    ap.add_argument("--lookup-order", choices=["row", "batch"], default="row",
+                    help="the step's lookup walks the lookahead batch in row order (reads a row once for all its "
+                         "occurrences) or in batch order (writes the output front to back)")
     ap.add_argument("--two-part", action="store_true",
                     help="the lookup in the two parts of Algorithm 2 (fs_prioritized_step_two_part_multi)")
     ap.add_argument("--keep-reduced", action="store_true",

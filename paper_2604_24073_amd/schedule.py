@@ -43,9 +43,9 @@ class TableBuffers:
         self.args: List[fs.fs_step_args] = []
 
     def allocate(self, L: int, P: int, n_records: int, emb_rotation: Optional[int], keep_reduced: bool,
-                 inverse: bool) -> None:
+                 inverse: bool, row_ordered_lookup: bool = True) -> None:
         dev, nmax = self.table.device, max(self.n)
-        self.layouts = [fs.alloc_layout(nmax, dev, inverse=inverse, sorted_ids=True) for _ in range(L)]
+        self.layouts = [fs.alloc_layout(nmax, dev, inverse=inverse, sorted_ids=row_ordered_lookup) for _ in range(L)]
         self.splits = [fs.alloc_split(nmax, nmax, dev) for _ in range(P)]
         # output batches: one per batch of the cycle (each step overwrites the batch it looks ahead to), or
         # `emb_rotation` buffers of the largest size in turn (a test that wants to look at every batch afterwards)
@@ -119,7 +119,7 @@ class StepLoop:
 
     def __init__(self, tables: Sequence[TableBuffers], groups: int = 1, iters_per_chain: Optional[int] = None,
                  emb_rotation: Optional[int] = None, keep_reduced: bool = False, two_part: bool = False,
-                 lookahead: Optional[int] = None):
+                 lookahead: Optional[int] = None, row_ordered_lookup: bool = True):
         self.tables = list(tables)
         G = max(1, min(groups, len(self.tables)))
         self.groups = group_tables(self.tables, G)
@@ -141,7 +141,8 @@ class StepLoop:
         self.n_records = self.period
         self.two_part = two_part
         for t in self.tables:
-            t.allocate(self.L, self.P, self.n_records, emb_rotation, keep_reduced, inverse=two_part)
+            t.allocate(self.L, self.P, self.n_records, emb_rotation, keep_reduced, inverse=two_part,
+                       row_ordered_lookup=row_ordered_lookup)
         self.ctxs = [fs.Context(max_ids=max(max(t.n) for t in g), max_dim=max(t.dim for t in g)) for g in self.groups]
         # The chip gives a process four hardware queues and a context owns three streams, so the first group is
         # stepped on the default stream (the fourth queue); a stream of its own for it costs 25 % (5 queues in use).
