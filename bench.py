@@ -4,7 +4,7 @@
 A "step" is one pass of the full hot path over one batch of every table of the shard: dedup of the lookahead
 IDs, collision split and class order, priority pass (gradient segment-reduce fused with row-wise Adagrad on the
 collision rows), deferred pass (the same on the exclusive rows) on its own stream, and the jagged gather of the
-lookahead batch.  One invocation times BASELINE configs[1], [2], [3] and [4]; the headline (`value`,
+lookahead batch.  One invocation times the workload configurations [1], [2], [3] and [4]; the headline (`value`,
 `ms_per_step`, `config.workload`) is the largest single-GPU configuration, configs[2] (eight tables per shard,
 2 GB per step); the others are in `per_config`.  Every configuration cycles through ALL its batches (two, or
 the ten of the streaming configuration with its drifting hot set): step s works on batch s mod T with batch
