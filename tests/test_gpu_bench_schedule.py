@@ -68,7 +68,7 @@ def same_bits(got, want, what):
         raise AssertionError(f"{what}: {len(bad[0])} of {got.size} elements differ, first at {[int(x[0]) for x in bad]}")
 
 
-def check_on_bench_schedule(cfg_index, steps, groups):
+def check_on_bench_schedule(cfg_index, steps, groups, row_ordered_lookup=True):
     cfg = CONFIGS[cfg_index]
     its_all = make_iterations(cfg)
     for per_table in its_all:
@@ -84,7 +84,7 @@ def check_on_bench_schedule(cfg_index, steps, groups):
         bufs.append(TableBuffers(table, state, [torch.from_numpy(it.values).to(dev) for it in its],
                                  [torch.from_numpy(it.offsets).to(dev) for it in its],
                                  [torch.from_numpy(it.grads).to(dev) for it in its], cfg.lr, cfg.eps))
-    loop = StepLoop(bufs, groups=groups, emb_rotation=steps)
+    loop = StepLoop(bufs, groups=groups, emb_rotation=steps, row_ordered_lookup=row_ordered_lookup)
     assert steps <= loop.period
     for tab, b in zip(cfg.tables, bufs):
         if tab.init == "hash":
@@ -128,6 +128,11 @@ def test_config0_on_the_timed_schedule():
 @pytest.mark.timeout(600)
 def test_config1_on_the_timed_schedule():
     check_on_bench_schedule(1, steps=6, groups=1)
+
+
+@pytest.mark.timeout(600)
+def test_config1_with_the_lookup_in_batch_order():
+    check_on_bench_schedule(1, steps=3, groups=1, row_ordered_lookup=False)
 
 
 @pytest.mark.timeout(900)
