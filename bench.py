@@ -51,6 +51,19 @@ def algorithmic_bytes(n_t, u_t, n_t1, u_t1, dim, w):
             "total": unique + split + gather + reduce_update}
 
 
+def device_info():
+    """What the runtime says about the chip the figures were taken on (as found: nothing is set or locked)."""
+    import torch
+    p = torch.cuda.get_device_properties(0)
+    info = {"name": p.name, "compute_units": p.multi_processor_count, "memory_GiB": p.total_memory / 2 ** 30,
+            "hbm_peak_GBps_used": HBM_PEAK_GBPS}
+    for field in ("gcnArchName", "clock_rate", "memory_clock_rate", "memory_bus_width", "L2_cache_size"):
+        v = getattr(p, field, None)
+        if v is not None:
+            info[field] = v
+    return info
+
+
 def read_traffic(path=TRAFFIC_FILE):
     """profiles/hbm_traffic_per_launch.txt -> {(workload, kernel): HBM bytes per launch, launches per step}.
     Columns (blanks; '#' starts a comment): workload, kernel (no blanks; "/LPRnn" marks the launch of one row
@@ -655,6 +668,7 @@ def main() -> int:
         "step_frac_of_hbm_peak": head["step_frac_of_hbm_peak"],
         "roofline": head["roofline"], "cpu_baseline": head["cpu_baseline"],
         "per_config": {f"configs[{c}]": results[c] for c in configs},
+        "device": device_info(),
     }
     print(json.dumps(out))
     return 0
