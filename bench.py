@@ -443,8 +443,19 @@ def measure_without_index(loop, s_next, step_bytes, ms_per_step):
     loop.join()
     torch.cuda.synchronize()
     us = (time.perf_counter() - t0) / reps * 1e6
+    # once more with the kernels of one call in eight between event pairs (not the timed run: the records cost)
+    ctx = loop.ctxs[0]
+    fs.fs_ctx_set_kernel_timing(ctx, reps // 8 + 2, 8)
+    replay(reps)
+    loop.join()
+    kinds = {"gather": fs.FS_TIME_GATHER, "priority_pass": fs.FS_TIME_UPDATE_CO, "deferred_pass": fs.FS_TIME_UPDATE_EX}
+    kernel_us = {}
+    for name, kind in kinds.items():
+        vals = fs.fs_ctx_get_kernel_timing(ctx, kind, reps)
+        kernel_us[name] = (sum(vals) / len(vals) * 1e3) if vals else None
+    fs.fs_ctx_set_kernel_timing(ctx, 0)
     loop.join(check=True)
-    return {"us_per_step": us, "frac_of_hbm_peak_on_the_step's_algorithmic_bytes": step_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS,
+    return {"us_per_step": us, "kernel_avg_us": kernel_us, "frac_of_hbm_peak_on_the_step's_algorithmic_bytes": step_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS,
             "index_chains_cost_us_per_step": ms_per_step * 1e3 - us,
             "note": "priority pass, deferred pass and lookup of the two newest iterations replayed in turn, no index "
                     "launches beside them; 200 calls"}
